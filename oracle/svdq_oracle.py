@@ -1,0 +1,287 @@
+"""CPU oracle for the SVDQuant W4A4 + low-rank linear layer.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, step-by-step numpy implementation of what the layer computes,
+written from the paper (arXiv 2411.05007).  It exists so that the GPU library
+can be checked against something that shares no code with it.  Only the test
+suite, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the product path never does.
+
+Notation follows the paper: X [b x m] activations, W [m x n] weights,
+lambda the per-input-channel smoothing factor, X^ = X diag(lambda)^-1,
+W^ = diag(lambda) W, W^ = L1 L2 + R with rank r, Q(.) the symmetric max-abs
+quantizer with q_max = 7 (signed 4 bit).  In code: M = b tokens, K = m input
+channels, N = n output channels, g = 64 the group size, G = K / 64.
+
+What each function follows
+--------------------------
+* ``quantize_groups``       Eq. (1) applied per group of 64 along K with 16-bit
+                            (fp16) scales (App. "Implementation Details").
+* ``smoothing_factor``      lambda_i = max|X_:,i|^alpha / max|W_i,:|^(1-alpha)
+                            (App. "Implementation Details").
+* ``smooth_weight``         W^ = diag(lambda) W  (Sec. 4.2; the paper prints
+                            W diag(lambda), which does not type-check for
+                            W in R^{m x n}; X^ W^ = X W forces row scaling).
+* ``lowrank_svd``           L1 = U Sigma[:, :r], L2 = V[:r, :] (Sec. 4.2, text
+                            after Prop. 4.2; Eckart-Young).
+* ``prepare``               smoothing -> SVD -> residual -> per-group INT4.
+* ``forward``               Eq. (5): X^ L1 L2 (16-bit branch) + Q(X^) Q(R)
+                            (4-bit branch, Eq. (2) per group), plus bias.
+
+Readings where the paper is silent (each is listed in the design document):
+round = round-half-to-even; the scale is rounded to fp16 *before* it is used;
+codes come from x * (1.0f / s) with one correctly rounded reciprocal per group;
+codes are clamped to [-7, 7]; an all-zero group has scale 0 and codes 0; a scale
+above the fp16 range saturates at 65504; lambda = 1 where it would be
+degenerate; the residual is taken against the bf16-rounded, stored factors; the
+activation scale of the 16-bit branch is folded into L1 (L1s = diag(lambda)^-1
+L1), so the branch consumes the bf16 input exactly.
+
+All run-time arithmetic is IEEE fp32 with explicit fp16 / bf16 roundings so
+that codes and scales can be compared bit for bit; offline arithmetic is fp64.
+
+Every function here is pinned by ``tests/test_oracle_*.py`` to closed forms,
+invariants, exact-rational brute force or textbook routines.  The one thing
+pinned only up to invariants is the *choice* among equally valid SVD factors
+(signs, near-degenerate singular vectors).
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+
+GROUP = 64
+QMAX = 7
+FP16_MAX = np.float32(65504.0)
+
+
+# --------------------------------------------------------------------------
+# number formats
+# --------------------------------------------------------------------------
+
+def bf16_round(a: np.ndarray) -> np.ndarray:
+    """Round fp32/fp64 values to bf16 (nearest, ties to even); returns uint16 bit patterns."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# --------------------------------------------------------------------------
+# Eq. (1): symmetric max-abs quantizer, per group of 64 along the last axis
+# --------------------------------------------------------------------------
+
+def quantize_groups(v: np.ndarray):
+    """Quantize fp32 ``v`` [..., K] in groups of 64 along the last axis.
+
+    Returns (codes int8 [..., K] in [-7, 7], scales fp16 [..., K/64]).
+    s = fp16(max|v| / 7); q = clamp(rne(v * (1/s)), -7, 7).
+    """
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    K = v.shape[-1]
+    assert K % GROUP == 0
+    vg = v.reshape(v.shape[:-1] + (K // GROUP, GROUP))
+    amax = np.max(np.abs(vg), axis=-1)                                   # fp32
+    s32 = np.minimum(amax / np.float32(QMAX), FP16_MAX).astype(np.float32)
+    s16 = s32.astype(np.float16)                                         # 16-bit scale, RNE
+    s = s16.astype(np.float32)
+    with np.errstate(divide="ignore"):
+        rcp = np.where(s > 0, np.float32(1.0) / s, np.float32(0.0)).astype(np.float32)
+    y = (vg * rcp[..., None]).astype(np.float32)
+    q = np.clip(np.rint(y), -QMAX, QMAX).astype(np.int8)
+    return q.reshape(v.shape), s16
+
+
+def dequantize_groups(q: np.ndarray, s16: np.ndarray) -> np.ndarray:
+    """Q(X) = s_X * Q_X, in fp32 (the product of a 4-bit integer and an fp16 is exact)."""
+    K = q.shape[-1]
+    qg = q.reshape(q.shape[:-1] + (K // GROUP, GROUP)).astype(np.float32)
+    return (qg * s16.astype(np.float32)[..., None]).reshape(q.shape)
+
+
+# --------------------------------------------------------------------------
+# offline: smoothing, low-rank split, residual quantization
+# --------------------------------------------------------------------------
+
+def smoothing_factor(x_absmax: np.ndarray, W: np.ndarray, alpha: float = 0.5) -> np.ndarray:
+    """lambda_k = max|X_:,k|^alpha / max|W_k,:|^(1-alpha) in fp64; 1 where degenerate."""
+    ax = np.asarray(x_absmax, dtype=np.float64)
+    aw = np.max(np.abs(np.asarray(W, dtype=np.float64)), axis=1)
+    with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
+        lam = np.power(ax, alpha) / np.power(aw, 1.0 - alpha)
+    bad = ~np.isfinite(lam) | (lam <= 0) | (ax <= 0) | (aw <= 0)
+    lam = np.where(bad, 1.0, lam)
+    return lam
+
+
+def reciprocal_f32(lam: np.ndarray) -> np.ndarray:
+    """The run-time smoothing multiplier: fp32(1 / lambda)."""
+    return (1.0 / np.asarray(lam, dtype=np.float64)).astype(np.float32)
+
+
+def smooth_weight(W: np.ndarray, lam: np.ndarray) -> np.ndarray:
+    """W^ = diag(lambda) W in fp64."""
+    return np.asarray(lam, dtype=np.float64)[:, None] * np.asarray(W, dtype=np.float64)
+
+
+def lowrank_svd(W_hat: np.ndarray, r: int):
+    """Best rank-r split of W^ (fp64): L1 = U[:, :r] Sigma[:r], L2 = Vt[:r, :]; also all singular values."""
+    U, S, Vt = np.linalg.svd(np.asarray(W_hat, dtype=np.float64), full_matrices=False)
+    return U[:, :r] * S[:r][None, :], Vt[:r, :], S
+
+
+def residual(W: np.ndarray, lam_eff: np.ndarray, l1s_bits: np.ndarray, l2_bits: np.ndarray) -> np.ndarray:
+    """R = diag(lambda) W - diag(lambda) (L1s L2b), fp64, against the *stored* bf16 factors."""
+    lam_eff = np.asarray(lam_eff, dtype=np.float64)
+    W_hat = lam_eff[:, None] * np.asarray(W, dtype=np.float64)
+    P = bf16_to_f32(l1s_bits).astype(np.float64) @ bf16_to_f32(l2_bits).astype(np.float64)
+    return W_hat - lam_eff[:, None] * P
+
+
+def quantize_residual(R: np.ndarray):
+    """Per-group INT4 of R [K, N], groups of 64 along K: codes int8 [K, N], scales fp16 [G, N]."""
+    q_t, s_t = quantize_groups(np.asarray(R, dtype=np.float64).astype(np.float32).T)   # [N, K], [N, G]
+    return np.ascontiguousarray(q_t.T), np.ascontiguousarray(s_t.T)
+
+
+def residual_codes_from_factors(W, rinv, l1s_bits, l2_bits):
+    """Steps after the SVD, for given stored factors: what any valid factor choice must quantize to."""
+    lam_eff = 1.0 / np.asarray(rinv, dtype=np.float32).astype(np.float64)
+    R = residual(W, lam_eff, l1s_bits, l2_bits)
+    qw, sw = quantize_residual(R)
+    return qw, sw, R
+
+
+def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
+            bias: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Offline quantization of one layer.  W fp32 [K, N], x_absmax fp32 [K]."""
+    W = np.asarray(W, dtype=np.float32)
+    K, N = W.shape
+    assert K % GROUP == 0 and 0 <= rank <= min(K, N)
+    lam = smoothing_factor(x_absmax, W, alpha)
+    rinv = reciprocal_f32(lam)
+    lam_eff = 1.0 / rinv.astype(np.float64)          # exact inverse of what the run time multiplies by
+    W_hat = smooth_weight(W, lam_eff)
+    if rank > 0:
+        L1, L2, S = lowrank_svd(W_hat, rank)
+        l1s_bits = bf16_round((L1 / lam_eff[:, None]).astype(np.float32))
+        l2_bits = bf16_round(L2.astype(np.float32))
+    else:
+        S = np.linalg.svd(W_hat, compute_uv=False)
+        l1s_bits = np.zeros((K, 0), dtype=np.uint16)
+        l2_bits = np.zeros((0, N), dtype=np.uint16)
+    qw, sw, R = residual_codes_from_factors(W, rinv, l1s_bits, l2_bits)
+    b = np.zeros(N, dtype=np.float32) if bias is None else np.asarray(bias, dtype=np.float32)
+    return {"rinv": rinv, "lam": lam_eff, "l1s": l1s_bits, "l2": l2_bits, "qw": qw, "sw": sw,
+            "bias": b, "R": R, "W_hat": W_hat, "sigma": S}
+
+
+# --------------------------------------------------------------------------
+# run time: Eq. (5)
+# --------------------------------------------------------------------------
+
+def quantize_activation(x_bits: np.ndarray, rinv: np.ndarray):
+    """Smooth and quantize bf16 activations: returns (x^ fp32, codes int8 [M,K], scales fp16 [M,G])."""
+    x = bf16_to_f32(x_bits)
+    x_hat = (x * np.asarray(rinv, dtype=np.float32)[None, :]).astype(np.float32)
+    q, s = quantize_groups(x_hat)
+    return x_hat, q, s
+
+
+def down_projection(x_bits: np.ndarray, l1s_bits: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """H = X^ L1 = X (diag(lambda)^-1 L1) = X L1s, accumulated in ``dtype``."""
+    return bf16_to_f32(x_bits).astype(dtype) @ bf16_to_f32(l1s_bits).astype(dtype)
+
+
+def group_sums(qx: np.ndarray, qw: np.ndarray) -> np.ndarray:
+    """A_g[m, n] = sum_{k in group g} qx[m, k] * qw[k, n]  ->  int32 [G, M, N].
+
+    Evaluated as fp32 matrix products per group, which is exact here:
+    |A_g| <= 64 * 7 * 7 = 3136 < 2^24 and every partial sum is an integer.
+    """
+    M, K = qx.shape
+    N = qw.shape[1]
+    G = K // GROUP
+    out = np.empty((G, M, N), dtype=np.int32)
+    for g in range(G):
+        a = qx[:, g * GROUP:(g + 1) * GROUP].astype(np.float32)
+        b = qw[g * GROUP:(g + 1) * GROUP, :].astype(np.float32)
+        out[g] = (a @ b).astype(np.int32)
+    return out
+
+
+def group_sums_int_loops(qx: np.ndarray, qw: np.ndarray) -> np.ndarray:
+    """The same sums with pure Python integers (tiny inputs only)."""
+    M, K = qx.shape
+    N = qw.shape[1]
+    G = K // GROUP
+    out = np.zeros((G, M, N), dtype=np.int32)
+    for g in range(G):
+        for m in range(M):
+            for n in range(N):
+                acc = 0
+                for k in range(g * GROUP, (g + 1) * GROUP):
+                    acc += int(qx[m, k]) * int(qw[k, n])
+                out[g, m, n] = acc
+    return out
+
+
+def forward(x_bits: np.ndarray, prep: Dict[str, np.ndarray], want_group_sums: bool = False,
+            want_f64: bool = False, lowrank: bool = True) -> Dict[str, np.ndarray]:
+    """One quantized linear layer on bf16 activations ``x_bits`` uint16 [M, K].
+
+    Y = sum_g (s_x[m,g] s_w[g,n]) A_g[m,n]  +  H L2  +  bias     (fp32, ascending g)
+    """
+    rinv, qw, sw = prep["rinv"], prep["qw"], prep["sw"]
+    M, K = x_bits.shape
+    N = qw.shape[1]
+    G = K // GROUP
+    x_hat, qx, sx = quantize_activation(x_bits, rinv)
+    sx32 = sx.astype(np.float32)
+    sw32 = sw.astype(np.float32)
+    Y = np.zeros((M, N), dtype=np.float32)
+    Y64 = np.zeros((M, N), dtype=np.float64) if want_f64 else None
+    A_all = np.empty((G, M, N), dtype=np.int32) if want_group_sums else None
+    for g in range(G):
+        a = qx[:, g * GROUP:(g + 1) * GROUP].astype(np.float32)
+        b = qw[g * GROUP:(g + 1) * GROUP, :].astype(np.float32)
+        A = a @ b                                                   # exact integers in fp32
+        if want_group_sums:
+            A_all[g] = A.astype(np.int32)
+        scale = (sx32[:, g][:, None] * sw32[g][None, :]).astype(np.float32)
+        Y += (scale * A).astype(np.float32)
+        if want_f64:
+            Y64 += sx32[:, g].astype(np.float64)[:, None] * sw32[g].astype(np.float64)[None, :] * A.astype(np.float64)
+    H = None
+    if lowrank and prep["l1s"].shape[1] > 0:
+        H = down_projection(x_bits, prep["l1s"], np.float32)
+        Y += (H @ bf16_to_f32(prep["l2"])).astype(np.float32)
+        if want_f64:
+            H64 = down_projection(x_bits, prep["l1s"], np.float64)
+            Y64 += H64 @ bf16_to_f32(prep["l2"]).astype(np.float64)
+    Y += prep["bias"][None, :].astype(np.float32)
+    if want_f64:
+        Y64 += prep["bias"][None, :].astype(np.float64)
+    out = {"x_hat": x_hat, "qx": qx, "sx": sx, "H": H, "Y": Y, "Y_bf16": bf16_round(Y)}
+    if want_group_sums:
+        out["A"] = A_all
+    if want_f64:
+        out["Y64"] = Y64
+    return out
+
+
+# --------------------------------------------------------------------------
+# error measures used by the paper's analysis (Sec. 4.1, Prop. 4.1 / 4.2)
+# --------------------------------------------------------------------------
+
+def quantization_error(Xh: np.ndarray, Wm: np.ndarray) -> float:
+    """E(X, W) = || X W - Q(X) Q(W) ||_F with both operands quantized per group along K (Eq. 3)."""
+    qx, sx = quantize_groups(Xh.astype(np.float32))
+    qw_t, sw_t = quantize_groups(np.ascontiguousarray(Wm.astype(np.float32).T))
+    dx = dequantize_groups(qx, sx).astype(np.float64)
+    dw = dequantize_groups(qw_t, sw_t).astype(np.float64).T
+    return float(np.linalg.norm(Xh.astype(np.float64) @ Wm.astype(np.float64) - dx @ dw))

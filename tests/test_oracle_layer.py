@@ -1,0 +1,246 @@
+"""Pins for the oracle's offline steps and forward pass (paper Sec. 4.1-4.2, Eq. 2, 3, 5; Prop. 4.1, 4.2).
+
+Closed forms, invariants, textbook special cases and brute force; nothing here
+retypes the oracle's own formulas to compare them with themselves.
+"""
+import numpy as np
+import pytest
+
+from oracle import svdq_oracle as O
+from paper_2411_05007_amd import inputs as I
+
+
+def _small_layer(M=48, K=256, N=96, seed=0, x_out=True, w_out=True):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    if x_out:
+        x[:, rng.choice(K, 3, replace=False)] *= 50
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    if w_out:
+        w[rng.choice(K, 2, replace=False), :] *= 20
+    xb = O.bf16_round(x)
+    ax = np.abs(O.bf16_to_f32(xb)).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    return xb, w, b, ax
+
+
+# ------------------------------- smoothing ---------------------------------------------------
+
+def test_smoothing_factor_closed_forms():
+    W = np.array([[1.0, -4.0], [0.25, 0.1], [0.0, 0.0], [2.0, 2.0]], dtype=np.float32)
+    ax = np.array([4.0, 9.0, 3.0, 0.0], dtype=np.float32)
+    lam = O.smoothing_factor(ax, W, 0.5)
+    # sqrt(4)/sqrt(4) = 1 ; sqrt(9)/sqrt(.25) = 6 ; zero weight row and zero activation -> 1
+    assert np.allclose(lam, [1.0, 6.0, 1.0, 1.0], rtol=1e-15)
+    assert np.allclose(O.smoothing_factor(ax[:2], W[:2], 1.0), [4.0, 9.0])          # alpha=1: max|X|
+    assert np.allclose(O.smoothing_factor(ax[:2], W[:2], 0.0), [0.25, 4.0])         # alpha=0: 1/max|W|
+    assert np.allclose(O.smoothing_factor(ax[:2], W[:2], 0.25), [4 ** .25 / 4 ** .75, 9 ** .25 / .25 ** .75])
+
+
+def test_smoothing_leaves_the_product_unchanged_and_moves_outliers():
+    xb, w, _, ax = _small_layer(seed=1)
+    x = O.bf16_to_f32(xb).astype(np.float64)
+    lam = O.smoothing_factor(ax, w, 0.5)
+    xh = x / lam[None, :]
+    wh = O.smooth_weight(w, lam)
+    ref = x @ w.astype(np.float64)
+    assert np.linalg.norm(xh @ wh - ref) / np.linalg.norm(ref) < 1e-13
+    # Fig. 4: the activation range shrinks, the weight range grows
+    assert np.abs(xh).max() < 0.5 * np.abs(x).max()
+    assert np.abs(wh).max() > 2.0 * np.abs(w).max()
+    # rows are scaled (input channels), not columns
+    assert np.allclose(wh[3], lam[3] * w[3].astype(np.float64))
+
+
+# ------------------------------- low-rank split ---------------------------------------------
+
+def test_lowrank_matches_eckart_young_and_known_factors():
+    rng = np.random.default_rng(2)
+    K, N, r = 96, 64, 8
+    U, _ = np.linalg.qr(rng.standard_normal((K, N)))
+    V, _ = np.linalg.qr(rng.standard_normal((N, N)))
+    sig = np.concatenate([np.linspace(50, 20, r), np.linspace(1.0, 0.1, N - r)])
+    Wh = (U * sig[None, :]) @ V.T
+    L1, L2, S = O.lowrank_svd(Wh, r)
+    assert L1.shape == (K, r) and L2.shape == (r, N)
+    assert np.allclose(S, sig, rtol=1e-12)
+    # the rank-r product is unique even though the factors are not
+    assert np.allclose(L1 @ L2, (U[:, :r] * sig[:r]) @ V[:, :r].T, atol=1e-11)
+    # ||R||_F = sqrt(sum_{i>r} sigma_i^2)   (text after Prop. 4.2)
+    assert np.isclose(np.linalg.norm(Wh - L1 @ L2), np.sqrt(np.sum(sig[r:] ** 2)), rtol=1e-12)
+    # Sigma is carried wholly by L1: L2 has orthonormal rows
+    assert np.allclose(L2 @ L2.T, np.eye(r), atol=1e-12)
+
+
+def test_prepare_residual_identity_and_ranges():
+    xb, w, b, ax = _small_layer(seed=3)
+    P = O.prepare(w, ax, rank=16, bias=b)
+    lam = P["lam"]
+    l1s = O.bf16_to_f32(P["l1s"]).astype(np.float64)
+    l2 = O.bf16_to_f32(P["l2"]).astype(np.float64)
+    # L1 L2 + R = W^ holds against the stored (rounded) factors
+    assert np.allclose(lam[:, None] * (l1s @ l2) + P["R"], P["W_hat"], rtol=0, atol=1e-12)
+    # run-time multiplier and offline scaling are exact inverses up to fp64
+    assert np.allclose(P["rinv"].astype(np.float64) * lam, 1.0, rtol=1e-15)
+    # residual against rounded factors is close to the Eckart-Young optimum
+    opt = np.sqrt(np.sum(P["sigma"][16:] ** 2))
+    assert opt <= np.linalg.norm(P["R"]) * (1 + 1e-12)
+    assert np.linalg.norm(P["R"]) <= opt * 1.01
+    # Fig. 4(d)->(e): the residual has a much narrower range than the smoothed weight
+    assert np.abs(P["R"]).max() < 0.25 * np.abs(P["W_hat"]).max()
+    # weight codes/scales are the quantizer applied down the K axis of R
+    for n in (0, 17, 95):
+        q, s = O.quantize_groups(P["R"][:, n].astype(np.float32)[None, :])
+        assert np.array_equal(q[0], P["qw"][:, n]) and np.array_equal(s[0], P["sw"][:, n])
+    assert P["qw"].shape == w.shape and P["sw"].shape == (w.shape[0] // 64, w.shape[1])
+
+
+def test_full_rank_gives_zero_residual_and_reproduces_xw():
+    xb, w, b, ax = _small_layer(M=32, K=128, N=64, seed=4)
+    P = O.prepare(w, ax, rank=64, bias=b)
+    # R holds only the bf16 rounding of the factors: tiny against W^
+    assert np.linalg.norm(P["R"]) < 1e-2 * np.linalg.norm(P["W_hat"])
+    out = O.forward(xb, P, want_f64=True)
+    ref = O.bf16_to_f32(xb).astype(np.float64) @ w.astype(np.float64) + b
+    assert np.linalg.norm(out["Y64"] - ref) / np.linalg.norm(ref) < 2e-3
+    # with exact (unrounded) factors and no 4-bit branch the identity is exact
+    lam = P["lam"]
+    L1, L2, _ = O.lowrank_svd(P["W_hat"], 64)
+    xh = O.bf16_to_f32(xb).astype(np.float64) / lam[None, :]
+    assert np.linalg.norm(xh @ L1 @ L2 + b - ref) / np.linalg.norm(ref) < 1e-12
+
+
+# ------------------------------- integer GEMM -----------------------------------------------
+
+def test_group_sums_against_integer_loops_and_extremes():
+    rng = np.random.default_rng(6)
+    qx = rng.integers(-7, 8, size=(16, 128)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(128, 16)).astype(np.int8)
+    A = O.group_sums(qx, qw)
+    assert A.dtype == np.int32 and A.shape == (2, 16, 16)
+    assert np.array_equal(A, O.group_sums_int_loops(qx, qw))
+    assert np.array_equal(A.sum(axis=0), qx.astype(np.int64) @ qw.astype(np.int64))
+    hi = O.group_sums(np.full((2, 64), 7, np.int8), np.full((64, 3), -7, np.int8))
+    assert np.all(hi == -3136)
+    # one-hot row picks out a single weight code per group
+    e = np.zeros((1, 128), np.int8)
+    e[0, 5] = 1
+    e[0, 64 + 9] = -2
+    A1 = O.group_sums(e, qw)
+    assert np.array_equal(A1[0, 0], qw[5]) and np.array_equal(A1[1, 0], -2 * qw[73].astype(np.int32))
+
+
+# ------------------------------- forward (Eq. 5) --------------------------------------------
+
+def test_forward_equals_plain_definition_of_eq5():
+    xb, w, b, ax = _small_layer(seed=7)
+    P = O.prepare(w, ax, rank=16, bias=b)
+    out = O.forward(xb, P, want_group_sums=True, want_f64=True)
+    x = O.bf16_to_f32(xb).astype(np.float64)
+    # Q(X^) Q(R) with Q(.) = s * codes, written as two dense dequantized matrices
+    dq_x = np.repeat(out["sx"].astype(np.float64), 64, axis=1) * out["qx"]
+    dq_w = np.repeat(P["sw"].astype(np.float64), 64, axis=0) * P["qw"]
+    low = (x @ O.bf16_to_f32(P["l1s"]).astype(np.float64)) @ O.bf16_to_f32(P["l2"]).astype(np.float64)
+    ref = dq_x @ dq_w + low + b
+    assert np.linalg.norm(out["Y64"] - ref) / np.linalg.norm(ref) < 1e-13
+    assert np.linalg.norm(out["Y"] - out["Y64"]) / np.linalg.norm(out["Y64"]) < 1e-6
+    # exact integer group sums
+    assert np.array_equal(out["A"][:, :4, :5], O.group_sums_int_loops(out["qx"][:4], P["qw"][:, :5]))
+    assert np.abs(out["A"]).max() <= 3136
+    # the activation codes are the quantizer applied to bf16(x) * fp32(1/lambda)
+    xh = (O.bf16_to_f32(xb) * P["rinv"][None, :]).astype(np.float32)
+    assert np.array_equal(out["x_hat"], xh)
+    q, s = O.quantize_groups(xh[5:6])
+    assert np.array_equal(q[0], out["qx"][5]) and np.array_equal(s[0], out["sx"][5])
+    # the 16-bit branch: H = X L1s in fp32
+    assert np.allclose(out["H"], x @ O.bf16_to_f32(P["l1s"]).astype(np.float64), rtol=1e-4, atol=1e-4)
+    # output rounding to bf16 is round-to-nearest-even of Y
+    assert np.max(np.abs(O.bf16_to_f32(out["Y_bf16"]) - out["Y"]) / np.maximum(np.abs(out["Y"]), 1e-30)) <= 2.0 ** -8
+
+
+def test_forward_approximates_xw_and_error_identity():
+    xb, w, b, ax = _small_layer(M=64, K=512, N=128, seed=8)
+    r = 16
+    P = O.prepare(w, ax, rank=r, bias=b)
+    out = O.forward(xb, P, want_f64=True)
+    x = O.bf16_to_f32(xb).astype(np.float64)
+    ref = x @ w.astype(np.float64) + b
+    rel = np.linalg.norm(out["Y64"] - ref) / np.linalg.norm(ref)
+    assert rel < 0.12
+    # || X^W^ - (X^ L1L2 + Q(X^)Q(R)) ||_F = || X^R - Q(X^)Q(R) ||_F = E(X^, R)   (Sec. 4.2)
+    xh = out["x_hat"].astype(np.float64)
+    dq_x = np.repeat(out["sx"].astype(np.float64), 64, axis=1) * out["qx"]
+    dq_w = np.repeat(P["sw"].astype(np.float64), 64, axis=0) * P["qw"]
+    lhs = np.linalg.norm(ref - out["Y64"])
+    rhs = np.linalg.norm(xh @ P["R"] - dq_x @ dq_w)
+    assert abs(lhs - rhs) <= 1e-4 * rhs          # differs only by fp32 rounding of x^ vs x/lambda
+    assert np.isclose(rhs, O.quantization_error(out["x_hat"], P["R"]), rtol=1e-9)
+
+
+def test_error_ordering_naive_smooth_svdquant():
+    # ablation (Sec. 5.3): naive W4A4 > smoothing only > smoothing + low-rank
+    xb, w, b, ax = _small_layer(M=128, K=512, N=256, seed=9)
+    x = O.bf16_to_f32(xb)
+    naive = O.quantization_error(x, w)
+    lam = O.smoothing_factor(ax, w, 0.5)
+    xh = (x.astype(np.float64) / lam).astype(np.float32)
+    smooth = O.quantization_error(xh, O.smooth_weight(w, lam))
+    P = O.prepare(w, ax, rank=32)
+    svdq = O.quantization_error(xh, P["R"])
+    assert naive > smooth > svdq
+    assert svdq < 0.5 * naive
+
+
+def test_prop_4_1_error_decomposition_bound():
+    rng = np.random.default_rng(10)
+    for seed in range(4):
+        xb, w, _, ax = _small_layer(M=32, K=256, N=48, seed=20 + seed, x_out=seed % 2 == 0)
+        x = O.bf16_to_f32(xb)
+        qx, sx = O.quantize_groups(x)
+        qwt, swt = O.quantize_groups(np.ascontiguousarray(w.T))
+        dx = O.dequantize_groups(qx, sx).astype(np.float64)
+        dw = O.dequantize_groups(qwt, swt).astype(np.float64).T
+        X, W = x.astype(np.float64), w.astype(np.float64)
+        E = np.linalg.norm(X @ W - dx @ dw)
+        nX, nW = np.linalg.norm(X), np.linalg.norm(W)
+        eX, eW = np.linalg.norm(X - dx), np.linalg.norm(W - dw)
+        assert E <= nX * eW + eX * (nW + eW)
+        assert np.isclose(E, O.quantization_error(x, w), rtol=1e-12)
+
+
+def test_prop_4_2_gaussian_quantization_error_bound():
+    # E||R - Q(R)||_F <= c sqrt(size)/q_max E||R||_F with c = sqrt(log(size) pi / size), per group (size 64)
+    rng = np.random.default_rng(12)
+    R = rng.standard_normal((4096, 64)).astype(np.float32) * 0.37
+    q, s = O.quantize_groups(R)
+    err = np.linalg.norm((R - O.dequantize_groups(q, s)).astype(np.float64), axis=1).mean()
+    nrm = np.linalg.norm(R.astype(np.float64), axis=1).mean()
+    c = np.sqrt(np.log(64.0) * np.pi / 64.0)
+    assert err <= c * np.sqrt(64.0) / 7.0 * nrm
+    # and the bound is not vacuous by orders of magnitude (uniform rounding error ~ s * sqrt(size/12))
+    assert err >= 0.1 * c * np.sqrt(64.0) / 7.0 * nrm
+
+
+def test_lowrank_cost_ratio_and_tiny_config_shapes():
+    # (m r + n r) / (m n): the 16-bit branch is a few percent of the layer (Sec. 4.2)
+    c = I.metric_case()
+    ratio = (c.K * c.rank + c.N * c.rank) / (c.K * c.N)
+    assert np.isclose(ratio, 32 * (3072 + 12288) / (3072 * 12288)) and ratio < 0.015
+    t = I.case_by_name("tiny")
+    L = I.make_layer(t, M=32)
+    assert L["x_bf16"].shape == (32, 1152) and L["w"].shape == (1152, 1152)
+    # seeded: same call, same bits
+    assert np.array_equal(L["x_bf16"], I.make_x(t, M=32))
+    assert len(I.all_cases()) == 6 + 16
+
+
+@pytest.mark.parametrize("alpha", [0.3, 0.5])
+def test_tiny_config_end_to_end_quality(alpha):
+    t = I.case_by_name("tiny")
+    L = I.make_layer(t, M=64)
+    w = L["w"][:, :256].copy()
+    P = O.prepare(w, L["x_absmax"], rank=32, alpha=alpha, bias=L["bias"][:256])
+    out = O.forward(L["x_bf16"], P, want_f64=True)
+    ref = O.bf16_to_f32(L["x_bf16"]).astype(np.float64) @ w.astype(np.float64) + L["bias"][:256]
+    assert np.linalg.norm(out["Y64"] - ref) / np.linalg.norm(ref) < 0.2
+    assert np.linalg.norm(out["Y"] - out["Y64"]) / np.linalg.norm(out["Y64"]) < 1e-6

@@ -1,0 +1,67 @@
+"""The pins must be able to fail: plant plausible mistakes in the oracle (on the CPU) and check a pin trips.
+
+Each mutation swaps one oracle function for a subtly wrong variant (a transposed operand, a wrong
+rounding mode, a dropped term, the wrong scale index) and re-runs one pinned test, which must fail.
+"""
+import numpy as np
+import pytest
+
+from oracle import svdq_oracle as O
+import tests.test_oracle_layer as TL
+import tests.test_oracle_quantizer as TQ
+
+
+def _must_fail(fn):
+    with pytest.raises(AssertionError):
+        fn()
+
+
+def test_wrong_rounding_mode_is_caught(monkeypatch):
+    real = np.rint
+    monkeypatch.setattr(O.np, "rint", lambda a: np.sign(a) * np.floor(np.abs(a) + 0.5))   # half away from zero
+    _must_fail(TQ.test_round_half_to_even_ties_from_golden_file)
+    monkeypatch.setattr(O.np, "rint", real)
+    TQ.test_round_half_to_even_ties_from_golden_file()
+
+
+def test_unrounded_scale_is_caught(monkeypatch):
+    def bad(v):
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        vg = v.reshape(v.shape[:-1] + (v.shape[-1] // 64, 64))
+        s = np.max(np.abs(vg), axis=-1) / np.float32(7)          # scale never rounded to 16 bit
+        q = np.clip(np.rint(vg / np.where(s > 0, s, 1)[..., None]), -7, 7).astype(np.int8)
+        return q.reshape(v.shape), s.astype(np.float16)
+    monkeypatch.setattr(O, "quantize_groups", bad)
+    _must_fail(TQ.test_bruteforce_against_exact_rationals)
+
+
+def test_column_scaling_instead_of_row_scaling_is_caught(monkeypatch):
+    monkeypatch.setattr(O, "smooth_weight", lambda W, lam: np.asarray(W, np.float64) * np.asarray(lam, np.float64)[: W.shape[1]][None, :])
+    _must_fail(TL.test_smoothing_leaves_the_product_unchanged_and_moves_outliers)
+
+
+def test_sigma_split_mistake_is_caught(monkeypatch):
+    def bad(W_hat, r):
+        U, S, Vt = np.linalg.svd(W_hat, full_matrices=False)
+        return U[:, :r] * np.sqrt(S[:r]), np.sqrt(S[:r])[:, None] * Vt[:r], S      # Sigma split between factors
+    monkeypatch.setattr(O, "lowrank_svd", bad)
+    _must_fail(TL.test_lowrank_matches_eckart_young_and_known_factors)
+
+
+def test_dropped_lowrank_term_and_wrong_scale_index_are_caught(monkeypatch):
+    real_forward = O.forward
+    monkeypatch.setattr(O, "forward", lambda xb, P, **kw: real_forward(xb, P, **{**kw, "lowrank": False}))
+    _must_fail(TL.test_forward_equals_plain_definition_of_eq5)
+    monkeypatch.setattr(O, "forward", real_forward)
+
+    def bad_quantize_residual(R):            # groups taken along N instead of K
+        q, s = O.quantize_groups(np.asarray(R, np.float64).astype(np.float32))
+        return q, np.ascontiguousarray(np.repeat(s, 64, axis=1)[: R.shape[0] // 64, :])
+    monkeypatch.setattr(O, "quantize_residual", bad_quantize_residual)
+    _must_fail(TL.test_prepare_residual_identity_and_ranges)
+
+
+def test_transposed_group_sum_is_caught(monkeypatch):
+    real = O.group_sums
+    monkeypatch.setattr(O, "group_sums", lambda qx, qw: real(qx, np.ascontiguousarray(qw[::-1])))
+    _must_fail(TL.test_group_sums_against_integer_loops_and_extremes)
