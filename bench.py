@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused W4A4 + low-rank linear layer (arXiv 2411.05007, Eq. 5) on one MI355X.
+
+One "step" is one pass of the whole hot path - activation kernel (smooth + INT4 quantize + down
+projection) and W4A4 GEMM (with up projection, bias and bf16 store) - over one batch of synthetic
+FLUX-MLP-shaped input (M=4608, K=3072, N=12288, r=32) already resident in HBM.
+
+Prints ONE JSON line with the headline metric (TOPS of the 4-bit branch, 2*M*N*K per layer time),
+the roofline of the dominant kernel (the GEMM, against the INT8 MFMA peak) measured live with HIP
+events on the stream the kernels run on, and the CPU oracle timed on a bounded row sample.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0       # MI355X dense INT8, published
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic of one GEMM launch at the headline shape from `rocprofv3 --pmc FETCH_SIZE` /
+# `--pmc WRITE_SIZE` (see profiles/), scaled by a copy kernel of known size; None until measured.
+GEMM_TRAFFIC_BYTES = None
+
+
+class Hip:
+    """The few HIP runtime calls the timing needs (events on a given stream)."""
+
+    def __init__(self):
+        self.rt = C.CDLL("libamdhip64.so")
+        self.rt.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.rt.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.rt.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.rt.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.rt.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def event(self):
+        e = C.c_void_p()
+        assert self.rt.hipEventCreate(C.byref(e)) == 0
+        return e
+
+    def record(self, e, stream):
+        assert self.rt.hipEventRecord(e, C.c_void_p(stream)) == 0
+
+    def sync(self, e):
+        assert self.rt.hipEventSynchronize(e) == 0
+
+    def ms(self, a, b):
+        out = C.c_float()
+        assert self.rt.hipEventElapsedTime(C.byref(out), a, b) == 0
+        return float(out.value)
+
+
+def cpu_baseline(case, L, prep_canon, rows=768):
+    """The oracle as it stands, timed on the host cores over the first `rows` tokens of the same workload."""
+    import numpy as np
+    from oracle import svdq_oracle as O
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    xb = L["x_bf16"][:rows]
+    best = float("inf")
+    for _ in range(2):
+        t0 = time.perf_counter()
+        O.forward(xb, prep_canon)
+        best = min(best, time.perf_counter() - t0)
+    ops = 2.0 * rows * case.N * case.K
+    return {"value": ops / best / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {rows} of {case.M} tokens, all K and N, best of 2 ({best:.2f} s); scaled by 2*rows*N*K",
+            "us_per_layer_extrapolated": best * case.M / rows * 1e6}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--case", default="flux_mlp_up", help="layer name from paper_2411_05007_amd.inputs (default: the metric shape)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile", type=int, default=0, help="GEMM tile configuration id (0 = library default)")
+    ap.add_argument("--breakdown", action="store_true", help="also time naive INT4 (no low-rank) and the unfused 4-kernel pipeline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X per box); run with --gpus 1. "
+              "Rows of X are independent, so N GPUs would each take M/N tokens with replicated weights.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2411_05007_amd import inputs as I
+    from paper_2411_05007_amd import svdq as S
+
+    S.lib()   # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    case = I.case_by_name(args.case)
+    L = I.make_layer(case)
+    prep = S.svdq_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    layer = S.DeviceLayer(prep, dev)
+
+    # >= 3 independent (X, Y, workspace) sets so the footprint exceeds the 256 MB last-level cache
+    nsets = 3
+    xs, ys, wss = [], [], []
+    for i in range(nsets):
+        xb = L["x_bf16"] if i == 0 else np.roll(L["x_bf16"], 17 * i, axis=0)
+        xs.append(S.bf16_tensor_from_bits(np.ascontiguousarray(xb), dev))
+        ys.append(torch.empty((case.M, case.N), dtype=torch.bfloat16, device=dev))
+        wss.append(layer.workspace(case.M))
+
+    hip = Hip()
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def run(flags, steps, warmup, split):
+        S.svdq_forward_options(flags | (args.tile << S.OPT_TILE_SHIFT))
+        for i in range(warmup):
+            layer.forward(xs[i % nsets], out=ys[i % nsets], workspace=wss[i % nsets], stream=stream)
+        torch.cuda.synchronize()
+        ev = [(hip.event(), hip.event(), hip.event()) for _ in range(steps)] if split else None
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            j = i % nsets
+            if split:
+                a, m, b = ev[i]
+                S.svdq_profile_event(m.value)
+                hip.record(a, sh)
+                layer.forward(xs[j], out=ys[j], workspace=wss[j], stream=stream)
+                hip.record(b, sh)
+            else:
+                layer.forward(xs[j], out=ys[j], workspace=wss[j], stream=stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        S.svdq_profile_event(None)
+        res = {"ms_per_step": wall * 1e3 / steps}
+        if split:
+            act = [hip.ms(a, m) for a, m, b in ev]
+            gemm = [hip.ms(m, b) for a, m, b in ev]
+            for a, m, b in ev:
+                for e in (a, m, b):
+                    hip.rt.hipEventDestroy(e)
+            res.update(act_ms=float(np.mean(act)), gemm_ms=float(np.mean(gemm)),
+                       gemm_ms_min=float(np.min(gemm)), act_ms_min=float(np.min(act)))
+        return res
+
+    main_res = run(0, args.steps, args.warmup, split=True)
+    ms = main_res["ms_per_step"]
+    ops = float(case.ops)
+    tops = ops / (ms * 1e-3) / 1e12
+    gemm_tops = ops / (main_res["gemm_ms"] * 1e-3) / 1e12
+    G = case.K // 64
+    act_bytes = case.M * case.K * (2 + 0.5 + 2.0 / 64) + 4.0 * case.M * case.rank     # algorithmic bytes of the activation pass
+    out = {
+        "metric": "fused W4A4+low-rank linear TOPS & us/layer, FLUX MLP M=4608 K=3072 N=12288 r=32"
+                  if case.name == "flux_mlp_up" else f"fused W4A4+low-rank linear TOPS & us/layer, {case.name}",
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "us_per_layer": ms * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8 MFMA (int4 codes), int32 group sums, fp32 rescale, bf16 out",
+        "data": "synthetic",
+        "config": {"workload": f"{case.name}: M={case.M} K={case.K} N={case.N} r={case.rank} g=64 "
+                               f"(BASELINE configs[3] up projection)", "tile": args.tile, "sets_rotated": nsets},
+        "kernels": {"act_us": main_res["act_ms"] * 1e3, "gemm_us": main_res["gemm_ms"] * 1e3,
+                    "gemm_us_min": main_res["gemm_ms_min"] * 1e3,
+                    "act_GBps": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9,
+                    "act_frac_hbm_peak": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (W4A4 GEMM + up projection epilogue)",
+                     "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
+                     "note": "INT8 tera-ops/s: 2*M*N*K per launch / mean launch duration (HIP events on the launch stream)",
+                     "frac": gemm_tops / INT8_MFMA_PEAK_TOPS, "traffic": GEMM_TRAFFIC_BYTES},
+    }
+    if args.breakdown:
+        naive = run(S.OPT_SKIP_LOWRANK, max(20, args.steps // 4), 5, split=False)
+        unfused = run(S.OPT_UNFUSED, max(20, args.steps // 4), 5, split=False)
+        out["breakdown"] = {"fused_us": ms * 1e3, "naive_int4_us": naive["ms_per_step"] * 1e3,
+                            "unfused_us": unfused["ms_per_step"] * 1e3,
+                            "lowrank_overhead_fused": ms / naive["ms_per_step"] - 1.0,
+                            "lowrank_overhead_unfused": unfused["ms_per_step"] / naive["ms_per_step"] - 1.0}
+    S.svdq_forward_options(0)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case, L, S.svdq_unpack(prep))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

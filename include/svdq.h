@@ -1,0 +1,170 @@
+/*
+ * libsvdq - SVDQuant W4A4 + low-rank linear layer for AMD MI355X (gfx950 / CDNA4).
+ *
+ * The layer computes (arXiv 2411.05007, Eq. 5, with the per-group form of Eq. 2):
+ *
+ *     Y = X^ L1 L2  +  Q(X^) Q(R)  +  bias
+ *
+ *   X^ = X diag(lambda)^-1      smoothed activation (Sec. 4.2 "Migrate outliers")
+ *   W^ = diag(lambda) W = L1 L2 + R,  L1 = U Sigma[:, :r], L2 = V[:r, :]  (Sec. 4.2, SVD)
+ *   Q(.)  symmetric max-abs quantizer of Eq. 1 with q_max = 7 (signed 4 bit), applied to
+ *         groups of 64 consecutive input channels, with fp16 scales (App. "Implementation
+ *         Details"): s = fp16(max|v| / 7), code = clamp(rne(v * (1.0f / s)), -7, 7).
+ *
+ * Shapes: X [M x K] tokens x input channels, W [K x N] (y = x W), r = rank, G = K / 64.
+ *
+ * Conventions
+ *   - Every function returns an svdq_status (0 = ok, negative = error); nothing throws or exits.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the
+ *     current device.  The library never allocates, frees or copies device memory for the
+ *     caller and never creates streams: all buffers and the stream come from the caller.
+ *   - svdq_linear_forward only enqueues kernels on the given stream (no host synchronisation).
+ *     Calls for different layers may overlap on different streams if they use different
+ *     workspaces.
+ *   - 16-bit floats cross the boundary as uint16_t bit patterns (bf16 or fp16 as stated).
+ *   - "native" buffers are opaque, kernel-ordered; the svdq_unpack_ / svdq_pack_ functions
+ *     convert them from and to the canonical row-major forms documented below.
+ */
+#ifndef SVDQ_H
+#define SVDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SVDQ_OK = 0,
+    SVDQ_EINVAL = -1,       /* null pointer, non-positive size, misaligned pointer */
+    SVDQ_EUNSUPPORTED = -2, /* K % 64 != 0, rank % 16 != 0, rank > 256, rank > min(K, N), N % 16 != 0, group != 64 */
+    SVDQ_ENOMEM = -3,       /* host allocation failed inside svdq_prepare */
+    SVDQ_ENOSPACE = -4,     /* workspace smaller than svdq_workspace_bytes() */
+    SVDQ_EHIP = -5          /* a HIP call failed; see svdq_last_hip_error() */
+} svdq_status;
+
+const char *svdq_status_string(int status);
+/* hipError_t of the last failing HIP call made by this library on the calling thread (0 if none). */
+int svdq_last_hip_error(void);
+
+/* Static description of one layer.  group must be 64.  alpha is the migration strength of the
+ * smoothing factor lambda_k = max|X_:,k|^alpha / max|W_k,:|^(1-alpha) (App. "Implementation Details"). */
+typedef struct {
+    int K, N, rank, group;
+    float alpha;
+} svdq_shape;
+
+/* Byte sizes of the prepared ("native") buffers of one layer. */
+typedef struct {
+    size_t rinv;    /* fp32 [K]                     1 / lambda                                    */
+    size_t l1s;     /* bf16, K * rank elements      diag(lambda)^-1 L1, MFMA-fragment order       */
+    size_t l2;      /* bf16, Npad * rank elements   L2 transposed                                 */
+    size_t wcodes;  /* G * Npad * 32 bytes          4-bit codes of R, two per byte, group-major   */
+    size_t wscales; /* fp16 [G][Npad]               scales of R                                    */
+    size_t bias;    /* fp32 [Npad]                                                                 */
+} svdq_sizes;
+
+int svdq_prepared_sizes(const svdq_shape *shape, svdq_sizes *out);
+
+/*
+ * Offline quantization of one layer on the HOST (Sec. 4.2; App. "Implementation Details"):
+ * smoothing factor -> W^ = diag(lambda) W -> rank-r truncated SVD -> residual against the
+ * bf16-rounded factors -> per-group INT4 codes + fp16 scales -> native packing.
+ *   W         host fp32 [K x N] row-major
+ *   x_absmax  host fp32 [K]: calibration statistic max_m |X[m, k]|
+ *   bias      host fp32 [N] or NULL (treated as zero)
+ * All out_* are host buffers allocated by the caller with the sizes of svdq_prepared_sizes();
+ * the caller keeps ownership and uploads them to the device itself.
+ * lambda is set to 1 for channels where it would be zero, infinite or NaN.
+ * The truncated SVD is a randomized subspace iteration in fp64 (any rank-r factors are valid:
+ * the residual absorbs what they miss).  No iterative refinement or GPTQ is applied.
+ */
+int svdq_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                 float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                 uint16_t *out_wscales, float *out_bias);
+
+/*
+ * Pack an externally quantized layer (canonical forms, all HOST) into native buffers:
+ *   rinv fp32 [K]; l1s bf16 [K x rank]; l2 bf16 [rank x N]; qw int8 [K x N] codes in [-7, 7];
+ *   sw fp16 [G x N]; bias fp32 [N] or NULL.
+ * Codes outside [-8, 7] are rejected with SVDQ_EINVAL.
+ */
+int svdq_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
+              const int8_t *qw, const uint16_t *sw, const float *bias,
+              float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+              uint16_t *out_wscales, float *out_bias);
+
+/* Native -> canonical views (HOST), for inspection and parity checks. */
+int svdq_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, int8_t *out_qw /* [K x N] */);
+int svdq_unpack_wscales(const svdq_shape *shape, const uint16_t *wscales, uint16_t *out_sw /* fp16 [G x N] */);
+int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out /* bf16 [K x rank] */);
+int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out /* bf16 [rank x N] */);
+
+/* Device copies of the native buffers of one layer (all DEVICE pointers, 16-byte aligned). */
+typedef struct {
+    const void *rinv, *l1s, *l2, *wcodes, *wscales, *bias;
+    svdq_shape shape;
+} svdq_layer_dev;
+
+/* Bytes of device scratch one forward of M tokens needs: activation codes and scales,
+ * and the low-rank intermediate H = X^ L1 (fp32 [M x rank]).  0 if the shape is unsupported. */
+size_t svdq_workspace_bytes(int M, const svdq_shape *shape);
+
+/*
+ * The hot path (Eq. 5; kernel split after Sec. 4.3 / Fig. 6b): two kernels on `hip_stream`
+ *   1. activation kernel: reads X once; smoothing, per-group INT4 quantization with fp16 scales,
+ *      and the down projection H = X^ L1
+ *   2. W4A4 GEMM: INT4 -> INT8 MFMA with exact int32 sums per group of 64, fp32 rescale by
+ *      s_x s_w, then H L2, bias and the bf16 store in the epilogue.
+ *   X  device bf16 [M x K] row-major, 16-byte aligned;  Y device bf16 [M x N] row-major.
+ *   workspace: device, 256-byte aligned, >= svdq_workspace_bytes(M, shape); contents are
+ *   overwritten; two forwards that share a workspace must be ordered on one stream.
+ *   M = 0 is a no-op.  hip_stream is a hipStream_t (NULL = the default stream).
+ */
+int svdq_linear_forward(const svdq_layer_dev *layer, const void *X, int M, void *Y,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Parity views of what the last svdq_linear_forward left in `workspace` (same stream ordering):
+ * canonical activation codes int8 [M x K], scales fp16 [M x G], H fp32 [M x rank]; any out
+ * pointer may be NULL.  All DEVICE pointers.
+ */
+int svdq_debug_act(const svdq_layer_dev *layer, const void *workspace, int M,
+                   int8_t *out_codes, uint16_t *out_sx, float *out_H, void *hip_stream);
+
+/*
+ * Exact int32 group sums A_g[m, n] = sum_{k in g} qx[m, k] qw[k, n] for the window
+ * m0 <= m < m1, n0 <= n < n1, all g, produced by the GEMM kernel itself (the same instantiation
+ * of the MFMA loop with an extra store), from the codes in `workspace`.
+ *   out device int32 [(m1 - m0) x (n1 - n0) x G].
+ */
+int svdq_debug_group_acc(const svdq_layer_dev *layer, const void *workspace, int M,
+                         int m0, int m1, int n0, int n1, int32_t *out, void *hip_stream);
+
+/*
+ * Measurement switches, process-wide, read at each svdq_linear_forward (Sec. 4.3 / Fig. 6a,
+ * App. "Latency Results": naive INT4 and the unfused four-kernel pipeline).  Returns the
+ * previous flags; pass a negative value to query only.
+ */
+enum {
+    SVDQ_OPT_SKIP_LOWRANK = 1, /* 4-bit branch only: no down projection, no up projection        */
+    SVDQ_OPT_UNFUSED = 2,      /* down projection, quantize, 4-bit GEMM, up projection as four
+                                  kernels; needs workspace of svdq_workspace_bytes()              */
+    SVDQ_OPT_TILE_SHIFT = 8,   /* bits 8..15: GEMM tile configuration id, 0 = chosen by shape     */
+    SVDQ_OPT_TILE_MASK = 0xff00
+};
+int svdq_forward_options(int flags);
+
+/*
+ * Measurement only, process-wide: if `hip_event` (a hipEvent_t) is non-NULL, every following
+ * svdq_linear_forward records it on its stream between the activation kernel and the GEMM, so a
+ * caller that brackets the call with its own events gets the two kernels' durations separately
+ * (the per-kernel split behind Fig. 6a).  Pass NULL to switch it off.  Returns SVDQ_OK.
+ */
+int svdq_profile_event(void *hip_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVDQ_H */

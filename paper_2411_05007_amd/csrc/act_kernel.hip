@@ -1,0 +1,179 @@
+// Activation kernel: one pass over X that fuses smoothing, per-group INT4 quantization with fp16
+// scales, and the low-rank down projection H = X^ L1 (arXiv 2411.05007 Sec. 4.3, Fig. 6b: "Quantize"
+// and "Down Projection" share their input; quantizer = Eq. 1 per group of 64, App. "Implementation
+// Details").
+//
+// Work split: one workgroup (4 wavefronts) owns 16 tokens and all of K; wavefront w takes the groups
+// g = w, w+4, ...  Inside a wavefront, lane l holds token (l % 16) and the 16 consecutive channels
+// 16*(l/16) .. +15 of the current group, i.e. exactly the A-operand fragment of two
+// v_mfma_f32_16x16x32_bf16 steps, so the bf16 registers loaded from HBM feed the matrix core as they
+// are while the same registers are smoothed and quantized on the vector ALU.
+// The k order inside a group is permuted relative to the instruction's nominal order; l1s is stored
+// offline in the matching order, and a dot product does not care.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+#include "layout.h"
+
+namespace svdq {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int RBMAX, bool QUANT, bool PROJ>
+__global__ __launch_bounds__(256) void act_kernel(ActParams p) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int row = lane & 15;
+    const int blk = lane >> 4;
+    const int m0 = blockIdx.x * 16;
+    const int m = m0 + row;
+    const bool valid = m < p.M;
+    const int mload = valid ? m : p.M - 1;
+    const int rb = p.rank / 16;
+
+    floatx4 acc[RBMAX];
+#pragma unroll
+    for (int c = 0; c < RBMAX; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const uint16_t *xrow = p.X + (size_t)mload * p.K + 16 * blk;
+
+    for (int g = wave; g < p.G; g += 4) {
+        const uint4 *xp = reinterpret_cast<const uint4 *>(xrow + 64 * g);
+        const uint4 x0 = xp[0];
+        const uint4 x1 = xp[1];
+
+        if (PROJ) {
+            const uint4 *lp = reinterpret_cast<const uint4 *>(p.l1s) + ((size_t)g * 2 * rb) * 64 + lane;
+#pragma unroll
+            for (int c = 0; c < RBMAX; ++c) {
+                if (c < rb) {
+                    const uint4 b0 = lp[(size_t)c * 64];
+                    const uint4 b1 = lp[(size_t)(rb + c) * 64];
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0),
+                                                                     __builtin_bit_cast(bf16x8, b0), acc[c], 0, 0, 0);
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1),
+                                                                     __builtin_bit_cast(bf16x8, b1), acc[c], 0, 0, 0);
+                }
+            }
+        }
+
+        if (QUANT) {
+            const float4 *rp = reinterpret_cast<const float4 *>(p.rinv + 64 * g + 16 * blk);
+            const float4 r0 = rp[0], r1 = rp[1], r2 = rp[2], r3 = rp[3];
+            float xh[16];
+            xh[0] = bf16lo(x0.x) * r0.x;  xh[1] = bf16hi(x0.x) * r0.y;
+            xh[2] = bf16lo(x0.y) * r0.z;  xh[3] = bf16hi(x0.y) * r0.w;
+            xh[4] = bf16lo(x0.z) * r1.x;  xh[5] = bf16hi(x0.z) * r1.y;
+            xh[6] = bf16lo(x0.w) * r1.z;  xh[7] = bf16hi(x0.w) * r1.w;
+            xh[8] = bf16lo(x1.x) * r2.x;  xh[9] = bf16hi(x1.x) * r2.y;
+            xh[10] = bf16lo(x1.y) * r2.z; xh[11] = bf16hi(x1.y) * r2.w;
+            xh[12] = bf16lo(x1.z) * r3.x; xh[13] = bf16hi(x1.z) * r3.y;
+            xh[14] = bf16lo(x1.w) * r3.z; xh[15] = bf16hi(x1.w) * r3.w;
+            float amax = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(xh[e]));
+            amax = fmaxf(amax, __shfl_xor(amax, 16, 64));
+            amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+            // Eq. 1: s = max|x| / q_max, stored as fp16; codes from x * (1/s)
+            float s32 = amax / 7.0f;
+            s32 = fminf(s32, 65504.0f);
+            const _Float16 sh = (_Float16)s32;
+            const float s = (float)sh;
+            const float rcp = s > 0.f ? 1.0f / s : 0.f;
+            uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float q = __builtin_rintf(xh[e] * rcp);
+                q = fminf(7.f, fmaxf(-7.f, q));
+                const uint32_t nib = (uint32_t)((int)q) & 0xfu;
+                packed[e >> 3] |= nib << (4 * (e & 7));
+            }
+            if (valid) {
+                uint2 *cp = reinterpret_cast<uint2 *>(p.codes + ((size_t)g * p.Mpad + m) * kCodeBytes + 8 * blk);
+                *cp = make_uint2(packed[0], packed[1]);
+                if (blk == 0) p.sx[(size_t)g * p.Mpad + m] = __builtin_bit_cast(uint16_t, sh);
+            }
+        }
+    }
+
+    if (PROJ) {
+        // deterministic reduction of the four wavefronts' partial H through LDS
+        __shared__ float red[3][16][RBMAX * 16 + 1];
+        if (wave > 0) {
+#pragma unroll
+            for (int c = 0; c < RBMAX; ++c)
+                if (c < rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) red[wave - 1][4 * blk + v][16 * c + row] = acc[c][v];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int c = 0; c < RBMAX; ++c)
+                if (c < rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int r = 4 * blk + v, col = 16 * c + row;
+                        float h = acc[c][v];
+                        h += red[0][r][col];
+                        h += red[1][r][col];
+                        h += red[2][r][col];
+                        if (m0 + r < p.M) p.H[(size_t)(m0 + r) * p.rank + col] = h;
+                    }
+        }
+    }
+}
+
+template <int RBMAX>
+hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
+    const dim3 grid((p.M + 15) / 16), block(256);
+    const bool q = flags & 1, pr = (flags & 2) && p.rank > 0;
+    if (q && pr) hipLaunchKernelGGL((act_kernel<RBMAX, true, true>), grid, block, 0, stream, p);
+    else if (q) hipLaunchKernelGGL((act_kernel<1, true, false>), grid, block, 0, stream, p);
+    else if (pr) hipLaunchKernelGGL((act_kernel<RBMAX, false, true>), grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+// canonical views of the workspace for parity checks
+__global__ void debug_act_kernel(DebugActParams p) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t ncodes = (size_t)p.M * p.K;
+    if (p.out_codes && idx < ncodes) {
+        const int m = (int)(idx / p.K), k = (int)(idx % p.K);
+        const int g = k / 64, kk = k % 64;
+        const uint8_t b = p.codes[((size_t)g * p.Mpad + m) * kCodeBytes + kk / 2];
+        const int nib = (kk & 1) ? (b >> 4) : (b & 0xf);
+        p.out_codes[idx] = (int8_t)((nib ^ 8) - 8);
+    }
+    if (p.out_sx && idx < (size_t)p.M * p.G) {
+        const int m = (int)(idx / p.G), g = (int)(idx % p.G);
+        p.out_sx[idx] = p.sx[(size_t)g * p.Mpad + m];
+    }
+    if (p.out_H && idx < (size_t)p.M * p.rank) p.out_H[idx] = p.H[idx];
+}
+
+}  // namespace
+
+hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    if (p.rank <= 32) return launch_rb<2>(p, flags, stream);
+    if (p.rank <= 64) return launch_rb<4>(p, flags, stream);
+    if (p.rank <= 128) return launch_rb<8>(p, flags, stream);
+    return launch_rb<16>(p, flags, stream);
+}
+
+hipError_t launch_debug_act(const DebugActParams &p, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    const size_t n = (size_t)p.M * p.K;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    hipLaunchKernelGGL(debug_act_kernel, grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace svdq

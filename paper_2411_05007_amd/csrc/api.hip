@@ -1,0 +1,177 @@
+// C-ABI entry points that run on the GPU: argument checks, workspace carve-up, kernel launches.
+// Nothing here allocates device memory or synchronises with the host.
+#include <hip/hip_runtime.h>
+#include <atomic>
+#include <cstdlib>
+
+#include "../../include/svdq.h"
+#include "kernels.h"
+#include "layout.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+std::atomic<int> g_options{0};
+std::atomic<void *> g_profile_event{nullptr};
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return SVDQ_EHIP;
+}
+
+int check_layer(const svdq_layer_dev *L) {
+    if (!L) return SVDQ_EINVAL;
+    const svdq_shape &s = L->shape;
+    if (s.K <= 0 || s.N <= 0 || s.rank < 0) return SVDQ_EINVAL;
+    if (s.group != svdq::kGroup || s.K % svdq::kGroup != 0 || s.N % 16 != 0 || s.rank % 16 != 0 ||
+        s.rank > svdq::kMaxRank || s.rank > (s.K < s.N ? s.K : s.N))
+        return SVDQ_EUNSUPPORTED;
+    if (!L->rinv || !L->wcodes || !L->wscales || !L->bias) return SVDQ_EINVAL;
+    if (s.rank > 0 && (!L->l1s || !L->l2)) return SVDQ_EINVAL;
+    const uintptr_t bits = (uintptr_t)L->rinv | (uintptr_t)L->wcodes | (uintptr_t)L->wscales | (uintptr_t)L->bias |
+                           (uintptr_t)L->l1s | (uintptr_t)L->l2;
+    if (bits & 15) return SVDQ_EINVAL;
+    return SVDQ_OK;
+}
+
+int tile_override() {
+    const int opt = (g_options.load() & SVDQ_OPT_TILE_MASK) >> SVDQ_OPT_TILE_SHIFT;
+    if (opt) return opt;
+    static const int v = [] {
+        const char *e = std::getenv("SVDQ_GEMM_TILE");
+        return e ? std::atoi(e) : 0;
+    }();
+    return v;
+}
+
+svdq::GemmParams gemm_params(const svdq_layer_dev *L, unsigned char *ws, const svdq::Workspace &w, int M, void *Y, int rank) {
+    const svdq_shape &s = L->shape;
+    svdq::GemmParams g{};
+    g.xcodes = ws + w.codes_off;
+    g.sx = reinterpret_cast<const uint16_t *>(ws + w.sx_off);
+    g.H = reinterpret_cast<const float *>(ws + w.h_off);
+    g.wcodes = static_cast<const uint8_t *>(L->wcodes);
+    g.sw = static_cast<const uint16_t *>(L->wscales);
+    g.l2t = static_cast<const uint16_t *>(L->l2);
+    g.bias = static_cast<const float *>(L->bias);
+    g.Y = static_cast<uint16_t *>(Y);
+    g.M = M; g.N = s.N; g.K = s.K; g.G = s.K / svdq::kGroup;
+    g.Mpad = w.Mpad; g.Npad = svdq::round_up(s.N, svdq::kRowPad);
+    g.rank = rank;
+    g.dbg = nullptr;
+    g.magic = svdq::kMagicBits;
+    return g;
+}
+
+}  // namespace
+
+extern "C" {
+
+int svdq_last_hip_error(void) { return g_last_hip_error; }
+
+int svdq_forward_options(int flags) {
+    if (flags < 0) return g_options.load();
+    return g_options.exchange(flags & (SVDQ_OPT_SKIP_LOWRANK | SVDQ_OPT_UNFUSED | SVDQ_OPT_TILE_MASK));
+}
+
+int svdq_profile_event(void *hip_event) {
+    g_profile_event.store(hip_event);
+    return SVDQ_OK;
+}
+
+size_t svdq_workspace_bytes(int M, const svdq_shape *s) {
+    if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
+    return svdq::workspace_layout(M, s->K, s->rank).total;
+}
+
+int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
+                        size_t workspace_bytes, void *hip_stream) {
+    const int st = check_layer(L);
+    if (st != SVDQ_OK) return st;
+    if (M < 0) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    if (!X || !Y || !workspace) return SVDQ_EINVAL;
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
+    const svdq_shape &s = L->shape;
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.rank);
+    if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    const int opts = g_options.load();
+    const bool lowrank = s.rank > 0 && !(opts & SVDQ_OPT_SKIP_LOWRANK);
+    const bool unfused = opts & SVDQ_OPT_UNFUSED;
+
+    svdq::ActParams a{};
+    a.X = static_cast<const uint16_t *>(X);
+    a.rinv = static_cast<const float *>(L->rinv);
+    a.l1s = static_cast<const uint16_t *>(L->l1s);
+    a.codes = ws + w.codes_off;
+    a.sx = reinterpret_cast<uint16_t *>(ws + w.sx_off);
+    a.H = reinterpret_cast<float *>(ws + w.h_off);
+    a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
+
+    hipError_t e;
+    if (!unfused) {
+        e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
+        if (e != hipSuccess) return hip_fail(e);
+        if (void *ev = g_profile_event.load()) {
+            e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        const svdq::GemmParams g = gemm_params(L, ws, w, M, Y, lowrank ? s.rank : 0);
+        e = svdq::launch_gemm(g, tile_override(), stream);
+        if (e != hipSuccess) return hip_fail(e);
+    } else {
+        // the four-kernel pipeline of Fig. 6a: down projection, quantize, 4-bit GEMM, up projection
+        if (lowrank) {
+            e = svdq::launch_act(a, 2, stream);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        e = svdq::launch_act(a, 1, stream);
+        if (e != hipSuccess) return hip_fail(e);
+        const svdq::GemmParams g = gemm_params(L, ws, w, M, Y, 0);
+        e = svdq::launch_gemm(g, tile_override(), stream);
+        if (e != hipSuccess) return hip_fail(e);
+        if (lowrank) {
+            e = svdq::launch_upproj(a.H, g.l2t, g.Y, M, s.N, s.rank, stream);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+    }
+    return SVDQ_OK;
+}
+
+int svdq_debug_act(const svdq_layer_dev *L, const void *workspace, int M, int8_t *out_codes, uint16_t *out_sx,
+                   float *out_H, void *hip_stream) {
+    const int st = check_layer(L);
+    if (st != SVDQ_OK) return st;
+    if (M < 0 || !workspace) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    const svdq_shape &s = L->shape;
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.rank);
+    const unsigned char *ws = static_cast<const unsigned char *>(workspace);
+    svdq::DebugActParams d{};
+    d.codes = ws + w.codes_off;
+    d.sx = reinterpret_cast<const uint16_t *>(ws + w.sx_off);
+    d.H = reinterpret_cast<const float *>(ws + w.h_off);
+    d.out_codes = out_codes; d.out_sx = out_sx; d.out_H = s.rank > 0 ? out_H : nullptr;
+    d.M = M; d.K = s.K; d.G = s.K / svdq::kGroup; d.Mpad = w.Mpad; d.rank = s.rank;
+    const hipError_t e = svdq::launch_debug_act(d, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
+int svdq_debug_group_acc(const svdq_layer_dev *L, const void *workspace, int M, int m0, int m1, int n0, int n1,
+                         int32_t *out, void *hip_stream) {
+    const int st = check_layer(L);
+    if (st != SVDQ_OK) return st;
+    const svdq_shape &s = L->shape;
+    if (!workspace || !out || M <= 0 || m0 < 0 || m1 > M || m0 >= m1 || n0 < 0 || n1 > s.N || n0 >= n1) return SVDQ_EINVAL;
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.rank);
+    unsigned char *ws = const_cast<unsigned char *>(static_cast<const unsigned char *>(workspace));
+    // the window-export instantiation of the kernel never stores Y
+    svdq::GemmParams g = gemm_params(L, ws, w, M, nullptr, 0);
+    g.dbg = out; g.m0 = m0; g.m1 = m1; g.n0 = n0; g.n1 = n1;
+    const hipError_t e = svdq::launch_gemm(g, tile_override(), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
+}  // extern "C"

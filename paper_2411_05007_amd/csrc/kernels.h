@@ -1,0 +1,59 @@
+// Internal launch interface between the C-ABI layer and the HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace svdq {
+
+// Bit pattern of 1.5 * 2^23.  An int32 MFMA accumulator seeded with it holds, read back as fp32,
+// exactly 12582912 + (integer sum) as long as |sum| < 2^22, which turns the int->float conversion
+// of every per-group partial sum into part of the rescale FMA.
+constexpr int32_t kMagicBits = 0x4B400000;
+constexpr float kMagic = 12582912.0f;
+
+struct ActParams {
+    const uint16_t *X;       // bf16 [M][K]
+    const float *rinv;       // fp32 [K]
+    const uint16_t *l1s;     // bf16, fragment order
+    uint8_t *codes;          // [G][Mpad][32]
+    uint16_t *sx;            // fp16 [G][Mpad]
+    float *H;                // fp32 [Mpad][rank]
+    int M, K, G, Mpad, rank;
+};
+
+// flags: bit 0 = quantize (codes + scales), bit 1 = down projection (H)
+hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream);
+
+struct GemmParams {
+    const uint8_t *xcodes;   // [G][Mpad][32]
+    const uint16_t *sx;      // fp16 [G][Mpad]
+    const float *H;          // fp32 [Mpad][rank]
+    const uint8_t *wcodes;   // [G][Npad][32]
+    const uint16_t *sw;      // fp16 [G][Npad]
+    const uint16_t *l2t;     // bf16 [Npad][rank]
+    const float *bias;       // fp32 [Npad]
+    uint16_t *Y;             // bf16 [M][N]
+    int M, N, K, G, Mpad, Npad, rank;   // rank == 0: no low-rank epilogue
+    int32_t *dbg;            // debug window of exact group sums, or null
+    int m0, m1, n0, n1;
+    int magic;               // kMagicBits, passed at run time so it stays in registers
+};
+
+// tile: 0 = choose by shape, otherwise a tile-config id (see gemm_kernel.hip)
+hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream);
+
+// Y[m][n] += sum_j H[m][j] L2[j][n]  as a separate read-modify-write pass (unfused baseline only)
+hipError_t launch_upproj(const float *H, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank, hipStream_t stream);
+
+struct DebugActParams {
+    const uint8_t *codes;
+    const uint16_t *sx;
+    const float *H;
+    int8_t *out_codes;       // [M][K] or null
+    uint16_t *out_sx;        // [M][G] or null
+    float *out_H;            // [M][rank] or null
+    int M, K, G, Mpad, rank;
+};
+hipError_t launch_debug_act(const DebugActParams &p, hipStream_t stream);
+
+}  // namespace svdq

@@ -1,0 +1,66 @@
+// Native buffer layouts shared by the host packer and the HIP kernels.
+//
+// Both 4-bit operands are stored "group-major": for every group g of 64 input channels, the
+// 64 codes of one row (a token of the activation, an output channel of the weight) are one
+// 32-byte block, and the blocks of all rows of that group are contiguous:
+//
+//     codes[g][row][32 bytes],   byte j = code(k = 64 g + 2 j) & 15  |  code(k = 64 g + 2 j + 1) << 4
+//     scales[g][row]  (fp16)
+//
+// so the GEMM's K loop streams one contiguous slab per operand per step.  Rows are padded to a
+// multiple of 256 so a full tile can always be read; padding rows of the weight hold zero
+// codes and zero scales.
+//
+// The two bf16 low-rank factors are stored in the order the MFMA instructions consume them:
+//   l1s  [G][2 (k step)][rank/16 (column block)][64 (lane)][8]  - B operand of
+//        v_mfma_f32_16x16x32_bf16 in the activation kernel: lane l, element e of k step s holds
+//        L1s[64 g + 16 (l / 16) + 8 s + e][16 c + l % 16]
+//   l2   [Npad][rank]  (L2 transposed) - B operand of v_mfma_f32_32x32x16_bf16 in the GEMM epilogue.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#ifndef __HIPCC__
+#ifndef __host__
+#define __host__
+#endif
+#ifndef __device__
+#define __device__
+#endif
+#endif
+
+namespace svdq {
+
+constexpr int kGroup = 64;
+constexpr int kRowPad = 256;        // rows of every group-major tensor are padded to this
+constexpr int kCodeBytes = 32;      // packed bytes of one row of one group
+constexpr int kMaxRank = 256;
+
+inline __host__ __device__ int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline __host__ __device__ size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+inline __host__ __device__ size_t l1s_index(int K, int rank, int k, int j) {
+    (void)K;
+    const int g = k / 64, kk = k % 64;
+    const int blk = kk / 16, s = (kk % 16) / 8, e = kk % 8;
+    const int c = j / 16, lane = blk * 16 + (j % 16);
+    return ((((size_t)g * 2 + s) * (rank / 16) + c) * 64 + lane) * 8 + e;
+}
+
+// Workspace carve-up for a forward of M tokens.
+struct Workspace {
+    size_t codes_off, sx_off, h_off, total;
+    int Mpad;
+};
+inline __host__ __device__ Workspace workspace_layout(int M, int K, int rank) {
+    Workspace w;
+    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
+    const int G = K / kGroup;
+    w.codes_off = 0;
+    w.sx_off = align256((size_t)G * w.Mpad * kCodeBytes);
+    w.h_off = w.sx_off + align256((size_t)G * w.Mpad * 2);
+    w.total = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    return w;
+}
+
+}  // namespace svdq

@@ -1,0 +1,516 @@
+// Host side of libsvdq: offline quantization of one layer and packing to the native layouts.
+//
+// Follows arXiv 2411.05007 Sec. 4.2 and App. "Implementation Details":
+//   lambda_k = max|X_:,k|^alpha / max|W_k,:|^(1-alpha)          smoothing factor
+//   W^ = diag(lambda) W = L1 L2 + R,  L1 = U Sigma[:, :r], L2 = V[:r, :]   (truncated SVD)
+//   R quantized per group of 64 along K with Eq. 1 (q_max = 7) and fp16 scales.
+// The truncated SVD is a randomized subspace iteration in fp64: every rank-r factor pair is a
+// valid low-rank branch because the residual R is taken against the factors actually stored
+// (rounded to bf16), so what the factors miss is absorbed by the 4-bit branch.
+//
+// All run-time-visible roundings (fp32 reciprocal of lambda, bf16 factors, fp16 scales, codes)
+// are done with explicit, correctly rounded steps; this file must be compiled without
+// fast-math and without floating-point contraction.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <functional>
+#include <new>
+#include <random>
+#include <thread>
+#include <vector>
+
+#include "../../include/svdq.h"
+#include "layout.h"
+
+namespace {
+
+using svdq::kCodeBytes;
+using svdq::kGroup;
+using svdq::kRowPad;
+
+// ----------------------------------------------------------------------------------------------
+// 16-bit float conversions (round to nearest, ties to even)
+// ----------------------------------------------------------------------------------------------
+inline uint32_t f32_bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+inline float bits_f32(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
+
+inline uint16_t f32_to_bf16(float f) {
+    uint32_t u = f32_bits(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+inline float bf16_to_f32(uint16_t b) { return bits_f32((uint32_t)b << 16); }
+
+inline uint16_t f32_to_f16(float f) {
+    const uint32_t u = f32_bits(f);
+    const uint32_t sign = (u >> 16) & 0x8000u;
+    const uint32_t a = u & 0x7fffffffu;
+    if (a >= 0x7f800000u) return (uint16_t)(sign | (a > 0x7f800000u ? 0x7e00u : 0x7c00u));
+    if (a >= 0x477ff000u) return (uint16_t)(sign | 0x7c00u);            // rounds to infinity
+    if (a < 0x33000001u) return (uint16_t)sign;                         // <= 2^-25 rounds to zero
+    int exp = (int)(a >> 23) - 127;
+    uint32_t man = (a & 0x7fffffu) | 0x800000u;
+    int shift;
+    uint32_t base;
+    if (exp < -14) { shift = 13 + (-14 - exp); base = 0; }              // subnormal half
+    else { shift = 13; base = (uint32_t)(exp + 15) << 10; man &= 0x7fffffu; }
+    const uint32_t q = man >> shift;
+    const uint32_t rem = man & ((1u << shift) - 1u);
+    const uint32_t half = 1u << (shift - 1);
+    uint32_t h = base + q;
+    if (rem > half || (rem == half && (q & 1u))) ++h;                   // carries into the exponent correctly
+    return (uint16_t)(sign | h);
+}
+inline float f16_to_f32(uint16_t h) {
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    const uint32_t exp = (h >> 10) & 0x1fu;
+    const uint32_t man = h & 0x3ffu;
+    if (exp == 0) {
+        if (man == 0) return bits_f32(sign);
+        const float v = (float)man * 5.9604644775390625e-08f;          // man * 2^-24, exact
+        return sign ? -v : v;
+    }
+    if (exp == 31) return bits_f32(sign | 0x7f800000u | (man << 13));
+    return bits_f32(sign | ((exp + 112u) << 23) | (man << 13));
+}
+
+// ----------------------------------------------------------------------------------------------
+// a minimal fork-join helper
+// ----------------------------------------------------------------------------------------------
+int thread_count() {
+    static const int n = [] {
+        int v = (int)std::thread::hardware_concurrency();
+        if (const char *e = std::getenv("SVDQ_THREADS")) v = std::atoi(e);
+        return std::max(1, std::min(v, 16));
+    }();
+    return n;
+}
+
+template <class F>
+void parallel_for(size_t n, F &&body) {   // body(begin, end, thread_index)
+    const int T = (int)std::min<size_t>((size_t)thread_count(), std::max<size_t>(n, 1));
+    if (T <= 1) { body((size_t)0, n, 0); return; }
+    std::vector<std::thread> th;
+    th.reserve(T);
+    for (int t = 0; t < T; ++t) {
+        const size_t b = n * t / T, e = n * (t + 1) / T;
+        th.emplace_back([&body, b, e, t] { body(b, e, t); });
+    }
+    for (auto &x : th) x.join();
+}
+
+// ----------------------------------------------------------------------------------------------
+// dense fp64 helpers for the randomized SVD.  A is K x N row-major.
+// ----------------------------------------------------------------------------------------------
+// C[k][0..l) = sum_n A[k][n] B[n][0..l)
+void mul_A_B(const double *A, int K, int N, const double *B, int l, double *C) {
+    parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+        for (size_t k = k0; k < k1; ++k) {
+            double *c = C + k * l;
+            std::fill(c, c + l, 0.0);
+            const double *a = A + k * (size_t)N;
+            for (int n = 0; n < N; ++n) {
+                const double av = a[n];
+                const double *b = B + (size_t)n * l;
+                for (int j = 0; j < l; ++j) c[j] += av * b[j];
+            }
+        }
+    });
+}
+
+// C[n][0..l) = sum_k A[k][n] B[k][0..l)      (A^T B)
+void mul_At_B(const double *A, int K, int N, const double *B, int l, double *C) {
+    parallel_for((size_t)N, [&](size_t n0, size_t n1, int) {
+        std::fill(C + n0 * l, C + n1 * l, 0.0);
+        for (int k = 0; k < K; ++k) {
+            const double *a = A + (size_t)k * N;
+            const double *b = B + (size_t)k * l;
+            for (size_t n = n0; n < n1; ++n) {
+                const double av = a[n];
+                double *c = C + n * l;
+                for (int j = 0; j < l; ++j) c[j] += av * b[j];
+            }
+        }
+    });
+}
+
+// G = Q^T Q for Q rows x l
+void gram(const double *Q, size_t rows, int l, std::vector<double> &G) {
+    const int T = thread_count();
+    std::vector<std::vector<double>> part(T, std::vector<double>((size_t)l * l, 0.0));
+    parallel_for(rows, [&](size_t r0, size_t r1, int t) {
+        double *g = part[t].data();
+        for (size_t r = r0; r < r1; ++r) {
+            const double *q = Q + r * l;
+            for (int i = 0; i < l; ++i) {
+                const double qi = q[i];
+                double *gi = g + (size_t)i * l;
+                for (int j = i; j < l; ++j) gi[j] += qi * q[j];
+            }
+        }
+    });
+    G.assign((size_t)l * l, 0.0);
+    for (int t = 0; t < T; ++t)
+        for (size_t i = 0; i < (size_t)l * l; ++i) G[i] += part[t][i];
+    for (int i = 0; i < l; ++i)
+        for (int j = 0; j < i; ++j) G[(size_t)i * l + j] = G[(size_t)j * l + i];
+}
+
+// Cyclic Jacobi eigen-decomposition of the symmetric l x l matrix S (destroyed).
+// On return ev[i] are the eigenvalues in descending order and V[:, i] (column i, row-major V) the vectors.
+void jacobi_eig(std::vector<double> &S, int l, std::vector<double> &ev, std::vector<double> &V) {
+    V.assign((size_t)l * l, 0.0);
+    for (int i = 0; i < l; ++i) V[(size_t)i * l + i] = 1.0;
+    for (int sweep = 0; sweep < 60; ++sweep) {
+        double off = 0.0, diag = 0.0;
+        for (int i = 0; i < l; ++i) {
+            diag += S[(size_t)i * l + i] * S[(size_t)i * l + i];
+            for (int j = i + 1; j < l; ++j) off += S[(size_t)i * l + j] * S[(size_t)i * l + j];
+        }
+        if (off <= 1e-30 * diag || off == 0.0) break;
+        for (int p = 0; p < l - 1; ++p) {
+            for (int q = p + 1; q < l; ++q) {
+                const double apq = S[(size_t)p * l + q];
+                if (apq == 0.0) continue;
+                const double app = S[(size_t)p * l + p], aqq = S[(size_t)q * l + q];
+                const double theta = (aqq - app) / (2.0 * apq);
+                const double t = (theta >= 0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
+                const double c = 1.0 / std::sqrt(t * t + 1.0), s = t * c;
+                for (int k = 0; k < l; ++k) {          // columns p, q
+                    const double skp = S[(size_t)k * l + p], skq = S[(size_t)k * l + q];
+                    S[(size_t)k * l + p] = c * skp - s * skq;
+                    S[(size_t)k * l + q] = s * skp + c * skq;
+                }
+                for (int k = 0; k < l; ++k) {          // rows p, q
+                    const double spk = S[(size_t)p * l + k], sqk = S[(size_t)q * l + k];
+                    S[(size_t)p * l + k] = c * spk - s * sqk;
+                    S[(size_t)q * l + k] = s * spk + c * sqk;
+                }
+                for (int k = 0; k < l; ++k) {
+                    const double vkp = V[(size_t)k * l + p], vkq = V[(size_t)k * l + q];
+                    V[(size_t)k * l + p] = c * vkp - s * vkq;
+                    V[(size_t)k * l + q] = s * vkp + c * vkq;
+                }
+            }
+        }
+    }
+    std::vector<int> order(l);
+    for (int i = 0; i < l; ++i) order[i] = i;
+    std::sort(order.begin(), order.end(), [&](int a, int b) { return S[(size_t)a * l + a] > S[(size_t)b * l + b]; });
+    ev.resize(l);
+    std::vector<double> Vs((size_t)l * l);
+    for (int i = 0; i < l; ++i) {
+        ev[i] = S[(size_t)order[i] * l + order[i]];
+        for (int k = 0; k < l; ++k) Vs[(size_t)k * l + i] = V[(size_t)k * l + order[i]];
+    }
+    V.swap(Vs);
+}
+
+// Q <- Q T for Q rows x l (row-major) and T l x l
+void right_multiply(double *Q, size_t rows, int l, const std::vector<double> &T) {
+    parallel_for(rows, [&](size_t r0, size_t r1, int) {
+        std::vector<double> tmp(l);
+        for (size_t r = r0; r < r1; ++r) {
+            double *q = Q + r * l;
+            std::fill(tmp.begin(), tmp.end(), 0.0);
+            for (int i = 0; i < l; ++i) {
+                const double qi = q[i];
+                const double *t = T.data() + (size_t)i * l;
+                for (int j = 0; j < l; ++j) tmp[j] += qi * t[j];
+            }
+            std::copy(tmp.begin(), tmp.end(), q);
+        }
+    });
+}
+
+// Orthonormalize the columns of Q (rows x l) through the eigen-decomposition of its Gram matrix;
+// directions whose energy is below 1e-24 of the largest are zeroed (rank-deficient input).
+void orthonormalize(double *Q, size_t rows, int l) {
+    std::vector<double> G, ev, V, T((size_t)l * l);
+    for (int pass = 0; pass < 2; ++pass) {
+        gram(Q, rows, l, G);
+        jacobi_eig(G, l, ev, V);
+        const double top = ev.empty() ? 0.0 : ev[0];
+        for (int j = 0; j < l; ++j) {
+            const double s = (ev[j] > 1e-24 * top && ev[j] > 0.0) ? 1.0 / std::sqrt(ev[j]) : 0.0;
+            for (int i = 0; i < l; ++i) T[(size_t)i * l + j] = V[(size_t)i * l + j] * s;
+        }
+        right_multiply(Q, rows, l, T);
+    }
+}
+
+// Rank-r factors of A (K x N): L1 = U Sigma (K x r), L2 = V^T (r x N).
+void truncated_svd(const double *A, int K, int N, int r, std::vector<double> &L1, std::vector<double> &L2) {
+    const int l = std::min(std::min(K, N), r + 16);
+    const int iters = 6;
+    std::vector<double> Om((size_t)N * l), Q((size_t)K * l), Z((size_t)N * l);
+    std::mt19937_64 gen(0x5eed5eedULL);
+    std::normal_distribution<double> nd(0.0, 1.0);
+    for (auto &v : Om) v = nd(gen);
+    mul_A_B(A, K, N, Om.data(), l, Q.data());
+    orthonormalize(Q.data(), (size_t)K, l);
+    for (int it = 0; it < iters; ++it) {
+        mul_At_B(A, K, N, Q.data(), l, Z.data());
+        orthonormalize(Z.data(), (size_t)N, l);
+        mul_A_B(A, K, N, Z.data(), l, Q.data());
+        orthonormalize(Q.data(), (size_t)K, l);
+    }
+    // B^T = A^T Q  (N x l);  B B^T = Ub diag(sigma^2) Ub^T
+    mul_At_B(A, K, N, Q.data(), l, Z.data());
+    std::vector<double> G, ev, Ub;
+    gram(Z.data(), (size_t)N, l, G);
+    jacobi_eig(G, l, ev, Ub);
+    L1.assign((size_t)K * r, 0.0);
+    L2.assign((size_t)r * N, 0.0);
+    std::vector<double> sigma(r, 0.0);
+    for (int j = 0; j < r; ++j) sigma[j] = ev[j] > 0.0 ? std::sqrt(ev[j]) : 0.0;
+    const double tiny = sigma.empty() ? 0.0 : sigma[0] * 1e-13;
+    parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+        for (size_t k = k0; k < k1; ++k)
+            for (int j = 0; j < r; ++j) {
+                if (sigma[j] <= tiny) continue;
+                double acc = 0.0;
+                for (int i = 0; i < l; ++i) acc += Q[k * l + i] * Ub[(size_t)i * l + j];
+                L1[k * r + j] = acc * sigma[j];
+            }
+    });
+    parallel_for((size_t)N, [&](size_t n0, size_t n1, int) {
+        for (size_t n = n0; n < n1; ++n)
+            for (int j = 0; j < r; ++j) {
+                if (sigma[j] <= tiny) continue;
+                double acc = 0.0;
+                for (int i = 0; i < l; ++i) acc += Z[n * l + i] * Ub[(size_t)i * l + j];
+                L2[(size_t)j * N + n] = acc / sigma[j];
+            }
+    });
+}
+
+// ----------------------------------------------------------------------------------------------
+// shape checks and sizes
+// ----------------------------------------------------------------------------------------------
+int check_shape(const svdq_shape *s) {
+    if (!s) return SVDQ_EINVAL;
+    if (s->K <= 0 || s->N <= 0 || s->rank < 0) return SVDQ_EINVAL;
+    if (s->group != kGroup || s->K % kGroup != 0 || s->N % 16 != 0 || s->rank % 16 != 0 ||
+        s->rank > svdq::kMaxRank || s->rank > std::min(s->K, s->N))
+        return SVDQ_EUNSUPPORTED;
+    return SVDQ_OK;
+}
+
+// Eq. 1 on one group of 64 values (stride `stride` apart): fp16 scale and 64 codes.
+inline uint16_t quantize_group(const float *v, size_t stride, int8_t *codes) {
+    float amax = 0.0f;
+    for (int i = 0; i < kGroup; ++i) amax = std::max(amax, std::fabs(v[i * stride]));
+    float s32 = amax / 7.0f;
+    if (!(s32 <= 65504.0f)) s32 = 65504.0f;
+    const uint16_t s16 = f32_to_f16(s32);
+    const float s = f16_to_f32(s16);
+    const float rcp = s > 0.0f ? 1.0f / s : 0.0f;
+    for (int i = 0; i < kGroup; ++i) {
+        const float y = v[i * stride] * rcp;
+        float q = std::nearbyintf(y);                      // default rounding mode: ties to even
+        q = std::min(7.0f, std::max(-7.0f, q));
+        codes[i] = (int8_t)q;
+    }
+    return s16;
+}
+
+void pack_native(const svdq_shape *sh, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
+                 const int8_t *qw, const uint16_t *sw, const float *bias, float *o_rinv, uint16_t *o_l1s,
+                 uint16_t *o_l2, uint8_t *o_wcodes, uint16_t *o_wscales, float *o_bias) {
+    const int K = sh->K, N = sh->N, r = sh->rank, G = K / kGroup;
+    const int Np = svdq::round_up(N, kRowPad);
+    if (o_rinv != rinv) std::memcpy(o_rinv, rinv, (size_t)K * 4);
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < r; ++j) o_l1s[svdq::l1s_index(K, r, k, j)] = l1s[(size_t)k * r + j];
+    std::memset(o_l2, 0, (size_t)Np * r * 2);
+    for (int j = 0; j < r; ++j)
+        for (int n = 0; n < N; ++n) o_l2[(size_t)n * r + j] = l2[(size_t)j * N + n];
+    std::memset(o_wcodes, 0, (size_t)G * Np * kCodeBytes);
+    std::memset(o_wscales, 0, (size_t)G * Np * 2);
+    parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
+        for (size_t g = g0; g < g1; ++g)
+            for (int n = 0; n < N; ++n) {
+                uint8_t *dst = o_wcodes + (g * Np + n) * kCodeBytes;
+                for (int j = 0; j < kCodeBytes; ++j) {
+                    const int8_t lo = qw[(g * kGroup + 2 * j) * (size_t)N + n];
+                    const int8_t hi = qw[(g * kGroup + 2 * j + 1) * (size_t)N + n];
+                    dst[j] = (uint8_t)((lo & 0xf) | ((hi & 0xf) << 4));
+                }
+                o_wscales[g * Np + n] = sw[g * N + n];
+            }
+    });
+    for (int n = 0; n < Np; ++n) o_bias[n] = (n < N && bias) ? bias[n] : 0.0f;
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+const char *svdq_status_string(int status) {
+    switch (status) {
+        case SVDQ_OK: return "ok";
+        case SVDQ_EINVAL: return "invalid argument";
+        case SVDQ_EUNSUPPORTED: return "unsupported shape (need K % 64 == 0, N % 16 == 0, rank % 16 == 0, rank <= min(256, K, N), group == 64)";
+        case SVDQ_ENOMEM: return "out of host memory";
+        case SVDQ_ENOSPACE: return "workspace too small";
+        case SVDQ_EHIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+int svdq_prepared_sizes(const svdq_shape *shape, svdq_sizes *out) {
+    if (!out) return SVDQ_EINVAL;
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    const size_t K = shape->K, r = shape->rank, G = shape->K / kGroup;
+    const size_t Np = svdq::round_up(shape->N, kRowPad);
+    out->rinv = K * 4;
+    out->l1s = std::max<size_t>(K * r * 2, 16);
+    out->l2 = std::max<size_t>(Np * r * 2, 16);
+    out->wcodes = G * Np * kCodeBytes;
+    out->wscales = G * Np * 2;
+    out->bias = Np * 4;
+    return SVDQ_OK;
+}
+
+int svdq_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
+              const int8_t *qw, const uint16_t *sw, const float *bias, float *out_rinv, uint16_t *out_l1s,
+              uint16_t *out_l2, uint8_t *out_wcodes, uint16_t *out_wscales, float *out_bias) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!rinv || !qw || !sw || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
+        return SVDQ_EINVAL;
+    if (shape->rank > 0 && (!l1s || !l2)) return SVDQ_EINVAL;
+    const size_t total = (size_t)shape->K * shape->N;
+    for (size_t i = 0; i < total; ++i)
+        if (qw[i] < -8 || qw[i] > 7) return SVDQ_EINVAL;
+    pack_native(shape, rinv, l1s, l2, qw, sw, bias, out_rinv, out_l1s, out_l2, out_wcodes, out_wscales, out_bias);
+    return SVDQ_OK;
+}
+
+int svdq_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                 float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                 uint16_t *out_wscales, float *out_bias) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
+        return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, r = shape->rank, G = K / kGroup;
+    const double alpha = (double)shape->alpha;
+    try {
+        // smoothing factor (App. "Implementation Details"); the run time multiplies by fp32(1/lambda),
+        // so the offline side scales by the exact inverse of that rounded value.
+        std::vector<double> lam(K);
+        std::vector<float> rinv(K);
+        parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+            for (size_t k = k0; k < k1; ++k) {
+                double aw = 0.0;
+                for (int n = 0; n < N; ++n) aw = std::max(aw, (double)std::fabs(W[k * N + n]));
+                const double ax = (double)x_absmax[k];
+                double l = std::pow(ax, alpha) / std::pow(aw, 1.0 - alpha);
+                if (!(ax > 0.0) || !(aw > 0.0) || !std::isfinite(l) || !(l > 0.0)) l = 1.0;
+                rinv[k] = (float)(1.0 / l);
+                lam[k] = 1.0 / (double)rinv[k];
+            }
+        });
+        std::vector<double> What((size_t)K * N);
+        parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+            for (size_t k = k0; k < k1; ++k)
+                for (int n = 0; n < N; ++n) What[k * N + n] = lam[k] * (double)W[k * N + n];
+        });
+        // low-rank split and bf16 storage of the factors (lambda^-1 folded into L1)
+        std::vector<uint16_t> l1s((size_t)K * r), l2((size_t)r * N);
+        if (r > 0) {
+            std::vector<double> L1, L2;
+            truncated_svd(What.data(), K, N, r, L1, L2);
+            for (size_t k = 0; k < (size_t)K; ++k)
+                for (int j = 0; j < r; ++j) l1s[k * r + j] = f32_to_bf16((float)(L1[k * r + j] / lam[k]));
+            for (size_t i = 0; i < (size_t)r * N; ++i) l2[i] = f32_to_bf16((float)L2[i]);
+        }
+        // residual against the stored factors, R = W^ - diag(lambda) (L1s L2b), then Eq. 1 per group
+        std::vector<int8_t> qw((size_t)K * N);
+        std::vector<uint16_t> sw((size_t)G * N);
+        std::vector<double> l2d((size_t)r * N);
+        for (size_t i = 0; i < l2d.size(); ++i) l2d[i] = (double)bf16_to_f32(l2[i]);
+        parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
+            std::vector<float> Rg((size_t)kGroup * N);
+            std::vector<double> prow(N);
+            int8_t codes[kGroup];
+            for (size_t g = g0; g < g1; ++g) {
+                for (int kk = 0; kk < kGroup; ++kk) {
+                    const size_t k = g * kGroup + kk;
+                    std::fill(prow.begin(), prow.end(), 0.0);
+                    for (int j = 0; j < r; ++j) {
+                        const double a = (double)bf16_to_f32(l1s[k * r + j]);
+                        const double *b = l2d.data() + (size_t)j * N;
+                        for (int n = 0; n < N; ++n) prow[n] += a * b[n];
+                    }
+                    for (int n = 0; n < N; ++n)
+                        Rg[(size_t)kk * N + n] = (float)(What[k * N + n] - lam[k] * prow[n]);
+                }
+                for (int n = 0; n < N; ++n) {
+                    sw[g * N + n] = quantize_group(Rg.data() + n, (size_t)N, codes);
+                    for (int kk = 0; kk < kGroup; ++kk) qw[(g * kGroup + kk) * (size_t)N + n] = codes[kk];
+                }
+            }
+        });
+        pack_native(shape, rinv.data(), l1s.data(), l2.data(), qw.data(), sw.data(), bias, out_rinv, out_l1s,
+                    out_l2, out_wcodes, out_wscales, out_bias);
+    } catch (const std::bad_alloc &) {
+        return SVDQ_ENOMEM;
+    }
+    return SVDQ_OK;
+}
+
+int svdq_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, int8_t *out_qw) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!wcodes || !out_qw) return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, G = K / kGroup, Np = svdq::round_up(N, kRowPad);
+    for (int g = 0; g < G; ++g)
+        for (int n = 0; n < N; ++n) {
+            const uint8_t *src = wcodes + ((size_t)g * Np + n) * kCodeBytes;
+            for (int j = 0; j < kCodeBytes; ++j) {
+                const int lo = (int)((src[j] & 0xf) ^ 8) - 8, hi = (int)((src[j] >> 4) ^ 8) - 8;   // sign-extend 4 bits
+                out_qw[((size_t)g * kGroup + 2 * j) * N + n] = (int8_t)lo;
+                out_qw[((size_t)g * kGroup + 2 * j + 1) * N + n] = (int8_t)hi;
+            }
+        }
+    return SVDQ_OK;
+}
+
+int svdq_unpack_wscales(const svdq_shape *shape, const uint16_t *wscales, uint16_t *out_sw) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!wscales || !out_sw) return SVDQ_EINVAL;
+    const int N = shape->N, G = shape->K / kGroup, Np = svdq::round_up(N, kRowPad);
+    for (int g = 0; g < G; ++g) std::memcpy(out_sw + (size_t)g * N, wscales + (size_t)g * Np, (size_t)N * 2);
+    return SVDQ_OK;
+}
+
+int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!l1s || !out) return SVDQ_EINVAL;
+    for (int k = 0; k < shape->K; ++k)
+        for (int j = 0; j < shape->rank; ++j)
+            out[(size_t)k * shape->rank + j] = l1s[svdq::l1s_index(shape->K, shape->rank, k, j)];
+    return SVDQ_OK;
+}
+
+int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!l2 || !out) return SVDQ_EINVAL;
+    for (int j = 0; j < shape->rank; ++j)
+        for (int n = 0; n < shape->N; ++n) out[(size_t)j * shape->N + n] = l2[(size_t)n * shape->rank + j];
+    return SVDQ_OK;
+}
+
+}  // extern "C"

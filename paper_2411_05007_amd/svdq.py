@@ -1,0 +1,257 @@
+"""Thin ctypes binding over libsvdq.so: argument marshalling only.
+
+Every step of the layer runs inside the library (host-side offline quantization in C++,
+run-time kernels in HIP); PyTorch is used here only to own device memory and streams.
+Function names mirror the C ABI declared in ``include/svdq.h``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsvdq.so")
+
+OPT_SKIP_LOWRANK = 1
+OPT_UNFUSED = 2
+OPT_TILE_SHIFT = 8
+
+EXPORTS = [
+    "svdq_status_string", "svdq_last_hip_error", "svdq_prepared_sizes", "svdq_prepare", "svdq_pack",
+    "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2",
+    "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
+    "svdq_forward_options", "svdq_profile_event",
+]
+
+
+class SvdqError(RuntimeError):
+    pass
+
+
+class Shape(C.Structure):
+    _fields_ = [("K", C.c_int), ("N", C.c_int), ("rank", C.c_int), ("group", C.c_int), ("alpha", C.c_float)]
+
+
+class Sizes(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")]
+
+
+class LayerDev(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")] + [("shape", Shape)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libsvdq.so (built in-tree by ``build.py``); raise loudly if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SvdqError(
+                f"{LIB_PATH} not found: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+                "There is no CPU fallback for the layer.")
+        L = C.CDLL(LIB_PATH)
+        L.svdq_status_string.restype = C.c_char_p
+        L.svdq_status_string.argtypes = [C.c_int]
+        L.svdq_workspace_bytes.restype = C.c_size_t
+        L.svdq_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
+        L.svdq_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
+        vp = C.c_void_p
+        L.svdq_prepare.argtypes = [C.POINTER(Shape)] + [vp] * 9
+        L.svdq_pack.argtypes = [C.POINTER(Shape)] + [vp] * 12
+        for n in ("svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2"):
+            getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
+        L.svdq_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
+        L.svdq_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
+        L.svdq_debug_group_acc.argtypes = [C.POINTER(LayerDev), vp, C.c_int] + [C.c_int] * 4 + [vp, vp]
+        L.svdq_forward_options.argtypes = [C.c_int]
+        L.svdq_profile_event.argtypes = [vp]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        L = lib()
+        msg = L.svdq_status_string(status).decode()
+        extra = f" (hipError {L.svdq_last_hip_error()})" if status == -5 else ""
+        raise SvdqError(f"{what}: {msg}{extra}")
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def make_shape(K: int, N: int, rank: int, alpha: float = 0.5, group: int = 64) -> Shape:
+    return Shape(K, N, rank, group, alpha)
+
+
+@dataclass
+class PreparedHost:
+    """Native (kernel-ordered) host buffers of one quantized layer."""
+    shape: Shape
+    rinv: np.ndarray
+    l1s: np.ndarray
+    l2: np.ndarray
+    wcodes: np.ndarray
+    wscales: np.ndarray
+    bias: np.ndarray
+
+
+def _alloc_prepared(shape: Shape) -> PreparedHost:
+    sz = Sizes()
+    _check(lib().svdq_prepared_sizes(C.byref(shape), C.byref(sz)), "svdq_prepared_sizes")
+    return PreparedHost(
+        shape=shape,
+        rinv=np.zeros(sz.rinv // 4, np.float32),
+        l1s=np.zeros(sz.l1s // 2, np.uint16),
+        l2=np.zeros(sz.l2 // 2, np.uint16),
+        wcodes=np.zeros(sz.wcodes, np.uint8),
+        wscales=np.zeros(sz.wscales // 2, np.uint16),
+        bias=np.zeros(sz.bias // 4, np.float32),
+    )
+
+
+def svdq_prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
+                 bias: Optional[np.ndarray] = None) -> PreparedHost:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    K, N = W.shape
+    x_absmax = np.ascontiguousarray(x_absmax, dtype=np.float32)
+    assert x_absmax.shape == (K,)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha)
+    out = _alloc_prepared(shape)
+    _check(lib().svdq_prepare(C.byref(shape), _ptr(W), _ptr(x_absmax), _ptr(b), _ptr(out.rinv), _ptr(out.l1s),
+                              _ptr(out.l2), _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias)), "svdq_prepare")
+    return out
+
+
+def svdq_pack(rinv, l1s_bits, l2_bits, qw, sw_f16, bias=None, alpha: float = 0.5) -> PreparedHost:
+    """Pack canonical arrays (e.g. from another quantizer) into native buffers."""
+    qw = np.ascontiguousarray(qw, dtype=np.int8)
+    K, N = qw.shape
+    l1s_bits = np.ascontiguousarray(l1s_bits, dtype=np.uint16)
+    rank = l1s_bits.shape[1] if l1s_bits.ndim == 2 else 0
+    l2_bits = np.ascontiguousarray(l2_bits, dtype=np.uint16)
+    sw = np.ascontiguousarray(np.asarray(sw_f16).view(np.uint16))
+    rinv = np.ascontiguousarray(rinv, dtype=np.float32)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha)
+    out = _alloc_prepared(shape)
+    _check(lib().svdq_pack(C.byref(shape), _ptr(rinv), _ptr(l1s_bits) if rank else None, _ptr(l2_bits) if rank else None,
+                           _ptr(qw), _ptr(sw), _ptr(b), _ptr(out.rinv), _ptr(out.l1s), _ptr(out.l2),
+                           _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias)), "svdq_pack")
+    return out
+
+
+def svdq_unpack(p: PreparedHost):
+    """Canonical views of a prepared layer: dict(rinv, l1s bf16 [K,r], l2 bf16 [r,N], qw int8 [K,N], sw fp16 [G,N], bias)."""
+    K, N, r = p.shape.K, p.shape.N, p.shape.rank
+    G = K // 64
+    qw = np.zeros((K, N), np.int8)
+    sw = np.zeros((G, N), np.uint16)
+    l1s = np.zeros((K, r), np.uint16)
+    l2 = np.zeros((r, N), np.uint16)
+    L = lib()
+    _check(L.svdq_unpack_wcodes(C.byref(p.shape), _ptr(p.wcodes), _ptr(qw)), "svdq_unpack_wcodes")
+    _check(L.svdq_unpack_wscales(C.byref(p.shape), _ptr(p.wscales), _ptr(sw)), "svdq_unpack_wscales")
+    if r > 0:
+        _check(L.svdq_unpack_l1s(C.byref(p.shape), _ptr(p.l1s), _ptr(l1s)), "svdq_unpack_l1s")
+        _check(L.svdq_unpack_l2(C.byref(p.shape), _ptr(p.l2), _ptr(l2)), "svdq_unpack_l2")
+    return {"rinv": p.rinv.copy(), "l1s": l1s, "l2": l2, "qw": qw, "sw": sw.view(np.float16), "bias": p.bias[:N].copy()}
+
+
+def svdq_forward_options(flags: int) -> int:
+    return lib().svdq_forward_options(int(flags))
+
+
+def svdq_profile_event(event_handle: Optional[int]) -> None:
+    _check(lib().svdq_profile_event(event_handle), "svdq_profile_event")
+
+
+def svdq_workspace_bytes(M: int, shape: Shape) -> int:
+    return int(lib().svdq_workspace_bytes(int(M), C.byref(shape)))
+
+
+class DeviceLayer:
+    """A prepared layer resident in HBM (torch tensors own the memory) plus its forward call."""
+
+    def __init__(self, prepared: PreparedHost, device: str = "cuda:0"):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise SvdqError("no GPU visible: the SVDQuant layer has no CPU path")
+        self.torch = torch
+        self.device = torch.device(device)
+        self.shape = prepared.shape
+        self.K, self.N, self.rank = prepared.shape.K, prepared.shape.N, prepared.shape.rank
+        self.G = self.K // 64
+        up = lambda a: torch.from_numpy(a.view(np.uint8) if a.dtype != np.uint8 else a).to(self.device)
+        self._bufs = {n: up(getattr(prepared, n)) for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")}
+        self.cdesc = LayerDev(*[self._bufs[n].data_ptr() for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")],
+                              prepared.shape)
+
+    def workspace(self, M: int):
+        n = svdq_workspace_bytes(M, self.shape)
+        if n == 0:
+            raise SvdqError("unsupported shape")
+        return self.torch.empty(n, dtype=self.torch.uint8, device=self.device)
+
+    def forward(self, x, out=None, workspace=None, stream=None):
+        """x: torch bf16 [M, K] on the GPU.  Returns bf16 [M, N].  Enqueues only; does not synchronise."""
+        torch = self.torch
+        assert x.dtype == torch.bfloat16 and x.is_contiguous() and x.shape[1] == self.K and x.is_cuda
+        M = x.shape[0]
+        if out is None:
+            out = torch.empty((M, self.N), dtype=torch.bfloat16, device=x.device)
+        if workspace is None:
+            workspace = self.workspace(M)
+        s = torch.cuda.current_stream(x.device) if stream is None else stream
+        _check(lib().svdq_linear_forward(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
+                                         workspace.numel(), s.cuda_stream), "svdq_linear_forward")
+        self._last_ws, self._last_M = workspace, M
+        return out
+
+    def debug_act(self, workspace=None, M=None):
+        """Canonical codes int8 [M,K], scales fp16 [M,G], H fp32 [M,r] of the last forward (numpy)."""
+        torch = self.torch
+        workspace = self._last_ws if workspace is None else workspace
+        M = self._last_M if M is None else M
+        codes = torch.empty((M, self.K), dtype=torch.int8, device=self.device)
+        sx = torch.empty((M, self.G), dtype=torch.float16, device=self.device)
+        H = torch.empty((M, max(self.rank, 1)), dtype=torch.float32, device=self.device)
+        s = torch.cuda.current_stream(self.device)
+        _check(lib().svdq_debug_act(C.byref(self.cdesc), workspace.data_ptr(), M, codes.data_ptr(), sx.data_ptr(),
+                                    H.data_ptr() if self.rank else None, s.cuda_stream), "svdq_debug_act")
+        torch.cuda.synchronize(self.device)
+        return codes.cpu().numpy(), sx.cpu().numpy(), (H.cpu().numpy() if self.rank else None)
+
+    def debug_group_acc(self, m0, m1, n0, n1, workspace=None, M=None):
+        """Exact int32 group sums of a window, int32 [m1-m0, n1-n0, G] (numpy)."""
+        torch = self.torch
+        workspace = self._last_ws if workspace is None else workspace
+        M = self._last_M if M is None else M
+        out = torch.zeros((m1 - m0, n1 - n0, self.G), dtype=torch.int32, device=self.device)
+        s = torch.cuda.current_stream(self.device)
+        _check(lib().svdq_debug_group_acc(C.byref(self.cdesc), workspace.data_ptr(), M, m0, m1, n0, n1, out.data_ptr(),
+                                          s.cuda_stream), "svdq_debug_group_acc")
+        torch.cuda.synchronize(self.device)
+        return out.cpu().numpy()
+
+
+def bf16_tensor_from_bits(bits: np.ndarray, device="cuda:0"):
+    """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 tensor on the device."""
+    import torch
+
+    return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def bits_from_bf16_tensor(t) -> np.ndarray:
+    import torch
+
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

@@ -1,0 +1,174 @@
+"""CPU-side checks of libsvdq.so: exported symbols, host-side offline quantization vs the oracle,
+native packing round trips and error handling.  No GPU call is made here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import svdq_oracle as O
+from paper_2411_05007_amd import inputs as I
+from paper_2411_05007_amd import svdq as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(S.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    return S.lib()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "svdq.h")).read()
+    declared = set(re.findall(r"^(?:int|size_t|const char \*)\s*(svdq_[a-z0-9_]+)\s*\(", header, flags=re.M))
+    assert declared == set(S.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.svdq_status_string(0) == b"ok"
+    assert b"unsupported" in lib.svdq_status_string(-2)
+
+
+def _layer(K=256, N=192, M=64, seed=0):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, 3, replace=False)] *= 50
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 2, replace=False), :] *= 20
+    xb = O.bf16_round(x)
+    ax = np.abs(O.bf16_to_f32(xb)).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    return xb, w, b, ax
+
+
+def test_prepare_matches_oracle_given_the_same_factors(lib):
+    xb, w, b, ax = _layer()
+    P = S.svdq_prepare(w, ax, rank=32, bias=b)
+    U = S.svdq_unpack(P)
+    ref = O.prepare(w, ax, rank=32, bias=b)
+    # smoothing factor: same formula in fp64, then one rounding to fp32
+    assert np.array_equal(U["rinv"], ref["rinv"])
+    assert np.array_equal(U["bias"], b)
+    # the SVD factors may differ (any rank-r factors are valid); everything after them must not
+    qw, sw, R = O.residual_codes_from_factors(w, U["rinv"], U["l1s"], U["l2"])
+    assert np.array_equal(U["qw"], qw)
+    assert np.array_equal(U["sw"].view(np.uint16), sw.view(np.uint16))
+    # quality of the library's own truncated SVD against the Eckart-Young optimum
+    opt = np.sqrt(np.sum(ref["sigma"][32:] ** 2))
+    assert np.linalg.norm(R) <= 1.005 * opt
+    assert np.linalg.norm(R) >= opt * (1 - 1e-9)
+    # L2 has (nearly, after bf16 rounding) orthonormal rows: Sigma went wholly into L1
+    l2 = O.bf16_to_f32(U["l2"]).astype(np.float64)
+    assert np.allclose(l2 @ l2.T, np.eye(32), atol=2e-2)
+    # and the layer it defines approximates X W as well as the oracle's does
+    prep_lib = dict(ref, rinv=U["rinv"], l1s=U["l1s"], l2=U["l2"], qw=U["qw"], sw=U["sw"])
+    y_lib = O.forward(xb, prep_lib, want_f64=True)["Y64"]
+    y_ref = O.forward(xb, ref, want_f64=True)["Y64"]
+    exact = O.bf16_to_f32(xb).astype(np.float64) @ w.astype(np.float64) + b
+    e_lib = np.linalg.norm(y_lib - exact) / np.linalg.norm(exact)
+    e_ref = np.linalg.norm(y_ref - exact) / np.linalg.norm(exact)
+    assert e_lib < 1.1 * e_ref + 1e-3
+
+
+def test_prepare_tall_and_wide_and_rank_edge_cases(lib):
+    for (K, N, r) in ((128, 512, 16), (512, 128, 48), (64, 64, 64), (128, 96, 0)):
+        xb, w, b, ax = _layer(K=K, N=N, M=16, seed=K + N)
+        P = S.svdq_prepare(w, ax, rank=r, bias=None)
+        U = S.svdq_unpack(P)
+        qw, sw, R = O.residual_codes_from_factors(w, U["rinv"], U["l1s"].reshape(K, r), U["l2"].reshape(r, N))
+        assert np.array_equal(U["qw"], qw) and np.array_equal(U["sw"].view(np.uint16), sw.view(np.uint16))
+        assert np.all(U["bias"] == 0)
+        if r == min(K, N):      # full rank: the residual is only the bf16 rounding of the factors
+            What = O.smooth_weight(w, 1.0 / U["rinv"].astype(np.float64))
+            assert np.linalg.norm(R) < 1e-2 * np.linalg.norm(What)
+
+
+def test_prepare_degenerate_inputs(lib):
+    K, N = 128, 64
+    w = np.zeros((K, N), np.float32)
+    ax = np.zeros(K, np.float32)
+    U = S.svdq_unpack(S.svdq_prepare(w, ax, rank=16))
+    assert np.all(U["rinv"] == 1.0) and np.all(U["qw"] == 0) and np.all(U["sw"].view(np.uint16) == 0)
+    assert np.all(O.bf16_to_f32(U["l1s"]) == 0)
+    # rank-deficient weight (rank 3 < r): finite factors, exact-zero-ish residual
+    rng = np.random.default_rng(1)
+    w = (rng.standard_normal((K, 3)) @ rng.standard_normal((3, N))).astype(np.float32)
+    U = S.svdq_unpack(S.svdq_prepare(w, np.ones(K, np.float32), rank=16))
+    assert np.all(np.isfinite(O.bf16_to_f32(U["l1s"]))) and np.all(np.isfinite(O.bf16_to_f32(U["l2"])))
+    _, _, R = O.residual_codes_from_factors(w, U["rinv"], U["l1s"], U["l2"])
+    assert np.linalg.norm(R) < 2e-2 * np.linalg.norm(w)
+
+
+def test_pack_unpack_round_trip_and_byte_layout(lib):
+    rng = np.random.default_rng(2)
+    K, N, r = 192, 80, 16
+    qw = rng.integers(-7, 8, size=(K, N)).astype(np.int8)
+    sw = rng.uniform(1e-3, 1, size=(K // 64, N)).astype(np.float16)
+    l1s = rng.integers(0, 2 ** 16, size=(K, r)).astype(np.uint16)
+    l2 = rng.integers(0, 2 ** 16, size=(r, N)).astype(np.uint16)
+    rinv = rng.uniform(0.1, 2, size=K).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    P = S.svdq_pack(rinv, l1s, l2, qw, sw, bias)
+    U = S.svdq_unpack(P)
+    assert np.array_equal(U["qw"], qw) and np.array_equal(U["sw"], sw)
+    assert np.array_equal(U["l1s"], l1s) and np.array_equal(U["l2"], l2)
+    assert np.array_equal(U["rinv"], rinv) and np.array_equal(U["bias"], bias)
+    # documented layout: codes[g][row][32 bytes], byte j = code(2j) & 15 | code(2j+1) << 4, rows padded to 256
+    Np = 256
+    blk = P.wcodes.reshape(K // 64, Np, 32)
+    g, n, j = 2, 17, 5
+    want = (int(qw[64 * g + 2 * j, n]) & 15) | ((int(qw[64 * g + 2 * j + 1, n]) & 15) << 4)
+    assert blk[g, n, j] == want
+    assert np.all(blk[:, N:, :] == 0) and np.all(P.wscales.reshape(K // 64, Np)[:, N:] == 0)
+    assert P.bias.shape == (Np,) and np.all(P.bias[N:] == 0)
+    # out-of-range code is rejected
+    bad = qw.copy()
+    bad[0, 0] = 9
+    with pytest.raises(S.SvdqError):
+        S.svdq_pack(rinv, l1s, l2, bad, sw, bias)
+
+
+def test_shape_errors_and_workspace_size(lib):
+    sz = S.Sizes()
+    assert lib.svdq_prepared_sizes(C.byref(S.make_shape(100, 64, 16)), C.byref(sz)) == -2     # K % 64
+    assert lib.svdq_prepared_sizes(C.byref(S.make_shape(128, 60, 16)), C.byref(sz)) == -2     # N % 16
+    assert lib.svdq_prepared_sizes(C.byref(S.make_shape(128, 64, 24)), C.byref(sz)) == -2     # rank % 16
+    assert lib.svdq_prepared_sizes(C.byref(S.make_shape(128, 64, 80)), C.byref(sz)) == -2     # rank > min(K, N)
+    assert lib.svdq_prepared_sizes(C.byref(S.make_shape(128, 64, 16, group=32)), C.byref(sz)) == -2
+    assert lib.svdq_prepared_sizes(C.byref(S.make_shape(0, 64, 16)), C.byref(sz)) == -1
+    assert lib.svdq_prepared_sizes(None, C.byref(sz)) == -1
+    assert lib.svdq_prepared_sizes(C.byref(S.make_shape(128, 64, 16)), C.byref(sz)) == 0
+    assert (sz.rinv, sz.l1s, sz.l2, sz.wcodes, sz.wscales, sz.bias) == (512, 128 * 16 * 2, 256 * 16 * 2, 2 * 256 * 32, 2 * 256 * 2, 1024)
+    sh = S.make_shape(3072, 12288, 32)
+    ws = S.svdq_workspace_bytes(4608, sh)
+    # codes M*K/2 + scales 2*M*G + H 4*M*r, all with M padded to 256 (4608 is a multiple already)
+    assert ws == 4608 * 3072 // 2 + 2 * 4608 * 48 + 4 * 4608 * 32
+    assert S.svdq_workspace_bytes(1, sh) == 256 * 3072 // 2 + 2 * 256 * 48 + 4 * 256 * 32
+    assert S.svdq_workspace_bytes(16, S.make_shape(100, 64, 16)) == 0
+    # forward argument checks happen before any GPU call
+    bad = S.LayerDev()
+    assert lib.svdq_linear_forward(C.byref(bad), None, 4, None, None, 0, None) == -1
+    assert lib.svdq_linear_forward(None, None, 4, None, None, 0, None) == -1
+    assert lib.svdq_forward_options(-1) == 0
+
+
+def test_fp16_and_bf16_roundings_of_the_library_match_numpy(lib):
+    # scales cover normal, subnormal and saturating fp16 values; codes at tie points
+    K, N = 64, 16
+    R = np.zeros((K, N), np.float64)
+    mags = [7.0, 7 * 6.1e-5, 7 * 3.0e-8, 7 * 5.96e-8, 3.2e6, 7 * 65504.0, 0.0, 7 * 2.0 ** -14, 7 * (2.0 ** -14 - 2.0 ** -25),
+            1e-9, 123.456, 7 * 0.333251953125, 5e5, 4.58e5, 4.5861e5, 7 * 1.0009765625]
+    for n, m in enumerate(mags):
+        R[0, n] = m
+        R[1:, n] = np.linspace(-1, 1, K - 1) * m
+    w = R.astype(np.float32)
+    # rank 0 and x_absmax chosen so that lambda = 1: R == W exactly
+    ax = np.max(np.abs(w), axis=1)
+    ax[ax == 0] = 1
+    U = S.svdq_unpack(S.svdq_prepare(w, ax, rank=0, alpha=0.0 + 0.5))
+    qw, sw, _ = O.residual_codes_from_factors(w, U["rinv"], np.zeros((K, 0), np.uint16), np.zeros((0, N), np.uint16))
+    assert np.array_equal(U["sw"].view(np.uint16), sw.view(np.uint16))
+    assert np.array_equal(U["qw"], qw)
