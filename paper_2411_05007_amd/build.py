@@ -18,6 +18,9 @@ COMMON = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-ffp-contract=off", "-fno-fast-math",
+    # MFMA results go to ordinary VGPRs: the rescale consumes them on the vector ALU right away,
+    # and an AGPR destination would cost one v_accvgpr_read per partial sum
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]
 

@@ -22,6 +22,7 @@
 // first MFMA and the next 16 for the second, for the activation and the weight alike.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "kernels.h"
 #include "layout.h"
@@ -49,14 +50,14 @@ struct Tile {
     static constexpr int kThreads = kWaves * 64;
     static constexpr int kRB = WM / 32, kCB = WN / 32;
     static constexpr int kStageA = BM * kLdsRow, kStageB = BN * kLdsRow;
-    // per stage: A codes, B codes, sx fp32 [BM], sw pairs fp32 [BN][2]
-    static constexpr int kStageBytes = kStageA + kStageB + BM * 4 + BN * 8;
-    static constexpr int kLdsBytes = 2 * kStageBytes;
+    // per stage: A codes, B codes, sx fp16 [BM] (row-permuted), sw pairs fp32 [BN][2]
+    static constexpr int kStageBytes = kStageA + kStageB + BM * 2 + BN * 8;
+    static constexpr int kLdsBytes = 3 * kStageBytes;      // ring of three slots
 };
 
 // MODE 0: normal forward.  MODE 1: additionally export exact group sums of a window (parity checks).
 template <int BM, int BN, int WM, int WN, int MODE>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(GemmParams p) {
     using T = Tile<BM, BN, WM, WN>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -68,9 +69,24 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmPa
     const int wm0 = (wave % T::kWavesM) * WM;
     const int wn0 = (wave / T::kWavesM) * WN;
 
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that an
+    // XCD owns a contiguous run of tiles, walked in bands of kBand tile rows: the tiles that run at the
+    // same time on one XCD then share their activation rows and weight columns through that XCD's L2.
     const int tiles_m = (p.M + BM - 1) / BM;
-    const int tile_m = blockIdx.x % tiles_m;
-    const int tile_n = blockIdx.x / tiles_m;
+    const int tiles_n = (p.N + BN - 1) / BN;
+    int tile_m, tile_n;
+    {
+        const int total = tiles_m * tiles_n;
+        const int per = (total + 7) / 8;
+        // a bijection only when the tile count divides by 8; otherwise keep the launch order
+        const int id = (total % 8 == 0) ? (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+        constexpr int kBand = 4;
+        const int band = id / (kBand * tiles_n);
+        const int band_rows = (tiles_m - band * kBand) < kBand ? (tiles_m - band * kBand) : kBand;
+        const int in = id - band * kBand * tiles_n;
+        tile_m = band * kBand + in % band_rows;
+        tile_n = in / band_rows;
+    }
     const int gm0 = tile_m * BM;
     const int gn0 = tile_n * BN;
     if (MODE == 1) {   // window export: only tiles that touch the window do any work (uniform per block)
@@ -89,147 +105,246 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmPa
 #pragma unroll
     for (int v = 0; v < 16; ++v) magic[v] = p.magic;
 
-    // ---- global -> register staging of one group's slab --------------------------------------
-    constexpr int kUnitsA = BM * 2, kUnitsB = BN * 2;                 // 16-byte units per group
-    constexpr int kNA = (kUnitsA + T::kThreads - 1) / T::kThreads;
-    constexpr int kNB = (kUnitsB + T::kThreads - 1) / T::kThreads;
-    uint4 ra[kNA], rb[kNB];
-    uint32_t rsx = 0, rsw = 0;
+    // ---- global -> register -> LDS staging of one group's slab ----------------------------------
+    // Each operand's slab of one group (rows x 32 packed bytes) is split evenly over the block's
+    // threads, in 16-byte units if there are enough of them and in 8-byte granules otherwise, so the
+    // loop body has no branches: one basic block that the instruction scheduler can pipeline.
+    constexpr int kGranA = (BM * 2 >= T::kThreads) ? 16 : 8;
+    constexpr int kGranB = (BN * 2 >= T::kThreads) ? 16 : 8;
+    constexpr int kNA = BM * 32 / kGranA / T::kThreads;
+    constexpr int kNB = BN * 32 / kGranB / T::kThreads;
+    static_assert(kNA >= 1 && kNA * kGranA * T::kThreads == BM * 32, "A slab must split evenly over the threads");
+    static_assert(kNB >= 1 && kNB * kGranB * T::kThreads == BN * 32, "B slab must split evenly over the threads");
+    static_assert(T::kThreads >= BM && T::kThreads >= BN, "one thread per row stages the scales");
+    struct Staged {                  // one group's share of this thread, on its way from memory to LDS
+        uint4 a[kNA], b[kNB];        // only .x/.y are used for 8-byte granules
+        uint32_t sx, sw;
+    };
+    const int xrow = tid % BM, wrow = tid % BN;
+    // the 16 rows one lane rescales are contiguous: row = 32*blk + 8*j + 4*h + v -> 32*blk + 16*h + 4*j + v
+    const int xpos = (xrow & ~31) + ((xrow >> 2) & 1) * 16 + ((xrow >> 3) & 3) * 4 + (xrow & 3);
+
+    // uniform (scalar) slab bases + small per-thread offsets, so the loads need no 64-bit vector adds
+    const unsigned char *xbase = p.xcodes + (size_t)gm0 * kCodeBytes;
+    const unsigned char *wbase = p.wcodes + (size_t)gn0 * kCodeBytes;
+    const uint16_t *sxbase = p.sx + gm0;
+    const uint16_t *swbase = p.sw + gn0;
+    const size_t xstride = (size_t)p.Mpad * kCodeBytes, wstride = (size_t)p.Npad * kCodeBytes;
 
     auto load_group = [&](int g) {
-        const uint4 *ga = reinterpret_cast<const uint4 *>(p.xcodes + ((size_t)g * p.Mpad + gm0) * kCodeBytes);
-        const uint4 *gb = reinterpret_cast<const uint4 *>(p.wcodes + ((size_t)g * p.Npad + gn0) * kCodeBytes);
+        Staged q;
+        uint4 (&ra)[kNA] = q.a;
+        uint4 (&rb)[kNB] = q.b;
+        const unsigned char *ga = xbase + (size_t)g * xstride;
+        const unsigned char *gb = wbase + (size_t)g * wstride;
 #pragma unroll
         for (int i = 0; i < kNA; ++i) {
-            const int u = tid + i * T::kThreads;
-            if (kUnitsA % T::kThreads == 0 || u < kUnitsA) ra[i] = ga[u];
+            const unsigned u = tid + i * T::kThreads;
+            if (kGranA == 16) ra[i] = *reinterpret_cast<const uint4 *>(ga + u * 16u);
+            else { const uint2 v = *reinterpret_cast<const uint2 *>(ga + u * 8u); ra[i].x = v.x; ra[i].y = v.y; }
         }
 #pragma unroll
         for (int i = 0; i < kNB; ++i) {
-            const int u = tid + i * T::kThreads;
-            if (kUnitsB % T::kThreads == 0 || u < kUnitsB) rb[i] = gb[u];
+            const unsigned u = tid + i * T::kThreads;
+            if (kGranB == 16) rb[i] = *reinterpret_cast<const uint4 *>(gb + u * 16u);
+            else { const uint2 v = *reinterpret_cast<const uint2 *>(gb + u * 8u); rb[i].x = v.x; rb[i].y = v.y; }
         }
-        if (tid < BM / 2) rsx = reinterpret_cast<const uint32_t *>(p.sx + (size_t)g * p.Mpad + gm0)[tid];
-        if (tid < BN / 2) rsw = reinterpret_cast<const uint32_t *>(p.sw + (size_t)g * p.Npad + gn0)[tid];
+        q.sx = sxbase[(size_t)g * p.Mpad + (unsigned)xrow];
+        q.sw = swbase[(size_t)g * p.Npad + (unsigned)wrow];
+        return q;
     };
 
-    auto widen_store = [&](unsigned char *dst, const uint4 &x) {
+    // An empty volatile asm keeps its operand's consumers at this point of the program: without it the
+    // compiler hoists the widening to the top of the iteration, right behind the global loads it waits on.
+    auto pin = [](uint32_t &v) { asm volatile("" : "+v"(v)); };
+
+    // widen packed nibbles to bytes holding 16 * code: (x << 4) & 0xF0F0F0F0 are the even codes, x & 0xF0F0F0F0 the odd
+    auto widen_store = [&](unsigned char *dst, const uint4 &x, int gran, unsigned u) {
         uint4 lo, hi;
         lo.x = (x.x << 4) & 0xf0f0f0f0u; lo.y = x.x & 0xf0f0f0f0u;
         lo.z = (x.y << 4) & 0xf0f0f0f0u; lo.w = x.y & 0xf0f0f0f0u;
-        hi.x = (x.z << 4) & 0xf0f0f0f0u; hi.y = x.z & 0xf0f0f0f0u;
-        hi.z = (x.w << 4) & 0xf0f0f0f0u; hi.w = x.w & 0xf0f0f0f0u;
-        reinterpret_cast<uint4 *>(dst)[0] = lo;
-        reinterpret_cast<uint4 *>(dst)[1] = hi;
+        if (gran == 16) {
+            hi.x = (x.z << 4) & 0xf0f0f0f0u; hi.y = x.z & 0xf0f0f0f0u;
+            hi.z = (x.w << 4) & 0xf0f0f0f0u; hi.w = x.w & 0xf0f0f0f0u;
+            uint4 *q = reinterpret_cast<uint4 *>(dst + (u >> 1) * kLdsRow + (u & 1) * 32);
+            q[0] = lo;
+            q[1] = hi;
+        } else {
+            *reinterpret_cast<uint4 *>(dst + (u >> 2) * kLdsRow + (u & 3) * 16) = lo;
+        }
     };
 
-    auto store_group = [&](int stage) {
-        unsigned char *sa = lds + stage * T::kStageBytes;
+    auto store_group = [&](int slot, Staged q) {
+        uint4 (&ra)[kNA] = q.a;
+        uint4 (&rb)[kNB] = q.b;
+        uint32_t &rsx = q.sx, &rsw = q.sw;
+#pragma unroll
+        for (int i = 0; i < kNA; ++i) { pin(ra[i].x); pin(ra[i].y); if (kGranA == 16) { pin(ra[i].z); pin(ra[i].w); } }
+#pragma unroll
+        for (int i = 0; i < kNB; ++i) { pin(rb[i].x); pin(rb[i].y); if (kGranB == 16) { pin(rb[i].z); pin(rb[i].w); } }
+        pin(rsx);
+        pin(rsw);
+        unsigned char *sa = lds + slot * T::kStageBytes;
         unsigned char *sb = sa + T::kStageA;
-        float *ssx = reinterpret_cast<float *>(sb + T::kStageB);
+        uint16_t *ssx = reinterpret_cast<uint16_t *>(sb + T::kStageB);
         float2 *ssw = reinterpret_cast<float2 *>(ssx + BM);
 #pragma unroll
-        for (int i = 0; i < kNA; ++i) {
-            const int u = tid + i * T::kThreads;
-            if (kUnitsA % T::kThreads == 0 || u < kUnitsA) widen_store(sa + (u >> 1) * kLdsRow + (u & 1) * 32, ra[i]);
-        }
+        for (int i = 0; i < kNA; ++i) widen_store(sa, ra[i], kGranA, tid + i * T::kThreads);
 #pragma unroll
-        for (int i = 0; i < kNB; ++i) {
-            const int u = tid + i * T::kThreads;
-            if (kUnitsB % T::kThreads == 0 || u < kUnitsB) widen_store(sb + (u >> 1) * kLdsRow + (u & 1) * 32, rb[i]);
-        }
-        if (tid < BM / 2) {
-            // rows 2*tid, 2*tid+1; permuted so that the 16 rows one lane rescales are contiguous:
-            // row = 32*blk + 8*j + 4*h + v  ->  32*blk + 16*h + 4*j + v
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int row = 2 * tid + e;
-                const int pos = (row & ~31) + ((row >> 2) & 1) * 16 + ((row >> 3) & 3) * 4 + (row & 3);
-                const _Float16 h = __builtin_bit_cast(_Float16, (uint16_t)(e ? (rsx >> 16) : (rsx & 0xffffu)));
-                ssx[pos] = (float)h;
-            }
-        }
-        if (tid < BN / 2) {
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const _Float16 h = __builtin_bit_cast(_Float16, (uint16_t)(e ? (rsw >> 16) : (rsw & 0xffffu)));
-                const float s = (float)h * 0.00390625f;                 // sw * 2^-8 (both operands carry a factor 16)
-                ssw[2 * tid + e] = make_float2(s, -kMagic * s);
-            }
-        }
+        for (int i = 0; i < kNB; ++i) widen_store(sb, rb[i], kGranB, tid + i * T::kThreads);
+        ssx[xpos] = (uint16_t)rsx;       // threads beyond BM / BN repeat the first ones' (identical) stores
+        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)rsw) * 0.00390625f;   // sw * 2^-8: both operands carry a factor 16
+        ssw[wrow] = make_float2(s, -kMagic * s);
     };
 
-    // ---- main loop over groups -----------------------------------------------------------------
-    load_group(0);
-    store_group(0);
-    __syncthreads();
+    // ---- fragments: LDS -> registers --------------------------------------------------------------
+    typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+    constexpr int kSub = T::kRB * T::kCB;
+    intx4 af[T::kRB][2], bf[T::kCB][2];
+    halfx8 sxv[T::kRB][2];
+    float2 swv[T::kCB];
 
-    for (int g = 0; g < p.G; ++g) {
-        const int stage = g & 1;
-        if (g + 1 < p.G) load_group(g + 1);
-
-        const unsigned char *sa = lds + stage * T::kStageBytes;
+    auto read_codes = [&](int slot) {
+        const unsigned char *sa = lds + slot * T::kStageBytes;
         const unsigned char *sb = sa + T::kStageA;
-        const float *ssx = reinterpret_cast<const float *>(sb + T::kStageB);
-        const float2 *ssw = reinterpret_cast<const float2 *>(ssx + BM);
-
-        intx4 af[T::kRB][2];
-        float sxv[T::kRB][16];
 #pragma unroll
         for (int r = 0; r < T::kRB; ++r) {
             const unsigned char *ap = sa + (wm0 + r * 32 + li) * kLdsRow + lh * 32;
             af[r][0] = *reinterpret_cast<const intx4 *>(ap);
             af[r][1] = *reinterpret_cast<const intx4 *>(ap + 16);
-            const float4 *sp = reinterpret_cast<const float4 *>(ssx + wm0 + r * 32 + lh * 16);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 s4 = sp[q];
-                sxv[r][4 * q + 0] = s4.x; sxv[r][4 * q + 1] = s4.y; sxv[r][4 * q + 2] = s4.z; sxv[r][4 * q + 3] = s4.w;
-            }
         }
 #pragma unroll
         for (int c = 0; c < T::kCB; ++c) {
             const unsigned char *bp = sb + (wn0 + c * 32 + li) * kLdsRow + lh * 32;
-            const intx4 b0 = *reinterpret_cast<const intx4 *>(bp);
-            const intx4 b1 = *reinterpret_cast<const intx4 *>(bp + 16);
-            const float2 sw = ssw[wn0 + c * 32 + li];
+            bf[c][0] = *reinterpret_cast<const intx4 *>(bp);
+            bf[c][1] = *reinterpret_cast<const intx4 *>(bp + 16);
+        }
+    };
+    auto read_scales = [&](int slot) {
+        const unsigned char *sb = lds + slot * T::kStageBytes + T::kStageA;
+        const uint16_t *ssx = reinterpret_cast<const uint16_t *>(sb + T::kStageB);
+        const float2 *ssw = reinterpret_cast<const float2 *>(ssx + BM);
 #pragma unroll
-            for (int r = 0; r < T::kRB; ++r) {
-                intx16 d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][0], b0, magic, 0, 0, 0);
-                d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][1], b1, d, 0, 0, 0);
+        for (int r = 0; r < T::kRB; ++r) {
+            const halfx8 *sp = reinterpret_cast<const halfx8 *>(ssx + wm0 + r * 32 + lh * 16);
+            sxv[r][0] = sp[0];
+            sxv[r][1] = sp[1];
+        }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float t = __builtin_fmaf(__int_as_float(d[v]), sw.x, sw.y);
-                    acc[r][c][v] = __builtin_fmaf(t, sxv[r][v], acc[r][c][v]);
-                }
+        for (int c = 0; c < T::kCB; ++c) swv[c] = ssw[wn0 + c * 32 + li];
+    };
+
+    auto rescale = [&](floatx16 &a, const intx16 &d, const float2 sw, const halfx8 &s0, const halfx8 &s1) {
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const float t = __builtin_fmaf(__int_as_float(d[v]), sw.x, sw.y);
+            a[v] = __builtin_fmaf(t, (float)s0[v], a[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const float t = __builtin_fmaf(__int_as_float(d[v + 8]), sw.x, sw.y);
+            a[v + 8] = __builtin_fmaf(t, (float)s1[v], a[v + 8]);
+        }
+    };
+
+    // ---- main loop over groups: a ring of three LDS slots -----------------------------------------
+    // While group g is multiplied out of registers, the codes of g+1 are read from their slot (filled
+    // one iteration ago), g+2 (fetched from memory two iterations ago) is widened and written to the
+    // third slot, and the fetch of g+4 is issued: a memory round trip has two full iterations to
+    // complete.  One barrier per group; a wavefront reaches it with its next operands already on the way.
+    //
+    // A wavefront cannot overlap its own MFMA with its own vector-ALU work, but two wavefronts on one
+    // SIMD can: each walks its 32x32 sub-tiles one at a time, issues the two MFMAs of sub-tile t and
+    // then rescales sub-tile t-1, whose MFMAs finished long ago.
+    const int glast = p.G - 1;
+    Staged q0, q1;                     // groups g+2 and g+3 in flight
+    auto body = [&](int g, auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
+        const int g4 = g + 4 < p.G ? g + 4 : p.G - 1;           // past the end: refetch the last group (unused)
+        const Staged qn = load_group(g4);                         // consumed two iterations from now
+        intx16 d[2];
+#pragma unroll
+        for (int t = 0; t <= kSub; ++t) {
+            if (t < kSub) {
+                const int c = t / T::kRB, r = t % T::kRB;
+                d[t & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][0], bf[c][0], magic, 0, 0, 0);
+                d[t & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][1], bf[c][1], d[t & 1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (t == kSub - 1) read_codes((slot + 1) % 3);       // all MFMAs of g are issued: fetch g+1's operands
+            if (t == kSub) store_group((slot + 2) % 3, q0);      // widen g+2 (fetched two iterations ago) into the free slot
+            if (t > 0) {
+                const int c = (t - 1) / T::kRB, r = (t - 1) % T::kRB;
+                rescale(acc[r][c], d[(t - 1) & 1], swv[c], sxv[r][0], sxv[r][1]);
                 if (MODE == 1) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int row = gm0 + wm0 + r * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                         const int col = gn0 + wn0 + c * 32 + li;
                         if (row >= p.m0 && row < p.m1 && col >= p.n0 && col < p.n1)
-                            p.dbg[((size_t)(row - p.m0) * (p.n1 - p.n0) + (col - p.n0)) * p.G + g] = (d[v] - kMagicBits) >> 8;
+                            p.dbg[((size_t)(row - p.m0) * (p.n1 - p.n0) + (col - p.n0)) * p.G + g] = (d[(t - 1) & 1][v] - kMagicBits) >> 8;
                     }
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
-
-        if (g + 1 < p.G) store_group(stage ^ 1);
+        read_scales((slot + 1) % 3);
+        q0 = q1;
+        q1 = qn;
         __syncthreads();
+    };
+
+    store_group(0, load_group(0));
+    store_group(1, load_group(1 < glast ? 1 : glast));
+    q0 = load_group(2 < glast ? 2 : glast);
+    q1 = load_group(3 < glast ? 3 : glast);
+    __syncthreads();
+    read_codes(0);
+    read_scales(0);
+    {
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        using S2 = std::integral_constant<int, 2>;
+        int g = 0;
+        for (; g + 3 <= p.G; g += 3) {
+            body(g, S0{});
+            body(g + 1, S1{});
+            body(g + 2, S2{});
+        }
+        if (g < p.G) body(g, S0{});
+        if (g + 1 < p.G) body(g + 1, S1{});
     }
 
     if (MODE == 1) return;   // the window export writes no Y
 
     // ---- epilogue: low-rank up projection on the matrix core, bias, bf16 store -----------------
+    // acc += H L2 as bf16 MFMAs with the fp32 accumulator tile as C.  H is fp32; it is split into
+    // bf16 hi + lo parts (two MFMAs) so the 16-bit branch loses nothing against an fp32 evaluation.
+    // The loads of rank step k+1 are in flight while step k is multiplied.
     if (p.rank > 0) {
-        for (int kk = 0; kk < p.rank; kk += 16) {
-            bf16x8 hh[T::kRB], hl[T::kRB];
+        const int ksteps = p.rank / 16;
+        float4 hraw[2][T::kRB][2];
+        uint4 braw[2][T::kCB];
+        auto load_step = [&](int buf, int ks) {
 #pragma unroll
             for (int r = 0; r < T::kRB; ++r) {
                 int row = gm0 + wm0 + r * 32 + li;
                 row = row < p.M ? row : p.M - 1;
-                const float4 *hp = reinterpret_cast<const float4 *>(p.H + (size_t)row * p.rank + kk + 8 * lh);
-                const float4 h0 = hp[0], h1 = hp[1];
+                const float4 *hp = reinterpret_cast<const float4 *>(p.H + (size_t)row * p.rank + ks * 16 + 8 * lh);
+                hraw[buf][r][0] = hp[0];
+                hraw[buf][r][1] = hp[1];
+            }
+#pragma unroll
+            for (int c = 0; c < T::kCB; ++c) {
+                const int col = gn0 + wn0 + c * 32 + li;        // < Npad
+                braw[buf][c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
+            }
+        };
+        auto compute_step = [&](int buf) {
+            bf16x8 hh[T::kRB], hl[T::kRB];
+#pragma unroll
+            for (int r = 0; r < T::kRB; ++r) {
+                const float4 h0 = hraw[buf][r][0], h1 = hraw[buf][r][1];
                 const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
                 uint32_t hi[8], lo[8];
 #pragma unroll
@@ -245,14 +360,21 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmPa
             }
 #pragma unroll
             for (int c = 0; c < T::kCB; ++c) {
-                const int col = gn0 + wn0 + c * 32 + li;        // < Npad
-                const uint4 bw = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + kk + 8 * lh);
-                const bf16x8 bl = __builtin_bit_cast(bf16x8, bw);
+                const bf16x8 bl = __builtin_bit_cast(bf16x8, braw[buf][c]);
 #pragma unroll
                 for (int r = 0; r < T::kRB; ++r) {
                     acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hh[r], bl, acc[r][c], 0, 0, 0);
                     acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hl[r], bl, acc[r][c], 0, 0, 0);
                 }
+            }
+        };
+        load_step(0, 0);
+        for (int ks = 0; ks < ksteps; ks += 2) {
+            if (ks + 1 < ksteps) load_step(1, ks + 1);
+            compute_step(0);
+            if (ks + 1 < ksteps) {
+                if (ks + 2 < ksteps) load_step(0, ks + 2);
+                compute_step(1);
             }
         }
     }
