@@ -86,17 +86,20 @@ __global__ __launch_bounds__(256) void act_kernel(ActParams p) {
             const _Float16 sh = (_Float16)s32;
             const float s = (float)sh;
             const float rcp = s > 0.f ? 1.0f / s : 0.f;
-            uint32_t packed[2] = {0u, 0u};
+            // the codes leave as int8 = 16 * code, the operand form of the int8 MFMA in the GEMM, in the byte
+            // order in which the GEMM's nibble widening leaves the weight codes (act_byte_pos)
+            uint32_t bytes[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float q = __builtin_rintf(xh[e] * rcp);
                 q = fminf(7.f, fmaxf(-7.f, q));
-                const uint32_t nib = (uint32_t)((int)q) & 0xfu;
-                packed[e >> 3] |= nib << (4 * (e & 7));
+                const uint32_t b = ((uint32_t)((int)q) & 0xfu) << 4;
+                const int pos = act_byte_pos(e);
+                bytes[pos >> 2] |= b << (8 * (pos & 3));
             }
             if (valid) {
-                uint2 *cp = reinterpret_cast<uint2 *>(p.codes + ((size_t)g * p.Mpad + m) * kCodeBytes + 8 * blk);
-                *cp = make_uint2(packed[0], packed[1]);
+                uint4 *cp = reinterpret_cast<uint4 *>(p.codes + ((size_t)g * p.Mpad + m) * kActBytes + 16 * blk);
+                *cp = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
                 if (blk == 0) p.sx[(size_t)g * p.Mpad + m] = __builtin_bit_cast(uint16_t, sh);
             }
         }
@@ -147,9 +150,8 @@ __global__ void debug_act_kernel(DebugActParams p) {
     if (p.out_codes && idx < ncodes) {
         const int m = (int)(idx / p.K), k = (int)(idx % p.K);
         const int g = k / 64, kk = k % 64;
-        const uint8_t b = p.codes[((size_t)g * p.Mpad + m) * kCodeBytes + kk / 2];
-        const int nib = (kk & 1) ? (b >> 4) : (b & 0xf);
-        p.out_codes[idx] = (int8_t)((nib ^ 8) - 8);
+        const int8_t b = (int8_t)p.codes[((size_t)g * p.Mpad + m) * kActBytes + (kk & ~15) + act_byte_pos(kk & 15)];
+        p.out_codes[idx] = (int8_t)(b >> 4);
     }
     if (p.out_sx && idx < (size_t)p.M * p.G) {
         const int m = (int)(idx / p.G), g = (int)(idx % p.G);

@@ -4,21 +4,27 @@
 //   Y[m][n] = sum_g sx[m][g] sw[g][n] A_g[m][n]  +  sum_j H[m][j] L2[j][n]  +  bias[n]
 //   A_g[m][n] = sum_{k in group g} qx[m][k] qw[k][n]        (exact int32, Eq. 2 per group of 64)
 //
-// gfx950 has no 4-bit integer MFMA, so the codes are widened to int8 on the way into LDS: a packed
-// dword x becomes  (x << 4) & 0xF0F0F0F0  (even codes) and  x & 0xF0F0F0F0  (odd codes), i.e. every
-// byte is 16 * code with the sign in place, at three vector-ALU operations per eight codes.  Both
-// operands get the factor 16, so an MFMA sum is 256 * A_g; the 2^-8 is folded into the weight scale.
+// gfx950 has no 4-bit integer MFMA, so both operands reach the matrix core as int8 holding
+// 16 * code.  The activation kernel already writes its codes in that form (one byte per code);
+// the packed weight nibbles are widened on the way into LDS: a packed dword x becomes
+// (x << 4) & 0xF0F0F0F0 (even codes) and x & 0xF0F0F0F0 (odd codes), three vector-ALU operations
+// per eight codes, once per workgroup.  An MFMA sum is therefore 256 * A_g; the 2^-8 is folded into
+// the weight scale.
 //
 // One group of 64 channels is two v_mfma_i32_32x32x32_i8.  Their accumulator is seeded with the bit
 // pattern of 1.5 * 2^23, so the int32 result read as fp32 is exactly 12582912 + 256 * A_g and
 //     t   = fma(F, sw * 2^-8, -12582912 * sw * 2^-8)     == A_g * sw      (exact: 12 + 11 bits)
 //     acc = fma(t, sx, acc)
-// rescales a partial sum in two FMAs with no integer-to-float conversion.  The per-group rescale
-// (one partial sum per 64 multiply-accumulates) is what bounds this kernel on the vector ALU, not
-// the matrix core.
+// rescales a partial sum in two FMAs with no integer-to-float conversion.  This per-group rescale
+// (one partial sum per 64 multiply-accumulates, two vector instructions each) is what bounds the
+// kernel: a wavefront cannot overlap its own MFMA with its own vector work, so the overlap comes
+// from the second wavefront on each SIMD, and every vector instruction that is not a rescale FMA
+// (address arithmetic, widening, scale conversion) costs matrix-core time.  Hence: buffer loads
+// with scalar offsets, A operand stored ready-made, the weight widening shared by the whole
+// workgroup, the scale conversion done once per workgroup and group.
 //
-// The k order inside a group only has to be the same for both operands, so the widened 64-byte rows
-// are consumed as they lie in LDS: lane half h of a fragment takes bytes 32 h .. 32 h + 15 for the
+// The k order inside a group only has to be the same for both operands, so the 64-byte rows are
+// consumed as they lie in LDS: lane half h of a fragment takes bytes 32 h .. 32 h + 15 for the
 // first MFMA and the next 16 for the second, for the activation and the weight alike.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -34,8 +40,12 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kLdsRow = 80;   // 64 int8 + 16 pad: ds_read_b128 of consecutive rows hits distinct banks
+constexpr int kLdsRow = 80;      // 64 int8 + 16 pad: ds_read_b128 of consecutive rows hits distinct banks
+constexpr int kScaleRing = 4;    // scales live in their own small ring, read at the start of the iteration that uses them
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -43,22 +53,38 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
     return u >> 16;
 }
 
-template <int BM, int BN, int WM, int WN>
+// A raw buffer descriptor over [base, base + bytes): loads take a per-thread byte offset in a VGPR and a
+// uniform byte offset in an SGPR, so walking the K dimension costs scalar adds only, and reads past the
+// end return zero instead of faulting.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, size_t bytes) {
+    const uint32_t n = bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)n, 0x00020000);
+}
+
+template <int BM, int BN>
 struct Tile {
-    static constexpr int kWavesM = BM / WM, kWavesN = BN / WN;
+    static constexpr int kWavesM = BM / 64, kWavesN = BN / 64;
     static constexpr int kWaves = kWavesM * kWavesN;
     static constexpr int kThreads = kWaves * 64;
-    static constexpr int kRB = WM / 32, kCB = WN / 32;
-    static constexpr int kStageA = BM * kLdsRow, kStageB = BN * kLdsRow;
-    // per stage: A codes, B codes, sx fp16 [BM] (row-permuted), sw pairs fp32 [BN][2]
-    static constexpr int kStageBytes = kStageA + kStageB + BM * 2 + BN * 8;
-    static constexpr int kLdsBytes = 3 * kStageBytes;      // ring of three slots
+    static constexpr int kSlotA = BM * kLdsRow, kSlotB = BN * kLdsRow;
+    static constexpr int kSlot = kSlotA + kSlotB;
+    static constexpr int kSxOff = 2 * kSlot;                       // fp16 [ring][BM], row-permuted
+    static constexpr int kSwOff = kSxOff + kScaleRing * BM * 2;    // float2 [ring][BN]
+    static constexpr int kLdsBytes = kSwOff + kScaleRing * BN * 8;
+    // staging split: the A slab of a group is BM x 64 bytes in 16-byte chunks, the packed B slab BN x 32 bytes
+    // in 16-byte granules if there are enough of them for every thread and in 8-byte granules otherwise
+    static constexpr int kNA = BM * 4 / kThreads;
+    static constexpr int kGranB = (BN * 2 >= kThreads) ? 16 : 8;
+    static constexpr int kNB = BN * 32 / kGranB / kThreads;
+    static_assert(kNA >= 1 && kNA * kThreads == BM * 4, "A slab must split evenly over the threads");
+    static_assert(kNB >= 1 && kNB * kGranB * kThreads == BN * 32, "B slab must split evenly over the threads");
+    static_assert(kThreads >= 64 && (BM % kThreads == 0 || kThreads % BM == 0) && (BN % kThreads == 0 || kThreads % BN == 0), "");
 };
 
 // MODE 0: normal forward.  MODE 1: additionally export exact group sums of a window (parity checks).
-template <int BM, int BN, int WM, int WN, int MODE>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(GemmParams p) {
-    using T = Tile<BM, BN, WM, WN>;
+template <int BM, int BN, int MODE>
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_kernel(GemmParams p) {
+    using T = Tile<BM, BN>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
@@ -66,8 +92,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
     const int wave = tid >> 6;
     const int li = lane & 31;      // row (A) / column (B) inside a 32-wide MFMA block
     const int lh = lane >> 5;      // which half of the k range this lane feeds
-    const int wm0 = (wave % T::kWavesM) * WM;
-    const int wn0 = (wave / T::kWavesM) * WN;
+    const int wm0 = (wave % T::kWavesM) * 64;
+    const int wn0 = (wave / T::kWavesM) * 64;
 
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that an
     // XCD owns a contiguous run of tiles, walked in bands of kBand tile rows: the tiles that run at the
@@ -93,11 +119,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
         if (gm0 >= p.m1 || gm0 + BM <= p.m0 || gn0 >= p.n1 || gn0 + BN <= p.n0) return;
     }
 
-    floatx16 acc[T::kRB][T::kCB];
+    floatx16 acc[2][2];
 #pragma unroll
-    for (int r = 0; r < T::kRB; ++r)
+    for (int r = 0; r < 2; ++r)
 #pragma unroll
-        for (int c = 0; c < T::kCB; ++c)
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
@@ -105,214 +131,188 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
 #pragma unroll
     for (int v = 0; v < 16; ++v) magic[v] = p.magic;
 
-    // ---- global -> register -> LDS staging of one group's slab ----------------------------------
-    // Each operand's slab of one group (rows x 32 packed bytes) is split evenly over the block's
-    // threads, in 16-byte units if there are enough of them and in 8-byte granules otherwise, so the
-    // loop body has no branches: one basic block that the instruction scheduler can pipeline.
-    constexpr int kGranA = (BM * 2 >= T::kThreads) ? 16 : 8;
-    constexpr int kGranB = (BN * 2 >= T::kThreads) ? 16 : 8;
-    constexpr int kNA = BM * 32 / kGranA / T::kThreads;
-    constexpr int kNB = BN * 32 / kGranB / T::kThreads;
-    static_assert(kNA >= 1 && kNA * kGranA * T::kThreads == BM * 32, "A slab must split evenly over the threads");
-    static_assert(kNB >= 1 && kNB * kGranB * T::kThreads == BN * 32, "B slab must split evenly over the threads");
-    static_assert(T::kThreads >= BM && T::kThreads >= BN, "one thread per row stages the scales");
-    struct Staged {                  // one group's share of this thread, on its way from memory to LDS
-        uint4 a[kNA], b[kNB];        // only .x/.y are used for 8-byte granules
-        uint32_t sx, sw;
-    };
+    // ---- global -> register staging of one group's slabs ----------------------------------------
+    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.xcodes, (size_t)p.G * p.Mpad * kActBytes);
+    const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(p.wcodes, (size_t)p.G * p.Npad * kCodeBytes);
+    const __amdgpu_buffer_rsrc_t rs_sx = make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2);
+    const __amdgpu_buffer_rsrc_t rs_sw = make_rsrc(p.sw, (size_t)p.G * p.Npad * 2);
+    const int a_stride = p.Mpad * kActBytes, b_stride = p.Npad * kCodeBytes;
+    const int a_base = gm0 * kActBytes, b_base = gn0 * kCodeBytes;
+    const int sx_stride = p.Mpad * 2, sw_stride = p.Npad * 2;
     const int xrow = tid % BM, wrow = tid % BN;
     // the 16 rows one lane rescales are contiguous: row = 32*blk + 8*j + 4*h + v -> 32*blk + 16*h + 4*j + v
     const int xpos = (xrow & ~31) + ((xrow >> 2) & 1) * 16 + ((xrow >> 3) & 3) * 4 + (xrow & 3);
 
-    // uniform (scalar) slab bases + small per-thread offsets, so the loads need no 64-bit vector adds
-    const unsigned char *xbase = p.xcodes + (size_t)gm0 * kCodeBytes;
-    const unsigned char *wbase = p.wcodes + (size_t)gn0 * kCodeBytes;
-    const uint16_t *sxbase = p.sx + gm0;
-    const uint16_t *swbase = p.sw + gn0;
-    const size_t xstride = (size_t)p.Mpad * kCodeBytes, wstride = (size_t)p.Npad * kCodeBytes;
-
+    struct Staged {                  // one group's share of this thread, on its way from memory to LDS
+        u32x4 a[T::kNA];
+        u32x4 b[T::kNB];             // only .x/.y are used for 8-byte granules
+        uint32_t sx, sw;
+    };
     auto load_group = [&](int g) {
         Staged q;
-        uint4 (&ra)[kNA] = q.a;
-        uint4 (&rb)[kNB] = q.b;
-        const unsigned char *ga = xbase + (size_t)g * xstride;
-        const unsigned char *gb = wbase + (size_t)g * wstride;
+        u32x4 (&ra)[T::kNA] = q.a;
+        u32x4 (&rb)[T::kNB] = q.b;
+        const int sa = a_base + g * a_stride, sb = b_base + g * b_stride;
 #pragma unroll
-        for (int i = 0; i < kNA; ++i) {
-            const unsigned u = tid + i * T::kThreads;
-            if (kGranA == 16) ra[i] = *reinterpret_cast<const uint4 *>(ga + u * 16u);
-            else { const uint2 v = *reinterpret_cast<const uint2 *>(ga + u * 8u); ra[i].x = v.x; ra[i].y = v.y; }
-        }
+        for (int i = 0; i < T::kNA; ++i)
+            ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_a, tid * 16, sa + i * T::kThreads * 16, 0);
 #pragma unroll
-        for (int i = 0; i < kNB; ++i) {
-            const unsigned u = tid + i * T::kThreads;
-            if (kGranB == 16) rb[i] = *reinterpret_cast<const uint4 *>(gb + u * 16u);
-            else { const uint2 v = *reinterpret_cast<const uint2 *>(gb + u * 8u); rb[i].x = v.x; rb[i].y = v.y; }
+        for (int i = 0; i < T::kNB; ++i) {
+            if (T::kGranB == 16) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_b, tid * 16, sb + i * T::kThreads * 16, 0);
+            else { const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs_b, tid * 8, sb + i * T::kThreads * 8, 0); rb[i].x = v.x; rb[i].y = v.y; }
         }
-        q.sx = sxbase[(size_t)g * p.Mpad + (unsigned)xrow];
-        q.sw = swbase[(size_t)g * p.Npad + (unsigned)wrow];
+        q.sx = __builtin_amdgcn_raw_buffer_load_b16(rs_sx, xrow * 2, (g * p.Mpad + gm0) * 2, 0);
+        q.sw = __builtin_amdgcn_raw_buffer_load_b16(rs_sw, wrow * 2, (g * p.Npad + gn0) * 2, 0);
+        (void)sx_stride; (void)sw_stride;
         return q;
     };
 
-    // An empty volatile asm keeps its operand's consumers at this point of the program: without it the
-    // compiler hoists the widening to the top of the iteration, right behind the global loads it waits on.
-    auto pin = [](uint32_t &v) { asm volatile("" : "+v"(v)); };
-
+    // ---- register -> LDS: A is copied, B is widened, scales are converted ------------------------
     // widen packed nibbles to bytes holding 16 * code: (x << 4) & 0xF0F0F0F0 are the even codes, x & 0xF0F0F0F0 the odd
-    auto widen_store = [&](unsigned char *dst, const uint4 &x, int gran, unsigned u) {
-        uint4 lo, hi;
-        lo.x = (x.x << 4) & 0xf0f0f0f0u; lo.y = x.x & 0xf0f0f0f0u;
-        lo.z = (x.y << 4) & 0xf0f0f0f0u; lo.w = x.y & 0xf0f0f0f0u;
-        if (gran == 16) {
-            hi.x = (x.z << 4) & 0xf0f0f0f0u; hi.y = x.z & 0xf0f0f0f0u;
-            hi.z = (x.w << 4) & 0xf0f0f0f0u; hi.w = x.w & 0xf0f0f0f0u;
-            uint4 *q = reinterpret_cast<uint4 *>(dst + (u >> 1) * kLdsRow + (u & 1) * 32);
-            q[0] = lo;
-            q[1] = hi;
-        } else {
-            *reinterpret_cast<uint4 *>(dst + (u >> 2) * kLdsRow + (u & 3) * 16) = lo;
+    auto store_group = [&](int slot, int ring, const Staged &q) {
+        unsigned char *sa = lds + slot * T::kSlot;
+        unsigned char *sb = sa + T::kSlotA;
+#pragma unroll
+        for (int i = 0; i < T::kNA; ++i) {
+            const unsigned u = tid + i * T::kThreads;
+            *reinterpret_cast<u32x4 *>(sa + (u >> 2) * kLdsRow + (u & 3) * 16) = q.a[i];
         }
-    };
-
-    auto store_group = [&](int slot, Staged q) {
-        uint4 (&ra)[kNA] = q.a;
-        uint4 (&rb)[kNB] = q.b;
-        uint32_t &rsx = q.sx, &rsw = q.sw;
 #pragma unroll
-        for (int i = 0; i < kNA; ++i) { pin(ra[i].x); pin(ra[i].y); if (kGranA == 16) { pin(ra[i].z); pin(ra[i].w); } }
-#pragma unroll
-        for (int i = 0; i < kNB; ++i) { pin(rb[i].x); pin(rb[i].y); if (kGranB == 16) { pin(rb[i].z); pin(rb[i].w); } }
-        pin(rsx);
-        pin(rsw);
-        unsigned char *sa = lds + slot * T::kStageBytes;
-        unsigned char *sb = sa + T::kStageA;
-        uint16_t *ssx = reinterpret_cast<uint16_t *>(sb + T::kStageB);
-        float2 *ssw = reinterpret_cast<float2 *>(ssx + BM);
-#pragma unroll
-        for (int i = 0; i < kNA; ++i) widen_store(sa, ra[i], kGranA, tid + i * T::kThreads);
-#pragma unroll
-        for (int i = 0; i < kNB; ++i) widen_store(sb, rb[i], kGranB, tid + i * T::kThreads);
-        ssx[xpos] = (uint16_t)rsx;       // threads beyond BM / BN repeat the first ones' (identical) stores
-        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)rsw) * 0.00390625f;   // sw * 2^-8: both operands carry a factor 16
+        for (int i = 0; i < T::kNB; ++i) {
+            const unsigned u = tid + i * T::kThreads;
+            const u32x4 x = q.b[i];
+            u32x4 lo, hi;
+            lo.x = (x.x << 4) & 0xf0f0f0f0u; lo.y = x.x & 0xf0f0f0f0u;
+            lo.z = (x.y << 4) & 0xf0f0f0f0u; lo.w = x.y & 0xf0f0f0f0u;
+            if (T::kGranB == 16) {
+                hi.x = (x.z << 4) & 0xf0f0f0f0u; hi.y = x.z & 0xf0f0f0f0u;
+                hi.z = (x.w << 4) & 0xf0f0f0f0u; hi.w = x.w & 0xf0f0f0f0u;
+                u32x4 *w = reinterpret_cast<u32x4 *>(sb + (u >> 1) * kLdsRow + (u & 1) * 32);
+                w[0] = lo;
+                w[1] = hi;
+            } else {
+                *reinterpret_cast<u32x4 *>(sb + (u >> 2) * kLdsRow + (u & 3) * 16) = lo;
+            }
+        }
+        uint16_t *ssx = reinterpret_cast<uint16_t *>(lds + T::kSxOff) + ring * BM;
+        float2 *ssw = reinterpret_cast<float2 *>(lds + T::kSwOff) + ring * BN;
+        ssx[xpos] = (uint16_t)q.sx;      // threads beyond BM / BN repeat the first ones' (identical) stores
+        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sw) * 0.00390625f;   // sw * 2^-8: both operands carry a factor 16
         ssw[wrow] = make_float2(s, -kMagic * s);
     };
 
     // ---- fragments: LDS -> registers --------------------------------------------------------------
-    typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
-    constexpr int kSub = T::kRB * T::kCB;
-    intx4 af[T::kRB][2], bf[T::kCB][2];
-    halfx8 sxv[T::kRB][2];
-    float2 swv[T::kCB];
+    intx4 af[2][2], bf[2][2];
+    halfx8 sxv[2][2];
+    float2 swv[2];
+    const unsigned char *a_rd = lds + (wm0 + li) * kLdsRow + lh * 32;
+    const unsigned char *b_rd = lds + T::kSlotA + (wn0 + li) * kLdsRow + lh * 32;
 
-    auto read_codes = [&](int slot) {
-        const unsigned char *sa = lds + slot * T::kStageBytes;
-        const unsigned char *sb = sa + T::kStageA;
-#pragma unroll
-        for (int r = 0; r < T::kRB; ++r) {
-            const unsigned char *ap = sa + (wm0 + r * 32 + li) * kLdsRow + lh * 32;
-            af[r][0] = *reinterpret_cast<const intx4 *>(ap);
-            af[r][1] = *reinterpret_cast<const intx4 *>(ap + 16);
-        }
-#pragma unroll
-        for (int c = 0; c < T::kCB; ++c) {
-            const unsigned char *bp = sb + (wn0 + c * 32 + li) * kLdsRow + lh * 32;
-            bf[c][0] = *reinterpret_cast<const intx4 *>(bp);
-            bf[c][1] = *reinterpret_cast<const intx4 *>(bp + 16);
-        }
+    auto read_a = [&](int slot, int r) {
+        const unsigned char *ap = a_rd + slot * T::kSlot + r * 32 * kLdsRow;
+        af[r][0] = *reinterpret_cast<const intx4 *>(ap);
+        af[r][1] = *reinterpret_cast<const intx4 *>(ap + 16);
     };
-    auto read_scales = [&](int slot) {
-        const unsigned char *sb = lds + slot * T::kStageBytes + T::kStageA;
-        const uint16_t *ssx = reinterpret_cast<const uint16_t *>(sb + T::kStageB);
-        const float2 *ssw = reinterpret_cast<const float2 *>(ssx + BM);
+    auto read_b = [&](int slot, int c) {
+        const unsigned char *bp = b_rd + slot * T::kSlot + c * 32 * kLdsRow;
+        bf[c][0] = *reinterpret_cast<const intx4 *>(bp);
+        bf[c][1] = *reinterpret_cast<const intx4 *>(bp + 16);
+    };
+    auto read_scales = [&](int ring) {
+        const uint16_t *ssx = reinterpret_cast<const uint16_t *>(lds + T::kSxOff) + ring * BM;
+        const float2 *ssw = reinterpret_cast<const float2 *>(lds + T::kSwOff) + ring * BN;
 #pragma unroll
-        for (int r = 0; r < T::kRB; ++r) {
+        for (int r = 0; r < 2; ++r) {
             const halfx8 *sp = reinterpret_cast<const halfx8 *>(ssx + wm0 + r * 32 + lh * 16);
             sxv[r][0] = sp[0];
             sxv[r][1] = sp[1];
         }
 #pragma unroll
-        for (int c = 0; c < T::kCB; ++c) swv[c] = ssw[wn0 + c * 32 + li];
+        for (int c = 0; c < 2; ++c) swv[c] = ssw[wn0 + c * 32 + li];
     };
 
-    auto rescale = [&](floatx16 &a, const intx16 &d, const float2 sw, const halfx8 &s0, const halfx8 &s1) {
+    // one 32x32 sub-tile of one group: two MFMAs, then the rescale of their 16 partial sums per lane
+    auto subtile = [&](int g, int r, int c) {
+        intx16 d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][0], bf[c][0], magic, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][1], bf[c][1], d, 0, 0, 0);
+        const float2 sw = swv[c];
+        floatx16 &a = acc[r][c];
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
             const float t = __builtin_fmaf(__int_as_float(d[v]), sw.x, sw.y);
-            a[v] = __builtin_fmaf(t, (float)s0[v], a[v]);
+            a[v] = __builtin_fmaf(t, (float)sxv[r][0][v], a[v]);
         }
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
             const float t = __builtin_fmaf(__int_as_float(d[v + 8]), sw.x, sw.y);
-            a[v + 8] = __builtin_fmaf(t, (float)s1[v], a[v + 8]);
+            a[v + 8] = __builtin_fmaf(t, (float)sxv[r][1][v], a[v + 8]);
+        }
+        if (MODE == 1) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = gm0 + wm0 + r * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                const int col = gn0 + wn0 + c * 32 + li;
+                if (row >= p.m0 && row < p.m1 && col >= p.n0 && col < p.n1)
+                    p.dbg[((size_t)(row - p.m0) * (p.n1 - p.n0) + (col - p.n0)) * p.G + g] = (d[v] - kMagicBits) >> 8;
+            }
         }
     };
 
-    // ---- main loop over groups: a ring of three LDS slots -----------------------------------------
-    // While group g is multiplied out of registers, the codes of g+1 are read from their slot (filled
-    // one iteration ago), g+2 (fetched from memory two iterations ago) is widened and written to the
-    // third slot, and the fetch of g+4 is issued: a memory round trip has two full iterations to
-    // complete.  One barrier per group; a wavefront reaches it with its next operands already on the way.
-    //
-    // A wavefront cannot overlap its own MFMA with its own vector-ALU work, but two wavefronts on one
-    // SIMD can: each walks its 32x32 sub-tiles one at a time, issues the two MFMAs of sub-tile t and
-    // then rescales sub-tile t-1, whose MFMAs finished long ago.
-    const int glast = p.G - 1;
-    Staged q0, q1;                     // groups g+2 and g+3 in flight
-    auto body = [&](int g, auto slot_c) {
-        constexpr int slot = decltype(slot_c)::value;
-        const int g4 = g + 4 < p.G ? g + 4 : p.G - 1;           // past the end: refetch the last group (unused)
-        const Staged qn = load_group(g4);                         // consumed two iterations from now
-        intx16 d[2];
-#pragma unroll
-        for (int t = 0; t <= kSub; ++t) {
-            if (t < kSub) {
-                const int c = t / T::kRB, r = t % T::kRB;
-                d[t & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][0], bf[c][0], magic, 0, 0, 0);
-                d[t & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][1], bf[c][1], d[t & 1], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (t == kSub - 1) read_codes((slot + 1) % 3);       // all MFMAs of g are issued: fetch g+1's operands
-            if (t == kSub) store_group((slot + 2) % 3, q0);      // widen g+2 (fetched two iterations ago) into the free slot
-            if (t > 0) {
-                const int c = (t - 1) / T::kRB, r = (t - 1) % T::kRB;
-                rescale(acc[r][c], d[(t - 1) & 1], swv[c], sxv[r][0], sxv[r][1]);
-                if (MODE == 1) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = gm0 + wm0 + r * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                        const int col = gn0 + wn0 + c * 32 + li;
-                        if (row >= p.m0 && row < p.m1 && col >= p.n0 && col < p.n1)
-                            p.dbg[((size_t)(row - p.m0) * (p.n1 - p.n0) + (col - p.n0)) * p.G + g] = (d[(t - 1) & 1][v] - kMagicBits) >> 8;
-                    }
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
+    // ---- main loop over groups ----------------------------------------------------------------------
+    // Two LDS slots.  During iteration g the wavefronts multiply group g out of registers, read the
+    // fragments of group g+1 from slot (g+1)&1 (written one iteration ago) as the registers of group g
+    // fall free, and write group g+2 (fetched from memory two iterations ago) into slot g&1, whose
+    // contents every wavefront had finished reading before the barrier that ended iteration g-1.  One
+    // barrier per group.  The four sub-tiles are walked so that an operand is done with as early as
+    // possible: the walk of the next group starts at the sub-tile whose operands were replaced first,
+    // so no fragment is double-buffered.
+    // The staging registers never rotate: qe carries the even groups, qo the odd ones, each refilled right
+    // after it has been written to LDS, so no in-flight load destination is ever copied.
+    Staged qe, qo;                     // groups g+2 and g+3 on their way
+    auto body = [&](int g, auto odd_c, Staged &q) {
+        constexpr int odd = decltype(odd_c)::value;      // g & 1
+        constexpr int cur = odd, nxt = 1 - odd;
+        (void)cur;
+        read_scales(g & (kScaleRing - 1));
+        // even g: (0,0) (0,1) (1,1) (1,0); odd g: (0,1) (0,0) (1,0) (1,1)
+        constexpr int c0 = odd ? 1 : 0, c1 = 1 - c0;
+        subtile(g, 0, c0);
+        __builtin_amdgcn_sched_barrier(0);
+        subtile(g, 0, c1);
+        read_a(nxt, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        subtile(g, 1, c1);
+        read_b(nxt, c1);
+        store_group(odd, (g + 2) & (kScaleRing - 1), q);
+        {
+            // refill at once: the other set's loads are then a full iteration old when they are waited
+            // for, however conservatively the wait is counted
+            const int g4 = g + 4 < p.G ? g + 4 : p.G - 1;       // past the end: refetch the last group (unused)
+            q = load_group(g4);
         }
-        read_scales((slot + 1) % 3);
-        q0 = q1;
-        q1 = qn;
+        __builtin_amdgcn_sched_barrier(0);
+        subtile(g, 1, c0);
+        read_a(nxt, 1);
+        read_b(nxt, c0);
         __syncthreads();
     };
 
-    store_group(0, load_group(0));
-    store_group(1, load_group(1 < glast ? 1 : glast));
-    q0 = load_group(2 < glast ? 2 : glast);
-    q1 = load_group(3 < glast ? 3 : glast);
+    const int glast = p.G - 1;
+    store_group(0, 0, load_group(0));
+    store_group(1, 1, load_group(1 < glast ? 1 : glast));
+    qe = load_group(2 < glast ? 2 : glast);
+    qo = load_group(3 < glast ? 3 : glast);
     __syncthreads();
-    read_codes(0);
-    read_scales(0);
+    read_a(0, 0); read_a(0, 1); read_b(0, 0); read_b(0, 1);
     {
-        using S0 = std::integral_constant<int, 0>;
-        using S1 = std::integral_constant<int, 1>;
-        using S2 = std::integral_constant<int, 2>;
+        using Even = std::integral_constant<int, 0>;
+        using Odd = std::integral_constant<int, 1>;
         int g = 0;
-        for (; g + 3 <= p.G; g += 3) {
-            body(g, S0{});
-            body(g + 1, S1{});
-            body(g + 2, S2{});
+        for (; g + 2 <= p.G; g += 2) {
+            body(g, Even{}, qe);
+            body(g + 1, Odd{}, qo);
         }
-        if (g < p.G) body(g, S0{});
-        if (g + 1 < p.G) body(g + 1, S1{});
+        if (g < p.G) body(g, Even{}, qe);
     }
 
     if (MODE == 1) return;   // the window export writes no Y
@@ -323,11 +323,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
     // The loads of rank step k+1 are in flight while step k is multiplied.
     if (p.rank > 0) {
         const int ksteps = p.rank / 16;
-        float4 hraw[2][T::kRB][2];
-        uint4 braw[2][T::kCB];
+        float4 hraw[2][2][2];
+        uint4 braw[2][2];
         auto load_step = [&](int buf, int ks) {
 #pragma unroll
-            for (int r = 0; r < T::kRB; ++r) {
+            for (int r = 0; r < 2; ++r) {
                 int row = gm0 + wm0 + r * 32 + li;
                 row = row < p.M ? row : p.M - 1;
                 const float4 *hp = reinterpret_cast<const float4 *>(p.H + (size_t)row * p.rank + ks * 16 + 8 * lh);
@@ -335,15 +335,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
                 hraw[buf][r][1] = hp[1];
             }
 #pragma unroll
-            for (int c = 0; c < T::kCB; ++c) {
+            for (int c = 0; c < 2; ++c) {
                 const int col = gn0 + wn0 + c * 32 + li;        // < Npad
                 braw[buf][c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
             }
         };
         auto compute_step = [&](int buf) {
-            bf16x8 hh[T::kRB], hl[T::kRB];
+            bf16x8 hh[2], hl[2];
 #pragma unroll
-            for (int r = 0; r < T::kRB; ++r) {
+            for (int r = 0; r < 2; ++r) {
                 const float4 h0 = hraw[buf][r][0], h1 = hraw[buf][r][1];
                 const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
                 uint32_t hi[8], lo[8];
@@ -359,10 +359,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
                 hl[r] = __builtin_bit_cast(bf16x8, pl);
             }
 #pragma unroll
-            for (int c = 0; c < T::kCB; ++c) {
+            for (int c = 0; c < 2; ++c) {
                 const bf16x8 bl = __builtin_bit_cast(bf16x8, braw[buf][c]);
 #pragma unroll
-                for (int r = 0; r < T::kRB; ++r) {
+                for (int r = 0; r < 2; ++r) {
                     acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hh[r], bl, acc[r][c], 0, 0, 0);
                     acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hl[r], bl, acc[r][c], 0, 0, 0);
                 }
@@ -380,11 +380,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
     }
 
 #pragma unroll
-    for (int c = 0; c < T::kCB; ++c) {
+    for (int c = 0; c < 2; ++c) {
         const int col = gn0 + wn0 + c * 32 + li;
         const float b = p.bias[col];                            // bias is padded to Npad
 #pragma unroll
-        for (int r = 0; r < T::kRB; ++r) {
+        for (int r = 0; r < 2; ++r) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = gm0 + wm0 + r * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
@@ -394,19 +394,19 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_kernel(Gem
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN>
 hipError_t launch_tile(const GemmParams &p, hipStream_t stream) {
-    using T = Tile<BM, BN, WM, WN>;
+    using T = Tile<BM, BN>;
     const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
     const dim3 grid(tiles), block(T::kThreads);
     hipError_t e;
     if (p.dbg) {
-        auto k = gemm_kernel<BM, BN, WM, WN, 1>;
+        auto k = gemm_kernel<BM, BN, 1>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
     } else {
-        auto k = gemm_kernel<BM, BN, WM, WN, 0>;
+        auto k = gemm_kernel<BM, BN, 0>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
@@ -432,10 +432,10 @@ hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
     if (tile == 0) tile = 1;
     switch (tile) {
-        case 1: return launch_tile<128, 128, 64, 64>(p, stream);
-        case 2: return launch_tile<256, 256, 64, 128>(p, stream);
-        case 3: return launch_tile<256, 128, 64, 64>(p, stream);
-        case 4: return launch_tile<128, 256, 64, 128>(p, stream);
+        case 1: return launch_tile<256, 128>(p, stream);
+        case 2: return launch_tile<128, 128>(p, stream);
+        case 3: return launch_tile<128, 256>(p, stream);
+        case 4: return launch_tile<64, 128>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -15,7 +15,7 @@ struct ActParams {
     const uint16_t *X;       // bf16 [M][K]
     const float *rinv;       // fp32 [K]
     const uint16_t *l1s;     // bf16, fragment order
-    uint8_t *codes;          // [G][Mpad][32]
+    uint8_t *codes;          // [G][Mpad][64], int8 = 16 * code
     uint16_t *sx;            // fp16 [G][Mpad]
     float *H;                // fp32 [Mpad][rank]
     int M, K, G, Mpad, rank;
@@ -25,7 +25,7 @@ struct ActParams {
 hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream);
 
 struct GemmParams {
-    const uint8_t *xcodes;   // [G][Mpad][32]
+    const uint8_t *xcodes;   // [G][Mpad][64], int8 = 16 * code
     const uint16_t *sx;      // fp16 [G][Mpad]
     const float *H;          // fp32 [Mpad][rank]
     const uint8_t *wcodes;   // [G][Npad][32]

@@ -2,14 +2,21 @@
 //
 // Both 4-bit operands are stored "group-major": for every group g of 64 input channels, the
 // 64 codes of one row (a token of the activation, an output channel of the weight) are one
-// 32-byte block, and the blocks of all rows of that group are contiguous:
+// block, and the blocks of all rows of that group are contiguous, so the GEMM's K loop streams
+// one contiguous slab per operand per step:
 //
-//     codes[g][row][32 bytes],   byte j = code(k = 64 g + 2 j) & 15  |  code(k = 64 g + 2 j + 1) << 4
-//     scales[g][row]  (fp16)
+//     weight codes  wcodes[g][n][32 bytes], byte j = code(k = 64 g + 2 j) & 15 | code(k = 64 g + 2 j + 1) << 4
+//     weight scales wscales[g][n]  (fp16)
+//     activation codes (workspace) xcodes[g][m][64 bytes], one int8 = 16 * code per channel; inside every
+//         16-byte chunk the channels sit in the order the GEMM's nibble widening gives the weight codes
+//         (even channels of each eight first, see act_byte_pos), so both operands agree on k:
+//         the activation kernel emits its INT4 codes already in the int8 operand form of the
+//         matrix core (there is no 4-bit integer MFMA), which spares the GEMM the widening of
+//         this operand; the tensor lives only between the two kernels of one forward.
+//     activation scales (workspace) sx[g][m]  (fp16)
 //
-// so the GEMM's K loop streams one contiguous slab per operand per step.  Rows are padded to a
-// multiple of 256 so a full tile can always be read; padding rows of the weight hold zero
-// codes and zero scales.
+// Rows are padded to a multiple of 256 so a full tile can always be read; padding rows of the
+// weight hold zero codes and zero scales.
 //
 // The two bf16 low-rank factors are stored in the order the MFMA instructions consume them:
 //   l1s  [G][2 (k step)][rank/16 (column block)][64 (lane)][8]  - B operand of
@@ -33,8 +40,13 @@ namespace svdq {
 
 constexpr int kGroup = 64;
 constexpr int kRowPad = 256;        // rows of every group-major tensor are padded to this
-constexpr int kCodeBytes = 32;      // packed bytes of one row of one group
+constexpr int kCodeBytes = 32;      // packed bytes of one weight row of one group
+constexpr int kActBytes = 64;       // bytes of one activation row of one group (one int8 = 16 * code per channel)
 constexpr int kMaxRank = 256;
+
+// Position, inside its 16-byte chunk, of channel e (0..15) of an activation row: widening a packed dword of
+// eight weight nibbles yields the four even codes, then the four odd ones.
+inline __host__ __device__ int act_byte_pos(int e) { return (e & 8) + (e & 1) * 4 + ((e & 7) >> 1); }
 
 inline __host__ __device__ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline __host__ __device__ size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -57,7 +69,7 @@ inline __host__ __device__ Workspace workspace_layout(int M, int K, int rank) {
     w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
     const int G = K / kGroup;
     w.codes_off = 0;
-    w.sx_off = align256((size_t)G * w.Mpad * kCodeBytes);
+    w.sx_off = align256((size_t)G * w.Mpad * kActBytes);
     w.h_off = w.sx_off + align256((size_t)G * w.Mpad * 2);
     w.total = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
     return w;
