@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void act_kernel(ActParams p) {
                 bytes[pos >> 2] |= b << (8 * (pos & 3));
             }
             if (valid) {
-                uint4 *cp = reinterpret_cast<uint4 *>(p.codes + ((size_t)g * p.Mpad + m) * kActBytes + 16 * blk);
+                uint4 *cp = reinterpret_cast<uint4 *>(p.codes + act_chunk_offset(g, p.Mpad, m, blk));
                 *cp = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
                 if (blk == 0) p.sx[(size_t)g * p.Mpad + m] = __builtin_bit_cast(uint16_t, sh);
             }
@@ -150,7 +150,7 @@ __global__ void debug_act_kernel(DebugActParams p) {
     if (p.out_codes && idx < ncodes) {
         const int m = (int)(idx / p.K), k = (int)(idx % p.K);
         const int g = k / 64, kk = k % 64;
-        const int8_t b = (int8_t)p.codes[((size_t)g * p.Mpad + m) * kActBytes + (kk & ~15) + act_byte_pos(kk & 15)];
+        const int8_t b = (int8_t)p.codes[act_chunk_offset(g, p.Mpad, m, kk >> 4) + act_byte_pos(kk & 15)];
         p.out_codes[idx] = (int8_t)(b >> 4);
     }
     if (p.out_sx && idx < (size_t)p.M * p.G) {

@@ -5,11 +5,12 @@
 //   A_g[m][n] = sum_{k in group g} qx[m][k] qw[k][n]        (exact int32, Eq. 2 per group of 64)
 //
 // gfx950 has no 4-bit integer MFMA, so both operands reach the matrix core as int8 holding
-// 16 * code.  The activation kernel already writes its codes in that form (one byte per code);
-// the packed weight nibbles are widened on the way into LDS: a packed dword x becomes
-// (x << 4) & 0xF0F0F0F0 (even codes) and x & 0xF0F0F0F0 (odd codes), three vector-ALU operations
-// per eight codes, once per workgroup.  An MFMA sum is therefore 256 * A_g; the 2^-8 is folded into
-// the weight scale.
+// 16 * code.  The activation kernel writes its codes in that form and in the register order of
+// the MFMA A operand, so a wavefront loads its activation fragments straight from memory (one
+// contiguous kilobyte per instruction) and they never pass through LDS.  The packed weight
+// nibbles are widened on the way into LDS: a packed dword x becomes (x << 4) & 0xF0F0F0F0 (even
+// codes) and x & 0xF0F0F0F0 (odd codes), three vector-ALU operations per eight codes, once per
+// workgroup.  An MFMA sum is therefore 256 * A_g; the 2^-8 is folded into the weight scale.
 //
 // One group of 64 channels is two v_mfma_i32_32x32x32_i8.  Their accumulator is seeded with the bit
 // pattern of 1.5 * 2^23, so the int32 result read as fp32 is exactly 12582912 + 256 * A_g and
@@ -17,15 +18,15 @@
 //     acc = fma(t, sx, acc)
 // rescales a partial sum in two FMAs with no integer-to-float conversion.  This per-group rescale
 // (one partial sum per 64 multiply-accumulates, two vector instructions each) is what bounds the
-// kernel: a wavefront cannot overlap its own MFMA with its own vector work, so the overlap comes
-// from the second wavefront on each SIMD, and every vector instruction that is not a rescale FMA
-// (address arithmetic, widening, scale conversion) costs matrix-core time.  Hence: buffer loads
-// with scalar offsets, A operand stored ready-made, the weight widening shared by the whole
-// workgroup, the scale conversion done once per workgroup and group.
+// kernel: the MFMA's accumulator traffic and the FMAs' operands go through the same vector
+// register file, so matrix and vector work overlap only partly, and every vector instruction that
+// is not a rescale FMA costs matrix-core time.  Hence: buffer loads with scalar offsets, the A
+// operand stored ready-made, the weight widening and the scale conversions shared by the whole
+// workgroup.
 //
-// The k order inside a group only has to be the same for both operands, so the 64-byte rows are
-// consumed as they lie in LDS: lane half h of a fragment takes bytes 32 h .. 32 h + 15 for the
-// first MFMA and the next 16 for the second, for the activation and the weight alike.
+// The k order inside a group only has to be the same for both operands: lane half h of a fragment
+// takes bytes 32 h .. 32 h + 15 of a row for the first MFMA and the next 16 for the second, for the
+// activation and the weight alike.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
@@ -38,14 +39,16 @@ namespace {
 
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kLdsRow = 80;      // 64 int8 + 16 pad: ds_read_b128 of consecutive rows hits distinct banks
 constexpr int kScaleRing = 4;    // scales live in their own small ring, read at the start of the iteration that uses them
+constexpr int kOutRow = 144;     // epilogue staging: 64 bf16 columns + 16 bytes pad per row
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -66,19 +69,18 @@ struct Tile {
     static constexpr int kWavesM = BM / 64, kWavesN = BN / 64;
     static constexpr int kWaves = kWavesM * kWavesN;
     static constexpr int kThreads = kWaves * 64;
-    static constexpr int kSlotA = BM * kLdsRow, kSlotB = BN * kLdsRow;
-    static constexpr int kSlot = kSlotA + kSlotB;
-    static constexpr int kSxOff = 2 * kSlot;                       // fp16 [ring][BM], row-permuted
-    static constexpr int kSwOff = kSxOff + kScaleRing * BM * 2;    // float2 [ring][BN]
-    static constexpr int kLdsBytes = kSwOff + kScaleRing * BN * 8;
-    // staging split: the A slab of a group is BM x 64 bytes in 16-byte chunks, the packed B slab BN x 32 bytes
-    // in 16-byte granules if there are enough of them for every thread and in 8-byte granules otherwise
-    static constexpr int kNA = BM * 4 / kThreads;
+    static constexpr int kSlot = BN * kLdsRow;                     // widened weight codes of one group
+    static constexpr int kSxOff = 2 * kSlot;                       // fp32 [ring][BM]
+    static constexpr int kSwOff = kSxOff + kScaleRing * BM * 4;    // float2 [ring][BN]
+    static constexpr int kLoopBytes = kSwOff + kScaleRing * BN * 8;
+    static constexpr int kOutBytes = kWaves * 32 * kOutRow;        // epilogue: one 32 x 64 bf16 block per wavefront
+    static constexpr int kLdsBytes = kLoopBytes > kOutBytes ? kLoopBytes : kOutBytes;
+    // staging split of the packed weight slab of one group (BN x 32 bytes): 16-byte granules if there are
+    // enough of them for every thread, 8-byte granules otherwise
     static constexpr int kGranB = (BN * 2 >= kThreads) ? 16 : 8;
     static constexpr int kNB = BN * 32 / kGranB / kThreads;
-    static_assert(kNA >= 1 && kNA * kThreads == BM * 4, "A slab must split evenly over the threads");
     static_assert(kNB >= 1 && kNB * kGranB * kThreads == BN * 32, "B slab must split evenly over the threads");
-    static_assert(kThreads >= 64 && (BM % kThreads == 0 || kThreads % BM == 0) && (BN % kThreads == 0 || kThreads % BN == 0), "");
+    static_assert(kThreads >= BM && kThreads >= BN, "one thread per row / column stages the scales");
 };
 
 // MODE 0: normal forward.  MODE 1: additionally export exact group sums of a window (parity checks).
@@ -89,7 +91,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform per wavefront: keeps its offsets in scalar registers
     const int li = lane & 31;      // row (A) / column (B) inside a 32-wide MFMA block
     const int lh = lane >> 5;      // which half of the k range this lane feeds
     const int wm0 = (wave % T::kWavesM) * 64;
@@ -129,33 +131,43 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
 
     intx16 magic;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) magic[v] = p.magic;
+    for (int v = 0; v < 16; ++v) {
+        int m = p.magic;
+        asm volatile("" : "+v"(m));      // sixteen vector registers for good: the MFMA C operand cannot be scalar
+        magic[v] = m;
+    }
 
-    // ---- global -> register staging of one group's slabs ----------------------------------------
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.xcodes, (size_t)p.G * p.Mpad * kActBytes);
     const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(p.wcodes, (size_t)p.G * p.Npad * kCodeBytes);
     const __amdgpu_buffer_rsrc_t rs_sx = make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2);
     const __amdgpu_buffer_rsrc_t rs_sw = make_rsrc(p.sw, (size_t)p.G * p.Npad * 2);
-    const int a_stride = p.Mpad * kActBytes, b_stride = p.Npad * kCodeBytes;
-    const int a_base = gm0 * kActBytes, b_base = gn0 * kCodeBytes;
-    const int sx_stride = p.Mpad * 2, sw_stride = p.Npad * 2;
+
+    // ---- A fragments: memory -> registers, in the order the activation kernel wrote them -----------
+    // xcodes[g][m / 32][j][lane][16 bytes]: one load instruction fetches one contiguous kilobyte
+    const int a_stride = p.Mpad * kActBytes;
+    const int a_base = (gm0 + wm0) * kActBytes;        // 32 rows = 2 KB
+    auto load_a = [&](intx4 (&dst)[2][2], int g) {
+        const int s0 = a_base + g * a_stride;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                dst[r][j] = __builtin_bit_cast(intx4, __builtin_amdgcn_raw_buffer_load_b128(rs_a, lane * 16, s0 + (r * 2 + j) * 1024, 0));
+    };
+
+    // ---- B codes and both scales: memory -> registers -> LDS, shared by the workgroup --------------
+    const int b_stride = p.Npad * kCodeBytes;
+    const int b_base = gn0 * kCodeBytes;
     const int xrow = tid % BM, wrow = tid % BN;
-    // the 16 rows one lane rescales are contiguous: row = 32*blk + 8*j + 4*h + v -> 32*blk + 16*h + 4*j + v
-    const int xpos = (xrow & ~31) + ((xrow >> 2) & 1) * 16 + ((xrow >> 3) & 3) * 4 + (xrow & 3);
 
     struct Staged {                  // one group's share of this thread, on its way from memory to LDS
-        u32x4 a[T::kNA];
         u32x4 b[T::kNB];             // only .x/.y are used for 8-byte granules
         uint32_t sx, sw;
     };
     auto load_group = [&](int g) {
         Staged q;
-        u32x4 (&ra)[T::kNA] = q.a;
         u32x4 (&rb)[T::kNB] = q.b;
-        const int sa = a_base + g * a_stride, sb = b_base + g * b_stride;
-#pragma unroll
-        for (int i = 0; i < T::kNA; ++i)
-            ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_a, tid * 16, sa + i * T::kThreads * 16, 0);
+        const int sb = b_base + g * b_stride;
 #pragma unroll
         for (int i = 0; i < T::kNB; ++i) {
             if (T::kGranB == 16) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_b, tid * 16, sb + i * T::kThreads * 16, 0);
@@ -163,20 +175,12 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         }
         q.sx = __builtin_amdgcn_raw_buffer_load_b16(rs_sx, xrow * 2, (g * p.Mpad + gm0) * 2, 0);
         q.sw = __builtin_amdgcn_raw_buffer_load_b16(rs_sw, wrow * 2, (g * p.Npad + gn0) * 2, 0);
-        (void)sx_stride; (void)sw_stride;
         return q;
     };
 
-    // ---- register -> LDS: A is copied, B is widened, scales are converted ------------------------
     // widen packed nibbles to bytes holding 16 * code: (x << 4) & 0xF0F0F0F0 are the even codes, x & 0xF0F0F0F0 the odd
     auto store_group = [&](int slot, int ring, const Staged &q) {
-        unsigned char *sa = lds + slot * T::kSlot;
-        unsigned char *sb = sa + T::kSlotA;
-#pragma unroll
-        for (int i = 0; i < T::kNA; ++i) {
-            const unsigned u = tid + i * T::kThreads;
-            *reinterpret_cast<u32x4 *>(sa + (u >> 2) * kLdsRow + (u & 3) * 16) = q.a[i];
-        }
+        unsigned char *sb = lds + slot * T::kSlot;
 #pragma unroll
         for (int i = 0; i < T::kNB; ++i) {
             const unsigned u = tid + i * T::kThreads;
@@ -194,59 +198,62 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
                 *reinterpret_cast<u32x4 *>(sb + (u >> 2) * kLdsRow + (u & 3) * 16) = lo;
             }
         }
-        uint16_t *ssx = reinterpret_cast<uint16_t *>(lds + T::kSxOff) + ring * BM;
+        float *ssx = reinterpret_cast<float *>(lds + T::kSxOff) + ring * BM;
         float2 *ssw = reinterpret_cast<float2 *>(lds + T::kSwOff) + ring * BN;
-        ssx[xpos] = (uint16_t)q.sx;      // threads beyond BM / BN repeat the first ones' (identical) stores
+        // the scales are converted once per workgroup: the rescale then runs on plain fp32 FMAs
+        ssx[xrow] = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sx);   // threads beyond BM / BN repeat the first ones' stores
         const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sw) * 0.00390625f;   // sw * 2^-8: both operands carry a factor 16
         ssw[wrow] = make_float2(s, -kMagic * s);
     };
 
-    // ---- fragments: LDS -> registers --------------------------------------------------------------
-    intx4 af[2][2], bf[2][2];
-    halfx8 sxv[2][2];
-    float2 swv[2];
-    const unsigned char *a_rd = lds + (wm0 + li) * kLdsRow + lh * 32;
-    const unsigned char *b_rd = lds + T::kSlotA + (wn0 + li) * kLdsRow + lh * 32;
-
-    auto read_a = [&](int slot, int r) {
-        const unsigned char *ap = a_rd + slot * T::kSlot + r * 32 * kLdsRow;
-        af[r][0] = *reinterpret_cast<const intx4 *>(ap);
-        af[r][1] = *reinterpret_cast<const intx4 *>(ap + 16);
-    };
+    // ---- fragments and scales: LDS -> registers ---------------------------------------------------
+    intx4 bf[2][2];
+    const unsigned char *b_rd = lds + (wn0 + li) * kLdsRow + lh * 32;
     auto read_b = [&](int slot, int c) {
         const unsigned char *bp = b_rd + slot * T::kSlot + c * 32 * kLdsRow;
         bf[c][0] = *reinterpret_cast<const intx4 *>(bp);
         bf[c][1] = *reinterpret_cast<const intx4 *>(bp + 16);
     };
-    auto read_scales = [&](int ring) {
-        const uint16_t *ssx = reinterpret_cast<const uint16_t *>(lds + T::kSxOff) + ring * BM;
+    // The sixteen activation scales a lane needs for one 32-row block (rows 8 j + 4 h + i for accumulator
+    // register 4 j + i) live in ONE register per block, spread over the lanes: lane l holds the scale of
+    // row 8 ((l % 16) / 4) + 4 (l / 32) + l % 4, and the rescale FMA for register v reads it with the DPP
+    // row broadcast of lane v of its own 16-lane row.  A weight scale pair belongs to the lane's column.
+    struct Scales {
+        float sx[2];
+        float2 sw[2];
+    };
+    const int sx_lane = wm0 + 8 * ((lane & 15) >> 2) + 4 * lh + (lane & 3);
+    auto read_scales = [&](Scales &sc, int ring) {
+        const float *ssx = reinterpret_cast<const float *>(lds + T::kSxOff) + ring * BM;
         const float2 *ssw = reinterpret_cast<const float2 *>(lds + T::kSwOff) + ring * BN;
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const halfx8 *sp = reinterpret_cast<const halfx8 *>(ssx + wm0 + r * 32 + lh * 16);
-            sxv[r][0] = sp[0];
-            sxv[r][1] = sp[1];
-        }
+        for (int r = 0; r < 2; ++r) sc.sx[r] = ssx[sx_lane + r * 32];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) swv[c] = ssw[wn0 + c * 32 + li];
+        for (int c = 0; c < 2; ++c) sc.sw[c] = ssw[wn0 + c * 32 + li];
     };
 
-    // one 32x32 sub-tile of one group: two MFMAs, then the rescale of their 16 partial sums per lane
-    auto subtile = [&](int g, int r, int c) {
+// acc += bcast(sx, lane V of the row) * t
+#define SVDQ_FMAC_BCAST(ACC, SX, TT, V) \
+    asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:" #V " row_mask:0xf bank_mask:0xf" : "+v"(ACC) : "v"(SX), "v"(TT))
+
+    // one 32x32 sub-tile of one group: two MFMAs, then the rescale of their 16 partial sums per lane.
+    // The first FMAs of eight partial sums are issued before their second ones, so that no instruction
+    // waits for the result of the one just before it.
+    auto subtile = [&](const intx4 (&af)[2][2], const Scales &sc, int g, int r, int c) {
         intx16 d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][0], bf[c][0], magic, 0, 0, 0);
         d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][1], bf[c][1], d, 0, 0, 0);
-        const float2 sw = swv[c];
+        const float2 sw = sc.sw[c];
+        const float sx = sc.sx[r];
         floatx16 &a = acc[r][c];
+        float t[8];
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            const float t = __builtin_fmaf(__int_as_float(d[v]), sw.x, sw.y);
-            a[v] = __builtin_fmaf(t, (float)sxv[r][0][v], a[v]);
-        }
+        for (int v = 0; v < 8; ++v) t[v] = __builtin_fmaf(__int_as_float(d[v]), sw.x, sw.y);
+        SVDQ_FMAC_BCAST(a[0], sx, t[0], 0); SVDQ_FMAC_BCAST(a[1], sx, t[1], 1); SVDQ_FMAC_BCAST(a[2], sx, t[2], 2); SVDQ_FMAC_BCAST(a[3], sx, t[3], 3);
+        SVDQ_FMAC_BCAST(a[4], sx, t[4], 4); SVDQ_FMAC_BCAST(a[5], sx, t[5], 5); SVDQ_FMAC_BCAST(a[6], sx, t[6], 6); SVDQ_FMAC_BCAST(a[7], sx, t[7], 7);
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            const float t = __builtin_fmaf(__int_as_float(d[v + 8]), sw.x, sw.y);
-            a[v + 8] = __builtin_fmaf(t, (float)sxv[r][1][v], a[v + 8]);
-        }
+        for (int v = 0; v < 8; ++v) t[v] = __builtin_fmaf(__int_as_float(d[8 + v]), sw.x, sw.y);
+        SVDQ_FMAC_BCAST(a[8], sx, t[0], 8); SVDQ_FMAC_BCAST(a[9], sx, t[1], 9); SVDQ_FMAC_BCAST(a[10], sx, t[2], 10); SVDQ_FMAC_BCAST(a[11], sx, t[3], 11);
+        SVDQ_FMAC_BCAST(a[12], sx, t[4], 12); SVDQ_FMAC_BCAST(a[13], sx, t[5], 13); SVDQ_FMAC_BCAST(a[14], sx, t[6], 14); SVDQ_FMAC_BCAST(a[15], sx, t[7], 15);
         if (MODE == 1) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -259,61 +266,55 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     };
 
     // ---- main loop over groups ----------------------------------------------------------------------
-    // Two LDS slots.  During iteration g the wavefronts multiply group g out of registers, read the
-    // fragments of group g+1 from slot (g+1)&1 (written one iteration ago) as the registers of group g
-    // fall free, and write group g+2 (fetched from memory two iterations ago) into slot g&1, whose
-    // contents every wavefront had finished reading before the barrier that ended iteration g-1.  One
-    // barrier per group.  The four sub-tiles are walked so that an operand is done with as early as
-    // possible: the walk of the next group starts at the sub-tile whose operands were replaced first,
-    // so no fragment is double-buffered.
-    // The staging registers never rotate: qe carries the even groups, qo the odd ones, each refilled right
-    // after it has been written to LDS, so no in-flight load destination is ever copied.
-    Staged qe, qo;                     // groups g+2 and g+3 on their way
-    auto body = [&](int g, auto odd_c, Staged &q) {
+    // Iteration g multiplies group g.  Its activation fragments were loaded from memory one iteration
+    // earlier into the register set of its parity; the other set is refilled with group g+1 right at the
+    // start.  Weight codes go through two LDS slots: group g+1 is read from slot (g+1)&1 (written one
+    // iteration ago) as the registers of group g fall free, and group g+2 (fetched two iterations ago) is
+    // widened into slot g&1, which every wavefront finished reading before the barrier that ended
+    // iteration g-1.  One barrier per group.  The staging registers never rotate: qe carries the even
+    // groups, qo the odd ones, each refilled right after it has been written to LDS.
+    intx4 afe[2][2], afo[2][2];
+    Scales sce, sco;
+    Staged qe, qo;
+    auto body = [&](int g, auto odd_c, const intx4 (&af)[2][2], intx4 (&afn)[2][2], const Scales &sc, Scales &scn, Staged &q) {
         constexpr int odd = decltype(odd_c)::value;      // g & 1
-        constexpr int cur = odd, nxt = 1 - odd;
-        (void)cur;
-        read_scales(g & (kScaleRing - 1));
-        // even g: (0,0) (0,1) (1,1) (1,0); odd g: (0,1) (0,0) (1,0) (1,1)
-        constexpr int c0 = odd ? 1 : 0, c1 = 1 - c0;
-        subtile(g, 0, c0);
+        constexpr int nxt = 1 - odd;
+        load_a(afn, g + 1 < p.G ? g + 1 : p.G - 1);      // past the end: refetch the last group (unused)
+        read_scales(scn, (g + 1) & (kScaleRing - 1));    // written one iteration ago
+        subtile(af, sc, g, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        subtile(g, 0, c1);
-        read_a(nxt, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        subtile(g, 1, c1);
-        read_b(nxt, c1);
+        subtile(af, sc, g, 1, 0);
+        read_b(nxt, 0);
         store_group(odd, (g + 2) & (kScaleRing - 1), q);
-        {
-            // refill at once: the other set's loads are then a full iteration old when they are waited
-            // for, however conservatively the wait is counted
-            const int g4 = g + 4 < p.G ? g + 4 : p.G - 1;       // past the end: refetch the last group (unused)
-            q = load_group(g4);
-        }
+        q = load_group(g + 4 < p.G ? g + 4 : p.G - 1);
         __builtin_amdgcn_sched_barrier(0);
-        subtile(g, 1, c0);
-        read_a(nxt, 1);
-        read_b(nxt, c0);
+        subtile(af, sc, g, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        subtile(af, sc, g, 0, 1);
+        read_b(nxt, 1);
         __syncthreads();
     };
 
     const int glast = p.G - 1;
+    load_a(afe, 0);
     store_group(0, 0, load_group(0));
     store_group(1, 1, load_group(1 < glast ? 1 : glast));
     qe = load_group(2 < glast ? 2 : glast);
     qo = load_group(3 < glast ? 3 : glast);
     __syncthreads();
-    read_a(0, 0); read_a(0, 1); read_b(0, 0); read_b(0, 1);
+    read_b(0, 0); read_b(0, 1);
+    read_scales(sce, 0);
     {
         using Even = std::integral_constant<int, 0>;
         using Odd = std::integral_constant<int, 1>;
         int g = 0;
         for (; g + 2 <= p.G; g += 2) {
-            body(g, Even{}, qe);
-            body(g + 1, Odd{}, qo);
+            body(g, Even{}, afe, afo, sce, sco, qe);
+            body(g + 1, Odd{}, afo, afe, sco, sce, qo);
         }
-        if (g < p.G) body(g, Even{}, qe);
+        if (g < p.G) body(g, Even{}, afe, afo, sce, sco, qe);
     }
+#undef SVDQ_FMAC_BCAST
 
     if (MODE == 1) return;   // the window export writes no Y
 
@@ -379,16 +380,41 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         }
     }
 
+    // Bias, one rounding to bf16, and the store.  A lane holds one column and sixteen rows of a 32x32
+    // block; each wavefront turns its tile, 32 rows at a time, through a private LDS block so that a lane
+    // stores 16 bytes of one row and a store instruction writes whole 128-byte lines.
+    // (The last barrier of the main loop has passed: LDS is free.)
+    unsigned char *ob = lds + wave * (32 * kOutRow);
+    const float bias0 = p.bias[gn0 + wn0 + li], bias1 = p.bias[gn0 + wn0 + 32 + li];      // bias is padded to Npad
+    const bool full = gm0 + BM <= p.M && gn0 + BN <= p.N && (p.N % 8) == 0;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const int col = gn0 + wn0 + c * 32 + li;
-        const float b = p.bias[col];                            // bias is padded to Npad
+    for (int r = 0; r < 2; ++r) {
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
+        for (int c = 0; c < 2; ++c) {
+            const float b = c ? bias1 : bias0;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = gm0 + wm0 + r * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (row < p.M && col < p.N) p.Y[(size_t)row * p.N + col] = (uint16_t)bf16_rne_bits(acc[r][c][v] + b);
+                const int row = 8 * (v >> 2) + 4 * lh + (v & 3);
+                *reinterpret_cast<uint16_t *>(ob + row * kOutRow + (c * 32 + li) * 2) = (uint16_t)bf16_rne_bits(acc[r][c][v] + b);
+            }
+        }
+        // 32 rows x 128 bytes = 256 chunks of 16 bytes: four per lane
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int q = lane + 64 * i;
+            const int row = q >> 3, ch = q & 7;
+            const uint4 v = *reinterpret_cast<const uint4 *>(ob + row * kOutRow + ch * 16);
+            const int grow = gm0 + wm0 + r * 32 + row;
+            const int gcol = gn0 + wn0 + ch * 8;
+            uint16_t *dst = p.Y + (size_t)grow * p.N + gcol;
+            if (full) {
+                *reinterpret_cast<uint4 *>(dst) = v;
+            } else if (grow < p.M) {
+                const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
+                                       (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (gcol + k < p.N) dst[k] = e[k];
             }
         }
     }
@@ -430,7 +456,7 @@ __global__ __launch_bounds__(256) void upproj_kernel(const float *H, const uint1
 
 hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
-    if (tile == 0) tile = 1;
+    if (tile == 0) tile = 2;     // two independent 128x128 workgroups per CU measured fastest on the large-M shapes
     switch (tile) {
         case 1: return launch_tile<256, 128>(p, stream);
         case 2: return launch_tile<128, 128>(p, stream);

@@ -7,9 +7,12 @@
 //
 //     weight codes  wcodes[g][n][32 bytes], byte j = code(k = 64 g + 2 j) & 15 | code(k = 64 g + 2 j + 1) << 4
 //     weight scales wscales[g][n]  (fp16)
-//     activation codes (workspace) xcodes[g][m][64 bytes], one int8 = 16 * code per channel; inside every
-//         16-byte chunk the channels sit in the order the GEMM's nibble widening gives the weight codes
-//         (even channels of each eight first, see act_byte_pos), so both operands agree on k:
+//     activation codes (workspace) xcodes[g][m / 32][j][h][m % 32][16 bytes], one int8 = 16 * code per
+//         channel: the 16-byte chunk (j, h) of a row holds its channels 32 h + 16 j .. + 15, i.e. what lane
+//         32 h + m % 32 feeds to the j-th of the two MFMAs of a group, so a wavefront's A operand is one
+//         contiguous kilobyte (act_chunk_offset).  Inside a chunk the channels sit in the order the GEMM's
+//         nibble widening gives the weight codes (even channels of each eight first, act_byte_pos), so
+//         both operands agree on k:
 //         the activation kernel emits its INT4 codes already in the int8 operand form of the
 //         matrix core (there is no 4-bit integer MFMA), which spares the GEMM the widening of
 //         this operand; the tensor lives only between the two kernels of one forward.
@@ -47,6 +50,13 @@ constexpr int kMaxRank = 256;
 // Position, inside its 16-byte chunk, of channel e (0..15) of an activation row: widening a packed dword of
 // eight weight nibbles yields the four even codes, then the four odd ones.
 inline __host__ __device__ int act_byte_pos(int e) { return (e & 8) + (e & 1) * 4 + ((e & 7) >> 1); }
+
+// Byte offset of the 16-byte chunk that holds channels 16 blk .. 16 blk + 15 of group g of activation row m
+// (blk = 2 h + j: lane half h, MFMA j).  Mpad is a multiple of 32.
+inline __host__ __device__ size_t act_chunk_offset(int g, int Mpad, int m, int blk) {
+    const int h = blk >> 1, j = blk & 1;
+    return ((((size_t)g * (Mpad / 32) + m / 32) * 2 + j) * 64 + (h * 32 + m % 32)) * 16;
+}
 
 inline __host__ __device__ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline __host__ __device__ size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
