@@ -25,9 +25,10 @@ if ROOT not in sys.path:
 INT8_MFMA_PEAK_TOPS = 5000.0       # MI355X dense INT8, published
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic of one GEMM launch at the headline shape from `rocprofv3 --pmc FETCH_SIZE` /
-# `--pmc WRITE_SIZE` (see profiles/), scaled by a copy kernel of known size; None until measured.
-GEMM_TRAFFIC_BYTES = None
+# HBM-side traffic of one GEMM launch at the headline shape from `rocprofv3 --pmc FETCH_SIZE` /
+# `--pmc WRITE_SIZE` (profiles/flux_mlp_up_kernel_stats.md), each scaled by what the same counter
+# reads for a plain 256 MiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0): 300.9 MB read + 113.2 MB written.
+GEMM_TRAFFIC_BYTES = 414.1e6
 
 
 class Hip:
@@ -89,6 +90,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="GEMM tile configuration id (0 = library default)")
     ap.add_argument("--breakdown", action="store_true", help="also time naive INT4 (no low-rank) and the unfused 4-kernel pipeline")
+    ap.add_argument("--pmc-run", action="store_true",
+                    help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a few forwards plus one plain copy of 256 MiB "
+                         "(the known-size kernel the counters are scaled by), no timing, no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X per box); run with --gpus 1. "
@@ -121,6 +125,18 @@ def main():
     hip = Hip()
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
+
+    if args.pmc_run:
+        S.svdq_forward_options(args.tile << S.OPT_TILE_SHIFT)
+        for i in range(4):
+            layer.forward(xs[i % nsets], out=ys[i % nsets], workspace=wss[i % nsets], stream=stream)
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print("pmc-run done: 4 forwards, 2 copies of 268435456 bytes", flush=True)
+        return
 
     def run(flags, steps, warmup, split):
         S.svdq_forward_options(flags | (args.tile << S.OPT_TILE_SHIFT))
@@ -177,7 +193,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel (W4A4 GEMM + up projection epilogue)",
                      "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
                      "note": "INT8 tera-ops/s: 2*M*N*K per launch / mean launch duration (HIP events on the launch stream)",
-                     "frac": gemm_tops / INT8_MFMA_PEAK_TOPS, "traffic": GEMM_TRAFFIC_BYTES},
+                     "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
+                     "traffic": GEMM_TRAFFIC_BYTES if case.name == "flux_mlp_up" else None},
     }
     if args.breakdown:
         naive = run(S.OPT_SKIP_LOWRANK, max(20, args.steps // 4), 5, split=False)
