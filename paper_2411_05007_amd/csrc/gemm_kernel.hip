@@ -47,13 +47,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kLdsRow = 80;      // 64 int8 + 16 pad: ds_read_b128 of consecutive rows hits distinct banks
-constexpr int kScaleRing = 4;    // scales live in their own small ring, read at the start of the iteration that uses them
+constexpr int kScaleRing = 2;    // the scales of a group live beside its codes: slot = parity of the group
 constexpr int kOutRow = 144;     // epilogue staging: 64 bf16 columns + 16 bytes pad per row
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+// round-to-nearest-even fp32 -> bf16 (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t bf16_rne_bits(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ uint32_t bf16_rne_pair(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 // A raw buffer descriptor over [base, base + bytes): loads take a per-thread byte offset in a VGPR and a
@@ -236,24 +239,28 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
 #define SVDQ_FMAC_BCAST(ACC, SX, TT, V) \
     asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:" #V " row_mask:0xf bank_mask:0xf" : "+v"(ACC) : "v"(SX), "v"(TT))
 
-    // one 32x32 sub-tile of one group: two MFMAs, then the rescale of their 16 partial sums per lane.
-    // The first FMAs of eight partial sums are issued before their second ones, so that no instruction
-    // waits for the result of the one just before it.
-    auto subtile = [&](const intx4 (&af)[2][2], const Scales &sc, int g, int r, int c) {
-        intx16 d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][0], bf[c][0], magic, 0, 0, 0);
-        d = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[r][1], bf[c][1], d, 0, 0, 0);
+    // One 32x32 sub-tile of one group is two chained MFMAs and the rescale of their 16 partial sums per
+    // lane.  The pieces are issued interleaved: between the two MFMAs of sub-tile t, and after them, runs
+    // the rescale of sub-tile t-1, whose sums are long complete, so a wavefront has independent vector work
+    // to issue while its own MFMA executes.  Within a rescale, the first FMAs of eight partial sums come
+    // before their second ones, so that no instruction waits for the result of the one just before it.
+    auto rescale_half = [&](const Scales &sc, const intx16 &d, int r, int c, auto half_c) {
+        constexpr int h = decltype(half_c)::value;
         const float2 sw = sc.sw[c];
         const float sx = sc.sx[r];
         floatx16 &a = acc[r][c];
         float t[8];
 #pragma unroll
-        for (int v = 0; v < 8; ++v) t[v] = __builtin_fmaf(__int_as_float(d[v]), sw.x, sw.y);
-        SVDQ_FMAC_BCAST(a[0], sx, t[0], 0); SVDQ_FMAC_BCAST(a[1], sx, t[1], 1); SVDQ_FMAC_BCAST(a[2], sx, t[2], 2); SVDQ_FMAC_BCAST(a[3], sx, t[3], 3);
-        SVDQ_FMAC_BCAST(a[4], sx, t[4], 4); SVDQ_FMAC_BCAST(a[5], sx, t[5], 5); SVDQ_FMAC_BCAST(a[6], sx, t[6], 6); SVDQ_FMAC_BCAST(a[7], sx, t[7], 7);
-#pragma unroll
-        for (int v = 0; v < 8; ++v) t[v] = __builtin_fmaf(__int_as_float(d[8 + v]), sw.x, sw.y);
-        SVDQ_FMAC_BCAST(a[8], sx, t[0], 8); SVDQ_FMAC_BCAST(a[9], sx, t[1], 9); SVDQ_FMAC_BCAST(a[10], sx, t[2], 10); SVDQ_FMAC_BCAST(a[11], sx, t[3], 11);
-        SVDQ_FMAC_BCAST(a[12], sx, t[4], 12); SVDQ_FMAC_BCAST(a[13], sx, t[5], 13); SVDQ_FMAC_BCAST(a[14], sx, t[6], 14); SVDQ_FMAC_BCAST(a[15], sx, t[7], 15);
+        for (int v = 0; v < 8; ++v) t[v] = __builtin_fmaf(__int_as_float(d[8 * h + v]), sw.x, sw.y);
+        if (h == 0) {
+            SVDQ_FMAC_BCAST(a[0], sx, t[0], 0); SVDQ_FMAC_BCAST(a[1], sx, t[1], 1); SVDQ_FMAC_BCAST(a[2], sx, t[2], 2); SVDQ_FMAC_BCAST(a[3], sx, t[3], 3);
+            SVDQ_FMAC_BCAST(a[4], sx, t[4], 4); SVDQ_FMAC_BCAST(a[5], sx, t[5], 5); SVDQ_FMAC_BCAST(a[6], sx, t[6], 6); SVDQ_FMAC_BCAST(a[7], sx, t[7], 7);
+        } else {
+            SVDQ_FMAC_BCAST(a[8], sx, t[0], 8); SVDQ_FMAC_BCAST(a[9], sx, t[1], 9); SVDQ_FMAC_BCAST(a[10], sx, t[2], 10); SVDQ_FMAC_BCAST(a[11], sx, t[3], 11);
+            SVDQ_FMAC_BCAST(a[12], sx, t[4], 12); SVDQ_FMAC_BCAST(a[13], sx, t[5], 13); SVDQ_FMAC_BCAST(a[14], sx, t[6], 14); SVDQ_FMAC_BCAST(a[15], sx, t[7], 15);
+        }
+    };
+    auto export_sums = [&](const intx16 &d, int g, int r, int c) {
         if (MODE == 1) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -264,6 +271,8 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
             }
         }
     };
+    using H0 = std::integral_constant<int, 0>;
+    using H1 = std::integral_constant<int, 1>;
 
     // ---- main loop over groups ----------------------------------------------------------------------
     // Iteration g multiplies group g.  Its activation fragments were loaded from memory one iteration
@@ -280,18 +289,46 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         constexpr int odd = decltype(odd_c)::value;      // g & 1
         constexpr int nxt = 1 - odd;
         load_a(afn, g + 1 < p.G ? g + 1 : p.G - 1);      // past the end: refetch the last group (unused)
-        read_scales(scn, (g + 1) & (kScaleRing - 1));    // written one iteration ago
-        subtile(af, sc, g, 0, 0);
+        read_scales(scn, nxt);                           // written one iteration ago
+        intx16 da, db;
+        // sub-tiles in the order (0,0) (1,0) (1,1) (0,1): the weight fragments of column block 0 fall free first
+        da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][0], bf[0][0], magic, 0, 0, 0);
+        da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][1], bf[0][1], da, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        subtile(af, sc, g, 1, 0);
+        db = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][0], bf[0][0], magic, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        rescale_half(sc, da, 0, 0, H0{});
+        __builtin_amdgcn_sched_barrier(0);
+        db = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][1], bf[0][1], db, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        rescale_half(sc, da, 0, 0, H1{});
+        export_sums(da, g, 0, 0);
         read_b(nxt, 0);
-        store_group(odd, (g + 2) & (kScaleRing - 1), q);
+        __builtin_amdgcn_sched_barrier(0);
+        da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][0], bf[1][0], magic, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        rescale_half(sc, db, 1, 0, H0{});
+        store_group(odd, odd, q);
         q = load_group(g + 4 < p.G ? g + 4 : p.G - 1);
         __builtin_amdgcn_sched_barrier(0);
-        subtile(af, sc, g, 1, 1);
+        da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][1], bf[1][1], da, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        subtile(af, sc, g, 0, 1);
+        rescale_half(sc, db, 1, 0, H1{});
+        export_sums(db, g, 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        db = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][0], bf[1][0], magic, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        rescale_half(sc, da, 1, 1, H0{});
+        __builtin_amdgcn_sched_barrier(0);
+        db = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][1], bf[1][1], db, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        rescale_half(sc, da, 1, 1, H1{});
+        export_sums(da, g, 1, 1);
         read_b(nxt, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        rescale_half(sc, db, 0, 1, H0{});
+        rescale_half(sc, db, 0, 1, H1{});
+        export_sums(db, g, 0, 1);
         __syncthreads();
     };
 
@@ -347,15 +384,15 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
             for (int r = 0; r < 2; ++r) {
                 const float4 h0 = hraw[buf][r][0], h1 = hraw[buf][r][1];
                 const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                uint32_t hi[8], lo[8];
+                uint32_t hi[4], lo[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    hi[e] = bf16_rne_bits(hv[e]);
-                    lo[e] = bf16_rne_bits(hv[e] - __uint_as_float(hi[e] << 16));
+                for (int e = 0; e < 4; ++e) {
+                    hi[e] = bf16_rne_pair(hv[2 * e], hv[2 * e + 1]);
+                    lo[e] = bf16_rne_pair(hv[2 * e] - __uint_as_float(hi[e] << 16), hv[2 * e + 1] - __uint_as_float(hi[e] & 0xffff0000u));
                 }
                 uint4 ph, pl;
-                ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16); ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
-                pl.x = lo[0] | (lo[1] << 16); pl.y = lo[2] | (lo[3] << 16); pl.z = lo[4] | (lo[5] << 16); pl.w = lo[6] | (lo[7] << 16);
+                ph.x = hi[0]; ph.y = hi[1]; ph.z = hi[2]; ph.w = hi[3];
+                pl.x = lo[0]; pl.y = lo[1]; pl.z = lo[2]; pl.w = lo[3];
                 hh[r] = __builtin_bit_cast(bf16x8, ph);
                 hl[r] = __builtin_bit_cast(bf16x8, pl);
             }
@@ -393,9 +430,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         for (int c = 0; c < 2; ++c) {
             const float b = c ? bias1 : bias0;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
+            for (int v = 0; v < 16; v += 2) {
                 const int row = 8 * (v >> 2) + 4 * lh + (v & 3);
-                *reinterpret_cast<uint16_t *>(ob + row * kOutRow + (c * 32 + li) * 2) = (uint16_t)bf16_rne_bits(acc[r][c][v] + b);
+                const uint32_t pr = bf16_rne_pair(acc[r][c][v] + b, acc[r][c][v + 1] + b);      // rows `row` and `row + 1`
+                *reinterpret_cast<uint16_t *>(ob + row * kOutRow + (c * 32 + li) * 2) = (uint16_t)pr;
+                *reinterpret_cast<uint16_t *>(ob + (row + 1) * kOutRow + (c * 32 + li) * 2) = (uint16_t)(pr >> 16);
             }
         }
         // 32 rows x 128 bytes = 256 chunks of 16 bytes: four per lane
