@@ -4,7 +4,9 @@
 // Details").
 //
 // Work split: one workgroup (4 or 8 wavefronts) owns 16 tokens and all of K; wavefront w takes a contiguous
-// run of G / W groups.  Inside a wavefront, lane l holds token (l % 16) and the 16 consecutive channels
+// run of G / W groups.  A 16-token slice gives the chip barely more than one workgroup per CU, so the kernel is
+// written for latency: every wavefront puts all its loads in flight at once, registers stay under 128 so two
+// workgroups fit a CU (one round of workgroups, not two), and the final reduction is spread over all threads.  Inside a wavefront, lane l holds token (l % 16) and the 16 consecutive channels
 // 16*(l/16) .. +15 of the current group, i.e. exactly the A-operand fragment of two
 // v_mfma_f32_16x16x32_bf16 steps, so the bf16 registers loaded from HBM feed the matrix core as they
 // are while the same registers are smoothed and quantized on the vector ALU.
@@ -25,21 +27,21 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// One group's inputs of one lane, fetched one group ahead of their use.
-template <int RBMAX, bool QUANT, bool PROJ>
-struct ActStage {
-    uint4 x0, x1;                 // 16 bf16 activations of the lane's token
-    float4 r[QUANT ? 4 : 1];      // their 16 reciprocal smoothing factors
-    // L1s fragments (k steps 0 and 1 for every 16-column block) travel with the stage only for small ranks;
-    // wider ones are fetched (from L2) right before their MFMAs, or the stages would not fit the registers
-    static constexpr bool kStageB = PROJ && RBMAX <= 2;
-    uint4 b[kStageB ? 2 * RBMAX : 1];
+// LDS of one workgroup: the smoothing factors of all its groups (fp32 [G][64], each wavefront stages and
+// reads only its own run of groups) followed by the per-wavefront partial H for the final reduction.
+template <int RBMAX, int WAVES>
+struct ActLds {
+    static constexpr int kRedRow = RBMAX * 16 + 1;
+    static __host__ __device__ size_t rinv_bytes(int G) { return (size_t)G * 64 * 4; }
+    static __host__ __device__ size_t red_bytes() { return (size_t)WAVES * 16 * kRedRow * 4; }
 };
 
 template <int RBMAX, int WAVES, bool QUANT, bool PROJ>
-__global__ __launch_bounds__(WAVES * 64, (RBMAX <= 2 && WAVES >= 8) ? 2 : 1) void act_kernel(ActParams p) {
+__global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) void act_kernel(ActParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char act_lds[];
+    using L = ActLds<RBMAX, WAVES>;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = lane & 15;
     const int blk = lane >> 4;
     const int m0 = blockIdx.x * 16;
@@ -52,51 +54,91 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 2 && WAVES >= 8) ? 2 : 1) voi
 #pragma unroll
     for (int c = 0; c < RBMAX; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const uint16_t *xrow = p.X + (size_t)mload * p.K + 16 * blk;
-    using Stage = ActStage<RBMAX, QUANT, PROJ>;
+    // wavefront w owns a contiguous run of groups, walked in steps of two; a run of odd length repeats its
+    // last group once more (it recomputes and rewrites the same codes and is kept out of the projection), so
+    // the loop body has no divergent or data-dependent control flow around its memory operations and the
+    // load/store counters can be waited on precisely
+    const int per = (p.G + WAVES - 1) / WAVES;
+    const int g0 = wave * per, g1 = (g0 + per < p.G) ? g0 + per : p.G;
+    const int npairs = g0 < g1 ? (g1 - g0 + 1) / 2 : 0;
 
-    auto fetch = [&](int g) {
-        Stage s;
+    const uint16_t *xrow = p.X + (size_t)mload * p.K + 16 * blk;
+    struct XStage { uint4 x0, x1; };                   // 16 bf16 activations of the lane's token
+    struct BStage { uint4 b[PROJ ? 2 * RBMAX : 1]; };  // L1s fragments: k steps 0 and 1 of every 16-column block
+    constexpr bool kStageB = PROJ && RBMAX <= 2;       // wider ranks fetch them (from L2) right before their MFMAs
+
+    auto clampg = [&](int g) { return g < g1 ? g : g1 - 1; };
+    auto fetch_x = [&](int g) {
+        XStage s;
         const uint4 *xp = reinterpret_cast<const uint4 *>(xrow + 64 * g);
         s.x0 = xp[0];
         s.x1 = xp[1];
-        if (QUANT) {
-            const float4 *rp = reinterpret_cast<const float4 *>(p.rinv + 64 * g + 16 * blk);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) s.r[i] = rp[i];
-        }
-        if (Stage::kStageB) {
+        return s;
+    };
+    auto fetch_b = [&](int g) {
+        BStage s;
+        if (kStageB) {
             const uint4 *lp = reinterpret_cast<const uint4 *>(p.l1s) + ((size_t)g * 2 * rb) * 64 + lane;
 #pragma unroll
             for (int c = 0; c < RBMAX; ++c) {
-                if (c < rb) {
-                    s.b[2 * c] = lp[(size_t)c * 64];
-                    s.b[2 * c + 1] = lp[(size_t)(rb + c) * 64];
-                }
+                const int cc = c < rb ? c : rb - 1;      // blocks past the rank repeat the last one (branch-free); their sums are dropped
+                s.b[2 * c] = lp[(size_t)cc * 64];
+                s.b[2 * c + 1] = lp[(size_t)(rb + cc) * 64];
             }
         }
         return s;
     };
 
-    auto process = [&](int g, const Stage &s) {
-        const uint4 x0 = s.x0, x1 = s.x1;
+    // All of a wavefront's memory traffic starts at once.  First the smoothing factors of its whole run
+    // (staged through LDS, so they cost no registers while they wait; issued first so that their arrival
+    // can be waited for without waiting for X), then the operands of its first two groups.
+    float *lrinv = reinterpret_cast<float *>(act_lds);
+    if (QUANT) {
+        // 64 lanes x 4 floats = the factors of four groups per load
+        for (int g = g0; g < g1; g += 4) {
+            const int k = 64 * g + 4 * lane;
+            if (k < 64 * g1) *reinterpret_cast<float4 *>(lrinv + k) = *reinterpret_cast<const float4 *>(p.rinv + k);
+        }
+        // only this wavefront reads what it wrote: no barrier, the LDS queue of a wavefront is in order
+    }
+    XStage xs0, xs1;      // X of the next even / odd step
+    BStage bs0, bs1;      // L1s fragments of the next even / odd step
+    if (npairs > 0) {
+        // same order as the refills inside the loop: the wait counts the compiler derives at the loop head
+        // are the more conservative of the two orders
+        bs0 = fetch_b(g0);
+        xs0 = fetch_x(g0);
+        __builtin_amdgcn_sched_barrier(0);
+        bs1 = fetch_b(clampg(g0 + 1));
+        xs1 = fetch_x(clampg(g0 + 1));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    auto project = [&](int g, const XStage &sx, const BStage &sb) {
+        const uint4 x0 = sx.x0, x1 = sx.x1;
         if (PROJ) {
             const uint4 *lp = reinterpret_cast<const uint4 *>(p.l1s) + ((size_t)g * 2 * rb) * 64 + lane;
 #pragma unroll
             for (int c = 0; c < RBMAX; ++c) {
-                if (c < rb) {
-                    const uint4 b0 = Stage::kStageB ? s.b[Stage::kStageB ? 2 * c : 0] : lp[(size_t)c * 64];
-                    const uint4 b1 = Stage::kStageB ? s.b[Stage::kStageB ? 2 * c + 1 : 0] : lp[(size_t)(rb + c) * 64];
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0),
-                                                                     __builtin_bit_cast(bf16x8, b0), acc[c], 0, 0, 0);
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1),
-                                                                     __builtin_bit_cast(bf16x8, b1), acc[c], 0, 0, 0);
-                }
+                const int cc = c < rb ? c : rb - 1;
+                const uint4 b0 = kStageB ? sb.b[kStageB ? 2 * c : 0] : lp[(size_t)cc * 64];
+                const uint4 b1 = kStageB ? sb.b[kStageB ? 2 * c + 1 : 0] : lp[(size_t)(rb + cc) * 64];
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0),
+                                                                 __builtin_bit_cast(bf16x8, b0), acc[c], 0, 0, 0);
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1),
+                                                                 __builtin_bit_cast(bf16x8, b1), acc[c], 0, 0, 0);
             }
         }
+    };
+    struct Smoothed { float v[QUANT ? 16 : 1]; };
+    // x^ = x * (1 / lambda): after this the raw X registers are dead and can take the next load
+    auto smooth = [&](int g, const XStage &sx) {
+        Smoothed o;
         if (QUANT) {
-            const float4 r0 = s.r[0], r1 = s.r[1], r2 = s.r[2], r3 = s.r[3];
-            float xh[16];
+            const uint4 x0 = sx.x0, x1 = sx.x1;
+            const float4 *rp = reinterpret_cast<const float4 *>(lrinv + 64 * g + 16 * blk);
+            const float4 r0 = rp[0], r1 = rp[1], r2 = rp[2], r3 = rp[3];
+            float (&xh)[QUANT ? 16 : 1] = o.v;
             xh[0] = bf16lo(x0.x) * r0.x;  xh[1] = bf16hi(x0.x) * r0.y;
             xh[2] = bf16lo(x0.y) * r0.z;  xh[3] = bf16hi(x0.y) * r0.w;
             xh[4] = bf16lo(x0.z) * r1.x;  xh[5] = bf16hi(x0.z) * r1.y;
@@ -105,6 +147,12 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 2 && WAVES >= 8) ? 2 : 1) voi
             xh[10] = bf16lo(x1.y) * r2.z; xh[11] = bf16hi(x1.y) * r2.w;
             xh[12] = bf16lo(x1.z) * r3.x; xh[13] = bf16hi(x1.z) * r3.y;
             xh[14] = bf16lo(x1.w) * r3.z; xh[15] = bf16hi(x1.w) * r3.w;
+        }
+        return o;
+    };
+    auto quantize = [&](int g, const Smoothed &sm) {
+        if (QUANT) {
+            const float (&xh)[QUANT ? 16 : 1] = sm.v;
             float amax = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(xh[e]));
@@ -115,75 +163,95 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 2 && WAVES >= 8) ? 2 : 1) voi
             s32 = fminf(s32, 65504.0f);
             const _Float16 sh = (_Float16)s32;
             const float sc = (float)sh;
-            const float rcp = sc > 0.f ? 1.0f / sc : 0.f;
-            // the codes leave as int8 = 16 * code, the operand form of the int8 MFMA in the GEMM, in the byte
-            // order in which the GEMM's nibble widening leaves the weight codes (act_byte_pos)
+            const float rcp_any = 1.0f / (sc > 0.f ? sc : 1.0f);     // branch-free: the division always runs
+            const float rcp = sc > 0.f ? rcp_any : 0.f;
+            // The codes leave as int8 = 16 * code, the operand form of the int8 MFMA in the GEMM, in the byte
+            // order in which the GEMM's nibble widening leaves the weight codes (act_byte_pos).
+            // q * 16 + 128 lies in [16, 240]: v_cvt_pk_u8_f32 converts it and drops it into its byte in one
+            // instruction, and flipping bit 7 of every byte afterwards takes the 128 off again (two's complement)
             uint32_t bytes[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float q = __builtin_rintf(xh[e] * rcp);
                 q = fminf(7.f, fmaxf(-7.f, q));
-                const uint32_t b = ((uint32_t)((int)q) & 0xfu) << 4;
                 const int pos = act_byte_pos(e);
-                bytes[pos >> 2] |= b << (8 * (pos & 3));
+                bytes[pos >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(q, 16.f, 128.f), pos & 3, bytes[pos >> 2]);
             }
-            if (valid) {
-                uint4 *cp = reinterpret_cast<uint4 *>(p.codes + act_chunk_offset(g, p.Mpad, m, blk));
-                *cp = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
-                if (blk == 0) p.sx[(size_t)g * p.Mpad + m] = __builtin_bit_cast(uint16_t, sh);
-            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bytes[i] ^= 0x80808080u;
+            // Unconditional stores: rows past M land in the padding rows of the workspace (it is sized for
+            // Mpad rows), and the four lanes that share a token and a group write the same scale.
+            uint4 *cp = reinterpret_cast<uint4 *>(p.codes + act_chunk_offset(g, p.Mpad, m, blk));
+            *cp = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
+            p.sx[(size_t)g * p.Mpad + m] = __builtin_bit_cast(uint16_t, sh);
         }
     };
 
-    // The loads of a wavefront's next group are in flight while the current one is quantized and
-    // multiplied.  Registers are kept under 128 so that two 8-wavefront workgroups share a CU: a
-    // 16-token slice gives the chip only ~1.1 workgroups per CU, and a second resident workgroup is
-    // what evens that out.
-    // wavefront w owns a contiguous run of groups, so it streams 16 row segments of several hundred bytes
-    const int per = (p.G + WAVES - 1) / WAVES;
-    const int g0 = wave * per, g1 = (g0 + per < p.G) ? g0 + per : p.G;
-    if (g0 < g1) {
-        Stage cur = fetch(g0);
-        for (int g = g0; g < g1; ++g) {
-            const Stage nxt = fetch(g + 1 < g1 ? g + 1 : g);
-            process(g, cur);
-            cur = nxt;
-        }
+    // One step = one group.  Its operands were requested two steps ago; right after the MFMAs have consumed
+    // them the same registers are refilled with the operands of the group two steps on, L1s fragments first:
+    // loads complete in order, so waiting for a step's fragments never waits for X requested after them.
+    auto step = [&](int g, bool real, XStage &xs, BStage &bs) {
+        XStage px = xs;
+        if (!real) px.x0 = px.x1 = make_uint4(0u, 0u, 0u, 0u);     // the repeated group of an odd run adds nothing to H
+        project(g, px, bs);
+        const Smoothed sm = smooth(g, xs);       // last use of the raw X registers: the refill below lands in them
+        __builtin_amdgcn_sched_barrier(0);       // keep the refills here, in this order, in the instruction stream
+        bs = fetch_b(clampg(g + 2));
+        xs = fetch_x(clampg(g + 2));
+        __builtin_amdgcn_sched_barrier(0);
+        quantize(g, sm);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int ip = 0; ip < npairs; ++ip) {
+        const int g = g0 + 2 * ip;
+        step(g, true, xs0, bs0);
+        step(clampg(g + 1), g + 1 < g1, xs1, bs1);
     }
 
     if (PROJ) {
-        // deterministic reduction of the wavefronts' partial H through LDS, in wavefront order
-        __shared__ float red[WAVES - 1][16][RBMAX * 16 + 1];
-        if (wave > 0) {
+        // Deterministic reduction of the wavefronts' partial H through LDS: every wavefront deposits its
+        // partial sums, then all threads share the 16 x rank outputs and add the partials in wavefront order.
+        float *red = reinterpret_cast<float *>(act_lds + L::rinv_bytes(QUANT ? p.G : 0));
 #pragma unroll
-            for (int c = 0; c < RBMAX; ++c)
-                if (c < rb)
+        for (int c = 0; c < RBMAX; ++c)
+            if (c < rb)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) red[wave - 1][4 * blk + v][16 * c + row] = acc[c][v];
-        }
+                for (int v = 0; v < 4; ++v) red[(wave * 16 + 4 * blk + v) * L::kRedRow + 16 * c + row] = acc[c][v];
         __syncthreads();
-        if (wave == 0) {
+        for (int idx = threadIdx.x; idx < 16 * p.rank; idx += WAVES * 64) {
+            const int r = idx / p.rank, col = idx - r * p.rank;
+            float h = 0.f;
 #pragma unroll
-            for (int c = 0; c < RBMAX; ++c)
-                if (c < rb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int r = 4 * blk + v, col = 16 * c + row;
-                        float h = acc[c][v];
-                        for (int w = 0; w < WAVES - 1; ++w) h += red[w][r][col];
-                        if (m0 + r < p.M) p.H[(size_t)(m0 + r) * p.rank + col] = h;
-                    }
+            for (int w = 0; w < WAVES; ++w) h += red[(w * 16 + r) * L::kRedRow + col];
+            if (m0 + r < p.M) p.H[(size_t)(m0 + r) * p.rank + col] = h;
         }
     }
 }
 
 template <int RBMAX, int WAVES>
 hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
+    using L = ActLds<RBMAX, WAVES>;
     const dim3 grid((p.M + 15) / 16), block(WAVES * 64);
     const bool q = flags & 1, pr = (flags & 2) && p.rank > 0;
-    if (q && pr) hipLaunchKernelGGL((act_kernel<RBMAX, WAVES, true, true>), grid, block, 0, stream, p);
-    else if (q) hipLaunchKernelGGL((act_kernel<1, WAVES, true, false>), grid, block, 0, stream, p);
-    else if (pr) hipLaunchKernelGGL((act_kernel<RBMAX, WAVES, false, true>), grid, block, 0, stream, p);
+    const size_t lds = (q ? L::rinv_bytes(p.G) : 0) + (pr ? L::red_bytes() : 0);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    hipError_t e = hipSuccess;
+    if (q && pr) {
+        auto k = act_kernel<RBMAX, WAVES, true, true>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k, grid, block, lds, stream, p);
+    } else if (q) {
+        auto k = act_kernel<1, WAVES, true, false>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k, grid, block, lds, stream, p);
+    } else if (pr) {
+        auto k = act_kernel<RBMAX, WAVES, false, true>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k, grid, block, lds, stream, p);
+    }
     return hipGetLastError();
 }
 
@@ -210,8 +278,8 @@ hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
     // wavefronts per 16-token slice: more of them when K is long enough to give each a few groups
     const bool wide = p.G >= 32;
-    if (p.rank <= 32) return wide ? launch_rb<2, 16>(p, flags, stream) : launch_rb<2, 4>(p, flags, stream);
-    if (p.rank <= 64) return wide ? launch_rb<4, 16>(p, flags, stream) : launch_rb<4, 4>(p, flags, stream);
+    if (p.rank <= 32) return wide ? launch_rb<2, 8>(p, flags, stream) : launch_rb<2, 4>(p, flags, stream);
+    if (p.rank <= 64) return wide ? launch_rb<4, 8>(p, flags, stream) : launch_rb<4, 4>(p, flags, stream);
     if (p.rank <= 128) return launch_rb<8, 4>(p, flags, stream);
     return launch_rb<16, 4>(p, flags, stream);
 }
