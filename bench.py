@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side traffic of one GEMM launch at the headline shape from `rocprofv3 --pmc FETCH_SIZE` /
 # `--pmc WRITE_SIZE` (profiles/flux_mlp_up_kernel_stats.md), each scaled by what the same counter
 # reads for a plain 256 MiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0): 300.9 MB read + 113.2 MB written.
-GEMM_TRAFFIC_BYTES = 414.1e6
+GEMM_TRAFFIC_BYTES = 417.8e6
 
 
 class Hip:
@@ -84,8 +84,8 @@ def cpu_baseline(case, L, prep_canon, rows=768):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=100, help="untimed steps; the clocks need tens of milliseconds of load to settle")
     ap.add_argument("--case", default="flux_mlp_up", help="layer name from paper_2411_05007_amd.inputs (default: the metric shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="GEMM tile configuration id (0 = library default)")

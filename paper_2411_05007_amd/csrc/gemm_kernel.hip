@@ -495,7 +495,12 @@ __global__ __launch_bounds__(256) void upproj_kernel(const float *H, const uint1
 
 hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
-    if (tile == 0) tile = 2;     // two independent 128x128 workgroups per CU measured fastest on the large-M shapes
+    if (tile == 0) {
+        // Two independent 128x128 workgroups per CU measured fastest on the large shapes.  A launch with fewer than
+        // two such workgroups per CU leaves SIMDs empty, and halving the tile height there measured 2-6 % faster.
+        const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+        tile = tiles128 < 512 ? 4 : 2;
+    }
     switch (tile) {
         case 1: return launch_tile<256, 128>(p, stream);
         case 2: return launch_tile<128, 128>(p, stream);
