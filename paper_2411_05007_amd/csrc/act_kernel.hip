@@ -5,11 +5,16 @@
 //
 // Work split: one workgroup (4 or 8 wavefronts) owns 16 tokens and all of K; wavefront w takes a contiguous
 // run of G / W groups.  A 16-token slice gives the chip barely more than one workgroup per CU, so the kernel is
-// written for latency: every wavefront puts all its loads in flight at once, registers stay under 128 so two
-// workgroups fit a CU (one round of workgroups, not two), and the final reduction is spread over all threads.  Inside a wavefront, lane l holds token (l % 16) and the 16 consecutive channels
-// 16*(l/16) .. +15 of the current group, i.e. exactly the A-operand fragment of two
-// v_mfma_f32_16x16x32_bf16 steps, so the bf16 registers loaded from HBM feed the matrix core as they
-// are while the same registers are smoothed and quantized on the vector ALU.
+// written for latency: every wavefront keeps the loads of two groups in flight, registers stay under 128 so
+// two workgroups fit a CU (one round of workgroups, not two), and the final reduction is spread over all
+// threads.
+// Two lane maps are in play.  Memory is read with lane l -> token l/8 (and l/8 + 8 for the second load),
+// channels 8*(l%8) .. +7 of the group: every load instruction then covers whole 128-byte lines, which the
+// memory pipeline serves at twice the rate of the 16-lines-by-halves pattern that the matrix core's operand
+// map (lane l -> token l%16, channels 16*(l/16) .. +15) would give.  Smoothing and quantization run in the
+// load map (a group's maximum is a reduction over 8 neighbouring lanes, done with DPP); for the projection
+// the raw bf16 registers take one trip through a wavefront-private LDS block to arrive in the operand map of
+// v_mfma_f32_16x16x32_bf16.
 // The k order inside a group is permuted relative to the instruction's nominal order; l1s is stored
 // offline in the matching order, and a dot product does not care.
 #include <hip/hip_runtime.h>
@@ -28,13 +33,24 @@ __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w <
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 // LDS of one workgroup: the smoothing factors of all its groups (fp32 [G][64], each wavefront stages and
-// reads only its own run of groups) followed by the per-wavefront partial H for the final reduction.
+// reads only its own run of groups) followed by one private block per wavefront, used first to turn X from
+// the load map into the MFMA operand map and at the end for the wavefront's partial H.
 template <int RBMAX, int WAVES>
 struct ActLds {
     static constexpr int kRedRow = RBMAX * 16 + 1;
+    static constexpr int kXRow = 144;      // 128 B of one token's group + 16: the 16 rows of an operand read fall on distinct banks
+    static constexpr int kWaveBytes = (16 * kXRow > 16 * kRedRow * 4) ? 16 * kXRow : 16 * kRedRow * 4;
     static __host__ __device__ size_t rinv_bytes(int G) { return (size_t)G * 64 * 4; }
-    static __host__ __device__ size_t red_bytes() { return (size_t)WAVES * 16 * kRedRow * 4; }
+    static __host__ __device__ size_t wave_bytes() { return (size_t)WAVES * kWaveBytes; }
 };
+
+// maximum over the 8 lanes l%8 = 0..7 that share a token in the load map
+__device__ __forceinline__ float max_over_8_lanes(float a) {
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true)));    // quad_perm [1,0,3,2]
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4E, 0xf, 0xf, true)));    // quad_perm [2,3,0,1]
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x141, 0xf, 0xf, true)));   // row_half_mirror
+    return a;
+}
 
 template <int RBMAX, int WAVES, bool QUANT, bool PROJ>
 __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) void act_kernel(ActParams p) {
@@ -42,12 +58,10 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
     using L = ActLds<RBMAX, WAVES>;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int row = lane & 15;
-    const int blk = lane >> 4;
+    const int row = lane & 15, blk = lane >> 4;      // MFMA operand / accumulator map
+    const int r8 = lane >> 3, c8 = lane & 7;         // load map: tokens r8 and r8 + 8, channels 8*c8 .. +7
     const int m0 = blockIdx.x * 16;
-    const int m = m0 + row;
-    const bool valid = m < p.M;
-    const int mload = valid ? m : p.M - 1;
+    const int ma = m0 + r8, mb = ma + 8;
     const int rb = p.rank / 16;
 
     floatx4 acc[RBMAX];
@@ -62,17 +76,18 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
     const int g0 = wave * per, g1 = (g0 + per < p.G) ? g0 + per : p.G;
     const int npairs = g0 < g1 ? (g1 - g0 + 1) / 2 : 0;
 
-    const uint16_t *xrow = p.X + (size_t)mload * p.K + 16 * blk;
-    struct XStage { uint4 x0, x1; };                   // 16 bf16 activations of the lane's token
+    // rows past M read the last row; what they produce lands in padding rows and is never used
+    const uint16_t *xa = p.X + (size_t)(ma < p.M ? ma : p.M - 1) * p.K + 8 * c8;
+    const uint16_t *xb = p.X + (size_t)(mb < p.M ? mb : p.M - 1) * p.K + 8 * c8;
+    struct XStage { uint4 x0, x1; };                   // 8 bf16 activations of token r8 and of token r8 + 8
     struct BStage { uint4 b[PROJ ? 2 * RBMAX : 1]; };  // L1s fragments: k steps 0 and 1 of every 16-column block
     constexpr bool kStageB = PROJ && RBMAX <= 2;       // wider ranks fetch them (from L2) right before their MFMAs
 
     auto clampg = [&](int g) { return g < g1 ? g : g1 - 1; };
     auto fetch_x = [&](int g) {
         XStage s;
-        const uint4 *xp = reinterpret_cast<const uint4 *>(xrow + 64 * g);
-        s.x0 = xp[0];
-        s.x1 = xp[1];
+        s.x0 = *reinterpret_cast<const uint4 *>(xa + 64 * g);
+        s.x1 = *reinterpret_cast<const uint4 *>(xb + 64 * g);
         return s;
     };
     auto fetch_b = [&](int g) {
@@ -89,23 +104,25 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
         return s;
     };
 
-    // All of a wavefront's memory traffic starts at once.  First the smoothing factors of its whole run
-    // (staged through LDS, so they cost no registers while they wait; issued first so that their arrival
-    // can be waited for without waiting for X), then the operands of its first two groups.
+    // All of a wavefront's memory traffic starts at once.  First the smoothing factors of its run (64 lanes
+    // x 4 floats = the factors of four groups per load; the first eight groups wait in registers), then the
+    // operands of its first two groups; the factors are the older loads, so dropping them into LDS (where
+    // they cost no registers) waits for them alone.
     float *lrinv = reinterpret_cast<float *>(act_lds);
-    if (QUANT) {
-        // 64 lanes x 4 floats = the factors of four groups per load
-        for (int g = g0; g < g1; g += 4) {
-            const int k = 64 * g + 4 * lane;
-            if (k < 64 * g1) *reinterpret_cast<float4 *>(lrinv + k) = *reinterpret_cast<const float4 *>(p.rinv + k);
-        }
-        // only this wavefront reads what it wrote: no barrier, the LDS queue of a wavefront is in order
+    unsigned char *wlds = act_lds + L::rinv_bytes(QUANT ? p.G : 0) + (size_t)wave * L::kWaveBytes;
+    const int kr0 = 64 * g0 + 4 * lane, kr1 = kr0 + 256, kend = 64 * g1;
+    float4 rv0 = make_float4(0.f, 0.f, 0.f, 0.f), rv1 = rv0;
+    if (QUANT && npairs > 0) {
+        // out-of-run lanes read the run's first factors again (an address that is always valid) and drop them
+        rv0 = *reinterpret_cast<const float4 *>(p.rinv + (kr0 < kend ? kr0 : 64 * g0));
+        rv1 = *reinterpret_cast<const float4 *>(p.rinv + (kr1 < kend ? kr1 : 64 * g0));
     }
     XStage xs0, xs1;      // X of the next even / odd step
     BStage bs0, bs1;      // L1s fragments of the next even / odd step
     if (npairs > 0) {
         // same order as the refills inside the loop: the wait counts the compiler derives at the loop head
         // are the more conservative of the two orders
+        __builtin_amdgcn_sched_barrier(0);
         bs0 = fetch_b(g0);
         xs0 = fetch_x(g0);
         __builtin_amdgcn_sched_barrier(0);
@@ -113,10 +130,26 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
         xs1 = fetch_x(clampg(g0 + 1));
         __builtin_amdgcn_sched_barrier(0);
     }
+    if (QUANT && npairs > 0) {
+        // only this wavefront reads what it writes here: no barrier, the LDS queue of a wavefront is in order
+        if (kr0 < kend) *reinterpret_cast<float4 *>(lrinv + kr0) = rv0;
+        if (kr1 < kend) *reinterpret_cast<float4 *>(lrinv + kr1) = rv1;
+        for (int k = kr1 + 256; k < kend; k += 256)      // runs longer than eight groups: the rest, one load at a time
+            *reinterpret_cast<float4 *>(lrinv + k) = *reinterpret_cast<const float4 *>(p.rinv + k);
+    }
 
-    auto project = [&](int g, const XStage &sx, const BStage &sb) {
-        const uint4 x0 = sx.x0, x1 = sx.x1;
+    // X of one group, load map -> LDS -> operand map: lane (row, blk) picks up channels 16*blk .. +15 of token row
+    auto to_lds = [&](const XStage &sx) {
         if (PROJ) {
+            *reinterpret_cast<uint4 *>(wlds + r8 * L::kXRow + 16 * c8) = sx.x0;
+            *reinterpret_cast<uint4 *>(wlds + (r8 + 8) * L::kXRow + 16 * c8) = sx.x1;
+        }
+    };
+    auto project = [&](int g, bool real, const BStage &sb) {
+        if (PROJ) {
+            const uint4 *ap = reinterpret_cast<const uint4 *>(wlds + row * L::kXRow + 32 * blk);
+            uint4 x0 = ap[0], x1 = ap[1];
+            if (!real) x0 = x1 = make_uint4(0u, 0u, 0u, 0u);     // the repeated group of an odd run adds nothing to H
             const uint4 *lp = reinterpret_cast<const uint4 *>(p.l1s) + ((size_t)g * 2 * rb) * 64 + lane;
 #pragma unroll
             for (int c = 0; c < RBMAX; ++c) {
@@ -130,71 +163,77 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
             }
         }
     };
-    struct Smoothed { float v[QUANT ? 16 : 1]; };
+    struct Smoothed { float a[QUANT ? 8 : 1], b[QUANT ? 8 : 1]; };     // tokens r8 and r8 + 8
     // x^ = x * (1 / lambda): after this the raw X registers are dead and can take the next load
     auto smooth = [&](int g, const XStage &sx) {
         Smoothed o;
         if (QUANT) {
-            const uint4 x0 = sx.x0, x1 = sx.x1;
-            const float4 *rp = reinterpret_cast<const float4 *>(lrinv + 64 * g + 16 * blk);
-            const float4 r0 = rp[0], r1 = rp[1], r2 = rp[2], r3 = rp[3];
-            float (&xh)[QUANT ? 16 : 1] = o.v;
-            xh[0] = bf16lo(x0.x) * r0.x;  xh[1] = bf16hi(x0.x) * r0.y;
-            xh[2] = bf16lo(x0.y) * r0.z;  xh[3] = bf16hi(x0.y) * r0.w;
-            xh[4] = bf16lo(x0.z) * r1.x;  xh[5] = bf16hi(x0.z) * r1.y;
-            xh[6] = bf16lo(x0.w) * r1.z;  xh[7] = bf16hi(x0.w) * r1.w;
-            xh[8] = bf16lo(x1.x) * r2.x;  xh[9] = bf16hi(x1.x) * r2.y;
-            xh[10] = bf16lo(x1.y) * r2.z; xh[11] = bf16hi(x1.y) * r2.w;
-            xh[12] = bf16lo(x1.z) * r3.x; xh[13] = bf16hi(x1.z) * r3.y;
-            xh[14] = bf16lo(x1.w) * r3.z; xh[15] = bf16hi(x1.w) * r3.w;
+            const float4 *rp = reinterpret_cast<const float4 *>(lrinv + 64 * g + 8 * c8);
+            const float4 r0 = rp[0], r1 = rp[1];
+            const float r[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+            const uint32_t wa[4] = {sx.x0.x, sx.x0.y, sx.x0.z, sx.x0.w};
+            const uint32_t wb[4] = {sx.x1.x, sx.x1.y, sx.x1.z, sx.x1.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                o.a[2 * i] = bf16lo(wa[i]) * r[2 * i];
+                o.a[2 * i + 1] = bf16hi(wa[i]) * r[2 * i + 1];
+                o.b[2 * i] = bf16lo(wb[i]) * r[2 * i];
+                o.b[2 * i + 1] = bf16hi(wb[i]) * r[2 * i + 1];
+            }
         }
         return o;
     };
+    // Eq. 1 for the 8 channels this lane holds of one token's group: s = max|x| / q_max over the whole group
+    // (8 lanes), stored as fp16; codes from x * (1/s).
+    // The codes leave as int8 = 16 * code, the operand form of the int8 MFMA in the GEMM, in the byte order in
+    // which the GEMM's nibble widening leaves the weight codes (act_byte_pos: a lane's 8 channels are one half
+    // of a 16-byte chunk, channel i at byte 4*(i%2) + i/2 of the half).
+    // q * 16 + 128 lies in [16, 240]: v_cvt_pk_u8_f32 converts it and drops it into its byte in one
+    // instruction, and flipping bit 7 of every byte afterwards takes the 128 off again (two's complement)
+    auto encode = [&](const float (&xh)[QUANT ? 8 : 1], uint2 &bytes, uint16_t &sbits) {
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xh[e]));
+        amax = max_over_8_lanes(amax);
+        float s32 = amax / 7.0f;
+        s32 = fminf(s32, 65504.0f);
+        const _Float16 sh = (_Float16)s32;
+        const float sc = (float)sh;
+        const float rcp_any = 1.0f / (sc > 0.f ? sc : 1.0f);     // branch-free: the division always runs
+        const float rcp = sc > 0.f ? rcp_any : 0.f;
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float q = __builtin_rintf(xh[e] * rcp);
+            q = fminf(7.f, fmaxf(-7.f, q));
+            w[e & 1] = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(q, 16.f, 128.f), e >> 1, w[e & 1]);
+        }
+        bytes = make_uint2(w[0] ^ 0x80808080u, w[1] ^ 0x80808080u);
+        sbits = __builtin_bit_cast(uint16_t, sh);
+    };
     auto quantize = [&](int g, const Smoothed &sm) {
         if (QUANT) {
-            const float (&xh)[QUANT ? 16 : 1] = sm.v;
-            float amax = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(xh[e]));
-            amax = fmaxf(amax, __shfl_xor(amax, 16, 64));
-            amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
-            // Eq. 1: s = max|x| / q_max, stored as fp16; codes from x * (1/s)
-            float s32 = amax / 7.0f;
-            s32 = fminf(s32, 65504.0f);
-            const _Float16 sh = (_Float16)s32;
-            const float sc = (float)sh;
-            const float rcp_any = 1.0f / (sc > 0.f ? sc : 1.0f);     // branch-free: the division always runs
-            const float rcp = sc > 0.f ? rcp_any : 0.f;
-            // The codes leave as int8 = 16 * code, the operand form of the int8 MFMA in the GEMM, in the byte
-            // order in which the GEMM's nibble widening leaves the weight codes (act_byte_pos).
-            // q * 16 + 128 lies in [16, 240]: v_cvt_pk_u8_f32 converts it and drops it into its byte in one
-            // instruction, and flipping bit 7 of every byte afterwards takes the 128 off again (two's complement)
-            uint32_t bytes[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float q = __builtin_rintf(xh[e] * rcp);
-                q = fminf(7.f, fmaxf(-7.f, q));
-                const int pos = act_byte_pos(e);
-                bytes[pos >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(q, 16.f, 128.f), pos & 3, bytes[pos >> 2]);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) bytes[i] ^= 0x80808080u;
+            uint2 ca, cb;
+            uint16_t sa, sb;
+            encode(sm.a, ca, sa);
+            encode(sm.b, cb, sb);
             // Unconditional stores: rows past M land in the padding rows of the workspace (it is sized for
-            // Mpad rows), and the four lanes that share a token and a group write the same scale.
-            uint4 *cp = reinterpret_cast<uint4 *>(p.codes + act_chunk_offset(g, p.Mpad, m, blk));
-            *cp = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
-            p.sx[(size_t)g * p.Mpad + m] = __builtin_bit_cast(uint16_t, sh);
+            // Mpad rows); each store instruction fills four whole 128-byte lines.  Even lanes write the
+            // scale of token r8, odd lanes that of token r8 + 8 (four lanes each, the same value).
+            *reinterpret_cast<uint2 *>(p.codes + act_chunk_offset(g, p.Mpad, ma, c8 >> 1) + 8 * (c8 & 1)) = ca;
+            *reinterpret_cast<uint2 *>(p.codes + act_chunk_offset(g, p.Mpad, mb, c8 >> 1) + 8 * (c8 & 1)) = cb;
+            p.sx[(size_t)g * p.Mpad + ((c8 & 1) ? mb : ma)] = (c8 & 1) ? sb : sa;
         }
     };
 
-    // One step = one group.  Its operands were requested two steps ago; right after the MFMAs have consumed
-    // them the same registers are refilled with the operands of the group two steps on, L1s fragments first:
-    // loads complete in order, so waiting for a step's fragments never waits for X requested after them.
+    // One step = one group.  Its operands were requested two steps ago; as soon as the raw X registers have
+    // been smoothed and dropped into LDS, and the MFMAs have consumed the L1s fragments, the same registers
+    // are refilled with the operands of the group two steps on, L1s fragments first: loads complete in order,
+    // so waiting for a step's fragments never waits for X requested after them.
     auto step = [&](int g, bool real, XStage &xs, BStage &bs) {
-        XStage px = xs;
-        if (!real) px.x0 = px.x1 = make_uint4(0u, 0u, 0u, 0u);     // the repeated group of an odd run adds nothing to H
-        project(g, px, bs);
+        to_lds(xs);
         const Smoothed sm = smooth(g, xs);       // last use of the raw X registers: the refill below lands in them
+        project(g, real, bs);
         __builtin_amdgcn_sched_barrier(0);       // keep the refills here, in this order, in the instruction stream
         bs = fetch_b(clampg(g + 2));
         xs = fetch_x(clampg(g + 2));
@@ -210,19 +249,21 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
 
     if (PROJ) {
         // Deterministic reduction of the wavefronts' partial H through LDS: every wavefront deposits its
-        // partial sums, then all threads share the 16 x rank outputs and add the partials in wavefront order.
-        float *red = reinterpret_cast<float *>(act_lds + L::rinv_bytes(QUANT ? p.G : 0));
+        // partial sums in its own block, then all threads share the 16 x rank outputs and add the partials
+        // in wavefront order.
+        float *red = reinterpret_cast<float *>(wlds);
 #pragma unroll
         for (int c = 0; c < RBMAX; ++c)
             if (c < rb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) red[(wave * 16 + 4 * blk + v) * L::kRedRow + 16 * c + row] = acc[c][v];
+                for (int v = 0; v < 4; ++v) red[(4 * blk + v) * L::kRedRow + 16 * c + row] = acc[c][v];
         __syncthreads();
+        const unsigned char *all = act_lds + L::rinv_bytes(QUANT ? p.G : 0);
         for (int idx = threadIdx.x; idx < 16 * p.rank; idx += WAVES * 64) {
             const int r = idx / p.rank, col = idx - r * p.rank;
             float h = 0.f;
 #pragma unroll
-            for (int w = 0; w < WAVES; ++w) h += red[(w * 16 + r) * L::kRedRow + col];
+            for (int w = 0; w < WAVES; ++w) h += reinterpret_cast<const float *>(all + (size_t)w * L::kWaveBytes)[r * L::kRedRow + col];
             if (m0 + r < p.M) p.H[(size_t)(m0 + r) * p.rank + col] = h;
         }
     }
@@ -233,7 +274,7 @@ hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     using L = ActLds<RBMAX, WAVES>;
     const dim3 grid((p.M + 15) / 16), block(WAVES * 64);
     const bool q = flags & 1, pr = (flags & 2) && p.rank > 0;
-    const size_t lds = (q ? L::rinv_bytes(p.G) : 0) + (pr ? L::red_bytes() : 0);
+    const size_t lds = (q ? L::rinv_bytes(p.G) : 0) + (pr ? L::wave_bytes() : 0);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
     if (q && pr) {

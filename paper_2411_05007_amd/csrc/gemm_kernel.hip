@@ -334,10 +334,83 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
 
     const int glast = p.G - 1;
     load_a(afe, 0);
-    store_group(0, 0, load_group(0));
-    store_group(1, 1, load_group(1 < glast ? 1 : glast));
-    qe = load_group(2 < glast ? 2 : glast);
-    qo = load_group(3 < glast ? 3 : glast);
+    {
+        const Staged q0 = load_group(0), q1 = load_group(1 < glast ? 1 : glast);
+        qe = load_group(2 < glast ? 2 : glast);
+        qo = load_group(3 < glast ? 3 : glast);
+        __builtin_amdgcn_sched_barrier(0);      // everything the main loop needs first is requested before H and L2
+        // ---- low-rank up projection on the matrix core: the accumulators START as H L2 ----------------
+        // bf16 MFMAs with the fp32 accumulator tile as C.  H is fp32; it is split into bf16 hi + lo parts (two
+        // MFMAs) so the 16-bit branch loses nothing against an fp32 evaluation.  The loads of rank step k+1 are
+        // in flight while step k is multiplied.  Doing this before the main loop instead of after it puts the
+        // memory round trip of H and L2 under the one the first groups need anyway.
+        const bool lowrank = MODE == 0 && p.rank > 0;
+        {
+            const int ksteps = p.rank / 16;
+            float4 hraw[2][2][2];
+            uint4 braw[2][2];
+            auto load_step = [&](int buf, int ks) {
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    int row = gm0 + wm0 + r * 32 + li;
+                    row = row < p.M ? row : p.M - 1;
+                    const float4 *hp = reinterpret_cast<const float4 *>(p.H + (size_t)row * p.rank + ks * 16 + 8 * lh);
+                    hraw[buf][r][0] = hp[0];
+                    hraw[buf][r][1] = hp[1];
+                }
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const int col = gn0 + wn0 + c * 32 + li;        // < Npad
+                    braw[buf][c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
+                }
+            };
+            auto compute_step = [&](int buf) {
+                bf16x8 hh[2], hl[2];
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const float4 h0 = hraw[buf][r][0], h1 = hraw[buf][r][1];
+                    const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+                    uint32_t hi[4], lo[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        hi[e] = bf16_rne_pair(hv[2 * e], hv[2 * e + 1]);
+                        lo[e] = bf16_rne_pair(hv[2 * e] - __uint_as_float(hi[e] << 16), hv[2 * e + 1] - __uint_as_float(hi[e] & 0xffff0000u));
+                    }
+                    uint4 ph, pl;
+                    ph.x = hi[0]; ph.y = hi[1]; ph.z = hi[2]; ph.w = hi[3];
+                    pl.x = lo[0]; pl.y = lo[1]; pl.z = lo[2]; pl.w = lo[3];
+                    hh[r] = __builtin_bit_cast(bf16x8, ph);
+                    hl[r] = __builtin_bit_cast(bf16x8, pl);
+                }
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const bf16x8 bl = __builtin_bit_cast(bf16x8, braw[buf][c]);
+#pragma unroll
+                    for (int r = 0; r < 2; ++r) {
+                        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hh[r], bl, acc[r][c], 0, 0, 0);
+                        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hl[r], bl, acc[r][c], 0, 0, 0);
+                    }
+                }
+            };
+            if (lowrank) {
+                load_step(0, 0);
+                if (1 < ksteps) load_step(1, 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            store_group(0, 0, q0);      // the oldest loads: this waits for them alone
+            store_group(1, 1, q1);
+            if (lowrank) {
+                for (int ks = 0; ks < ksteps; ks += 2) {
+                    compute_step(0);
+                    if (ks + 1 < ksteps) {
+                        if (ks + 2 < ksteps) load_step(0, ks + 2);
+                        compute_step(1);
+                        if (ks + 3 < ksteps) load_step(1, ks + 3);
+                    }
+                }
+            }
+        }
+    }
     __syncthreads();
     read_b(0, 0); read_b(0, 1);
     read_scales(sce, 0);
@@ -355,68 +428,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
 
     if (MODE == 1) return;   // the window export writes no Y
 
-    // ---- epilogue: low-rank up projection on the matrix core, bias, bf16 store -----------------
-    // acc += H L2 as bf16 MFMAs with the fp32 accumulator tile as C.  H is fp32; it is split into
-    // bf16 hi + lo parts (two MFMAs) so the 16-bit branch loses nothing against an fp32 evaluation.
-    // The loads of rank step k+1 are in flight while step k is multiplied.
-    if (p.rank > 0) {
-        const int ksteps = p.rank / 16;
-        float4 hraw[2][2][2];
-        uint4 braw[2][2];
-        auto load_step = [&](int buf, int ks) {
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                int row = gm0 + wm0 + r * 32 + li;
-                row = row < p.M ? row : p.M - 1;
-                const float4 *hp = reinterpret_cast<const float4 *>(p.H + (size_t)row * p.rank + ks * 16 + 8 * lh);
-                hraw[buf][r][0] = hp[0];
-                hraw[buf][r][1] = hp[1];
-            }
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int col = gn0 + wn0 + c * 32 + li;        // < Npad
-                braw[buf][c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
-            }
-        };
-        auto compute_step = [&](int buf) {
-            bf16x8 hh[2], hl[2];
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const float4 h0 = hraw[buf][r][0], h1 = hraw[buf][r][1];
-                const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                uint32_t hi[4], lo[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    hi[e] = bf16_rne_pair(hv[2 * e], hv[2 * e + 1]);
-                    lo[e] = bf16_rne_pair(hv[2 * e] - __uint_as_float(hi[e] << 16), hv[2 * e + 1] - __uint_as_float(hi[e] & 0xffff0000u));
-                }
-                uint4 ph, pl;
-                ph.x = hi[0]; ph.y = hi[1]; ph.z = hi[2]; ph.w = hi[3];
-                pl.x = lo[0]; pl.y = lo[1]; pl.z = lo[2]; pl.w = lo[3];
-                hh[r] = __builtin_bit_cast(bf16x8, ph);
-                hl[r] = __builtin_bit_cast(bf16x8, pl);
-            }
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const bf16x8 bl = __builtin_bit_cast(bf16x8, braw[buf][c]);
-#pragma unroll
-                for (int r = 0; r < 2; ++r) {
-                    acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hh[r], bl, acc[r][c], 0, 0, 0);
-                    acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hl[r], bl, acc[r][c], 0, 0, 0);
-                }
-            }
-        };
-        load_step(0, 0);
-        for (int ks = 0; ks < ksteps; ks += 2) {
-            if (ks + 1 < ksteps) load_step(1, ks + 1);
-            compute_step(0);
-            if (ks + 1 < ksteps) {
-                if (ks + 2 < ksteps) load_step(0, ks + 2);
-                compute_step(1);
-            }
-        }
-    }
-
+    // ---- epilogue: bias, bf16 store -----------------------------------------------------------------
     // Bias, one rounding to bf16, and the store.  A lane holds one column and sixteen rows of a 32x32
     // block; each wavefront turns its tile, 32 rows at a time, through a private LDS block so that a lane
     // stores 16 bytes of one row and a store instruction writes whole 128-byte lines.
