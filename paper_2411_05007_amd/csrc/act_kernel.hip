@@ -321,8 +321,8 @@ hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
     const bool wide = p.G >= 32;
     if (p.rank <= 32) return wide ? launch_rb<2, 8>(p, flags, stream) : launch_rb<2, 4>(p, flags, stream);
     if (p.rank <= 64) return wide ? launch_rb<4, 8>(p, flags, stream) : launch_rb<4, 4>(p, flags, stream);
-    if (p.rank <= 128) return launch_rb<8, 4>(p, flags, stream);
-    return launch_rb<16, 4>(p, flags, stream);
+    if (p.rank <= 128) return wide ? launch_rb<8, 8>(p, flags, stream) : launch_rb<8, 4>(p, flags, stream);
+    return wide ? launch_rb<16, 8>(p, flags, stream) : launch_rb<16, 4>(p, flags, stream);
 }
 
 hipError_t launch_debug_act(const DebugActParams &p, hipStream_t stream) {
