@@ -107,8 +107,10 @@ typedef struct {
     svdq_shape shape;
 } svdq_layer_dev;
 
-/* Bytes of device scratch one forward of M tokens needs: activation codes and scales,
- * and the low-rank intermediate H = X^ L1 (fp32 [M x rank]).  0 if the shape is unsupported. */
+/* Bytes of device scratch one forward of M tokens needs: activation codes (one byte each, in the
+ * operand order of the integer matrix instruction) and scales, and the low-rank intermediate
+ * H = X^ L1 (fp32 [M x rank], plus the same values as bf16 operand fragments for the up projection).
+ * 0 if the shape is unsupported. */
 size_t svdq_workspace_bytes(int M, const svdq_shape *shape);
 
 /*

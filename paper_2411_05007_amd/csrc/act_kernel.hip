@@ -31,6 +31,14 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// round-to-nearest-even fp32 -> bf16 of two values (v_cvt_pk_bf16_f32), lo in the low half
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_rne_pair(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
 
 // LDS of one workgroup: the smoothing factors of all its groups (fp32 [G][64], each wavefront stages and
 // reads only its own run of groups) followed by one private block per wavefront, used first to turn X from
@@ -259,12 +267,30 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
                 for (int v = 0; v < 4; ++v) red[(4 * blk + v) * L::kRedRow + 16 * c + row] = acc[c][v];
         __syncthreads();
         const unsigned char *all = act_lds + L::rinv_bytes(QUANT ? p.G : 0);
-        for (int idx = threadIdx.x; idx < 16 * p.rank; idx += WAVES * 64) {
-            const int r = idx / p.rank, col = idx - r * p.rank;
-            float h = 0.f;
+        // a thread takes eight neighbouring columns of one token: two 16-byte stores of fp32 H, and one each
+        // of the bf16 hi and lo parts that the GEMM feeds to its matrix core as they are
+        const int chunks = p.rank / 8;
+        for (int idx = threadIdx.x; idx < 16 * chunks; idx += WAVES * 64) {
+            const int r = idx / chunks, col = 8 * (idx - r * chunks);
+            float h[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w = 0; w < WAVES; ++w) h += reinterpret_cast<const float *>(all + (size_t)w * L::kWaveBytes)[r * L::kRedRow + col];
-            if (m0 + r < p.M) p.H[(size_t)(m0 + r) * p.rank + col] = h;
+            for (int w = 0; w < WAVES; ++w) {
+                const float *pw = reinterpret_cast<const float *>(all + (size_t)w * L::kWaveBytes) + r * L::kRedRow + col;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) h[e] += pw[e];
+            }
+            const int m = m0 + r;       // < Mpad: rows past M land in padding
+            float4 *hp = reinterpret_cast<float4 *>(p.H + (size_t)m * p.rank + col);
+            hp[0] = make_float4(h[0], h[1], h[2], h[3]);
+            hp[1] = make_float4(h[4], h[5], h[6], h[7]);
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                hi[e] = bf16_rne_pair(h[2 * e], h[2 * e + 1]);
+                lo[e] = bf16_rne_pair(h[2 * e] - bf16lo(hi[e]), h[2 * e + 1] - bf16hi(hi[e]));
+            }
+            *reinterpret_cast<uint4 *>(p.hfrag + hfrag_offset(p.rank, m, col, 0)) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *reinterpret_cast<uint4 *>(p.hfrag + hfrag_offset(p.rank, m, col, 1)) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
         }
     }
 }

@@ -49,7 +49,7 @@ svdq::GemmParams gemm_params(const svdq_layer_dev *L, unsigned char *ws, const s
     svdq::GemmParams g{};
     g.xcodes = ws + w.codes_off;
     g.sx = reinterpret_cast<const uint16_t *>(ws + w.sx_off);
-    g.H = reinterpret_cast<const float *>(ws + w.h_off);
+    g.hfrag = ws + w.hfrag_off;
     g.wcodes = static_cast<const uint8_t *>(L->wcodes);
     g.sw = static_cast<const uint16_t *>(L->wscales);
     g.l2t = static_cast<const uint16_t *>(L->l2);
@@ -108,6 +108,7 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     a.codes = ws + w.codes_off;
     a.sx = reinterpret_cast<uint16_t *>(ws + w.sx_off);
     a.H = reinterpret_cast<float *>(ws + w.h_off);
+    a.hfrag = ws + w.hfrag_off;
     a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
 
     hipError_t e;

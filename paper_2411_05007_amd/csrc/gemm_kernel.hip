@@ -340,23 +340,22 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         qo = load_group(3 < glast ? 3 : glast);
         __builtin_amdgcn_sched_barrier(0);      // everything the main loop needs first is requested before H and L2
         // ---- low-rank up projection on the matrix core: the accumulators START as H L2 ----------------
-        // bf16 MFMAs with the fp32 accumulator tile as C.  H is fp32; it is split into bf16 hi + lo parts (two
-        // MFMAs) so the 16-bit branch loses nothing against an fp32 evaluation.  The loads of rank step k+1 are
-        // in flight while step k is multiplied.  Doing this before the main loop instead of after it puts the
+        // bf16 MFMAs with the fp32 accumulator tile as C.  The activation kernel leaves H split into bf16 hi + lo
+        // parts (two MFMAs), so the 16-bit branch loses nothing against an fp32 evaluation, already in operand
+        // order.  The loads of rank step k+1 are in flight while step k is multiplied.  Doing this before the main loop instead of after it puts the
         // memory round trip of H and L2 under the one the first groups need anyway.
         const bool lowrank = MODE == 0 && p.rank > 0;
         {
             const int ksteps = p.rank / 16;
-            float4 hraw[2][2][2];
+            uint4 hhi[2][2], hlo[2][2];      // [buffer][row block]: bf16 hi and lo parts of H, ready-made A operands
             uint4 braw[2][2];
+            const unsigned char *hf = p.hfrag + (size_t)((gm0 + wm0) / 32) * ksteps * 2048 + lane * 16;
             auto load_step = [&](int buf, int ks) {
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
-                    int row = gm0 + wm0 + r * 32 + li;
-                    row = row < p.M ? row : p.M - 1;
-                    const float4 *hp = reinterpret_cast<const float4 *>(p.H + (size_t)row * p.rank + ks * 16 + 8 * lh);
-                    hraw[buf][r][0] = hp[0];
-                    hraw[buf][r][1] = hp[1];
+                    const unsigned char *hp = hf + ((size_t)r * ksteps + ks) * 2048;
+                    hhi[buf][r] = *reinterpret_cast<const uint4 *>(hp);
+                    hlo[buf][r] = *reinterpret_cast<const uint4 *>(hp + 1024);
                 }
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
@@ -365,30 +364,13 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
                 }
             };
             auto compute_step = [&](int buf) {
-                bf16x8 hh[2], hl[2];
-#pragma unroll
-                for (int r = 0; r < 2; ++r) {
-                    const float4 h0 = hraw[buf][r][0], h1 = hraw[buf][r][1];
-                    const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                    uint32_t hi[4], lo[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        hi[e] = bf16_rne_pair(hv[2 * e], hv[2 * e + 1]);
-                        lo[e] = bf16_rne_pair(hv[2 * e] - __uint_as_float(hi[e] << 16), hv[2 * e + 1] - __uint_as_float(hi[e] & 0xffff0000u));
-                    }
-                    uint4 ph, pl;
-                    ph.x = hi[0]; ph.y = hi[1]; ph.z = hi[2]; ph.w = hi[3];
-                    pl.x = lo[0]; pl.y = lo[1]; pl.z = lo[2]; pl.w = lo[3];
-                    hh[r] = __builtin_bit_cast(bf16x8, ph);
-                    hl[r] = __builtin_bit_cast(bf16x8, pl);
-                }
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
                     const bf16x8 bl = __builtin_bit_cast(bf16x8, braw[buf][c]);
 #pragma unroll
                     for (int r = 0; r < 2; ++r) {
-                        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hh[r], bl, acc[r][c], 0, 0, 0);
-                        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hl[r], bl, acc[r][c], 0, 0, 0);
+                        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, hhi[buf][r]), bl, acc[r][c], 0, 0, 0);
+                        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, hlo[buf][r]), bl, acc[r][c], 0, 0, 0);
                     }
                 }
             };

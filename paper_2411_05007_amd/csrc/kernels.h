@@ -18,6 +18,7 @@ struct ActParams {
     uint8_t *codes;          // [G][Mpad][64], int8 = 16 * code
     uint16_t *sx;            // fp16 [G][Mpad]
     float *H;                // fp32 [Mpad][rank]
+    uint8_t *hfrag;          // H as bf16 hi + lo parts in MFMA operand order (layout.h), Mpad * rank * 4 bytes
     int M, K, G, Mpad, rank;
 };
 
@@ -27,7 +28,7 @@ hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream);
 struct GemmParams {
     const uint8_t *xcodes;   // [G][Mpad][64], int8 = 16 * code
     const uint16_t *sx;      // fp16 [G][Mpad]
-    const float *H;          // fp32 [Mpad][rank]
+    const uint8_t *hfrag;    // H as bf16 hi + lo parts in MFMA operand order (layout.h)
     const uint8_t *wcodes;   // [G][Npad][32]
     const uint16_t *sw;      // fp16 [G][Npad]
     const uint16_t *l2t;     // bf16 [Npad][rank]

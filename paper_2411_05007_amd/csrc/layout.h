@@ -17,6 +17,10 @@
 //         matrix core (there is no 4-bit integer MFMA), which spares the GEMM the widening of
 //         this operand; the tensor lives only between the two kernels of one forward.
 //     activation scales (workspace) sx[g][m]  (fp16)
+//     low-rank activations (workspace) H[m][rank] fp32, and the same values split into bf16 hi + lo parts
+//         (hi = bf16(h), lo = bf16(h - hi)) in the A-operand order of v_mfma_f32_32x32x16_bf16:
+//         hfrag[m / 32][rank step of 16][part][lane = 32 ((j % 16) / 8) + m % 32][8 bf16], so the GEMM loads
+//         a ready-made operand with one 16-byte load per lane (hfrag_offset)
 //
 // Rows are padded to a multiple of 256 so a full tile can always be read; padding rows of the
 // weight hold zero codes and zero scales.
@@ -58,6 +62,12 @@ inline __host__ __device__ size_t act_chunk_offset(int g, int Mpad, int m, int b
     return ((((size_t)g * (Mpad / 32) + m / 32) * 2 + j) * 64 + (h * 32 + m % 32)) * 16;
 }
 
+// Byte offset of the 16-byte chunk of hfrag that holds columns 8 (j / 8) .. + 7 of row m; part 0 = hi, 1 = lo.
+inline __host__ __device__ size_t hfrag_offset(int rank, int m, int j, int part) {
+    const int ks = j / 16, kq = (j % 16) / 8;
+    return ((((size_t)(m / 32) * (rank / 16) + ks) * 2 + part) * 64 + (kq * 32 + m % 32)) * 16;
+}
+
 inline __host__ __device__ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline __host__ __device__ size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
@@ -71,7 +81,7 @@ inline __host__ __device__ size_t l1s_index(int K, int rank, int k, int j) {
 
 // Workspace carve-up for a forward of M tokens.
 struct Workspace {
-    size_t codes_off, sx_off, h_off, total;
+    size_t codes_off, sx_off, h_off, hfrag_off, total;
     int Mpad;
 };
 inline __host__ __device__ Workspace workspace_layout(int M, int K, int rank) {
@@ -81,7 +91,8 @@ inline __host__ __device__ Workspace workspace_layout(int M, int K, int rank) {
     w.codes_off = 0;
     w.sx_off = align256((size_t)G * w.Mpad * kActBytes);
     w.h_off = w.sx_off + align256((size_t)G * w.Mpad * 2);
-    w.total = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.total = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
     return w;
 }
 

@@ -144,9 +144,10 @@ def test_shape_errors_and_workspace_size(lib):
     assert (sz.rinv, sz.l1s, sz.l2, sz.wcodes, sz.wscales, sz.bias) == (512, 128 * 16 * 2, 256 * 16 * 2, 2 * 256 * 32, 2 * 256 * 2, 1024)
     sh = S.make_shape(3072, 12288, 32)
     ws = S.svdq_workspace_bytes(4608, sh)
-    # codes M*K/2 + scales 2*M*G + H 4*M*r, all with M padded to 256 (4608 is a multiple already)
-    assert ws == 4608 * 3072 // 2 + 2 * 4608 * 48 + 4 * 4608 * 32
-    assert S.svdq_workspace_bytes(1, sh) == 256 * 3072 // 2 + 2 * 256 * 48 + 4 * 256 * 32
+    # codes M*K (one int8 = 16 * code each) + scales 2*M*G + H 4*M*r as fp32 and again as bf16 hi/lo operand
+    # fragments, all with M padded to 256 (4608 is a multiple already)
+    assert ws == 4608 * 3072 + 2 * 4608 * 48 + 2 * 4 * 4608 * 32
+    assert S.svdq_workspace_bytes(1, sh) == 256 * 3072 + 2 * 256 * 48 + 2 * 4 * 256 * 32
     assert S.svdq_workspace_bytes(16, S.make_shape(100, 64, 16)) == 0
     # forward argument checks happen before any GPU call
     bad = S.LayerDev()
