@@ -109,7 +109,8 @@ typedef struct {
 
 /* Bytes of device scratch one forward of M tokens needs: activation codes (one byte each, in the
  * operand order of the integer matrix instruction) and scales, and the low-rank intermediate
- * H = X^ L1 (fp32 [M x rank], plus the same values as bf16 operand fragments for the up projection).
+ * H = X^ L1 (fp32 [M x rank], plus the same values as bf16 operand fragments for the up projection);
+ * for launches with few tiles and a long K also fp32 partial output tiles and one counter per tile.
  * 0 if the shape is unsupported. */
 size_t svdq_workspace_bytes(int M, const svdq_shape *shape);
 

@@ -255,6 +255,10 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
         step(clampg(g + 1), g + 1 < g1, xs1, bs1);
     }
 
+    // housekeeping for the kernel that follows on the stream: its tile arrival counters start at zero
+    // (a few words per workgroup, after the real work, so that nobody's loads queue behind these stores)
+    for (int i = blockIdx.x * (WAVES * 64) + threadIdx.x; i < p.n_zero; i += gridDim.x * (WAVES * 64)) p.zero_words[i] = 0u;
+
     if (PROJ) {
         // Deterministic reduction of the wavefronts' partial H through LDS: every wavefront deposits its
         // partial sums in its own block, then all threads share the 16 x rank outputs and add the partials

@@ -44,6 +44,15 @@ int tile_override() {
     return v;
 }
 
+// experiments only: force the K split of small launches (read once)
+int ksplit_override() {
+    static const int v = [] {
+        const char *e = std::getenv("SVDQ_GEMM_KSPLIT");
+        return e ? std::atoi(e) : 0;
+    }();
+    return v;
+}
+
 svdq::GemmParams gemm_params(const svdq_layer_dev *L, unsigned char *ws, const svdq::Workspace &w, int M, void *Y, int rank) {
     const svdq_shape &s = L->shape;
     svdq::GemmParams g{};
@@ -60,6 +69,9 @@ svdq::GemmParams gemm_params(const svdq_layer_dev *L, unsigned char *ws, const s
     g.rank = rank;
     g.dbg = nullptr;
     g.magic = svdq::kMagicBits;
+    g.ksplit = 1;
+    g.partial = reinterpret_cast<float *>(ws + w.partial_off);
+    g.counters = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     return g;
 }
 
@@ -81,7 +93,7 @@ int svdq_profile_event(void *hip_event) {
 
 size_t svdq_workspace_bytes(int M, const svdq_shape *s) {
     if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
-    return svdq::workspace_layout(M, s->K, s->rank).total;
+    return svdq::workspace_layout(M, s->K, s->N, s->rank, ksplit_override()).total;
 }
 
 int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
@@ -93,7 +105,7 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.rank);
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -110,6 +122,12 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     a.H = reinterpret_cast<float *>(ws + w.h_off);
     a.hfrag = ws + w.hfrag_off;
     a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
+    a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);
+    a.n_zero = w.n_counters;
+    // a forced tile shape runs without the K split; otherwise tile and split follow the plan the workspace was sized for
+    const svdq::GemmPlan plan = svdq::plan_gemm(M, s.N, s.K / svdq::kGroup, ksplit_override());
+    const int tile = tile_override() ? tile_override() : plan.tile;
+    const int ksplit = tile_override() ? 1 : plan.ksplit;
 
     hipError_t e;
     if (!unfused) {
@@ -119,8 +137,9 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
             e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
             if (e != hipSuccess) return hip_fail(e);
         }
-        const svdq::GemmParams g = gemm_params(L, ws, w, M, Y, lowrank ? s.rank : 0);
-        e = svdq::launch_gemm(g, tile_override(), stream);
+        svdq::GemmParams g = gemm_params(L, ws, w, M, Y, lowrank ? s.rank : 0);
+        g.ksplit = ksplit;
+        e = svdq::launch_gemm(g, tile, stream);
         if (e != hipSuccess) return hip_fail(e);
     } else {
         // the four-kernel pipeline of Fig. 6a: down projection, quantize, 4-bit GEMM, up projection
@@ -130,8 +149,9 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
         }
         e = svdq::launch_act(a, 1, stream);
         if (e != hipSuccess) return hip_fail(e);
-        const svdq::GemmParams g = gemm_params(L, ws, w, M, Y, 0);
-        e = svdq::launch_gemm(g, tile_override(), stream);
+        svdq::GemmParams g = gemm_params(L, ws, w, M, Y, 0);
+        g.ksplit = ksplit;
+        e = svdq::launch_gemm(g, tile, stream);
         if (e != hipSuccess) return hip_fail(e);
         if (lowrank) {
             e = svdq::launch_upproj(a.H, g.l2t, g.Y, M, s.N, s.rank, stream);
@@ -148,7 +168,7 @@ int svdq_debug_act(const svdq_layer_dev *L, const void *workspace, int M, int8_t
     if (M < 0 || !workspace) return SVDQ_EINVAL;
     if (M == 0) return SVDQ_OK;
     const svdq_shape &s = L->shape;
-    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.rank);
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
     const unsigned char *ws = static_cast<const unsigned char *>(workspace);
     svdq::DebugActParams d{};
     d.codes = ws + w.codes_off;
@@ -166,12 +186,13 @@ int svdq_debug_group_acc(const svdq_layer_dev *L, const void *workspace, int M, 
     if (st != SVDQ_OK) return st;
     const svdq_shape &s = L->shape;
     if (!workspace || !out || M <= 0 || m0 < 0 || m1 > M || m0 >= m1 || n0 < 0 || n1 > s.N || n0 >= n1) return SVDQ_EINVAL;
-    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.rank);
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
     unsigned char *ws = const_cast<unsigned char *>(static_cast<const unsigned char *>(workspace));
     // the window-export instantiation of the kernel never stores Y
     svdq::GemmParams g = gemm_params(L, ws, w, M, nullptr, 0);
     g.dbg = out; g.m0 = m0; g.m1 = m1; g.n0 = n0; g.n1 = n1;
-    const hipError_t e = svdq::launch_gemm(g, tile_override(), static_cast<hipStream_t>(hip_stream));
+    const int tile = tile_override() ? tile_override() : svdq::plan_gemm(M, s.N, s.K / svdq::kGroup).tile;
+    const hipError_t e = svdq::launch_gemm(g, tile, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SVDQ_OK : hip_fail(e);
 }
 

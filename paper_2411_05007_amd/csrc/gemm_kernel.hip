@@ -105,12 +105,18 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     // same time on one XCD then share their activation rows and weight columns through that XCD's L2.
     const int tiles_m = (p.M + BM - 1) / BM;
     const int tiles_n = (p.N + BN - 1) / BN;
+    const int total = tiles_m * tiles_n;
+    // with a split K loop the grid holds ksplit copies of the tile set; copy `split` multiplies groups [g_begin, g_end)
+    const int split = (int)blockIdx.x / total;
+    const int bid = (int)blockIdx.x - split * total;
+    const int g_per = (p.G + p.ksplit - 1) / p.ksplit;
+    const int g_begin = split * g_per;
+    const int g_end = g_begin + g_per < p.G ? g_begin + g_per : p.G;
     int tile_m, tile_n;
     {
-        const int total = tiles_m * tiles_n;
         const int per = (total + 7) / 8;
         // a bijection only when the tile count divides by 8; otherwise keep the launch order
-        const int id = (total % 8 == 0) ? (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+        const int id = (total % 8 == 0) ? (bid % 8) * per + (bid / 8) : bid;
         constexpr int kBand = 4;
         const int band = id / (kBand * tiles_n);
         const int band_rows = (tiles_m - band * kBand) < kBand ? (tiles_m - band * kBand) : kBand;
@@ -288,7 +294,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     auto body = [&](int g, auto odd_c, const intx4 (&af)[2][2], intx4 (&afn)[2][2], const Scales &sc, Scales &scn, Staged &q) {
         constexpr int odd = decltype(odd_c)::value;      // g & 1
         constexpr int nxt = 1 - odd;
-        load_a(afn, g + 1 < p.G ? g + 1 : p.G - 1);      // past the end: refetch the last group (unused)
+        load_a(afn, g + 1 < g_end ? g + 1 : g_end - 1);      // past the end: refetch the last group (unused)
         read_scales(scn, nxt);                           // written one iteration ago
         intx16 da, db;
         // sub-tiles in the order (0,0) (1,0) (1,1) (0,1): the weight fragments of column block 0 fall free first
@@ -309,7 +315,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         __builtin_amdgcn_sched_barrier(0);
         rescale_half(sc, db, 1, 0, H0{});
         store_group(odd, odd, q);
-        q = load_group(g + 4 < p.G ? g + 4 : p.G - 1);
+        q = load_group(g + 4 < g_end ? g + 4 : g_end - 1);
         __builtin_amdgcn_sched_barrier(0);
         da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][1], bf[1][1], da, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -332,19 +338,19 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         __syncthreads();
     };
 
-    const int glast = p.G - 1;
-    load_a(afe, 0);
+    const int glast = g_end - 1;
+    load_a(afe, g_begin);
     {
-        const Staged q0 = load_group(0), q1 = load_group(1 < glast ? 1 : glast);
-        qe = load_group(2 < glast ? 2 : glast);
-        qo = load_group(3 < glast ? 3 : glast);
+        const Staged q0 = load_group(g_begin), q1 = load_group(g_begin + 1 < glast ? g_begin + 1 : glast);
+        qe = load_group(g_begin + 2 < glast ? g_begin + 2 : glast);
+        qo = load_group(g_begin + 3 < glast ? g_begin + 3 : glast);
         __builtin_amdgcn_sched_barrier(0);      // everything the main loop needs first is requested before H and L2
         // ---- low-rank up projection on the matrix core: the accumulators START as H L2 ----------------
         // bf16 MFMAs with the fp32 accumulator tile as C.  The activation kernel leaves H split into bf16 hi + lo
         // parts (two MFMAs), so the 16-bit branch loses nothing against an fp32 evaluation, already in operand
         // order.  The loads of rank step k+1 are in flight while step k is multiplied.  Doing this before the main loop instead of after it puts the
         // memory round trip of H and L2 under the one the first groups need anyway.
-        const bool lowrank = MODE == 0 && p.rank > 0;
+        const bool lowrank = MODE == 0 && p.rank > 0 && split == 0;      // one split carries the low-rank product
         {
             const int ksteps = p.rank / 16;
             uint4 hhi[2][2], hlo[2][2];      // [buffer][row block]: bf16 hi and lo parts of H, ready-made A operands
@@ -399,16 +405,61 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     {
         using Even = std::integral_constant<int, 0>;
         using Odd = std::integral_constant<int, 1>;
-        int g = 0;
-        for (; g + 2 <= p.G; g += 2) {
+        int g = g_begin;
+        for (; g + 2 <= g_end; g += 2) {
             body(g, Even{}, afe, afo, sce, sco, qe);
             body(g + 1, Odd{}, afo, afe, sco, sce, qo);
         }
-        if (g < p.G) body(g, Even{}, afe, afo, sce, sco, qe);
+        if (g < g_end) body(g, Even{}, afe, afo, sce, sco, qe);
     }
 #undef SVDQ_FMAC_BCAST
 
     if (MODE == 1) return;   // the window export writes no Y
+
+    // ---- split K loop: park the partial tile, the last workgroup to arrive adds them all up ----------
+    // Partial tiles are stored in register order (64 floats per thread, consecutive threads consecutive
+    // addresses).  The L2 caches of the chip's eight XCDs are not coherent with each other, so partials are
+    // written and read with device-scope atomic accesses, which go past them; no cache is flushed.  A
+    // workgroup takes its ticket once all its stores have been acknowledged; the one holding the last ticket
+    // reads all ksplit partials back, its own included, and adds them in split order, so the sum does not
+    // depend on which workgroup came last.  Nobody waits for anybody.
+    if (p.ksplit > 1) {
+        const int tile_lin = tile_m * tiles_n + tile_n;
+        constexpr int kTileWords = BM * BN;
+        float *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    __hip_atomic_store(mine + ((r * 2 + c) * 16 + v) * T::kThreads, acc[r][c][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // every store of this thread has been acknowledged
+        __syncthreads();
+        uint32_t *ticket = reinterpret_cast<uint32_t *>(lds);      // the main loop is over: LDS is free
+        if (tid == 0) *ticket = __hip_atomic_fetch_add(&p.counters[tile_lin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const bool last = *ticket == (uint32_t)(p.ksplit - 1);
+        __syncthreads();                                          // the epilogue reuses this LDS word
+        if (!last) return;
+        if (tid == 0) __hip_atomic_store(&p.counters[tile_lin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next launch
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+        const float *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
+        for (int s = 0; s < p.ksplit; ++s) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[r][c][v] += __hip_atomic_load(all + (size_t)s * kTileWords + ((r * 2 + c) * 16 + v) * T::kThreads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 
     // ---- epilogue: bias, bf16 store -----------------------------------------------------------------
     // Bias, one rounding to bf16, and the store.  A lane holds one column and sixteen rows of a 32x32
@@ -457,7 +508,8 @@ template <int BM, int BN>
 hipError_t launch_tile(const GemmParams &p, hipStream_t stream) {
     using T = Tile<BM, BN>;
     const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-    const dim3 grid(tiles), block(T::kThreads);
+    if (p.ksplit < 1 || p.ksplit > p.G || (p.ksplit > 1 && (p.dbg || !p.partial || !p.counters))) return hipErrorInvalidValue;
+    const dim3 grid(tiles * p.ksplit), block(T::kThreads);
     hipError_t e;
     if (p.dbg) {
         auto k = gemm_kernel<BM, BN, 1>;
@@ -489,12 +541,7 @@ __global__ __launch_bounds__(256) void upproj_kernel(const float *H, const uint1
 
 hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
-    if (tile == 0) {
-        // Two independent 128x128 workgroups per CU measured fastest on the large shapes.  A launch with fewer than
-        // two such workgroups per CU leaves SIMDs empty, and halving the tile height there measured 2-6 % faster.
-        const long tiles128 = (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
-        tile = tiles128 < 512 ? 4 : 2;
-    }
+    if (tile == 0) tile = plan_gemm(p.M, p.N, p.G).tile;
     switch (tile) {
         case 1: return launch_tile<256, 128>(p, stream);
         case 2: return launch_tile<128, 128>(p, stream);

@@ -20,6 +20,8 @@ struct ActParams {
     float *H;                // fp32 [Mpad][rank]
     uint8_t *hfrag;          // H as bf16 hi + lo parts in MFMA operand order (layout.h), Mpad * rank * 4 bytes
     int M, K, G, Mpad, rank;
+    uint32_t *zero_words;    // cleared by the first workgroup: the arrival counters of the GEMM that follows
+    int n_zero;
 };
 
 // flags: bit 0 = quantize (codes + scales), bit 1 = down projection (H)
@@ -38,9 +40,12 @@ struct GemmParams {
     int32_t *dbg;            // debug window of exact group sums, or null
     int m0, m1, n0, n1;
     int magic;               // kMagicBits, passed at run time so it stays in registers
+    int ksplit;              // workgroups per tile along K (1 = no split)
+    float *partial;          // ksplit > 1: fp32 [tile][split][BM * BN] partial tiles, register order
+    uint32_t *counters;      // ksplit > 1: one arrival counter per tile, zero when the kernel starts
 };
 
-// tile: 0 = choose by shape, otherwise a tile-config id (see gemm_kernel.hip)
+// tile: a tile-config id (see gemm_kernel.hip); p.ksplit > 1 needs p.partial and p.counters
 hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream);
 
 // Y[m][n] += sum_j H[m][j] L2[j][n]  as a separate read-modify-write pass (unfused baseline only)

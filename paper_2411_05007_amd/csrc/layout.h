@@ -79,12 +79,49 @@ inline __host__ __device__ size_t l1s_index(int K, int rank, int k, int j) {
     return ((((size_t)g * 2 + s) * (rank / 16) + c) * 64 + lane) * 8 + e;
 }
 
+// How the GEMM of an M x N x (64 G) layer is launched when the caller does not force a tile shape.
+// Large launches use 128x128 tiles, two workgroups per CU.  A launch with fewer than two such workgroups
+// per CU uses 64x128 tiles, and if even those leave most SIMDs without a second wavefront, the K loop is
+// split over `ksplit` workgroups per tile: each writes its fp32 partial tile to the workspace, and the one
+// that finishes last adds them up (in split order, so the result does not depend on who is last) and stores Y.
+struct GemmPlan {
+    int tile;        // tile-config id of the GEMM kernel: 2 = 128x128, 4 = 64x128
+    int bm, bn;
+    int tiles;       // workgroups per split
+    int ksplit;      // >= 1
+};
+constexpr int kMaxKSplit = 8;
+inline GemmPlan plan_gemm(int M, int N, int G, int ksplit_override = 0) {
+    GemmPlan pl;
+    const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (tiles128 >= 512) {
+        pl.tile = 2; pl.bm = 128; pl.bn = 128; pl.tiles = (int)tiles128; pl.ksplit = 1;
+        return pl;
+    }
+    pl.tile = 4; pl.bm = 64; pl.bn = 128;
+    pl.tiles = ((M + 63) / 64) * ((N + 127) / 128);
+    const int waves = 2 * pl.tiles;                 // the chip has 1024 SIMDs and wants two wavefronts on each
+    int s = 1;
+    // measured: parking and re-reading the partial tiles costs about as much as half of a 48-group K loop,
+    // so the split pays only when the launch is well below one wavefront per SIMD and K is long
+    if (waves <= 768) {
+        s = 4;
+        while (s > 1 && G / s < 12) --s;            // at least twelve groups per split
+    }
+    if (ksplit_override > 0) s = ksplit_override < kMaxKSplit ? ksplit_override : kMaxKSplit;
+    if (s > G) s = G > 0 ? G : 1;
+    const int per = (G + s - 1) / s;
+    pl.ksplit = (G + per - 1) / per;                // no empty split
+    return pl;
+}
+
 // Workspace carve-up for a forward of M tokens.
 struct Workspace {
-    size_t codes_off, sx_off, h_off, hfrag_off, total;
+    size_t codes_off, sx_off, h_off, hfrag_off, counters_off, partial_off, total;
     int Mpad;
+    int n_counters;      // one arrival counter per tile when the K loop is split, else 0
 };
-inline __host__ __device__ Workspace workspace_layout(int M, int K, int rank) {
+inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_override = 0) {
     Workspace w;
     w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
     const int G = K / kGroup;
@@ -92,7 +129,11 @@ inline __host__ __device__ Workspace workspace_layout(int M, int K, int rank) {
     w.sx_off = align256((size_t)G * w.Mpad * kActBytes);
     w.h_off = w.sx_off + align256((size_t)G * w.Mpad * 2);
     w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    w.total = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    const GemmPlan pl = plan_gemm(M > 0 ? M : 1, N, G, ksplit_override);
+    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
+    w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
+    w.total = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * pl.bm * pl.bn * 4) : 0);
     return w;
 }
 

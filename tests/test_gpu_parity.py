@@ -128,6 +128,31 @@ def test_ragged_shapes(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"ragged {M}x{K}x{N} r{r}", window=M >= 3 and N >= 16)
 
 
+@pytest.mark.parametrize("M,K,N,r", [(100, 3072, 272, 32), (70, 3136, 144, 16), (200, 6144, 400, 48)])
+def test_small_launches_with_split_k_loop(torch, M, K, N, r):
+    """Few tiles and a long K: the library splits the K loop over several workgroups per tile, which park fp32
+    partial tiles in the workspace; the last one to arrive adds them in split order.  K = 3136 gives splits of
+    unequal length.  The result must match the oracle and must not depend on arrival order."""
+    rng = np.random.default_rng(7000 + M + K + N)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, K // 100, replace=False)] *= 50
+    xb = O.bf16_round(x)
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 4, replace=False)] *= 20
+    ax = np.abs(O.bf16_to_f32(xb)).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    prep = S.svdq_prepare(w, ax, r, bias=b)
+    _say(f"split-K: M={M} K={K} N={N} r={r}")
+    _run_and_compare(torch, xb, prep, what=f"split-K {M}x{K}x{N} r{r}")
+    layer = S.DeviceLayer(prep)
+    xt = S.bf16_tensor_from_bits(xb)
+    ws = layer.workspace(M)
+    first = layer.forward(xt, workspace=ws).clone()
+    for _ in range(5):      # the same workspace again: the arrival counters must have been left ready
+        again = layer.forward(xt, workspace=ws)
+        assert torch.equal(first.view(torch.int16), again.view(torch.int16))
+
+
 @pytest.mark.parametrize("tile", [1, 2, 3, 4])
 def test_every_gemm_tile_configuration(torch, tile):
     case = I.case_by_name("tiny")

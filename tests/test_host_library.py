@@ -147,7 +147,9 @@ def test_shape_errors_and_workspace_size(lib):
     # codes M*K (one int8 = 16 * code each) + scales 2*M*G + H 4*M*r as fp32 and again as bf16 hi/lo operand
     # fragments, all with M padded to 256 (4608 is a multiple already)
     assert ws == 4608 * 3072 + 2 * 4608 * 48 + 2 * 4 * 4608 * 32
-    assert S.svdq_workspace_bytes(1, sh) == 256 * 3072 + 2 * 256 * 48 + 2 * 4 * 256 * 32
+    # a one-token forward runs 64x128 tiles (96 of them) with the K loop split four ways: one arrival counter per
+    # tile (padded to 256 bytes) and four fp32 partial tiles per tile come on top
+    assert S.svdq_workspace_bytes(1, sh) == 256 * 3072 + 2 * 256 * 48 + 2 * 4 * 256 * 32 + 512 + 4 * 96 * 64 * 128 * 4
     assert S.svdq_workspace_bytes(16, S.make_shape(100, 64, 16)) == 0
     # forward argument checks happen before any GPU call
     bad = S.LayerDev()
