@@ -60,8 +60,8 @@ __device__ __forceinline__ float max_over_8_lanes(float a) {
     return a;
 }
 
-template <int RBMAX, int WAVES, bool QUANT, bool PROJ>
-__global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) void act_kernel(ActParams p) {
+template <int RBMAX, int WAVES, bool QUANT, bool PROJ, bool STAGE>
+__global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) ? 2 : 1) void act_kernel(ActParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char act_lds[];
     using L = ActLds<RBMAX, WAVES>;
     const int lane = threadIdx.x & 63;
@@ -89,7 +89,10 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
     const uint16_t *xb = p.X + (size_t)(mb < p.M ? mb : p.M - 1) * p.K + 8 * c8;
     struct XStage { uint4 x0, x1; };                   // 8 bf16 activations of token r8 and of token r8 + 8
     struct BStage { uint4 b[PROJ ? 2 * RBMAX : 1]; };  // L1s fragments: k steps 0 and 1 of every 16-column block
-    constexpr bool kStageB = PROJ && RBMAX <= 2;       // wider ranks fetch them (from L2) right before their MFMAs
+    // STAGE: the fragments of the next two groups wait in registers (at rank 128 this fills the register file
+    // and one workgroup owns a CU); otherwise all fragments of a group are requested right before its MFMAs,
+    // every load in flight before the first wait.
+    constexpr bool kStageB = PROJ && STAGE;
 
     auto clampg = [&](int g) { return g < g1 ? g : g1 - 1; };
     auto fetch_x = [&](int g) {
@@ -159,15 +162,29 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
             uint4 x0 = ap[0], x1 = ap[1];
             if (!real) x0 = x1 = make_uint4(0u, 0u, 0u, 0u);     // the repeated group of an odd run adds nothing to H
             const uint4 *lp = reinterpret_cast<const uint4 *>(p.l1s) + ((size_t)g * 2 * rb) * 64 + lane;
+            // unstaged ranks: at most eight column blocks (sixteen fragments) are requested at a time
+            constexpr int kChunk = RBMAX < 8 ? RBMAX : 8;
 #pragma unroll
-            for (int c = 0; c < RBMAX; ++c) {
-                const int cc = c < rb ? c : rb - 1;
-                const uint4 b0 = kStageB ? sb.b[kStageB ? 2 * c : 0] : lp[(size_t)cc * 64];
-                const uint4 b1 = kStageB ? sb.b[kStageB ? 2 * c + 1 : 0] : lp[(size_t)(rb + cc) * 64];
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0),
-                                                                 __builtin_bit_cast(bf16x8, b0), acc[c], 0, 0, 0);
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1),
-                                                                 __builtin_bit_cast(bf16x8, b1), acc[c], 0, 0, 0);
+            for (int c0 = 0; c0 < RBMAX; c0 += kChunk) {
+                uint4 late[kStageB ? 1 : 2 * kChunk];
+                if (!kStageB) {
+#pragma unroll
+                    for (int c = 0; c < kChunk; ++c) {
+                        const int cc = c0 + c < rb ? c0 + c : rb - 1;
+                        late[kStageB ? 0 : 2 * c] = lp[(size_t)cc * 64];
+                        late[kStageB ? 0 : 2 * c + 1] = lp[(size_t)(rb + cc) * 64];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);      // all requests go out before the first MFMA waits for its pair
+                }
+#pragma unroll
+                for (int c = 0; c < kChunk; ++c) {
+                    const uint4 b0 = kStageB ? sb.b[kStageB ? 2 * (c0 + c) : 0] : late[kStageB ? 0 : 2 * c];
+                    const uint4 b1 = kStageB ? sb.b[kStageB ? 2 * (c0 + c) + 1 : 0] : late[kStageB ? 0 : 2 * c + 1];
+                    acc[c0 + c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0),
+                                                                      __builtin_bit_cast(bf16x8, b0), acc[c0 + c], 0, 0, 0);
+                    acc[c0 + c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1),
+                                                                      __builtin_bit_cast(bf16x8, b1), acc[c0 + c], 0, 0, 0);
+                }
             }
         }
     };
@@ -299,7 +316,7 @@ __global__ __launch_bounds__(WAVES * 64, (RBMAX <= 4 && WAVES <= 8) ? 2 : 1) voi
     }
 }
 
-template <int RBMAX, int WAVES>
+template <int RBMAX, int WAVES, bool STAGE>
 hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     using L = ActLds<RBMAX, WAVES>;
     const dim3 grid((p.M + 15) / 16), block(WAVES * 64);
@@ -308,17 +325,17 @@ hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
     if (q && pr) {
-        auto k = act_kernel<RBMAX, WAVES, true, true>;
+        auto k = act_kernel<RBMAX, WAVES, true, true, STAGE>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
     } else if (q) {
-        auto k = act_kernel<1, WAVES, true, false>;
+        auto k = act_kernel<1, WAVES, true, false, false>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
     } else if (pr) {
-        auto k = act_kernel<RBMAX, WAVES, false, true>;
+        auto k = act_kernel<RBMAX, WAVES, false, true, STAGE>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
@@ -349,10 +366,16 @@ hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
     // wavefronts per 16-token slice: more of them when K is long enough to give each a few groups
     const bool wide = p.G >= 32;
-    if (p.rank <= 32) return wide ? launch_rb<2, 8>(p, flags, stream) : launch_rb<2, 4>(p, flags, stream);
-    if (p.rank <= 64) return wide ? launch_rb<4, 8>(p, flags, stream) : launch_rb<4, 4>(p, flags, stream);
-    if (p.rank <= 128) return wide ? launch_rb<8, 8>(p, flags, stream) : launch_rb<8, 4>(p, flags, stream);
-    return wide ? launch_rb<16, 8>(p, flags, stream) : launch_rb<16, 4>(p, flags, stream);
+    if (p.rank <= 32) return wide ? launch_rb<2, 8, true>(p, flags, stream) : launch_rb<2, 4, true>(p, flags, stream);
+    if (p.rank <= 64) return wide ? launch_rb<4, 8, false>(p, flags, stream) : launch_rb<4, 4, false>(p, flags, stream);
+    if (p.rank <= 128) {
+        // staged fragments cost a CU its second workgroup: worth it when K is long, or when the launch has no
+        // more workgroups than CUs anyway
+        const bool stage = p.G >= 96 || (p.M + 15) / 16 <= 256;
+        if (!wide) return launch_rb<8, 4, false>(p, flags, stream);
+        return stage ? launch_rb<8, 8, true>(p, flags, stream) : launch_rb<8, 8, false>(p, flags, stream);
+    }
+    return wide ? launch_rb<16, 8, false>(p, flags, stream) : launch_rb<16, 4, false>(p, flags, stream);
 }
 
 hipError_t launch_debug_act(const DebugActParams &p, hipStream_t stream) {
