@@ -170,7 +170,14 @@ def main():
                        gemm_ms_min=float(np.min(gemm)), act_ms_min=float(np.min(act)))
         return res
 
-    main_res = run(0, args.steps, args.warmup, split=True)
+    # The timed region proper: K forwards back to back, nothing else on the stream.  The per-kernel durations
+    # come from a second pass over the same K steps with three HIP events per step on the launch stream (one of
+    # them recorded by the library between its two kernels); the events cost a few microseconds per step, which
+    # is why they stay out of the pass that `value` is computed from.
+    timed = run(0, args.steps, args.warmup, split=False)
+    main_res = run(0, args.steps, min(args.warmup, 20), split=True)
+    main_res["ms_per_step_with_events"] = main_res["ms_per_step"]
+    main_res["ms_per_step"] = timed["ms_per_step"]
     ms = main_res["ms_per_step"]
     ops = float(case.ops)
     tops = ops / (ms * 1e-3) / 1e12
@@ -188,19 +195,21 @@ def main():
                                f"(BASELINE configs[3] up projection)", "tile": args.tile, "sets_rotated": nsets},
         "kernels": {"act_us": main_res["act_ms"] * 1e3, "gemm_us": main_res["gemm_ms"] * 1e3,
                     "gemm_us_min": main_res["gemm_ms_min"] * 1e3,
+                    "us_per_layer_with_events": main_res["ms_per_step_with_events"] * 1e3,
                     "act_GBps": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9,
                     "act_frac_hbm_peak": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (W4A4 GEMM + up projection epilogue)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (W4A4 GEMM + fused up projection, bias, bf16 store)",
                      "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
                      "note": "INT8 tera-ops/s: 2*M*N*K per launch / mean launch duration (HIP events on the launch stream)",
                      "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
                      "traffic": GEMM_TRAFFIC_BYTES if case.name == "flux_mlp_up" else None},
     }
     if args.breakdown:
-        naive = run(S.OPT_SKIP_LOWRANK, max(20, args.steps // 4), 5, split=False)
-        unfused = run(S.OPT_UNFUSED, max(20, args.steps // 4), 5, split=False)
+        naive = run(S.OPT_SKIP_LOWRANK, args.steps, 20, split=False)
+        unfused = run(S.OPT_UNFUSED, max(20, args.steps // 2), 20, split=False)
+        again = run(0, args.steps, 20, split=False)      # the fused path once more, after the others: drift check
         out["breakdown"] = {"fused_us": ms * 1e3, "naive_int4_us": naive["ms_per_step"] * 1e3,
-                            "unfused_us": unfused["ms_per_step"] * 1e3,
+                            "unfused_us": unfused["ms_per_step"] * 1e3, "fused_us_again": again["ms_per_step"] * 1e3,
                             "lowrank_overhead_fused": ms / naive["ms_per_step"] - 1.0,
                             "lowrank_overhead_unfused": unfused["ms_per_step"] / naive["ms_per_step"] - 1.0}
     S.svdq_forward_options(0)

@@ -119,7 +119,7 @@ size_t svdq_workspace_bytes(int M, const svdq_shape *shape);
  *   1. activation kernel: reads X once; smoothing, per-group INT4 quantization with fp16 scales,
  *      and the down projection H = X^ L1
  *   2. W4A4 GEMM: INT4 -> INT8 MFMA with exact int32 sums per group of 64, fp32 rescale by
- *      s_x s_w, then H L2, bias and the bf16 store in the epilogue.
+ *      s_x s_w, accumulated on top of H L2 in the same registers; bias and the bf16 store.
  *   X  device bf16 [M x K] row-major, 16-byte aligned;  Y device bf16 [M x N] row-major.
  *   workspace: device, 256-byte aligned, >= svdq_workspace_bytes(M, shape); contents are
  *   overwritten; two forwards that share a workspace must be ordered on one stream.

@@ -154,7 +154,7 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
         e = svdq::launch_gemm(g, tile, stream);
         if (e != hipSuccess) return hip_fail(e);
         if (lowrank) {
-            e = svdq::launch_upproj(a.H, g.l2t, g.Y, M, s.N, s.rank, stream);
+            e = svdq::launch_upproj(a.hfrag, g.l2t, g.Y, M, s.N, s.rank, stream);
             if (e != hipSuccess) return hip_fail(e);
         }
     }

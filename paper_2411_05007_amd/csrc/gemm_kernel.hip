@@ -525,16 +525,43 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-// Separate up projection for the unfused baseline: Y += H L2 as its own read-modify-write pass.
-__global__ __launch_bounds__(256) void upproj_kernel(const float *H, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank) {
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    const int m = blockIdx.y;
-    if (n >= N || m >= M) return;
-    float acc = 0.f;
-    for (int j = 0; j < rank; ++j)
-        acc = __builtin_fmaf(H[(size_t)m * rank + j], __uint_as_float((uint32_t)l2t[(size_t)n * rank + j] << 16), acc);
-    const size_t idx = (size_t)m * N + n;
-    Y[idx] = (uint16_t)bf16_rne_bits(__uint_as_float((uint32_t)Y[idx] << 16) + acc);
+// Separate up projection for the unfused baseline (Fig. 6a): Y += H L2 as its own pass that reads and rewrites
+// the 16-bit output.  Same arithmetic as the fused branch (bf16 MFMAs on the hi and lo parts of H); a wavefront
+// owns 32 rows x 64 columns, a workgroup four such blocks side by side.
+__global__ __launch_bounds__(256) void upproj_kernel(const uint8_t *hfrag, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int ksteps = rank / 16;
+    const int n0 = (blockIdx.x * 4 + wave) * 64;
+    const int m0 = blockIdx.y * 32;
+    floatx16 acc[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+    const uint8_t *hf = hfrag + (size_t)blockIdx.y * ksteps * 2048 + lane * 16;
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const bf16x8 hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(hf + (size_t)ks * 2048));
+        const bf16x8 lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(hf + (size_t)ks * 2048 + 1024));
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int col = n0 + c * 32 + li;       // < Npad: l2t is padded
+            const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(l2t + (size_t)col * rank + ks * 16 + 8 * lh));
+            acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, bl, acc[c], 0, 0, 0);
+            acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, bl, acc[c], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + 8 * (v >> 2) + 4 * lh + (v & 3);
+            const int col = n0 + c * 32 + li;
+            if (row < M && col < N) {
+                const size_t idx = (size_t)row * N + col;
+                Y[idx] = (uint16_t)bf16_rne_bits(__uint_as_float((uint32_t)Y[idx] << 16) + acc[c][v]);
+            }
+        }
 }
 
 }  // namespace
@@ -551,10 +578,10 @@ hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream) {
     }
 }
 
-hipError_t launch_upproj(const float *H, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank, hipStream_t stream) {
+hipError_t launch_upproj(const uint8_t *hfrag, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank, hipStream_t stream) {
     if (M <= 0 || rank <= 0) return hipSuccess;
-    const dim3 grid((N + 255) / 256, M), block(256);
-    hipLaunchKernelGGL(upproj_kernel, grid, block, 0, stream, H, l2t, Y, M, N, rank);
+    const dim3 grid((N + 255) / 256, (M + 31) / 32), block(256);
+    hipLaunchKernelGGL(upproj_kernel, grid, block, 0, stream, hfrag, l2t, Y, M, N, rank);
     return hipGetLastError();
 }
 

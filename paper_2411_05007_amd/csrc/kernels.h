@@ -36,7 +36,7 @@ struct GemmParams {
     const uint16_t *l2t;     // bf16 [Npad][rank]
     const float *bias;       // fp32 [Npad]
     uint16_t *Y;             // bf16 [M][N]
-    int M, N, K, G, Mpad, Npad, rank;   // rank == 0: no low-rank epilogue
+    int M, N, K, G, Mpad, Npad, rank;   // rank == 0: no low-rank branch
     int32_t *dbg;            // debug window of exact group sums, or null
     int m0, m1, n0, n1;
     int magic;               // kMagicBits, passed at run time so it stays in registers
@@ -49,7 +49,7 @@ struct GemmParams {
 hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream);
 
 // Y[m][n] += sum_j H[m][j] L2[j][n]  as a separate read-modify-write pass (unfused baseline only)
-hipError_t launch_upproj(const float *H, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank, hipStream_t stream);
+hipError_t launch_upproj(const uint8_t *hfrag, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank, hipStream_t stream);
 
 struct DebugActParams {
     const uint8_t *codes;

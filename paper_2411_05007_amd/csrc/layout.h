@@ -29,7 +29,7 @@
 //   l1s  [G][2 (k step)][rank/16 (column block)][64 (lane)][8]  - B operand of
 //        v_mfma_f32_16x16x32_bf16 in the activation kernel: lane l, element e of k step s holds
 //        L1s[64 g + 16 (l / 16) + 8 s + e][16 c + l % 16]
-//   l2   [Npad][rank]  (L2 transposed) - B operand of v_mfma_f32_32x32x16_bf16 in the GEMM epilogue.
+//   l2   [Npad][rank]  (L2 transposed) - B operand of v_mfma_f32_32x32x16_bf16 in the GEMM (up projection).
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
