@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "buffer.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -28,6 +29,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -84,9 +86,18 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     const int g0 = wave * per, g1 = (g0 + per < p.G) ? g0 + per : p.G;
     const int npairs = g0 < g1 ? (g1 - g0 + 1) / 2 : 0;
 
+    // All global traffic of the loop goes through buffer descriptors: a per-lane byte offset fixed for the whole
+    // kernel plus a scalar offset per group, so that addressing costs no vector instructions.
     // rows past M read the last row; what they produce lands in padding rows and is never used
-    const uint16_t *xa = p.X + (size_t)(ma < p.M ? ma : p.M - 1) * p.K + 8 * c8;
-    const uint16_t *xb = p.X + (size_t)(mb < p.M ? mb : p.M - 1) * p.K + 8 * c8;
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.X, (size_t)p.M * p.K * 2);
+    const __amdgpu_buffer_rsrc_t rs_l = make_rsrc(p.l1s, (size_t)p.K * p.rank * 2);
+    const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, (size_t)p.G * p.Mpad * kActBytes);
+    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2);
+    const int vxa = ((ma < p.M ? ma : p.M - 1) * p.K + 8 * c8) * 2;
+    const int vxb = ((mb < p.M ? mb : p.M - 1) * p.K + 8 * c8) * 2;
+    const int vca = (int)act_chunk_offset(0, p.Mpad, ma, c8 >> 1) + 8 * (c8 & 1);
+    const int vcb = (int)act_chunk_offset(0, p.Mpad, mb, c8 >> 1) + 8 * (c8 & 1);
+    const int vsx = ((c8 & 1) ? mb : ma) * 2;
     struct XStage { uint4 x0, x1; };                   // 8 bf16 activations of token r8 and of token r8 + 8
     struct BStage { uint4 b[PROJ ? 2 * RBMAX : 1]; };  // L1s fragments: k steps 0 and 1 of every 16-column block
     // STAGE: the fragments of the next two groups wait in registers (at rank 128 this fills the register file
@@ -97,19 +108,19 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     auto clampg = [&](int g) { return g < g1 ? g : g1 - 1; };
     auto fetch_x = [&](int g) {
         XStage s;
-        s.x0 = *reinterpret_cast<const uint4 *>(xa + 64 * g);
-        s.x1 = *reinterpret_cast<const uint4 *>(xb + 64 * g);
+        s.x0 = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, vxa, g * 128, 0));
+        s.x1 = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, vxb, g * 128, 0));
         return s;
     };
     auto fetch_b = [&](int g) {
         BStage s;
         if (kStageB) {
-            const uint4 *lp = reinterpret_cast<const uint4 *>(p.l1s) + ((size_t)g * 2 * rb) * 64 + lane;
+            const int sg = g * 2 * rb * 1024;
 #pragma unroll
             for (int c = 0; c < RBMAX; ++c) {
                 const int cc = c < rb ? c : rb - 1;      // blocks past the rank repeat the last one (branch-free); their sums are dropped
-                s.b[2 * c] = lp[(size_t)cc * 64];
-                s.b[2 * c + 1] = lp[(size_t)(rb + cc) * 64];
+                s.b[2 * c] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_l, lane * 16, sg + cc * 1024, 0));
+                s.b[2 * c + 1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_l, lane * 16, sg + (rb + cc) * 1024, 0));
             }
         }
         return s;
@@ -161,7 +172,7 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
             const uint4 *ap = reinterpret_cast<const uint4 *>(wlds + row * L::kXRow + 32 * blk);
             uint4 x0 = ap[0], x1 = ap[1];
             if (!real) x0 = x1 = make_uint4(0u, 0u, 0u, 0u);     // the repeated group of an odd run adds nothing to H
-            const uint4 *lp = reinterpret_cast<const uint4 *>(p.l1s) + ((size_t)g * 2 * rb) * 64 + lane;
+            const int sg = g * 2 * rb * 1024;
             // unstaged ranks: at most eight column blocks (sixteen fragments) are requested at a time
             constexpr int kChunk = RBMAX < 8 ? RBMAX : 8;
 #pragma unroll
@@ -171,8 +182,8 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
 #pragma unroll
                     for (int c = 0; c < kChunk; ++c) {
                         const int cc = c0 + c < rb ? c0 + c : rb - 1;
-                        late[kStageB ? 0 : 2 * c] = lp[(size_t)cc * 64];
-                        late[kStageB ? 0 : 2 * c + 1] = lp[(size_t)(rb + cc) * 64];
+                        late[kStageB ? 0 : 2 * c] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_l, lane * 16, sg + cc * 1024, 0));
+                        late[kStageB ? 0 : 2 * c + 1] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_l, lane * 16, sg + (rb + cc) * 1024, 0));
                     }
                     __builtin_amdgcn_sched_barrier(0);      // all requests go out before the first MFMA waits for its pair
                 }
@@ -220,11 +231,20 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
 #pragma unroll
         for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xh[e]));
         amax = max_over_8_lanes(amax);
-        float s32 = amax / 7.0f;
+        // amax / 7.0f and 1.0f / s, both correctly rounded like the IEEE divisions they stand for, in three
+        // instructions each: a product with the rounded reciprocal (1/7 as a constant, v_rcp_f32 for s, good to
+        // one ulp), the exact remainder by FMA, one correction by FMA.  For the division by 7 this equals the
+        // IEEE quotient for every finite fp32 numerator, and for 1/s for every positive fp16 s even from a
+        // start two ulps off (both checked exhaustively on the host).
+        constexpr float kInv7 = 0x1.24924ap-3f;                  // 1.0f / 7.0f
+        const float q0 = amax * kInv7;
+        float s32 = __builtin_fmaf(__builtin_fmaf(-7.0f, q0, amax), kInv7, q0);
         s32 = fminf(s32, 65504.0f);
         const _Float16 sh = (_Float16)s32;
         const float sc = (float)sh;
-        const float rcp_any = 1.0f / (sc > 0.f ? sc : 1.0f);     // branch-free: the division always runs
+        const float den = sc > 0.f ? sc : 1.0f;                  // branch-free: the reciprocal always runs
+        const float y0 = __builtin_amdgcn_rcpf(den);
+        const float rcp_any = __builtin_fmaf(__builtin_fmaf(-den, y0, 1.0f), y0, y0);
         const float rcp = sc > 0.f ? rcp_any : 0.f;
         uint32_t w[2] = {0u, 0u};
 #pragma unroll
@@ -245,9 +265,10 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
             // Unconditional stores: rows past M land in the padding rows of the workspace (it is sized for
             // Mpad rows); each store instruction fills four whole 128-byte lines.  Even lanes write the
             // scale of token r8, odd lanes that of token r8 + 8 (four lanes each, the same value).
-            *reinterpret_cast<uint2 *>(p.codes + act_chunk_offset(g, p.Mpad, ma, c8 >> 1) + 8 * (c8 & 1)) = ca;
-            *reinterpret_cast<uint2 *>(p.codes + act_chunk_offset(g, p.Mpad, mb, c8 >> 1) + 8 * (c8 & 1)) = cb;
-            p.sx[(size_t)g * p.Mpad + ((c8 & 1) ? mb : ma)] = (c8 & 1) ? sb : sa;
+            const int sc = g * p.Mpad * kActBytes;      // one group of codes: Mpad rows of 64 bytes
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{ca.x, ca.y}, rs_c, vca, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{cb.x, cb.y}, rs_c, vcb, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b16((c8 & 1) ? sb : sa, rs_s, vsx, g * p.Mpad * 2, 0);
         }
     };
 

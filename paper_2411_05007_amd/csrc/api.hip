@@ -107,6 +107,9 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     const svdq_shape &s = L->shape;
     const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
+    // the kernels address X, the activation codes and the weight codes with 32-bit byte offsets
+    if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
+        return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     const int opts = g_options.load();

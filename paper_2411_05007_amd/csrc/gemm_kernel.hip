@@ -31,6 +31,7 @@
 #include <stdint.h>
 #include <type_traits>
 
+#include "buffer.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -57,14 +58,6 @@ __device__ __forceinline__ uint32_t bf16_rne_pair(float lo, float hi) {
     v[0] = (__bf16)lo;
     v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
-}
-
-// A raw buffer descriptor over [base, base + bytes): loads take a per-thread byte offset in a VGPR and a
-// uniform byte offset in an SGPR, so walking the K dimension costs scalar adds only, and reads past the
-// end return zero instead of faulting.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, size_t bytes) {
-    const uint32_t n = bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes;
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)n, 0x00020000);
 }
 
 template <int BM, int BN>
