@@ -111,7 +111,8 @@ def test_oracle_prepared_layer_via_pack(torch):
 
 
 @pytest.mark.parametrize("M,K,N,r", [(1, 64, 16, 16), (17, 128, 48, 16), (100, 256, 80, 32), (257, 192, 272, 48),
-                                     (300, 320, 1040, 64), (130, 1152, 144, 128), (64, 128, 64, 0)])
+                                     (300, 320, 1040, 64), (130, 1152, 144, 128), (64, 128, 64, 0),
+                                     (90, 512, 256, 256), (40, 3072, 256, 112)])
 def test_ragged_shapes(torch, M, K, N, r):
     rng = np.random.default_rng(1000 + M + K + N)
     x = rng.standard_normal((M, K)).astype(np.float32)
@@ -222,10 +223,12 @@ def test_full_size_layers_on_sampled_rows(torch, name):
     _run_and_compare(torch, L["x_bf16"], prep, rows=rows, what=name)
 
 
-@pytest.mark.parametrize("name", ["flux_block_out_M4608_r128", "flux_block_mlp_up_M512_r32", "flux_block_mlp_down_M512_r128",
-                                  "flux_block_qkv_M512_r128"])
+SWEEP = [f"flux_block_{layer}_M{M}_r{r}" for M in (4608, 512) for r in (32, 128) for layer in ("qkv", "out", "mlp_up", "mlp_down")]
+
+
+@pytest.mark.parametrize("name", SWEEP)
 def test_block_sweep_cases_on_sampled_rows(torch, name):
-    """A spread of BASELINE config 5 (M in {4608, 512}, r in {32, 128})."""
+    """All sixteen cases of BASELINE config 5 (M in {4608, 512}, r in {32, 128}, four layers)."""
     case = I.case_by_name(name)
     _say(f"{name}: M={case.M} K={case.K} N={case.N} r={case.rank}: generating")
     L = I.make_layer(case)

@@ -156,6 +156,17 @@ def test_shape_errors_and_workspace_size(lib):
     assert lib.svdq_linear_forward(C.byref(bad), None, 4, None, None, 0, None) == -1
     assert lib.svdq_linear_forward(None, None, 4, None, None, 0, None) == -1
     assert lib.svdq_forward_options(-1) == 0
+    # a batch beyond the kernels' 32-bit offsets is refused, not launched: 2^31 activation elements per call
+    # (the pointers are never dereferenced: the size checks come first)
+    fake = S.LayerDev()
+    for name in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias"):
+        setattr(fake, name, 0x1000)
+    fake.shape = S.make_shape(12288, 3072, 32)
+    big = 2 ** 31 // 12288 + 1
+    assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), big, C.c_void_p(0x1000), C.c_void_p(0x1000),
+                                   C.c_size_t(1 << 62), None) == -2
+    assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), big, C.c_void_p(0x1000), C.c_void_p(0x1000),
+                                   C.c_size_t(1 << 20), None) == -4
 
 
 def test_fp16_and_bf16_roundings_of_the_library_match_numpy(lib):
