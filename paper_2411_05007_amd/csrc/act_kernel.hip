@@ -93,8 +93,9 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     const __amdgpu_buffer_rsrc_t rs_l = make_rsrc(p.l1s, (size_t)p.K * p.rank * 2);
     const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, (size_t)p.G * p.Mpad * kActBytes);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2);
-    const int vxa = ((ma < p.M ? ma : p.M - 1) * p.K + 8 * c8) * 2;
-    const int vxb = ((mb < p.M ? mb : p.M - 1) * p.K + 8 * c8) * 2;
+    // (byte offsets below 2^32: the entry point refuses batches of 2^31 elements or more; unsigned on purpose)
+    const int vxa = (int)(((uint32_t)(ma < p.M ? ma : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
+    const int vxb = (int)(((uint32_t)(mb < p.M ? mb : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
     const int vca = (int)act_chunk_offset(0, p.Mpad, ma, c8 >> 1) + 8 * (c8 & 1);
     const int vcb = (int)act_chunk_offset(0, p.Mpad, mb, c8 >> 1) + 8 * (c8 & 1);
     const int vsx = ((c8 & 1) ? mb : ma) * 2;
