@@ -154,6 +154,37 @@ def test_small_launches_with_split_k_loop(torch, M, K, N, r):
         assert torch.equal(first.view(torch.int16), again.view(torch.int16))
 
 
+def test_activation_scales_over_the_whole_fp16_range(torch):
+    """Groups whose maximum spans 2^-30 .. 2^20: scales that are zero, fp16 subnormal, normal and saturated at
+    65504 (Eq. 1 with the readings for degenerate groups).  Codes and scales must still match bit for bit, which
+    exercises the kernel's short division sequences against the oracle's IEEE divisions over every binade."""
+    rng = np.random.default_rng(424242)
+    M, K, N, r = 96, 2048, 64, 16
+    mag = np.exp2(rng.uniform(-30, 20, size=(M, K // 64)))                       # one magnitude per token and group
+    x = rng.standard_normal((M, K)) * np.repeat(mag, 64, axis=1)
+    x[5, 128:192] = 0.0
+    xb = O.bf16_round(x.astype(np.float32))
+    rinv = np.exp2(rng.uniform(-3, 3, size=K)).astype(np.float32)                 # arbitrary fp32 smoothing factors
+    qw = rng.integers(-7, 8, size=(K, N)).astype(np.int8)
+    sw = rng.uniform(1e-3, 2e-3, size=(K // 64, N)).astype(np.float16)
+    l1 = O.bf16_round((rng.standard_normal((K, r)) * 1e-3).astype(np.float32))
+    l2 = O.bf16_round((rng.standard_normal((r, N)) * 1e-3).astype(np.float32))
+    prep = S.svdq_pack(rinv, l1, l2, qw, sw, None)
+    S.svdq_forward_options(0)
+    layer = S.DeviceLayer(prep)
+    y = layer.forward(S.bf16_tensor_from_bits(xb))
+    torch.cuda.synchronize()
+    ref = O.forward(xb, S.svdq_unpack(prep))
+    codes, sx, _ = layer.debug_act()
+    sxb = ref["sx"].view(np.uint16)
+    _say(f"  scale classes: zero {int((sxb == 0).sum())}, subnormal {int(((sxb > 0) & (sxb < 0x400)).sum())}, "
+         f"saturated {int((sxb == 0x7BFF).sum())}, of {sxb.size}")
+    assert (sxb == 0).any() and ((sxb > 0) & (sxb < 0x400)).any() and (sxb == 0x7BFF).any()
+    assert np.array_equal(sx.view(np.uint16), sxb)
+    assert np.array_equal(codes, ref["qx"])
+    assert np.all(np.isfinite(O.bf16_to_f32(S.bits_from_bf16_tensor(y))))
+
+
 @pytest.mark.parametrize("tile", [1, 2, 3, 4])
 def test_every_gemm_tile_configuration(torch, tile):
     case = I.case_by_name("tiny")
