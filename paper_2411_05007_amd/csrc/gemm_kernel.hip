@@ -292,14 +292,14 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         intx16 da, db;
         // sub-tiles in the order (0,0) (1,0) (1,1) (0,1): the weight fragments of column block 0 fall free first.
         // The issue arbiter of a SIMD serves the older of its two wavefronts first, which starves the younger
-        // one for as long as they live together; a wavefront therefore walks its own priority 2, 1, 0, 1 over
+        // one for as long as they live together; a wavefront therefore walks its own priority 3, 2, 0, 1 over
         // the four sub-tiles, so that two wavefronts at different points of the loop take turns (measured:
         // 1 % on the large shapes, 4-7 % on launches where the two never swap roles).
-        __builtin_amdgcn_s_setprio(2);
+        __builtin_amdgcn_s_setprio(3);
         da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][0], bf[0][0], magic, 0, 0, 0);
         da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][1], bf[0][1], da, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_setprio(1);
+        __builtin_amdgcn_s_setprio(2);
         db = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][0], bf[0][0], magic, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         rescale_half(sc, da, 0, 0, H0{});
