@@ -403,6 +403,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     __syncthreads();
     read_b(0, 0); read_b(0, 1);
     read_scales(sce, 0);
+    __syncthreads();      // the first iteration refills slot 0: every wavefront must have taken the first group out of it
     {
         using Even = std::integral_constant<int, 0>;
         using Odd = std::integral_constant<int, 1>;
