@@ -243,7 +243,8 @@ FULL = ["pixart_ffn_up", "pixart_ffn_down", "flux_qkv", "flux_mlp_up", "flux_mlp
 
 @pytest.mark.parametrize("name", FULL)
 def test_full_size_layers_on_sampled_rows(torch, name):
-    """BASELINE configs 2-4 at full size, in the launch configuration bench.py times; the oracle
+    """The PixArt FFN pair, the FLUX QKV projection and the FLUX MLP pair at full size, in the launch configuration
+    bench.py times; the oracle
     evaluates a seeded sample of rows (rows are independent) over all N columns."""
     case = I.case_by_name(name)
     _say(f"{name}: M={case.M} K={case.K} N={case.N} r={case.rank}: generating")
@@ -259,7 +260,7 @@ SWEEP = [f"flux_block_{layer}_M{M}_r{r}" for M in (4608, 512) for r in (32, 128)
 
 @pytest.mark.parametrize("name", SWEEP)
 def test_block_sweep_cases_on_sampled_rows(torch, name):
-    """All sixteen cases of BASELINE config 5 (M in {4608, 512}, r in {32, 128}, four layers)."""
+    """All sixteen cases of the FLUX block sweep (M in {4608, 512}, r in {32, 128}, four layers)."""
     case = I.case_by_name(name)
     _say(f"{name}: M={case.M} K={case.K} N={case.N} r={case.rank}: generating")
     L = I.make_layer(case)
