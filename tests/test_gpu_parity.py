@@ -154,6 +154,29 @@ def test_small_launches_with_split_k_loop(torch, M, K, N, r):
         assert torch.equal(first.view(torch.int16), again.view(torch.int16))
 
 
+def test_seeded_random_shapes(torch):
+    """Thirty seeded shapes (M 1..5000, K 64..4416, N 16..5000, rank 0..256, every third one large): canonical
+    layers packed straight from random codes and scales, all rows compared with the oracle."""
+    rng = np.random.default_rng(20241105)
+    for it in range(30):
+        big = it % 3 == 0
+        K = 64 * int(rng.integers(1, 20 if big else 70))
+        N = 128 * int(rng.integers(8, 40)) if big else 16 * int(rng.integers(1, 40))
+        M = int(rng.integers(1500, 5000)) if big else int(rng.integers(1, 700))
+        r = 16 * int(rng.integers(0, min(K, N, 256) // 16 + 1))
+        x = rng.standard_normal((M, K)).astype(np.float32)
+        x[:, rng.choice(K, max(1, K // 100), replace=False)] *= 50
+        xb = O.bf16_round(x)
+        qw = rng.integers(-7, 8, size=(K, N)).astype(np.int8)
+        sw = rng.uniform(5e-4, 4e-3, size=(K // 64, N)).astype(np.float16)
+        rinv = np.exp2(rng.uniform(-2, 2, size=K)).astype(np.float32)
+        l1 = O.bf16_round((rng.standard_normal((K, r)) * 0.02).astype(np.float32)) if r else np.zeros((K, 0), np.uint16)
+        l2 = O.bf16_round((rng.standard_normal((r, N)) * 0.05).astype(np.float32)) if r else np.zeros((0, N), np.uint16)
+        prep = S.svdq_pack(rinv, l1, l2, qw, sw, rng.standard_normal(N).astype(np.float32))
+        _say(f"random shape {it}: M={M} K={K} N={N} r={r}")
+        _run_and_compare(torch, xb, prep, what=f"random {M}x{K}x{N} r{r}", window=M >= 3 and N >= 16)
+
+
 def test_activation_scales_over_the_whole_fp16_range(torch):
     """Groups whose maximum spans 2^-30 .. 2^20: scales that are zero, fp16 subnormal, normal and saturated at
     65504 (Eq. 1 with the readings for degenerate groups).  Codes and scales must still match bit for bit, which
