@@ -261,6 +261,44 @@ def test_deterministic_and_stream_ordered(torch):
         layer.forward(x, workspace=small)
 
 
+@pytest.mark.parametrize("M,K,N,r", [(300, 1152, 656, 32), (100, 3072, 272, 32)])
+def test_forward_replayed_from_a_hip_graph(torch, M, K, N, r):
+    """The forward only enqueues kernels, so a caller may capture it.  Every replay, with eager work and
+    synchronisations in between, must reproduce the eager result bit for bit; the second shape runs with the
+    K loop split, whose arrival counters have to be left ready by each replay."""
+    rng = np.random.default_rng(99 + M)
+    xb = O.bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    qw = rng.integers(-7, 8, size=(K, N)).astype(np.int8)
+    sw = rng.uniform(5e-4, 4e-3, size=(K // 64, N)).astype(np.float16)
+    l1 = O.bf16_round((rng.standard_normal((K, r)) * 0.02).astype(np.float32))
+    l2 = O.bf16_round((rng.standard_normal((r, N)) * 0.05).astype(np.float32))
+    prep = S.svdq_pack(np.ones(K, np.float32), l1, l2, qw, sw, rng.standard_normal(N).astype(np.float32))
+    S.svdq_forward_options(0)
+    layer = S.DeviceLayer(prep)
+    x = S.bf16_tensor_from_bits(xb)
+    ws = layer.workspace(M)
+    eager = layer.forward(x, workspace=ws).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    y = torch.empty_like(eager)
+    with torch.cuda.stream(side):
+        layer.forward(x, out=y, workspace=ws, stream=side)      # warm-up on the capture stream
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            layer.forward(x, out=y, workspace=ws, stream=side)
+            layer.forward(x, out=y, workspace=ws, stream=side)
+    for _ in range(4):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), eager.view(torch.int16))
+        again = layer.forward(x, workspace=ws)                  # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(again.view(torch.int16), eager.view(torch.int16))
+
+
 FULL = ["pixart_ffn_up", "pixart_ffn_down", "flux_qkv", "flux_mlp_up", "flux_mlp_down"]
 
 
