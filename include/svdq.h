@@ -126,7 +126,9 @@ size_t svdq_workspace_bytes(int M, const svdq_shape *shape);
  *   M = 0 is a no-op.  hip_stream is a hipStream_t (NULL = the default stream).
  *   One call handles up to 2^31 activation elements (M padded to 256, times K); larger batches
  *   return SVDQ_EUNSUPPORTED and have to be split by the caller (rows are independent).
- *   K above 32768 is not supported either (SVDQ_EUNSUPPORTED).
+ *   The activation kernel keeps the K smoothing factors in LDS beside its per-wavefront blocks: K up to
+ *   32768 is supported for rank <= 64, up to 32704 for rank <= 128 and up to 24512 for rank <= 256;
+ *   beyond that the call returns SVDQ_EUNSUPPORTED.
  */
 int svdq_linear_forward(const svdq_layer_dev *layer, const void *X, int M, void *Y,
                         void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -387,7 +387,7 @@ __global__ void debug_act_kernel(DebugActParams p) {
 hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
     // wavefronts per 16-token slice: more of them when K is long enough to give each a few groups
-    const bool wide = p.G >= 32;
+    const bool wide = act_waves(p.K, p.rank) == 8;
     if (p.rank <= 32) return wide ? launch_rb<2, 8, true>(p, flags, stream) : launch_rb<2, 4, true>(p, flags, stream);
     if (p.rank <= 64) return wide ? launch_rb<4, 8, false>(p, flags, stream) : launch_rb<4, 4, false>(p, flags, stream);
     if (p.rank <= 128) {

@@ -107,8 +107,9 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     const svdq_shape &s = L->shape;
     const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    // the activation kernel keeps 1 / lambda of all K channels in LDS (4 K bytes of the CU's 160 KB)
-    if (s.K > 32768) return SVDQ_EUNSUPPORTED;
+    // the activation kernel keeps 1 / lambda of all K channels in LDS beside its per-wavefront blocks
+    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+        return SVDQ_EUNSUPPORTED;
     // the kernels address X, the activation codes and the weight codes with 32-bit byte offsets
     if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
         return SVDQ_EUNSUPPORTED;

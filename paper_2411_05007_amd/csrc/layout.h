@@ -115,6 +115,17 @@ inline GemmPlan plan_gemm(int M, int N, int G, int ksplit_override = 0) {
     return pl;
 }
 
+// LDS bytes of one activation-kernel workgroup with `waves` wavefronts: 1 / lambda of all K channels (fp32), plus
+// one private block per wavefront (X turn-around during the loop, partial H at the end).
+constexpr int kLdsBytesPerCU = 160 * 1024;
+inline size_t act_lds_bytes(int K, int rank, int waves) {
+    const int rbmax = rank <= 32 ? 2 : rank <= 64 ? 4 : rank <= 128 ? 8 : 16;
+    const size_t red = (size_t)16 * (rbmax * 16 + 1) * 4;
+    return (size_t)K * 4 + (size_t)waves * (red > 2304 ? red : 2304);
+}
+// Wavefronts per 16-token slice: eight when K gives each of them a few groups and their LDS fits, else four.
+inline int act_waves(int K, int rank) { return (K / kGroup >= 32 && act_lds_bytes(K, rank, 8) <= (size_t)kLdsBytesPerCU) ? 8 : 4; }
+
 // Workspace carve-up for a forward of M tokens.
 struct Workspace {
     size_t codes_off, sx_off, h_off, hfrag_off, counters_off, partial_off, total;

@@ -112,7 +112,7 @@ def test_oracle_prepared_layer_via_pack(torch):
 
 @pytest.mark.parametrize("M,K,N,r", [(1, 64, 16, 16), (17, 128, 48, 16), (100, 256, 80, 32), (257, 192, 272, 48),
                                      (300, 320, 1040, 64), (130, 1152, 144, 128), (64, 128, 64, 0),
-                                     (90, 512, 256, 256), (40, 3072, 256, 112)])
+                                     (90, 512, 256, 256), (40, 3072, 256, 112), (33, 3072, 256, 256), (20, 12288, 256, 256)])
 def test_ragged_shapes(torch, M, K, N, r):
     rng = np.random.default_rng(1000 + M + K + N)
     x = rng.standard_normal((M, K)).astype(np.float32)

@@ -167,10 +167,11 @@ def test_shape_errors_and_workspace_size(lib):
                                    C.c_size_t(1 << 62), None) == -2
     assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), big, C.c_void_p(0x1000), C.c_void_p(0x1000),
                                    C.c_size_t(1 << 20), None) == -4
-    # more input channels than the activation kernel can keep smoothing factors for
-    fake.shape = S.make_shape(32768 + 64, 3072, 32)
-    assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), 16, C.c_void_p(0x1000), C.c_void_p(0x1000),
-                                   C.c_size_t(1 << 62), None) == -2
+    # more input channels than the activation kernel can keep smoothing factors for (the limit depends on the rank)
+    for K, r in ((32768 + 64, 32), (32768, 128), (24576, 256)):
+        fake.shape = S.make_shape(K, 3072, r)
+        assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), 16, C.c_void_p(0x1000), C.c_void_p(0x1000),
+                                       C.c_size_t(1 << 62), None) == -2, (K, r)
 
 
 def test_fp16_and_bf16_roundings_of_the_library_match_numpy(lib):
