@@ -66,9 +66,9 @@ struct Tile {
     static constexpr int kWaves = kWavesM * kWavesN;
     static constexpr int kThreads = kWaves * 64;
     static constexpr int kSlot = BN * kLdsRow;                     // widened weight codes of one group
-    static constexpr int kSxOff = 2 * kSlot;                       // fp32 [ring][BM]
-    static constexpr int kSwOff = kSxOff + kScaleRing * BM * 4;    // float2 [ring][BN]
-    static constexpr int kLoopBytes = kSwOff + kScaleRing * BN * 8;
+    static constexpr int kScOff = 2 * kSlot;                       // float2 [ring][BM + BN]: activation scales of the rows, then weight scales of the columns
+    static constexpr int kLoopBytes = kScOff + kScaleRing * (BM + BN) * 8;
+    static constexpr int kNS = (BM + BN + kThreads - 1) / kThreads; // scale values per thread and group
     static constexpr int kOutBytes = kWaves * 32 * kOutRow;        // epilogue: one 32 x 64 bf16 block per wavefront
     static constexpr int kLdsBytes = kLoopBytes > kOutBytes ? kLoopBytes : kOutBytes;
     // staging split of the packed weight slab of one group (BN x 32 bytes): 16-byte granules if there are
@@ -76,7 +76,6 @@ struct Tile {
     static constexpr int kGranB = (BN * 2 >= kThreads) ? 16 : 8;
     static constexpr int kNB = BN * 32 / kGranB / kThreads;
     static_assert(kNB >= 1 && kNB * kGranB * kThreads == BN * 32, "B slab must split evenly over the threads");
-    static_assert(kThreads >= BM && kThreads >= BN, "one thread per row / column stages the scales");
 };
 
 // MODE 0: normal forward.  MODE 1: additionally export exact group sums of a window (parity checks).
@@ -141,8 +140,24 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
 
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.xcodes, (size_t)p.G * p.Mpad * kActBytes);
     const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(p.wcodes, (size_t)p.G * p.Npad * kCodeBytes);
-    const __amdgpu_buffer_rsrc_t rs_sx = make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2);
-    const __amdgpu_buffer_rsrc_t rs_sw = make_rsrc(p.sw, (size_t)p.G * p.Npad * 2);
+    // The BM + BN scales of a group are staged one per thread: whole wavefronts take activation scales,
+    // the others weight scales, so a wavefront issues one small load per group instead of two.
+    __amdgpu_buffer_rsrc_t rs_sc[T::kNS];
+    int sc_voff[T::kNS], sc_base[T::kNS], sc_stride[T::kNS], sc_idx[T::kNS];
+    float sc_fac[T::kNS];
+#pragma unroll
+    for (int i = 0; i < T::kNS; ++i) {
+        // uniform per wavefront (BM and BN are multiples of 64); wavefronts beyond the last value repeat the first ones' share
+        const int first = (wave * 64 + i * T::kThreads) % (BM + BN);
+        const bool is_x = first < BM;
+        const int idx = first + lane;
+        sc_idx[i] = idx;
+        rs_sc[i] = is_x ? make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2) : make_rsrc(p.sw, (size_t)p.G * p.Npad * 2);
+        sc_voff[i] = (is_x ? idx : idx - BM) * 2;
+        sc_base[i] = (is_x ? gm0 : gn0) * 2;
+        sc_stride[i] = (is_x ? p.Mpad : p.Npad) * 2;
+        sc_fac[i] = is_x ? 1.0f : 0.00390625f;                         // sw * 2^-8: both operands carry a factor 16
+    }
 
     // ---- A fragments: memory -> registers, in the order the activation kernel wrote them -----------
     // xcodes[g][m / 32][j][lane][16 bytes]: one load instruction fetches one contiguous kilobyte
@@ -160,11 +175,10 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     // ---- B codes and both scales: memory -> registers -> LDS, shared by the workgroup --------------
     const int b_stride = p.Npad * kCodeBytes;
     const int b_base = gn0 * kCodeBytes;
-    const int xrow = tid % BM, wrow = tid % BN;
 
     struct Staged {                  // one group's share of this thread, on its way from memory to LDS
         u32x4 b[T::kNB];             // only .x/.y are used for 8-byte granules
-        uint32_t sx, sw;
+        uint32_t sc[T::kNS];
     };
     auto load_group = [&](int g) {
         Staged q;
@@ -175,8 +189,8 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
             if (T::kGranB == 16) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_b, tid * 16, sb + i * T::kThreads * 16, 0);
             else { const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs_b, tid * 8, sb + i * T::kThreads * 8, 0); rb[i].x = v.x; rb[i].y = v.y; }
         }
-        q.sx = __builtin_amdgcn_raw_buffer_load_b16(rs_sx, xrow * 2, (g * p.Mpad + gm0) * 2, 0);
-        q.sw = __builtin_amdgcn_raw_buffer_load_b16(rs_sw, wrow * 2, (g * p.Npad + gn0) * 2, 0);
+#pragma unroll
+        for (int i = 0; i < T::kNS; ++i) q.sc[i] = __builtin_amdgcn_raw_buffer_load_b16(rs_sc[i], sc_voff[i], sc_base[i] + g * sc_stride[i], 0);
         return q;
     };
 
@@ -200,12 +214,13 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
                 *reinterpret_cast<u32x4 *>(sb + (u >> 2) * kLdsRow + (u & 3) * 16) = lo;
             }
         }
-        float *ssx = reinterpret_cast<float *>(lds + T::kSxOff) + ring * BM;
-        float2 *ssw = reinterpret_cast<float2 *>(lds + T::kSwOff) + ring * BN;
         // the scales are converted once per workgroup: the rescale then runs on plain fp32 FMAs
-        ssx[xrow] = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sx);   // threads beyond BM / BN repeat the first ones' stores
-        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sw) * 0.00390625f;   // sw * 2^-8: both operands carry a factor 16
-        ssw[wrow] = make_float2(s, -kMagic * s);
+        float2 *ssc = reinterpret_cast<float2 *>(lds + T::kScOff) + ring * (BM + BN);
+#pragma unroll
+        for (int i = 0; i < T::kNS; ++i) {
+            const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sc[i]) * sc_fac[i];
+            ssc[sc_idx[i]] = make_float2(s, -kMagic * s);          // the second word is used for weight scales only
+        }
     };
 
     // ---- fragments and scales: LDS -> registers ---------------------------------------------------
@@ -226,12 +241,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     };
     const int sx_lane = wm0 + 8 * ((lane & 15) >> 2) + 4 * lh + (lane & 3);
     auto read_scales = [&](Scales &sc, int ring) {
-        const float *ssx = reinterpret_cast<const float *>(lds + T::kSxOff) + ring * BM;
-        const float2 *ssw = reinterpret_cast<const float2 *>(lds + T::kSwOff) + ring * BN;
+        const float2 *ssc = reinterpret_cast<const float2 *>(lds + T::kScOff) + ring * (BM + BN);
 #pragma unroll
-        for (int r = 0; r < 2; ++r) sc.sx[r] = ssx[sx_lane + r * 32];
+        for (int r = 0; r < 2; ++r) sc.sx[r] = ssc[sx_lane + r * 32].x;
 #pragma unroll
-        for (int c = 0; c < 2; ++c) sc.sw[c] = ssw[wn0 + c * 32 + li];
+        for (int c = 0; c < 2; ++c) sc.sw[c] = ssc[BM + wn0 + c * 32 + li];
     };
 
 // acc += bcast(sx, lane V of the row) * t
