@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="GEMM tile configuration id (0 = library default)")
     ap.add_argument("--breakdown", action="store_true", help="also time naive INT4 (no low-rank) and the unfused 4-kernel pipeline")
+    ap.add_argument("--lora", type=int, default=0, metavar="R",
+                    help="append a synthetic rank-R adapter to the layer's 16-bit branch (no re-quantization) and time that")
     ap.add_argument("--pmc-run", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a few forwards plus one plain copy of 256 MiB "
                          "(the known-size kernel the counters are scaled by), no timing, no JSON")
@@ -111,6 +113,11 @@ def main():
     case = I.case_by_name(args.case)
     L = I.make_layer(case)
     prep = S.svdq_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    if args.lora > 0:
+        rng = np.random.default_rng(241105999)
+        down = (rng.standard_normal((case.K, args.lora)) * 0.02).astype(np.float32)
+        up = (rng.standard_normal((args.lora, case.N)) * 0.02).astype(np.float32)
+        prep = S.svdq_append_lora(prep, down, up, 1.0)
     layer = S.DeviceLayer(prep, dev)
 
     # >= 3 independent (X, Y, workspace) sets so the footprint exceeds the 256 MB last-level cache
@@ -192,6 +199,7 @@ def main():
         "vs_baseline": None, "dtype": "int8 MFMA (int4 codes), int32 group sums, fp32 rescale, bf16 out",
         "data": "synthetic",
         "config": {"workload": f"{case.name}: M={case.M} K={case.K} N={case.N} r={case.rank} g=64"
+                               + (f" + LoRA r={args.lora} (branch rank {prep.shape.rank})" if args.lora else "")
                                + (" (the FLUX MLP up projection the metric is quoted on)" if case.name == "flux_mlp_up" else ""),
                    "tile": args.tile, "sets_rotated": nsets},
         "kernels": {"act_us": main_res["act_ms"] * 1e3, "gemm_us": main_res["gemm_ms"] * 1e3,

@@ -101,6 +101,24 @@ int svdq_unpack_wscales(const svdq_shape *shape, const uint16_t *wscales, uint16
 int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out /* bf16 [K x rank] */);
 int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out /* bf16 [rank x N] */);
 
+/*
+ * HOST.  Adds a low-rank adapter (LoRA) to a prepared layer WITHOUT re-quantizing it (Sec. 5.2,
+ * "Integrate with LoRA"): the adapter's factors are appended to the 16-bit branch, whose rank grows, so that
+ * the forward returns  Y + scale * X down up  at the price of the wider branch only.  The 4-bit residual, its
+ * scales, the smoothing factors and the bias are not touched and are shared with the original layer.
+ *   l1s, l2     native factors of the layer (may be NULL when shape->rank is 0)
+ *   down        host fp32 [K x r_add] row-major, applied to the UNSMOOTHED input like the layer's own l1s
+ *   up          host fp32 [r_add x N] row-major
+ *   scale       the adapter's strength (alpha / r in LoRA's notation), folded into `down` before rounding
+ *   out_shape   receives the shape of the new layer: rank = shape->rank + r_add rounded up to a multiple of 16
+ *   out_l1s, out_l2  host buffers of svdq_prepared_sizes(out_shape).l1s / .l2 bytes; both factors are
+ *               rounded to bf16 (RNE); padding columns are zero
+ * SVDQ_EUNSUPPORTED when the new rank exceeds 256 or min(K, N).
+ */
+int svdq_append_lora(const svdq_shape *shape, const uint16_t *l1s, const uint16_t *l2,
+                     const float *down, const float *up, int r_add, float scale,
+                     svdq_shape *out_shape, uint16_t *out_l1s, uint16_t *out_l2);
+
 /* Device copies of the native buffers of one layer (all DEVICE pointers, 16-byte aligned). */
 typedef struct {
     const void *rinv, *l1s, *l2, *wcodes, *wscales, *bias;

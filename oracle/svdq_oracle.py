@@ -275,6 +275,37 @@ def forward(x_bits: np.ndarray, prep: Dict[str, np.ndarray], want_group_sums: bo
 
 
 # --------------------------------------------------------------------------
+# low-rank adapters (Sec. 5.2, "Integrate with LoRA")
+# --------------------------------------------------------------------------
+
+def append_lora(prep: Dict[str, np.ndarray], down: np.ndarray, up: np.ndarray, scale: float = 1.0,
+                rank_multiple: int = 16) -> Dict[str, np.ndarray]:
+    """The layer with an adapter  scale * X down up  fused into its 16-bit branch by growing the rank.
+
+    The adapter acts on the unsmoothed input, exactly like the stored factor L1s = diag(lambda)^-1 L1, so its
+    down matrix is appended as it is (times the strength, then rounded to bf16); the up matrix is appended to
+    L2.  The 4-bit residual is left alone: no re-quantization.  The rank is padded with zero columns to a
+    multiple of ``rank_multiple``.
+    """
+    down = np.asarray(down, dtype=np.float32)
+    up = np.asarray(up, dtype=np.float32)
+    K, r = prep["l1s"].shape
+    N = prep["l2"].shape[1]
+    r_add = down.shape[1]
+    assert down.shape == (K, r_add) and up.shape == (r_add, N)
+    r_new = -(-(r + r_add) // rank_multiple) * rank_multiple
+    l1s = np.zeros((K, r_new), dtype=np.uint16)
+    l2 = np.zeros((r_new, N), dtype=np.uint16)
+    l1s[:, :r] = prep["l1s"]
+    l2[:r] = prep["l2"]
+    l1s[:, r:r + r_add] = bf16_round((np.float32(scale) * down).astype(np.float32))
+    l2[r:r + r_add] = bf16_round(up)
+    out = dict(prep)
+    out["l1s"], out["l2"] = l1s, l2
+    return out
+
+
+# --------------------------------------------------------------------------
 # error measures used by the paper's analysis (Sec. 4.1, Prop. 4.1 / 4.2)
 # --------------------------------------------------------------------------
 

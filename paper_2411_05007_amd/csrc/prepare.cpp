@@ -513,4 +513,38 @@ int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out) {
     return SVDQ_OK;
 }
 
+int svdq_append_lora(const svdq_shape *shape, const uint16_t *l1s, const uint16_t *l2, const float *down,
+                     const float *up, int r_add, float scale, svdq_shape *out_shape, uint16_t *out_l1s,
+                     uint16_t *out_l2) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!down || !up || !out_shape || r_add <= 0) return SVDQ_EINVAL;
+    if (shape->rank > 0 && (!l1s || !l2)) return SVDQ_EINVAL;
+    svdq_shape ns = *shape;
+    ns.rank = svdq::round_up(shape->rank + r_add, 16);
+    const int st2 = check_shape(&ns);
+    if (st2 != SVDQ_OK) return st2;
+    *out_shape = ns;
+    if (!out_l1s || !out_l2) return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, r = shape->rank, rn = ns.rank;
+    const int Np = svdq::round_up(N, kRowPad);
+    // columns [0, r): the layer's own factors; [r, r + r_add): the adapter; the rest (rank padding): zero
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < rn; ++j) {
+            uint16_t v = 0;
+            if (j < r) v = l1s[svdq::l1s_index(K, r, k, j)];
+            else if (j < r + r_add) v = f32_to_bf16(scale * down[(size_t)k * r_add + (j - r)]);
+            out_l1s[svdq::l1s_index(K, rn, k, j)] = v;
+        }
+    std::memset(out_l2, 0, (size_t)Np * rn * 2);
+    for (int n = 0; n < N; ++n)
+        for (int j = 0; j < rn; ++j) {
+            uint16_t v = 0;
+            if (j < r) v = l2[(size_t)n * r + j];
+            else if (j < r + r_add) v = f32_to_bf16(up[(size_t)(j - r) * N + n]);
+            out_l2[(size_t)n * rn + j] = v;
+        }
+    return SVDQ_OK;
+}
+
 }  // extern "C"

@@ -22,7 +22,7 @@ OPT_TILE_SHIFT = 8
 
 EXPORTS = [
     "svdq_status_string", "svdq_last_hip_error", "svdq_prepared_sizes", "svdq_prepare", "svdq_pack",
-    "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2",
+    "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2", "svdq_append_lora",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
     "svdq_forward_options", "svdq_profile_event",
 ]
@@ -66,6 +66,7 @@ def lib() -> C.CDLL:
         L.svdq_pack.argtypes = [C.POINTER(Shape)] + [vp] * 12
         for n in ("svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2"):
             getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
+        L.svdq_append_lora.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.c_int, C.c_float, C.POINTER(Shape), vp, vp]
         L.svdq_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_debug_group_acc.argtypes = [C.POINTER(LayerDev), vp, C.c_int] + [C.c_int] * 4 + [vp, vp]
@@ -164,6 +165,25 @@ def svdq_unpack(p: PreparedHost):
         _check(L.svdq_unpack_l1s(C.byref(p.shape), _ptr(p.l1s), _ptr(l1s)), "svdq_unpack_l1s")
         _check(L.svdq_unpack_l2(C.byref(p.shape), _ptr(p.l2), _ptr(l2)), "svdq_unpack_l2")
     return {"rinv": p.rinv.copy(), "l1s": l1s, "l2": l2, "qw": qw, "sw": sw.view(np.float16), "bias": p.bias[:N].copy()}
+
+
+def svdq_append_lora(p: PreparedHost, down: np.ndarray, up: np.ndarray, scale: float = 1.0) -> PreparedHost:
+    """A layer with the adapter `scale * down @ up` appended to its 16-bit branch; everything else is shared with `p`."""
+    down = np.ascontiguousarray(down, dtype=np.float32)
+    up = np.ascontiguousarray(up, dtype=np.float32)
+    r_add = down.shape[1]
+    assert down.shape == (p.shape.K, r_add) and up.shape == (r_add, p.shape.N)
+    has = p.shape.rank > 0
+    want = make_shape(p.shape.K, p.shape.N, (p.shape.rank + r_add + 15) // 16 * 16, p.shape.alpha)
+    sz = Sizes()
+    _check(lib().svdq_prepared_sizes(C.byref(want), C.byref(sz)), "svdq_prepared_sizes")
+    l1s = np.zeros(sz.l1s // 2, np.uint16)
+    l2 = np.zeros(sz.l2 // 2, np.uint16)
+    ns = Shape()
+    _check(lib().svdq_append_lora(C.byref(p.shape), _ptr(p.l1s) if has else None, _ptr(p.l2) if has else None, _ptr(down),
+                                  _ptr(up), r_add, float(scale), C.byref(ns), _ptr(l1s), _ptr(l2)), "svdq_append_lora")
+    assert ns.rank == want.rank
+    return PreparedHost(shape=ns, rinv=p.rinv, l1s=l1s, l2=l2, wcodes=p.wcodes, wscales=p.wscales, bias=p.bias)
 
 
 def svdq_forward_options(flags: int) -> int:

@@ -129,6 +129,39 @@ def test_ragged_shapes(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"ragged {M}x{K}x{N} r{r}", window=M >= 3 and N >= 16)
 
 
+@pytest.mark.parametrize("r,r_add", [(32, 16), (16, 5), (0, 32), (32, 96)])
+def test_lora_appended_without_requantization(torch, r, r_add):
+    """Sec. 5.2, "Integrate with LoRA": the adapter joins the 16-bit branch (rank r + r_add, padded to 16); the
+    library's appended factors must equal the oracle's bit for bit, the 4-bit buffers must be the original
+    ones, and the forward must match the oracle's forward of the oracle's appended layer."""
+    M, K, N = 150, 512, 400
+    rng = np.random.default_rng(4200 + r + r_add)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, 5, replace=False)] *= 50
+    xb = O.bf16_round(x)
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    ax = np.abs(O.bf16_to_f32(xb)).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    down = (rng.standard_normal((K, r_add)) * 0.05).astype(np.float32)
+    up = (rng.standard_normal((r_add, N)) * 0.05).astype(np.float32)
+    base = S.svdq_prepare(w, ax, r, bias=b)
+    tuned = S.svdq_append_lora(base, down, up, scale=0.8)
+    assert tuned.wcodes is base.wcodes and tuned.wscales is base.wscales and tuned.rinv is base.rinv
+    want = O.append_lora(S.svdq_unpack(base), down, up, scale=0.8)
+    got = S.svdq_unpack(tuned)
+    assert got["l1s"].shape == want["l1s"].shape == (K, (r + r_add + 15) // 16 * 16)
+    assert np.array_equal(got["l1s"], want["l1s"]) and np.array_equal(got["l2"], want["l2"])
+    _say(f"lora: r={r} + {r_add} -> {tuned.shape.rank}")
+    _run_and_compare(torch, xb, tuned, what=f"lora r{r}+{r_add}")
+    # and the adapter really changed the output by scale * X down up (to the rounding of the factors and of Y)
+    layer0, layer1 = S.DeviceLayer(base), S.DeviceLayer(tuned)
+    xt = S.bf16_tensor_from_bits(xb)
+    y0 = O.bf16_to_f32(S.bits_from_bf16_tensor(layer0.forward(xt))).astype(np.float64)
+    y1 = O.bf16_to_f32(S.bits_from_bf16_tensor(layer1.forward(xt))).astype(np.float64)
+    delta = 0.8 * (O.bf16_to_f32(xb).astype(np.float64) @ down.astype(np.float64) @ up.astype(np.float64))
+    assert np.linalg.norm((y1 - y0) - delta) <= 2e-2 * np.linalg.norm(delta) + 2.0 ** -7 * np.linalg.norm(y1)
+
+
 @pytest.mark.parametrize("M,K,N,r", [(100, 3072, 272, 32), (70, 3136, 144, 16), (200, 6144, 400, 48)])
 def test_small_launches_with_split_k_loop(torch, M, K, N, r):
     """Few tiles and a long K: the library splits the K loop over several workgroups per tile, which park fp32

@@ -191,3 +191,33 @@ def test_fp16_and_bf16_roundings_of_the_library_match_numpy(lib):
     qw, sw, _ = O.residual_codes_from_factors(w, U["rinv"], np.zeros((K, 0), np.uint16), np.zeros((0, N), np.uint16))
     assert np.array_equal(U["sw"].view(np.uint16), sw.view(np.uint16))
     assert np.array_equal(U["qw"], qw)
+
+
+def test_append_lora_matches_the_oracle_and_refuses_oversized_ranks(lib):
+    rng = np.random.default_rng(77)
+    K, N, r = 192, 80, 16
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    ax = np.abs(rng.standard_normal(K)).astype(np.float32) + 0.1
+    base = S.svdq_prepare(w, ax, r)
+    for r_add, scale in ((16, 1.0), (7, 0.3), (33, -2.0)):
+        down = rng.standard_normal((K, r_add)).astype(np.float32)
+        up = rng.standard_normal((r_add, N)).astype(np.float32)
+        tuned = S.svdq_append_lora(base, down, up, scale)
+        want = O.append_lora(S.svdq_unpack(base), down, up, scale)
+        got = S.svdq_unpack(tuned)
+        assert tuned.shape.rank == want["l1s"].shape[1] == (r + r_add + 15) // 16 * 16
+        assert np.array_equal(got["l1s"], want["l1s"]) and np.array_equal(got["l2"], want["l2"])
+        assert np.array_equal(got["qw"], want["qw"]) and np.array_equal(got["sw"].view(np.uint16), want["sw"].view(np.uint16))
+    # a layer without a low-rank branch gets one
+    plain = S.svdq_prepare(w, ax, 0)
+    tuned = S.svdq_append_lora(plain, down, up, 1.0)
+    assert tuned.shape.rank == 48 and np.array_equal(S.svdq_unpack(tuned)["l2"][:33], O.bf16_round(up))
+    # rank beyond min(K, N) = 80, and beyond 256
+    with pytest.raises(S.SvdqError):
+        S.svdq_append_lora(base, np.zeros((K, 70), np.float32), np.zeros((70, N), np.float32))
+    ns = S.Shape()
+    sh = S.make_shape(512, 512, 240)
+    z = np.zeros(512 * 512, np.uint16)
+    f = np.zeros(512 * 32, np.float32)
+    assert lib.svdq_append_lora(C.byref(sh), S._ptr(z), S._ptr(z), S._ptr(f), S._ptr(f), 32, C.c_float(1.0), C.byref(ns), S._ptr(z), S._ptr(z)) == -2
+    assert lib.svdq_append_lora(C.byref(sh), S._ptr(z), S._ptr(z), None, S._ptr(f), 16, C.c_float(1.0), C.byref(ns), S._ptr(z), S._ptr(z)) == -1

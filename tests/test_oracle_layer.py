@@ -158,6 +158,46 @@ def test_forward_equals_plain_definition_of_eq5():
     assert np.max(np.abs(O.bf16_to_f32(out["Y_bf16"]) - out["Y"]) / np.maximum(np.abs(out["Y"]), 1e-30)) <= 2.0 ** -8
 
 
+def test_lora_appended_to_the_lowrank_branch_adds_x_down_up_and_nothing_else():
+    """Sec. 5.2, "Integrate with LoRA": the adapter rides in the 16-bit branch; the 4-bit branch is not re-quantized."""
+    xb, w, b, ax = _small_layer(seed=11)
+    P = O.prepare(w, ax, rank=16, bias=b)
+    rng = np.random.default_rng(12)
+    r_add, scale = 5, 0.75                                   # a rank that is not a multiple of 16: padded with zeros
+    down = rng.standard_normal((w.shape[0], r_add)).astype(np.float32) * 0.05
+    up = rng.standard_normal((r_add, w.shape[1])).astype(np.float32) * 0.05
+    P2 = O.append_lora(P, down, up, scale)
+    assert P2["l1s"].shape == (w.shape[0], 32) and P2["l2"].shape == (32, w.shape[1])
+    assert np.array_equal(P2["l1s"][:, :16], P["l1s"]) and np.array_equal(P2["l2"][:16], P["l2"])
+    assert not P2["l1s"][:, 21:].any() and not P2["l2"][21:].any()
+    assert P2["qw"] is P["qw"] and P2["sw"] is P["sw"] and P2["rinv"] is P["rinv"]
+    y0 = O.forward(xb, P, want_f64=True)
+    y1 = O.forward(xb, P2, want_f64=True)
+    assert np.array_equal(y0["qx"], y1["qx"]) and np.array_equal(y0["sx"], y1["sx"])
+    # the difference is the adapter applied to the UNSMOOTHED input, with both factors rounded to 16 bit ...
+    x = O.bf16_to_f32(xb).astype(np.float64)
+    d16 = O.bf16_to_f32(O.bf16_round((np.float32(scale) * down).astype(np.float32))).astype(np.float64)
+    u16 = O.bf16_to_f32(O.bf16_round(up)).astype(np.float64)
+    delta = y1["Y64"] - y0["Y64"]
+    want = x @ d16 @ u16
+    assert np.linalg.norm(delta - want) / np.linalg.norm(want) < 1e-12
+    # ... which is the LoRA update  scale * X down up  up to that rounding (2^-9 relative per factor)
+    exact = scale * (x @ down.astype(np.float64) @ up.astype(np.float64))
+    assert np.linalg.norm(delta - exact) / np.linalg.norm(exact) < 2.0 ** -8
+    assert np.linalg.norm(y1["Y"] - y1["Y64"]) / np.linalg.norm(y1["Y64"]) < 1e-6
+    # against re-quantizing the merged weight: same function up to the quantization error of either
+    merged = O.prepare(w + scale * (down @ up), ax, rank=16, bias=b)
+    y2 = O.forward(xb, merged, want_f64=True)["Y64"]
+    full = x @ (w.astype(np.float64) + exact_w(scale, down, up)) + b
+    e_append = np.linalg.norm(y1["Y64"] - full) / np.linalg.norm(full)
+    e_requant = np.linalg.norm(y2 - full) / np.linalg.norm(full)
+    assert e_append < 1.5 * e_requant + 1e-3, (e_append, e_requant)
+
+
+def exact_w(scale, down, up):
+    return scale * (down.astype(np.float64) @ up.astype(np.float64))
+
+
 def test_forward_approximates_xw_and_error_identity():
     xb, w, b, ax = _small_layer(M=64, K=512, N=128, seed=8)
     r = 16

@@ -65,3 +65,12 @@ def test_transposed_group_sum_is_caught(monkeypatch):
     real = O.group_sums
     monkeypatch.setattr(O, "group_sums", lambda qx, qw: real(qx, np.ascontiguousarray(qw[::-1])))
     _must_fail(TL.test_group_sums_against_integer_loops_and_extremes)
+
+
+def test_adapter_applied_to_the_smoothed_input_is_caught(monkeypatch):
+    real = O.append_lora
+
+    def bad(prep, down, up, scale=1.0, rank_multiple=16):      # treats the adapter like L1 instead of like L1s
+        return real(prep, np.asarray(down, np.float32) * prep["rinv"][:, None], up, scale, rank_multiple)
+    monkeypatch.setattr(O, "append_lora", bad)
+    _must_fail(TL.test_lora_appended_to_the_lowrank_branch_adds_x_down_up_and_nothing_else)
