@@ -74,3 +74,26 @@ def test_adapter_applied_to_the_smoothed_input_is_caught(monkeypatch):
         return real(prep, np.asarray(down, np.float32) * prep["rinv"][:, None], up, scale, rank_multiple)
     monkeypatch.setattr(O, "append_lora", bad)
     _must_fail(TL.test_lora_appended_to_the_lowrank_branch_adds_x_down_up_and_nothing_else)
+
+
+def test_fp4_mistakes_are_caught(monkeypatch):
+    from oracle import svdq_fp4_oracle as F
+    import tests.test_oracle_fp4 as TF
+    real_round, real_scale = F.round_e2m1, F.block_scale_byte
+
+    def away(y):                                  # ties away from zero instead of to even
+        y = np.asarray(y, np.float32)
+        a = np.minimum(np.abs(y), 6).astype(np.float64)
+        idx = np.argmin(np.abs(a[..., None] - F.E2M1.astype(np.float64))[..., ::-1], axis=-1)
+        return ((7 - idx) + 8 * (y < 0)).astype(np.uint8)
+    monkeypatch.setattr(F, "round_e2m1", away)
+    _must_fail(TF.test_e2m1_ties_from_golden_file)
+    monkeypatch.setattr(F, "round_e2m1", real_round)
+    # scale from floor(log2(max)) - 2, the other common convention: blocks with max in (6 s, 8 s) would clip
+    monkeypatch.setattr(F, "block_scale_byte", lambda a: np.where(np.asarray(a) > 0, np.clip(np.frexp(np.asarray(a, np.float64))[1] - 3 + 127, 0, 254), 0).astype(np.uint8))
+    _must_fail(TF.test_block_scale_is_the_smallest_power_of_two_that_keeps_the_block_in_range)
+    _must_fail(TF.test_quantizer_invariants)
+    monkeypatch.setattr(F, "block_scale_byte", real_scale)
+    # the weight side quantized from the smoothed weight instead of the residual (low-rank term dropped from R)
+    monkeypatch.setattr(F.O, "residual", lambda W, lam, a, b: np.asarray(W, np.float64) * np.asarray(lam, np.float64)[:, None])
+    _must_fail(TF.test_forward_equals_the_dense_definition_of_eq5)
