@@ -190,6 +190,41 @@ int svdq_forward_options(int flags);
  */
 int svdq_profile_event(void *hip_event);
 
+/* ------------------------------------------------------------------------------------------------
+ * 4-bit FLOATING-POINT variant.  The paper runs the same method with FP4 operands in the block format
+ * its GPU multiplies natively (App. "Implementation Details"); the MI355X's native block format is
+ * MXFP4: E2M1 elements {0, .5, 1, 1.5, 2, 3, 4, 6} with a sign, blocks of 32 along K, one
+ * power-of-two scale byte per block (value 2^(byte - 127)).  Everything but the quantizer is the
+ * layer above: smoothing, rank-r 16-bit branch, residual against the stored factors, Eq. 5.
+ *   quantizer (Eq. 1 with q_max = 6): scale = the smallest power of two s >= 2^-126 with
+ *   max|x| <= 6 s (byte 0 marks an all-zero block); codes = E2M1 element nearest to x / s, ties to
+ *   the even code, sign in bit 3.
+ * These entry points take a svdq_shape with group = 32.  Buffers, ownership, alignment, stream and
+ * error behaviour are those of their INT4 namesakes; wscales holds scale bytes instead of fp16.
+ * The K / rank limits of svdq_linear_forward apply.  svdq_unpack_l1s, svdq_unpack_l2 and
+ * svdq_append_lora accept either group size.
+ * ------------------------------------------------------------------------------------------------ */
+int svdq_fp4_prepared_sizes(const svdq_shape *shape, svdq_sizes *out);
+int svdq_fp4_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                     float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                     uint8_t *out_wscales, float *out_bias);
+/* canonical forms (HOST): qw uint8 [K x N], one code 0..15 per byte; bw uint8 [K/32 x N] scale bytes (255 is refused) */
+int svdq_fp4_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
+                  const uint8_t *qw, const uint8_t *bw, const float *bias,
+                  float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                  uint8_t *out_wscales, float *out_bias);
+int svdq_fp4_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, uint8_t *out_qw /* [K x N] */);
+int svdq_fp4_unpack_wscales(const svdq_shape *shape, const uint8_t *wscales, uint8_t *out_bw /* [K/32 x N] */);
+size_t svdq_fp4_workspace_bytes(int M, const svdq_shape *shape);
+/* Y = bf16( sum over blocks 2^(ex + ew) (elements . elements) + (X l1s) l2 + bias ), asynchronous on the stream:
+ * the activation kernel (smoothing, MXFP4 quantization, down projection) and the block-scaled MFMA GEMM. */
+int svdq_fp4_linear_forward(const svdq_layer_dev *layer, const void *X, int M, void *Y,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+/* canonical views of what the last forward left in the workspace (DEVICE outputs, any may be NULL):
+ * codes uint8 [M x K] (0..15), scale bytes uint8 [M x K/32], H fp32 [M x rank] */
+int svdq_fp4_debug_act(const svdq_layer_dev *layer, const void *workspace, int M,
+                       uint8_t *out_codes, uint8_t *out_bx, float *out_H, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ What each function follows
 * ``prepare`` / ``forward``  the INT4 oracle's steps with Q(.) replaced; Eq. (5).
 
 Readings (also listed in the design document): block = 32 consecutive elements along K for both
-operands; scale byte b encodes 2^(b - 127), clamped to [0, 254]; an all-zero block has byte 0 and codes 0;
+operands; scale byte b encodes 2^(b - 127), clamped to [1, 254] (byte 0 is kept for the all-zero block, whose codes are 0);
 the sign of a zero code is immaterial (comparisons are made on decoded values); the 4-bit branch is
 evaluated as sum over blocks of 2^(ex + ew) * (sum of element products), element products being exact
 multiples of 1/4.
@@ -64,12 +64,12 @@ def decode_e2m1(codes: np.ndarray) -> np.ndarray:
 
 
 def block_scale_byte(amax: np.ndarray) -> np.ndarray:
-    """E8M0 byte of the smallest power of two s with amax <= 6 s (fp32 ``amax`` >= 0); 0 for an all-zero block."""
+    """E8M0 byte of the smallest power of two s >= 2^-126 with amax <= 6 s (fp32 ``amax`` >= 0); 0 for an all-zero block."""
     amax = np.asarray(amax, dtype=np.float32)
     m, ex = np.frexp(amax.astype(np.float64))                    # amax = m 2^ex, m in [0.5, 1)
     # amax <= 6 * 2^e  <=>  2m * 2^(ex-1) <= 1.5 * 2^(e+2):  e = ex - 3 if 2m <= 1.5 else ex - 2
     e = np.where(m <= 0.75, ex - 3, ex - 2)
-    byte = np.clip(e + 127, 0, 254)
+    byte = np.clip(e + 127, 1, 254)
     return np.where(amax > 0, byte, 0).astype(np.uint8)
 
 

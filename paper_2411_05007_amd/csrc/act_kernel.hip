@@ -54,6 +54,13 @@ struct ActLds {
     static __host__ __device__ size_t wave_bytes() { return (size_t)WAVES * kWaveBytes; }
 };
 
+// maximum over the 4 lanes of a quad (one MXFP4 block of a token in the load map)
+__device__ __forceinline__ float max_over_4_lanes(float a) {
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true)));    // quad_perm [1,0,3,2]
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4E, 0xf, 0xf, true)));    // quad_perm [2,3,0,1]
+    return a;
+}
+
 // maximum over the 8 lanes l%8 = 0..7 that share a token in the load map
 __device__ __forceinline__ float max_over_8_lanes(float a) {
     a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true)));    // quad_perm [1,0,3,2]
@@ -62,7 +69,8 @@ __device__ __forceinline__ float max_over_8_lanes(float a) {
     return a;
 }
 
-template <int RBMAX, int WAVES, bool QUANT, bool PROJ, bool STAGE>
+// FMT 0: INT4 codes with fp16 group scales; FMT 1: MXFP4 (E2M1 codes, one power-of-two scale byte per block of 32)
+template <int RBMAX, int WAVES, bool QUANT, bool PROJ, bool STAGE, int FMT>
 __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) ? 2 : 1) void act_kernel(ActParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char act_lds[];
     using L = ActLds<RBMAX, WAVES>;
@@ -91,14 +99,15 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     // rows past M read the last row; what they produce lands in padding rows and is never used
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.X, (size_t)p.M * p.K * 2);
     const __amdgpu_buffer_rsrc_t rs_l = make_rsrc(p.l1s, (size_t)p.K * p.rank * 2);
-    const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, (size_t)p.G * p.Mpad * kActBytes);
-    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2);
+    const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, (size_t)p.G * p.Mpad * (FMT ? kFp4RowBytes : kActBytes));
+    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sx, FMT ? fp4_scale_bytes(p.G, p.Mpad) : (size_t)p.G * p.Mpad * 2);
     // (byte offsets below 2^32: the entry point refuses batches of 2^31 elements or more; unsigned on purpose)
     const int vxa = (int)(((uint32_t)(ma < p.M ? ma : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
     const int vxb = (int)(((uint32_t)(mb < p.M ? mb : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
-    const int vca = (int)act_chunk_offset(0, p.Mpad, ma, c8 >> 1) + 8 * (c8 & 1);
-    const int vcb = (int)act_chunk_offset(0, p.Mpad, mb, c8 >> 1) + 8 * (c8 & 1);
-    const int vsx = ((c8 & 1) ? mb : ma) * 2;
+    // MXFP4: a lane's 8 channels are a quarter of block c8 / 4 of its token; its 8 codes are one dword
+    const int vca = FMT ? (int)fp4_code_offset(0, p.Mpad, ma, c8 >> 2) + 4 * (c8 & 3) : (int)act_chunk_offset(0, p.Mpad, ma, c8 >> 1) + 8 * (c8 & 1);
+    const int vcb = FMT ? (int)fp4_code_offset(0, p.Mpad, mb, c8 >> 2) + 4 * (c8 & 3) : (int)act_chunk_offset(0, p.Mpad, mb, c8 >> 1) + 8 * (c8 & 1);
+    const int vsx = FMT ? (int)fp4_scale_offset(0, p.Mpad, (c8 & 1) ? mb : ma, c8 >> 2) : ((c8 & 1) ? mb : ma) * 2;
     struct XStage { uint4 x0, x1; };                   // 8 bf16 activations of token r8 and of token r8 + 8
     struct BStage { uint4 b[PROJ ? 2 * RBMAX : 1]; };  // L1s fragments: k steps 0 and 1 of every 16-column block
     // STAGE: the fragments of the next two groups wait in registers (at rank 128 this fills the register file
@@ -257,8 +266,42 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
         bytes = make_uint2(w[0] ^ 0x80808080u, w[1] ^ 0x80808080u);
         sbits = __builtin_bit_cast(uint16_t, sh);
     };
+    // Eq. 1 for one MXFP4 block (the 32 channels held by 4 neighbouring lanes): the scale is the smallest power
+    // of two s = 2^e >= 2^-126 with max|x| <= 6 s, found from the exponent and mantissa bits of the maximum
+    // (max|x| = 1.m * 2^(E - 127) <= 1.5 * 2^(e + 2)  <=>  e = E - 129, one more if 1.m > 1.5), stored as the
+    // byte e + 127 (0 for an all-zero block); the codes come from the hardware conversion, which divides by
+    // the scale's power of two and rounds to the nearest E2M1 element, ties to even, saturating.
+    auto encode_fp4 = [&](const float (&xh)[QUANT ? 8 : 1], uint32_t &word, uint32_t &sbyte) {
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xh[e]));
+        amax = max_over_4_lanes(amax);
+        const uint32_t bits = __float_as_uint(amax);
+        int byte = (int)(bits >> 23) - 2 + ((bits & 0x7fffffu) > 0x400000u ? 1 : 0);
+        byte = byte < 1 ? 1 : (byte > 254 ? 254 : byte);
+        const bool zero = !(amax > 0.f);
+        sbyte = zero ? 0u : (uint32_t)byte;
+        const float scale = __uint_as_float((zero ? 127u : (uint32_t)byte) << 23);
+        uint32_t w = 0u;
+        w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, xh[0], xh[QUANT ? 1 : 0], scale, 0);
+        w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, xh[QUANT ? 2 : 0], xh[QUANT ? 3 : 0], scale, 1);
+        w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, xh[QUANT ? 4 : 0], xh[QUANT ? 5 : 0], scale, 2);
+        w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, xh[QUANT ? 6 : 0], xh[QUANT ? 7 : 0], scale, 3);
+        word = w;
+    };
     auto quantize = [&](int g, const Smoothed &sm) {
-        if (QUANT) {
+        if (QUANT && FMT == 1) {
+            uint32_t wa, wb, ba, bb;
+            encode_fp4(sm.a, wa, ba);
+            encode_fp4(sm.b, wb, bb);
+            // unconditional stores, as below; the four lanes of a block write the same scale byte (lanes with an
+            // even c8 that of token r8, odd ones that of token r8 + 8)
+            const int sc = g * p.Mpad * kFp4RowBytes;
+            __builtin_amdgcn_raw_buffer_store_b32(wa, rs_c, vca, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(wb, rs_c, vcb, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b8((uint8_t)((c8 & 1) ? bb : ba), rs_s, vsx, (g >> 2) * p.Mpad * 8 + (g & 3), 0);
+        }
+        if (QUANT && FMT == 0) {
             uint2 ca, cb;
             uint16_t sa, sb;
             encode(sm.a, ca, sa);
@@ -338,7 +381,7 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     }
 }
 
-template <int RBMAX, int WAVES, bool STAGE>
+template <int RBMAX, int WAVES, bool STAGE, int FMT>
 hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     using L = ActLds<RBMAX, WAVES>;
     const dim3 grid((p.M + 15) / 16), block(WAVES * 64);
@@ -347,17 +390,17 @@ hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
     if (q && pr) {
-        auto k = act_kernel<RBMAX, WAVES, true, true, STAGE>;
+        auto k = act_kernel<RBMAX, WAVES, true, true, STAGE, FMT>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
     } else if (q) {
-        auto k = act_kernel<1, WAVES, true, false, false>;
+        auto k = act_kernel<1, WAVES, true, false, false, FMT>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
     } else if (pr) {
-        auto k = act_kernel<RBMAX, WAVES, false, true, STAGE>;
+        auto k = act_kernel<RBMAX, WAVES, false, true, STAGE, 0>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
@@ -382,22 +425,43 @@ __global__ void debug_act_kernel(DebugActParams p) {
     if (p.out_H && idx < (size_t)p.M * p.rank) p.out_H[idx] = p.H[idx];
 }
 
+// the same for the MXFP4 workspace: codes one per byte [M][K], scale bytes [M][K / 32]
+__global__ void debug_act_fp4_kernel(DebugActFp4Params p) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p.out_codes && idx < (size_t)p.M * p.K) {
+        const int m = (int)(idx / p.K), k = (int)(idx % p.K);
+        const int g = k / 64, kb = (k % 64) / 32, t = k % 32;
+        const uint8_t b = p.codes[fp4_code_offset(g, p.Mpad, m, kb) + t / 2];
+        p.out_codes[idx] = (t & 1) ? (b >> 4) : (b & 0xf);
+    }
+    if (p.out_bx && idx < (size_t)p.M * p.G * 2) {
+        const int m = (int)(idx / (p.G * 2)), blk = (int)(idx % (p.G * 2));
+        p.out_bx[idx] = p.bx[fp4_scale_offset(blk / 2, p.Mpad, m, blk & 1)];
+    }
+    if (p.out_H && idx < (size_t)p.M * p.rank) p.out_H[idx] = p.H[idx];
+}
+
 }  // namespace
 
-hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
-    if (p.M <= 0) return hipSuccess;
+template <int FMT>
+hipError_t launch_act_fmt(const ActParams &p, int flags, hipStream_t stream) {
     // wavefronts per 16-token slice: more of them when K is long enough to give each a few groups
     const bool wide = act_waves(p.K, p.rank) == 8;
-    if (p.rank <= 32) return wide ? launch_rb<2, 8, true>(p, flags, stream) : launch_rb<2, 4, true>(p, flags, stream);
-    if (p.rank <= 64) return wide ? launch_rb<4, 8, false>(p, flags, stream) : launch_rb<4, 4, false>(p, flags, stream);
+    if (p.rank <= 32) return wide ? launch_rb<2, 8, true, FMT>(p, flags, stream) : launch_rb<2, 4, true, FMT>(p, flags, stream);
+    if (p.rank <= 64) return wide ? launch_rb<4, 8, false, FMT>(p, flags, stream) : launch_rb<4, 4, false, FMT>(p, flags, stream);
     if (p.rank <= 128) {
         // staged fragments cost a CU its second workgroup: worth it when K is long, or when the launch has no
         // more workgroups than CUs anyway
         const bool stage = p.G >= 96 || (p.M + 15) / 16 <= 256;
-        if (!wide) return launch_rb<8, 4, false>(p, flags, stream);
-        return stage ? launch_rb<8, 8, true>(p, flags, stream) : launch_rb<8, 8, false>(p, flags, stream);
+        if (!wide) return launch_rb<8, 4, false, FMT>(p, flags, stream);
+        return stage ? launch_rb<8, 8, true, FMT>(p, flags, stream) : launch_rb<8, 8, false, FMT>(p, flags, stream);
     }
-    return wide ? launch_rb<16, 8, false>(p, flags, stream) : launch_rb<16, 4, false>(p, flags, stream);
+    return wide ? launch_rb<16, 8, false, FMT>(p, flags, stream) : launch_rb<16, 4, false, FMT>(p, flags, stream);
+}
+
+hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    return p.fmt == 1 ? launch_act_fmt<1>(p, flags, stream) : launch_act_fmt<0>(p, flags, stream);
 }
 
 hipError_t launch_debug_act(const DebugActParams &p, hipStream_t stream) {
@@ -405,6 +469,14 @@ hipError_t launch_debug_act(const DebugActParams &p, hipStream_t stream) {
     const size_t n = (size_t)p.M * p.K;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
     hipLaunchKernelGGL(debug_act_kernel, grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_debug_act_fp4(const DebugActFp4Params &p, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    const size_t n = (size_t)p.M * p.K;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    hipLaunchKernelGGL(debug_act_fp4_kernel, grid, block, 0, stream, p);
     return hipGetLastError();
 }
 

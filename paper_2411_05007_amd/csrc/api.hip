@@ -19,11 +19,11 @@ int hip_fail(hipError_t e) {
     return SVDQ_EHIP;
 }
 
-int check_layer(const svdq_layer_dev *L) {
+int check_layer(const svdq_layer_dev *L, int group = svdq::kGroup) {
     if (!L) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
     if (s.K <= 0 || s.N <= 0 || s.rank < 0) return SVDQ_EINVAL;
-    if (s.group != svdq::kGroup || s.K % svdq::kGroup != 0 || s.N % 16 != 0 || s.rank % 16 != 0 ||
+    if (s.group != group || s.K % svdq::kGroup != 0 || s.N % 16 != 0 || s.rank % 16 != 0 ||
         s.rank > svdq::kMaxRank || s.rank > (s.K < s.N ? s.K : s.N))
         return SVDQ_EUNSUPPORTED;
     if (!L->rinv || !L->wcodes || !L->wscales || !L->bias) return SVDQ_EINVAL;
@@ -199,6 +199,83 @@ int svdq_debug_group_acc(const svdq_layer_dev *L, const void *workspace, int M, 
     g.dbg = out; g.m0 = m0; g.m1 = m1; g.n0 = n0; g.n1 = n1;
     const int tile = tile_override() ? tile_override() : svdq::plan_gemm(M, s.N, s.K / svdq::kGroup).tile;
     const hipError_t e = svdq::launch_gemm(g, tile, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
+// ---- MXFP4 variant ----------------------------------------------------------------------------------------
+
+size_t svdq_fp4_workspace_bytes(int M, const svdq_shape *s) {
+    if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
+    return svdq::workspace_layout_fp4(M, s->K, s->rank).total;
+}
+
+int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+    const int st = check_layer(L, svdq::kFp4Block);
+    if (st != SVDQ_OK) return st;
+    if (M < 0) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    if (!X || !Y || !workspace) return SVDQ_EINVAL;
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
+    const svdq_shape &s = L->shape;
+    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.rank);
+    if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
+    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+        return SVDQ_EUNSUPPORTED;
+    if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
+        return SVDQ_EUNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
+
+    svdq::ActParams a{};
+    a.X = static_cast<const uint16_t *>(X);
+    a.rinv = static_cast<const float *>(L->rinv);
+    a.l1s = static_cast<const uint16_t *>(L->l1s);
+    a.codes = ws + w.codes_off;
+    a.sx = reinterpret_cast<uint16_t *>(ws + w.bx_off);
+    a.H = reinterpret_cast<float *>(ws + w.h_off);
+    a.hfrag = ws + w.hfrag_off;
+    a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
+    a.fmt = 1;
+    hipError_t e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    if (void *ev = g_profile_event.load()) {
+        e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    svdq::GemmFp4Params g{};
+    g.xcodes = ws + w.codes_off;
+    g.bx = ws + w.bx_off;
+    g.hfrag = ws + w.hfrag_off;
+    g.wcodes = static_cast<const uint8_t *>(L->wcodes);
+    g.bw = static_cast<const uint8_t *>(L->wscales);
+    g.l2t = static_cast<const uint16_t *>(L->l2);
+    g.bias = static_cast<const float *>(L->bias);
+    g.Y = static_cast<uint16_t *>(Y);
+    g.M = M; g.N = s.N; g.K = s.K; g.G = s.K / svdq::kGroup;
+    g.Mpad = w.Mpad; g.Npad = svdq::round_up(s.N, svdq::kRowPad);
+    g.rank = lowrank ? s.rank : 0;
+    e = svdq::launch_gemm_fp4(g, stream);
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
+int svdq_fp4_debug_act(const svdq_layer_dev *L, const void *workspace, int M, uint8_t *out_codes, uint8_t *out_bx,
+                       float *out_H, void *hip_stream) {
+    const int st = check_layer(L, svdq::kFp4Block);
+    if (st != SVDQ_OK) return st;
+    if (M < 0 || !workspace) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    const svdq_shape &s = L->shape;
+    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.rank);
+    const unsigned char *ws = static_cast<const unsigned char *>(workspace);
+    svdq::DebugActFp4Params d{};
+    d.codes = ws + w.codes_off;
+    d.bx = ws + w.bx_off;
+    d.H = reinterpret_cast<const float *>(ws + w.h_off);
+    d.out_codes = out_codes; d.out_bx = out_bx; d.out_H = s.rank > 0 ? out_H : nullptr;
+    d.M = M; d.K = s.K; d.G = s.K / svdq::kGroup; d.Mpad = w.Mpad; d.rank = s.rank;
+    const hipError_t e = svdq::launch_debug_act_fp4(d, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SVDQ_OK : hip_fail(e);
 }
 

@@ -22,6 +22,8 @@ struct ActParams {
     int M, K, G, Mpad, rank;
     uint32_t *zero_words;    // cleared by the first workgroup: the arrival counters of the GEMM that follows
     int n_zero;
+    int fmt;                 // 0: INT4 as described above.  1: MXFP4 - codes = packed E2M1 in the GEMM's operand order,
+                             // sx = scale bytes (layout.h, fp4_code_offset / fp4_scale_offset)
 };
 
 // flags: bit 0 = quantize (codes + scales), bit 1 = down projection (H)
@@ -61,5 +63,30 @@ struct DebugActParams {
     int M, K, G, Mpad, rank;
 };
 hipError_t launch_debug_act(const DebugActParams &p, hipStream_t stream);
+
+struct DebugActFp4Params {
+    const uint8_t *codes;    // MXFP4 workspace tensors
+    const uint8_t *bx;
+    const float *H;
+    uint8_t *out_codes;      // [M][K], one code (0..15) per byte, or null
+    uint8_t *out_bx;         // [M][K / 32] scale bytes, or null
+    float *out_H;            // [M][rank] or null
+    int M, K, G, Mpad, rank;
+};
+hipError_t launch_debug_act_fp4(const DebugActFp4Params &p, hipStream_t stream);
+
+// MXFP4 GEMM: Y = sum over blocks of 2^(ex + ew) (elements . elements) + H L2 + bias, block-scaled matrix-core instruction
+struct GemmFp4Params {
+    const uint8_t *xcodes;   // [G][Mpad / 32][2][32][16]
+    const uint8_t *bx;       // scale bytes of the activations
+    const uint8_t *hfrag;
+    const uint8_t *wcodes;   // [G][Npad / 32][2][32][16]
+    const uint8_t *bw;       // scale bytes of the weights
+    const uint16_t *l2t;     // bf16 [Npad][rank]
+    const float *bias;       // fp32 [Npad]
+    uint16_t *Y;             // bf16 [M][N]
+    int M, N, K, G, Mpad, Npad, rank;
+};
+hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream);
 
 }  // namespace svdq

@@ -79,6 +79,39 @@ inline __host__ __device__ size_t l1s_index(int K, int rank, int k, int j) {
     return ((((size_t)g * 2 + s) * (rank / 16) + c) * 64 + lane) * 8 + e;
 }
 
+// ---- MXFP4 variant (E2M1 elements, blocks of 32 along K, one power-of-two scale byte per block) ----------
+// Both operands use the A / B operand order of v_mfma_scale_f32_32x32x64_f8f6f4, whose lane l feeds row (or
+// column) l % 32 with the 32 elements of block l / 32 of a 64-channel step:
+//     codes   c4[g][row / 32][kb][row % 32][16 bytes], nibble t of the 16 bytes = element k = 64 g + 32 kb + t
+//     scales  s4[g / 4][row / 32][kb * 32 + row % 32][g % 4]: one dword per lane carries the scale bytes of
+//             four consecutive steps, picked by the instruction's byte selector
+// so one 32-row block of one step is one contiguous kilobyte of codes, loaded with one 16-byte load per lane.
+constexpr int kFp4Block = 32;
+constexpr int kFp4RowBytes = 32;     // packed bytes of one row of one 64-channel step
+inline __host__ __device__ size_t fp4_code_offset(int g, int rows_pad, int row, int kb) {
+    return ((((size_t)g * (rows_pad / 32) + row / 32) * 2 + kb) * 32 + row % 32) * 16;
+}
+inline __host__ __device__ size_t fp4_scale_offset(int g, int rows_pad, int row, int kb) {
+    return ((((size_t)(g / 4) * (rows_pad / 32) + row / 32) * 64 + kb * 32 + row % 32) * 4) + g % 4;
+}
+inline __host__ __device__ size_t fp4_scale_bytes(int G, int rows_pad) { return (size_t)((G + 3) / 4) * rows_pad * 8; }
+
+struct WorkspaceFp4 {
+    size_t codes_off, bx_off, h_off, hfrag_off, total;
+    int Mpad;
+};
+inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int rank) {
+    WorkspaceFp4 w;
+    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
+    const int G = K / kGroup;
+    w.codes_off = 0;
+    w.bx_off = align256((size_t)G * w.Mpad * kFp4RowBytes);
+    w.h_off = w.bx_off + align256(fp4_scale_bytes(G, w.Mpad));
+    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.total = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    return w;
+}
+
 // How the GEMM of an M x N x (64 G) layer is launched when the caller does not force a tile shape.
 // Large launches use 128x128 tiles, two workgroups per CU.  A launch with fewer than two such workgroups
 // per CU uses 64x128 tiles, and if even those leave most SIMDs without a second wavefront, the K loop is

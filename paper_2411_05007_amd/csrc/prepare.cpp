@@ -292,13 +292,44 @@ void truncated_svd(const double *A, int K, int N, int r, std::vector<double> &L1
 // ----------------------------------------------------------------------------------------------
 // shape checks and sizes
 // ----------------------------------------------------------------------------------------------
-int check_shape(const svdq_shape *s) {
+// `group` selects the 4-bit format: 64 = INT4 with fp16 scales, 32 = MXFP4 (E2M1 with power-of-two block scales);
+// 0 accepts either (functions that only touch the 16-bit branch).
+int check_shape(const svdq_shape *s, int group = kGroup) {
     if (!s) return SVDQ_EINVAL;
     if (s->K <= 0 || s->N <= 0 || s->rank < 0) return SVDQ_EINVAL;
-    if (s->group != kGroup || s->K % kGroup != 0 || s->N % 16 != 0 || s->rank % 16 != 0 ||
+    const bool group_ok = group ? s->group == group : (s->group == kGroup || s->group == svdq::kFp4Block);
+    if (!group_ok || s->K % kGroup != 0 || s->N % 16 != 0 || s->rank % 16 != 0 ||
         s->rank > svdq::kMaxRank || s->rank > std::min(s->K, s->N))
         return SVDQ_EUNSUPPORTED;
     return SVDQ_OK;
+}
+
+// Eq. 1 on one MXFP4 block of 32 values (stride `stride` apart): the scale is the smallest power of two
+// 2^e >= 2^-126 with max|v| <= 6 * 2^e, stored as the byte e + 127 (0 for an all-zero block); the codes are the
+// E2M1 elements nearest to v / 2^e, ties to the even code, sign in bit 3.
+inline uint8_t quantize_block_fp4(const float *v, size_t stride, uint8_t *codes) {
+    float amax = 0.0f;
+    for (int i = 0; i < svdq::kFp4Block; ++i) amax = std::max(amax, std::fabs(v[i * stride]));
+    if (!(amax > 0.0f)) {
+        for (int i = 0; i < svdq::kFp4Block; ++i) codes[i] = 0;
+        return 0;
+    }
+    int ex;
+    const float m = std::frexp(amax, &ex);                       // amax = m 2^ex, m in [0.5, 1)
+    int e = (m <= 0.75f) ? ex - 3 : ex - 2;                      // amax <= 1.5 * 2^(e + 2)
+    e = std::min(127, std::max(-126, e));
+    static const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    for (int i = 0; i < svdq::kFp4Block; ++i) {
+        const float y = std::ldexp(v[i * stride], -e);
+        const float a = std::min(std::fabs(y), 6.0f);
+        int best = 0;
+        for (int c = 1; c < 8; ++c) {
+            const float d = std::fabs(a - grid[c]), db = std::fabs(a - grid[best]);
+            if (d < db || (d == db && (c & 1) == 0)) best = c;
+        }
+        codes[i] = (uint8_t)(best | (y < 0.0f ? 8 : 0));
+    }
+    return (uint8_t)(e + 127);
 }
 
 // Eq. 1 on one group of 64 values (stride `stride` apart): fp16 scale and 64 codes.
@@ -345,6 +376,103 @@ void pack_native(const svdq_shape *sh, const float *rinv, const uint16_t *l1s, c
             }
     });
     for (int n = 0; n < Np; ++n) o_bias[n] = (n < N && bias) ? bias[n] : 0.0f;
+}
+
+}  // namespace
+
+namespace {
+
+// Steps shared by both 4-bit formats (Sec. 4.2): smoothing factor, W^ = diag(lambda) W, rank-r split with the
+// factors stored in bf16 (lambda^-1 folded into L1).
+struct SplitLayer {
+    std::vector<double> lam, What;
+    std::vector<float> rinv;
+    std::vector<uint16_t> l1s, l2;      // canonical: [K x r], [r x N]
+    std::vector<double> l2d;
+};
+void split_layer(const svdq_shape *shape, const float *W, const float *x_absmax, SplitLayer &o) {
+    const int K = shape->K, N = shape->N, r = shape->rank;
+    const double alpha = (double)shape->alpha;
+    // smoothing factor (App. "Implementation Details"); the run time multiplies by fp32(1/lambda),
+    // so the offline side scales by the exact inverse of that rounded value.
+    o.lam.resize(K);
+    o.rinv.resize(K);
+    parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+        for (size_t k = k0; k < k1; ++k) {
+            double aw = 0.0;
+            for (int n = 0; n < N; ++n) aw = std::max(aw, (double)std::fabs(W[k * N + n]));
+            const double ax = (double)x_absmax[k];
+            double l = std::pow(ax, alpha) / std::pow(aw, 1.0 - alpha);
+            if (!(ax > 0.0) || !(aw > 0.0) || !std::isfinite(l) || !(l > 0.0)) l = 1.0;
+            o.rinv[k] = (float)(1.0 / l);
+            o.lam[k] = 1.0 / (double)o.rinv[k];
+        }
+    });
+    o.What.resize((size_t)K * N);
+    parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+        for (size_t k = k0; k < k1; ++k)
+            for (int n = 0; n < N; ++n) o.What[k * N + n] = o.lam[k] * (double)W[k * N + n];
+    });
+    o.l1s.assign((size_t)K * r, 0);
+    o.l2.assign((size_t)r * N, 0);
+    if (r > 0) {
+        std::vector<double> L1, L2;
+        truncated_svd(o.What.data(), K, N, r, L1, L2);
+        for (size_t k = 0; k < (size_t)K; ++k)
+            for (int j = 0; j < r; ++j) o.l1s[k * r + j] = f32_to_bf16((float)(L1[k * r + j] / o.lam[k]));
+        for (size_t i = 0; i < (size_t)r * N; ++i) o.l2[i] = f32_to_bf16((float)L2[i]);
+    }
+    o.l2d.resize((size_t)r * N);
+    for (size_t i = 0; i < o.l2d.size(); ++i) o.l2d[i] = (double)bf16_to_f32(o.l2[i]);
+}
+
+// Rows 64 g .. 64 g + 63 of the residual against the STORED factors, R = W^ - diag(lambda) (L1s L2b), as fp32 [64 x N]
+void residual_rows(const svdq_shape *shape, const SplitLayer &o, size_t g, std::vector<float> &Rg, std::vector<double> &prow) {
+    const int N = shape->N, r = shape->rank;
+    for (int kk = 0; kk < kGroup; ++kk) {
+        const size_t k = g * kGroup + kk;
+        std::fill(prow.begin(), prow.end(), 0.0);
+        for (int j = 0; j < r; ++j) {
+            const double a = (double)bf16_to_f32(o.l1s[k * r + j]);
+            const double *b = o.l2d.data() + (size_t)j * N;
+            for (int n = 0; n < N; ++n) prow[n] += a * b[n];
+        }
+        for (int n = 0; n < N; ++n) Rg[(size_t)kk * N + n] = (float)(o.What[k * N + n] - o.lam[k] * prow[n]);
+    }
+}
+
+// factors, smoothing reciprocals and bias into their native places (the same for both formats)
+void pack_common(const svdq_shape *sh, const float *rinv, const uint16_t *l1s, const uint16_t *l2, const float *bias,
+                 float *o_rinv, uint16_t *o_l1s, uint16_t *o_l2, float *o_bias) {
+    const int K = sh->K, N = sh->N, r = sh->rank;
+    const int Np = svdq::round_up(N, kRowPad);
+    if (o_rinv != rinv) std::memcpy(o_rinv, rinv, (size_t)K * 4);
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < r; ++j) o_l1s[svdq::l1s_index(K, r, k, j)] = l1s[(size_t)k * r + j];
+    std::memset(o_l2, 0, (size_t)Np * r * 2);
+    for (int j = 0; j < r; ++j)
+        for (int n = 0; n < N; ++n) o_l2[(size_t)n * r + j] = l2[(size_t)j * N + n];
+    for (int n = 0; n < Np; ++n) o_bias[n] = (n < N && bias) ? bias[n] : 0.0f;
+}
+
+// MXFP4 codes [K x N] (one per byte) and block bytes [K/32 x N] into the GEMM's operand order (layout.h)
+void pack_fp4_weights(const svdq_shape *sh, const uint8_t *qw, const uint8_t *bw, uint8_t *o_wcodes, uint8_t *o_wscales) {
+    const int K = sh->K, N = sh->N, G = K / kGroup;
+    const int Np = svdq::round_up(N, kRowPad);
+    std::memset(o_wcodes, 0, (size_t)G * Np * svdq::kFp4RowBytes);
+    std::memset(o_wscales, 0, svdq::fp4_scale_bytes(G, Np));
+    parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
+        for (size_t g = g0; g < g1; ++g)
+            for (int n = 0; n < N; ++n)
+                for (int kb = 0; kb < 2; ++kb) {
+                    uint8_t *dst = o_wcodes + svdq::fp4_code_offset((int)g, Np, n, kb);
+                    for (int j = 0; j < 16; ++j) {
+                        const size_t k = g * kGroup + 32 * kb + 2 * j;
+                        dst[j] = (uint8_t)((qw[k * N + n] & 0xf) | ((qw[(k + 1) * N + n] & 0xf) << 4));
+                    }
+                    o_wscales[svdq::fp4_scale_offset((int)g, Np, n, kb)] = bw[(g * 2 + kb) * (size_t)N + n];
+                }
+    });
 }
 
 }  // namespace
@@ -401,70 +529,127 @@ int svdq_prepare(const svdq_shape *shape, const float *W, const float *x_absmax,
     if (st != SVDQ_OK) return st;
     if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
         return SVDQ_EINVAL;
-    const int K = shape->K, N = shape->N, r = shape->rank, G = K / kGroup;
-    const double alpha = (double)shape->alpha;
+    const int K = shape->K, N = shape->N, G = K / kGroup;
     try {
-        // smoothing factor (App. "Implementation Details"); the run time multiplies by fp32(1/lambda),
-        // so the offline side scales by the exact inverse of that rounded value.
-        std::vector<double> lam(K);
-        std::vector<float> rinv(K);
-        parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
-            for (size_t k = k0; k < k1; ++k) {
-                double aw = 0.0;
-                for (int n = 0; n < N; ++n) aw = std::max(aw, (double)std::fabs(W[k * N + n]));
-                const double ax = (double)x_absmax[k];
-                double l = std::pow(ax, alpha) / std::pow(aw, 1.0 - alpha);
-                if (!(ax > 0.0) || !(aw > 0.0) || !std::isfinite(l) || !(l > 0.0)) l = 1.0;
-                rinv[k] = (float)(1.0 / l);
-                lam[k] = 1.0 / (double)rinv[k];
-            }
-        });
-        std::vector<double> What((size_t)K * N);
-        parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
-            for (size_t k = k0; k < k1; ++k)
-                for (int n = 0; n < N; ++n) What[k * N + n] = lam[k] * (double)W[k * N + n];
-        });
-        // low-rank split and bf16 storage of the factors (lambda^-1 folded into L1)
-        std::vector<uint16_t> l1s((size_t)K * r), l2((size_t)r * N);
-        if (r > 0) {
-            std::vector<double> L1, L2;
-            truncated_svd(What.data(), K, N, r, L1, L2);
-            for (size_t k = 0; k < (size_t)K; ++k)
-                for (int j = 0; j < r; ++j) l1s[k * r + j] = f32_to_bf16((float)(L1[k * r + j] / lam[k]));
-            for (size_t i = 0; i < (size_t)r * N; ++i) l2[i] = f32_to_bf16((float)L2[i]);
-        }
-        // residual against the stored factors, R = W^ - diag(lambda) (L1s L2b), then Eq. 1 per group
+        SplitLayer sl;
+        split_layer(shape, W, x_absmax, sl);
+        // Eq. 1 per group of 64 along K
         std::vector<int8_t> qw((size_t)K * N);
         std::vector<uint16_t> sw((size_t)G * N);
-        std::vector<double> l2d((size_t)r * N);
-        for (size_t i = 0; i < l2d.size(); ++i) l2d[i] = (double)bf16_to_f32(l2[i]);
         parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
             std::vector<float> Rg((size_t)kGroup * N);
             std::vector<double> prow(N);
             int8_t codes[kGroup];
             for (size_t g = g0; g < g1; ++g) {
-                for (int kk = 0; kk < kGroup; ++kk) {
-                    const size_t k = g * kGroup + kk;
-                    std::fill(prow.begin(), prow.end(), 0.0);
-                    for (int j = 0; j < r; ++j) {
-                        const double a = (double)bf16_to_f32(l1s[k * r + j]);
-                        const double *b = l2d.data() + (size_t)j * N;
-                        for (int n = 0; n < N; ++n) prow[n] += a * b[n];
-                    }
-                    for (int n = 0; n < N; ++n)
-                        Rg[(size_t)kk * N + n] = (float)(What[k * N + n] - lam[k] * prow[n]);
-                }
+                residual_rows(shape, sl, g, Rg, prow);
                 for (int n = 0; n < N; ++n) {
                     sw[g * N + n] = quantize_group(Rg.data() + n, (size_t)N, codes);
                     for (int kk = 0; kk < kGroup; ++kk) qw[(g * kGroup + kk) * (size_t)N + n] = codes[kk];
                 }
             }
         });
-        pack_native(shape, rinv.data(), l1s.data(), l2.data(), qw.data(), sw.data(), bias, out_rinv, out_l1s,
+        pack_native(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), qw.data(), sw.data(), bias, out_rinv, out_l1s,
                     out_l2, out_wcodes, out_wscales, out_bias);
     } catch (const std::bad_alloc &) {
         return SVDQ_ENOMEM;
     }
+    return SVDQ_OK;
+}
+
+// ---- MXFP4 variant ------------------------------------------------------------------------------------
+int svdq_fp4_prepared_sizes(const svdq_shape *shape, svdq_sizes *out) {
+    if (!out) return SVDQ_EINVAL;
+    const int st = check_shape(shape, svdq::kFp4Block);
+    if (st != SVDQ_OK) return st;
+    const size_t K = shape->K, r = shape->rank;
+    const int G = shape->K / kGroup, Np = svdq::round_up(shape->N, kRowPad);
+    out->rinv = K * 4;
+    out->l1s = std::max<size_t>(K * r * 2, 16);
+    out->l2 = std::max<size_t>((size_t)Np * r * 2, 16);
+    out->wcodes = (size_t)G * Np * svdq::kFp4RowBytes;
+    out->wscales = svdq::fp4_scale_bytes(G, Np);
+    out->bias = (size_t)Np * 4;
+    return SVDQ_OK;
+}
+
+int svdq_fp4_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
+                  const uint8_t *qw, const uint8_t *bw, const float *bias, float *out_rinv, uint16_t *out_l1s,
+                  uint16_t *out_l2, uint8_t *out_wcodes, uint8_t *out_wscales, float *out_bias) {
+    const int st = check_shape(shape, svdq::kFp4Block);
+    if (st != SVDQ_OK) return st;
+    if (!rinv || !qw || !bw || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
+        return SVDQ_EINVAL;
+    if (shape->rank > 0 && (!l1s || !l2)) return SVDQ_EINVAL;
+    const size_t total = (size_t)shape->K * shape->N;
+    for (size_t i = 0; i < total; ++i)
+        if (qw[i] > 15) return SVDQ_EINVAL;
+    for (size_t i = 0; i < total / svdq::kFp4Block; ++i)
+        if (bw[i] == 255) return SVDQ_EINVAL;               // the scale type's NaN
+    pack_common(shape, rinv, l1s, l2, bias, out_rinv, out_l1s, out_l2, out_bias);
+    pack_fp4_weights(shape, qw, bw, out_wcodes, out_wscales);
+    return SVDQ_OK;
+}
+
+int svdq_fp4_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                     float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                     uint8_t *out_wscales, float *out_bias) {
+    const int st = check_shape(shape, svdq::kFp4Block);
+    if (st != SVDQ_OK) return st;
+    if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
+        return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, G = K / kGroup;
+    try {
+        SplitLayer sl;
+        split_layer(shape, W, x_absmax, sl);
+        // Eq. 1 per block of 32 along K
+        std::vector<uint8_t> qw((size_t)K * N), bw((size_t)2 * G * N);
+        parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
+            std::vector<float> Rg((size_t)kGroup * N);
+            std::vector<double> prow(N);
+            uint8_t codes[svdq::kFp4Block];
+            for (size_t g = g0; g < g1; ++g) {
+                residual_rows(shape, sl, g, Rg, prow);
+                for (int n = 0; n < N; ++n)
+                    for (int kb = 0; kb < 2; ++kb) {
+                        bw[(g * 2 + kb) * (size_t)N + n] = quantize_block_fp4(Rg.data() + (size_t)32 * kb * N + n, (size_t)N, codes);
+                        for (int kk = 0; kk < 32; ++kk) qw[(g * kGroup + 32 * kb + kk) * (size_t)N + n] = codes[kk];
+                    }
+            }
+        });
+        pack_common(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), bias, out_rinv, out_l1s, out_l2, out_bias);
+        pack_fp4_weights(shape, qw.data(), bw.data(), out_wcodes, out_wscales);
+    } catch (const std::bad_alloc &) {
+        return SVDQ_ENOMEM;
+    }
+    return SVDQ_OK;
+}
+
+int svdq_fp4_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, uint8_t *out_qw) {
+    const int st = check_shape(shape, svdq::kFp4Block);
+    if (st != SVDQ_OK) return st;
+    if (!wcodes || !out_qw) return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, G = K / kGroup, Np = svdq::round_up(N, kRowPad);
+    for (int g = 0; g < G; ++g)
+        for (int n = 0; n < N; ++n)
+            for (int kb = 0; kb < 2; ++kb) {
+                const uint8_t *src = wcodes + svdq::fp4_code_offset(g, Np, n, kb);
+                for (int j = 0; j < 16; ++j) {
+                    const size_t k = (size_t)g * kGroup + 32 * kb + 2 * j;
+                    out_qw[k * N + n] = src[j] & 0xf;
+                    out_qw[(k + 1) * N + n] = src[j] >> 4;
+                }
+            }
+    return SVDQ_OK;
+}
+
+int svdq_fp4_unpack_wscales(const svdq_shape *shape, const uint8_t *wscales, uint8_t *out_bw) {
+    const int st = check_shape(shape, svdq::kFp4Block);
+    if (st != SVDQ_OK) return st;
+    if (!wscales || !out_bw) return SVDQ_EINVAL;
+    const int N = shape->N, G = shape->K / kGroup, Np = svdq::round_up(N, kRowPad);
+    for (int g = 0; g < G; ++g)
+        for (int n = 0; n < N; ++n)
+            for (int kb = 0; kb < 2; ++kb) out_bw[((size_t)g * 2 + kb) * N + n] = wscales[svdq::fp4_scale_offset(g, Np, n, kb)];
     return SVDQ_OK;
 }
 
@@ -495,7 +680,7 @@ int svdq_unpack_wscales(const svdq_shape *shape, const uint16_t *wscales, uint16
 }
 
 int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out) {
-    const int st = check_shape(shape);
+    const int st = check_shape(shape, 0);
     if (st != SVDQ_OK) return st;
     if (!l1s || !out) return SVDQ_EINVAL;
     for (int k = 0; k < shape->K; ++k)
@@ -505,7 +690,7 @@ int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out)
 }
 
 int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out) {
-    const int st = check_shape(shape);
+    const int st = check_shape(shape, 0);
     if (st != SVDQ_OK) return st;
     if (!l2 || !out) return SVDQ_EINVAL;
     for (int j = 0; j < shape->rank; ++j)
@@ -516,13 +701,13 @@ int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out) {
 int svdq_append_lora(const svdq_shape *shape, const uint16_t *l1s, const uint16_t *l2, const float *down,
                      const float *up, int r_add, float scale, svdq_shape *out_shape, uint16_t *out_l1s,
                      uint16_t *out_l2) {
-    const int st = check_shape(shape);
+    const int st = check_shape(shape, 0);
     if (st != SVDQ_OK) return st;
     if (!down || !up || !out_shape || r_add <= 0) return SVDQ_EINVAL;
     if (shape->rank > 0 && (!l1s || !l2)) return SVDQ_EINVAL;
     svdq_shape ns = *shape;
     ns.rank = svdq::round_up(shape->rank + r_add, 16);
-    const int st2 = check_shape(&ns);
+    const int st2 = check_shape(&ns, 0);
     if (st2 != SVDQ_OK) return st2;
     *out_shape = ns;
     if (!out_l1s || !out_l2) return SVDQ_EINVAL;

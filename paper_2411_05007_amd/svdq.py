@@ -23,6 +23,8 @@ OPT_TILE_SHIFT = 8
 EXPORTS = [
     "svdq_status_string", "svdq_last_hip_error", "svdq_prepared_sizes", "svdq_prepare", "svdq_pack",
     "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2", "svdq_append_lora",
+    "svdq_fp4_prepared_sizes", "svdq_fp4_prepare", "svdq_fp4_pack", "svdq_fp4_unpack_wcodes", "svdq_fp4_unpack_wscales",
+    "svdq_fp4_workspace_bytes", "svdq_fp4_linear_forward", "svdq_fp4_debug_act",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
     "svdq_forward_options", "svdq_profile_event",
 ]
@@ -67,6 +69,15 @@ def lib() -> C.CDLL:
         for n in ("svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2"):
             getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
         L.svdq_append_lora.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.c_int, C.c_float, C.POINTER(Shape), vp, vp]
+        L.svdq_fp4_workspace_bytes.restype = C.c_size_t
+        L.svdq_fp4_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
+        L.svdq_fp4_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
+        L.svdq_fp4_prepare.argtypes = [C.POINTER(Shape)] + [vp] * 9
+        L.svdq_fp4_pack.argtypes = [C.POINTER(Shape)] + [vp] * 12
+        for n in ("svdq_fp4_unpack_wcodes", "svdq_fp4_unpack_wscales"):
+            getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
+        L.svdq_fp4_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
+        L.svdq_fp4_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_debug_group_acc.argtypes = [C.POINTER(LayerDev), vp, C.c_int] + [C.c_int] * 4 + [vp, vp]
@@ -104,16 +115,23 @@ class PreparedHost:
     bias: np.ndarray
 
 
+def _is_fp4(shape: Shape) -> bool:
+    return shape.group == 32
+
+
 def _alloc_prepared(shape: Shape) -> PreparedHost:
     sz = Sizes()
-    _check(lib().svdq_prepared_sizes(C.byref(shape), C.byref(sz)), "svdq_prepared_sizes")
+    if _is_fp4(shape):
+        _check(lib().svdq_fp4_prepared_sizes(C.byref(shape), C.byref(sz)), "svdq_fp4_prepared_sizes")
+    else:
+        _check(lib().svdq_prepared_sizes(C.byref(shape), C.byref(sz)), "svdq_prepared_sizes")
     return PreparedHost(
         shape=shape,
         rinv=np.zeros(sz.rinv // 4, np.float32),
         l1s=np.zeros(sz.l1s // 2, np.uint16),
         l2=np.zeros(sz.l2 // 2, np.uint16),
         wcodes=np.zeros(sz.wcodes, np.uint8),
-        wscales=np.zeros(sz.wscales // 2, np.uint16),
+        wscales=np.zeros(sz.wscales, np.uint8) if _is_fp4(shape) else np.zeros(sz.wscales // 2, np.uint16),
         bias=np.zeros(sz.bias // 4, np.float32),
     )
 
@@ -167,6 +185,56 @@ def svdq_unpack(p: PreparedHost):
     return {"rinv": p.rinv.copy(), "l1s": l1s, "l2": l2, "qw": qw, "sw": sw.view(np.float16), "bias": p.bias[:N].copy()}
 
 
+def svdq_fp4_prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
+                     bias: Optional[np.ndarray] = None) -> PreparedHost:
+    """The MXFP4 variant of svdq_prepare (shape.group = 32)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    K, N = W.shape
+    x_absmax = np.ascontiguousarray(x_absmax, dtype=np.float32)
+    assert x_absmax.shape == (K,)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha, group=32)
+    out = _alloc_prepared(shape)
+    _check(lib().svdq_fp4_prepare(C.byref(shape), _ptr(W), _ptr(x_absmax), _ptr(b), _ptr(out.rinv), _ptr(out.l1s),
+                                  _ptr(out.l2), _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias)), "svdq_fp4_prepare")
+    return out
+
+
+def svdq_fp4_pack(rinv, l1s_bits, l2_bits, qw, bw, bias=None, alpha: float = 0.5) -> PreparedHost:
+    """Pack canonical MXFP4 arrays: qw uint8 [K, N] codes 0..15, bw uint8 [K/32, N] scale bytes."""
+    qw = np.ascontiguousarray(qw, dtype=np.uint8)
+    bw = np.ascontiguousarray(bw, dtype=np.uint8)
+    K, N = qw.shape
+    assert bw.shape == (K // 32, N)
+    l1s_bits = np.ascontiguousarray(l1s_bits, dtype=np.uint16)
+    rank = l1s_bits.shape[1] if l1s_bits.ndim == 2 else 0
+    l2_bits = np.ascontiguousarray(l2_bits, dtype=np.uint16)
+    rinv = np.ascontiguousarray(rinv, dtype=np.float32)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha, group=32)
+    out = _alloc_prepared(shape)
+    _check(lib().svdq_fp4_pack(C.byref(shape), _ptr(rinv), _ptr(l1s_bits) if rank else None, _ptr(l2_bits) if rank else None,
+                               _ptr(qw), _ptr(bw), _ptr(b), _ptr(out.rinv), _ptr(out.l1s), _ptr(out.l2),
+                               _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias)), "svdq_fp4_pack")
+    return out
+
+
+def svdq_fp4_unpack(p: PreparedHost):
+    """Canonical views of an MXFP4 layer: dict(rinv, l1s, l2, qw uint8 [K,N], bw uint8 [K/32,N], bias)."""
+    K, N, r = p.shape.K, p.shape.N, p.shape.rank
+    qw = np.zeros((K, N), np.uint8)
+    bw = np.zeros((K // 32, N), np.uint8)
+    l1s = np.zeros((K, r), np.uint16)
+    l2 = np.zeros((r, N), np.uint16)
+    L = lib()
+    _check(L.svdq_fp4_unpack_wcodes(C.byref(p.shape), _ptr(p.wcodes), _ptr(qw)), "svdq_fp4_unpack_wcodes")
+    _check(L.svdq_fp4_unpack_wscales(C.byref(p.shape), _ptr(p.wscales), _ptr(bw)), "svdq_fp4_unpack_wscales")
+    if r > 0:
+        _check(L.svdq_unpack_l1s(C.byref(p.shape), _ptr(p.l1s), _ptr(l1s)), "svdq_unpack_l1s")
+        _check(L.svdq_unpack_l2(C.byref(p.shape), _ptr(p.l2), _ptr(l2)), "svdq_unpack_l2")
+    return {"rinv": p.rinv.copy(), "l1s": l1s, "l2": l2, "qw": qw, "bw": bw, "bias": p.bias[:N].copy()}
+
+
 def svdq_append_lora(p: PreparedHost, down: np.ndarray, up: np.ndarray, scale: float = 1.0) -> PreparedHost:
     """A layer with the adapter `scale * down @ up` appended to its 16-bit branch; everything else is shared with `p`."""
     down = np.ascontiguousarray(down, dtype=np.float32)
@@ -174,11 +242,9 @@ def svdq_append_lora(p: PreparedHost, down: np.ndarray, up: np.ndarray, scale: f
     r_add = down.shape[1]
     assert down.shape == (p.shape.K, r_add) and up.shape == (r_add, p.shape.N)
     has = p.shape.rank > 0
-    want = make_shape(p.shape.K, p.shape.N, (p.shape.rank + r_add + 15) // 16 * 16, p.shape.alpha)
-    sz = Sizes()
-    _check(lib().svdq_prepared_sizes(C.byref(want), C.byref(sz)), "svdq_prepared_sizes")
-    l1s = np.zeros(sz.l1s // 2, np.uint16)
-    l2 = np.zeros(sz.l2 // 2, np.uint16)
+    want = make_shape(p.shape.K, p.shape.N, (p.shape.rank + r_add + 15) // 16 * 16, p.shape.alpha, p.shape.group)
+    blank = _alloc_prepared(want)
+    l1s, l2 = blank.l1s, blank.l2
     ns = Shape()
     _check(lib().svdq_append_lora(C.byref(p.shape), _ptr(p.l1s) if has else None, _ptr(p.l2) if has else None, _ptr(down),
                                   _ptr(up), r_add, float(scale), C.byref(ns), _ptr(l1s), _ptr(l2)), "svdq_append_lora")
@@ -195,6 +261,8 @@ def svdq_profile_event(event_handle: Optional[int]) -> None:
 
 
 def svdq_workspace_bytes(M: int, shape: Shape) -> int:
+    if _is_fp4(shape):
+        return int(lib().svdq_fp4_workspace_bytes(int(M), C.byref(shape)))
     return int(lib().svdq_workspace_bytes(int(M), C.byref(shape)))
 
 
@@ -211,6 +279,7 @@ class DeviceLayer:
         self.shape = prepared.shape
         self.K, self.N, self.rank = prepared.shape.K, prepared.shape.N, prepared.shape.rank
         self.G = self.K // 64
+        self.fp4 = _is_fp4(prepared.shape)
         up = lambda a: torch.from_numpy(a.view(np.uint8) if a.dtype != np.uint8 else a).to(self.device)
         self._bufs = {n: up(getattr(prepared, n)) for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")}
         self.cdesc = LayerDev(*[self._bufs[n].data_ptr() for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")],
@@ -232,8 +301,9 @@ class DeviceLayer:
         if workspace is None:
             workspace = self.workspace(M)
         s = torch.cuda.current_stream(x.device) if stream is None else stream
-        _check(lib().svdq_linear_forward(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
-                                         workspace.numel(), s.cuda_stream), "svdq_linear_forward")
+        fwd = lib().svdq_fp4_linear_forward if self.fp4 else lib().svdq_linear_forward
+        _check(fwd(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
+                   workspace.numel(), s.cuda_stream), "svdq_fp4_linear_forward" if self.fp4 else "svdq_linear_forward")
         self._last_ws, self._last_M = workspace, M
         return out
 
@@ -242,10 +312,17 @@ class DeviceLayer:
         torch = self.torch
         workspace = self._last_ws if workspace is None else workspace
         M = self._last_M if M is None else M
-        codes = torch.empty((M, self.K), dtype=torch.int8, device=self.device)
-        sx = torch.empty((M, self.G), dtype=torch.float16, device=self.device)
         H = torch.empty((M, max(self.rank, 1)), dtype=torch.float32, device=self.device)
         s = torch.cuda.current_stream(self.device)
+        if self.fp4:      # codes uint8 [M,K] (0..15), scale bytes uint8 [M,K/32]
+            codes = torch.empty((M, self.K), dtype=torch.uint8, device=self.device)
+            bx = torch.empty((M, self.K // 32), dtype=torch.uint8, device=self.device)
+            _check(lib().svdq_fp4_debug_act(C.byref(self.cdesc), workspace.data_ptr(), M, codes.data_ptr(), bx.data_ptr(),
+                                            H.data_ptr() if self.rank else None, s.cuda_stream), "svdq_fp4_debug_act")
+            torch.cuda.synchronize(self.device)
+            return codes.cpu().numpy(), bx.cpu().numpy(), (H.cpu().numpy() if self.rank else None)
+        codes = torch.empty((M, self.K), dtype=torch.int8, device=self.device)
+        sx = torch.empty((M, self.G), dtype=torch.float16, device=self.device)
         _check(lib().svdq_debug_act(C.byref(self.cdesc), workspace.data_ptr(), M, codes.data_ptr(), sx.data_ptr(),
                                     H.data_ptr() if self.rank else None, s.cuda_stream), "svdq_debug_act")
         torch.cuda.synchronize(self.device)

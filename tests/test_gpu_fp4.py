@@ -1,0 +1,161 @@
+"""GPU parity of the MXFP4 variant: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bar: activation codes (as decoded values: the sign of a zero is immaterial) and scale bytes bit-exact; H within 1e-5
+relative; the bf16 output within rel-L2 <= 2e-3 and max-abs <= 1e-2 * max|Y| of the oracle's evaluation of the same
+codes.  The block-scaled matrix-core instruction accumulates in fp32 in an order of its own, so there is no
+integer partial sum to compare bit for bit.
+"""
+import numpy as np
+import pytest
+
+from oracle import svdq_fp4_oracle as F
+from oracle import svdq_oracle as O
+from paper_2411_05007_amd import inputs as I
+from paper_2411_05007_amd import svdq as S
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 2e-3
+MAX_ABS = 1e-2
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    S.lib()
+    yield t
+    S.svdq_forward_options(0)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run_and_compare(torch, xb, prep, rows=None, what=""):
+    layer = S.DeviceLayer(prep)
+    assert layer.fp4
+    x = S.bf16_tensor_from_bits(xb)
+    M = xb.shape[0]
+    y = torch.full((M, layer.N), float("nan"), dtype=torch.bfloat16, device="cuda:0")      # unwritten elements would show
+    layer.forward(x, out=y)
+    torch.cuda.synchronize()
+    U = S.svdq_fp4_unpack(prep)
+    rows = np.arange(M) if rows is None else np.asarray(rows)
+    ref = F.forward(xb[rows], U)
+    codes, bx, H = layer.debug_act()
+    assert np.array_equal(bx[rows], ref["bx"]), f"{what}: activation scale bytes"
+    assert np.array_equal(F.decode_e2m1(codes[rows]), F.decode_e2m1(ref["qx"])), f"{what}: activation codes"
+    if layer.rank:
+        hs = max(np.max(np.abs(ref["H"])), 1e-30)
+        assert np.max(np.abs(H[rows] - ref["H"])) <= 1e-5 * hs, f"{what}: H"
+    yg = O.bf16_to_f32(S.bits_from_bf16_tensor(y)[rows]).astype(np.float64)
+    r64 = ref["Y64"]
+    rel = np.linalg.norm(yg - r64) / max(np.linalg.norm(r64), 1e-30)
+    ymax = max(np.max(np.abs(r64)), 1e-30)
+    mx = np.max(np.abs(yg - r64)) / ymax
+    _say(f"  {what}: rel-L2 {rel:.3e}  max-abs/max|Y| {mx:.3e}")
+    assert np.all(np.isfinite(yg)), what
+    assert mx <= MAX_ABS, (what, mx)
+    # element-wise: one bf16 rounding (2^-8 relative, 2^-7 with slack for a different fp32 summation order)
+    assert np.all(np.abs(yg - r64) <= 2.0 ** -7 * np.abs(r64) + 2e-5 * ymax), what
+    if r64.size >= 4096:
+        assert rel <= REL_L2, (what, rel)
+    return rel, mx
+
+
+def _random_layer(rng, M, K, N):
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, max(1, K // 100), replace=False)] *= 50
+    if M > 2:
+        x[2, :32] = 0.0                    # an all-zero block: scale byte 0, codes 0
+    xb = O.bf16_round(x)
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 2, replace=False)] *= 20
+    ax = np.abs(O.bf16_to_f32(xb)).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    return xb, w, ax, b
+
+
+def test_tiny_config_full_parity(torch):
+    case = I.case_by_name("tiny")
+    L = I.make_layer(case)
+    prep = S.svdq_fp4_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    _say(f"fp4 tiny: M={case.M} K={case.K} N={case.N} r={case.rank}")
+    _run_and_compare(torch, L["x_bf16"], prep, what="fp4 tiny")
+
+
+def test_oracle_prepared_layer_via_pack(torch):
+    case = I.case_by_name("tiny")
+    L = I.make_layer(case, M=96)
+    w = np.ascontiguousarray(L["w"][:, :384])
+    P = F.prepare(w, L["x_absmax"], rank=32, bias=L["bias"][:384])
+    prep = S.svdq_fp4_pack(P["rinv"], P["l1s"], P["l2"], P["qw"], P["bw"], P["bias"])
+    _run_and_compare(torch, L["x_bf16"], prep, what="fp4 oracle-prepared")
+
+
+@pytest.mark.parametrize("M,K,N,r", [(1, 64, 16, 16), (17, 128, 48, 16), (100, 256, 80, 32), (257, 192, 272, 48),
+                                     (300, 320, 1040, 64), (130, 1152, 144, 128), (64, 128, 64, 0),
+                                     (129, 448, 528, 32), (90, 512, 256, 256), (40, 3072, 256, 112)])
+def test_ragged_shapes(torch, M, K, N, r):
+    """Ragged M and N, K that is not a multiple of 4 steps (the scale dwords carry four steps), every rank class."""
+    rng = np.random.default_rng(2000 + M + K + N)
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    prep = S.svdq_fp4_prepare(w, ax, r, bias=b)
+    _say(f"fp4 ragged: M={M} K={K} N={N} r={r}")
+    _run_and_compare(torch, xb, prep, what=f"fp4 ragged {M}x{K}x{N} r{r}")
+
+
+def test_scales_over_a_wide_exponent_range_and_exact_grid_inputs(torch):
+    """Activations whose blocks span 2^-60 .. 2^60, and inputs that sit exactly on the E2M1 grid (reproduced exactly)."""
+    rng = np.random.default_rng(2100)
+    M, K, N = 64, 256, 64
+    g = F.E2M1[rng.integers(0, 8, (M, K))] * rng.choice([-1.0, 1.0], (M, K)).astype(np.float32)
+    g[:, ::32] = 6.0
+    ex = rng.integers(-60, 61, (M, K // 32))
+    x = (g * np.exp2(np.repeat(ex, 32, axis=1))).astype(np.float32)
+    xb = O.bf16_round(x)
+    assert np.array_equal(O.bf16_to_f32(xb), x)              # grid values times powers of two are bf16 numbers
+    qw = rng.integers(0, 16, (K, N)).astype(np.uint8)
+    bw = rng.integers(100, 140, (K // 32, N)).astype(np.uint8)
+    prep = S.svdq_fp4_pack(np.ones(K, np.float32), np.zeros((K, 0), np.uint16), np.zeros((0, N), np.uint16), qw, bw, None)
+    layer = S.DeviceLayer(prep)
+    layer.forward(S.bf16_tensor_from_bits(xb))
+    codes, bx, _ = layer.debug_act()
+    assert np.array_equal(bx, (ex + 127).astype(np.uint8))
+    assert np.array_equal(F.decode_e2m1(codes), g)
+    _run_and_compare(torch, xb, prep, what="fp4 wide exponents")
+
+
+def test_seeded_random_shapes(torch):
+    rng = np.random.default_rng(2200)
+    for i in range(16):
+        M = int(rng.integers(1, 400))
+        K = 64 * int(rng.integers(1, 24))
+        N = 16 * int(rng.integers(1, 48))
+        r = 16 * int(rng.integers(0, min(K, N, 96) // 16 + 1))
+        xb, w, ax, b = _random_layer(rng, M, K, N)
+        prep = S.svdq_fp4_prepare(w, ax, r, bias=b)
+        _say(f"fp4 random {i}: M={M} K={K} N={N} r={r}")
+        _run_and_compare(torch, xb, prep, what=f"fp4 random {M}x{K}x{N} r{r}")
+
+
+def test_deterministic(torch):
+    rng = np.random.default_rng(2300)
+    xb, w, ax, b = _random_layer(rng, 300, 512, 528)
+    layer = S.DeviceLayer(S.svdq_fp4_prepare(w, ax, 32, bias=b))
+    x = S.bf16_tensor_from_bits(xb)
+    y0 = S.bits_from_bf16_tensor(layer.forward(x))
+    for _ in range(3):
+        assert np.array_equal(S.bits_from_bf16_tensor(layer.forward(x)), y0)
+
+
+@pytest.mark.parametrize("name", ["flux_mlp_up", "flux_mlp_down"])
+def test_full_size_layers_on_sampled_rows(torch, name):
+    """The bench configuration (same launch shapes), checked on sampled rows the oracle can afford."""
+    case = I.case_by_name(name)
+    L = I.make_layer(case)
+    prep = S.svdq_fp4_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.random.default_rng(5).integers(0, case.M, 24), np.arange(case.M - 4, case.M)]))
+    _say(f"fp4 {name}: M={case.M} K={case.K} N={case.N} r={case.rank}, {len(rows)} sampled rows")
+    _run_and_compare(torch, L["x_bf16"], prep, rows=rows, what=f"fp4 {name}")

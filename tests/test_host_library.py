@@ -221,3 +221,48 @@ def test_append_lora_matches_the_oracle_and_refuses_oversized_ranks(lib):
     f = np.zeros(512 * 32, np.float32)
     assert lib.svdq_append_lora(C.byref(sh), S._ptr(z), S._ptr(z), S._ptr(f), S._ptr(f), 32, C.c_float(1.0), C.byref(ns), S._ptr(z), S._ptr(z)) == -2
     assert lib.svdq_append_lora(C.byref(sh), S._ptr(z), S._ptr(z), None, S._ptr(f), 16, C.c_float(1.0), C.byref(ns), S._ptr(z), S._ptr(z)) == -1
+
+
+def test_fp4_prepare_matches_the_oracle_given_the_same_factors(lib):
+    from oracle import svdq_fp4_oracle as F
+    rng = np.random.default_rng(91)
+    K, N, r = 256, 112, 16
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 2, replace=False)] *= 20
+    w[64:96, 5] = 0.0                                   # with rank 0 below: an all-zero block
+    ax = np.abs(rng.standard_normal(K)).astype(np.float32) + 0.1
+    b = rng.standard_normal(N).astype(np.float32)
+    for rank in (r, 0):
+        prep = S.svdq_fp4_prepare(w, ax, rank, bias=b)
+        assert prep.shape.group == 32
+        U = S.svdq_fp4_unpack(prep)
+        lam = O.smoothing_factor(ax, w, 0.5)
+        assert np.array_equal(U["rinv"], O.reciprocal_f32(lam))
+        qw, bw, R = F.residual_codes_from_factors(w, U["rinv"], U["l1s"], U["l2"])
+        assert np.array_equal(U["bw"], bw)
+        assert np.array_equal(F.decode_e2m1(U["qw"]), F.decode_e2m1(qw))
+        assert np.array_equal(U["bias"], b)
+        if rank == 0:
+            assert U["bw"][2, 5] == 0 and not U["qw"][64:96, 5].any()
+        # round trip through the canonical forms
+        again = S.svdq_fp4_pack(U["rinv"], U["l1s"], U["l2"], U["qw"], U["bw"], U["bias"])
+        assert np.array_equal(again.wcodes, prep.wcodes) and np.array_equal(again.wscales, prep.wscales)
+        assert np.array_equal(again.l1s, prep.l1s) and np.array_equal(again.l2, prep.l2)
+    # native order: nibble t of the 16 bytes at fp4_code_offset = element 32 kb + t of the step; 4 steps share a scale dword
+    Np = 256
+    g, n, kb, t = 3, 37, 1, 13
+    off = (((g * (Np // 32) + n // 32) * 2 + kb) * 32 + n % 32) * 16 + t // 2
+    nib = (prep.wcodes[off] >> 4) if t & 1 else (prep.wcodes[off] & 15)
+    assert nib == U["qw"][64 * g + 32 * kb + t, n]
+    soff = (((g // 4) * (Np // 32) + n // 32) * 64 + kb * 32 + n % 32) * 4 + g % 4
+    assert prep.wscales[soff] == U["bw"][2 * g + kb, n]
+    # errors: INT4 entry points refuse the MXFP4 shape and vice versa; 255 is not a scale
+    sz = S.Sizes()
+    assert lib.svdq_prepared_sizes(C.byref(prep.shape), C.byref(sz)) == -2
+    assert lib.svdq_fp4_prepared_sizes(C.byref(S.make_shape(K, N, 16)), C.byref(sz)) == -2
+    bad = U["bw"].copy()
+    bad[0, 0] = 255
+    with pytest.raises(S.SvdqError):
+        S.svdq_fp4_pack(U["rinv"], U["l1s"], U["l2"], U["qw"], bad, U["bias"])
+    # workspace: codes G * Mpad * 32, scale dwords ceil(G/4) * Mpad * 8, H and its bf16 split (rank 0: one column each)
+    assert S.svdq_workspace_bytes(300, prep.shape) == 4 * 512 * 32 + 1 * 512 * 8 + 2 * (512 * 1 * 4)

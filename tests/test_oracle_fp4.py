@@ -49,8 +49,8 @@ def test_block_scale_is_the_smallest_power_of_two_that_keeps_the_block_in_range(
         if not np.isfinite(amax) or amax == 0:
             continue
         b = int(F.block_scale_byte(amax))
-        assert b == min(254, max(0, k + 127)), k                    # exactly 6 * 2^k  ->  2^k
-        if 0 < k + 127 < 254:
+        assert b == min(254, max(1, k + 127)), k                    # exactly 6 * 2^k  ->  2^k
+        if 1 < k + 127 < 254:
             assert int(F.block_scale_byte(np.nextafter(amax, np.float32(np.inf)))) == b + 1      # just above -> next power
             assert int(F.block_scale_byte(np.nextafter(amax, np.float32(0)))) == b
     rng = np.random.default_rng(6)
