@@ -159,3 +159,49 @@ def test_full_size_layers_on_sampled_rows(torch, name):
     rows = np.unique(np.concatenate([np.arange(0, 4), np.random.default_rng(5).integers(0, case.M, 24), np.arange(case.M - 4, case.M)]))
     _say(f"fp4 {name}: M={case.M} K={case.K} N={case.N} r={case.rank}, {len(rows)} sampled rows")
     _run_and_compare(torch, L["x_bf16"], prep, rows=rows, what=f"fp4 {name}")
+
+
+def test_lora_appended_to_an_fp4_layer(torch):
+    """The adapter path is format-independent: it only touches the 16-bit branch."""
+    rng = np.random.default_rng(2400)
+    M, K, N, r, r_add = 150, 512, 400, 32, 24
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    down = (rng.standard_normal((K, r_add)) * 0.05).astype(np.float32)
+    up = (rng.standard_normal((r_add, N)) * 0.05).astype(np.float32)
+    base = S.svdq_fp4_prepare(w, ax, r, bias=b)
+    tuned = S.svdq_append_lora(base, down, up, scale=0.5)
+    assert tuned.shape.group == 32 and tuned.shape.rank == 64 and tuned.wcodes is base.wcodes
+    U0, U1 = S.svdq_fp4_unpack(base), S.svdq_fp4_unpack(tuned)
+    want = O.append_lora({"l1s": U0["l1s"], "l2": U0["l2"]}, down, up, scale=0.5)
+    assert np.array_equal(U1["l1s"], want["l1s"]) and np.array_equal(U1["l2"], want["l2"])
+    _run_and_compare(torch, xb, tuned, what="fp4 + lora")
+
+
+def test_forward_replayed_from_a_hip_graph(torch):
+    """Both kernels captured once and replayed with eager work and synchronisations in between: every replay
+    must reproduce the eager result bit for bit (the direct-to-LDS ring and the barriers hold no state across launches)."""
+    rng = np.random.default_rng(2500)
+    xb, w, ax, b = _random_layer(rng, 200, 704, 528)
+    layer = S.DeviceLayer(S.svdq_fp4_prepare(w, ax, 32, bias=b))
+    x = S.bf16_tensor_from_bits(xb)
+    ws = layer.workspace(200)
+    y_eager = S.bits_from_bf16_tensor(layer.forward(x, workspace=ws))
+    y = torch.zeros((200, 528), dtype=torch.bfloat16, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        layer.forward(x, out=y, workspace=ws, stream=side)      # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            layer.forward(x, out=y, workspace=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(4):
+        y.zero_()
+        ws.random_(0, 255)                                    # scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(S.bits_from_bf16_tensor(y), y_eager), f"replay {i}"
+        _ = layer.forward(x)                                  # eager work between the replays
+        torch.cuda.synchronize()
