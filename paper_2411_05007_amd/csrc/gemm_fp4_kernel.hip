@@ -75,9 +75,15 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     const int tiles_m = (p.M + kBM - 1) / kBM;
     const int tiles_n = (p.N + kBN - 1) / kBN;
     const int total = tiles_m * tiles_n;
+    // with a split K loop the grid holds ksplit copies of the tile set; copy `split` multiplies steps [g_begin, g_end),
+    // a multiple of four steps each (the scale dwords carry four steps)
+    const int split = (int)blockIdx.x / total;
+    const int g_per = ((p.G + p.ksplit - 1) / p.ksplit + 3) / 4 * 4;
+    const int g_begin = split * g_per;
+    const int g_end = g_begin + g_per < p.G ? g_begin + g_per : p.G;
     int tile_m, tile_n;
     {
-        const int bid = (int)blockIdx.x;
+        const int bid = (int)blockIdx.x - split * total;
         const int per = (total + 7) / 8;
         const int id = (total % 8 == 0) ? (bid % 8) * per + (bid / 8) : bid;      // a bijection only when 8 divides the count
         constexpr int kBand = 4;
@@ -119,7 +125,7 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     };
     // Memory -> LDS without a stop in registers: wavefront w fetches activation block w and weight blocks w and w + 4
     // of the step (one kilobyte each, lane l's 16 bytes land at l * 16 of the block, which is the operand order).
-    const int glast = p.G - 1;
+    const int glast = g_end - 1;
     const int ta_base = gm0 * kFp4RowBytes + wave * 1024, tb_base = gn0 * kFp4RowBytes + wave * 1024;
     auto dma = [&](int g, int stage) {
         const int gc = g < glast ? g : glast;      // past the end: the last step once more (never read), so that every step issues three requests
@@ -144,19 +150,19 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     // all LDS reads of this wavefront have returned; tied to the registers they fill, so that nothing that uses them moves above
 #define SVDQ_READS_DONE(F) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(F.a[0]), "+v"(F.a[1]), "+v"(F.b[0]), "+v"(F.b[1]), "+v"(F.b[2]), "+v"(F.b[3]))
 
-    const int chunks = (p.G + 3) / 4;
+    const int q_begin = g_begin / 4, q_end = (g_end + 3) / 4;
     Frags f0, f1;
     Scales sc;
-    load_scales(sc, 0);
-    dma(0, 0);
-    dma(1, 1);
-    dma(2, 2);
+    load_scales(sc, q_begin);
+    dma(g_begin, 0);
+    dma(g_begin + 1, 1);
+    dma(g_begin + 2, 2);
     __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
 
     // ---- low-rank up projection: the accumulators START as H L2 (bf16 MFMAs, H as exact hi + lo parts) ----
     // The operands of rank step ks + 1 are requested before step ks is multiplied, so the branch pays one memory
     // round trip (shared with the first operand blocks of the main loop), not one per 16 columns of H.
-    if (p.rank > 0) {
+    if (p.rank > 0 && split == 0) {      // one split carries the low-rank product
         const int ksteps = p.rank / 16;
         const unsigned char *hf = p.hfrag + (size_t)((gm0 + wm0) / 32) * ksteps * 2048 + lane * 16;
         struct LowRank { uint4 hhi[kRB], hlo[kRB], braw[kCB]; };
@@ -208,11 +214,11 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     SVDQ_READ_STAGE(f0, 0)
     SVDQ_READS_DONE(f0);
 #define SVDQ_FP4_STEP(SEL, cur, nxt)                                                                                  \
-    if (g0 + SEL < p.G) {                                                                                             \
+    if (g0 + SEL < g_end) {                                                                                           \
         asm volatile("s_waitcnt vmcnt(3)" ::: "memory");                                                              \
         __builtin_amdgcn_s_barrier();                                                                                 \
         SVDQ_READ_STAGE(nxt, (SEL + 1) & 3)                                                                           \
-        if (SEL == 0) load_scales(sn, q + 1 < chunks ? q + 1 : q);                                                    \
+        if (SEL == 0) load_scales(sn, q + 1 < q_end ? q + 1 : q);                                                     \
         dma(g0 + SEL + 3, (SEL + 3) & 3);                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                            \
         _Pragma("unroll") for (int r = 0; r < kRB; ++r)                                                               \
@@ -222,7 +228,7 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
         __builtin_amdgcn_sched_barrier(0);                                                                            \
         SVDQ_READS_DONE(nxt);                                                                                         \
     }
-    for (int q = 0; q < chunks; ++q) {
+    for (int q = q_begin; q < q_end; ++q) {
         const int g0 = 4 * q;
         Scales sn;
         SVDQ_FP4_STEP(0, f0, f1)
@@ -235,6 +241,50 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     // the ring becomes the epilogue's staging area: every request of every wavefront must have landed first
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
+
+    // ---- split K loop: park the partial tile, the last workgroup to arrive adds them all up -------------------------
+    // Partial tiles are stored in register order (128 floats per thread, consecutive threads consecutive addresses)
+    // with device-scope atomic accesses: the L2 caches of the chip's eight XCDs are not coherent with each other, and
+    // these accesses go past them; no cache is flushed.  A workgroup takes its ticket once all its stores have been
+    // acknowledged; the holder of the last ticket reads all partials back, its own included, and adds them in split
+    // order, so the sum does not depend on who came last.  Nobody waits for anybody.
+    if (p.ksplit > 1) {
+        const int tile_lin = tile_m * tiles_n + tile_n;
+        constexpr int kTileWords = kBM * kBN;
+        float *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
+#pragma unroll
+        for (int r = 0; r < kRB; ++r)
+#pragma unroll
+            for (int c = 0; c < kCB; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    __hip_atomic_store(mine + ((r * kCB + c) * 16 + v) * 256, acc[r][c][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // every store of this thread has been acknowledged
+        __syncthreads();
+        uint32_t *ticket = reinterpret_cast<uint32_t *>(lds);      // the ring is no longer in use
+        if (tid == 0) *ticket = __hip_atomic_fetch_add(&p.counters[tile_lin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const bool last = *ticket == (uint32_t)(p.ksplit - 1);
+        __syncthreads();                                          // the epilogue reuses this LDS word
+        if (!last) return;
+        if (tid == 0) __hip_atomic_store(&p.counters[tile_lin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next launch
+#pragma unroll
+        for (int r = 0; r < kRB; ++r)
+#pragma unroll
+            for (int c = 0; c < kCB; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+        const float *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
+        for (int sidx = 0; sidx < p.ksplit; ++sidx) {
+#pragma unroll
+            for (int r = 0; r < kRB; ++r)
+#pragma unroll
+                for (int c = 0; c < kCB; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[r][c][v] += __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * kCB + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 
     // ---- epilogue: bias, bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores --------
     unsigned char *ob = lds + wave * (32 * kOutRowFp4);
@@ -285,7 +335,10 @@ hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream) {
         (size_t)p.G * p.Mpad * kFp4RowBytes >= (size_t)1 << 31 || (size_t)p.G * p.Npad * kFp4RowBytes >= (size_t)1 << 31)
         return hipErrorInvalidValue;
     const int tiles = ((p.M + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN);
-    const dim3 grid(tiles), block(256);
+    if (p.ksplit < 1 || (p.ksplit > 1 && (!p.partial || !p.counters))) return hipErrorInvalidValue;
+    // every split must own at least one step (splits are multiples of four steps)
+    if (p.ksplit > 1 && (size_t)(p.ksplit - 1) * (((p.G + p.ksplit - 1) / p.ksplit + 3) / 4 * 4) >= (size_t)p.G) return hipErrorInvalidValue;
+    const dim3 grid(tiles * p.ksplit), block(256);
     auto k = gemm_fp4_kernel;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsFp4);
     if (e != hipSuccess) return e;

@@ -86,6 +86,9 @@ struct GemmFp4Params {
     const float *bias;       // fp32 [Npad]
     uint16_t *Y;             // bf16 [M][N]
     int M, N, K, G, Mpad, Npad, rank;
+    int ksplit;              // workgroups per tile along K (1 = no split); splits are multiples of four steps
+    float *partial;          // ksplit > 1: fp32 [tile][split][128 * 256] partial tiles, register order
+    uint32_t *counters;      // ksplit > 1: one arrival counter per tile, zero when the kernel starts
 };
 hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream);
 

@@ -88,6 +88,7 @@ inline __host__ __device__ size_t l1s_index(int K, int rank, int k, int j) {
 // so one 32-row block of one step is one contiguous kilobyte of codes, loaded with one 16-byte load per lane.
 constexpr int kFp4Block = 32;
 constexpr int kFp4RowBytes = 32;     // packed bytes of one row of one 64-channel step
+constexpr int kMaxKSplitFp4 = 8;
 inline __host__ __device__ size_t fp4_code_offset(int g, int rows_pad, int row, int kb) {
     return ((((size_t)g * (rows_pad / 32) + row / 32) * 2 + kb) * 32 + row % 32) * 16;
 }
@@ -96,11 +97,33 @@ inline __host__ __device__ size_t fp4_scale_offset(int g, int rows_pad, int row,
 }
 inline __host__ __device__ size_t fp4_scale_bytes(int G, int rows_pad) { return (size_t)((G + 3) / 4) * rows_pad * 8; }
 
-struct WorkspaceFp4 {
-    size_t codes_off, bx_off, h_off, hfrag_off, total;
-    int Mpad;
+// Launch plan of the MXFP4 GEMM (one tile shape, 128 x 256).  A launch with fewer workgroups than the chip has
+// places for (two per CU) splits the K loop over `ksplit` workgroups per tile, each a multiple of four steps and
+// at least eight steps long; the partial tiles meet in the workspace as in the INT4 kernel.
+struct GemmPlanFp4 {
+    int tiles, ksplit;
 };
-inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int rank) {
+inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G) {
+    GemmPlanFp4 pl;
+    pl.tiles = ((M + 127) / 128) * ((N + 255) / 256);
+    int s = 1;
+    if (pl.tiles < 384) {
+        s = 512 / pl.tiles;
+        if (s > kMaxKSplitFp4) s = kMaxKSplitFp4;
+        while (s > 1 && G / s < 8) --s;
+    }
+    // normalise: splits are multiples of four steps, none empty
+    while (s > 1 && (size_t)(s - 1) * (((G + s - 1) / s + 3) / 4 * 4) >= (size_t)G) --s;
+    pl.ksplit = s < 1 ? 1 : s;
+    return pl;
+}
+
+struct WorkspaceFp4 {
+    size_t codes_off, bx_off, h_off, hfrag_off, counters_off, partial_off, total;
+    int Mpad;
+    int n_counters;
+};
+inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank) {
     WorkspaceFp4 w;
     w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
     const int G = K / kGroup;
@@ -108,7 +131,11 @@ inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int rank) {
     w.bx_off = align256((size_t)G * w.Mpad * kFp4RowBytes);
     w.h_off = w.bx_off + align256(fp4_scale_bytes(G, w.Mpad));
     w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    w.total = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, G);
+    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
+    w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
+    w.total = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);
     return w;
 }
 

@@ -106,6 +106,24 @@ def test_ragged_shapes(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"fp4 ragged {M}x{K}x{N} r{r}")
 
 
+@pytest.mark.parametrize("M,K,N,r", [(100, 3072, 272, 32), (70, 3136, 144, 16), (200, 6144, 400, 48), (512, 3072, 3072, 32)])
+def test_small_launches_with_split_k_loop(torch, M, K, N, r):
+    """Few tiles and a long K: the K loop is split over several workgroups per tile (each a multiple of four steps),
+    which park fp32 partial tiles in the workspace; the last one to arrive adds them in split order.  Run twice on
+    the same workspace: the arrival counters must be left ready, and the result must not depend on arrival order."""
+    rng = np.random.default_rng(2600 + M + K)
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    prep = S.svdq_fp4_prepare(w, ax, r, bias=b)
+    _say(f"fp4 split-K: M={M} K={K} N={N} r={r}")
+    _run_and_compare(torch, xb, prep, what=f"fp4 split {M}x{K}x{N} r{r}")
+    layer = S.DeviceLayer(prep)
+    x = S.bf16_tensor_from_bits(xb)
+    ws = layer.workspace(M)
+    y0 = S.bits_from_bf16_tensor(layer.forward(x, workspace=ws))
+    for _ in range(3):
+        assert np.array_equal(S.bits_from_bf16_tensor(layer.forward(x, workspace=ws)), y0)
+
+
 def test_scales_over_a_wide_exponent_range_and_exact_grid_inputs(torch):
     """Activations whose blocks span 2^-60 .. 2^60, and inputs that sit exactly on the E2M1 grid (reproduced exactly)."""
     rng = np.random.default_rng(2100)
@@ -177,16 +195,17 @@ def test_lora_appended_to_an_fp4_layer(torch):
     _run_and_compare(torch, xb, tuned, what="fp4 + lora")
 
 
-def test_forward_replayed_from_a_hip_graph(torch):
+@pytest.mark.parametrize("M,K,N", [(200, 704, 528), (90, 3072, 272)])
+def test_forward_replayed_from_a_hip_graph(torch, M, K, N):
     """Both kernels captured once and replayed with eager work and synchronisations in between: every replay
     must reproduce the eager result bit for bit (the direct-to-LDS ring and the barriers hold no state across launches)."""
     rng = np.random.default_rng(2500)
-    xb, w, ax, b = _random_layer(rng, 200, 704, 528)
+    xb, w, ax, b = _random_layer(rng, M, K, N)      # the second shape runs with the K loop split
     layer = S.DeviceLayer(S.svdq_fp4_prepare(w, ax, 32, bias=b))
     x = S.bf16_tensor_from_bits(xb)
-    ws = layer.workspace(200)
+    ws = layer.workspace(M)
     y_eager = S.bits_from_bf16_tensor(layer.forward(x, workspace=ws))
-    y = torch.zeros((200, 528), dtype=torch.bfloat16, device="cuda:0")
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
