@@ -206,7 +206,7 @@ int svdq_debug_group_acc(const svdq_layer_dev *L, const void *workspace, int M, 
 
 size_t svdq_fp4_workspace_bytes(int M, const svdq_shape *s) {
     if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
-    return svdq::workspace_layout_fp4(M, s->K, s->N, s->rank).total;
+    return svdq::workspace_layout_fp4(M, s->K, s->N, s->rank, ksplit_override()).total;
 }
 
 int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
@@ -218,7 +218,7 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank);
+    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank, ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
     if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
@@ -258,7 +258,7 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     g.M = M; g.N = s.N; g.K = s.K; g.G = s.K / svdq::kGroup;
     g.Mpad = w.Mpad; g.Npad = svdq::round_up(s.N, svdq::kRowPad);
     g.rank = lowrank ? s.rank : 0;
-    g.ksplit = svdq::plan_gemm_fp4(M, s.N, s.K / svdq::kGroup).ksplit;
+    g.ksplit = svdq::plan_gemm_fp4(M, s.N, s.K / svdq::kGroup, ksplit_override()).ksplit;
     g.partial = reinterpret_cast<float *>(ws + w.partial_off);
     g.counters = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     e = svdq::launch_gemm_fp4(g, stream);
@@ -272,7 +272,7 @@ int svdq_fp4_debug_act(const svdq_layer_dev *L, const void *workspace, int M, ui
     if (M < 0 || !workspace) return SVDQ_EINVAL;
     if (M == 0) return SVDQ_OK;
     const svdq_shape &s = L->shape;
-    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank);
+    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank, ksplit_override());
     const unsigned char *ws = static_cast<const unsigned char *>(workspace);
     svdq::DebugActFp4Params d{};
     d.codes = ws + w.codes_off;

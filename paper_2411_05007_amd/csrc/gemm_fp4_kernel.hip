@@ -277,12 +277,21 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
         const float *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
         for (int sidx = 0; sidx < p.ksplit; ++sidx) {
 #pragma unroll
-            for (int r = 0; r < kRB; ++r)
+            for (int r = 0; r < kRB; ++r) {
+                // the 64 values of a row of blocks are requested together, then added: one round trip per batch
+                float t[kCB][16];
 #pragma unroll
                 for (int c = 0; c < kCB; ++c)
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
-                        acc[r][c][v] += __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * kCB + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        t[c][v] = __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * kCB + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c = 0; c < kCB; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[r][c][v] += t[c][v];
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
 

@@ -98,20 +98,23 @@ inline __host__ __device__ size_t fp4_scale_offset(int g, int rows_pad, int row,
 inline __host__ __device__ size_t fp4_scale_bytes(int G, int rows_pad) { return (size_t)((G + 3) / 4) * rows_pad * 8; }
 
 // Launch plan of the MXFP4 GEMM (one tile shape, 128 x 256).  A launch with fewer workgroups than the chip has
-// places for (two per CU) splits the K loop over `ksplit` workgroups per tile, each a multiple of four steps and
-// at least eight steps long; the partial tiles meet in the workspace as in the INT4 kernel.
+// places for (two per CU) splits a long K loop over up to four workgroups per tile, each a multiple of four steps
+// and at least 32 steps long (measured: at 48 steps per tile the parked partial tiles cost what the shorter loop
+// saves; at 192 steps four splits halve the time, eight are slower again); the partial tiles meet in the
+// workspace as in the INT4 kernel.
 struct GemmPlanFp4 {
     int tiles, ksplit;
 };
-inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G) {
+inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0) {
     GemmPlanFp4 pl;
     pl.tiles = ((M + 127) / 128) * ((N + 255) / 256);
     int s = 1;
-    if (pl.tiles < 384) {
+    if (pl.tiles <= 128) {                          // measured: with 160 tiles and 72 steps two splits are slower than none
         s = 512 / pl.tiles;
-        if (s > kMaxKSplitFp4) s = kMaxKSplitFp4;
-        while (s > 1 && G / s < 8) --s;
+        if (s > 4) s = 4;
+        while (s > 1 && G / s < 32) --s;
     }
+    if (ksplit_override > 0) s = ksplit_override < kMaxKSplitFp4 ? ksplit_override : kMaxKSplitFp4;
     // normalise: splits are multiples of four steps, none empty
     while (s > 1 && (size_t)(s - 1) * (((G + s - 1) / s + 3) / 4 * 4) >= (size_t)G) --s;
     pl.ksplit = s < 1 ? 1 : s;
@@ -123,7 +126,7 @@ struct WorkspaceFp4 {
     int Mpad;
     int n_counters;
 };
-inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank) {
+inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank, int ksplit_override = 0) {
     WorkspaceFp4 w;
     w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
     const int G = K / kGroup;
@@ -132,7 +135,7 @@ inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank) {
     w.h_off = w.bx_off + align256(fp4_scale_bytes(G, w.Mpad));
     w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
     w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, G);
+    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, G, ksplit_override);
     w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
     w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
     w.total = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);

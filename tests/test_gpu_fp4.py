@@ -106,11 +106,12 @@ def test_ragged_shapes(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"fp4 ragged {M}x{K}x{N} r{r}")
 
 
-@pytest.mark.parametrize("M,K,N,r", [(100, 3072, 272, 32), (70, 3136, 144, 16), (200, 6144, 400, 48), (512, 3072, 3072, 32)])
+@pytest.mark.parametrize("M,K,N,r", [(100, 6144, 272, 32), (70, 6208, 144, 16), (200, 12288, 400, 48), (130, 4160, 528, 0)])
 def test_small_launches_with_split_k_loop(torch, M, K, N, r):
     """Few tiles and a long K: the K loop is split over several workgroups per tile (each a multiple of four steps),
     which park fp32 partial tiles in the workspace; the last one to arrive adds them in split order.  Run twice on
-    the same workspace: the arrival counters must be left ready, and the result must not depend on arrival order."""
+    the same workspace: the arrival counters must be left ready, and the result must not depend on arrival order.
+    (K = 6144: 3 splits of 32 steps; 6208: 97 steps as 36 + 36 + 25; 12288: 4 splits; 4160: 65 steps as 36 + 29.)"""
     rng = np.random.default_rng(2600 + M + K)
     xb, w, ax, b = _random_layer(rng, M, K, N)
     prep = S.svdq_fp4_prepare(w, ax, r, bias=b)
@@ -195,7 +196,7 @@ def test_lora_appended_to_an_fp4_layer(torch):
     _run_and_compare(torch, xb, tuned, what="fp4 + lora")
 
 
-@pytest.mark.parametrize("M,K,N", [(200, 704, 528), (90, 3072, 272)])
+@pytest.mark.parametrize("M,K,N", [(200, 704, 528), (90, 6144, 272)])
 def test_forward_replayed_from_a_hip_graph(torch, M, K, N):
     """Both kernels captured once and replayed with eager work and synchronisations in between: every replay
     must reproduce the eager result bit for bit (the direct-to-LDS ring and the barriers hold no state across launches)."""

@@ -266,3 +266,6 @@ def test_fp4_prepare_matches_the_oracle_given_the_same_factors(lib):
         S.svdq_fp4_pack(U["rinv"], U["l1s"], U["l2"], U["qw"], bad, U["bias"])
     # workspace: codes G * Mpad * 32, scale dwords ceil(G/4) * Mpad * 8, H and its bf16 split (rank 0: one column each)
     assert S.svdq_workspace_bytes(300, prep.shape) == 4 * 512 * 32 + 1 * 512 * 8 + 2 * (512 * 1 * 4)
+    # a long K and few tiles: arrival counters (one per tile, padded to 256 bytes) and ksplit fp32 partial tiles of 128 x 256 per tile
+    long_k = S.make_shape(12288, 3072, 32, group=32)
+    assert S.svdq_workspace_bytes(512, long_k) == 192 * 512 * 32 + 48 * 512 * 8 + 2 * (512 * 32 * 4) + 256 + 4 * 48 * 128 * 256 * 4
