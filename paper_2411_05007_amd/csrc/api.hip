@@ -258,7 +258,9 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     g.M = M; g.N = s.N; g.K = s.K; g.G = s.K / svdq::kGroup;
     g.Mpad = w.Mpad; g.Npad = svdq::round_up(s.N, svdq::kRowPad);
     g.rank = lowrank ? s.rank : 0;
-    g.ksplit = svdq::plan_gemm_fp4(M, s.N, s.K / svdq::kGroup, ksplit_override()).ksplit;
+    const svdq::GemmPlanFp4 plan = svdq::plan_gemm_fp4(M, s.N, s.K / svdq::kGroup, ksplit_override());
+    g.tile = plan.tile;
+    g.ksplit = plan.ksplit;
     g.partial = reinterpret_cast<float *>(ws + w.partial_off);
     g.counters = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     e = svdq::launch_gemm_fp4(g, stream);

@@ -36,16 +36,23 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBM = 128, kBN = 256;          // workgroup tile
-constexpr int kWM = 64, kWN = 128;           // wavefront tile
-constexpr int kRB = kWM / 32, kCB = kWN / 32;
-constexpr int kOutRowFp4 = kWN * 2 + 16;     // epilogue staging: 128 bf16 columns + 16 bytes pad per row
-constexpr int kStages = 4;                   // operand ring in LDS: one stage = the 4 + 8 operand blocks of one 64-channel step
-constexpr int kFragsA = kBM / 32, kFragsB = kBN / 32;
-constexpr int kStageBytes = (kFragsA + kFragsB) * 1024;
-constexpr int kRingBytes = kStages * kStageBytes;
-constexpr int kOutBytesFp4 = 4 * 32 * kOutRowFp4;
-constexpr int kLdsFp4 = kRingBytes > kOutBytesFp4 ? kRingBytes : kOutBytesFp4;
+// Tile configuration: 2 x 2 wavefronts, each RB x CB MFMA blocks of 32 x 32.  <2, 4>: 128 x 256 workgroup tile;
+// <3, 3>: 192 x 192 (nine MFMAs per six operand blocks instead of eight; used where it makes the tile count a whole
+// number of rounds of the chip's 512 workgroup places, e.g. 24 x 64 = 1536 tiles for M = 4608, N = 12288).
+// Both have 12 operand blocks per step: three direct-to-LDS loads per wavefront.
+template <int RB, int CB>
+struct Fp4Tile {
+    static constexpr int kRB = RB, kCB = CB;
+    static constexpr int kWM = 32 * RB, kWN = 32 * CB;               // wavefront tile
+    static constexpr int kBM = 2 * kWM, kBN = 2 * kWN;               // workgroup tile
+    static constexpr int kOutRow = kWN * 2 + 16;                     // epilogue staging: one row of bf16 + 16 bytes pad
+    static constexpr int kFragsA = kBM / 32, kFragsB = kBN / 32;
+    static constexpr int kStageBytes = (kFragsA + kFragsB) * 1024;   // one stage = the operand blocks of one 64-channel step
+    static constexpr int kRingBytes = 4 * kStageBytes;               // four stages
+    static constexpr int kOutBytes = 4 * 32 * kOutRow;
+    static constexpr int kLdsBytes = kRingBytes > kOutBytes ? kRingBytes : kOutBytes;
+    static_assert(kFragsA + kFragsB == 12 && RB + CB == 6, "three direct loads per wavefront and step, six operand blocks per wavefront");
+};
 typedef __attribute__((address_space(3))) void *lds_ptr;
 constexpr int kFmtE2M1 = 4;                  // operand format selector of the instruction
 
@@ -61,7 +68,11 @@ __device__ __forceinline__ intx8 as_operand(u32x4 v) {
     return intx8{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
 }
 
+template <int RB, int CB>
 __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
+    using T = Fp4Tile<RB, CB>;
+    constexpr int kRB = RB, kCB = CB, kWM = T::kWM, kWN = T::kWN, kBM = T::kBM, kBN = T::kBN;
+    constexpr int kFragsA = T::kFragsA, kStageBytes = T::kStageBytes, kOutRowFp4 = T::kOutRow;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -93,7 +104,7 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
         tile_m = band * kBand + in % band_rows;
         tile_n = in / band_rows;
     }
-    const int gm0 = tile_m * kBM, gn0 = tile_n * kBN;      // gm0 + 128 <= Mpad, gn0 + 256 <= Npad (both padded to 256)
+    const int gm0 = tile_m * kBM, gn0 = tile_n * kBN;      // the launch checks that every tile lies inside the padded rows and columns
 
     floatx16 acc[kRB][kCB];
 #pragma unroll
@@ -115,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     const int sa_stride = p.Mpad * 8, sa_base = (gm0 + wm0) * 8;
     const int sb_stride = p.Npad * 8, sb_base = (gn0 + wn0) * 8;
 
-    struct Frags { u32x4 a[kRB], b[kCB]; };
+    struct Frags { u32x4 f[kRB + kCB]; };      // the wavefront's activation blocks, then its weight blocks
     struct Scales { uint32_t a[kRB], b[kCB]; };
     auto load_scales = [&](Scales &s, int q) {
 #pragma unroll
@@ -123,32 +134,39 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
 #pragma unroll
         for (int c = 0; c < kCB; ++c) s.b[c] = __builtin_amdgcn_raw_buffer_load_b32(rs_sb, lane * 4, sb_base + q * sb_stride + c * 256, 0);
     };
-    // Memory -> LDS without a stop in registers: wavefront w fetches activation block w and weight blocks w and w + 4
-    // of the step (one kilobyte each, lane l's 16 bytes land at l * 16 of the block, which is the operand order).
+    // Memory -> LDS without a stop in registers: the twelve operand blocks of a step (activation blocks first) are
+    // dealt to the four wavefronts, blocks w, w + 4 and w + 8 to wavefront w (one kilobyte each; lane l's 16 bytes
+    // land at l * 16 of the block, which is the operand order).  Which operand a block belongs to is uniform per wavefront.
     const int glast = g_end - 1;
-    const int ta_base = gm0 * kFp4RowBytes + wave * 1024, tb_base = gn0 * kFp4RowBytes + wave * 1024;
+    __amdgpu_buffer_rsrc_t rs_d[3];
+    int d_base[3], d_stride[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int j = wave + 4 * i;
+        const bool is_a = j < kFragsA;
+        rs_d[i] = is_a ? make_rsrc(p.xcodes, (size_t)p.G * p.Mpad * kFp4RowBytes) : make_rsrc(p.wcodes, (size_t)p.G * p.Npad * kFp4RowBytes);
+        d_base[i] = is_a ? gm0 * kFp4RowBytes + j * 1024 : gn0 * kFp4RowBytes + (j - kFragsA) * 1024;
+        d_stride[i] = is_a ? a_stride : b_stride;
+    }
     auto dma = [&](int g, int stage) {
         const int gc = g < glast ? g : glast;      // past the end: the last step once more (never read), so that every step issues three requests
         unsigned char *st = lds + stage * kStageBytes + wave * 1024;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)st, 16, lane * 16, ta_base + gc * a_stride, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(st + kFragsA * 1024), 16, lane * 16, tb_base + gc * b_stride, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(st + (kFragsA + 4) * 1024), 16, lane * 16, tb_base + gc * b_stride + 4096, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_d[i], (lds_ptr)(st + i * 4096), 16, lane * 16, d_base[i] + gc * d_stride[i], 0, 0);
     };
     // LDS -> registers.  These reads are written as instructions of their own, with explicit waits, because the
     // compiler would make every LDS read wait for ALL outstanding memory-to-LDS requests, also those of later stages.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
     const uint32_t rd_a = lds_base + lane * 16 + (wm0 / 32) * 1024;
     const uint32_t rd_b = lds_base + lane * 16 + (kFragsA + wn0 / 32) * 1024;
-#define SVDQ_LDS_READ(DST, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST) : "v"(ADDR), "n"(OFF))
-#define SVDQ_READ_STAGE(F, STAGE)                                \
-    SVDQ_LDS_READ(F.a[0], rd_a, (STAGE) * kStageBytes);          \
-    SVDQ_LDS_READ(F.a[1], rd_a, (STAGE) * kStageBytes + 1024);   \
-    SVDQ_LDS_READ(F.b[0], rd_b, (STAGE) * kStageBytes);          \
-    SVDQ_LDS_READ(F.b[1], rd_b, (STAGE) * kStageBytes + 1024);   \
-    SVDQ_LDS_READ(F.b[2], rd_b, (STAGE) * kStageBytes + 2048);   \
-    SVDQ_LDS_READ(F.b[3], rd_b, (STAGE) * kStageBytes + 3072);
+#define SVDQ_LDS_READ(F, I, STAGE) \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(F.f[I]) : "v"((I) < kRB ? rd_a : rd_b), "n"((STAGE) * kStageBytes + ((I) < kRB ? (I) : (I) - kRB) * 1024))
+#define SVDQ_READ_STAGE(F, STAGE) \
+    SVDQ_LDS_READ(F, 0, STAGE); SVDQ_LDS_READ(F, 1, STAGE); SVDQ_LDS_READ(F, 2, STAGE); \
+    SVDQ_LDS_READ(F, 3, STAGE); SVDQ_LDS_READ(F, 4, STAGE); SVDQ_LDS_READ(F, 5, STAGE);
     // all LDS reads of this wavefront have returned; tied to the registers they fill, so that nothing that uses them moves above
-#define SVDQ_READS_DONE(F) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(F.a[0]), "+v"(F.a[1]), "+v"(F.b[0]), "+v"(F.b[1]), "+v"(F.b[2]), "+v"(F.b[3]))
+#define SVDQ_READS_DONE(F) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(F.f[0]), "+v"(F.f[1]), "+v"(F.f[2]), "+v"(F.f[3]), "+v"(F.f[4]), "+v"(F.f[5]))
 
     const int q_begin = g_begin / 4, q_end = (g_end + 3) / 4;
     Frags f0, f1;
@@ -223,7 +241,7 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
         __builtin_amdgcn_sched_barrier(0);                                                                            \
         _Pragma("unroll") for (int r = 0; r < kRB; ++r)                                                               \
             _Pragma("unroll") for (int c = 0; c < kCB; ++c)                                                           \
-                acc[r][c] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(cur.a[r]), as_operand(cur.b[c]), acc[r][c], \
+                acc[r][c] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_operand(cur.f[r]), as_operand(cur.f[kRB + c]), acc[r][c], \
                                                                             kFmtE2M1, kFmtE2M1, SEL, (int)sc.a[r], SEL, (int)sc.b[c]); \
         __builtin_amdgcn_sched_barrier(0);                                                                            \
         SVDQ_READS_DONE(nxt);                                                                                         \
@@ -250,7 +268,7 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     // order, so the sum does not depend on who came last.  Nobody waits for anybody.
     if (p.ksplit > 1) {
         const int tile_lin = tile_m * tiles_n + tile_n;
-        constexpr int kTileWords = kBM * kBN;
+        constexpr int kTileWords = T::kBM * T::kBN;
         float *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
 #pragma unroll
         for (int r = 0; r < kRB; ++r)
@@ -313,11 +331,11 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
                 *reinterpret_cast<uint16_t *>(ob + (row + 1) * kOutRowFp4 + (c * 32 + li) * 2) = (uint16_t)(pr >> 16);
             }
         }
-        // 32 rows x 256 bytes = 512 chunks of 16 bytes: eight per lane, sixteen lanes per row
+        // 32 rows of kWN bf16 = 32 * kWN / 8 chunks of 16 bytes: kWN / 16 per lane, kWN / 8 lanes per row
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < kWN / 16; ++i) {
             const int q = lane + 64 * i;
-            const int row = q >> 4, ch = q & 15;
+            const int row = q / (kWN / 8), ch = q % (kWN / 8);
             const uint4 v = *reinterpret_cast<const uint4 *>(ob + row * kOutRowFp4 + ch * 16);
             const int grow = gm0 + wm0 + r * 32 + row;
             const int gcol = gn0 + wn0 + ch * 8;
@@ -335,6 +353,20 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     }
 }
 
+template <int RB, int CB>
+hipError_t launch_fp4_tile(const GemmFp4Params &p, hipStream_t stream) {
+    using T = Fp4Tile<RB, CB>;
+    const int tiles_m = (p.M + T::kBM - 1) / T::kBM, tiles_n = (p.N + T::kBN - 1) / T::kBN;
+    // H, L2 and the bias are read with plain loads: every tile must lie inside the padded rows and columns
+    if (tiles_m * T::kBM > p.Mpad || tiles_n * T::kBN > p.Npad) return hipErrorInvalidValue;
+    const dim3 grid(tiles_m * tiles_n * p.ksplit), block(256);
+    auto k = gemm_fp4_kernel<RB, CB>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream) {
@@ -343,16 +375,14 @@ hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream) {
     if (p.G <= 0 || p.K != p.G * kGroup || p.Mpad % kRowPad || p.Npad % kRowPad || p.Mpad < p.M || p.Npad < p.N || p.rank % 16 ||
         (size_t)p.G * p.Mpad * kFp4RowBytes >= (size_t)1 << 31 || (size_t)p.G * p.Npad * kFp4RowBytes >= (size_t)1 << 31)
         return hipErrorInvalidValue;
-    const int tiles = ((p.M + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN);
-    if (p.ksplit < 1 || (p.ksplit > 1 && (!p.partial || !p.counters))) return hipErrorInvalidValue;
+    if (p.ksplit < 1 || (p.ksplit > 1 && (!p.partial || !p.counters || p.tile != 0))) return hipErrorInvalidValue;
     // every split must own at least one step (splits are multiples of four steps)
     if (p.ksplit > 1 && (size_t)(p.ksplit - 1) * (((p.G + p.ksplit - 1) / p.ksplit + 3) / 4 * 4) >= (size_t)p.G) return hipErrorInvalidValue;
-    const dim3 grid(tiles * p.ksplit), block(256);
-    auto k = gemm_fp4_kernel;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsFp4);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k, grid, block, kLdsFp4, stream, p);
-    return hipGetLastError();
+    switch (p.tile) {
+        case 0: return launch_fp4_tile<2, 4>(p, stream);
+        case 1: return launch_fp4_tile<3, 3>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace svdq

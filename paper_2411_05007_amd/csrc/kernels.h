@@ -86,6 +86,7 @@ struct GemmFp4Params {
     const float *bias;       // fp32 [Npad]
     uint16_t *Y;             // bf16 [M][N]
     int M, N, K, G, Mpad, Npad, rank;
+    int tile;                // 0: 128 x 256 workgroup tile, 1: 192 x 192 (only without a split K loop)
     int ksplit;              // workgroups per tile along K (1 = no split); splits are multiples of four steps
     float *partial;          // ksplit > 1: fp32 [tile][split][128 * 256] partial tiles, register order
     uint32_t *counters;      // ksplit > 1: one arrival counter per tile, zero when the kernel starts

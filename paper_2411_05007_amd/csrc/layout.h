@@ -103,6 +103,7 @@ inline __host__ __device__ size_t fp4_scale_bytes(int G, int rows_pad) { return 
 // saves; at 192 steps four splits halve the time, eight are slower again); the partial tiles meet in the
 // workspace as in the INT4 kernel.
 struct GemmPlanFp4 {
+    int tile;        // 0: 128 x 256, 1: 192 x 192
     int tiles, ksplit;
 };
 inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0) {
@@ -118,6 +119,18 @@ inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0) {
     // normalise: splits are multiples of four steps, none empty
     while (s > 1 && (size_t)(s - 1) * (((G + s - 1) / s + 3) / 4 * 4) >= (size_t)G) --s;
     pl.ksplit = s < 1 ? 1 : s;
+    pl.tile = 0;
+    // 192 x 192 tiles do nine MFMAs per step and wavefront instead of eight; they pay where they save a round of
+    // the chip's 512 workgroup places (two per CU) and fit the padded rows and columns exactly
+    if (pl.ksplit == 1 && pl.tiles > 512) {
+        const int tm = (M + 191) / 192, tn = (N + 191) / 192;
+        const long t192 = (long)tm * tn;
+        const long rounds128 = (pl.tiles + 511) / 512, rounds192 = (t192 + 511) / 512;
+        if (tm * 192 <= round_up(M, kRowPad) && tn * 192 <= round_up(N, kRowPad) && rounds192 * 9 < rounds128 * 8) {
+            pl.tile = 1;
+            pl.tiles = (int)t192;
+        }
+    }
     return pl;
 }
 

@@ -484,7 +484,7 @@ const char *svdq_status_string(int status) {
     switch (status) {
         case SVDQ_OK: return "ok";
         case SVDQ_EINVAL: return "invalid argument";
-        case SVDQ_EUNSUPPORTED: return "unsupported shape (need K % 64 == 0, N % 16 == 0, rank % 16 == 0, rank <= min(256, K, N), group == 64)";
+        case SVDQ_EUNSUPPORTED: return "unsupported shape (need K % 64 == 0, N % 16 == 0, rank % 16 == 0, rank <= min(256, K, N), group == 64 for INT4 or 32 for MXFP4)";
         case SVDQ_ENOMEM: return "out of host memory";
         case SVDQ_ENOSPACE: return "workspace too small";
         case SVDQ_EHIP: return "HIP error";

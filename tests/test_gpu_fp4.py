@@ -225,3 +225,14 @@ def test_forward_replayed_from_a_hip_graph(torch, M, K, N):
         assert np.array_equal(S.bits_from_bf16_tensor(y), y_eager), f"replay {i}"
         _ = layer.forward(x)                                  # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_ragged_launch_on_the_192_tile(torch):
+    """A launch large enough for the 192 x 192 tile configuration (more than 512 tiles, a round of workgroup places
+    saved), with M and N that end inside the last tiles; checked on sampled rows including the last ones."""
+    rng = np.random.default_rng(2700)
+    M, K, N, r = 4500, 256, 12208, 16
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    prep = S.svdq_fp4_prepare(w, ax, r, bias=b)
+    rows = np.unique(np.concatenate([np.arange(0, 3), rng.integers(0, M, 40), np.arange(190, 194), np.arange(M - 3, M)]))
+    _run_and_compare(torch, xb, prep, rows=rows, what="fp4 192-tile ragged")
