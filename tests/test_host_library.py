@@ -269,3 +269,22 @@ def test_fp4_prepare_matches_the_oracle_given_the_same_factors(lib):
     # a long K and few tiles: arrival counters (one per tile, padded to 256 bytes) and ksplit fp32 partial tiles of 128 x 256 per tile
     long_k = S.make_shape(12288, 3072, 32, group=32)
     assert S.svdq_workspace_bytes(512, long_k) == 192 * 512 * 32 + 48 * 512 * 8 + 2 * (512 * 32 * 4) + 256 + 4 * 48 * 128 * 256 * 4
+
+
+def test_fp4_forward_argument_errors(lib):
+    """The FP4 entry points refuse what they cannot run before touching the GPU (no compute call is made here)."""
+    fake = S.LayerDev(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, S.make_shape(3072, 3072, 32, group=32))
+    fwd = lib.svdq_fp4_linear_forward
+    args = lambda M, ws_bytes: (C.byref(fake), C.c_void_p(0x1000), M, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(ws_bytes), None)
+    assert fwd(*args(-1, 1 << 40)) == -1
+    assert fwd(*args(0, 0)) == 0                           # nothing to do
+    assert fwd(*args(16, 1024)) == -4                      # workspace too small
+    assert fwd(C.byref(fake), C.c_void_p(0x1004), 16, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1 << 40), None) == -1   # X misaligned
+    fake.shape = S.make_shape(3072, 3072, 32)              # an INT4 shape on the FP4 entry point
+    assert fwd(*args(16, 1 << 40)) == -2
+    fake.shape = S.make_shape(3072, 3072, 32, group=32)
+    assert lib.svdq_linear_forward(*args(16, 1 << 40)) == -2      # and the other way round
+    for K, r in ((32768 + 64, 32), (24576, 256)):          # the activation kernel's LDS limit applies to both formats
+        fake.shape = S.make_shape(K, 3072, r, group=32)
+        assert fwd(*args(16, 1 << 62)) == -2, (K, r)
+    assert lib.svdq_fp4_workspace_bytes(-1, C.byref(fake.shape)) == 0
