@@ -85,6 +85,21 @@ int svdq_prepare(const svdq_shape *shape, const float *W, const float *x_absmax,
                  uint16_t *out_wscales, float *out_bias);
 
 /*
+ * svdq_prepare (or, for a shape with group = 32, svdq_fp4_prepare below) followed by `iterations` rounds of the
+ * iterative update of the low-rank branch (Sec. 4.2, last sentences): decompose W^ - Q(R) of the previous
+ * iterate, store the new factors in bf16, take the residual against them and quantize it again; the iterate with
+ * the smallest error || W^ - L1 L2 - Q(R) ||_F is the one packed (iterate 0 is the plain split, so the result is
+ * never worse than svdq_prepare's in that measure).  0 <= iterations <= 64.  Offline cost: one truncated SVD per round.
+ *   out_wscales  fp16 [G][Npad] for group 64, scale bytes for group 32 (sizes as in the *_prepared_sizes call)
+ *   out_errors   host, iterations + 1 doubles: the error of every iterate, or NULL
+ *   out_pick     host: index of the iterate that was packed, or NULL
+ */
+int svdq_prepare_refined(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                         int iterations, float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2,
+                         uint8_t *out_wcodes, void *out_wscales, float *out_bias,
+                         double *out_errors, int *out_pick);
+
+/*
  * Pack an externally quantized layer (canonical forms, all HOST) into native buffers:
  *   rinv fp32 [K]; l1s bf16 [K x rank]; l2 bf16 [rank x N]; qw int8 [K x N] codes in [-7, 7];
  *   sw fp16 [G x N]; bias fp32 [N] or NULL.

@@ -111,7 +111,7 @@ def residual_codes_from_factors(W, rinv, l1s_bits, l2_bits):
 
 
 def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
-            bias: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+            bias: Optional[np.ndarray] = None, refine_iters: int = 0) -> Dict[str, np.ndarray]:
     """Offline quantization of one layer to MXFP4 + rank-r 16-bit branch.  W fp32 [K, N], x_absmax fp32 [K]."""
     W = np.asarray(W, dtype=np.float32)
     K, N = W.shape
@@ -120,17 +120,23 @@ def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
     rinv = O.reciprocal_f32(lam)
     lam_eff = 1.0 / rinv.astype(np.float64)
     W_hat = O.smooth_weight(W, lam_eff)
-    if rank > 0:
-        L1, L2, _ = O.lowrank_svd(W_hat, rank)
-        l1s_bits = O.bf16_round((L1 / lam_eff[:, None]).astype(np.float32))
-        l2_bits = O.bf16_round(L2.astype(np.float32))
+    extra = {}
+    if rank > 0 and refine_iters > 0:
+        deq = lambda q, b_: dequantize_blocks(np.ascontiguousarray(q.T), np.ascontiguousarray(b_.T)).T
+        l1s_bits, l2_bits, qw, bw, R, errs, pick = O.refine_lowrank(W, rinv, W_hat, rank, refine_iters, residual_codes_from_factors, deq)
+        extra = {"refine_errors": errs, "refine_pick": pick}
     else:
-        l1s_bits = np.zeros((K, 0), dtype=np.uint16)
-        l2_bits = np.zeros((0, N), dtype=np.uint16)
-    qw, bw, R = residual_codes_from_factors(W, rinv, l1s_bits, l2_bits)
+        if rank > 0:
+            L1, L2, _ = O.lowrank_svd(W_hat, rank)
+            l1s_bits = O.bf16_round((L1 / lam_eff[:, None]).astype(np.float32))
+            l2_bits = O.bf16_round(L2.astype(np.float32))
+        else:
+            l1s_bits = np.zeros((K, 0), dtype=np.uint16)
+            l2_bits = np.zeros((0, N), dtype=np.uint16)
+        qw, bw, R = residual_codes_from_factors(W, rinv, l1s_bits, l2_bits)
     b = np.zeros(N, dtype=np.float32) if bias is None else np.asarray(bias, dtype=np.float32)
     return {"rinv": rinv, "lam": lam_eff, "l1s": l1s_bits, "l2": l2_bits, "qw": qw, "bw": bw, "bias": b,
-            "R": R, "W_hat": W_hat}
+            "R": R, "W_hat": W_hat, **extra}
 
 
 def quantize_activation(x_bits: np.ndarray, rinv: np.ndarray):

@@ -24,6 +24,8 @@ What each function follows
 * ``lowrank_svd``           L1 = U Sigma[:, :r], L2 = V[:r, :] (Sec. 4.2, text
                             after Prop. 4.2; Eckart-Young).
 * ``prepare``               smoothing -> SVD -> residual -> per-group INT4.
+* ``refine_lowrank``        the iterative update of the low-rank branch (Sec. 4.2, end):
+                            decompose W^ - Q(R), re-quantize, keep the best iterate.
 * ``forward``               Eq. (5): X^ L1 L2 (16-bit branch) + Q(X^) Q(R)
                             (4-bit branch, Eq. (2) per group), plus bias.
 
@@ -156,8 +158,33 @@ def residual_codes_from_factors(W, rinv, l1s_bits, l2_bits):
     return qw, sw, R
 
 
+def refine_lowrank(W, rinv, W_hat, rank, iterations, codes_from_factors, dequantize):
+    """The low-rank branch updated iteratively (Sec. 4.2, last sentences before Sec. 4.3).
+
+    Iterate 0 is the plain split of W^.  Iterate t decomposes W^ - Q(R_{t-1}), i.e. what the quantized residual of
+    the previous iterate leaves for the 16-bit branch, stores the new factors in bf16, takes the residual R_t against
+    them and quantizes it.  Every iterate's error || W^ - L1 L2 - Q(R_t) ||_F (with the stored factors) is recorded and
+    the iterate with the smallest one is returned.  ``codes_from_factors`` and ``dequantize`` are the format's
+    quantizer steps (INT4 or MXFP4).  Returns (l1s_bits, l2_bits, codes, scales, R, errors, chosen index).
+    """
+    lam_eff = 1.0 / np.asarray(rinv, dtype=np.float32).astype(np.float64)
+    best = None
+    errors = []
+    D = np.zeros_like(W_hat)
+    for t in range(iterations + 1):
+        L1, L2, _ = lowrank_svd(W_hat - D, rank)
+        l1s_bits = bf16_round((L1 / lam_eff[:, None]).astype(np.float32))
+        l2_bits = bf16_round(L2.astype(np.float32))
+        q, sc, R = codes_from_factors(W, rinv, l1s_bits, l2_bits)
+        D = dequantize(q, sc)
+        errors.append(float(np.linalg.norm(R - D)))
+        if best is None or errors[-1] < best[0]:
+            best = (errors[-1], l1s_bits, l2_bits, q, sc, R, t)
+    return best[1], best[2], best[3], best[4], best[5], np.array(errors), best[6]
+
+
 def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
-            bias: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+            bias: Optional[np.ndarray] = None, refine_iters: int = 0) -> Dict[str, np.ndarray]:
     """Offline quantization of one layer.  W fp32 [K, N], x_absmax fp32 [K]."""
     W = np.asarray(W, dtype=np.float32)
     K, N = W.shape
@@ -166,18 +193,25 @@ def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
     rinv = reciprocal_f32(lam)
     lam_eff = 1.0 / rinv.astype(np.float64)          # exact inverse of what the run time multiplies by
     W_hat = smooth_weight(W, lam_eff)
-    if rank > 0:
-        L1, L2, S = lowrank_svd(W_hat, rank)
-        l1s_bits = bf16_round((L1 / lam_eff[:, None]).astype(np.float32))
-        l2_bits = bf16_round(L2.astype(np.float32))
-    else:
+    extra = {}
+    if rank > 0 and refine_iters > 0:
         S = np.linalg.svd(W_hat, compute_uv=False)
-        l1s_bits = np.zeros((K, 0), dtype=np.uint16)
-        l2_bits = np.zeros((0, N), dtype=np.uint16)
-    qw, sw, R = residual_codes_from_factors(W, rinv, l1s_bits, l2_bits)
+        deq = lambda q, s: dequantize_groups(np.ascontiguousarray(q.T), np.ascontiguousarray(s.T)).T.astype(np.float64)
+        l1s_bits, l2_bits, qw, sw, R, errs, pick = refine_lowrank(W, rinv, W_hat, rank, refine_iters, residual_codes_from_factors, deq)
+        extra = {"refine_errors": errs, "refine_pick": pick}
+    else:
+        if rank > 0:
+            L1, L2, S = lowrank_svd(W_hat, rank)
+            l1s_bits = bf16_round((L1 / lam_eff[:, None]).astype(np.float32))
+            l2_bits = bf16_round(L2.astype(np.float32))
+        else:
+            S = np.linalg.svd(W_hat, compute_uv=False)
+            l1s_bits = np.zeros((K, 0), dtype=np.uint16)
+            l2_bits = np.zeros((0, N), dtype=np.uint16)
+        qw, sw, R = residual_codes_from_factors(W, rinv, l1s_bits, l2_bits)
     b = np.zeros(N, dtype=np.float32) if bias is None else np.asarray(bias, dtype=np.float32)
     return {"rinv": rinv, "lam": lam_eff, "l1s": l1s_bits, "l2": l2_bits, "qw": qw, "sw": sw,
-            "bias": b, "R": R, "W_hat": W_hat, "sigma": S}
+            "bias": b, "R": R, "W_hat": W_hat, "sigma": S, **extra}
 
 
 # --------------------------------------------------------------------------

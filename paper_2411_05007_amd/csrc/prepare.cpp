@@ -390,6 +390,22 @@ struct SplitLayer {
     std::vector<uint16_t> l1s, l2;      // canonical: [K x r], [r x N]
     std::vector<double> l2d;
 };
+// rank-r split of A [K x N] (W^ itself, or W^ minus the dequantized residual of the previous iterate), stored in bf16
+void factor(const svdq_shape *shape, const double *A, SplitLayer &o) {
+    const int K = shape->K, N = shape->N, r = shape->rank;
+    o.l1s.assign((size_t)K * r, 0);
+    o.l2.assign((size_t)r * N, 0);
+    if (r > 0) {
+        std::vector<double> L1, L2;
+        truncated_svd(A, K, N, r, L1, L2);
+        for (size_t k = 0; k < (size_t)K; ++k)
+            for (int j = 0; j < r; ++j) o.l1s[k * r + j] = f32_to_bf16((float)(L1[k * r + j] / o.lam[k]));
+        for (size_t i = 0; i < (size_t)r * N; ++i) o.l2[i] = f32_to_bf16((float)L2[i]);
+    }
+    o.l2d.resize((size_t)r * N);
+    for (size_t i = 0; i < o.l2d.size(); ++i) o.l2d[i] = (double)bf16_to_f32(o.l2[i]);
+}
+
 void split_layer(const svdq_shape *shape, const float *W, const float *x_absmax, SplitLayer &o) {
     const int K = shape->K, N = shape->N, r = shape->rank;
     const double alpha = (double)shape->alpha;
@@ -413,21 +429,12 @@ void split_layer(const svdq_shape *shape, const float *W, const float *x_absmax,
         for (size_t k = k0; k < k1; ++k)
             for (int n = 0; n < N; ++n) o.What[k * N + n] = o.lam[k] * (double)W[k * N + n];
     });
-    o.l1s.assign((size_t)K * r, 0);
-    o.l2.assign((size_t)r * N, 0);
-    if (r > 0) {
-        std::vector<double> L1, L2;
-        truncated_svd(o.What.data(), K, N, r, L1, L2);
-        for (size_t k = 0; k < (size_t)K; ++k)
-            for (int j = 0; j < r; ++j) o.l1s[k * r + j] = f32_to_bf16((float)(L1[k * r + j] / o.lam[k]));
-        for (size_t i = 0; i < (size_t)r * N; ++i) o.l2[i] = f32_to_bf16((float)L2[i]);
-    }
-    o.l2d.resize((size_t)r * N);
-    for (size_t i = 0; i < o.l2d.size(); ++i) o.l2d[i] = (double)bf16_to_f32(o.l2[i]);
+    factor(shape, o.What.data(), o);
 }
 
 // Rows 64 g .. 64 g + 63 of the residual against the STORED factors, R = W^ - diag(lambda) (L1s L2b), as fp32 [64 x N]
-void residual_rows(const svdq_shape *shape, const SplitLayer &o, size_t g, std::vector<float> &Rg, std::vector<double> &prow) {
+void residual_rows(const svdq_shape *shape, const SplitLayer &o, size_t g, std::vector<float> &Rg, std::vector<double> &prow,
+                   double *Rd = nullptr) {
     const int N = shape->N, r = shape->rank;
     for (int kk = 0; kk < kGroup; ++kk) {
         const size_t k = g * kGroup + kk;
@@ -437,8 +444,70 @@ void residual_rows(const svdq_shape *shape, const SplitLayer &o, size_t g, std::
             const double *b = o.l2d.data() + (size_t)j * N;
             for (int n = 0; n < N; ++n) prow[n] += a * b[n];
         }
-        for (int n = 0; n < N; ++n) Rg[(size_t)kk * N + n] = (float)(o.What[k * N + n] - o.lam[k] * prow[n]);
+        for (int n = 0; n < N; ++n) {
+            const double rd = o.What[k * N + n] - o.lam[k] * prow[n];
+            Rg[(size_t)kk * N + n] = (float)rd;
+            if (Rd) Rd[(size_t)kk * N + n] = rd;
+        }
     }
+}
+
+static const float kE2M1Grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+
+// Quantizes the residual of the current factors in the format the shape's group size names and returns
+// || R - Q(R) ||_F^2.  qw: one code per byte [K x N] (INT4 codes as int8, E2M1 codes 0..15); sc: fp16 [G x N] for
+// INT4 (as uint16), scale bytes [2G x N] for MXFP4 (one per uint16 slot).  D, when given, receives Q(R) [K x N].
+double quantize_residual(const svdq_shape *shape, const SplitLayer &sl, std::vector<int8_t> &qw, std::vector<uint16_t> &sc,
+                         std::vector<double> *D) {
+    const int K = shape->K, N = shape->N, G = K / kGroup;
+    const bool fp4 = shape->group == svdq::kFp4Block;
+    qw.resize((size_t)K * N);
+    sc.resize((size_t)(fp4 ? 2 : 1) * G * N);
+    if (D) D->resize((size_t)K * N);
+    std::vector<double> err2((size_t)G, 0.0);
+    parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
+        std::vector<float> Rg((size_t)kGroup * N);
+        std::vector<double> Rd((size_t)kGroup * N), prow(N);
+        int8_t codes[kGroup];
+        uint8_t codes4[svdq::kFp4Block];
+        for (size_t g = g0; g < g1; ++g) {
+            residual_rows(shape, sl, g, Rg, prow, Rd.data());
+            double e2 = 0.0;
+            for (int n = 0; n < N; ++n) {
+                if (!fp4) {
+                    const uint16_t s16 = quantize_group(Rg.data() + n, (size_t)N, codes);
+                    sc[g * N + n] = s16;
+                    const double s = (double)f16_to_f32(s16);
+                    for (int kk = 0; kk < kGroup; ++kk) {
+                        const size_t k = g * kGroup + kk;
+                        qw[k * N + n] = codes[kk];
+                        const double d = s * codes[kk];
+                        if (D) (*D)[k * N + n] = d;
+                        const double diff = Rd[(size_t)kk * N + n] - d;
+                        e2 += diff * diff;
+                    }
+                } else {
+                    for (int kb = 0; kb < 2; ++kb) {
+                        const uint8_t byte = quantize_block_fp4(Rg.data() + (size_t)32 * kb * N + n, (size_t)N, codes4);
+                        sc[(g * 2 + kb) * (size_t)N + n] = byte;
+                        const double s = std::ldexp(1.0, (int)byte - 127);
+                        for (int kk = 0; kk < 32; ++kk) {
+                            const size_t k = g * kGroup + 32 * kb + kk;
+                            qw[k * N + n] = (int8_t)codes4[kk];
+                            const double d = s * ((codes4[kk] & 8) ? -(double)kE2M1Grid[codes4[kk] & 7] : (double)kE2M1Grid[codes4[kk] & 7]);
+                            if (D) (*D)[k * N + n] = d;
+                            const double diff = Rd[(size_t)(32 * kb + kk) * N + n] - d;
+                            e2 += diff * diff;
+                        }
+                    }
+                }
+            }
+            err2[g] = e2;
+        }
+    });
+    double total = 0.0;
+    for (double e : err2) total += e;       // fixed order: the result does not depend on the thread count
+    return total;
 }
 
 // factors, smoothing reciprocals and bias into their native places (the same for both formats)
@@ -522,6 +591,60 @@ int svdq_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, c
     return SVDQ_OK;
 }
 
+// Both prepare entry points and the refined one: split, then `iterations` rounds of the iterative update of the
+// low-rank branch (Sec. 4.2, end: decompose W^ - Q(R), take the residual again, keep the iterate with the smallest
+// || W^ - L1 L2 - Q(R) ||_F; iteration 0 is the plain split), then native packing.
+static int prepare_common(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias, int iterations,
+                          float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes, void *out_wscales,
+                          float *out_bias, double *out_errors, int *out_pick) {
+    const int K = shape->K, N = shape->N;
+    const bool fp4 = shape->group == svdq::kFp4Block;
+    if (shape->rank == 0) iterations = 0;      // nothing to update
+    try {
+        SplitLayer sl;
+        split_layer(shape, W, x_absmax, sl);
+        std::vector<int8_t> qw, best_qw;
+        std::vector<uint16_t> sc, best_sc, best_l1s, best_l2;
+        std::vector<double> D, A;
+        double best = -1.0;
+        int pick = 0;
+        for (int t = 0; t <= iterations; ++t) {
+            if (t > 0) {
+                A.resize(sl.What.size());
+                parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+                    for (size_t i = k0 * N; i < k1 * N; ++i) A[i] = sl.What[i] - D[i];
+                });
+                factor(shape, A.data(), sl);
+            }
+            const double e2 = quantize_residual(shape, sl, qw, sc, t < iterations ? &D : nullptr);
+            if (out_errors) out_errors[t] = std::sqrt(e2);
+            if (best < 0.0 || e2 < best) {
+                best = e2;
+                pick = t;
+                if (iterations > 0) { best_qw = qw; best_sc = sc; best_l1s = sl.l1s; best_l2 = sl.l2; }
+            }
+        }
+        if (out_pick) *out_pick = pick;
+        const std::vector<int8_t> &fq = iterations > 0 ? best_qw : qw;
+        const std::vector<uint16_t> &fs = iterations > 0 ? best_sc : sc;
+        const std::vector<uint16_t> &f1 = iterations > 0 ? best_l1s : sl.l1s;
+        const std::vector<uint16_t> &f2 = iterations > 0 ? best_l2 : sl.l2;
+        if (!fp4) {
+            pack_native(shape, sl.rinv.data(), f1.data(), f2.data(), fq.data(), fs.data(), bias, out_rinv, out_l1s, out_l2,
+                        out_wcodes, static_cast<uint16_t *>(out_wscales), out_bias);
+        } else {
+            std::vector<uint8_t> q8(fq.size()), b8(fs.size());
+            for (size_t i = 0; i < fq.size(); ++i) q8[i] = (uint8_t)fq[i];
+            for (size_t i = 0; i < fs.size(); ++i) b8[i] = (uint8_t)fs[i];
+            pack_common(shape, sl.rinv.data(), f1.data(), f2.data(), bias, out_rinv, out_l1s, out_l2, out_bias);
+            pack_fp4_weights(shape, q8.data(), b8.data(), out_wcodes, static_cast<uint8_t *>(out_wscales));
+        }
+    } catch (const std::bad_alloc &) {
+        return SVDQ_ENOMEM;
+    }
+    return SVDQ_OK;
+}
+
 int svdq_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
                  float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
                  uint16_t *out_wscales, float *out_bias) {
@@ -529,31 +652,19 @@ int svdq_prepare(const svdq_shape *shape, const float *W, const float *x_absmax,
     if (st != SVDQ_OK) return st;
     if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
         return SVDQ_EINVAL;
-    const int K = shape->K, N = shape->N, G = K / kGroup;
-    try {
-        SplitLayer sl;
-        split_layer(shape, W, x_absmax, sl);
-        // Eq. 1 per group of 64 along K
-        std::vector<int8_t> qw((size_t)K * N);
-        std::vector<uint16_t> sw((size_t)G * N);
-        parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
-            std::vector<float> Rg((size_t)kGroup * N);
-            std::vector<double> prow(N);
-            int8_t codes[kGroup];
-            for (size_t g = g0; g < g1; ++g) {
-                residual_rows(shape, sl, g, Rg, prow);
-                for (int n = 0; n < N; ++n) {
-                    sw[g * N + n] = quantize_group(Rg.data() + n, (size_t)N, codes);
-                    for (int kk = 0; kk < kGroup; ++kk) qw[(g * kGroup + kk) * (size_t)N + n] = codes[kk];
-                }
-            }
-        });
-        pack_native(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), qw.data(), sw.data(), bias, out_rinv, out_l1s,
-                    out_l2, out_wcodes, out_wscales, out_bias);
-    } catch (const std::bad_alloc &) {
-        return SVDQ_ENOMEM;
-    }
-    return SVDQ_OK;
+    return prepare_common(shape, W, x_absmax, bias, 0, out_rinv, out_l1s, out_l2, out_wcodes, out_wscales, out_bias, nullptr, nullptr);
+}
+
+int svdq_prepare_refined(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias, int iterations,
+                         float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes, void *out_wscales,
+                         float *out_bias, double *out_errors, int *out_pick) {
+    const int st = check_shape(shape, 0);
+    if (st != SVDQ_OK) return st;
+    if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias || iterations < 0 ||
+        iterations > 64)
+        return SVDQ_EINVAL;
+    return prepare_common(shape, W, x_absmax, bias, iterations, out_rinv, out_l1s, out_l2, out_wcodes, out_wscales, out_bias,
+                          out_errors, out_pick);
 }
 
 // ---- MXFP4 variant ------------------------------------------------------------------------------------
@@ -597,31 +708,7 @@ int svdq_fp4_prepare(const svdq_shape *shape, const float *W, const float *x_abs
     if (st != SVDQ_OK) return st;
     if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
         return SVDQ_EINVAL;
-    const int K = shape->K, N = shape->N, G = K / kGroup;
-    try {
-        SplitLayer sl;
-        split_layer(shape, W, x_absmax, sl);
-        // Eq. 1 per block of 32 along K
-        std::vector<uint8_t> qw((size_t)K * N), bw((size_t)2 * G * N);
-        parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
-            std::vector<float> Rg((size_t)kGroup * N);
-            std::vector<double> prow(N);
-            uint8_t codes[svdq::kFp4Block];
-            for (size_t g = g0; g < g1; ++g) {
-                residual_rows(shape, sl, g, Rg, prow);
-                for (int n = 0; n < N; ++n)
-                    for (int kb = 0; kb < 2; ++kb) {
-                        bw[(g * 2 + kb) * (size_t)N + n] = quantize_block_fp4(Rg.data() + (size_t)32 * kb * N + n, (size_t)N, codes);
-                        for (int kk = 0; kk < 32; ++kk) qw[(g * kGroup + 32 * kb + kk) * (size_t)N + n] = codes[kk];
-                    }
-            }
-        });
-        pack_common(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), bias, out_rinv, out_l1s, out_l2, out_bias);
-        pack_fp4_weights(shape, qw.data(), bw.data(), out_wcodes, out_wscales);
-    } catch (const std::bad_alloc &) {
-        return SVDQ_ENOMEM;
-    }
-    return SVDQ_OK;
+    return prepare_common(shape, W, x_absmax, bias, 0, out_rinv, out_l1s, out_l2, out_wcodes, out_wscales, out_bias, nullptr, nullptr);
 }
 
 int svdq_fp4_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, uint8_t *out_qw) {

@@ -22,7 +22,7 @@ OPT_TILE_SHIFT = 8
 
 EXPORTS = [
     "svdq_status_string", "svdq_last_hip_error", "svdq_prepared_sizes", "svdq_prepare", "svdq_pack",
-    "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2", "svdq_append_lora",
+    "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2", "svdq_append_lora", "svdq_prepare_refined",
     "svdq_fp4_prepared_sizes", "svdq_fp4_prepare", "svdq_fp4_pack", "svdq_fp4_unpack_wcodes", "svdq_fp4_unpack_wscales",
     "svdq_fp4_workspace_bytes", "svdq_fp4_linear_forward", "svdq_fp4_debug_act",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
         for n in ("svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2"):
             getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
         L.svdq_append_lora.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.c_int, C.c_float, C.POINTER(Shape), vp, vp]
+        L.svdq_prepare_refined.argtypes = [C.POINTER(Shape), vp, vp, vp, C.c_int] + [vp] * 8
         L.svdq_fp4_workspace_bytes.restype = C.c_size_t
         L.svdq_fp4_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
         L.svdq_fp4_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
@@ -183,6 +184,24 @@ def svdq_unpack(p: PreparedHost):
         _check(L.svdq_unpack_l1s(C.byref(p.shape), _ptr(p.l1s), _ptr(l1s)), "svdq_unpack_l1s")
         _check(L.svdq_unpack_l2(C.byref(p.shape), _ptr(p.l2), _ptr(l2)), "svdq_unpack_l2")
     return {"rinv": p.rinv.copy(), "l1s": l1s, "l2": l2, "qw": qw, "sw": sw.view(np.float16), "bias": p.bias[:N].copy()}
+
+
+def svdq_prepare_refined(W: np.ndarray, x_absmax: np.ndarray, rank: int, iterations: int, alpha: float = 0.5,
+                         bias: Optional[np.ndarray] = None, fp4: bool = False):
+    """Prepare with the iterative update of the low-rank branch.  Returns (PreparedHost, errors of all iterates, picked index)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    K, N = W.shape
+    x_absmax = np.ascontiguousarray(x_absmax, dtype=np.float32)
+    assert x_absmax.shape == (K,)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha, group=32 if fp4 else 64)
+    out = _alloc_prepared(shape)
+    errors = np.zeros(iterations + 1, np.float64)
+    pick = C.c_int(-1)
+    _check(lib().svdq_prepare_refined(C.byref(shape), _ptr(W), _ptr(x_absmax), _ptr(b), int(iterations), _ptr(out.rinv),
+                                      _ptr(out.l1s), _ptr(out.l2), _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias),
+                                      _ptr(errors), C.byref(pick)), "svdq_prepare_refined")
+    return out, errors, pick.value
 
 
 def svdq_fp4_prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,

@@ -288,3 +288,38 @@ def test_fp4_forward_argument_errors(lib):
         fake.shape = S.make_shape(K, 3072, r, group=32)
         assert fwd(*args(16, 1 << 62)) == -2, (K, r)
     assert lib.svdq_fp4_workspace_bytes(-1, C.byref(fake.shape)) == 0
+
+
+@pytest.mark.parametrize("fp4", [False, True])
+def test_refined_prepare_against_the_oracle(lib, fp4):
+    """The library's iterative update of the low-rank branch: same error measure as the oracle's, never worse than the
+    plain split, close to the oracle's sequence (the two use different SVD routines), and - as for the plain prepare -
+    bit-equal codes given the factors it chose."""
+    from oracle import svdq_fp4_oracle as F
+    mod = F if fp4 else O
+    rng = np.random.default_rng(123)
+    K, N, r, T = 256, 160, 16, 4
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 2, replace=False)] *= 20
+    ax = (np.abs(rng.standard_normal(K)) + 0.1).astype(np.float32)
+    ax[rng.choice(K, 3, replace=False)] *= 50
+    prep, errs, pick = S.svdq_prepare_refined(w, ax, r, T, fp4=fp4)
+    P = mod.prepare(w, ax, r, refine_iters=T)
+    assert pick == int(np.argmin(errs)) and errs[pick] <= errs[0]
+    assert np.allclose(errs, P["refine_errors"], rtol=2e-2), (errs, P["refine_errors"])
+    assert errs[pick] <= 1.01 * P["refine_errors"][P["refine_pick"]]
+    U = (S.svdq_fp4_unpack if fp4 else S.svdq_unpack)(prep)
+    q, sc, R = mod.residual_codes_from_factors(w, U["rinv"], U["l1s"], U["l2"])
+    if fp4:
+        assert np.array_equal(F.decode_e2m1(U["qw"]), F.decode_e2m1(q)) and np.array_equal(U["bw"], sc)
+        D = F.dequantize_blocks(np.ascontiguousarray(q.T), np.ascontiguousarray(sc.T)).T
+    else:
+        assert np.array_equal(U["qw"], q) and np.array_equal(U["sw"].view(np.uint16), sc.view(np.uint16))
+        D = O.dequantize_groups(np.ascontiguousarray(q.T), np.ascontiguousarray(sc.T)).T.astype(np.float64)
+    assert np.isclose(np.linalg.norm(R - D), errs[pick], rtol=1e-6)
+    # no iterations: the plain prepare
+    plain = (S.svdq_fp4_prepare if fp4 else S.svdq_prepare)(w, ax, r)
+    zero, e0, p0 = S.svdq_prepare_refined(w, ax, r, 0, fp4=fp4)
+    assert p0 == 0 and np.array_equal(zero.wcodes, plain.wcodes) and np.array_equal(zero.l1s, plain.l1s) and np.isclose(e0[0], errs[0], rtol=1e-6)
+    with pytest.raises(S.SvdqError):
+        S.svdq_prepare_refined(w, ax, r, 65, fp4=fp4)

@@ -198,6 +198,52 @@ def exact_w(scale, down, up):
     return scale * (down.astype(np.float64) @ up.astype(np.float64))
 
 
+@pytest.mark.parametrize("fmt", ["int4", "fp4"])
+def test_iterative_update_of_the_lowrank_branch(fmt):
+    """Sec. 4.2, end: decompose W^ - Q(R), adjust R, several iterations, keep the iterate with the smallest error."""
+    from oracle import svdq_fp4_oracle as F
+    mod = O if fmt == "int4" else F
+    xb, w, b, ax = _small_layer(M=64, K=256, N=160, seed=21)
+    P0 = mod.prepare(w, ax, rank=16, bias=b)
+    P = mod.prepare(w, ax, rank=16, bias=b, refine_iters=5)
+    errs, pick = P["refine_errors"], P["refine_pick"]
+    scales = "sw" if fmt == "int4" else "bw"
+
+    def deq(Pd):
+        if fmt == "int4":
+            return O.dequantize_groups(np.ascontiguousarray(Pd["qw"].T), np.ascontiguousarray(Pd["sw"].T)).T.astype(np.float64)
+        return F.dequantize_blocks(np.ascontiguousarray(Pd["qw"].T), np.ascontiguousarray(Pd["bw"].T)).T
+    # iterate 0 is the plain split; the error measure is || W^ - L1 L2 - Q(R) ||_F = || R - Q(R) ||_F with the stored factors
+    assert len(errs) == 6 and np.isclose(errs[0], np.linalg.norm(P0["R"] - deq(P0)), rtol=1e-12)
+    assert pick == int(np.argmin(errs)) and errs[pick] <= errs[0]
+    # on a layer with outliers the update does help, and by a margin that a no-op would not reach
+    assert errs[pick] < 0.95 * errs[0], errs
+    # what is returned is a consistent layer: R against the stored factors, its codes, the recorded error
+    R = O.residual(w, P["lam"], P["l1s"], P["l2"])
+    assert np.array_equal(R, P["R"])
+    q, sc, _ = mod.residual_codes_from_factors(w, P["rinv"], P["l1s"], P["l2"])
+    assert np.array_equal(q, P["qw"]) and np.array_equal(np.asarray(sc).view(np.uint8), np.asarray(P[scales]).view(np.uint8))
+    assert np.isclose(np.linalg.norm(P["R"] - deq(P)), errs[pick], rtol=1e-12)
+    # iterate 1 by hand: the best rank-16 approximation (Eckart-Young) of W^ - Q(R_0), up to the bf16 rounding of the factors
+    P1 = mod.prepare(w, ax, rank=16, bias=b, refine_iters=1)
+    if P1["refine_pick"] == 1:
+        target = P0["W_hat"] - deq(P0)
+        U, S, Vt = np.linalg.svd(target, full_matrices=False)
+        bestr = (U[:, :16] * S[:16]) @ Vt[:16]
+        got = P1["lam"][:, None] * (O.bf16_to_f32(P1["l1s"]).astype(np.float64) @ O.bf16_to_f32(P1["l2"]).astype(np.float64))
+        assert np.linalg.norm(got - bestr) <= 2.0 ** -7 * np.linalg.norm(bestr)
+    # no iterations = the plain prepare, bit for bit
+    Pz = mod.prepare(w, ax, rank=16, bias=b, refine_iters=0)
+    assert np.array_equal(Pz["qw"], P0["qw"]) and np.array_equal(Pz["l1s"], P0["l1s"]) and "refine_errors" not in Pz
+    # and the layer's output error on the calibration-like input does not get worse
+    x = O.bf16_to_f32(xb).astype(np.float64)
+    full = x @ w.astype(np.float64) + b
+    key = "Y64"
+    y0 = mod.forward(xb, P0, **({"want_f64": True} if fmt == "int4" else {}))[key]
+    y1 = mod.forward(xb, P, **({"want_f64": True} if fmt == "int4" else {}))[key]
+    assert np.linalg.norm(y1 - full) <= 1.02 * np.linalg.norm(y0 - full)
+
+
 def test_forward_approximates_xw_and_error_identity():
     xb, w, b, ax = _small_layer(M=64, K=512, N=128, seed=8)
     r = 16

@@ -97,3 +97,15 @@ def test_fp4_mistakes_are_caught(monkeypatch):
     # the weight side quantized from the smoothed weight instead of the residual (low-rank term dropped from R)
     monkeypatch.setattr(F.O, "residual", lambda W, lam, a, b: np.asarray(W, np.float64) * np.asarray(lam, np.float64)[:, None])
     _must_fail(TF.test_forward_equals_the_dense_definition_of_eq5)
+
+
+def test_refinement_that_ignores_the_quantized_residual_is_caught(monkeypatch):
+    real = O.lowrank_svd
+    state = {"first": None}
+
+    def bad(A, r):                      # every iterate decomposes W^ again instead of W^ - Q(R)
+        if state["first"] is None:
+            state["first"] = np.array(A, copy=True)
+        return real(state["first"], r)
+    monkeypatch.setattr(O, "lowrank_svd", bad)
+    _must_fail(lambda: TL.test_iterative_update_of_the_lowrank_branch("int4"))
