@@ -109,3 +109,20 @@ def test_refinement_that_ignores_the_quantized_residual_is_caught(monkeypatch):
         return real(state["first"], r)
     monkeypatch.setattr(O, "lowrank_svd", bad)
     _must_fail(lambda: TL.test_iterative_update_of_the_lowrank_branch("int4"))
+
+
+def test_w8a8_mistakes_are_caught(monkeypatch):
+    from oracle import svdq_w8a8_oracle as W8
+    import tests.test_oracle_w8a8 as TW
+    real = W8.quantize_rows
+
+    def per_tensor(v):                       # one scale for the whole tensor instead of one per row
+        v = np.ascontiguousarray(v, np.float32)
+        q, s = real(v.reshape(1, -1))
+        return q.reshape(v.shape), np.full(v.shape[:-1], s[0], np.float16)
+    monkeypatch.setattr(W8, "quantize_rows", per_tensor)
+    _must_fail(TW.test_quantizer_against_exact_rationals_and_invariants)
+    monkeypatch.setattr(W8, "quantize_rows", real)
+    # weights quantized per input channel (rows of R) instead of per output channel
+    monkeypatch.setattr(W8, "quantize_residual", lambda R: (lambda q, s: (q, np.resize(s, R.shape[1])))(*real(np.asarray(R, np.float64).astype(np.float32))))
+    _must_fail(TW.test_forward_equals_the_dense_definition_and_integer_sums_are_exact)
