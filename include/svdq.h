@@ -240,6 +240,36 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *layer, const void *X, int M, v
 int svdq_fp4_debug_act(const svdq_layer_dev *layer, const void *workspace, int M,
                        uint8_t *out_codes, uint8_t *out_bx, float *out_H, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * 8-bit setting (App. "Implementation Details": per-token dynamic activation quantization, per-channel
+ * weight quantization, low-rank branch of rank 16 in the paper; any supported rank here).
+ *   quantizer (Eq. 1 with q_max = 127): one fp16 scale per token (activations) or per output channel
+ *   (weights), s = fp16(max|x| / 127), codes = clamp(rne(x * (1.0f / s)), -127, 127), scale 0 for an all-zero row.
+ *   Y = bf16( s_x[m] s_w[n] (exact int32 sum of code products) + (X l1s) l2 + bias ).
+ * These entry points take a svdq_shape with group = 0.  Buffers, ownership, alignment, stream and error
+ * behaviour are those of their INT4 namesakes; wcodes holds one int8 per weight (K * Npad bytes, operand order
+ * of the int8 matrix-core instruction), wscales fp16 [Npad].  The forward enqueues three kernels (quantization,
+ * down projection, GEMM).  The K / rank limits of svdq_linear_forward apply; K * Npad and K * Mpad below 2^31.
+ * ------------------------------------------------------------------------------------------------ */
+int svdq_w8a8_prepared_sizes(const svdq_shape *shape, svdq_sizes *out);
+int svdq_w8a8_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                      float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                      uint16_t *out_wscales, float *out_bias);
+/* canonical forms (HOST): qw int8 [K x N] in [-127, 127] (-128 is refused); sw fp16 [N] */
+int svdq_w8a8_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
+                   const int8_t *qw, const uint16_t *sw, const float *bias,
+                   float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                   uint16_t *out_wscales, float *out_bias);
+int svdq_w8a8_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, int8_t *out_qw /* [K x N] */);
+int svdq_w8a8_unpack_wscales(const svdq_shape *shape, const uint16_t *wscales, uint16_t *out_sw /* fp16 [N] */);
+size_t svdq_w8a8_workspace_bytes(int M, const svdq_shape *shape);
+int svdq_w8a8_linear_forward(const svdq_layer_dev *layer, const void *X, int M, void *Y,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+/* canonical views of what the last forward left in the workspace (DEVICE outputs, any may be NULL):
+ * codes int8 [M x K], scales fp16 [M], H fp32 [M x rank] */
+int svdq_w8a8_debug_act(const svdq_layer_dev *layer, const void *workspace, int M,
+                        int8_t *out_codes, uint16_t *out_sx, float *out_H, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

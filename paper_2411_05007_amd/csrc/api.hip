@@ -286,4 +286,88 @@ int svdq_fp4_debug_act(const svdq_layer_dev *L, const void *workspace, int M, ui
     return e == hipSuccess ? SVDQ_OK : hip_fail(e);
 }
 
+// ---- 8-bit setting (W8A8) ---------------------------------------------------------------------------------------
+
+size_t svdq_w8a8_workspace_bytes(int M, const svdq_shape *s) {
+    if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
+    return svdq::workspace_layout_w8(M, s->K, s->rank).total;
+}
+
+int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
+                             size_t workspace_bytes, void *hip_stream) {
+    const int st = check_layer(L, 0);
+    if (st != SVDQ_OK) return st;
+    if (M < 0) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    if (!X || !Y || !workspace) return SVDQ_EINVAL;
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
+    const svdq_shape &s = L->shape;
+    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.rank);
+    if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
+    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+        return SVDQ_EUNSUPPORTED;
+    if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 31))
+        return SVDQ_EUNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
+
+    svdq::Quant8Params q{};
+    q.X = static_cast<const uint16_t *>(X);
+    q.rinv = static_cast<const float *>(L->rinv);
+    q.codes = ws + w.codes_off;
+    q.sx = reinterpret_cast<uint16_t *>(ws + w.sx_off);
+    q.M = M; q.K = s.K; q.Mpad = w.Mpad;
+    hipError_t e = svdq::launch_quant8(q, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    if (lowrank) {
+        // the down projection H = X L1s: the 4-bit path's activation kernel in its projection-only mode
+        svdq::ActParams a{};
+        a.X = q.X;
+        a.rinv = q.rinv;
+        a.l1s = static_cast<const uint16_t *>(L->l1s);
+        a.H = reinterpret_cast<float *>(ws + w.h_off);
+        a.hfrag = ws + w.hfrag_off;
+        a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
+        e = svdq::launch_act(a, 2, stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    if (void *ev = g_profile_event.load()) {
+        e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    svdq::GemmW8Params g{};
+    g.xcodes = ws + w.codes_off;
+    g.sx = reinterpret_cast<const uint16_t *>(ws + w.sx_off);
+    g.hfrag = ws + w.hfrag_off;
+    g.wcodes = static_cast<const uint8_t *>(L->wcodes);
+    g.sw = static_cast<const uint16_t *>(L->wscales);
+    g.l2t = static_cast<const uint16_t *>(L->l2);
+    g.bias = static_cast<const float *>(L->bias);
+    g.Y = static_cast<uint16_t *>(Y);
+    g.M = M; g.N = s.N; g.K = s.K; g.Mpad = w.Mpad; g.Npad = svdq::round_up(s.N, svdq::kRowPad);
+    g.rank = lowrank ? s.rank : 0;
+    e = svdq::launch_gemm_w8a8(g, stream);
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
+int svdq_w8a8_debug_act(const svdq_layer_dev *L, const void *workspace, int M, int8_t *out_codes, uint16_t *out_sx,
+                        float *out_H, void *hip_stream) {
+    const int st = check_layer(L, 0);
+    if (st != SVDQ_OK) return st;
+    if (M < 0 || !workspace) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    const svdq_shape &s = L->shape;
+    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.rank);
+    const unsigned char *ws = static_cast<const unsigned char *>(workspace);
+    svdq::DebugActW8Params d{};
+    d.codes = ws + w.codes_off;
+    d.sx = reinterpret_cast<const uint16_t *>(ws + w.sx_off);
+    d.H = reinterpret_cast<const float *>(ws + w.h_off);
+    d.out_codes = out_codes; d.out_sx = out_sx; d.out_H = s.rank > 0 ? out_H : nullptr;
+    d.M = M; d.K = s.K; d.Mpad = w.Mpad; d.rank = s.rank;
+    const hipError_t e = svdq::launch_debug_act_w8(d, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
 }  // extern "C"

@@ -93,4 +93,38 @@ struct GemmFp4Params {
 };
 hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream);
 
+// ---- 8-bit setting -------------------------------------------------------------------------------------------
+struct Quant8Params {
+    const uint16_t *X;       // bf16 [M][K]
+    const float *rinv;       // fp32 [K]
+    uint8_t *codes;          // int8, operand order (layout.h, i8_code_offset), K * Mpad bytes
+    uint16_t *sx;            // fp16 [Mpad]
+    int M, K, Mpad;
+};
+hipError_t launch_quant8(const Quant8Params &p, hipStream_t stream);
+
+struct GemmW8Params {
+    const uint8_t *xcodes;   // int8 [K / 32][Mpad / 32][64][16]
+    const uint16_t *sx;      // fp16 [Mpad]
+    const uint8_t *hfrag;
+    const uint8_t *wcodes;   // int8 [K / 32][Npad / 32][64][16]
+    const uint16_t *sw;      // fp16 [Npad]
+    const uint16_t *l2t;     // bf16 [Npad][rank]
+    const float *bias;       // fp32 [Npad]
+    uint16_t *Y;             // bf16 [M][N]
+    int M, N, K, Mpad, Npad, rank;
+};
+hipError_t launch_gemm_w8a8(const GemmW8Params &p, hipStream_t stream);
+
+struct DebugActW8Params {
+    const uint8_t *codes;
+    const uint16_t *sx;
+    const float *H;
+    int8_t *out_codes;       // [M][K] or null
+    uint16_t *out_sx;        // fp16 [M] or null
+    float *out_H;            // [M][rank] or null
+    int M, K, Mpad, rank;
+};
+hipError_t launch_debug_act_w8(const DebugActW8Params &p, hipStream_t stream);
+
 }  // namespace svdq

@@ -79,6 +79,29 @@ inline __host__ __device__ size_t l1s_index(int K, int rank, int k, int j) {
     return ((((size_t)g * 2 + s) * (rank / 16) + c) * 64 + lane) * 8 + e;
 }
 
+// ---- 8-bit setting (one int8 per code, one fp16 scale per token and per output channel) ---------------------
+// Both operands in the operand order of v_mfma_i32_32x32x32_i8, whose lane l feeds row (or column) l % 32 with
+// the 16 channels 16 (l / 32) .. + 15 of a 32-channel step:
+//     codes  c8[k / 32][row / 32][lane = 32 ((k % 32) / 16) + row % 32][16 bytes], byte k % 16
+// so one 32-row block of one 32-channel step is one contiguous kilobyte.  Scales: fp16 [rows_pad].
+inline __host__ __device__ size_t i8_code_offset(int k, int rows_pad, int row) {
+    return ((((size_t)(k / 32) * (rows_pad / 32) + row / 32) * 64 + ((k % 32) / 16) * 32 + row % 32) * 16) + k % 16;
+}
+struct WorkspaceW8 {
+    size_t codes_off, sx_off, h_off, hfrag_off, total;
+    int Mpad;
+};
+inline WorkspaceW8 workspace_layout_w8(int M, int K, int rank) {
+    WorkspaceW8 w;
+    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
+    w.codes_off = 0;
+    w.sx_off = align256((size_t)K * w.Mpad);
+    w.h_off = w.sx_off + align256((size_t)w.Mpad * 2);
+    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.total = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    return w;
+}
+
 // ---- MXFP4 variant (E2M1 elements, blocks of 32 along K, one power-of-two scale byte per block) ----------
 // Both operands use the A / B operand order of v_mfma_scale_f32_32x32x64_f8f6f4, whose lane l feeds row (or
 // column) l % 32 with the 32 elements of block l / 32 of a 64-channel step:

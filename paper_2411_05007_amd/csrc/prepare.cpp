@@ -292,12 +292,15 @@ void truncated_svd(const double *A, int K, int N, int r, std::vector<double> &L1
 // ----------------------------------------------------------------------------------------------
 // shape checks and sizes
 // ----------------------------------------------------------------------------------------------
-// `group` selects the 4-bit format: 64 = INT4 with fp16 scales, 32 = MXFP4 (E2M1 with power-of-two block scales);
-// 0 accepts either (functions that only touch the 16-bit branch).
+// `group` selects the format: 64 = INT4 with fp16 group scales, 32 = MXFP4 (E2M1 with power-of-two block scales),
+// 0 = the 8-bit setting (no groups: one scale per token and per output channel); kAnyGroup accepts all three
+// (functions that only touch the 16-bit branch), kAny4Bit the two 4-bit formats.
+constexpr int kAnyGroup = -1, kAny4Bit = -2;
 int check_shape(const svdq_shape *s, int group = kGroup) {
     if (!s) return SVDQ_EINVAL;
     if (s->K <= 0 || s->N <= 0 || s->rank < 0) return SVDQ_EINVAL;
-    const bool group_ok = group ? s->group == group : (s->group == kGroup || s->group == svdq::kFp4Block);
+    const bool four = s->group == kGroup || s->group == svdq::kFp4Block;
+    const bool group_ok = group == kAnyGroup ? (four || s->group == 0) : group == kAny4Bit ? four : s->group == group;
     if (!group_ok || s->K % kGroup != 0 || s->N % 16 != 0 || s->rank % 16 != 0 ||
         s->rank > svdq::kMaxRank || s->rank > std::min(s->K, s->N))
         return SVDQ_EUNSUPPORTED;
@@ -407,7 +410,7 @@ void factor(const svdq_shape *shape, const double *A, SplitLayer &o) {
 }
 
 void split_layer(const svdq_shape *shape, const float *W, const float *x_absmax, SplitLayer &o) {
-    const int K = shape->K, N = shape->N, r = shape->rank;
+    const int K = shape->K, N = shape->N;
     const double alpha = (double)shape->alpha;
     // smoothing factor (App. "Implementation Details"); the run time multiplies by fp32(1/lambda),
     // so the offline side scales by the exact inverse of that rounded value.
@@ -553,7 +556,7 @@ const char *svdq_status_string(int status) {
     switch (status) {
         case SVDQ_OK: return "ok";
         case SVDQ_EINVAL: return "invalid argument";
-        case SVDQ_EUNSUPPORTED: return "unsupported shape (need K % 64 == 0, N % 16 == 0, rank % 16 == 0, rank <= min(256, K, N), group == 64 for INT4 or 32 for MXFP4)";
+        case SVDQ_EUNSUPPORTED: return "unsupported shape (need K % 64 == 0, N % 16 == 0, rank % 16 == 0, rank <= min(256, K, N), group == 64 for INT4, 32 for MXFP4, 0 for W8A8)";
         case SVDQ_ENOMEM: return "out of host memory";
         case SVDQ_ENOSPACE: return "workspace too small";
         case SVDQ_EHIP: return "HIP error";
@@ -658,7 +661,7 @@ int svdq_prepare(const svdq_shape *shape, const float *W, const float *x_absmax,
 int svdq_prepare_refined(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias, int iterations,
                          float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes, void *out_wscales,
                          float *out_bias, double *out_errors, int *out_pick) {
-    const int st = check_shape(shape, 0);
+    const int st = check_shape(shape, kAny4Bit);
     if (st != SVDQ_OK) return st;
     if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias || iterations < 0 ||
         iterations > 64)
@@ -766,8 +769,111 @@ int svdq_unpack_wscales(const svdq_shape *shape, const uint16_t *wscales, uint16
     return SVDQ_OK;
 }
 
-int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out) {
+// ---- 8-bit setting (W8A8) -------------------------------------------------------------------------------
+int svdq_w8a8_prepared_sizes(const svdq_shape *shape, svdq_sizes *out) {
+    if (!out) return SVDQ_EINVAL;
     const int st = check_shape(shape, 0);
+    if (st != SVDQ_OK) return st;
+    const size_t K = shape->K, r = shape->rank;
+    const int Np = svdq::round_up(shape->N, kRowPad);
+    out->rinv = K * 4;
+    out->l1s = std::max<size_t>(K * r * 2, 16);
+    out->l2 = std::max<size_t>((size_t)Np * r * 2, 16);
+    out->wcodes = K * (size_t)Np;
+    out->wscales = (size_t)Np * 2;
+    out->bias = (size_t)Np * 4;
+    return SVDQ_OK;
+}
+
+int svdq_w8a8_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
+                   const int8_t *qw, const uint16_t *sw, const float *bias, float *out_rinv, uint16_t *out_l1s,
+                   uint16_t *out_l2, uint8_t *out_wcodes, uint16_t *out_wscales, float *out_bias) {
+    const int st = check_shape(shape, 0);
+    if (st != SVDQ_OK) return st;
+    if (!rinv || !qw || !sw || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
+        return SVDQ_EINVAL;
+    if (shape->rank > 0 && (!l1s || !l2)) return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, Np = svdq::round_up(N, kRowPad);
+    for (size_t i = 0; i < (size_t)K * N; ++i)
+        if (qw[i] == -128) return SVDQ_EINVAL;
+    pack_common(shape, rinv, l1s, l2, bias, out_rinv, out_l1s, out_l2, out_bias);
+    std::memset(out_wcodes, 0, (size_t)K * Np);
+    std::memset(out_wscales, 0, (size_t)Np * 2);
+    parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+        for (size_t k = k0; k < k1; ++k)
+            for (int n = 0; n < N; ++n) out_wcodes[svdq::i8_code_offset((int)k, Np, n)] = (uint8_t)qw[k * N + n];
+    });
+    std::memcpy(out_wscales, sw, (size_t)N * 2);
+    return SVDQ_OK;
+}
+
+int svdq_w8a8_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                      float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2, uint8_t *out_wcodes,
+                      uint16_t *out_wscales, float *out_bias) {
+    const int st = check_shape(shape, 0);
+    if (st != SVDQ_OK) return st;
+    if (!W || !x_absmax || !out_rinv || !out_l1s || !out_l2 || !out_wcodes || !out_wscales || !out_bias)
+        return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, G = K / kGroup;
+    try {
+        SplitLayer sl;
+        split_layer(shape, W, x_absmax, sl);
+        // the residual against the stored factors as fp32, then Eq. 1 per output channel over all K (q_max = 127)
+        std::vector<float> Rf((size_t)K * N);
+        parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
+            std::vector<float> Rg((size_t)kGroup * N);
+            std::vector<double> prow(N);
+            for (size_t g = g0; g < g1; ++g) {
+                residual_rows(shape, sl, g, Rg, prow);
+                std::memcpy(Rf.data() + g * kGroup * (size_t)N, Rg.data(), Rg.size() * 4);
+            }
+        });
+        std::vector<int8_t> qw((size_t)K * N);
+        std::vector<uint16_t> sw(N);
+        parallel_for((size_t)N, [&](size_t n0, size_t n1, int) {
+            for (size_t n = n0; n < n1; ++n) {
+                float amax = 0.0f;
+                for (int k = 0; k < K; ++k) amax = std::max(amax, std::fabs(Rf[(size_t)k * N + n]));
+                float s32 = amax / 127.0f;
+                if (!(s32 <= 65504.0f)) s32 = 65504.0f;
+                const uint16_t s16 = f32_to_f16(s32);
+                const float sc = f16_to_f32(s16);
+                const float rcp = sc > 0.0f ? 1.0f / sc : 0.0f;
+                for (int k = 0; k < K; ++k) {
+                    float q = std::nearbyintf(Rf[(size_t)k * N + n] * rcp);
+                    q = std::min(127.0f, std::max(-127.0f, q));
+                    qw[(size_t)k * N + n] = (int8_t)q;
+                }
+                sw[n] = s16;
+            }
+        });
+        return svdq_w8a8_pack(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), qw.data(), sw.data(), bias, out_rinv,
+                              out_l1s, out_l2, out_wcodes, out_wscales, out_bias);
+    } catch (const std::bad_alloc &) {
+        return SVDQ_ENOMEM;
+    }
+}
+
+int svdq_w8a8_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, int8_t *out_qw) {
+    const int st = check_shape(shape, 0);
+    if (st != SVDQ_OK) return st;
+    if (!wcodes || !out_qw) return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, Np = svdq::round_up(N, kRowPad);
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n) out_qw[(size_t)k * N + n] = (int8_t)wcodes[svdq::i8_code_offset(k, Np, n)];
+    return SVDQ_OK;
+}
+
+int svdq_w8a8_unpack_wscales(const svdq_shape *shape, const uint16_t *wscales, uint16_t *out_sw) {
+    const int st = check_shape(shape, 0);
+    if (st != SVDQ_OK) return st;
+    if (!wscales || !out_sw) return SVDQ_EINVAL;
+    std::memcpy(out_sw, wscales, (size_t)shape->N * 2);
+    return SVDQ_OK;
+}
+
+int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out) {
+    const int st = check_shape(shape, kAnyGroup);
     if (st != SVDQ_OK) return st;
     if (!l1s || !out) return SVDQ_EINVAL;
     for (int k = 0; k < shape->K; ++k)
@@ -777,7 +883,7 @@ int svdq_unpack_l1s(const svdq_shape *shape, const uint16_t *l1s, uint16_t *out)
 }
 
 int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out) {
-    const int st = check_shape(shape, 0);
+    const int st = check_shape(shape, kAnyGroup);
     if (st != SVDQ_OK) return st;
     if (!l2 || !out) return SVDQ_EINVAL;
     for (int j = 0; j < shape->rank; ++j)
@@ -788,13 +894,13 @@ int svdq_unpack_l2(const svdq_shape *shape, const uint16_t *l2, uint16_t *out) {
 int svdq_append_lora(const svdq_shape *shape, const uint16_t *l1s, const uint16_t *l2, const float *down,
                      const float *up, int r_add, float scale, svdq_shape *out_shape, uint16_t *out_l1s,
                      uint16_t *out_l2) {
-    const int st = check_shape(shape, 0);
+    const int st = check_shape(shape, kAnyGroup);
     if (st != SVDQ_OK) return st;
     if (!down || !up || !out_shape || r_add <= 0) return SVDQ_EINVAL;
     if (shape->rank > 0 && (!l1s || !l2)) return SVDQ_EINVAL;
     svdq_shape ns = *shape;
     ns.rank = svdq::round_up(shape->rank + r_add, 16);
-    const int st2 = check_shape(&ns, 0);
+    const int st2 = check_shape(&ns, kAnyGroup);
     if (st2 != SVDQ_OK) return st2;
     *out_shape = ns;
     if (!out_l1s || !out_l2) return SVDQ_EINVAL;

@@ -1,0 +1,420 @@
+// Kernels of the 8-bit setting of the layer (arXiv 2411.05007, App. "Implementation Details": per-token dynamic
+// activation quantization, per-channel weight quantization, low-rank branch of rank 16):
+//
+//   Y = s_x[m] s_w[n] (sum_k q_x[m,k] q_w[k,n])  +  H L2  +  bias                                   (Eq. 2, Eq. 5)
+//
+// quant8_kernel: smoothing and INT8 quantization with one fp16 scale per token (Eq. 1, q_max = 127), codes
+// written in the operand order of v_mfma_i32_32x32x32_i8.  The down projection H = X L1s is the 4-bit path's
+// activation kernel in its projection-only mode.
+// gemm_w8a8_kernel: the pipeline of the MXFP4 GEMM (128 x 256 workgroup tile, operands through a four-stage LDS ring
+// filled by direct-to-LDS loads, one barrier per step) with int8 MFMAs; a step is 32 channels, so the ring has the
+// same geometry (32 bytes per row and step).  The int32 sums are exact and are scaled once, after the K loop:
+// there is no per-group rescale, which is what holds the INT4 kernel back.  The 16-bit branch is added after
+// the scaling (bf16 MFMAs onto the fp32 tile), then bias, bf16 rounding and LDS-transposed stores.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "buffer.h"
+#include "kernels.h"
+#include "layout.h"
+
+namespace svdq {
+namespace {
+
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Tile configuration: 2 x 2 wavefronts, each RB x CB MFMA blocks of 32 x 32.  <2, 4>: 128 x 256 workgroup tile;
+// <3, 3>: 192 x 192 (nine MFMAs per six operand blocks instead of eight; used where it makes the tile count a whole
+// number of rounds of the chip's 512 workgroup places, e.g. 24 x 64 = 1536 tiles for M = 4608, N = 12288).
+// Both have 12 operand blocks per step: three direct-to-LDS loads per wavefront.
+template <int RB, int CB>
+struct W8Tile {
+    static constexpr int kRB = RB, kCB = CB;
+    static constexpr int kWM = 32 * RB, kWN = 32 * CB;               // wavefront tile
+    static constexpr int kBM = 2 * kWM, kBN = 2 * kWN;               // workgroup tile
+    static constexpr int kOutRow = kWN * 2 + 16;                     // epilogue staging: one row of bf16 + 16 bytes pad
+    static constexpr int kFragsA = kBM / 32, kFragsB = kBN / 32;
+    static constexpr int kStageBytes = (kFragsA + kFragsB) * 1024;   // one stage = the operand blocks of one 64-channel step
+    static constexpr int kRingBytes = 4 * kStageBytes;               // four stages
+    static constexpr int kOutBytes = 4 * 32 * kOutRow;
+    static constexpr int kLdsBytes = kRingBytes > kOutBytes ? kRingBytes : kOutBytes;
+    static_assert(kFragsA + kFragsB == 12 && RB + CB == 6, "three direct loads per wavefront and step, six operand blocks per wavefront");
+};
+typedef __attribute__((address_space(3))) void *lds_ptr;
+constexpr int kI8RowBytes = 32;      // bytes of one row of one 32-channel step
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// maximum over the 8 lanes l % 8 = 0..7 that share a token in the load map
+__device__ __forceinline__ float max_over_8_lanes(float a) {
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true)));    // quad_perm [1,0,3,2]
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4E, 0xf, 0xf, true)));    // quad_perm [2,3,0,1]
+    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x141, 0xf, 0xf, true)));   // row_half_mirror
+    return a;
+}
+
+// Per-token INT8 quantization.  A workgroup of four wavefronts owns 16 tokens; wavefront w takes the 64-channel
+// groups w, w + 4, ...  Lane map of the 4-bit activation kernel: lane l -> tokens l / 8 and l / 8 + 8, channels
+// 8 (l % 8) .. + 7 of the group, so every load and store instruction covers whole lines.  Pass 1 finds the tokens'
+// maxima (8 lanes by DPP, 4 wavefronts through LDS); pass 2 reads X again (cache resident) and writes the codes.
+__global__ __launch_bounds__(256) void quant8_kernel(Quant8Params p) {
+    __shared__ float red[4][16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r8 = lane >> 3, c8 = lane & 7;
+    const int m0 = blockIdx.x * 16;
+    const int ma = m0 + r8, mb = ma + 8;                               // < Mpad
+    const size_t xa = (size_t)(ma < p.M ? ma : p.M - 1) * p.K + 8 * c8;   // rows past M read the last row; their codes land in padding rows
+    const size_t xb = (size_t)(mb < p.M ? mb : p.M - 1) * p.K + 8 * c8;
+    const int G = p.K / 64;
+    auto smoothed = [&](int g, float (&a)[8], float (&b)[8]) {
+        const uint4 va = *reinterpret_cast<const uint4 *>(p.X + xa + (size_t)g * 64);
+        const uint4 vb = *reinterpret_cast<const uint4 *>(p.X + xb + (size_t)g * 64);
+        const float4 r0 = *reinterpret_cast<const float4 *>(p.rinv + g * 64 + 8 * c8);
+        const float4 r1 = *reinterpret_cast<const float4 *>(p.rinv + g * 64 + 8 * c8 + 4);
+        const float r[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+        const uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[2 * i] = bf16lo(wa[i]) * r[2 * i];
+            a[2 * i + 1] = bf16hi(wa[i]) * r[2 * i + 1];
+            b[2 * i] = bf16lo(wb[i]) * r[2 * i];
+            b[2 * i + 1] = bf16hi(wb[i]) * r[2 * i + 1];
+        }
+    };
+    float amax_a = 0.f, amax_b = 0.f;
+    for (int g = wave; g < G; g += 4) {
+        float a[8], b[8];
+        smoothed(g, a, b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            amax_a = fmaxf(amax_a, fabsf(a[e]));
+            amax_b = fmaxf(amax_b, fabsf(b[e]));
+        }
+    }
+    amax_a = max_over_8_lanes(amax_a);
+    amax_b = max_over_8_lanes(amax_b);
+    if (c8 == 0) {
+        red[wave][r8] = amax_a;
+        red[wave][r8 + 8] = amax_b;
+    }
+    __syncthreads();
+    amax_a = fmaxf(fmaxf(red[0][r8], red[1][r8]), fmaxf(red[2][r8], red[3][r8]));
+    amax_b = fmaxf(fmaxf(red[0][r8 + 8], red[1][r8 + 8]), fmaxf(red[2][r8 + 8], red[3][r8 + 8]));
+    // Eq. 1: s = fp16(max / 127) (IEEE division, round to nearest even, saturating), codes from x * (1.0f / s)
+    auto scale_of = [](float amax, _Float16 &sh) {
+        float s32 = amax / 127.0f;
+        s32 = fminf(s32, 65504.0f);
+        sh = (_Float16)s32;
+        const float sc = (float)sh;
+        return sc > 0.f ? 1.0f / sc : 0.f;
+    };
+    _Float16 sha, shb;
+    const float rcp_a = scale_of(amax_a, sha), rcp_b = scale_of(amax_b, shb);
+    if (wave == 0 && c8 == 0) {
+        p.sx[ma] = __builtin_bit_cast(uint16_t, sha);
+        p.sx[mb] = __builtin_bit_cast(uint16_t, shb);
+    }
+    // the 8 channels of a lane are half of a 16-byte operand chunk: step 2 g + c8 / 4, lane half (c8 % 4) / 2, bytes 8 (c8 % 2) ..
+    const int step_in = c8 >> 2, half = (c8 & 3) >> 1, byte0 = 8 * (c8 & 1);
+    for (int g = wave; g < G; g += 4) {
+        float a[8], b[8];
+        smoothed(g, a, b);
+        uint32_t wa[2] = {0u, 0u}, wb[2] = {0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float qa = fminf(127.f, fmaxf(-127.f, __builtin_rintf(a[e] * rcp_a)));
+            const float qb = fminf(127.f, fmaxf(-127.f, __builtin_rintf(b[e] * rcp_b)));
+            wa[e >> 2] |= ((uint32_t)(int)qa & 0xffu) << (8 * (e & 3));
+            wb[e >> 2] |= ((uint32_t)(int)qb & 0xffu) << (8 * (e & 3));
+        }
+        const int gs = 2 * g + step_in;
+        const size_t oa = ((((size_t)gs * (p.Mpad / 32) + ma / 32) * 64 + half * 32 + ma % 32) * 16) + byte0;
+        const size_t ob = ((((size_t)gs * (p.Mpad / 32) + mb / 32) * 64 + half * 32 + mb % 32) * 16) + byte0;
+        *reinterpret_cast<uint2 *>(p.codes + oa) = make_uint2(wa[0], wa[1]);
+        *reinterpret_cast<uint2 *>(p.codes + ob) = make_uint2(wb[0], wb[1]);
+    }
+}
+
+// canonical views of the workspace for parity checks
+__global__ void debug_act_w8_kernel(DebugActW8Params p) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p.out_codes && idx < (size_t)p.M * p.K) {
+        const int m = (int)(idx / p.K), k = (int)(idx % p.K);
+        p.out_codes[idx] = (int8_t)p.codes[i8_code_offset(k, p.Mpad, m)];
+    }
+    if (p.out_sx && idx < (size_t)p.M) p.out_sx[idx] = p.sx[idx];
+    if (p.out_H && idx < (size_t)p.M * p.rank) p.out_H[idx] = p.H[idx];
+}
+
+template <int RB, int CB>
+__global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
+    using T = W8Tile<RB, CB>;
+    constexpr int kRB = RB, kCB = CB, kWM = T::kWM, kWN = T::kWN, kBM = T::kBM, kBN = T::kBN;
+    constexpr int kFragsA = T::kFragsA, kStageBytes = T::kStageBytes, kOutRowW8 = T::kOutRow;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm0 = (wave & 1) * kWM;
+    const int wn0 = (wave >> 1) * kWN;
+
+    // XCD-aware tile order: workgroups are dealt round-robin to the 8 XCDs; renumber them so that an XCD owns a
+    // contiguous run of tiles, walked in bands of tile rows, and its L2 sees the same operand rows and columns
+    const int tiles_m = (p.M + kBM - 1) / kBM;
+    const int tiles_n = (p.N + kBN - 1) / kBN;
+    const int total = tiles_m * tiles_n;
+    const int g_begin = 0, g_end = p.K / 32;      // steps of 32 channels
+    int tile_m, tile_n;
+    {
+        const int bid = (int)blockIdx.x;
+        const int per = (total + 7) / 8;
+        const int id = (total % 8 == 0) ? (bid % 8) * per + (bid / 8) : bid;      // a bijection only when 8 divides the count
+        constexpr int kBand = 4;
+        const int band = id / (kBand * tiles_n);
+        const int band_rows = (tiles_m - band * kBand) < kBand ? (tiles_m - band * kBand) : kBand;
+        const int in = id - band * kBand * tiles_n;
+        tile_m = band * kBand + in % band_rows;
+        tile_n = in / band_rows;
+    }
+    const int gm0 = tile_m * kBM, gn0 = tile_n * kBN;      // the launch checks that every tile lies inside the padded rows and columns
+
+    intx16 iacc[kRB][kCB];
+#pragma unroll
+    for (int r = 0; r < kRB; ++r)
+#pragma unroll
+        for (int c = 0; c < kCB; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) iacc[r][c][v] = 0;
+
+
+    // one 32-row block of one step = one contiguous kilobyte: rows * 32 bytes from the start of the step's slab
+    const int a_stride = p.Mpad * kI8RowBytes;
+    const int b_stride = p.Npad * kI8RowBytes;
+    struct Frags { u32x4 f[kRB + kCB]; };      // the wavefront's activation blocks, then its weight blocks
+    // Memory -> LDS without a stop in registers: the twelve operand blocks of a step (activation blocks first) are
+    // dealt to the four wavefronts, blocks w, w + 4 and w + 8 to wavefront w (one kilobyte each; lane l's 16 bytes
+    // land at l * 16 of the block, which is the operand order).  Which operand a block belongs to is uniform per wavefront.
+    const int glast = g_end - 1;
+    __amdgpu_buffer_rsrc_t rs_d[3];
+    int d_base[3], d_stride[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int j = wave + 4 * i;
+        const bool is_a = j < kFragsA;
+        rs_d[i] = is_a ? make_rsrc(p.xcodes, (size_t)p.K * p.Mpad) : make_rsrc(p.wcodes, (size_t)p.K * p.Npad);
+        d_base[i] = is_a ? gm0 * kI8RowBytes + j * 1024 : gn0 * kI8RowBytes + (j - kFragsA) * 1024;
+        d_stride[i] = is_a ? a_stride : b_stride;
+    }
+    auto dma = [&](int g, int stage) {
+        const int gc = g < glast ? g : glast;      // past the end: the last step once more (never read), so that every step issues three requests
+        unsigned char *st = lds + stage * kStageBytes + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_d[i], (lds_ptr)(st + i * 4096), 16, lane * 16, d_base[i] + gc * d_stride[i], 0, 0);
+    };
+    // LDS -> registers.  These reads are written as instructions of their own, with explicit waits, because the
+    // compiler would make every LDS read wait for ALL outstanding memory-to-LDS requests, also those of later stages.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    const uint32_t rd_a = lds_base + lane * 16 + (wm0 / 32) * 1024;
+    const uint32_t rd_b = lds_base + lane * 16 + (kFragsA + wn0 / 32) * 1024;
+#define SVDQ_LDS_READ(F, I, STAGE) \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(F.f[I]) : "v"((I) < kRB ? rd_a : rd_b), "n"((STAGE) * kStageBytes + ((I) < kRB ? (I) : (I) - kRB) * 1024))
+#define SVDQ_READ_STAGE(F, STAGE) \
+    SVDQ_LDS_READ(F, 0, STAGE); SVDQ_LDS_READ(F, 1, STAGE); SVDQ_LDS_READ(F, 2, STAGE); \
+    SVDQ_LDS_READ(F, 3, STAGE); SVDQ_LDS_READ(F, 4, STAGE); SVDQ_LDS_READ(F, 5, STAGE);
+    // all LDS reads of this wavefront have returned; tied to the registers they fill, so that nothing that uses them moves above
+#define SVDQ_READS_DONE(F) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(F.f[0]), "+v"(F.f[1]), "+v"(F.f[2]), "+v"(F.f[3]), "+v"(F.f[4]), "+v"(F.f[5]))
+
+    const int q_begin = g_begin / 4, q_end = (g_end + 3) / 4;
+    Frags f0, f1;
+    dma(g_begin, 0);
+    dma(g_begin + 1, 1);
+    dma(g_begin + 2, 2);
+    __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
+
+    // ---- main loop -----------------------------------------------------------------------------------------------
+    // Step g multiplies from registers that were read from LDS during step g - 1.  Per step and wavefront: wait until
+    // its own requests for step g + 1 have landed (all but the newest three, which are those for step g + 2), one
+    // barrier (now every wavefront's share of step g + 1 is in LDS, and everybody is done reading the stage that
+    // step g + 3 will overwrite), read step g + 1 into the other register set, request step g + 3, 8 MFMAs.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    SVDQ_READ_STAGE(f0, 0)
+    SVDQ_READS_DONE(f0);
+#define SVDQ_W8_STEP(SEL, cur, nxt)                                                                                  \
+    if (g0 + SEL < g_end) {                                                                                           \
+        asm volatile("s_waitcnt vmcnt(3)" ::: "memory");                                                              \
+        __builtin_amdgcn_s_barrier();                                                                                 \
+        SVDQ_READ_STAGE(nxt, (SEL + 1) & 3)                                                                           \
+        dma(g0 + SEL + 3, (SEL + 3) & 3);                                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                            \
+        _Pragma("unroll") for (int r = 0; r < kRB; ++r)                                                               \
+            _Pragma("unroll") for (int c = 0; c < kCB; ++c)                                                           \
+                iacc[r][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(intx4, cur.f[r]), __builtin_bit_cast(intx4, cur.f[kRB + c]), iacc[r][c], 0, 0, 0); \
+        __builtin_amdgcn_sched_barrier(0);                                                                            \
+        SVDQ_READS_DONE(nxt);                                                                                         \
+    }
+    for (int q = q_begin; q < q_end; ++q) {
+        const int g0 = 4 * q;
+        SVDQ_W8_STEP(0, f0, f1)
+        SVDQ_W8_STEP(1, f1, f0)
+        SVDQ_W8_STEP(2, f0, f1)
+        SVDQ_W8_STEP(3, f1, f0)
+    }
+#undef SVDQ_W8_STEP
+    // the ring becomes the epilogue's staging area: every request of every wavefront must have landed first
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+
+    // ---- Eq. 2, once per output: the exact int32 sums become fp32 and take both scales ---------------------------
+    floatx16 acc[kRB][kCB];
+    {
+        float sw[kCB];
+#pragma unroll
+        for (int c = 0; c < kCB; ++c) sw[c] = (float)__builtin_bit_cast(_Float16, p.sw[gn0 + wn0 + c * 32 + li]);      // padded to Npad
+#pragma unroll
+        for (int r = 0; r < kRB; ++r)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // accumulator registers 4 j .. 4 j + 3 hold rows 8 j + 4 (lane / 32) .. + 3 of the block: four consecutive fp16 scales
+                const uint2 raw = *reinterpret_cast<const uint2 *>(p.sx + gm0 + wm0 + r * 32 + 8 * j + 4 * lh);      // < Mpad
+                const uint32_t w2[2] = {raw.x, raw.y};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float sx = (float)__builtin_bit_cast(_Float16, (uint16_t)(w2[i >> 1] >> (16 * (i & 1))));
+#pragma unroll
+                    for (int c = 0; c < kCB; ++c) acc[r][c][4 * j + i] = (float)iacc[r][c][4 * j + i] * (sx * sw[c]);
+                }
+            }
+    }
+
+    // ---- low-rank up projection: added onto the scaled tile (bf16 MFMAs, H as exact hi + lo parts) ----
+    // The operands of rank step ks + 1 are requested before step ks is multiplied, so the branch pays one memory
+    // round trip (shared with the first operand blocks of the main loop), not one per 16 columns of H.
+    if (p.rank > 0) {
+        const int ksteps = p.rank / 16;
+        const unsigned char *hf = p.hfrag + (size_t)((gm0 + wm0) / 32) * ksteps * 2048 + lane * 16;
+        struct LowRank { uint4 hhi[kRB], hlo[kRB], braw[kCB]; };
+        auto load_step = [&](LowRank &o, int ks) {
+#pragma unroll
+            for (int r = 0; r < kRB; ++r) {
+                const unsigned char *hp = hf + ((size_t)r * ksteps + ks) * 2048;
+                o.hhi[r] = *reinterpret_cast<const uint4 *>(hp);
+                o.hlo[r] = *reinterpret_cast<const uint4 *>(hp + 1024);
+            }
+#pragma unroll
+            for (int c = 0; c < kCB; ++c) {
+                const int col = gn0 + wn0 + c * 32 + li;        // < Npad
+                o.braw[c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
+            }
+        };
+        auto multiply = [&](const LowRank &o) {
+#pragma unroll
+            for (int c = 0; c < kCB; ++c) {
+                const bf16x8 bl = __builtin_bit_cast(bf16x8, o.braw[c]);
+#pragma unroll
+                for (int r = 0; r < kRB; ++r) {
+                    acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hhi[r]), bl, acc[r][c], 0, 0, 0);
+                    acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hlo[r]), bl, acc[r][c], 0, 0, 0);
+                }
+            }
+        };
+        LowRank e, o;
+        load_step(e, 0);
+        for (int ks = 0; ks < ksteps; ks += 2) {
+            if (ks + 1 < ksteps) load_step(o, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(e);
+            if (ks + 1 < ksteps) {
+                if (ks + 2 < ksteps) load_step(e, ks + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(o);
+            }
+        }
+    }
+
+    // ---- epilogue: bias, bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores --------
+    unsigned char *ob = lds + wave * (32 * kOutRowW8);
+    float bias[kCB];
+#pragma unroll
+    for (int c = 0; c < kCB; ++c) bias[c] = p.bias[gn0 + wn0 + c * 32 + li];      // padded to Npad
+    const bool full = gm0 + kBM <= p.M && gn0 + kBN <= p.N && (p.N % 8) == 0;
+#pragma unroll
+    for (int r = 0; r < kRB; ++r) {
+#pragma unroll
+        for (int c = 0; c < kCB; ++c) {
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const int row = 8 * (v >> 2) + 4 * lh + (v & 3);      // accumulator register v: row 8 (v / 4) + 4 (lane / 32) + v % 4
+                const uint32_t pr = bf16_pair(acc[r][c][v] + bias[c], acc[r][c][v + 1] + bias[c]);
+                *reinterpret_cast<uint16_t *>(ob + row * kOutRowW8 + (c * 32 + li) * 2) = (uint16_t)pr;
+                *reinterpret_cast<uint16_t *>(ob + (row + 1) * kOutRowW8 + (c * 32 + li) * 2) = (uint16_t)(pr >> 16);
+            }
+        }
+        // 32 rows of kWN bf16 = 32 * kWN / 8 chunks of 16 bytes: kWN / 16 per lane, kWN / 8 lanes per row
+#pragma unroll
+        for (int i = 0; i < kWN / 16; ++i) {
+            const int q = lane + 64 * i;
+            const int row = q / (kWN / 8), ch = q % (kWN / 8);
+            const uint4 v = *reinterpret_cast<const uint4 *>(ob + row * kOutRowW8 + ch * 16);
+            const int grow = gm0 + wm0 + r * 32 + row;
+            const int gcol = gn0 + wn0 + ch * 8;
+            uint16_t *dst = p.Y + (size_t)grow * p.N + gcol;
+            if (full) {
+                *reinterpret_cast<uint4 *>(dst) = v;
+            } else if (grow < p.M) {
+                const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
+                                       (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (gcol + k < p.N) dst[k] = e[k];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_quant8(const Quant8Params &p, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    if (p.K % 64 || p.Mpad % kRowPad || p.Mpad < p.M) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(quant8_kernel, dim3((p.M + 15) / 16), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_debug_act_w8(const DebugActW8Params &p, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    const size_t n = (size_t)p.M * p.K;
+    hipLaunchKernelGGL(debug_act_w8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_w8a8(const GemmW8Params &p, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    using T = W8Tile<2, 4>;
+    // what the kernel's addressing assumes
+    if (p.K <= 0 || p.K % 64 || p.Mpad % kRowPad || p.Npad % kRowPad || p.Mpad < p.M || p.Npad < p.N || p.rank % 16 ||
+        (size_t)p.K * p.Mpad >= (size_t)1 << 31 || (size_t)p.K * p.Npad >= (size_t)1 << 31)
+        return hipErrorInvalidValue;
+    const int tiles_m = (p.M + T::kBM - 1) / T::kBM, tiles_n = (p.N + T::kBN - 1) / T::kBN;
+    if (tiles_m * T::kBM > p.Mpad || tiles_n * T::kBN > p.Npad) return hipErrorInvalidValue;
+    auto k = gemm_w8a8_kernel<2, 4>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k, dim3(tiles_m * tiles_n), dim3(256), T::kLdsBytes, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace svdq

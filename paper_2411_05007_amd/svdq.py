@@ -25,6 +25,8 @@ EXPORTS = [
     "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2", "svdq_append_lora", "svdq_prepare_refined",
     "svdq_fp4_prepared_sizes", "svdq_fp4_prepare", "svdq_fp4_pack", "svdq_fp4_unpack_wcodes", "svdq_fp4_unpack_wscales",
     "svdq_fp4_workspace_bytes", "svdq_fp4_linear_forward", "svdq_fp4_debug_act",
+    "svdq_w8a8_prepared_sizes", "svdq_w8a8_prepare", "svdq_w8a8_pack", "svdq_w8a8_unpack_wcodes", "svdq_w8a8_unpack_wscales",
+    "svdq_w8a8_workspace_bytes", "svdq_w8a8_linear_forward", "svdq_w8a8_debug_act",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
     "svdq_forward_options", "svdq_profile_event",
 ]
@@ -79,6 +81,15 @@ def lib() -> C.CDLL:
             getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
         L.svdq_fp4_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_fp4_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
+        L.svdq_w8a8_workspace_bytes.restype = C.c_size_t
+        L.svdq_w8a8_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
+        L.svdq_w8a8_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
+        L.svdq_w8a8_prepare.argtypes = [C.POINTER(Shape)] + [vp] * 9
+        L.svdq_w8a8_pack.argtypes = [C.POINTER(Shape)] + [vp] * 12
+        for n in ("svdq_w8a8_unpack_wcodes", "svdq_w8a8_unpack_wscales"):
+            getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
+        L.svdq_w8a8_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
+        L.svdq_w8a8_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_debug_group_acc.argtypes = [C.POINTER(LayerDev), vp, C.c_int] + [C.c_int] * 4 + [vp, vp]
@@ -120,10 +131,16 @@ def _is_fp4(shape: Shape) -> bool:
     return shape.group == 32
 
 
+def _is_w8(shape: Shape) -> bool:
+    return shape.group == 0
+
+
 def _alloc_prepared(shape: Shape) -> PreparedHost:
     sz = Sizes()
     if _is_fp4(shape):
         _check(lib().svdq_fp4_prepared_sizes(C.byref(shape), C.byref(sz)), "svdq_fp4_prepared_sizes")
+    elif _is_w8(shape):
+        _check(lib().svdq_w8a8_prepared_sizes(C.byref(shape), C.byref(sz)), "svdq_w8a8_prepared_sizes")
     else:
         _check(lib().svdq_prepared_sizes(C.byref(shape), C.byref(sz)), "svdq_prepared_sizes")
     return PreparedHost(
@@ -254,6 +271,56 @@ def svdq_fp4_unpack(p: PreparedHost):
     return {"rinv": p.rinv.copy(), "l1s": l1s, "l2": l2, "qw": qw, "bw": bw, "bias": p.bias[:N].copy()}
 
 
+def svdq_w8a8_prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int = 16, alpha: float = 0.5,
+                      bias: Optional[np.ndarray] = None) -> PreparedHost:
+    """The 8-bit setting (shape.group = 0): per-channel INT8 residual, rank-r 16-bit branch."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    K, N = W.shape
+    x_absmax = np.ascontiguousarray(x_absmax, dtype=np.float32)
+    assert x_absmax.shape == (K,)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha, group=0)
+    out = _alloc_prepared(shape)
+    _check(lib().svdq_w8a8_prepare(C.byref(shape), _ptr(W), _ptr(x_absmax), _ptr(b), _ptr(out.rinv), _ptr(out.l1s),
+                                   _ptr(out.l2), _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias)), "svdq_w8a8_prepare")
+    return out
+
+
+def svdq_w8a8_pack(rinv, l1s_bits, l2_bits, qw, sw_f16, bias=None, alpha: float = 0.5) -> PreparedHost:
+    """Pack canonical W8A8 arrays: qw int8 [K, N], sw fp16 [N]."""
+    qw = np.ascontiguousarray(qw, dtype=np.int8)
+    K, N = qw.shape
+    sw = np.ascontiguousarray(np.asarray(sw_f16).view(np.uint16))
+    assert sw.shape == (N,)
+    l1s_bits = np.ascontiguousarray(l1s_bits, dtype=np.uint16)
+    rank = l1s_bits.shape[1] if l1s_bits.ndim == 2 else 0
+    l2_bits = np.ascontiguousarray(l2_bits, dtype=np.uint16)
+    rinv = np.ascontiguousarray(rinv, dtype=np.float32)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha, group=0)
+    out = _alloc_prepared(shape)
+    _check(lib().svdq_w8a8_pack(C.byref(shape), _ptr(rinv), _ptr(l1s_bits) if rank else None, _ptr(l2_bits) if rank else None,
+                                _ptr(qw), _ptr(sw), _ptr(b), _ptr(out.rinv), _ptr(out.l1s), _ptr(out.l2),
+                                _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias)), "svdq_w8a8_pack")
+    return out
+
+
+def svdq_w8a8_unpack(p: PreparedHost):
+    """Canonical views of a W8A8 layer: dict(rinv, l1s, l2, qw int8 [K,N], sw fp16 [N], bias)."""
+    K, N, r = p.shape.K, p.shape.N, p.shape.rank
+    qw = np.zeros((K, N), np.int8)
+    sw = np.zeros(N, np.uint16)
+    l1s = np.zeros((K, r), np.uint16)
+    l2 = np.zeros((r, N), np.uint16)
+    L = lib()
+    _check(L.svdq_w8a8_unpack_wcodes(C.byref(p.shape), _ptr(p.wcodes), _ptr(qw)), "svdq_w8a8_unpack_wcodes")
+    _check(L.svdq_w8a8_unpack_wscales(C.byref(p.shape), _ptr(p.wscales), _ptr(sw)), "svdq_w8a8_unpack_wscales")
+    if r > 0:
+        _check(L.svdq_unpack_l1s(C.byref(p.shape), _ptr(p.l1s), _ptr(l1s)), "svdq_unpack_l1s")
+        _check(L.svdq_unpack_l2(C.byref(p.shape), _ptr(p.l2), _ptr(l2)), "svdq_unpack_l2")
+    return {"rinv": p.rinv.copy(), "l1s": l1s, "l2": l2, "qw": qw, "sw": sw.view(np.float16), "bias": p.bias[:N].copy()}
+
+
 def svdq_append_lora(p: PreparedHost, down: np.ndarray, up: np.ndarray, scale: float = 1.0) -> PreparedHost:
     """A layer with the adapter `scale * down @ up` appended to its 16-bit branch; everything else is shared with `p`."""
     down = np.ascontiguousarray(down, dtype=np.float32)
@@ -282,6 +349,8 @@ def svdq_profile_event(event_handle: Optional[int]) -> None:
 def svdq_workspace_bytes(M: int, shape: Shape) -> int:
     if _is_fp4(shape):
         return int(lib().svdq_fp4_workspace_bytes(int(M), C.byref(shape)))
+    if _is_w8(shape):
+        return int(lib().svdq_w8a8_workspace_bytes(int(M), C.byref(shape)))
     return int(lib().svdq_workspace_bytes(int(M), C.byref(shape)))
 
 
@@ -299,6 +368,7 @@ class DeviceLayer:
         self.K, self.N, self.rank = prepared.shape.K, prepared.shape.N, prepared.shape.rank
         self.G = self.K // 64
         self.fp4 = _is_fp4(prepared.shape)
+        self.w8 = _is_w8(prepared.shape)
         up = lambda a: torch.from_numpy(a.view(np.uint8) if a.dtype != np.uint8 else a).to(self.device)
         self._bufs = {n: up(getattr(prepared, n)) for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")}
         self.cdesc = LayerDev(*[self._bufs[n].data_ptr() for n in ("rinv", "l1s", "l2", "wcodes", "wscales", "bias")],
@@ -320,9 +390,9 @@ class DeviceLayer:
         if workspace is None:
             workspace = self.workspace(M)
         s = torch.cuda.current_stream(x.device) if stream is None else stream
-        fwd = lib().svdq_fp4_linear_forward if self.fp4 else lib().svdq_linear_forward
-        _check(fwd(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
-                   workspace.numel(), s.cuda_stream), "svdq_fp4_linear_forward" if self.fp4 else "svdq_linear_forward")
+        name = "svdq_fp4_linear_forward" if self.fp4 else "svdq_w8a8_linear_forward" if self.w8 else "svdq_linear_forward"
+        _check(getattr(lib(), name)(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel(), s.cuda_stream), name)
         self._last_ws, self._last_M = workspace, M
         return out
 
@@ -341,6 +411,12 @@ class DeviceLayer:
             torch.cuda.synchronize(self.device)
             return codes.cpu().numpy(), bx.cpu().numpy(), (H.cpu().numpy() if self.rank else None)
         codes = torch.empty((M, self.K), dtype=torch.int8, device=self.device)
+        if self.w8:       # codes int8 [M,K], one fp16 scale per token
+            sx = torch.empty((M,), dtype=torch.float16, device=self.device)
+            _check(lib().svdq_w8a8_debug_act(C.byref(self.cdesc), workspace.data_ptr(), M, codes.data_ptr(), sx.data_ptr(),
+                                             H.data_ptr() if self.rank else None, s.cuda_stream), "svdq_w8a8_debug_act")
+            torch.cuda.synchronize(self.device)
+            return codes.cpu().numpy(), sx.cpu().numpy(), (H.cpu().numpy() if self.rank else None)
         sx = torch.empty((M, self.G), dtype=torch.float16, device=self.device)
         _check(lib().svdq_debug_act(C.byref(self.cdesc), workspace.data_ptr(), M, codes.data_ptr(), sx.data_ptr(),
                                     H.data_ptr() if self.rank else None, s.cuda_stream), "svdq_debug_act")

@@ -323,3 +323,42 @@ def test_refined_prepare_against_the_oracle(lib, fp4):
     assert p0 == 0 and np.array_equal(zero.wcodes, plain.wcodes) and np.array_equal(zero.l1s, plain.l1s) and np.isclose(e0[0], errs[0], rtol=1e-6)
     with pytest.raises(S.SvdqError):
         S.svdq_prepare_refined(w, ax, r, 65, fp4=fp4)
+
+
+def test_w8a8_prepare_matches_the_oracle_given_the_same_factors(lib):
+    from oracle import svdq_w8a8_oracle as W8
+    rng = np.random.default_rng(191)
+    K, N, r = 256, 112, 16
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 2, replace=False)] *= 20
+    w[:, 5] = 0.0                                       # with rank 0 below: an all-zero output channel
+    ax = np.abs(rng.standard_normal(K)).astype(np.float32) + 0.1
+    b = rng.standard_normal(N).astype(np.float32)
+    for rank in (r, 0):
+        prep = S.svdq_w8a8_prepare(w, ax, rank, bias=b)
+        assert prep.shape.group == 0
+        U = S.svdq_w8a8_unpack(prep)
+        qw, sw, _ = W8.residual_codes_from_factors(w, U["rinv"], U["l1s"], U["l2"])
+        assert np.array_equal(U["qw"], qw) and np.array_equal(U["sw"].view(np.uint16), sw.view(np.uint16))
+        assert np.array_equal(U["bias"], b)
+        if rank == 0:
+            assert U["sw"][5] == 0 and not U["qw"][:, 5].any()
+        again = S.svdq_w8a8_pack(U["rinv"], U["l1s"], U["l2"], U["qw"], U["sw"], U["bias"])
+        assert np.array_equal(again.wcodes, prep.wcodes) and np.array_equal(again.wscales, prep.wscales)
+    # native order: code (k, n) at [k / 32][n / 32][32 ((k % 32) / 16) + n % 32][k % 16], rows padded to 256
+    k, n, Np = 77, 37, 256
+    off = (((k // 32) * (Np // 32) + n // 32) * 64 + ((k % 32) // 16) * 32 + n % 32) * 16 + k % 16
+    assert np.int8(prep.wcodes[off]) == U["qw"][k, n]
+    sz = S.Sizes()
+    assert lib.svdq_prepared_sizes(C.byref(prep.shape), C.byref(sz)) == -2 and lib.svdq_fp4_prepared_sizes(C.byref(prep.shape), C.byref(sz)) == -2
+    bad = U["qw"].copy()
+    bad[0, 0] = -128
+    with pytest.raises(S.SvdqError):
+        S.svdq_w8a8_pack(U["rinv"], U["l1s"], U["l2"], bad, U["sw"], U["bias"])
+    # workspace: codes K * Mpad, scales, H and its bf16 split
+    assert S.svdq_workspace_bytes(300, prep.shape) == 256 * 512 + 512 * 2 + 2 * (512 * 1 * 4)
+    fake = S.LayerDev(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, S.make_shape(3072, 3072, 16, group=0))
+    fwd = lib.svdq_w8a8_linear_forward
+    assert fwd(C.byref(fake), C.c_void_p(0x1000), 16, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1024), None) == -4
+    assert fwd(C.byref(fake), C.c_void_p(0x1000), -1, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1 << 40), None) == -1
+    assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), 16, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1 << 40), None) == -2
