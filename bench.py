@@ -60,11 +60,13 @@ class Hip:
         return float(out.value)
 
 
-def cpu_baseline(case, L, prep_canon, rows=768, fp4=False):
+def cpu_baseline(case, L, prep_canon, rows=768, fmt="int4"):
     """The oracle as it stands, timed on the host cores over the first `rows` tokens of the same workload."""
     import numpy as np
-    if fp4:
+    if fmt == "fp4":
         from oracle import svdq_fp4_oracle as O
+    elif fmt == "w8a8":
+        from oracle import svdq_w8a8_oracle as O
     else:
         from oracle import svdq_oracle as O
 
@@ -94,9 +96,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="GEMM tile configuration id (0 = library default)")
     ap.add_argument("--breakdown", action="store_true", help="also time naive INT4 (no low-rank) and the unfused 4-kernel pipeline")
-    ap.add_argument("--format", choices=["int4", "fp4"], default="int4",
-                    help="4-bit format: int4 = the metric's (group 64, fp16 scales, INT8 MFMA); fp4 = the MXFP4 variant "
-                         "(E2M1, blocks of 32, power-of-two scales) on the block-scaled MFMA")
+    ap.add_argument("--format", choices=["int4", "fp4", "w8a8"], default="int4",
+                    help="int4 = the metric's format (group 64, fp16 scales, INT8 MFMA); fp4 = the MXFP4 variant "
+                         "(E2M1, blocks of 32, power-of-two scales) on the block-scaled MFMA; w8a8 = the paper's 8-bit setting "
+                         "(per-token / per-channel INT8, rank 16)")
     ap.add_argument("--lora", type=int, default=0, metavar="R",
                     help="append a synthetic rank-R adapter to the layer's 16-bit branch (no re-quantization) and time that")
     ap.add_argument("--pmc-run", action="store_true",
@@ -120,7 +123,9 @@ def main():
     case = I.case_by_name(args.case)
     L = I.make_layer(case)
     fp4 = args.format == "fp4"
-    prep = (S.svdq_fp4_prepare if fp4 else S.svdq_prepare)(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    w8 = args.format == "w8a8"
+    rank = 16 if w8 else case.rank                       # the paper's 8-bit setting uses rank 16
+    prep = (S.svdq_fp4_prepare if fp4 else S.svdq_w8a8_prepare if w8 else S.svdq_prepare)(L["w"], L["x_absmax"], rank, bias=L["bias"])
     if args.lora > 0:
         rng = np.random.default_rng(241105999)
         down = (rng.standard_normal((case.K, args.lora)) * 0.02).astype(np.float32)
@@ -202,14 +207,16 @@ def main():
     out = {
         "metric": ("fused W4A4+low-rank linear TOPS & us/layer, FLUX MLP M=4608 K=3072 N=12288 r=32"
                    if case.name == "flux_mlp_up" else f"fused W4A4+low-rank linear TOPS & us/layer, {case.name}")
-                  + (" [MXFP4 variant]" if fp4 else ""),
+                  + (" [MXFP4 variant]" if fp4 else " [W8A8 setting, r=16]" if w8 else ""),
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "us_per_layer": ms * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "fp4 (E2M1) block-scaled MFMA, fp32 accumulate, bf16 out" if fp4 else "int8 MFMA (int4 codes), int32 group sums, fp32 rescale, bf16 out",
+        "dtype": "fp4 (E2M1) block-scaled MFMA, fp32 accumulate, bf16 out" if fp4
+                 else "int8 MFMA (int8 codes), exact int32 sums, one fp32 rescale, bf16 out" if w8
+                 else "int8 MFMA (int4 codes), int32 group sums, fp32 rescale, bf16 out",
         "data": "synthetic",
         "config": {"workload": f"{case.name}: M={case.M} K={case.K} N={case.N} r={case.rank} g=64"
-                               + (" MXFP4 (blocks of 32)" if fp4 else "")
+                               + (" MXFP4 (blocks of 32)" if fp4 else " W8A8 (per token / per channel, branch rank 16)" if w8 else "")
                                + (f" + LoRA r={args.lora} (branch rank {prep.shape.rank})" if args.lora else "")
                                + (" (the FLUX MLP up projection the metric is quoted on)" if case.name == "flux_mlp_up" else ""),
                    "tile": args.tile, "sets_rotated": nsets},
@@ -219,7 +226,8 @@ def main():
                     "act_GBps": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9,
                     "act_frac_hbm_peak": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": "mfma",
-                     "kernel": ("gemm_fp4_kernel (MXFP4 GEMM" if fp4 else "gemm_kernel (W4A4 GEMM") + " + fused up projection, bias, bf16 store)",
+                     "kernel": ("gemm_fp4_kernel (MXFP4 GEMM" if fp4 else "gemm_w8a8_kernel (INT8 GEMM" if w8 else "gemm_kernel (W4A4 GEMM")
+                               + " + fused up projection, bias, bf16 store)",
                      "achieved": gemm_tops, "peak": FP4_MFMA_PEAK_TFLOPS if fp4 else INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
                      "note": ("FP4" if fp4 else "INT8") + " tera-ops/s: 2*M*N*K per launch / mean launch duration (HIP events on the launch stream)",
                      "frac": gemm_tops / (FP4_MFMA_PEAK_TFLOPS if fp4 else INT8_MFMA_PEAK_TOPS),
@@ -229,7 +237,7 @@ def main():
         naive = run(S.OPT_SKIP_LOWRANK, args.steps, 20, split=False)
         out["breakdown"] = {"fused_us": ms * 1e3, "naive_int4_us": naive["ms_per_step"] * 1e3,
                             "lowrank_overhead_fused": ms / naive["ms_per_step"] - 1.0}
-        if not fp4:                                      # the unfused pipeline exists for the INT4 path only
+        if not fp4 and not w8:                           # the unfused pipeline exists for the INT4 path only
             unfused = run(S.OPT_UNFUSED, max(20, args.steps // 2), 20, split=False)
             out["breakdown"].update(unfused_us=unfused["ms_per_step"] * 1e3,
                                     lowrank_overhead_unfused=unfused["ms_per_step"] / naive["ms_per_step"] - 1.0)
@@ -237,7 +245,8 @@ def main():
         out["breakdown"]["fused_us_again"] = again["ms_per_step"] * 1e3
     S.svdq_forward_options(0)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(case, L, (S.svdq_fp4_unpack if fp4 else S.svdq_unpack)(prep), fp4=fp4)
+        out["cpu_baseline"] = cpu_baseline(case, L, (S.svdq_fp4_unpack if fp4 else S.svdq_w8a8_unpack if w8 else S.svdq_unpack)(prep),
+                                           fmt=args.format)
     print(json.dumps(out), flush=True)
 
 

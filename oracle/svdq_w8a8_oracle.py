@@ -89,8 +89,13 @@ def quantize_activation(x_bits: np.ndarray, rinv: np.ndarray):
 
 
 def integer_product(qx: np.ndarray, qw: np.ndarray) -> np.ndarray:
-    """sum_k q_x[m,k] q_w[k,n], exact, int64."""
-    return qx.astype(np.int64) @ qw.astype(np.int64)
+    """sum_k q_x[m,k] q_w[k,n], exact, int64.
+
+    Computed as an fp64 matrix product: every partial sum is an integer below 127^2 K < 2^53, so fp64 holds it exactly
+    whatever the summation order (the test suite checks entries against Python integers).
+    """
+    assert qx.shape[1] * QMAX * QMAX < 2 ** 53
+    return np.rint(qx.astype(np.float64) @ qw.astype(np.float64)).astype(np.int64)
 
 
 def forward(x_bits: np.ndarray, prep: Dict[str, np.ndarray], lowrank: bool = True) -> Dict[str, np.ndarray]:
