@@ -231,7 +231,7 @@ def main():
                      "achieved": gemm_tops, "peak": FP4_MFMA_PEAK_TFLOPS if fp4 else INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
                      "note": ("FP4" if fp4 else "INT8") + " tera-ops/s: 2*M*N*K per launch / mean launch duration (HIP events on the launch stream)",
                      "frac": gemm_tops / (FP4_MFMA_PEAK_TFLOPS if fp4 else INT8_MFMA_PEAK_TOPS),
-                     "traffic": GEMM_TRAFFIC_BYTES if case.name == "flux_mlp_up" and not fp4 else None},
+                     "traffic": GEMM_TRAFFIC_BYTES if case.name == "flux_mlp_up" and args.format == "int4" else None},
     }
     if args.breakdown:
         naive = run(S.OPT_SKIP_LOWRANK, args.steps, 20, split=False)
