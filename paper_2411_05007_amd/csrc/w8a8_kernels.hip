@@ -401,20 +401,28 @@ hipError_t launch_debug_act_w8(const DebugActW8Params &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_w8a8(const GemmW8Params &p, hipStream_t stream) {
-    if (p.M <= 0) return hipSuccess;
-    using T = W8Tile<2, 4>;
-    // what the kernel's addressing assumes
-    if (p.K <= 0 || p.K % 64 || p.Mpad % kRowPad || p.Npad % kRowPad || p.Mpad < p.M || p.Npad < p.N || p.rank % 16 ||
-        (size_t)p.K * p.Mpad >= (size_t)1 << 31 || (size_t)p.K * p.Npad >= (size_t)1 << 31)
-        return hipErrorInvalidValue;
+template <int RB, int CB>
+static hipError_t launch_w8_tile(const GemmW8Params &p, hipStream_t stream) {
+    using T = W8Tile<RB, CB>;
     const int tiles_m = (p.M + T::kBM - 1) / T::kBM, tiles_n = (p.N + T::kBN - 1) / T::kBN;
+    // H, L2, the scales and the bias are read with plain loads: every tile must lie inside the padded rows and columns
     if (tiles_m * T::kBM > p.Mpad || tiles_n * T::kBN > p.Npad) return hipErrorInvalidValue;
-    auto k = gemm_w8a8_kernel<2, 4>;
+    auto k = gemm_w8a8_kernel<RB, CB>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k, dim3(tiles_m * tiles_n), dim3(256), T::kLdsBytes, stream, p);
     return hipGetLastError();
+}
+
+hipError_t launch_gemm_w8a8(const GemmW8Params &p, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    // what the kernel's addressing assumes
+    if (p.K <= 0 || p.K % 64 || p.Mpad % kRowPad || p.Npad % kRowPad || p.Mpad < p.M || p.Npad < p.N || p.rank % 16 ||
+        (size_t)p.K * p.Mpad >= (size_t)1 << 31 || (size_t)p.K * p.Npad >= (size_t)1 << 31)
+        return hipErrorInvalidValue;
+    // the tile shape follows the MXFP4 GEMM's rule (192 x 192 where it saves a round of workgroup places); no split K loop here
+    const GemmPlanFp4 plan = plan_gemm_fp4(p.M, p.N, p.K / kGroup, 1);
+    return plan.tile == 1 ? launch_w8_tile<3, 3>(p, stream) : launch_w8_tile<2, 4>(p, stream);
 }
 
 }  // namespace svdq
