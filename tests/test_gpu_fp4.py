@@ -236,3 +236,25 @@ def test_ragged_launch_on_the_192_tile(torch):
     prep = S.svdq_fp4_prepare(w, ax, r, bias=b)
     rows = np.unique(np.concatenate([np.arange(0, 3), rng.integers(0, M, 40), np.arange(190, 194), np.arange(M - 3, M)]))
     _run_and_compare(torch, xb, prep, rows=rows, what="fp4 192-tile ragged")
+
+
+def test_refined_layers_run_like_any_other(torch):
+    """Layers from svdq_prepare_refined (iterative update of the low-rank branch) in both 4-bit formats: same kernels,
+    same parity bar; the refined layer's output error against X W is not worse than the plain one's."""
+    from tests.test_gpu_parity import _run_and_compare as run_int4
+    rng = np.random.default_rng(2800)
+    M, K, N, r = 200, 512, 400, 32
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    full = O.bf16_to_f32(xb).astype(np.float64) @ w.astype(np.float64) + b
+    for fp4 in (True, False):
+        prep, errs, pick = S.svdq_prepare_refined(w, ax, r, 3, bias=b, fp4=fp4)
+        assert errs[pick] <= errs[0]
+        if fp4:
+            _run_and_compare(torch, xb, prep, what="fp4 refined")
+        else:
+            run_int4(torch, xb, prep, what="int4 refined")
+        plain = (S.svdq_fp4_prepare if fp4 else S.svdq_prepare)(w, ax, r, bias=b)
+        x = S.bf16_tensor_from_bits(xb)
+        y1 = O.bf16_to_f32(S.bits_from_bf16_tensor(S.DeviceLayer(prep).forward(x))).astype(np.float64)
+        y0 = O.bf16_to_f32(S.bits_from_bf16_tensor(S.DeviceLayer(plain).forward(x))).astype(np.float64)
+        assert np.linalg.norm(y1 - full) <= 1.03 * np.linalg.norm(y0 - full)

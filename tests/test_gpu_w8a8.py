@@ -144,3 +144,42 @@ def test_full_size_layers_on_sampled_rows(torch, name):
     rows = np.unique(np.concatenate([np.arange(0, 4), np.random.default_rng(5).integers(0, case.M, 24), np.arange(case.M - 4, case.M)]))
     _say(f"w8a8 {name}: M={case.M} K={case.K} N={case.N} r=16, {len(rows)} sampled rows")
     _run_and_compare(torch, L["x_bf16"], prep, rows=rows, what=f"w8a8 {name}")
+
+
+def test_lora_and_graph_replay(torch):
+    """An adapter appended to a W8A8 layer (the 16-bit branch is format-independent), and the three kernels of the
+    forward captured in a HIP graph and replayed with eager work in between: bit-equal to the eager result."""
+    rng = np.random.default_rng(3300)
+    M, K, N, r = 150, 512, 400, 16
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    down = (rng.standard_normal((K, 24)) * 0.05).astype(np.float32)
+    up = (rng.standard_normal((24, N)) * 0.05).astype(np.float32)
+    base = S.svdq_w8a8_prepare(w, ax, r, bias=b)
+    tuned = S.svdq_append_lora(base, down, up, scale=0.5)
+    assert tuned.shape.group == 0 and tuned.shape.rank == 48 and tuned.wcodes is base.wcodes
+    U0, U1 = S.svdq_w8a8_unpack(base), S.svdq_w8a8_unpack(tuned)
+    want = O.append_lora({"l1s": U0["l1s"], "l2": U0["l2"]}, down, up, scale=0.5)
+    assert np.array_equal(U1["l1s"], want["l1s"]) and np.array_equal(U1["l2"], want["l2"])
+    _run_and_compare(torch, xb, tuned, what="w8a8 + lora")
+    layer = S.DeviceLayer(tuned)
+    x = S.bf16_tensor_from_bits(xb)
+    ws = layer.workspace(M)
+    y_eager = S.bits_from_bf16_tensor(layer.forward(x, workspace=ws))
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        layer.forward(x, out=y, workspace=ws, stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            layer.forward(x, out=y, workspace=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(3):
+        y.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(S.bits_from_bf16_tensor(y), y_eager), f"replay {i}"
+        _ = layer.forward(x)
+        torch.cuda.synchronize()
