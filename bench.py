@@ -5,6 +5,9 @@ One "step" is one pass of the whole hot path - activation kernel (smooth + INT4 
 projection) and W4A4 GEMM (with up projection, bias and bf16 store) - over one batch of synthetic
 FLUX-MLP-shaped input (M=4608, K=3072, N=12288, r=32) already resident in HBM.
 
+`--format fp4` and `--format w8a8` time the MXFP4 variant and the 8-bit setting of the same layer instead (their GEMMs
+against the FP4 and INT8 MFMA peaks), `--lora R` appends an adapter first; the default line is the INT4 metric.
+
 Prints ONE JSON line with the headline metric (TOPS of the 4-bit branch, 2*M*N*K per layer time),
 the roofline of the dominant kernel (the GEMM, against the INT8 MFMA peak) measured live with HIP
 events on the stream the kernels run on, and the CPU oracle timed on a bounded row sample.

@@ -23,7 +23,7 @@ What each function follows
 * ``quantize_blocks``      Eq. (1) per block of 32 along K: codes = round_e2m1(x / s).
 * ``prepare`` / ``forward``  the INT4 oracle's steps with Q(.) replaced; Eq. (5).
 
-Readings (also listed in the design document): block = 32 consecutive elements along K for both
+Readings where the paper is silent: block = 32 consecutive elements along K for both
 operands; scale byte b encodes 2^(b - 127), clamped to [1, 254] (byte 0 is kept for the all-zero block, whose codes are 0);
 the sign of a zero code is immaterial (comparisons are made on decoded values); the 4-bit branch is
 evaluated as sum over blocks of 2^(ex + ew) * (sum of element products), element products being exact

@@ -29,7 +29,7 @@ What each function follows
 * ``forward``               Eq. (5): X^ L1 L2 (16-bit branch) + Q(X^) Q(R)
                             (4-bit branch, Eq. (2) per group), plus bias.
 
-Readings where the paper is silent (each is listed in the design document):
+Readings where the paper is silent:
 round = round-half-to-even; the scale is rounded to fp16 *before* it is used;
 codes come from x * (1.0f / s) with one correctly rounded reciprocal per group;
 codes are clamped to [-7, 7]; an all-zero group has scale 0 and codes 0; a scale
