@@ -240,6 +240,17 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *layer, const void *X, int M, v
 int svdq_fp4_debug_act(const svdq_layer_dev *layer, const void *workspace, int M,
                        uint8_t *out_codes, uint8_t *out_bx, float *out_H, void *hip_stream);
 
+/*
+ * W4A16 (App. "Implementation Details": the inputs of the linear layers in adaptive normalization stay 16-bit):
+ * the SAME prepared INT4 layer (shape.group = 64) applied to 16-bit activations,
+ *   Y = bf16( (X * 1/lambda) Q(R) + (X l1s) l2 + bias ),   Q(R) = wscales * codes,
+ * i.e. Eq. 5 without quantizing the activations.  Arguments, workspace (svdq_workspace_bytes), stream and errors as
+ * for svdq_linear_forward.  A weight-streaming kernel meant for the handful of rows these layers see; any M is
+ * accepted (eight rows per pass over the weights).  Enqueues two kernels (down projection, then this one).
+ */
+int svdq_w4a16_forward(const svdq_layer_dev *layer, const void *X, int M, void *Y,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------------
  * 8-bit setting (App. "Implementation Details": per-token dynamic activation quantization, per-channel
  * weight quantization, low-rank branch of rank 16 in the paper; any supported rank here).

@@ -24,6 +24,8 @@ What each function follows
 * ``lowrank_svd``           L1 = U Sigma[:, :r], L2 = V[:r, :] (Sec. 4.2, text
                             after Prop. 4.2; Eckart-Young).
 * ``prepare``               smoothing -> SVD -> residual -> per-group INT4.
+* ``forward_w4a16``         the same layer with 16-bit activations (W4A16, used for the
+                            adaptive-normalization layers; App. "Implementation Details").
 * ``refine_lowrank``        the iterative update of the low-rank branch (Sec. 4.2, end):
                             decompose W^ - Q(R), re-quantize, keep the best iterate.
 * ``forward``               Eq. (5): X^ L1 L2 (16-bit branch) + Q(X^) Q(R)
@@ -306,6 +308,26 @@ def forward(x_bits: np.ndarray, prep: Dict[str, np.ndarray], want_group_sums: bo
     if want_f64:
         out["Y64"] = Y64
     return out
+
+
+def forward_w4a16(x_bits: np.ndarray, prep: Dict[str, np.ndarray], lowrank: bool = True) -> Dict[str, np.ndarray]:
+    """The layer with 16-bit activations and the same 4-bit weights (App. "Implementation Details": the inputs of the
+    linear layers in adaptive normalization are kept in 16 bits, W4A16).
+
+    Y = X^ Q(R) + X L1s L2 + bias  with X^ = bf16(x) * (1/lambda) in fp32 and Q(R) = s_w * codes: Eq. (5) with Q(X^)
+    replaced by X^ itself.  Evaluated in fp64 and rounded once (``Y`` fp32, ``Y_bf16``).
+    """
+    x = bf16_to_f32(x_bits)
+    x_hat = (x * np.asarray(prep["rinv"], dtype=np.float32)[None, :]).astype(np.float32)
+    dq_w = np.repeat(prep["sw"].astype(np.float64), GROUP, axis=0) * prep["qw"].astype(np.float64)
+    Y64 = x_hat.astype(np.float64) @ dq_w
+    H = None
+    if lowrank and prep["l1s"].shape[1] > 0:
+        H = down_projection(x_bits, prep["l1s"], np.float32)
+        Y64 += down_projection(x_bits, prep["l1s"], np.float64) @ bf16_to_f32(prep["l2"]).astype(np.float64)
+    Y64 += prep["bias"][None, :].astype(np.float64)
+    Y = Y64.astype(np.float32)
+    return {"x_hat": x_hat, "H": H, "Y": Y, "Y64": Y64, "Y_bf16": bf16_round(Y)}
 
 
 # --------------------------------------------------------------------------

@@ -286,6 +286,53 @@ int svdq_fp4_debug_act(const svdq_layer_dev *L, const void *workspace, int M, ui
     return e == hipSuccess ? SVDQ_OK : hip_fail(e);
 }
 
+// ---- W4A16 -----------------------------------------------------------------------------------------------------
+
+int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
+                       size_t workspace_bytes, void *hip_stream) {
+    const int st = check_layer(L);
+    if (st != SVDQ_OK) return st;
+    if (M < 0) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    if (!X || !Y || !workspace) return SVDQ_EINVAL;
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
+    const svdq_shape &s = L->shape;
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
+    if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
+    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+        return SVDQ_EUNSUPPORTED;
+    if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
+        return SVDQ_EUNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
+    hipError_t e;
+    if (lowrank) {
+        svdq::ActParams a{};
+        a.X = static_cast<const uint16_t *>(X);
+        a.rinv = static_cast<const float *>(L->rinv);
+        a.l1s = static_cast<const uint16_t *>(L->l1s);
+        a.H = reinterpret_cast<float *>(ws + w.h_off);
+        a.hfrag = ws + w.hfrag_off;
+        a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
+        e = svdq::launch_act(a, 2, stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    svdq::W4A16Params q{};
+    q.X = static_cast<const uint16_t *>(X);
+    q.rinv = static_cast<const float *>(L->rinv);
+    q.wcodes = static_cast<const uint8_t *>(L->wcodes);
+    q.sw = static_cast<const uint16_t *>(L->wscales);
+    q.H = reinterpret_cast<const float *>(ws + w.h_off);
+    q.l2t = static_cast<const uint16_t *>(L->l2);
+    q.bias = static_cast<const float *>(L->bias);
+    q.Y = static_cast<uint16_t *>(Y);
+    q.M = M; q.N = s.N; q.K = s.K; q.Npad = svdq::round_up(s.N, svdq::kRowPad);
+    q.rank = lowrank ? s.rank : 0;
+    e = svdq::launch_w4a16(q, stream);
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
 // ---- 8-bit setting (W8A8) ---------------------------------------------------------------------------------------
 
 size_t svdq_w8a8_workspace_bytes(int M, const svdq_shape *s) {

@@ -93,6 +93,20 @@ struct GemmFp4Params {
 };
 hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream);
 
+// ---- W4A16: 16-bit activations, INT4 weights (small batches) ---------------------------------------------------
+struct W4A16Params {
+    const uint16_t *X;       // bf16 [M][K]
+    const float *rinv;       // fp32 [K]
+    const uint8_t *wcodes;   // [G][Npad][32]
+    const uint16_t *sw;      // fp16 [G][Npad]
+    const float *H;          // fp32 [Mpad][rank] (from the activation kernel in projection-only mode); unused when rank == 0
+    const uint16_t *l2t;     // bf16 [Npad][rank]
+    const float *bias;       // fp32 [Npad]
+    uint16_t *Y;             // bf16 [M][N]
+    int M, N, K, Npad, rank;
+};
+hipError_t launch_w4a16(const W4A16Params &p, hipStream_t stream);
+
 // ---- 8-bit setting -------------------------------------------------------------------------------------------
 struct Quant8Params {
     const uint16_t *X;       // bf16 [M][K]

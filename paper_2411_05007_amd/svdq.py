@@ -26,7 +26,7 @@ EXPORTS = [
     "svdq_fp4_prepared_sizes", "svdq_fp4_prepare", "svdq_fp4_pack", "svdq_fp4_unpack_wcodes", "svdq_fp4_unpack_wscales",
     "svdq_fp4_workspace_bytes", "svdq_fp4_linear_forward", "svdq_fp4_debug_act",
     "svdq_w8a8_prepared_sizes", "svdq_w8a8_prepare", "svdq_w8a8_pack", "svdq_w8a8_unpack_wcodes", "svdq_w8a8_unpack_wscales",
-    "svdq_w8a8_workspace_bytes", "svdq_w8a8_linear_forward", "svdq_w8a8_debug_act",
+    "svdq_w8a8_workspace_bytes", "svdq_w8a8_linear_forward", "svdq_w8a8_debug_act", "svdq_w4a16_forward",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
     "svdq_forward_options", "svdq_profile_event",
 ]
@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
             getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
         L.svdq_fp4_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_fp4_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
+        L.svdq_w4a16_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_w8a8_workspace_bytes.restype = C.c_size_t
         L.svdq_w8a8_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
         L.svdq_w8a8_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
@@ -394,6 +395,21 @@ class DeviceLayer:
         _check(getattr(lib(), name)(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
                                     workspace.numel(), s.cuda_stream), name)
         self._last_ws, self._last_M = workspace, M
+        return out
+
+    def forward_w4a16(self, x, out=None, workspace=None, stream=None):
+        """The INT4 layer applied to 16-bit activations (no activation quantization); small batches."""
+        torch = self.torch
+        assert not self.fp4 and not self.w8, "W4A16 uses a layer prepared for INT4 (group 64)"
+        assert x.dtype == torch.bfloat16 and x.is_contiguous() and x.shape[1] == self.K and x.is_cuda
+        M = x.shape[0]
+        if out is None:
+            out = torch.empty((M, self.N), dtype=torch.bfloat16, device=x.device)
+        if workspace is None:
+            workspace = self.workspace(M)
+        s = torch.cuda.current_stream(x.device) if stream is None else stream
+        _check(lib().svdq_w4a16_forward(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
+                                        workspace.numel(), s.cuda_stream), "svdq_w4a16_forward")
         return out
 
     def debug_act(self, workspace=None, M=None):

@@ -290,6 +290,23 @@ def test_fp4_forward_argument_errors(lib):
     assert lib.svdq_fp4_workspace_bytes(-1, C.byref(fake.shape)) == 0
 
 
+def test_w4a16_forward_argument_errors(lib):
+    """The 16-bit-activation entry point takes INT4 layers only and checks its arguments before touching the GPU."""
+    fake = S.LayerDev(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, S.make_shape(3072, 18432, 32))
+    fwd = lib.svdq_w4a16_forward
+    args = lambda M, ws_bytes: (C.byref(fake), C.c_void_p(0x1000), M, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(ws_bytes), None)
+    assert fwd(*args(-1, 1 << 40)) == -1
+    assert fwd(*args(0, 0)) == 0
+    assert fwd(*args(2, 1024)) == -4
+    assert fwd(C.byref(fake), None, 2, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1 << 40), None) == -1
+    assert fwd(C.byref(fake), C.c_void_p(0x1004), 2, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1 << 40), None) == -1
+    for group in (32, 0):                                  # MXFP4 and 8-bit layers
+        fake.shape = S.make_shape(3072, 18432, 32, group=group)
+        assert fwd(*args(2, 1 << 40)) == -2, group
+    fake.shape = S.make_shape(32768 + 64, 3072, 32)
+    assert fwd(*args(2, 1 << 62)) == -2
+
+
 @pytest.mark.parametrize("fp4", [False, True])
 def test_refined_prepare_against_the_oracle(lib, fp4):
     """The library's iterative update of the low-rank branch: same error measure as the oracle's, never worse than the

@@ -244,6 +244,34 @@ def test_iterative_update_of_the_lowrank_branch(fmt):
     assert np.linalg.norm(y1 - full) <= 1.02 * np.linalg.norm(y0 - full)
 
 
+def test_w4a16_forward_is_the_layer_without_activation_quantization():
+    """App. "Implementation Details": adaLN inputs stay 16-bit.  Pinned to the dense definition, to the W4A4 forward on
+    activations that quantize without error, and to the ordering of the errors."""
+    xb, w, b, ax = _small_layer(M=6, K=256, N=96, seed=41)
+    P = O.prepare(w, ax, rank=16, bias=b)
+    out = O.forward_w4a16(xb, P)
+    x = O.bf16_to_f32(xb).astype(np.float64)
+    xh = (O.bf16_to_f32(xb) * P["rinv"][None, :]).astype(np.float32).astype(np.float64)
+    dq_w = np.repeat(P["sw"].astype(np.float64), 64, axis=0) * P["qw"]
+    ref = xh @ dq_w + (x @ O.bf16_to_f32(P["l1s"]).astype(np.float64)) @ O.bf16_to_f32(P["l2"]).astype(np.float64) + b
+    assert np.linalg.norm(out["Y64"] - ref) / np.linalg.norm(ref) < 1e-13
+    # the weight side alone is in error: X^ (L1 L2 + Q(R)) against X^ W^ = X W
+    full = x @ w.astype(np.float64) + b
+    e16 = np.linalg.norm(out["Y64"] - full) / np.linalg.norm(full)
+    e4 = np.linalg.norm(O.forward(xb, P, want_f64=True)["Y64"] - full) / np.linalg.norm(full)
+    assert e16 < e4 and e16 < 0.1, (e16, e4)
+    # activations that the 4-bit quantizer reproduces exactly (codes times an fp16-exact scale, lambda = 1): both forwards agree
+    rng = np.random.default_rng(42)
+    codes = rng.integers(-7, 8, (4, 256)).astype(np.float32)
+    codes[:, ::64] = 7
+    xq = O.bf16_round(codes * np.float32(0.25))
+    P1 = dict(P)
+    P1["rinv"] = np.ones(256, np.float32)
+    a = O.forward_w4a16(xq, P1)["Y64"]
+    c = O.forward(xq, P1, want_f64=True)["Y64"]
+    assert np.linalg.norm(a - c) / np.linalg.norm(c) < 1e-12
+
+
 def test_forward_approximates_xw_and_error_identity():
     xb, w, b, ax = _small_layer(M=64, K=512, N=128, seed=8)
     r = 16
