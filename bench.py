@@ -90,6 +90,60 @@ def cpu_baseline(case, L, prep_canon, rows=768, fmt="int4"):
             "us_per_layer_extrapolated": best * case.M / rows * 1e6}
 
 
+def bench_w4a16(args, np, torch, S, hip):
+    """The W4A16 forward on a synthetic modulation layer: weight-stream bandwidth against the HBM roofline."""
+    from paper_2411_05007_amd import inputs as I
+    K, N, r, M = 3072, 18432, 32, args.w4a16
+    G = K // 64
+    rng = np.random.default_rng(241105016)
+    # the forward's speed does not depend on the values: seeded random codes and scales stand in for a prepared layer
+    # (preparing one needs an SVD of a 3072 x 18432 matrix on the host, which this mode does not time)
+    prep = S.svdq_pack((1.0 / (np.abs(rng.standard_normal(K)) + 0.5)).astype(np.float32),
+                       I.f32_to_bf16_bits((rng.standard_normal((K, r)) * 0.05).astype(np.float32)),
+                       I.f32_to_bf16_bits((rng.standard_normal((r, N)) * 0.05).astype(np.float32)),
+                       rng.integers(-8, 8, size=(K, N), dtype=np.int8),
+                       (np.abs(rng.standard_normal((G, N))) * 0.01 + 1e-3).astype(np.float16),
+                       bias=(rng.standard_normal(N) * 0.1).astype(np.float32))
+    nsets = 10                                           # 10 x 30 MB of weights rotate: past the 256 MB last-level cache
+    layers = [S.DeviceLayer(prep, "cuda:0") for _ in range(nsets)]
+    x = S.bf16_tensor_from_bits(I.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)), "cuda:0")
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
+    ws = layers[0].workspace(M)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    for i in range(args.warmup):
+        layers[i % nsets].forward_w4a16(x, out=y, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layers[i % nsets].forward_w4a16(x, out=y, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev = [(hip.event(), hip.event(), hip.event()) for _ in range(args.steps)]
+    for i, (a, m, b) in enumerate(ev):
+        S.svdq_profile_event(m.value)
+        hip.record(a, sh)
+        layers[i % nsets].forward_w4a16(x, out=y, workspace=ws, stream=stream)
+        hip.record(b, sh)
+    torch.cuda.synchronize()
+    S.svdq_profile_event(None)
+    proj_us = float(np.mean([hip.ms(a, m) for a, m, b in ev])) * 1e3
+    main_us = float(np.mean([hip.ms(m, b) for a, m, b in ev])) * 1e3
+    # algorithmic bytes of the weight-streaming kernel: codes, scales, L2 and bias once; X, H and Y are a few KB
+    nbytes = K * N // 2 + G * N * 2 + N * r * 2 + N * 4 + M * K * 2 + M * r * 4 + M * N * 2
+    gbs = nbytes / (main_us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": f"W4A16 linear (16-bit activations, INT4 weights + low-rank branch) us/layer, M={M} K={K} N={N} r={r}",
+        "value": ms * 1e3, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 codes widened to fp32, fp32 FMA and accumulate, bf16 out", "data": "synthetic",
+        "config": {"workload": f"FLUX.1 modulation linear: M={M} K={K} N={N} r={r} g=64, weights rotated over {nsets} copies"},
+        "kernels": {"projection_us": proj_us, "w4a16_us": main_us},
+        "roofline": {"bound": "hbm", "kernel": "w4a16_stream_kernel" if M <= 2 else "w4a16_kernel",
+                     "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +159,9 @@ def main():
                          "(per-token / per-channel INT8, rank 16)")
     ap.add_argument("--lora", type=int, default=0, metavar="R",
                     help="append a synthetic rank-R adapter to the layer's 16-bit branch (no re-quantization) and time that")
+    ap.add_argument("--w4a16", type=int, default=0, metavar="ROWS",
+                    help="time the 16-bit-activation forward (the adaptive-normalization linears) instead: ROWS conditioning "
+                         "rows through a FLUX.1 modulation layer, 3072 -> 18432, rank 32; a memory-bound side path, not the metric")
     ap.add_argument("--pmc-run", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a few forwards plus one plain copy of 256 MiB "
                          "(the known-size kernel the counters are scaled by), no timing, no JSON")
@@ -123,6 +180,9 @@ def main():
     S.lib()   # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
+    if args.w4a16 > 0:
+        bench_w4a16(args, np, torch, S, Hip())
+        return
     case = I.case_by_name(args.case)
     L = I.make_layer(case)
     fp4 = args.format == "fp4"

@@ -306,7 +306,7 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
-    hipError_t e;
+    hipError_t e = hipSuccess;
     if (lowrank) {
         svdq::ActParams a{};
         a.X = static_cast<const uint16_t *>(X);
@@ -316,6 +316,10 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
         a.hfrag = ws + w.hfrag_off;
         a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
         e = svdq::launch_act(a, 2, stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    if (void *ev = g_profile_event.load()) {
+        e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
         if (e != hipSuccess) return hip_fail(e);
     }
     svdq::W4A16Params q{};
