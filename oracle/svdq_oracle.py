@@ -28,6 +28,10 @@ What each function follows
                             adaptive-normalization layers; App. "Implementation Details").
 * ``refine_lowrank``        the iterative update of the low-rank branch (Sec. 4.2, end):
                             decompose W^ - Q(R), re-quantize, keep the best iterate.
+* ``gptq_quantize_residual``  the residual quantized with GPTQ instead of round-to-nearest (App.
+                            "Implementation Details"; the algorithm is Frantar et al. 2022, "GPTQ", Alg. 1:
+                            quantize input channels in order, spread each channel's error over the channels
+                            not yet quantized through the Cholesky factor of the inverse Hessian).
 * ``forward``               Eq. (5): X^ L1 L2 (16-bit branch) + Q(X^) Q(R)
                             (4-bit branch, Eq. (2) per group), plus bias.
 
@@ -185,9 +189,73 @@ def refine_lowrank(W, rinv, W_hat, rank, iterations, codes_from_factors, dequant
     return best[1], best[2], best[3], best[4], best[5], np.array(errors), best[6]
 
 
+# --------------------------------------------------------------------------
+# GPTQ on the residual (App. "Implementation Details")
+# --------------------------------------------------------------------------
+
+def gptq_hessian(x_cal: np.ndarray, rinv: np.ndarray) -> np.ndarray:
+    """H = X^^T X^ [K, K] of the smoothed calibration activations (fp64); X^ = x * (1/lambda) as at run time."""
+    xh = (np.asarray(x_cal, dtype=np.float32) * np.asarray(rinv, dtype=np.float32)[None, :]).astype(np.float64)
+    return xh.T @ xh
+
+
+def gptq_feedback(U: np.ndarray, k: int, e: np.ndarray) -> np.ndarray:
+    """What quantizing channel k with scaled error e [N] takes from the channels after it: U[k, k+1:] (x) e."""
+    return np.outer(U[k, k + 1:], e)
+
+
+def gptq_quantize_residual(R: np.ndarray, H: np.ndarray, damp: float = 0.01, stop_after: Optional[int] = None):
+    """Per-group INT4 of R [K, N] by GPTQ: minimises || X^ (R - Q(R)) ||_F greedily, one input channel at a time.
+
+    H = X^^T X^ (``gptq_hessian``); a channel the calibration set never excites (H_kk = 0) gets H_kk = 1 and weights
+    0; ``damp`` times the mean diagonal is added to the diagonal.  With U the upper Cholesky factor of H^-1
+    (H^-1 = U^T U), channel k is quantized by Eq. (1) with its group's scale, and
+    (R_k - Q(R_k)) / U_kk times U[k, k+1:] is subtracted from the later channels, which is their optimal adjustment
+    given the channels fixed so far.  A group's fp16 scale is taken, as in Eq. (1), from the group's 64 rows as
+    they stand when its first channel is reached.  ``stop_after`` = number of channels to process (for the pins).
+    Returns (codes int8 [K, N], scales fp16 [G, N], the working copy of R with every processed row's adjustments).
+    """
+    Rc = np.array(R, dtype=np.float64)
+    K, N = Rc.shape
+    assert K % GROUP == 0 and H.shape == (K, K)
+    Hd = np.array(H, dtype=np.float64)
+    idx = np.arange(K)
+    dead = Hd[idx, idx] == 0
+    Hd[idx[dead], idx[dead]] = 1.0
+    Rc[dead, :] = 0.0
+    Hd[idx, idx] += damp * np.mean(Hd[idx, idx])
+    U = np.linalg.cholesky(np.linalg.inv(Hd)).T                     # upper triangular, H^-1 = U^T U
+    q = np.zeros((K, N), dtype=np.int8)
+    sw = np.zeros((K // GROUP, N), dtype=np.float16)
+    for k in range(K if stop_after is None else stop_after):
+        g = k // GROUP
+        if k % GROUP == 0:
+            _, s_t = quantize_groups(np.ascontiguousarray(Rc[k:k + GROUP, :].astype(np.float32).T))     # [N, 1]
+            sw[g] = s_t[:, 0]
+        s = sw[g].astype(np.float32)
+        with np.errstate(divide="ignore"):
+            rcp = np.where(s > 0, np.float32(1.0) / s, np.float32(0.0)).astype(np.float32)
+        y = (Rc[k, :].astype(np.float32) * rcp).astype(np.float32)
+        q[k] = np.clip(np.rint(y), -QMAX, QMAX).astype(np.int8)
+        e = (Rc[k, :] - s.astype(np.float64) * q[k].astype(np.float64)) / U[k, k]
+        Rc[k + 1:, :] -= gptq_feedback(U, k, e)
+    return q, sw, Rc
+
+
+def gptq_objective(R: np.ndarray, D: np.ndarray, H: np.ndarray) -> float:
+    """|| X^ (R - D) ||_F^2 = tr((R - D)^T H (R - D)) for the undamped H."""
+    E = np.asarray(R, dtype=np.float64) - np.asarray(D, dtype=np.float64)
+    return float(np.sum(E * (np.asarray(H, dtype=np.float64) @ E)))
+
+
 def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
-            bias: Optional[np.ndarray] = None, refine_iters: int = 0) -> Dict[str, np.ndarray]:
-    """Offline quantization of one layer.  W fp32 [K, N], x_absmax fp32 [K]."""
+            bias: Optional[np.ndarray] = None, refine_iters: int = 0,
+            gptq_x: Optional[np.ndarray] = None, gptq_damp: float = 0.01) -> Dict[str, np.ndarray]:
+    """Offline quantization of one layer.  W fp32 [K, N], x_absmax fp32 [K].
+
+    ``gptq_x`` (calibration activations fp32 [Mc, K], unsmoothed): quantize the residual with GPTQ instead of
+    round-to-nearest.
+    """
     W = np.asarray(W, dtype=np.float32)
     K, N = W.shape
     assert K % GROUP == 0 and 0 <= rank <= min(K, N)
@@ -211,6 +279,8 @@ def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
             l1s_bits = np.zeros((K, 0), dtype=np.uint16)
             l2_bits = np.zeros((0, N), dtype=np.uint16)
         qw, sw, R = residual_codes_from_factors(W, rinv, l1s_bits, l2_bits)
+    if gptq_x is not None:
+        qw, sw, _ = gptq_quantize_residual(R, gptq_hessian(gptq_x, rinv), gptq_damp)
     b = np.zeros(N, dtype=np.float32) if bias is None else np.asarray(bias, dtype=np.float32)
     return {"rinv": rinv, "lam": lam_eff, "l1s": l1s_bits, "l2": l2_bits, "qw": qw, "sw": sw,
             "bias": b, "R": R, "W_hat": W_hat, "sigma": S, **extra}

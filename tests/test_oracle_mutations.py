@@ -9,6 +9,7 @@ import pytest
 from oracle import svdq_oracle as O
 import tests.test_oracle_layer as TL
 import tests.test_oracle_quantizer as TQ
+import tests.test_oracle_gptq as TG
 
 
 def _must_fail(fn):
@@ -126,3 +127,22 @@ def test_w8a8_mistakes_are_caught(monkeypatch):
     # weights quantized per input channel (rows of R) instead of per output channel
     monkeypatch.setattr(W8, "quantize_residual", lambda R: (lambda q, s: (q, np.resize(s, R.shape[1])))(*real(np.asarray(R, np.float64).astype(np.float32))))
     _must_fail(TW.test_forward_equals_the_dense_definition_and_integer_sums_are_exact)
+
+
+def test_gptq_mistakes_are_caught(monkeypatch):
+    real = O.gptq_feedback
+    for bad in (lambda U, k, e: -real(U, k, e),                                  # error pushed the wrong way
+                lambda U, k, e: np.outer(U[k + 1:, k], e),                       # the factor's other triangle: no feedback at all
+                lambda U, k, e: np.outer(U[k, k + 1:] / U[k, k], e)):            # divided by the diagonal twice
+        monkeypatch.setattr(O, "gptq_feedback", bad)
+        _must_fail(TG.test_remaining_rows_are_the_least_squares_optimum_given_the_fixed_ones)
+    for bad in (lambda U, k, e: -real(U, k, e), lambda U, k, e: np.outer(U[k + 1:, k], e)):
+        monkeypatch.setattr(O, "gptq_feedback", bad)
+        _must_fail(TG.test_objective_drops_below_round_to_nearest_and_so_does_the_layer_error)
+    monkeypatch.setattr(O, "gptq_feedback", real)
+    # the Hessian of the unsmoothed activations
+    real_h = O.gptq_hessian
+    monkeypatch.setattr(O, "gptq_hessian", lambda x, rinv: real_h(x, np.ones_like(rinv)))
+    _must_fail(TG.test_objective_drops_below_round_to_nearest_and_so_does_the_layer_error)
+    monkeypatch.setattr(O, "gptq_hessian", real_h)
+    TG.test_remaining_rows_are_the_least_squares_optimum_given_the_fixed_ones()
