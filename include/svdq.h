@@ -100,6 +100,24 @@ int svdq_prepare_refined(const svdq_shape *shape, const float *W, const float *x
                          double *out_errors, int *out_pick);
 
 /*
+ * svdq_prepare with the residual quantized by GPTQ instead of round-to-nearest (App. "Implementation Details": GPTQ is
+ * used for the residual weights; the algorithm is Frantar et al. 2022, Alg. 1).  Smoothing, the rank-r split and the
+ * residual are svdq_prepare's; then, with H = X^^T X^ of the smoothed calibration activations, the input channels
+ * are quantized in order (Eq. 1 per group of 64, the group's fp16 scale taken from the group as it stands when its
+ * first channel is reached) and each channel's error is spread over the later channels through the upper Cholesky
+ * factor of H^-1, which minimises || X^ (R - Q(R)) ||_F greedily.  INT4 layers only (shape.group = 64).
+ *   x_cal          host, fp32 [Mc][K] row-major: calibration activations of this layer, unsmoothed
+ *   damp           >= 0: this fraction of the mean diagonal of H is added to its diagonal (0.01 is customary);
+ *                  a channel that x_cal never excites gets H_kk = 1 and zero codes
+ *   out_objective  host, 2 doubles or NULL: || X^ (R - Q(R)) ||_F^2 for round-to-nearest and for the packed codes
+ * Outputs as for svdq_prepare.  Cost: O(K^3 + Mc K^2 + K^2 N) fp64 operations and three K x K fp64 matrices on the host.
+ * Errors: as svdq_prepare; SVDQ_EUNSUPPORTED also if H + damping is not positive definite (raise `damp`).
+ */
+int svdq_prepare_gptq(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                      const float *x_cal, int Mc, float damp, float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2,
+                      uint8_t *out_wcodes, uint16_t *out_wscales, float *out_bias, double *out_objective);
+
+/*
  * Pack an externally quantized layer (canonical forms, all HOST) into native buffers:
  *   rinv fp32 [K]; l1s bf16 [K x rank]; l2 bf16 [rank x N]; qw int8 [K x N] codes in [-7, 7];
  *   sw fp16 [G x N]; bias fp32 [N] or NULL.

@@ -513,6 +513,141 @@ double quantize_residual(const svdq_shape *shape, const SplitLayer &sl, std::vec
     return total;
 }
 
+// ---- GPTQ on the residual (App. "Implementation Details"; Frantar et al. 2022, "GPTQ", Alg. 1) ---------------------
+// Input channels are quantized in order; each channel's error, scaled by the diagonal of the upper Cholesky factor
+// U of the inverse Hessian (H^-1 = U^T U), is spread over the channels after it along that factor's row, which leaves
+// them at their least-squares optimum given the channels fixed so far.
+
+// fp16 scale of Eq. 1 for one group of 64 values (stride `stride` apart)
+inline uint16_t group_scale(const double *v, size_t stride) {
+    float amax = 0.0f;
+    for (int i = 0; i < kGroup; ++i) amax = std::max(amax, std::fabs((float)v[i * stride]));
+    float s32 = amax / 7.0f;
+    if (!(s32 <= 65504.0f)) s32 = 65504.0f;
+    return f32_to_f16(s32);
+}
+
+// U [K x K] row-major, upper triangular with H^-1 = U^T U, from the symmetric positive definite H [K x K] (destroyed).
+// With P the reversal of the channel order and P H P = L L^T (L lower), H^-1 = (P L^-1 P)^T (P L^-1 P) and P L^-1 P
+// is upper triangular with a positive diagonal, hence U: one Cholesky factorization and one triangular inverse.
+// Returns false if H is not positive definite.
+bool inverse_cholesky_upper(std::vector<double> &H, int K, std::vector<double> &U) {
+    std::vector<double> &L = H;                       // in place: L[i][j] for j <= i holds the factor of the reversed matrix
+    for (int i = 0; i < K / 2; ++i)                   // reverse rows and columns
+        for (int j = 0; j < K; ++j) std::swap(L[(size_t)i * K + j], L[(size_t)(K - 1 - i) * K + (K - 1 - j)]);
+    if (K % 2) {
+        double *mid = L.data() + (size_t)(K / 2) * K;
+        for (int j = 0; j < K / 2; ++j) std::swap(mid[j], mid[K - 1 - j]);
+    }
+    for (int j = 0; j < K; ++j) {                     // left-looking Cholesky, column by column
+        double *Lj = L.data() + (size_t)j * K;
+        double d = Lj[j];
+        for (int p = 0; p < j; ++p) d -= Lj[p] * Lj[p];
+        if (!(d > 0.0) || !std::isfinite(d)) return false;
+        const double piv = std::sqrt(d);
+        Lj[j] = piv;
+        parallel_for((size_t)(K - j - 1), [&](size_t a, size_t b, int) {
+            for (size_t i = j + 1 + a; i < j + 1 + b; ++i) {
+                double *Li = L.data() + i * K;
+                double v = Li[j];
+                for (int p = 0; p < j; ++p) v -= Li[p] * Lj[p];
+                Li[j] = v / piv;
+            }
+        });
+    }
+    U.assign((size_t)K * K, 0.0);
+    parallel_for((size_t)K, [&](size_t c0, size_t c1, int) {      // column c of L^-1 by forward substitution
+        std::vector<double> x(K);
+        for (size_t c = c0; c < c1; ++c) {
+            x[c] = 1.0 / L[c * K + c];
+            for (size_t i = c + 1; i < (size_t)K; ++i) {
+                const double *Li = L.data() + i * K;
+                double v = 0.0;
+                for (size_t p = c; p < i; ++p) v += Li[p] * x[p];
+                x[i] = -v / Li[i];
+            }
+            for (size_t i = c; i < (size_t)K; ++i) U[(K - 1 - i) * (size_t)K + (K - 1 - c)] = x[i];
+        }
+    });
+    return true;
+}
+
+// Quantizes R [K x N] (fp64, destroyed: it ends as the working copy with every adjustment) into qw / sw by GPTQ with
+// the factor U.  Columns are independent, so inside a group of 64 channels each thread walks its own columns; the
+// adjustment of the rows after the group is applied once per group (the same sums in a different order).
+void gptq_quantize(int K, int N, std::vector<double> &R, const std::vector<double> &U, const std::vector<uint8_t> &dead,
+                   std::vector<int8_t> &qw, std::vector<uint16_t> &sw) {
+    const int G = K / kGroup;
+    qw.assign((size_t)K * N, 0);
+    sw.assign((size_t)G * N, 0);
+    for (int k = 0; k < K; ++k)
+        if (dead[k]) std::fill(R.begin() + (size_t)k * N, R.begin() + (size_t)(k + 1) * N, 0.0);
+    std::vector<double> Err((size_t)kGroup * N);
+    for (int g = 0; g < G; ++g) {
+        const size_t k0 = (size_t)g * kGroup;
+        parallel_for((size_t)N, [&](size_t n0, size_t n1, int) {
+            for (size_t n = n0; n < n1; ++n) {
+                const uint16_t s16 = group_scale(R.data() + k0 * N + n, (size_t)N);
+                sw[(size_t)g * N + n] = s16;
+                const float s = f16_to_f32(s16);
+                const float rcp = s > 0.0f ? 1.0f / s : 0.0f;
+                for (int kk = 0; kk < kGroup; ++kk) {
+                    const size_t k = k0 + kk;
+                    const double w = R[k * N + n];
+                    float q = std::nearbyintf((float)w * rcp);
+                    q = std::min(7.0f, std::max(-7.0f, q));
+                    qw[k * N + n] = (int8_t)q;
+                    const double *Uk = U.data() + k * K;
+                    const double e = (w - (double)s * (double)q) / Uk[k];
+                    Err[(size_t)kk * N + n] = e;
+                    for (int k2 = kk + 1; k2 < kGroup; ++k2) R[(k0 + k2) * N + n] -= Uk[k0 + k2] * e;
+                }
+            }
+        });
+        const size_t later = (size_t)K - (k0 + kGroup);
+        parallel_for(later, [&](size_t a, size_t b, int) {
+            for (size_t k2 = k0 + kGroup + a; k2 < k0 + kGroup + b; ++k2) {
+                double *row = R.data() + k2 * N;
+                for (int kk = 0; kk < kGroup; ++kk) {
+                    const double c = U[(k0 + kk) * K + k2];
+                    const double *e = Err.data() + (size_t)kk * N;
+                    for (int n = 0; n < N; ++n) row[n] -= c * e[n];
+                }
+            }
+        });
+    }
+}
+
+// || X^ (R - Q(R)) ||_F^2 with X^ [Mc x K] row-major fp64
+double gptq_objective(const std::vector<double> &Xh, int Mc, int K, int N, const std::vector<double> &R,
+                      const std::vector<int8_t> &qw, const std::vector<uint16_t> &sw) {
+    std::vector<double> E((size_t)K * N);
+    parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
+        for (size_t k = k0; k < k1; ++k)
+            for (int n = 0; n < N; ++n)
+                E[k * N + n] = R[k * N + n] - (double)f16_to_f32(sw[(k / kGroup) * N + n]) * (double)qw[k * N + n];
+    });
+    std::vector<double> part((size_t)Mc, 0.0);
+    parallel_for((size_t)Mc, [&](size_t m0, size_t m1, int) {
+        std::vector<double> y(N);
+        for (size_t m = m0; m < m1; ++m) {
+            std::fill(y.begin(), y.end(), 0.0);
+            for (int k = 0; k < K; ++k) {
+                const double a = Xh[m * K + k];
+                if (a == 0.0) continue;
+                const double *e = E.data() + (size_t)k * N;
+                for (int n = 0; n < N; ++n) y[n] += a * e[n];
+            }
+            double t = 0.0;
+            for (int n = 0; n < N; ++n) t += y[n] * y[n];
+            part[m] = t;
+        }
+    });
+    double total = 0.0;
+    for (double t : part) total += t;                  // fixed order: independent of the thread count
+    return total;
+}
+
 // factors, smoothing reciprocals and bias into their native places (the same for both formats)
 void pack_common(const svdq_shape *sh, const float *rinv, const uint16_t *l1s, const uint16_t *l2, const float *bias,
                  float *o_rinv, uint16_t *o_l1s, uint16_t *o_l2, float *o_bias) {
@@ -671,6 +806,82 @@ int svdq_prepare_refined(const svdq_shape *shape, const float *W, const float *x
 }
 
 // ---- MXFP4 variant ------------------------------------------------------------------------------------
+int svdq_prepare_gptq(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
+                      const float *x_cal, int Mc, float damp, float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2,
+                      uint8_t *out_wcodes, uint16_t *out_wscales, float *out_bias, double *out_objective) {
+    const int st = check_shape(shape);
+    if (st != SVDQ_OK) return st;
+    if (!W || !x_absmax || !x_cal || Mc <= 0 || !(damp >= 0.0f) || !std::isfinite(damp) || !out_rinv || !out_l1s || !out_l2 ||
+        !out_wcodes || !out_wscales || !out_bias)
+        return SVDQ_EINVAL;
+    const int K = shape->K, N = shape->N, G = K / kGroup;
+    try {
+        SplitLayer sl;
+        split_layer(shape, W, x_absmax, sl);
+        // the residual against the stored factors, in fp64
+        std::vector<double> R((size_t)K * N);
+        parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
+            std::vector<float> Rg((size_t)kGroup * N);
+            std::vector<double> prow(N);
+            for (size_t g = g0; g < g1; ++g) residual_rows(shape, sl, g, Rg, prow, R.data() + g * kGroup * N);
+        });
+        // smoothed calibration activations as the run time forms them (one fp32 multiply), and H = X^^T X^
+        std::vector<double> Xh((size_t)Mc * K), Xt((size_t)K * Mc);
+        parallel_for((size_t)Mc, [&](size_t m0, size_t m1, int) {
+            for (size_t m = m0; m < m1; ++m)
+                for (int k = 0; k < K; ++k) {
+                    const double v = (double)(x_cal[m * K + k] * sl.rinv[k]);
+                    Xh[m * K + k] = v;
+                    Xt[(size_t)k * Mc + m] = v;
+                }
+        });
+        std::vector<double> H((size_t)K * K);
+        parallel_for((size_t)K, [&](size_t i0, size_t i1, int) {
+            for (size_t ii = i0; ii < i1; ++ii) {
+                // interleave long and short rows of the triangle so that the threads' shares are even
+                const size_t i = (ii % 2 == 0) ? ii / 2 : (size_t)K - 1 - ii / 2;
+                const double *a = Xt.data() + i * Mc;
+                for (size_t j = i; j < (size_t)K; ++j) {
+                    const double *b = Xt.data() + j * Mc;
+                    double t = 0.0;
+                    for (int m = 0; m < Mc; ++m) t += a[m] * b[m];
+                    H[i * K + j] = t;
+                    H[j * K + i] = t;
+                }
+            }
+        });
+        std::vector<double>().swap(Xt);
+        std::vector<uint8_t> dead(K, 0);
+        double mean = 0.0;
+        for (int k = 0; k < K; ++k) {
+            if (H[(size_t)k * K + k] == 0.0) { dead[k] = 1; H[(size_t)k * K + k] = 1.0; }
+            mean += H[(size_t)k * K + k];
+        }
+        mean /= K;
+        for (int k = 0; k < K; ++k) H[(size_t)k * K + k] += (double)damp * mean;
+        std::vector<double> U;
+        if (!inverse_cholesky_upper(H, K, U)) return SVDQ_EUNSUPPORTED;      // not positive definite: raise `damp`
+        std::vector<double>().swap(H);
+        std::vector<int8_t> qw;
+        std::vector<uint16_t> sw;
+        if (out_objective) {
+            std::vector<int8_t> q0;
+            std::vector<uint16_t> s0;
+            quantize_residual(shape, sl, q0, s0, nullptr);                   // round-to-nearest, for comparison
+            out_objective[0] = gptq_objective(Xh, Mc, K, N, R, q0, s0);
+        }
+        std::vector<double> Rc = R;
+        gptq_quantize(K, N, Rc, U, dead, qw, sw);
+        std::vector<double>().swap(Rc);
+        if (out_objective) out_objective[1] = gptq_objective(Xh, Mc, K, N, R, qw, sw);
+        pack_native(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), qw.data(), sw.data(), bias, out_rinv, out_l1s, out_l2,
+                    out_wcodes, out_wscales, out_bias);
+    } catch (const std::bad_alloc &) {
+        return SVDQ_ENOMEM;
+    }
+    return SVDQ_OK;
+}
+
 int svdq_fp4_prepared_sizes(const svdq_shape *shape, svdq_sizes *out) {
     if (!out) return SVDQ_EINVAL;
     const int st = check_shape(shape, svdq::kFp4Block);

@@ -22,7 +22,7 @@ OPT_TILE_SHIFT = 8
 
 EXPORTS = [
     "svdq_status_string", "svdq_last_hip_error", "svdq_prepared_sizes", "svdq_prepare", "svdq_pack",
-    "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2", "svdq_append_lora", "svdq_prepare_refined",
+    "svdq_unpack_wcodes", "svdq_unpack_wscales", "svdq_unpack_l1s", "svdq_unpack_l2", "svdq_append_lora", "svdq_prepare_refined", "svdq_prepare_gptq",
     "svdq_fp4_prepared_sizes", "svdq_fp4_prepare", "svdq_fp4_pack", "svdq_fp4_unpack_wcodes", "svdq_fp4_unpack_wscales",
     "svdq_fp4_workspace_bytes", "svdq_fp4_linear_forward", "svdq_fp4_debug_act",
     "svdq_w8a8_prepared_sizes", "svdq_w8a8_prepare", "svdq_w8a8_pack", "svdq_w8a8_unpack_wcodes", "svdq_w8a8_unpack_wscales",
@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
             getattr(L, n).argtypes = [C.POINTER(Shape), vp, vp]
         L.svdq_append_lora.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.c_int, C.c_float, C.POINTER(Shape), vp, vp]
         L.svdq_prepare_refined.argtypes = [C.POINTER(Shape), vp, vp, vp, C.c_int] + [vp] * 8
+        L.svdq_prepare_gptq.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.c_int, C.c_float] + [vp] * 7
         L.svdq_fp4_workspace_bytes.restype = C.c_size_t
         L.svdq_fp4_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
         L.svdq_fp4_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
@@ -220,6 +221,25 @@ def svdq_prepare_refined(W: np.ndarray, x_absmax: np.ndarray, rank: int, iterati
                                       _ptr(out.l1s), _ptr(out.l2), _ptr(out.wcodes), _ptr(out.wscales), _ptr(out.bias),
                                       _ptr(errors), C.byref(pick)), "svdq_prepare_refined")
     return out, errors, pick.value
+
+
+def svdq_prepare_gptq(W: np.ndarray, x_absmax: np.ndarray, rank: int, x_cal: np.ndarray, damp: float = 0.01,
+                      alpha: float = 0.5, bias: Optional[np.ndarray] = None):
+    """Prepare an INT4 layer with the residual quantized by GPTQ on calibration activations x_cal fp32 [Mc, K].
+    Returns (PreparedHost, (objective of round-to-nearest, objective of the packed codes))."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    K, N = W.shape
+    x_absmax = np.ascontiguousarray(x_absmax, dtype=np.float32)
+    x_cal = np.ascontiguousarray(x_cal, dtype=np.float32)
+    assert x_absmax.shape == (K,) and x_cal.ndim == 2 and x_cal.shape[1] == K
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    shape = make_shape(K, N, rank, alpha)
+    out = _alloc_prepared(shape)
+    objective = np.zeros(2, np.float64)
+    _check(lib().svdq_prepare_gptq(C.byref(shape), _ptr(W), _ptr(x_absmax), _ptr(b), _ptr(x_cal), int(x_cal.shape[0]),
+                                   float(damp), _ptr(out.rinv), _ptr(out.l1s), _ptr(out.l2), _ptr(out.wcodes),
+                                   _ptr(out.wscales), _ptr(out.bias), _ptr(objective)), "svdq_prepare_gptq")
+    return out, (float(objective[0]), float(objective[1]))
 
 
 def svdq_fp4_prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,

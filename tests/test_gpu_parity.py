@@ -129,6 +129,42 @@ def test_ragged_shapes(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"ragged {M}x{K}x{N} r{r}", window=M >= 3 and N >= 16)
 
 
+def test_gptq_prepared_layer_runs_the_same_path_and_lowers_the_output_error(torch):
+    """App. "Implementation Details": the residual quantized with GPTQ.  Only the offline codes change, so the forward
+    must match the oracle's forward of the same codes like any other layer; and on the tokens the Hessian was built
+    from, the GPU output must be closer to X W than the round-to-nearest layer's."""
+    rng = np.random.default_rng(9100)
+    M, K, N, r = 384, 256, 400, 16
+    z = rng.standard_normal((M, 8))
+    x = (0.9 * (z @ rng.standard_normal((8, K))) + 0.1 * rng.standard_normal((M, K))).astype(np.float32)
+    x[:, rng.choice(K, 3, replace=False)] *= 20
+    xb = O.bf16_round(x)
+    xf = O.bf16_to_f32(xb)
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    ax = np.abs(xf).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    rtn = S.svdq_prepare(w, ax, r, bias=b)
+    gq, (o_rtn, o_gq) = S.svdq_prepare_gptq(w, ax, r, xf, bias=b)
+    _say(f"gptq: objective {o_gq:.4e} vs round-to-nearest {o_rtn:.4e}")
+    assert o_gq < 0.5 * o_rtn
+    _run_and_compare(torch, xb, gq, what="gptq-prepared layer")
+    xt = S.bf16_tensor_from_bits(xb)
+    ref = xf.astype(np.float64) @ w.astype(np.float64) + b[None, :].astype(np.float64)
+    err = []
+    for prep in (rtn, gq):
+        y = O.bf16_to_f32(S.bits_from_bf16_tensor(S.DeviceLayer(prep).forward(xt))).astype(np.float64)
+        err.append(np.linalg.norm(y - ref) / np.linalg.norm(ref))
+    _say(f"gptq: relative output error {err[1]:.4e} vs round-to-nearest {err[0]:.4e}")
+    assert err[1] < err[0]
+    # with 16-bit activations only the weight quantizer is left in the error, and the gap is wide
+    err16 = []
+    for prep in (rtn, gq):
+        y = O.bf16_to_f32(S.bits_from_bf16_tensor(S.DeviceLayer(prep).forward_w4a16(xt))).astype(np.float64)
+        err16.append(np.linalg.norm(y - ref) / np.linalg.norm(ref))
+    _say(f"gptq: W4A16 relative output error {err16[1]:.4e} vs round-to-nearest {err16[0]:.4e}")
+    assert err16[1] < 0.5 * err16[0]
+
+
 @pytest.mark.parametrize("r,r_add", [(32, 16), (16, 5), (0, 32), (32, 96)])
 def test_lora_appended_without_requantization(torch, r, r_add):
     """Sec. 5.2, "Integrate with LoRA": the adapter joins the 16-bit branch (rank r + r_add, padded to 16); the

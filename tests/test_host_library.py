@@ -290,6 +290,49 @@ def test_fp4_forward_argument_errors(lib):
     assert lib.svdq_fp4_workspace_bytes(-1, C.byref(fake.shape)) == 0
 
 
+def test_gptq_prepare_against_the_oracle(lib):
+    """svdq_prepare_gptq: the same factors and residual as svdq_prepare; the codes are the oracle's GPTQ codes given
+    those factors, up to the handful of rounding ties that two fp64 evaluation orders of the same sums decide
+    differently (the library applies a group's feedback to the later rows once per group, the oracle row by row),
+    and the objective it reports is the oracle's."""
+    from tests.test_oracle_gptq import _calibration, _dequant
+    rng = np.random.default_rng(77)
+    K, N, r, Mc = 256, 144, 16, 384
+    x = _calibration(rng, Mc, K)
+    x[:, 5] = 0.0                                          # a channel the calibration set never excites
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 2, replace=False)] *= 20
+    ax = np.maximum(np.abs(x).max(axis=0), 1e-3).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    prep, (o_rtn, o_gptq) = S.svdq_prepare_gptq(w, ax, r, x, damp=0.01, bias=b)
+    plain = S.svdq_prepare(w, ax, r, bias=b)
+    U, U0 = S.svdq_unpack(prep), S.svdq_unpack(plain)
+    for key in ("rinv", "l1s", "l2", "bias"):
+        assert np.array_equal(U[key], U0[key]), key
+    R = O.residual(w, 1.0 / U["rinv"].astype(np.float64), U["l1s"], U["l2"])
+    H = O.gptq_hessian(x, U["rinv"])
+    q, sw, _ = O.gptq_quantize_residual(R, H, damp=0.01)
+    same = np.mean(U["qw"] == q)
+    assert same >= 0.999, same
+    assert np.mean(U["sw"].view(np.uint16) == sw.view(np.uint16)) >= 0.999
+    assert np.all(U["qw"][5] == 0)
+    want_rtn = O.gptq_objective(R, _dequant(U0["qw"], U0["sw"]), H)
+    want = O.gptq_objective(R, _dequant(q, sw), H)
+    got = O.gptq_objective(R, _dequant(U["qw"], U["sw"]), H)
+    assert np.isclose(o_rtn, want_rtn, rtol=1e-9) and np.isclose(o_gptq, got, rtol=1e-9)
+    assert np.isclose(got, want, rtol=1e-3) and o_gptq < 0.05 * o_rtn, (got, want, o_rtn)
+    # identity-like Hessian (orthogonal calibration rows): exactly svdq_prepare's codes
+    eye = np.eye(K, dtype=np.float32) / U["rinv"][None, :]
+    ident, _ = S.svdq_prepare_gptq(w, ax, r, eye, damp=0.0, bias=b)
+    Ui = S.svdq_unpack(ident)
+    assert np.mean(Ui["qw"] == U0["qw"]) >= 0.9999 and np.array_equal(Ui["sw"].view(np.uint16), U0["sw"].view(np.uint16))
+    # argument errors
+    with pytest.raises(S.SvdqError):
+        S.svdq_prepare_gptq(w, ax, r, x, damp=-1.0)
+    sh = S.make_shape(K, N, r, group=32)
+    assert lib.svdq_prepare_gptq(C.byref(sh), None, None, None, None, 1, C.c_float(0.01), *([None] * 7)) == -2
+
+
 def test_w4a16_forward_argument_errors(lib):
     """The 16-bit-activation entry point takes INT4 layers only and checks its arguments before touching the GPU."""
     fake = S.LayerDev(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, S.make_shape(3072, 18432, 32))
