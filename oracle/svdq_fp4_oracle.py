@@ -21,6 +21,7 @@ What each function follows
                            of two that is >= max|x| / 6, so that, as in Eq. (1), no element of the block
                            leaves the representable range.
 * ``quantize_blocks``      Eq. (1) per block of 32 along K: codes = round_e2m1(x / s).
+* ``gptq_quantize_residual``  GPTQ on the residual with this quantizer (App. "Implementation Details").
 * ``prepare`` / ``forward``  the INT4 oracle's steps with Q(.) replaced; Eq. (5).
 
 Readings where the paper is silent: block = 32 consecutive elements along K for both
@@ -110,8 +111,32 @@ def residual_codes_from_factors(W, rinv, l1s_bits, l2_bits):
     return qw, bw, R
 
 
+def gptq_quantize_residual(R: np.ndarray, H: np.ndarray, damp: float = 0.01, stop_after: Optional[int] = None):
+    """GPTQ (see ``svdq_oracle.gptq_quantize_residual``) with the MXFP4 quantizer: a block's scale byte is taken from
+    the block's 32 rows as they stand when its first channel is reached; channel k is rounded to E2M1 with that scale.
+    Returns (codes uint8 [K, N], scale bytes [K/32, N], working copy of R)."""
+    Rc = np.array(R, dtype=np.float64)
+    K, N = Rc.shape
+    assert K % BLOCK == 0 and H.shape == (K, K)
+    U, dead = O.gptq_factor(H, damp)
+    Rc[dead, :] = 0.0
+    q = np.zeros((K, N), dtype=np.uint8)
+    bw = np.zeros((K // BLOCK, N), dtype=np.uint8)
+    for k in range(K if stop_after is None else stop_after):
+        b = k // BLOCK
+        if k % BLOCK == 0:
+            bw[b] = block_scale_byte(np.max(np.abs(Rc[k:k + BLOCK, :].astype(np.float32)), axis=0))
+        s = scale_value(bw[b])
+        y = (Rc[k, :].astype(np.float32).astype(np.float64) / s).astype(np.float32)
+        q[k] = round_e2m1(y)
+        e = (Rc[k, :] - s * decode_e2m1(q[k]).astype(np.float64)) / U[k, k]
+        Rc[k + 1:, :] -= O.gptq_feedback(U, k, e)
+    return q, bw, Rc
+
+
 def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
-            bias: Optional[np.ndarray] = None, refine_iters: int = 0) -> Dict[str, np.ndarray]:
+            bias: Optional[np.ndarray] = None, refine_iters: int = 0,
+            gptq_x: Optional[np.ndarray] = None, gptq_damp: float = 0.01) -> Dict[str, np.ndarray]:
     """Offline quantization of one layer to MXFP4 + rank-r 16-bit branch.  W fp32 [K, N], x_absmax fp32 [K]."""
     W = np.asarray(W, dtype=np.float32)
     K, N = W.shape
@@ -134,6 +159,8 @@ def prepare(W: np.ndarray, x_absmax: np.ndarray, rank: int, alpha: float = 0.5,
             l1s_bits = np.zeros((K, 0), dtype=np.uint16)
             l2_bits = np.zeros((0, N), dtype=np.uint16)
         qw, bw, R = residual_codes_from_factors(W, rinv, l1s_bits, l2_bits)
+    if gptq_x is not None:
+        qw, bw, _ = gptq_quantize_residual(R, O.gptq_hessian(gptq_x, rinv), gptq_damp)
     b = np.zeros(N, dtype=np.float32) if bias is None else np.asarray(bias, dtype=np.float32)
     return {"rinv": rinv, "lam": lam_eff, "l1s": l1s_bits, "l2": l2_bits, "qw": qw, "bw": bw, "bias": b,
             "R": R, "W_hat": W_hat, **extra}

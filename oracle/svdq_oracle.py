@@ -204,6 +204,18 @@ def gptq_feedback(U: np.ndarray, k: int, e: np.ndarray) -> np.ndarray:
     return np.outer(U[k, k + 1:], e)
 
 
+def gptq_factor(H: np.ndarray, damp: float = 0.01):
+    """(U, dead): the upper Cholesky factor of (H + damping)^-1, H^-1 = U^T U, and the mask of channels with H_kk = 0
+    (they get H_kk = 1; their weights are set to zero by the caller).  Damping = ``damp`` x mean diagonal."""
+    Hd = np.array(H, dtype=np.float64)
+    K = Hd.shape[0]
+    idx = np.arange(K)
+    dead = Hd[idx, idx] == 0
+    Hd[idx[dead], idx[dead]] = 1.0
+    Hd[idx, idx] += damp * np.mean(Hd[idx, idx])
+    return np.linalg.cholesky(np.linalg.inv(Hd)).T, dead
+
+
 def gptq_quantize_residual(R: np.ndarray, H: np.ndarray, damp: float = 0.01, stop_after: Optional[int] = None):
     """Per-group INT4 of R [K, N] by GPTQ: minimises || X^ (R - Q(R)) ||_F greedily, one input channel at a time.
 
@@ -218,13 +230,8 @@ def gptq_quantize_residual(R: np.ndarray, H: np.ndarray, damp: float = 0.01, sto
     Rc = np.array(R, dtype=np.float64)
     K, N = Rc.shape
     assert K % GROUP == 0 and H.shape == (K, K)
-    Hd = np.array(H, dtype=np.float64)
-    idx = np.arange(K)
-    dead = Hd[idx, idx] == 0
-    Hd[idx[dead], idx[dead]] = 1.0
+    U, dead = gptq_factor(H, damp)                                  # upper triangular, H^-1 = U^T U
     Rc[dead, :] = 0.0
-    Hd[idx, idx] += damp * np.mean(Hd[idx, idx])
-    U = np.linalg.cholesky(np.linalg.inv(Hd)).T                     # upper triangular, H^-1 = U^T U
     q = np.zeros((K, N), dtype=np.int8)
     sw = np.zeros((K // GROUP, N), dtype=np.float16)
     for k in range(K if stop_after is None else stop_after):

@@ -422,3 +422,12 @@ def test_w8a8_prepare_matches_the_oracle_given_the_same_factors(lib):
     assert fwd(C.byref(fake), C.c_void_p(0x1000), 16, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1024), None) == -4
     assert fwd(C.byref(fake), C.c_void_p(0x1000), -1, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1 << 40), None) == -1
     assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), 16, C.c_void_p(0x1000), C.c_void_p(0x1000), C.c_size_t(1 << 40), None) == -2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is single-GPU: --gpus N > 1 exits with a message before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""

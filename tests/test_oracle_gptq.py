@@ -11,6 +11,7 @@ Frantar et al. 2022).  GPTQ is a greedy heuristic, so the pins are what the math
 """
 import numpy as np
 
+from oracle import svdq_fp4_oracle as F
 from oracle import svdq_oracle as O
 
 
@@ -105,3 +106,43 @@ def test_objective_drops_below_round_to_nearest_and_so_does_the_layer_error():
     e_rtn = np.linalg.norm(O.forward_w4a16(xb, rtn)["Y64"] - ref)
     e_gq = np.linalg.norm(O.forward_w4a16(xb, gq)["Y64"] - ref)
     assert e_gq < 0.3 * e_rtn, (e_gq, e_rtn)              # measured 0.13
+
+
+def _dequant_fp4(q, bw):
+    return F.dequantize_blocks(np.ascontiguousarray(q.T), np.ascontiguousarray(bw.T)).T
+
+
+def test_fp4_identity_hessian_is_round_to_nearest_and_remaining_rows_are_optimal():
+    rng = np.random.default_rng(6)
+    K, N = 128, 5
+    R = rng.standard_normal((K, N)) * 0.05
+    q, bw, _ = F.gptq_quantize_residual(R, 2.5 * np.eye(K))
+    q0, b0 = F.quantize_residual(R)
+    assert np.array_equal(F.decode_e2m1(q), F.decode_e2m1(q0)) and np.array_equal(bw, b0)
+    x = _calibration(rng, 400, K, corr=0.6)
+    H = O.gptq_hessian(x, np.ones(K, np.float32))
+    xh = x.astype(np.float64)
+    for k in (3, 40):                                      # 40 crosses a block boundary
+        q, bw, Rc = F.gptq_quantize_residual(R, H, damp=0.0, stop_after=k)
+        fixed = _dequant_fp4(q, bw)[:k]
+        v, *_ = np.linalg.lstsq(xh[:, k:], xh @ R - xh[:, :k] @ fixed, rcond=None)
+        assert np.allclose(Rc[k:], v, rtol=1e-7, atol=1e-10), k
+    # scale on entry: block 1's byte is Eq. (1) on the block as it stands after 32 channels
+    q, bw, _ = F.gptq_quantize_residual(R, H)
+    _, _, Rc = F.gptq_quantize_residual(R, H, stop_after=32)
+    assert np.array_equal(bw[1], F.quantize_residual(Rc[32:64])[1][0])
+
+
+def test_fp4_objective_drops_below_round_to_nearest():
+    rng = np.random.default_rng(7)
+    K, N, Mc, r = 256, 96, 512, 16
+    x = _calibration(rng, Mc, K)
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[rng.choice(K, 2, replace=False)] *= 20
+    ax = np.abs(x).max(axis=0)
+    rtn = F.prepare(w, ax, r)
+    gq = F.prepare(w, ax, r, gptq_x=x)
+    H = O.gptq_hessian(x, rtn["rinv"])
+    o_rtn = O.gptq_objective(rtn["R"], _dequant_fp4(rtn["qw"], rtn["bw"]), H)
+    o_gq = O.gptq_objective(gq["R"], _dequant_fp4(gq["qw"], gq["bw"]), H)
+    assert o_gq < 0.1 * o_rtn, (o_gq, o_rtn)
