@@ -105,17 +105,19 @@ int svdq_prepare_refined(const svdq_shape *shape, const float *W, const float *x
  * residual are svdq_prepare's; then, with H = X^^T X^ of the smoothed calibration activations, the input channels
  * are quantized in order (Eq. 1 per group of 64, the group's fp16 scale taken from the group as it stands when its
  * first channel is reached) and each channel's error is spread over the later channels through the upper Cholesky
- * factor of H^-1, which minimises || X^ (R - Q(R)) ||_F greedily.  INT4 layers only (shape.group = 64).
+ * factor of H^-1, which minimises || X^ (R - Q(R)) ||_F greedily.  shape.group = 64 (INT4) or 32 (MXFP4: Eq. 1 per
+ * block of 32, the block's scale byte taken on entry to the block; out_wscales then holds scale bytes as for
+ * svdq_fp4_prepare).
  *   x_cal          host, fp32 [Mc][K] row-major: calibration activations of this layer, unsmoothed
  *   damp           >= 0: this fraction of the mean diagonal of H is added to its diagonal (0.01 is customary);
  *                  a channel that x_cal never excites gets H_kk = 1 and zero codes
  *   out_objective  host, 2 doubles or NULL: || X^ (R - Q(R)) ||_F^2 for round-to-nearest and for the packed codes
- * Outputs as for svdq_prepare.  Cost: O(K^3 + Mc K^2 + K^2 N) fp64 operations and three K x K fp64 matrices on the host.
+ * Outputs as for svdq_prepare / svdq_fp4_prepare.  Cost: O(K^3 + Mc K^2 + K^2 N) fp64 operations and three K x K fp64 matrices on the host.
  * Errors: as svdq_prepare; SVDQ_EUNSUPPORTED also if H + damping is not positive definite (raise `damp`).
  */
 int svdq_prepare_gptq(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
                       const float *x_cal, int Mc, float damp, float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2,
-                      uint8_t *out_wcodes, uint16_t *out_wscales, float *out_bias, double *out_objective);
+                      uint8_t *out_wcodes, void *out_wscales, float *out_bias, double *out_objective);
 
 /*
  * Pack an externally quantized layer (canonical forms, all HOST) into native buffers:

@@ -310,29 +310,36 @@ int check_shape(const svdq_shape *s, int group = kGroup) {
 // Eq. 1 on one MXFP4 block of 32 values (stride `stride` apart): the scale is the smallest power of two
 // 2^e >= 2^-126 with max|v| <= 6 * 2^e, stored as the byte e + 127 (0 for an all-zero block); the codes are the
 // E2M1 elements nearest to v / 2^e, ties to the even code, sign in bit 3.
-inline uint8_t quantize_block_fp4(const float *v, size_t stride, uint8_t *codes) {
-    float amax = 0.0f;
-    for (int i = 0; i < svdq::kFp4Block; ++i) amax = std::max(amax, std::fabs(v[i * stride]));
-    if (!(amax > 0.0f)) {
-        for (int i = 0; i < svdq::kFp4Block; ++i) codes[i] = 0;
-        return 0;
-    }
+static const float kE2M1Grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+
+// scale byte of a block whose largest magnitude is amax (0 for an all-zero block)
+inline uint8_t fp4_scale_byte(float amax) {
+    if (!(amax > 0.0f)) return 0;
     int ex;
     const float m = std::frexp(amax, &ex);                       // amax = m 2^ex, m in [0.5, 1)
     int e = (m <= 0.75f) ? ex - 3 : ex - 2;                      // amax <= 1.5 * 2^(e + 2)
     e = std::min(127, std::max(-126, e));
-    static const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
-    for (int i = 0; i < svdq::kFp4Block; ++i) {
-        const float y = std::ldexp(v[i * stride], -e);
-        const float a = std::min(std::fabs(y), 6.0f);
-        int best = 0;
-        for (int c = 1; c < 8; ++c) {
-            const float d = std::fabs(a - grid[c]), db = std::fabs(a - grid[best]);
-            if (d < db || (d == db && (c & 1) == 0)) best = c;
-        }
-        codes[i] = (uint8_t)(best | (y < 0.0f ? 8 : 0));
-    }
     return (uint8_t)(e + 127);
+}
+// E2M1 code of v under the scale byte (nearest element of v / 2^e, ties to the even code, saturating)
+inline uint8_t fp4_code(float v, uint8_t byte) {
+    if (byte == 0) return 0;
+    static const float grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+    const float y = std::ldexp(v, 127 - (int)byte);
+    const float a = std::min(std::fabs(y), 6.0f);
+    int best = 0;
+    for (int c = 1; c < 8; ++c) {
+        const float d = std::fabs(a - grid[c]), db = std::fabs(a - grid[best]);
+        if (d < db || (d == db && (c & 1) == 0)) best = c;
+    }
+    return (uint8_t)(best | (y < 0.0f ? 8 : 0));
+}
+inline uint8_t quantize_block_fp4(const float *v, size_t stride, uint8_t *codes) {
+    float amax = 0.0f;
+    for (int i = 0; i < svdq::kFp4Block; ++i) amax = std::max(amax, std::fabs(v[i * stride]));
+    const uint8_t byte = fp4_scale_byte(amax);
+    for (int i = 0; i < svdq::kFp4Block; ++i) codes[i] = fp4_code(v[i * stride], byte);
+    return byte;
 }
 
 // Eq. 1 on one group of 64 values (stride `stride` apart): fp16 scale and 64 codes.
@@ -455,7 +462,6 @@ void residual_rows(const svdq_shape *shape, const SplitLayer &o, size_t g, std::
     }
 }
 
-static const float kE2M1Grid[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
 
 // Quantizes the residual of the current factors in the format the shape's group size names and returns
 // || R - Q(R) ||_F^2.  qw: one code per byte [K x N] (INT4 codes as int8, E2M1 codes 0..15); sc: fp16 [G x N] for
@@ -575,11 +581,11 @@ bool inverse_cholesky_upper(std::vector<double> &H, int K, std::vector<double> &
 // Quantizes R [K x N] (fp64, destroyed: it ends as the working copy with every adjustment) into qw / sw by GPTQ with
 // the factor U.  Columns are independent, so inside a group of 64 channels each thread walks its own columns; the
 // adjustment of the rows after the group is applied once per group (the same sums in a different order).
-void gptq_quantize(int K, int N, std::vector<double> &R, const std::vector<double> &U, const std::vector<uint8_t> &dead,
+void gptq_quantize(int K, int N, bool fp4, std::vector<double> &R, const std::vector<double> &U, const std::vector<uint8_t> &dead,
                    std::vector<int8_t> &qw, std::vector<uint16_t> &sw) {
     const int G = K / kGroup;
     qw.assign((size_t)K * N, 0);
-    sw.assign((size_t)G * N, 0);
+    sw.assign((size_t)(fp4 ? 2 : 1) * G * N, 0);
     for (int k = 0; k < K; ++k)
         if (dead[k]) std::fill(R.begin() + (size_t)k * N, R.begin() + (size_t)(k + 1) * N, 0.0);
     std::vector<double> Err((size_t)kGroup * N);
@@ -587,18 +593,37 @@ void gptq_quantize(int K, int N, std::vector<double> &R, const std::vector<doubl
         const size_t k0 = (size_t)g * kGroup;
         parallel_for((size_t)N, [&](size_t n0, size_t n1, int) {
             for (size_t n = n0; n < n1; ++n) {
-                const uint16_t s16 = group_scale(R.data() + k0 * N + n, (size_t)N);
-                sw[(size_t)g * N + n] = s16;
-                const float s = f16_to_f32(s16);
-                const float rcp = s > 0.0f ? 1.0f / s : 0.0f;
+                float s = 0.0f, rcp = 0.0f;
+                uint8_t byte = 0;
+                if (!fp4) {
+                    const uint16_t s16 = group_scale(R.data() + k0 * N + n, (size_t)N);
+                    sw[(size_t)g * N + n] = s16;
+                    s = f16_to_f32(s16);
+                    rcp = s > 0.0f ? 1.0f / s : 0.0f;
+                }
                 for (int kk = 0; kk < kGroup; ++kk) {
                     const size_t k = k0 + kk;
+                    if (fp4 && kk % svdq::kFp4Block == 0) {      // the block's scale from its rows as they stand now
+                        float amax = 0.0f;
+                        for (int i = 0; i < svdq::kFp4Block; ++i) amax = std::max(amax, std::fabs((float)R[(k + i) * N + n]));
+                        byte = fp4_scale_byte(amax);
+                        sw[((size_t)g * 2 + kk / svdq::kFp4Block) * N + n] = byte;
+                    }
                     const double w = R[k * N + n];
-                    float q = std::nearbyintf((float)w * rcp);
-                    q = std::min(7.0f, std::max(-7.0f, q));
-                    qw[k * N + n] = (int8_t)q;
+                    double deq;
+                    if (!fp4) {
+                        float q = std::nearbyintf((float)w * rcp);
+                        q = std::min(7.0f, std::max(-7.0f, q));
+                        qw[k * N + n] = (int8_t)q;
+                        deq = (double)s * (double)q;
+                    } else {
+                        const uint8_t c = fp4_code((float)w, byte);
+                        qw[k * N + n] = (int8_t)c;
+                        const double mag = (double)kE2M1Grid[c & 7];
+                        deq = byte ? std::ldexp((c & 8) ? -mag : mag, (int)byte - 127) : 0.0;
+                    }
                     const double *Uk = U.data() + k * K;
-                    const double e = (w - (double)s * (double)q) / Uk[k];
+                    const double e = (w - deq) / Uk[k];
                     Err[(size_t)kk * N + n] = e;
                     for (int k2 = kk + 1; k2 < kGroup; ++k2) R[(k0 + k2) * N + n] -= Uk[k0 + k2] * e;
                 }
@@ -619,13 +644,22 @@ void gptq_quantize(int K, int N, std::vector<double> &R, const std::vector<doubl
 }
 
 // || X^ (R - Q(R)) ||_F^2 with X^ [Mc x K] row-major fp64
-double gptq_objective(const std::vector<double> &Xh, int Mc, int K, int N, const std::vector<double> &R,
+double gptq_objective(const std::vector<double> &Xh, int Mc, int K, int N, bool fp4, const std::vector<double> &R,
                       const std::vector<int8_t> &qw, const std::vector<uint16_t> &sw) {
     std::vector<double> E((size_t)K * N);
     parallel_for((size_t)K, [&](size_t k0, size_t k1, int) {
         for (size_t k = k0; k < k1; ++k)
-            for (int n = 0; n < N; ++n)
-                E[k * N + n] = R[k * N + n] - (double)f16_to_f32(sw[(k / kGroup) * N + n]) * (double)qw[k * N + n];
+            for (int n = 0; n < N; ++n) {
+                double d;
+                if (!fp4) {
+                    d = (double)f16_to_f32(sw[(k / kGroup) * N + n]) * (double)qw[k * N + n];
+                } else {
+                    const int byte = (int)sw[(k / svdq::kFp4Block) * N + n], c = (int)(uint8_t)qw[k * N + n];
+                    const double mag = (double)kE2M1Grid[c & 7];
+                    d = byte ? std::ldexp((c & 8) ? -mag : mag, byte - 127) : 0.0;
+                }
+                E[k * N + n] = R[k * N + n] - d;
+            }
     });
     std::vector<double> part((size_t)Mc, 0.0);
     parallel_for((size_t)Mc, [&](size_t m0, size_t m1, int) {
@@ -808,13 +842,14 @@ int svdq_prepare_refined(const svdq_shape *shape, const float *W, const float *x
 // ---- MXFP4 variant ------------------------------------------------------------------------------------
 int svdq_prepare_gptq(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,
                       const float *x_cal, int Mc, float damp, float *out_rinv, uint16_t *out_l1s, uint16_t *out_l2,
-                      uint8_t *out_wcodes, uint16_t *out_wscales, float *out_bias, double *out_objective) {
-    const int st = check_shape(shape);
+                      uint8_t *out_wcodes, void *out_wscales, float *out_bias, double *out_objective) {
+    const int st = check_shape(shape, kAny4Bit);
     if (st != SVDQ_OK) return st;
     if (!W || !x_absmax || !x_cal || Mc <= 0 || !(damp >= 0.0f) || !std::isfinite(damp) || !out_rinv || !out_l1s || !out_l2 ||
         !out_wcodes || !out_wscales || !out_bias)
         return SVDQ_EINVAL;
     const int K = shape->K, N = shape->N, G = K / kGroup;
+    const bool fp4 = shape->group == svdq::kFp4Block;
     try {
         SplitLayer sl;
         split_layer(shape, W, x_absmax, sl);
@@ -868,14 +903,22 @@ int svdq_prepare_gptq(const svdq_shape *shape, const float *W, const float *x_ab
             std::vector<int8_t> q0;
             std::vector<uint16_t> s0;
             quantize_residual(shape, sl, q0, s0, nullptr);                   // round-to-nearest, for comparison
-            out_objective[0] = gptq_objective(Xh, Mc, K, N, R, q0, s0);
+            out_objective[0] = gptq_objective(Xh, Mc, K, N, fp4, R, q0, s0);
         }
         std::vector<double> Rc = R;
-        gptq_quantize(K, N, Rc, U, dead, qw, sw);
+        gptq_quantize(K, N, fp4, Rc, U, dead, qw, sw);
         std::vector<double>().swap(Rc);
-        if (out_objective) out_objective[1] = gptq_objective(Xh, Mc, K, N, R, qw, sw);
-        pack_native(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), qw.data(), sw.data(), bias, out_rinv, out_l1s, out_l2,
-                    out_wcodes, out_wscales, out_bias);
+        if (out_objective) out_objective[1] = gptq_objective(Xh, Mc, K, N, fp4, R, qw, sw);
+        if (!fp4) {
+            pack_native(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), qw.data(), sw.data(), bias, out_rinv, out_l1s, out_l2,
+                        out_wcodes, static_cast<uint16_t *>(out_wscales), out_bias);
+        } else {
+            std::vector<uint8_t> q8(qw.size()), b8(sw.size());
+            for (size_t i = 0; i < qw.size(); ++i) q8[i] = (uint8_t)qw[i];
+            for (size_t i = 0; i < sw.size(); ++i) b8[i] = (uint8_t)sw[i];
+            pack_common(shape, sl.rinv.data(), sl.l1s.data(), sl.l2.data(), bias, out_rinv, out_l1s, out_l2, out_bias);
+            pack_fp4_weights(shape, q8.data(), b8.data(), out_wcodes, static_cast<uint8_t *>(out_wscales));
+        }
     } catch (const std::bad_alloc &) {
         return SVDQ_ENOMEM;
     }

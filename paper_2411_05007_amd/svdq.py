@@ -224,8 +224,8 @@ def svdq_prepare_refined(W: np.ndarray, x_absmax: np.ndarray, rank: int, iterati
 
 
 def svdq_prepare_gptq(W: np.ndarray, x_absmax: np.ndarray, rank: int, x_cal: np.ndarray, damp: float = 0.01,
-                      alpha: float = 0.5, bias: Optional[np.ndarray] = None):
-    """Prepare an INT4 layer with the residual quantized by GPTQ on calibration activations x_cal fp32 [Mc, K].
+                      alpha: float = 0.5, bias: Optional[np.ndarray] = None, fp4: bool = False):
+    """Prepare an INT4 (or MXFP4) layer with the residual quantized by GPTQ on calibration activations x_cal fp32 [Mc, K].
     Returns (PreparedHost, (objective of round-to-nearest, objective of the packed codes))."""
     W = np.ascontiguousarray(W, dtype=np.float32)
     K, N = W.shape
@@ -233,7 +233,7 @@ def svdq_prepare_gptq(W: np.ndarray, x_absmax: np.ndarray, rank: int, x_cal: np.
     x_cal = np.ascontiguousarray(x_cal, dtype=np.float32)
     assert x_absmax.shape == (K,) and x_cal.ndim == 2 and x_cal.shape[1] == K
     b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
-    shape = make_shape(K, N, rank, alpha)
+    shape = make_shape(K, N, rank, alpha, group=32 if fp4 else 64)
     out = _alloc_prepared(shape)
     objective = np.zeros(2, np.float64)
     _check(lib().svdq_prepare_gptq(C.byref(shape), _ptr(W), _ptr(x_absmax), _ptr(b), _ptr(x_cal), int(x_cal.shape[0]),

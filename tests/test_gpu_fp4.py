@@ -258,3 +258,30 @@ def test_refined_layers_run_like_any_other(torch):
         y1 = O.bf16_to_f32(S.bits_from_bf16_tensor(S.DeviceLayer(prep).forward(x))).astype(np.float64)
         y0 = O.bf16_to_f32(S.bits_from_bf16_tensor(S.DeviceLayer(plain).forward(x))).astype(np.float64)
         assert np.linalg.norm(y1 - full) <= 1.03 * np.linalg.norm(y0 - full)
+
+
+def test_gptq_prepared_fp4_layer(torch):
+    """App. "Implementation Details": the residual quantized with GPTQ, here with the MXFP4 quantizer.  Same kernels, same
+    parity bar; on the tokens the Hessian was built from, the output is closer to X W than the round-to-nearest layer's."""
+    rng = np.random.default_rng(9200)
+    M, K, N, r = 384, 256, 400, 16
+    z = rng.standard_normal((M, 8))
+    x = (0.9 * (z @ rng.standard_normal((8, K))) + 0.1 * rng.standard_normal((M, K))).astype(np.float32)
+    x[:, rng.choice(K, 3, replace=False)] *= 20
+    xb = O.bf16_round(x)
+    xf = O.bf16_to_f32(xb)
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    ax = np.abs(xf).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    rtn = S.svdq_fp4_prepare(w, ax, r, bias=b)
+    gq, (o_rtn, o_gq) = S.svdq_prepare_gptq(w, ax, r, xf, bias=b, fp4=True)
+    assert gq.shape.group == 32 and o_gq < 0.5 * o_rtn
+    _run_and_compare(torch, xb, gq, what="fp4 gptq-prepared layer")
+    xt = S.bf16_tensor_from_bits(xb)
+    ref = xf.astype(np.float64) @ w.astype(np.float64) + b[None, :].astype(np.float64)
+    err = []
+    for prep in (rtn, gq):
+        y = O.bf16_to_f32(S.bits_from_bf16_tensor(S.DeviceLayer(prep).forward(xt))).astype(np.float64)
+        err.append(np.linalg.norm(y - ref) / np.linalg.norm(ref))
+    _say(f"fp4 gptq: relative output error {err[1]:.4e} vs round-to-nearest {err[0]:.4e}")
+    assert err[1] < err[0]

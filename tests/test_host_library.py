@@ -329,8 +329,19 @@ def test_gptq_prepare_against_the_oracle(lib):
     # argument errors
     with pytest.raises(S.SvdqError):
         S.svdq_prepare_gptq(w, ax, r, x, damp=-1.0)
-    sh = S.make_shape(K, N, r, group=32)
+    sh = S.make_shape(K, N, r, group=0)                   # the 8-bit setting has no GPTQ here
     assert lib.svdq_prepare_gptq(C.byref(sh), None, None, None, None, 1, C.c_float(0.01), *([None] * 7)) == -2
+    # the MXFP4 quantizer inside the same loop
+    from oracle import svdq_fp4_oracle as F
+    prep4, (o4_rtn, o4_gptq) = S.svdq_prepare_gptq(w, ax, r, x, damp=0.01, bias=b, fp4=True)
+    U4, P4 = S.svdq_fp4_unpack(prep4), S.svdq_fp4_unpack(S.svdq_fp4_prepare(w, ax, r, bias=b))
+    assert np.array_equal(U4["l1s"], P4["l1s"]) and np.array_equal(U4["l2"], P4["l2"])
+    q4, b4, _ = F.gptq_quantize_residual(R, H, damp=0.01)
+    assert np.mean(F.decode_e2m1(U4["qw"]) == F.decode_e2m1(q4)) >= 0.999 and np.mean(U4["bw"] == b4) >= 0.999
+    deq4 = lambda q_, b_: F.dequantize_blocks(np.ascontiguousarray(q_.T), np.ascontiguousarray(b_.T)).T
+    assert np.isclose(o4_gptq, O.gptq_objective(R, deq4(U4["qw"], U4["bw"]), H), rtol=1e-9)
+    assert np.isclose(o4_rtn, O.gptq_objective(R, deq4(P4["qw"], P4["bw"]), H), rtol=1e-9)
+    assert o4_gptq < 0.1 * o4_rtn
 
 
 def test_w4a16_forward_argument_errors(lib):
