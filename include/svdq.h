@@ -266,7 +266,7 @@ int svdq_fp4_debug_act(const svdq_layer_dev *layer, const void *workspace, int M
  *   Y = bf16( (X * 1/lambda) Q(R) + (X l1s) l2 + bias ),   Q(R) = wscales * codes,
  * i.e. Eq. 5 without quantizing the activations.  Arguments, workspace (svdq_workspace_bytes), stream and errors as
  * for svdq_linear_forward.  A weight-streaming kernel meant for the handful of rows these layers see; any M is
- * accepted (eight rows per pass over the weights).  Enqueues two kernels (down projection, then this one).
+ * accepted (eight rows per pass over the weights).  Enqueues two kernels (down projection, then the weight stream).
  */
 int svdq_w4a16_forward(const svdq_layer_dev *layer, const void *X, int M, void *Y,
                        void *workspace, size_t workspace_bytes, void *hip_stream);

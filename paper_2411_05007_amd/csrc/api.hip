@@ -307,7 +307,12 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
     hipError_t e = hipSuccess;
-    if (lowrank) {
+    if (lowrank && M <= svdq::kW4A16ProjRows) {
+        // a handful of rows: the projection kernel shaped for them (the activation kernel gives 16 tokens to a workgroup)
+        e = svdq::launch_w4a16_proj(static_cast<const uint16_t *>(X), static_cast<const uint16_t *>(L->l1s),
+                                    reinterpret_cast<float *>(ws + w.h_off), M, s.K, s.rank, stream);
+        if (e != hipSuccess) return hip_fail(e);
+    } else if (lowrank) {
         svdq::ActParams a{};
         a.X = static_cast<const uint16_t *>(X);
         a.rinv = static_cast<const float *>(L->rinv);

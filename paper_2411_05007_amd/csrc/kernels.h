@@ -99,13 +99,16 @@ struct W4A16Params {
     const float *rinv;       // fp32 [K]
     const uint8_t *wcodes;   // [G][Npad][32]
     const uint16_t *sw;      // fp16 [G][Npad]
-    const float *H;          // fp32 [Mpad][rank] (from the activation kernel in projection-only mode); unused when rank == 0
+    const float *H;          // fp32 [Mpad][rank], written by the projection launch before; unused when rank == 0
     const uint16_t *l2t;     // bf16 [Npad][rank]
     const float *bias;       // fp32 [Npad]
     uint16_t *Y;             // bf16 [M][N]
     int M, N, K, Npad, rank;
 };
 hipError_t launch_w4a16(const W4A16Params &p, hipStream_t stream);
+constexpr int kW4A16ProjRows = 16;     // up to this many rows the W4A16 forward uses its own projection kernel
+// H[m][j] = sum_k x[m][k] l1s[k][j] (fp32 [M][rank]) for a handful of rows; l1s in its stored fragment order
+hipError_t launch_w4a16_proj(const uint16_t *X, const uint16_t *l1s, float *H, int M, int K, int rank, hipStream_t stream);
 
 // ---- 8-bit setting -------------------------------------------------------------------------------------------
 struct Quant8Params {

@@ -6,7 +6,7 @@
 // These layers see a handful of rows (one conditioning vector per image), so the kernels are weight-streaming ones:
 // every 4-bit code is read once and widened on the vector ALU; the matrix cores are not used.  Codes are summed
 // against X^ in fp32 per group and scaled once per group; partial sums of wavefronts are added in wavefront order
-// (deterministic); then H L2 (H from the activation kernel in projection-only mode), bias, bf16.
+// (deterministic); then H L2 (H from w4a16_proj_kernel below, or from the activation kernel for many rows), bias, bf16.
 //   * one or two rows: w4a16_stream_kernel, one workgroup per compute unit, X^ in registers;
 //   * more rows: w4a16_kernel, a workgroup per 32 or 64 columns and 4 or 8 rows (further rows take further passes
 //     over the weights), X^ through a wavefront-private LDS block and back as broadcast reads.
@@ -281,6 +281,76 @@ __global__ __launch_bounds__(1024) void w4a16_stream_kernel(W4A16Params p, int C
     }
 }
 
+// Down projection for a handful of rows: H[m][j] = sum_k bf16(x[m][k]) * l1s[k][j] in fp32 (Sec. 4.2: the 16-bit branch,
+// lambda^-1 folded into l1s).  The activation kernel gives a whole workgroup to 16 tokens and walks K serially, which
+// for one row means one workgroup reading all of l1s; here a workgroup of 16 wavefronts takes one block of 16 columns
+// and one or two rows (more rows: more workgroups), wavefront w the groups w, w + 16, ..., three groups' operands requested at a time;  l1s is read in its stored fragment order (lane l of a
+// fragment: column l % 16, channels 16 (l / 16) + 8 s + e of the group for k step s), one 16-byte load per lane and
+// step; the four 16-channel quarters and the wavefronts are added in a fixed order through LDS.
+template <int ROWS>
+__global__ __launch_bounds__(1024) void w4a16_proj_kernel(const uint16_t *X, const uint16_t *l1s, float *H, int M, int K, int rank) {
+    constexpr int GPW = 3;                                // groups per wavefront whose operands are requested together
+    __shared__ float part[16][4][ROWS][16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, quarter = lane >> 4;
+    const int c = blockIdx.x, m0 = blockIdx.y * ROWS, G = K / 64, cb = rank / 16;
+    const uint16_t *xrow[ROWS];
+#pragma unroll
+    for (int m = 0; m < ROWS; ++m) xrow[m] = X + (size_t)(m0 + m < M ? m0 + m : M - 1) * K + 16 * quarter;   // rows past M repeat the last row; never stored
+    float acc[ROWS];
+#pragma unroll
+    for (int m = 0; m < ROWS; ++m) acc[m] = 0.f;
+    for (int gb = 0; gb < G; gb += 16 * GPW) {
+        uint4 f[GPW][2], xv[GPW][2][ROWS];
+#pragma unroll
+        for (int u = 0; u < GPW; ++u) {
+            const int g = gb + wave + 16 * u < G ? gb + wave + 16 * u : G - 1;      // past the end: a valid group, loaded and ignored
+#pragma unroll
+            for (int sidx = 0; sidx < 2; ++sidx) {
+                f[u][sidx] = *reinterpret_cast<const uint4 *>(l1s + ((((size_t)g * 2 + sidx) * cb + c) * 64 + lane) * 8);
+#pragma unroll
+                for (int m = 0; m < ROWS; ++m) xv[u][sidx][m] = *reinterpret_cast<const uint4 *>(xrow[m] + g * 64 + 8 * sidx);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < GPW; ++u) {
+            if (gb + wave + 16 * u >= G) break;                                      // uniform over the wavefront
+#pragma unroll
+            for (int sidx = 0; sidx < 2; ++sidx) {
+                const uint4 w4 = f[u][sidx];
+                const float w[8] = {__uint_as_float(w4.x << 16), __uint_as_float(w4.x & 0xffff0000u), __uint_as_float(w4.y << 16), __uint_as_float(w4.y & 0xffff0000u),
+                                    __uint_as_float(w4.z << 16), __uint_as_float(w4.z & 0xffff0000u), __uint_as_float(w4.w << 16), __uint_as_float(w4.w & 0xffff0000u)};
+#pragma unroll
+                for (int m = 0; m < ROWS; ++m) {
+                    const uint4 x4 = xv[u][sidx][m];
+                    float a = acc[m];
+                    a = __builtin_fmaf(__uint_as_float(x4.x << 16), w[0], a);
+                    a = __builtin_fmaf(__uint_as_float(x4.x & 0xffff0000u), w[1], a);
+                    a = __builtin_fmaf(__uint_as_float(x4.y << 16), w[2], a);
+                    a = __builtin_fmaf(__uint_as_float(x4.y & 0xffff0000u), w[3], a);
+                    a = __builtin_fmaf(__uint_as_float(x4.z << 16), w[4], a);
+                    a = __builtin_fmaf(__uint_as_float(x4.z & 0xffff0000u), w[5], a);
+                    a = __builtin_fmaf(__uint_as_float(x4.w << 16), w[6], a);
+                    a = __builtin_fmaf(__uint_as_float(x4.w & 0xffff0000u), w[7], a);
+                    acc[m] = a;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < ROWS; ++m) part[wave][quarter][m][col] = acc[m];
+    __syncthreads();
+    const int o_m = threadIdx.x / 16, o_c = threadIdx.x % 16;
+    if (o_m < ROWS && m0 + o_m < M) {
+        float h = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) h += part[w][q][o_m][o_c];
+        H[(size_t)(m0 + o_m) * rank + 16 * c + o_c] = h;
+    }
+}
+
 // ---- host side: the shape of the chip-filling launch ----
 struct StreamPlan { int cb, nw, wgs; };
 
@@ -307,6 +377,14 @@ void launch_one(const W4A16Params &p, int row_blocks, hipStream_t stream) {
 }
 
 }  // namespace
+
+hipError_t launch_w4a16_proj(const uint16_t *X, const uint16_t *l1s, float *H, int M, int K, int rank, hipStream_t stream) {
+    if (M <= 0 || rank <= 0) return hipSuccess;
+    if (K <= 0 || K % 64 || rank % 16) return hipErrorInvalidValue;
+    if (M == 1) hipLaunchKernelGGL(w4a16_proj_kernel<1>, dim3(rank / 16, 1), dim3(1024), 0, stream, X, l1s, H, M, K, rank);
+    else hipLaunchKernelGGL(w4a16_proj_kernel<2>, dim3(rank / 16, (M + 1) / 2), dim3(1024), 0, stream, X, l1s, H, M, K, rank);
+    return hipGetLastError();
+}
 
 hipError_t launch_w4a16(const W4A16Params &p, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
