@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM-side traffic of one GEMM launch at the headline shape from `rocprofv3 --pmc FETCH_SIZE` /
 # `--pmc WRITE_SIZE` (profiles/flux_mlp_up_kernel_stats.md), each scaled by what the same counter
-# reads for a plain 256 MiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0): 300.9 MB read + 113.2 MB written.
-GEMM_TRAFFIC_BYTES = 405.6e6
+# reads for a plain 256 MiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0): 301.6 MB read + 113.2 MB written.
+GEMM_TRAFFIC_BYTES = 414.9e6
 
 
 class Hip:

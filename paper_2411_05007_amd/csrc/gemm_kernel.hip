@@ -8,9 +8,11 @@
 // 16 * code.  The activation kernel writes its codes in that form and in the register order of
 // the MFMA A operand, so a wavefront loads its activation fragments straight from memory (one
 // contiguous kilobyte per instruction) and they never pass through LDS.  The packed weight
-// nibbles are widened on the way into LDS: a packed dword x becomes (x << 4) & 0xF0F0F0F0 (even
-// codes) and x & 0xF0F0F0F0 (odd codes), three vector-ALU operations per eight codes, once per
-// workgroup.  An MFMA sum is therefore 256 * A_g; the 2^-8 is folded into the weight scale.
+// nibbles are widened in registers: a packed dword x becomes (x << 4) & 0xF0F0F0F0 (even
+// codes) and x & 0xF0F0F0F0 (odd codes), three vector-ALU operations per eight codes - either
+// once per workgroup on the way into LDS (the staged path) or by every wavefront for its own
+// columns, straight from memory (the direct path: no LDS and no barrier in the loop).
+// An MFMA sum is therefore 256 * A_g; the 2^-8 is folded into the weight scale.
 //
 // One group of 64 channels is two v_mfma_i32_32x32x32_i8.  Their accumulator is seeded with the bit
 // pattern of 1.5 * 2^23, so the int32 result read as fp32 is exactly 12582912 + 256 * A_g and
@@ -21,8 +23,9 @@
 // kernel: the MFMA's accumulator traffic and the FMAs' operands go through the same vector
 // register file, so matrix and vector work overlap only partly, and every vector instruction that
 // is not a rescale FMA costs matrix-core time.  Hence: buffer loads with scalar offsets, the A
-// operand stored ready-made, the weight widening and the scale conversions shared by the whole
-// workgroup.
+// operand stored ready-made, and in the staged path the weight widening and the scale conversions
+// shared by the whole workgroup (the direct path spends 15 more vector instructions per group and
+// wavefront and saves the LDS round trip and the barrier, which on most shapes is the better trade).
 //
 // The k order inside a group only has to be the same for both operands: lane half h of a fragment
 // takes bytes 32 h .. 32 h + 15 of a row for the first MFMA and the next 16 for the second, for the
@@ -79,7 +82,9 @@ struct Tile {
 };
 
 // MODE 0: normal forward.  MODE 1: additionally export exact group sums of a window (parity checks).
-template <int BM, int BN, int MODE>
+// DIRECT: every wavefront fetches its own weight fragments and scales straight from memory (no LDS and no barrier in
+// the loop; the wavefronts that share columns fetch them twice, from cache) instead of the workgroup staging them in LDS.
+template <int BM, int BN, int MODE, bool DIRECT>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_kernel(GemmParams p) {
     using T = Tile<BM, BN>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -298,11 +303,54 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     intx4 afe[2][2], afo[2][2];
     Scales sce, sco;
     Staged qe, qo;
-    auto body = [&](int g, auto odd_c, const intx4 (&af)[2][2], intx4 (&afn)[2][2], const Scales &sc, Scales &scn, Staged &q) {
+    // DIRECT: lane (li, lh) takes the 16 packed bytes 16 lh .. + 15 of row li of each of its two 32-column blocks,
+    // which widen to exactly its two MFMA operands (the bytes the staged path would have read back from LDS); its
+    // scales come as four 2-byte loads.  One group ahead, like the activation fragments.
+    const __amdgpu_buffer_rsrc_t rs_sx = make_rsrc(p.sx, (size_t)p.G * p.Mpad * 2);
+    const __amdgpu_buffer_rsrc_t rs_sw = make_rsrc(p.sw, (size_t)p.G * p.Npad * 2);
+    struct RawB { u32x4 b[2]; uint32_t sx[2], sw[2]; };
+    RawB rbe, rbo;
+    auto load_raw = [&](RawB &q, int g) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            q.b[c] = __builtin_amdgcn_raw_buffer_load_b128(rs_b, li * kCodeBytes + lh * 16, (g * p.Npad + gn0 + wn0 + c * 32) * kCodeBytes, 0);
+#pragma unroll
+        for (int r = 0; r < 2; ++r) q.sx[r] = __builtin_amdgcn_raw_buffer_load_b16(rs_sx, (sx_lane + r * 32) * 2, (g * p.Mpad + gm0) * 2, 0);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) q.sw[c] = __builtin_amdgcn_raw_buffer_load_b16(rs_sw, (wn0 + c * 32 + li) * 2, (g * p.Npad + gn0) * 2, 0);
+    };
+    auto widen = [&](const RawB &q, int c) {
+        const u32x4 x = q.b[c];
+        bf[c][0][0] = (x.x << 4) & 0xf0f0f0f0u; bf[c][0][1] = x.x & 0xf0f0f0f0u;
+        bf[c][0][2] = (x.y << 4) & 0xf0f0f0f0u; bf[c][0][3] = x.y & 0xf0f0f0f0u;
+        bf[c][1][0] = (x.z << 4) & 0xf0f0f0f0u; bf[c][1][1] = x.z & 0xf0f0f0f0u;
+        bf[c][1][2] = (x.w << 4) & 0xf0f0f0f0u; bf[c][1][3] = x.w & 0xf0f0f0f0u;
+    };
+    auto conv_scales = [&](Scales &sc, const RawB &q) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) sc.sx[r] = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sx[r]);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const float w = (float)__builtin_bit_cast(_Float16, (uint16_t)q.sw[c]) * 0.00390625f;      // sw * 2^-8
+            sc.sw[c] = make_float2(w, -kMagic * w);
+        }
+    };
+    auto body = [&](int g, auto odd_c, const intx4 (&af)[2][2], intx4 (&afn)[2][2], const Scales &sc_staged, Scales &scn, Staged &q,
+                    const RawB &rq, RawB &rqn) {
         constexpr int odd = decltype(odd_c)::value;      // g & 1
         constexpr int nxt = 1 - odd;
         load_a(afn, g + 1 < g_end ? g + 1 : g_end - 1);      // past the end: refetch the last group (unused)
-        read_scales(scn, nxt);                           // written one iteration ago
+        Scales sc_direct;
+        if constexpr (DIRECT) {
+            load_raw(rqn, g + 1 < g_end ? g + 1 : g_end - 1);
+            conv_scales(sc_direct, rq);
+            widen(rq, 0);
+            widen(rq, 1);
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            read_scales(scn, nxt);                       // written one iteration ago
+        }
+        const Scales &sc = DIRECT ? sc_direct : sc_staged;
         intx16 da, db;
         // sub-tiles in the order (0,0) (1,0) (1,1) (0,1): the weight fragments of column block 0 fall free first.
         // The issue arbiter of a SIMD serves the older of its two wavefronts first, which starves the younger
@@ -322,14 +370,16 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         __builtin_amdgcn_sched_barrier(0);
         rescale_half(sc, da, 0, 0, H1{});
         export_sums(da, g, 0, 0);
-        read_b(nxt, 0);
+        if constexpr (!DIRECT) read_b(nxt, 0);
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(0);
         da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][0], bf[1][0], magic, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         rescale_half(sc, db, 1, 0, H0{});
-        store_group(odd, odd, q);
-        q = load_group(g + 4 < g_end ? g + 4 : g_end - 1);
+        if constexpr (!DIRECT) {
+            store_group(odd, odd, q);
+            q = load_group(g + 4 < g_end ? g + 4 : g_end - 1);
+        }
         __builtin_amdgcn_sched_barrier(0);
         da = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][1], bf[1][1], da, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -345,20 +395,26 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
         __builtin_amdgcn_sched_barrier(0);
         rescale_half(sc, da, 1, 1, H1{});
         export_sums(da, g, 1, 1);
-        read_b(nxt, 1);
+        if constexpr (!DIRECT) read_b(nxt, 1);
         __builtin_amdgcn_sched_barrier(0);
         rescale_half(sc, db, 0, 1, H0{});
         rescale_half(sc, db, 0, 1, H1{});
         export_sums(db, g, 0, 1);
-        __syncthreads();
+        if constexpr (!DIRECT) __syncthreads();
     };
 
     const int glast = g_end - 1;
     load_a(afe, g_begin);
     {
-        const Staged q0 = load_group(g_begin), q1 = load_group(g_begin + 1 < glast ? g_begin + 1 : glast);
-        qe = load_group(g_begin + 2 < glast ? g_begin + 2 : glast);
-        qo = load_group(g_begin + 3 < glast ? g_begin + 3 : glast);
+        Staged q0, q1;
+        if constexpr (DIRECT) {
+            load_raw(rbe, g_begin);
+        } else {
+            q0 = load_group(g_begin);
+            q1 = load_group(g_begin + 1 < glast ? g_begin + 1 : glast);
+            qe = load_group(g_begin + 2 < glast ? g_begin + 2 : glast);
+            qo = load_group(g_begin + 3 < glast ? g_begin + 3 : glast);
+        }
         __builtin_amdgcn_sched_barrier(0);      // everything the main loop needs first is requested before H and L2
         // ---- low-rank up projection on the matrix core: the accumulators START as H L2 ----------------
         // bf16 MFMAs with the fp32 accumulator tile as C.  The activation kernel leaves H split into bf16 hi + lo
@@ -400,8 +456,10 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
                 if (1 < ksteps) load_step(1, 1);
             }
             __builtin_amdgcn_sched_barrier(0);
-            store_group(0, 0, q0);      // the oldest loads: this waits for them alone
-            store_group(1, 1, q1);
+            if constexpr (!DIRECT) {
+                store_group(0, 0, q0);      // the oldest loads: this waits for them alone
+                store_group(1, 1, q1);
+            }
             if (lowrank) {
                 for (int ks = 0; ks < ksteps; ks += 2) {
                     compute_step(0);
@@ -414,19 +472,21 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
             }
         }
     }
-    __syncthreads();
-    read_b(0, 0); read_b(0, 1);
-    read_scales(sce, 0);
-    __syncthreads();      // the first iteration refills slot 0: every wavefront must have taken the first group out of it
+    if constexpr (!DIRECT) {
+        __syncthreads();
+        read_b(0, 0); read_b(0, 1);
+        read_scales(sce, 0);
+        __syncthreads();      // the first iteration refills slot 0: every wavefront must have taken the first group out of it
+    }
     {
         using Even = std::integral_constant<int, 0>;
         using Odd = std::integral_constant<int, 1>;
         int g = g_begin;
         for (; g + 2 <= g_end; g += 2) {
-            body(g, Even{}, afe, afo, sce, sco, qe);
-            body(g + 1, Odd{}, afo, afe, sco, sce, qo);
+            body(g, Even{}, afe, afo, sce, sco, qe, rbe, rbo);
+            body(g + 1, Odd{}, afo, afe, sco, sce, qo, rbo, rbe);
         }
-        if (g < g_end) body(g, Even{}, afe, afo, sce, sco, qe);
+        if (g < g_end) body(g, Even{}, afe, afo, sce, sco, qe, rbe, rbo);
     }
 #undef SVDQ_FMAC_BCAST
     __builtin_amdgcn_s_setprio(0);
@@ -521,7 +581,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, (BM * BN <= 128 * 128) 
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool DIRECT = false>
 hipError_t launch_tile(const GemmParams &p, hipStream_t stream) {
     using T = Tile<BM, BN>;
     const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
@@ -529,12 +589,12 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream) {
     const dim3 grid(tiles * p.ksplit), block(T::kThreads);
     hipError_t e;
     if (p.dbg) {
-        auto k = gemm_kernel<BM, BN, 1>;
+        auto k = gemm_kernel<BM, BN, 1, DIRECT>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
     } else {
-        auto k = gemm_kernel<BM, BN, 0>;
+        auto k = gemm_kernel<BM, BN, 0, DIRECT>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
@@ -591,6 +651,8 @@ hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream) {
         case 2: return launch_tile<128, 128>(p, stream);
         case 3: return launch_tile<128, 256>(p, stream);
         case 4: return launch_tile<64, 128>(p, stream);
+        case 5: return launch_tile<128, 128, true>(p, stream);
+        case 6: return launch_tile<64, 128, true>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

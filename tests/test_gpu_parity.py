@@ -277,7 +277,7 @@ def test_activation_scales_over_the_whole_fp16_range(torch):
     assert np.all(np.isfinite(O.bf16_to_f32(S.bits_from_bf16_tensor(y))))
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
 def test_every_gemm_tile_configuration(torch, tile):
     case = I.case_by_name("tiny")
     L = I.make_layer(case, M=300)
