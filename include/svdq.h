@@ -60,7 +60,7 @@ typedef struct {
     size_t rinv;    /* fp32 [K]                     1 / lambda                                    */
     size_t l1s;     /* bf16, K * rank elements      diag(lambda)^-1 L1, MFMA-fragment order       */
     size_t l2;      /* bf16, Npad * rank elements   L2 transposed                                 */
-    size_t wcodes;  /* G * Npad * 32 bytes          4-bit codes of R, two per byte, group-major   */
+    size_t wcodes;  /* G * Npad / 64 * 2304 bytes   4-bit codes of R (+ a copy of the scales), per group and 64 columns */
     size_t wscales; /* fp16 [G][Npad]               scales of R                                    */
     size_t bias;    /* fp32 [Npad]                                                                 */
 } svdq_sizes;
@@ -123,7 +123,7 @@ int svdq_prepare_gptq(const svdq_shape *shape, const float *W, const float *x_ab
  * Pack an externally quantized layer (canonical forms, all HOST) into native buffers:
  *   rinv fp32 [K]; l1s bf16 [K x rank]; l2 bf16 [rank x N]; qw int8 [K x N] codes in [-7, 7];
  *   sw fp16 [G x N]; bias fp32 [N] or NULL.
- * Codes outside [-8, 7] are rejected with SVDQ_EINVAL.
+ * Codes outside [-7, 7] (the symmetric quantizer's range) are rejected with SVDQ_EINVAL.
  */
 int svdq_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, const uint16_t *l2,
               const int8_t *qw, const uint16_t *sw, const float *bias,
@@ -160,8 +160,8 @@ typedef struct {
     svdq_shape shape;
 } svdq_layer_dev;
 
-/* Bytes of device scratch one forward of M tokens needs: activation codes (one byte each, in the
- * operand order of the integer matrix instruction) and scales, and the low-rank intermediate
+/* Bytes of device scratch one forward of M tokens needs: activation codes (6 bits each, in the
+ * operand order of the matrix instruction) and scales, and the low-rank intermediate
  * H = X^ L1 (fp32 [M x rank], plus the same values as bf16 operand fragments for the up projection);
  * for launches with few tiles and a long K also fp32 partial output tiles and one counter per tile.
  * 0 if the shape is unsupported. */
@@ -171,8 +171,9 @@ size_t svdq_workspace_bytes(int M, const svdq_shape *shape);
  * The hot path (Eq. 5; kernel split after Sec. 4.3 / Fig. 6b): two kernels on `hip_stream`
  *   1. activation kernel: reads X once; smoothing, per-group INT4 quantization with fp16 scales,
  *      and the down projection H = X^ L1
- *   2. W4A4 GEMM: INT4 -> INT8 MFMA with exact int32 sums per group of 64, fp32 rescale by
- *      s_x s_w, accumulated on top of H L2 in the same registers; bias and the bf16 store.
+ *   2. W4A4 GEMM: the INT4 codes go through the matrix core as exact 6-bit floats, one instruction per group of
+ *      64 with the exact integer group sum as its fp32 result; fp32 rescale by s_x s_w (the scale products of a
+ *      32 x 32 block come from an f16 MFMA), accumulated on top of H L2 in the same registers; bias, bf16 store.
  *   X  device bf16 [M x K] row-major, 16-byte aligned;  Y device bf16 [M x N] row-major.
  *   workspace: device, 256-byte aligned, >= svdq_workspace_bytes(M, shape); contents are
  *   overwritten; two forwards that share a workspace must be ordered on one stream.
@@ -204,22 +205,23 @@ int svdq_debug_group_acc(const svdq_layer_dev *layer, const void *workspace, int
                          int m0, int m1, int n0, int n1, int32_t *out, void *hip_stream);
 
 /*
- * Measurement switches, process-wide, read at each svdq_linear_forward (Sec. 4.3 / Fig. 6a,
- * App. "Latency Results": naive INT4 and the unfused four-kernel pipeline).  Returns the
- * previous flags; pass a negative value to query only.
+ * Measurement switches of the CALLING THREAD, read by the forwards and the workspace-size queries that this thread
+ * makes (Sec. 4.3 / Fig. 6a, App. "Latency Results": naive INT4 and the unfused four-kernel pipeline).  Other
+ * threads are not affected.  Returns the thread's previous flags; pass a negative value to query only.
  */
 enum {
     SVDQ_OPT_SKIP_LOWRANK = 1, /* 4-bit branch only: no down projection, no up projection        */
     SVDQ_OPT_UNFUSED = 2,      /* down projection, quantize, 4-bit GEMM, up projection as four
                                   kernels; needs workspace of svdq_workspace_bytes()              */
-    SVDQ_OPT_TILE_SHIFT = 8,   /* bits 8..15: GEMM tile configuration id, 0 = chosen by shape     */
-    SVDQ_OPT_TILE_MASK = 0xff00
+    SVDQ_OPT_KSPLIT_SHIFT = 8, /* bits 8..11: workgroups per output tile along K (1..8), 0 = chosen by shape;
+                                  set it before svdq_workspace_bytes(), which sizes the partial tiles  */
+    SVDQ_OPT_KSPLIT_MASK = 0xf00
 };
 int svdq_forward_options(int flags);
 
 /*
- * Measurement only, process-wide: if `hip_event` (a hipEvent_t) is non-NULL, every following
- * svdq_linear_forward records it on its stream between the activation kernel and the GEMM, so a
+ * Measurement only, for the calling thread: if `hip_event` (a hipEvent_t) is non-NULL, every following
+ * svdq_linear_forward of this thread records it on its stream between the activation kernel and the GEMM, so a
  * caller that brackets the call with its own events gets the two kernels' durations separately
  * (the per-kernel split behind Fig. 6a).  Pass NULL to switch it off.  Returns SVDQ_OK.
  */

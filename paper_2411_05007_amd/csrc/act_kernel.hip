@@ -69,6 +69,13 @@ __device__ __forceinline__ float max_over_8_lanes(float a) {
     return a;
 }
 
+// Byte offsets inside one group's run of activation blocks (layout.h): the first dword a lane stores for token m
+// (dword 0 of its triple for an even c8, dword 2 for an odd one), and the token's scale dword.
+__device__ __forceinline__ int w4_triple_offset(int m, int c8) {
+    return (m / 32) * kW4ABlock + 24 * (32 * (c8 >> 2) + m % 32) + 12 * ((c8 & 3) >> 1) + ((c8 & 1) ? 8 : 0);
+}
+__device__ __forceinline__ int w4_scale_offset(int m) { return (m / 32) * kW4ABlock + kW4ACodes + 4 * (m % 32); }
+
 // FMT 0: INT4 codes with fp16 group scales; FMT 1: MXFP4 (E2M1 codes, one power-of-two scale byte per block of 32)
 template <int RBMAX, int WAVES, bool QUANT, bool PROJ, bool STAGE, int FMT>
 __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) ? 2 : 1) void act_kernel(ActParams p) {
@@ -99,15 +106,22 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     // rows past M read the last row; what they produce lands in padding rows and is never used
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.X, (size_t)p.M * p.K * 2);
     const __amdgpu_buffer_rsrc_t rs_l = make_rsrc(p.l1s, (size_t)p.K * p.rank * 2);
-    const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, (size_t)p.G * p.Mpad * (FMT ? kFp4RowBytes : kActBytes));
+    const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, FMT ? (size_t)p.G * p.Mpad * kFp4RowBytes : w4_a_bytes(p.G, p.Mpad));
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sx, FMT ? fp4_scale_bytes(p.G, p.Mpad) : (size_t)p.G * p.Mpad * 2);
     // (byte offsets below 2^32: the entry point refuses batches of 2^31 elements or more; unsigned on purpose)
     const int vxa = (int)(((uint32_t)(ma < p.M ? ma : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
     const int vxb = (int)(((uint32_t)(mb < p.M ? mb : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
     // MXFP4: a lane's 8 channels are a quarter of block c8 / 4 of its token; its 8 codes are one dword
-    const int vca = FMT ? (int)fp4_code_offset(0, p.Mpad, ma, c8 >> 2) + 4 * (c8 & 3) : (int)act_chunk_offset(0, p.Mpad, ma, c8 >> 1) + 8 * (c8 & 1);
-    const int vcb = FMT ? (int)fp4_code_offset(0, p.Mpad, mb, c8 >> 2) + 4 * (c8 & 3) : (int)act_chunk_offset(0, p.Mpad, mb, c8 >> 1) + 8 * (c8 & 1);
-    const int vsx = FMT ? (int)fp4_scale_offset(0, p.Mpad, (c8 & 1) ? mb : ma, c8 >> 2) : ((c8 & 1) ? mb : ma) * 2;
+    // INT4: the lane's 8 channels are half of one 16-channel triple (three registers of the GEMM's 6-bit operand form,
+    // layout.h) of operand lane 32 (c8 / 4) + m % 32; the even lane of a pair stores the triple's first two dwords,
+    // the odd lane the third, and lane c8 = 1 also the token's scale dword (w4_int4_offsets below)
+    const int vca = FMT ? (int)fp4_code_offset(0, p.Mpad, ma, c8 >> 2) + 4 * (c8 & 3) : w4_triple_offset(ma, c8);
+    const int vcb = FMT ? (int)fp4_code_offset(0, p.Mpad, mb, c8 >> 2) + 4 * (c8 & 3) : w4_triple_offset(mb, c8);
+    const int vsx = FMT ? (int)fp4_scale_offset(0, p.Mpad, (c8 & 1) ? mb : ma, c8 >> 2) : 0;
+    // second INT4 store of a lane: the triple's second dword (even lanes), the token's scale (lane c8 = 1), or the
+    // third dword once more (the other odd lanes: same value to the same address)
+    const int vca2 = (c8 & 1) ? (c8 == 1 ? w4_scale_offset(ma) : vca) : vca + 4;
+    const int vcb2 = (c8 & 1) ? (c8 == 1 ? w4_scale_offset(mb) : vcb) : vcb + 4;
     struct XStage { uint4 x0, x1; };                   // 8 bf16 activations of token r8 and of token r8 + 8
     struct BStage { uint4 b[PROJ ? 2 * RBMAX : 1]; };  // L1s fragments: k steps 0 and 1 of every 16-column block
     // STAGE: the fragments of the next two groups wait in registers (at rank 128 this fills the register file
@@ -231,12 +245,12 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     };
     // Eq. 1 for the 8 channels this lane holds of one token's group: s = max|x| / q_max over the whole group
     // (8 lanes), stored as fp16; codes from x * (1/s).
-    // The codes leave as int8 = 16 * code, the operand form of the int8 MFMA in the GEMM, in the byte order in
-    // which the GEMM's nibble widening leaves the weight codes (act_byte_pos: a lane's 8 channels are one half
-    // of a 16-byte chunk, channel i at byte 4*(i%2) + i/2 of the half).
-    // q * 16 + 128 lies in [16, 240]: v_cvt_pk_u8_f32 converts it and drops it into its byte in one
-    // instruction, and flipping bit 7 of every byte afterwards takes the 128 off again (two's complement)
-    auto encode = [&](const float (&xh)[QUANT ? 8 : 1], uint2 &bytes, uint16_t &sbits) {
+    // The codes leave in the operand form of the GEMM's matrix instruction (layout.h): 6 bits per code, sign, two
+    // zero bits, magnitude; the lane's 8 codes are 48 bits (lo: bits 0-31, hi: bits 32-47), channel e at bit 6 e.
+    // Magnitudes are integer-valued floats below 8, so four of them pack exactly into one float by Horner steps
+    // with 64 (< 2^21) and one conversion; the sign of a code is the sign of x^ (1 / lambda and 1 / s are
+    // positive; a zero code may carry a sign, which the format ignores).
+    auto encode = [&](const float (&xh)[QUANT ? 8 : 1], uint32_t &lo, uint32_t &hi, uint32_t &sbits) {
         float amax = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xh[e]));
@@ -256,14 +270,21 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
         const float y0 = __builtin_amdgcn_rcpf(den);
         const float rcp_any = __builtin_fmaf(__builtin_fmaf(-den, y0, 1.0f), y0, y0);
         const float rcp = sc > 0.f ? rcp_any : 0.f;
-        uint32_t w[2] = {0u, 0u};
+        float mag[8];
+        uint32_t sa = 0u, sb = 0u;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float q = __builtin_rintf(xh[e] * rcp);
-            q = fminf(7.f, fmaxf(-7.f, q));
-            w[e & 1] = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(q, 16.f, 128.f), e >> 1, w[e & 1]);
+            mag[e] = fminf(fabsf(__builtin_rintf(xh[QUANT ? e : 0] * rcp)), 7.f);
+            const uint32_t bits = __float_as_uint(xh[QUANT ? e : 0]);
+            const int pos = 6 * (e & 3) + 5;                      // sign position inside the 24 bits of four codes
+            if (e < 4) sa |= (bits >> (31 - pos)) & (1u << pos);
+            else sb |= (bits >> (31 - pos)) & (1u << pos);
         }
-        bytes = make_uint2(w[0] ^ 0x80808080u, w[1] ^ 0x80808080u);
+        const float fa = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(mag[3], 64.f, mag[2]), 64.f, mag[1]), 64.f, mag[0]);
+        const float fb = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(mag[QUANT ? 7 : 0], 64.f, mag[QUANT ? 6 : 0]), 64.f, mag[QUANT ? 5 : 0]), 64.f, mag[QUANT ? 4 : 0]);
+        const uint32_t a24 = (uint32_t)fa | sa, b24 = (uint32_t)fb | sb;
+        lo = a24 | (b24 << 24);
+        hi = b24 >> 8;
         sbits = __builtin_bit_cast(uint16_t, sh);
     };
     // Eq. 1 for one MXFP4 block (the 32 channels held by 4 neighbouring lanes): the scale is the smallest power
@@ -302,17 +323,25 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
             __builtin_amdgcn_raw_buffer_store_b8((uint8_t)((c8 & 1) ? bb : ba), rs_s, vsx, (g >> 2) * p.Mpad * 8 + (g & 3), 0);
         }
         if (QUANT && FMT == 0) {
-            uint2 ca, cb;
-            uint16_t sa, sb;
-            encode(sm.a, ca, sa);
-            encode(sm.b, cb, sb);
-            // Unconditional stores: rows past M land in the padding rows of the workspace (it is sized for
-            // Mpad rows); each store instruction fills four whole 128-byte lines.  Even lanes write the
-            // scale of token r8, odd lanes that of token r8 + 8 (four lanes each, the same value).
-            const int sc = g * p.Mpad * kActBytes;      // one group of codes: Mpad rows of 64 bytes
-            __builtin_amdgcn_raw_buffer_store_b64(u32x2{ca.x, ca.y}, rs_c, vca, sc, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(u32x2{cb.x, cb.y}, rs_c, vcb, sc, 0);
-            __builtin_amdgcn_raw_buffer_store_b16((c8 & 1) ? sb : sa, rs_s, vsx, g * p.Mpad * 2, 0);
+            uint32_t alo, ahi, blo, bhi, sa, sb;
+            encode(sm.a, alo, ahi, sa);
+            encode(sm.b, blo, bhi, sb);
+            // Two neighbouring lanes hold the 16 codes of one triple = 96 bits: dword 0 is the even lane's low word,
+            // dword 1 the even lane's high 16 bits and the odd lane's low 16, dword 2 the rest of the odd lane.
+            const uint32_t na = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)alo, 0xB1, 0xf, 0xf, true);      // the pair's other lane
+            const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)blo, 0xB1, 0xf, 0xf, true);
+            const bool odd = c8 & 1;
+            const uint32_t a1 = odd ? ((alo >> 16) | (ahi << 16)) : alo;                // first store: dword 2 (odd) or dword 0 (even)
+            const uint32_t b1 = odd ? ((blo >> 16) | (bhi << 16)) : blo;
+            const uint32_t a2 = odd ? (c8 == 1 ? sa : a1) : (ahi | (na << 16));         // second: the scale, dword 2 again, or dword 1
+            const uint32_t b2 = odd ? (c8 == 1 ? sb : b1) : (bhi | (nb << 16));
+            // Unconditional stores, the same four for every lane: rows past M land in the padding rows of the
+            // workspace (it is sized for Mpad rows).
+            const int sc = g * (p.Mpad / 32) * kW4ABlock;      // one group of blocks
+            __builtin_amdgcn_raw_buffer_store_b32(a1, rs_c, vca, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(b1, rs_c, vcb, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(a2, rs_c, vca2, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(b2, rs_c, vcb2, sc, 0);
         }
     };
 
@@ -415,12 +444,15 @@ __global__ void debug_act_kernel(DebugActParams p) {
     if (p.out_codes && idx < ncodes) {
         const int m = (int)(idx / p.K), k = (int)(idx % p.K);
         const int g = k / 64, kk = k % 64;
-        const int8_t b = (int8_t)p.codes[act_chunk_offset(g, p.Mpad, m, kk >> 4) + act_byte_pos(kk & 15)];
-        p.out_codes[idx] = (int8_t)(b >> 4);
+        const uint8_t *lane = p.codes + w4_a_block(g, p.Mpad, m) + 24 * (32 * (kk / 32) + m % 32);
+        const int bit = 6 * (kk % 32);
+        const uint32_t two = (uint32_t)lane[bit / 8] | ((uint32_t)lane[bit / 8 + 1] << 8);      // a code spans at most two bytes (bit / 8 + 1 <= 23)
+        const int c = (int)((two >> (bit % 8)) & 63u);
+        p.out_codes[idx] = (int8_t)((c & 32) ? -(c & 7) : (c & 7));
     }
     if (p.out_sx && idx < (size_t)p.M * p.G) {
         const int m = (int)(idx / p.G), g = (int)(idx % p.G);
-        p.out_sx[idx] = p.sx[(size_t)g * p.Mpad + m];
+        p.out_sx[idx] = *reinterpret_cast<const uint16_t *>(p.codes + w4_a_block(g, p.Mpad, m) + kW4ACodes + 4 * (m % 32));
     }
     if (p.out_H && idx < (size_t)p.M * p.rank) p.out_H[idx] = p.H[idx];
 }

@@ -1,8 +1,6 @@
 // C-ABI entry points that run on the GPU: argument checks, workspace carve-up, kernel launches.
 // Nothing here allocates device memory or synchronises with the host.
 #include <hip/hip_runtime.h>
-#include <atomic>
-#include <cstdlib>
 
 #include "../../include/svdq.h"
 #include "kernels.h"
@@ -11,8 +9,10 @@
 namespace {
 
 thread_local int g_last_hip_error = 0;
-std::atomic<int> g_options{0};
-std::atomic<void *> g_profile_event{nullptr};
+// measurement switches and the profiling event belong to the calling thread: a thread that times the unfused
+// pipeline does not change what another thread's forward runs
+thread_local int g_options = 0;
+thread_local void *g_profile_event = nullptr;
 
 int hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -34,33 +34,15 @@ int check_layer(const svdq_layer_dev *L, int group = svdq::kGroup) {
     return SVDQ_OK;
 }
 
-int tile_override() {
-    const int opt = (g_options.load() & SVDQ_OPT_TILE_MASK) >> SVDQ_OPT_TILE_SHIFT;
-    if (opt) return opt;
-    static const int v = [] {
-        const char *e = std::getenv("SVDQ_GEMM_TILE");
-        return e ? std::atoi(e) : 0;
-    }();
-    return v;
-}
+// forced K split of the calling thread's option word (0 = by shape)
+int ksplit_override() { return (g_options & SVDQ_OPT_KSPLIT_MASK) >> SVDQ_OPT_KSPLIT_SHIFT; }
 
-// experiments only: force the K split of small launches (read once)
-int ksplit_override() {
-    static const int v = [] {
-        const char *e = std::getenv("SVDQ_GEMM_KSPLIT");
-        return e ? std::atoi(e) : 0;
-    }();
-    return v;
-}
-
-svdq::GemmParams gemm_params(const svdq_layer_dev *L, unsigned char *ws, const svdq::Workspace &w, int M, void *Y, int rank) {
+svdq::GemmW4Params gemm_params(const svdq_layer_dev *L, unsigned char *ws, const svdq::Workspace &w, int M, void *Y, int rank) {
     const svdq_shape &s = L->shape;
-    svdq::GemmParams g{};
-    g.xcodes = ws + w.codes_off;
-    g.sx = reinterpret_cast<const uint16_t *>(ws + w.sx_off);
+    svdq::GemmW4Params g{};
+    g.xa = ws + w.codes_off;
     g.hfrag = ws + w.hfrag_off;
-    g.wcodes = static_cast<const uint8_t *>(L->wcodes);
-    g.sw = static_cast<const uint16_t *>(L->wscales);
+    g.wb = static_cast<const uint8_t *>(L->wcodes);
     g.l2t = static_cast<const uint16_t *>(L->l2);
     g.bias = static_cast<const float *>(L->bias);
     g.Y = static_cast<uint16_t *>(Y);
@@ -68,11 +50,17 @@ svdq::GemmParams gemm_params(const svdq_layer_dev *L, unsigned char *ws, const s
     g.Mpad = w.Mpad; g.Npad = svdq::round_up(s.N, svdq::kRowPad);
     g.rank = rank;
     g.dbg = nullptr;
-    g.magic = svdq::kMagicBits;
     g.ksplit = 1;
     g.partial = reinterpret_cast<float *>(ws + w.partial_off);
     g.counters = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     return g;
+}
+
+// what every INT4 entry point checks about the sizes its kernels address with 32-bit byte offsets
+bool int4_sizes_ok(const svdq_shape &s, int Mpad) {
+    const int G = s.K / svdq::kGroup;
+    return (unsigned long long)Mpad * s.K < (1ull << 31) && svdq::w4_a_bytes(G, Mpad) < ((size_t)1 << 31) &&
+           svdq::w4_b_bytes(G, svdq::round_up(s.N, svdq::kRowPad)) < ((size_t)1 << 31);
 }
 
 }  // namespace
@@ -82,12 +70,13 @@ extern "C" {
 int svdq_last_hip_error(void) { return g_last_hip_error; }
 
 int svdq_forward_options(int flags) {
-    if (flags < 0) return g_options.load();
-    return g_options.exchange(flags & (SVDQ_OPT_SKIP_LOWRANK | SVDQ_OPT_UNFUSED | SVDQ_OPT_TILE_MASK));
+    const int old = g_options;
+    if (flags >= 0) g_options = flags & (SVDQ_OPT_SKIP_LOWRANK | SVDQ_OPT_UNFUSED | SVDQ_OPT_KSPLIT_MASK);
+    return old;
 }
 
 int svdq_profile_event(void *hip_event) {
-    g_profile_event.store(hip_event);
+    g_profile_event = hip_event;
     return SVDQ_OK;
 }
 
@@ -110,12 +99,11 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     // the activation kernel keeps 1 / lambda of all K channels in LDS beside its per-wavefront blocks
     if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
-    // the kernels address X, the activation codes and the weight codes with 32-bit byte offsets
-    if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
-        return SVDQ_EUNSUPPORTED;
+    // the kernels address X, the activation blocks and the weight blocks with 32-bit byte offsets
+    if (!int4_sizes_ok(s, w.Mpad)) return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
-    const int opts = g_options.load();
+    const int opts = g_options;
     const bool lowrank = s.rank > 0 && !(opts & SVDQ_OPT_SKIP_LOWRANK);
     const bool unfused = opts & SVDQ_OPT_UNFUSED;
 
@@ -124,28 +112,26 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     a.rinv = static_cast<const float *>(L->rinv);
     a.l1s = static_cast<const uint16_t *>(L->l1s);
     a.codes = ws + w.codes_off;
-    a.sx = reinterpret_cast<uint16_t *>(ws + w.sx_off);
+    a.sx = nullptr;
     a.H = reinterpret_cast<float *>(ws + w.h_off);
     a.hfrag = ws + w.hfrag_off;
     a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
     a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     a.n_zero = w.n_counters;
-    // a forced tile shape runs without the K split; otherwise tile and split follow the plan the workspace was sized for
+    // tile count and K split follow the plan the workspace was sized for
     const svdq::GemmPlan plan = svdq::plan_gemm(M, s.N, s.K / svdq::kGroup, ksplit_override());
-    const int tile = tile_override() ? tile_override() : plan.tile;
-    const int ksplit = tile_override() ? 1 : plan.ksplit;
 
     hipError_t e;
     if (!unfused) {
         e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
         if (e != hipSuccess) return hip_fail(e);
-        if (void *ev = g_profile_event.load()) {
+        if (void *ev = g_profile_event) {
             e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
             if (e != hipSuccess) return hip_fail(e);
         }
-        svdq::GemmParams g = gemm_params(L, ws, w, M, Y, lowrank ? s.rank : 0);
-        g.ksplit = ksplit;
-        e = svdq::launch_gemm(g, tile, stream);
+        svdq::GemmW4Params g = gemm_params(L, ws, w, M, Y, lowrank ? s.rank : 0);
+        g.ksplit = plan.ksplit;
+        e = svdq::launch_gemm_w4a4(g, stream);
         if (e != hipSuccess) return hip_fail(e);
     } else {
         // the four-kernel pipeline of Fig. 6a: down projection, quantize, 4-bit GEMM, up projection
@@ -155,9 +141,9 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
         }
         e = svdq::launch_act(a, 1, stream);
         if (e != hipSuccess) return hip_fail(e);
-        svdq::GemmParams g = gemm_params(L, ws, w, M, Y, 0);
-        g.ksplit = ksplit;
-        e = svdq::launch_gemm(g, tile, stream);
+        svdq::GemmW4Params g = gemm_params(L, ws, w, M, Y, 0);
+        g.ksplit = plan.ksplit;
+        e = svdq::launch_gemm_w4a4(g, stream);
         if (e != hipSuccess) return hip_fail(e);
         if (lowrank) {
             e = svdq::launch_upproj(a.hfrag, g.l2t, g.Y, M, s.N, s.rank, stream);
@@ -178,7 +164,6 @@ int svdq_debug_act(const svdq_layer_dev *L, const void *workspace, int M, int8_t
     const unsigned char *ws = static_cast<const unsigned char *>(workspace);
     svdq::DebugActParams d{};
     d.codes = ws + w.codes_off;
-    d.sx = reinterpret_cast<const uint16_t *>(ws + w.sx_off);
     d.H = reinterpret_cast<const float *>(ws + w.h_off);
     d.out_codes = out_codes; d.out_sx = out_sx; d.out_H = s.rank > 0 ? out_H : nullptr;
     d.M = M; d.K = s.K; d.G = s.K / svdq::kGroup; d.Mpad = w.Mpad; d.rank = s.rank;
@@ -195,10 +180,9 @@ int svdq_debug_group_acc(const svdq_layer_dev *L, const void *workspace, int M, 
     const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
     unsigned char *ws = const_cast<unsigned char *>(static_cast<const unsigned char *>(workspace));
     // the window-export instantiation of the kernel never stores Y
-    svdq::GemmParams g = gemm_params(L, ws, w, M, nullptr, 0);
+    svdq::GemmW4Params g = gemm_params(L, ws, w, M, nullptr, 0);
     g.dbg = out; g.m0 = m0; g.m1 = m1; g.n0 = n0; g.n1 = n1;
-    const int tile = tile_override() ? tile_override() : svdq::plan_gemm(M, s.N, s.K / svdq::kGroup).tile;
-    const hipError_t e = svdq::launch_gemm(g, tile, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = svdq::launch_gemm_w4a4(g, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SVDQ_OK : hip_fail(e);
 }
 
@@ -226,7 +210,7 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
         return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
-    const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
+    const bool lowrank = s.rank > 0 && !(g_options & SVDQ_OPT_SKIP_LOWRANK);
 
     svdq::ActParams a{};
     a.X = static_cast<const uint16_t *>(X);
@@ -242,7 +226,7 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     a.n_zero = w.n_counters;
     hipError_t e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
     if (e != hipSuccess) return hip_fail(e);
-    if (void *ev = g_profile_event.load()) {
+    if (void *ev = g_profile_event) {
         e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -301,11 +285,10 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
     if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
-    if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
-        return SVDQ_EUNSUPPORTED;
+    if (!int4_sizes_ok(s, w.Mpad)) return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
-    const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
+    const bool lowrank = s.rank > 0 && !(g_options & SVDQ_OPT_SKIP_LOWRANK);
     hipError_t e = hipSuccess;
     if (lowrank && M <= svdq::kW4A16ProjRows) {
         // a handful of rows: the projection kernel shaped for them (the activation kernel gives 16 tokens to a workgroup)
@@ -323,7 +306,7 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
         e = svdq::launch_act(a, 2, stream);
         if (e != hipSuccess) return hip_fail(e);
     }
-    if (void *ev = g_profile_event.load()) {
+    if (void *ev = g_profile_event) {
         e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -366,7 +349,7 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
         return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
-    const bool lowrank = s.rank > 0 && !(g_options.load() & SVDQ_OPT_SKIP_LOWRANK);
+    const bool lowrank = s.rank > 0 && !(g_options & SVDQ_OPT_SKIP_LOWRANK);
 
     svdq::Quant8Params q{};
     q.X = static_cast<const uint16_t *>(X);
@@ -388,7 +371,7 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
         e = svdq::launch_act(a, 2, stream);
         if (e != hipSuccess) return hip_fail(e);
     }
-    if (void *ev = g_profile_event.load()) {
+    if (void *ev = g_profile_event) {
         e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
         if (e != hipSuccess) return hip_fail(e);
     }

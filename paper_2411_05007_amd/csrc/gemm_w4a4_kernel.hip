@@ -1,0 +1,592 @@
+// W4A4 GEMM with fused low-rank up projection, bias and bf16 store (arXiv 2411.05007 Eq. 5;
+// Sec. 4.3 / Fig. 6b: "4-Bit Compute" and "Up Projection" share their output).
+//
+//   Y[m][n] = sum_g sx[m][g] sw[g][n] A_g[m][n]  +  sum_j H[m][j] L2[j][n]  +  bias[n]
+//   A_g[m][n] = sum_{k in group g} qx[m][k] qw[k][n]        (exact integer, Eq. 2 per group of 64)
+//
+// gfx950 has no 4-bit integer MFMA.  The INT4 codes reach the matrix core as 6-bit floats (E2M3 with zero
+// exponent bits: sign * |q| / 8, exact for every code, see layout.h) through v_mfma_scale_f32_32x32x64_f8f6f4:
+// ONE instruction per group of 64 and 32 x 32 outputs, at twice the rate of the 8-bit formats, and its fp32
+// result - with both block scales set to 2^3 - is the exact integer group sum (|A_g| <= 3136 < 2^24), so there
+// is no integer-to-float step.  The per-group rescale by sx[m][g] sw[g][n] (one partial sum per 64
+// multiply-accumulates) is what would otherwise bound the kernel on the vector ALU; here the scale products of a
+// 32 x 32 block come from the matrix core as well: they are the rank-1 matrix sx (x) sw, which
+// v_mfma_f32_32x32x8_f16 forms exactly (one non-zero k slot; a product of two fp16 values has 22 significant bits)
+// and in the accumulator layout, so that the vector ALU is left with ONE plain FMA per partial sum:
+//     acc[v] = fma(A_g[v], S_g[v], acc[v]).
+// A register-only loop of {fp6 MFMA, f16 MFMA, 16 FMAs} sustains ~35 ns per block and group and SIMD with two
+// wavefronts per SIMD, against ~31 ns for the two MFMAs alone and ~70 ns for the int8-MFMA formulation with its
+// two FMAs per partial sum.
+//
+// Structure.  A workgroup of four wavefronts owns a (32 RB) x 256 tile; wavefront w owns all its rows and columns
+// 64 w .. 64 w + 63 (RB x 2 blocks of 32 x 32), two workgroups per CU.  Per group the workgroup needs RB activation
+// blocks (shared by the four wavefronts) and eight weight blocks (two per wavefront, private); each block carries
+// its codes and its fp16 scales (layout.h), and all of them go from memory straight into a four-stage LDS ring
+// with direct-to-LDS loads, three groups ahead, no stop in registers.  Weight codes stay at four bits until they
+// are in registers, where three AND / AND-OR operations per pair of registers spread them to the 6-bit form.
+// One barrier per group.  The instruction stream of a wavefront is a chain of slots, one per 32 x 32 block:
+//     MFMA A_g(next block) | 16 FMAs of this block | MFMA S_g(next block)
+// (two buffers for A_g, one for S_g), with the LDS reads of the operands two slots ahead of their use.
+// The accumulators start as H L2 (bf16 MFMAs on the hi and lo parts of H); the epilogue adds the bias, rounds to
+// bf16 and turns every 32 x 64 block through a wavefront-private LDS block so that stores write whole lines.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "buffer.h"
+#include "kernels.h"
+#include "layout.h"
+
+namespace svdq {
+namespace {
+
+typedef int intx8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void *lds_ptr;
+
+constexpr int kFmtE2M3 = 2;                 // operand format selector of the instruction
+// Block scales of the group-sum MFMA, one byte each: 2^3 for the activation codes (undoes their 1/8), 2^1 for the
+// weight codes (their 1/8, and the factor 4 by which the scale tile comes out too large, see op_s below).
+constexpr int kScaleBytes = 0x8082;
+constexpr int kOutRowW4 = 144;              // epilogue staging: 64 bf16 columns + 16 bytes pad per row
+
+#ifndef SVDQ_W4_STAGES
+#define SVDQ_W4_STAGES 3
+#endif
+template <int RB>
+struct W4Tile {
+    static constexpr int kBM = 32 * RB, kBN = 256;
+    static constexpr int kAStage = RB * kW4ABlock;
+    static constexpr int kStage = kAStage + 4 * kW4BBlock;        // 16 KB for RB = 4; a multiple of 256
+    static constexpr int kStages = SVDQ_W4_STAGES;                // measured: two, three and four groups ahead run at the same speed
+    static constexpr int kRing = kStages * kStage;
+    static constexpr int kOutBytes = 4 * 32 * kOutRowW4;
+    static constexpr int kLdsBytes = kRing > kOutBytes ? kRing : kOutBytes;
+    static constexpr int kDmaPerStep = RB == 4 ? 5 : 4;           // direct-to-LDS instructions per wavefront and group
+    static_assert(kStage % 256 == 0 && kW4ABlock % 256 == 0 && kW4ACodes % 256 == 0, "scale reads address in units of 256 bytes");
+};
+
+__device__ __forceinline__ uint32_t bf16_bits_w4(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ uint32_t bf16_pair_w4(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// MODE 0: normal forward.  MODE 1: additionally export the exact group sums of a window (parity checks).
+template <int RB, int MODE>
+__global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
+    using T = W4Tile<RB>;
+    static_assert(RB == 4, "the slot schedule below is written for four row blocks");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lh = lane >> 5;
+    const int wn0 = wave * 64;
+
+    // XCD-aware tile order: workgroups are dealt round-robin to the 8 XCDs (each with its own L2); renumber them so
+    // that an XCD owns a contiguous run of tiles, walked in bands of tile rows
+    const int tiles_m = (p.M + T::kBM - 1) / T::kBM;
+    const int tiles_n = (p.N + T::kBN - 1) / T::kBN;
+    const int total = tiles_m * tiles_n;
+    const int split = (int)blockIdx.x / total;
+    const int bid = (int)blockIdx.x - split * total;
+    const int g_per = (p.G + p.ksplit - 1) / p.ksplit;
+    const int g_begin = split * g_per;
+    const int g_end = g_begin + g_per < p.G ? g_begin + g_per : p.G;
+    int tile_m, tile_n;
+    {
+        const int per = (total + 7) / 8;
+        const int id = (total % 8 == 0) ? (bid % 8) * per + (bid / 8) : bid;      // a bijection only when 8 divides the count
+        constexpr int kBand = 4;
+        const int band = id / (kBand * tiles_n);
+        const int band_rows = (tiles_m - band * kBand) < kBand ? (tiles_m - band * kBand) : kBand;
+        const int in = id - band * kBand * tiles_n;
+        tile_m = band * kBand + in % band_rows;
+        tile_n = in / band_rows;
+    }
+    const int gm0 = tile_m * T::kBM, gn0 = tile_n * T::kBN;      // the launch checks that every tile lies inside the padded rows and columns
+    if (MODE == 1) {   // window export: only tiles that touch the window do any work (uniform per workgroup)
+        if (gm0 >= p.m1 || gm0 + T::kBM <= p.m0 || gn0 >= p.n1 || gn0 + T::kBN <= p.n0) return;
+    }
+
+    // Plain scalars, not 16-wide vectors: the rescale FMAs then compile to the two-address v_fmac_f32, which two
+    // wavefronts together issue 1.5 times as fast as the three-address v_fma_f32 that updating a vector element gets
+    // (measured: 2.4 against 3.5 cycles per instruction and SIMD).
+    float acc[RB][2][16];
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+
+    // ---- memory -> LDS -------------------------------------------------------------------------------------------
+    // Per group the tile's RB activation blocks are contiguous (1792 bytes each, 1664 of them used), and a wavefront's
+    // 64 columns are one weight block (2304 bytes).  Wavefront w copies activation block w (1024 + 640 bytes: the
+    // second request runs on 40 lanes) and its own weight block (1024 + 1024 + 256 bytes).  A lane's 16 bytes land
+    // at 16 * lane of the request's LDS destination, so the LDS image is the memory image.
+    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.xa, w4_a_bytes(p.G, p.Mpad));
+    const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(p.wb, w4_b_bytes(p.G, p.Npad));
+    const int a_stride = (p.Mpad / 32) * kW4ABlock, b_stride = (p.Npad / 64) * kW4BBlock;
+    const int a_base = (gm0 / 32 + wave) * kW4ABlock;
+    const int b_base = (gn0 / 64 + wave) * kW4BBlock;
+    const int glast = g_end - 1;
+    auto dma = [&](int g, int stage) {
+        const int gc = g < glast ? g : glast;      // past the end: the last group once more (never used), so that every step issues the same requests
+        unsigned char *sa = lds + stage * T::kStage + wave * kW4ABlock;
+        unsigned char *sb = lds + stage * T::kStage + T::kAStage + wave * kW4BBlock;
+        const int oa = a_base + gc * a_stride, ob = b_base + gc * b_stride;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)sa, 16, lane * 16, oa, 0, 0);
+        if (lane < 40) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)(sa + 1024), 16, lane * 16, oa + 1024, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)sb, 16, lane * 16, ob, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(sb + 1024), 16, lane * 16, ob + 1024, 0, 0);
+        if (lane < 16) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(sb + 2048), 16, lane * 16, ob + 2048, 0, 0);
+    };
+
+    // ---- LDS -> registers ----------------------------------------------------------------------------------------
+    // These reads are written as instructions of their own, with explicit waits: the compiler would make every
+    // LDS read wait for ALL outstanding memory-to-LDS requests, also those of later stages.  LDS operations of a
+    // wavefront complete in order, so "all but the newest n" is an exact wait.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    const uint32_t la_a = lds_base + lane * 24;                                         // activation codes: 24 bytes per lane
+    const uint32_t la_sx = lds_base + li * 4;                                           // activation scales (+ 1536 + 1792 r through the offset field): both lane halves read the row's scale
+    const uint32_t la_b = lds_base + T::kAStage + wave * kW4BBlock + lane * 16;         // weight codes: 16 bytes per lane
+    const uint32_t la_sw = lds_base + T::kAStage + wave * kW4BBlock + kW4BCodes + li * 4;   // weight scales (+ 128 c through the offset field)
+    struct AFrag { u32x2 d[3]; };
+    struct BRaw { u32x4 d; };
+    struct BFrag { uint32_t d[6]; };
+// (early-clobber outputs: the three reads of one statement share the address register, which must not be one of
+// the destinations)
+#define W4_READ_A(F, ADDR, R) \
+    asm volatile("ds_read_b64 %0, %3 offset:%4\n\tds_read_b64 %1, %3 offset:%5\n\tds_read_b64 %2, %3 offset:%6" \
+                 : "=&v"(F.d[0]), "=&v"(F.d[1]), "=&v"(F.d[2]) : "v"(ADDR), "n"((R) * kW4ABlock), "n"((R) * kW4ABlock + 8), "n"((R) * kW4ABlock + 16))
+// A scale dword (fp16 scale, zero high half) read into BOTH registers of the f16 MFMA's operand: k slots 0 and 2 of
+// the lane's half then hold the scale and slots 1 and 3 zero.  With both operands built this way and both lane
+// halves reading the same row (column), the MFMA returns 4 sx sw; the group-sum MFMA's block scale takes the 4 out.
+#define W4_READ_SX(X, ADDR, R) asm volatile("ds_read2st64_b32 %0, %1 offset0:%2 offset1:%2" : "=v"(X) : "v"(ADDR), "n"((kW4ACodes + (R) * kW4ABlock) / 256))
+#define W4_READ_SW(X, ADDR, C) asm volatile("ds_read2_b32 %0, %1 offset0:%2 offset1:%2" : "=v"(X) : "v"(ADDR), "n"((C) * 32))
+#define W4_READ_B(Q, ADDR, C) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(Q.d) : "v"(ADDR), "n"((C) * 1024))
+#define W4_WAIT_LGKM(N, ...) asm volatile("s_waitcnt lgkmcnt(" #N ")" : __VA_ARGS__)
+
+    // the six operand registers of 32 weight codes from their four stored registers (layout.h)
+    auto expand = [&](BFrag &f, const BRaw &q) {
+        f.d[0] = q.d.x & ~kW4Z0;
+        f.d[1] = q.d.y & ~kW4Z1;
+        f.d[2] = (q.d.x & kW4Z0) | (q.d.y & kW4Z1);
+        f.d[3] = q.d.z & ~kW4Z0;
+        f.d[4] = q.d.w & ~kW4Z1;
+        f.d[5] = (q.d.z & kW4Z0) | (q.d.w & kW4Z1);
+    };
+    auto op_a = [&](const AFrag &f) { return intx8{(int)f.d[0].x, (int)f.d[0].y, (int)f.d[1].x, (int)f.d[1].y, (int)f.d[2].x, (int)f.d[2].y, 0, 0}; };
+    auto op_b = [&](const BFrag &f) { return intx8{(int)f.d[0], (int)f.d[1], (int)f.d[2], (int)f.d[3], (int)f.d[4], (int)f.d[5], 0, 0}; };
+    auto op_s = [&](u32x2 x) { return __builtin_bit_cast(halfx4, x); };
+    const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int scales = kScaleBytes;
+    asm volatile("" : "+v"(scales));      // one vector register for good (the scale operand cannot be a constant)
+
+#pragma unroll
+    for (int i = 0; i < T::kStages - 1; ++i) dma(g_begin + i, i);
+    __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
+
+    // ---- low-rank up projection: the accumulators START as H L2 (bf16 MFMAs, H as exact hi + lo parts) -----------
+    if (MODE == 0 && p.rank > 0 && split == 0) {      // one split carries the low-rank product
+        const int ksteps = p.rank / 16;
+        const unsigned char *hf = p.hfrag + (size_t)(gm0 / 32) * ksteps * 2048 + lane * 16;
+        struct LowRank { uint4 hhi[RB], hlo[RB], braw[2]; };
+        floatx16 lr[RB][2];
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) lr[r][c] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        auto load_step = [&](LowRank &o, int ks) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const unsigned char *hp = hf + ((size_t)r * ksteps + ks) * 2048;
+                o.hhi[r] = *reinterpret_cast<const uint4 *>(hp);
+                o.hlo[r] = *reinterpret_cast<const uint4 *>(hp + 1024);
+            }
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int col = gn0 + wn0 + c * 32 + li;        // < Npad
+                o.braw[c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
+            }
+        };
+        auto multiply = [&](const LowRank &o) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const bf16x8 bl = __builtin_bit_cast(bf16x8, o.braw[c]);
+#pragma unroll
+                for (int r = 0; r < RB; ++r) {
+                    lr[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hhi[r]), bl, lr[r][c], 0, 0, 0);
+                    lr[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hlo[r]), bl, lr[r][c], 0, 0, 0);
+                }
+            }
+        };
+        LowRank e, o;
+        load_step(e, 0);
+        for (int ks = 0; ks < ksteps; ks += 2) {
+            if (ks + 1 < ksteps) load_step(o, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(e);
+            if (ks + 1 < ksteps) {
+                if (ks + 2 < ksteps) load_step(e, ks + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(o);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[r][c][v] = lr[r][c][v];
+    }
+
+    // ---- main loop -----------------------------------------------------------------------------------------------
+    // Step g handles group g in eight slots t = 2 r + c (row block r, column block c).  Slot t issues the group-sum
+    // MFMA of block t + 1, the sixteen FMAs of block t, and the scale-tile MFMA of block t + 1 (block 8 = block 0 of
+    // group g + 1).  Operand registers: two activation fragments (row blocks alternate between them), the two
+    // expanded weight fragments (refreshed in place in slots 6 and 7), one scale operand per row block and per
+    // column block.
+    AFrag af[2];
+    BRaw braw[2];
+    BFrag bfr[2];
+    u32x2 sxr[RB], swr[2];
+    floatx16 ag[2], sg;
+    uint32_t st_cur = 0, st_nxt = T::kStage;      // byte offsets of the stages of group g and g + 1
+    int st_free = T::kStages - 1;                 // index of the stage that the requests of the top of the step fill
+
+    auto export_sums = [&](const floatx16 &d, int g, int r, int c) {
+        if (MODE == 1) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = gm0 + r * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                const int col = gn0 + wn0 + c * 32 + li;
+                if (row >= p.m0 && row < p.m1 && col >= p.n0 && col < p.n1)
+                    p.dbg[((size_t)(row - p.m0) * (p.n1 - p.n0) + (col - p.n0)) * p.G + g] = (int32_t)(4.0f * d[v]);
+            }
+        }
+    };
+// The order of a slot is pinned with empty asm statements that "rewrite" a value: the FMAs read the scale tile as
+// rewritten after the group-sum MFMA was issued, and the scale-tile MFMA reads an operand rewritten after the FMAs
+// (volatile asm statements keep their order; plain builtins would be moved to where the register pressure is lowest).
+#define W4_MFMA_A(DST, AF, BF)                                                                                                          \
+    DST = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(op_a(AF), op_b(BF), zero16, kFmtE2M3, kFmtE2M3, 0, scales, 1, scales);       \
+    asm volatile("" : "+v"(DST), "+v"(sg))
+#define W4_MFMA_S(R, C, SX, SW)                                                         \
+    asm volatile("" : "+v"(acc[R][C][0]), "+v"(acc[R][C][15]), "+v"(SX));              \
+    sg = __builtin_amdgcn_mfma_f32_32x32x8f16(op_s(SX), op_s(SW), zero16, 0, 0, 0);    \
+    asm volatile("" : "+v"(sg))
+#define W4_FMA(R, C, AG)                                                                           \
+    _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[R][C][v] = __builtin_fmaf(AG[v], sg[v], acc[R][C][v]);
+#define W4_SB() __builtin_amdgcn_sched_barrier(0)
+
+    // first operands: stage 0 is complete when all but the newest kStages - 2 groups of requests have landed
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((T::kStages - 2) * T::kDmaPerStep) : "memory");
+    __builtin_amdgcn_s_barrier();
+    {
+        W4_READ_A(af[0], la_a, 0);
+        W4_READ_B(braw[0], la_b, 0);
+        W4_READ_B(braw[1], la_b, 1);
+        W4_READ_SX(sxr[0], la_sx, 0);
+        W4_READ_SW(swr[0], la_sw, 0);
+        W4_READ_SW(swr[1], la_sw, 1);
+        W4_READ_A(af[1], la_a, 1);
+        W4_READ_SX(sxr[1], la_sx, 1);
+        W4_READ_SX(sxr[2], la_sx, 2);
+        W4_READ_SX(sxr[3], la_sx, 3);
+        W4_WAIT_LGKM(0, "+v"(af[0].d[0]), "+v"(af[0].d[1]), "+v"(af[0].d[2]), "+v"(af[1].d[0]), "+v"(af[1].d[1]), "+v"(af[1].d[2]),
+                     "+v"(braw[0].d), "+v"(braw[1].d), "+v"(sxr[0]), "+v"(sxr[1]), "+v"(sxr[2]), "+v"(sxr[3]), "+v"(swr[0]), "+v"(swr[1]));
+        expand(bfr[0], braw[0]);
+        expand(bfr[1], braw[1]);
+        sg = zero16;
+        W4_MFMA_A(ag[0], af[0], bfr[0]);
+        sg = __builtin_amdgcn_mfma_f32_32x32x8f16(op_s(sxr[0]), op_s(swr[0]), zero16, 0, 0, 0);
+        asm volatile("" : "+v"(sg));
+    }
+    W4_SB();
+
+    // LDS reads of a step, in issue order (each right behind the group-sum MFMA of its slot, so that it fills the
+    // wait between that MFMA and the first FMA):  slot 0: row block 2 (3 reads) | 1: sx 0', weights' (2) | 2: row
+    // block 3 (3) | 3: sx 1' | 4: row block 0' (3) | 5: sx 2' | 6: row block 1' (3), sw 0' | 7: sx 3', sw 1'
+    // (' = of the next group).  The waits name how many newer reads may still be in flight.
+    for (int g = g_begin; g < g_end; ++g) {
+        const uint32_t aa_c = la_a + st_cur, aa_n = la_a + st_nxt, ax_n = la_sx + st_nxt, ab_n = la_b + st_nxt, aw_n = la_sw + st_nxt;
+        W4_SB();
+        // slot 0: block (0,0); next (0,1).  Behind its group-sum MFMA sits the top of the step: stage g + 1 complete
+        // (the wavefront's own requests by its wait, the others' by the barrier), the stage of group g - 1 free for
+        // the requests of group g + kStages - 1.  Nothing before this point in the step reads stage g + 1.
+        W4_MFMA_A(ag[1], af[0], bfr[1]);
+        W4_READ_A(af[0], aa_c, 2);                       // row block 2 of this group
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((T::kStages - 3) * T::kDmaPerStep) : "memory");
+        __builtin_amdgcn_s_barrier();
+        dma(g + T::kStages - 1, st_free);
+        st_free = st_free + 1 == T::kStages ? 0 : st_free + 1;
+        W4_SB();
+        W4_FMA(0, 0, ag[0]);
+        export_sums(ag[0], g, 0, 0);
+        W4_SB();
+        W4_WAIT_LGKM(3, "+v"(swr[1]));                   // sw 1' (slot 7 of the previous step)
+        W4_MFMA_S(0, 0, sxr[0], swr[1]);
+        W4_SB();
+        // slot 1: block (0,1); next (1,0)
+        W4_WAIT_LGKM(3, "+v"(af[1].d[0]), "+v"(af[1].d[1]), "+v"(af[1].d[2]), "+v"(sxr[1]));      // row block 1 (slot 6 of the previous step)
+        W4_MFMA_A(ag[0], af[1], bfr[0]);
+        W4_READ_SX(sxr[0], ax_n, 0);
+        W4_READ_B(braw[0], ab_n, 0);                     // weight codes of the next group
+        W4_READ_B(braw[1], ab_n, 1);
+        W4_SB();
+        W4_FMA(0, 1, ag[1]);
+        export_sums(ag[1], g, 0, 1);
+        W4_SB();
+        W4_MFMA_S(0, 1, sxr[1], swr[0]);
+        W4_SB();
+        // slot 2: block (1,0); next (1,1)
+        W4_MFMA_A(ag[1], af[1], bfr[1]);
+        W4_READ_A(af[1], aa_c, 3);                       // row block 3 of this group
+        W4_SB();
+        W4_FMA(1, 0, ag[0]);
+        export_sums(ag[0], g, 1, 0);
+        W4_SB();
+        W4_MFMA_S(1, 0, sxr[1], swr[1]);
+        W4_SB();
+        // slot 3: block (1,1); next (2,0)
+        W4_WAIT_LGKM(6, "+v"(af[0].d[0]), "+v"(af[0].d[1]), "+v"(af[0].d[2]));      // row block 2 (slot 0)
+        W4_MFMA_A(ag[0], af[0], bfr[0]);
+        W4_READ_SX(sxr[1], ax_n, 1);
+        W4_SB();
+        W4_FMA(1, 1, ag[1]);
+        export_sums(ag[1], g, 1, 1);
+        W4_SB();
+        W4_MFMA_S(1, 1, sxr[2], swr[0]);
+        W4_SB();
+        // slot 4: block (2,0); next (2,1)
+        W4_MFMA_A(ag[1], af[0], bfr[1]);
+        W4_READ_A(af[0], aa_n, 0);                       // row block 0 of the next group
+        W4_SB();
+        W4_FMA(2, 0, ag[0]);
+        export_sums(ag[0], g, 2, 0);
+        W4_SB();
+        W4_MFMA_S(2, 0, sxr[2], swr[1]);
+        W4_SB();
+        // slot 5: block (2,1); next (3,0)
+        W4_WAIT_LGKM(4, "+v"(af[1].d[0]), "+v"(af[1].d[1]), "+v"(af[1].d[2]), "+v"(braw[0].d), "+v"(braw[1].d));   // row block 3 (slot 2), next weights (slot 1)
+        W4_MFMA_A(ag[0], af[1], bfr[0]);
+        W4_READ_SX(sxr[2], ax_n, 2);
+        W4_SB();
+        W4_FMA(2, 1, ag[1]);
+        export_sums(ag[1], g, 2, 1);
+        W4_SB();
+        W4_MFMA_S(2, 1, sxr[3], swr[0]);
+        W4_SB();
+        // slot 6: block (3,0); next (3,1).  Column block 0 of this group has been multiplied for the last time.
+        W4_MFMA_A(ag[1], af[1], bfr[1]);
+        W4_READ_A(af[1], aa_n, 1);                       // row block 1 of the next group
+        W4_READ_SW(swr[0], aw_n, 0);
+        expand(bfr[0], braw[0]);
+        W4_SB();
+        W4_FMA(3, 0, ag[0]);
+        export_sums(ag[0], g, 3, 0);
+        W4_SB();
+        W4_MFMA_S(3, 0, sxr[3], swr[1]);
+        W4_SB();
+        // slot 7: block (3,1); next (0,0) of group g + 1
+        W4_WAIT_LGKM(5, "+v"(af[0].d[0]), "+v"(af[0].d[1]), "+v"(af[0].d[2]), "+v"(sxr[0]));      // row block 0 of the next group (slot 4)
+        W4_MFMA_A(ag[0], af[0], bfr[0]);
+        W4_READ_SX(sxr[3], ax_n, 3);
+        W4_READ_SW(swr[1], aw_n, 1);
+        expand(bfr[1], braw[1]);
+        W4_SB();
+        W4_FMA(3, 1, ag[1]);
+        export_sums(ag[1], g, 3, 1);
+        W4_SB();
+        W4_WAIT_LGKM(2, "+v"(swr[0]));                   // sw 0' (slot 6)
+        W4_MFMA_S(3, 1, sxr[0], swr[0]);
+        W4_SB();
+        st_cur = st_nxt;
+        st_nxt = st_nxt + T::kStage == (uint32_t)T::kRing ? 0u : st_nxt + T::kStage;
+    }
+    // the ring becomes the epilogue's staging area: every request of every wavefront must have landed, and every LDS read returned
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    if (MODE == 1) return;   // the window export writes no Y
+
+    // ---- split K loop: park the partial tile, the last workgroup to arrive adds them all up ------------------------
+    // Partial tiles are stored in register order (consecutive threads consecutive addresses) with device-scope atomic
+    // accesses: the L2 caches of the chip's eight XCDs are not coherent with each other, and these accesses go past
+    // them; no cache is flushed.  A workgroup takes its ticket once all its stores have been acknowledged; the holder
+    // of the last ticket reads all partials back, its own included, and adds them in split order, so the sum does not
+    // depend on who came last.  Nobody waits for anybody.
+    if (p.ksplit > 1) {
+        const int tile_lin = tile_m * tiles_n + tile_n;
+        constexpr int kTileWords = T::kBM * T::kBN;
+        float *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    __hip_atomic_store(mine + ((r * 2 + c) * 16 + v) * 256, acc[r][c][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // every store of this thread has been acknowledged
+        __syncthreads();
+        uint32_t *ticket = reinterpret_cast<uint32_t *>(lds);      // the ring is no longer in use
+        if (tid == 0) *ticket = __hip_atomic_fetch_add(&p.counters[tile_lin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const bool last = *ticket == (uint32_t)(p.ksplit - 1);
+        __syncthreads();                                          // the epilogue reuses this LDS word
+        if (!last) return;
+        if (tid == 0) __hip_atomic_store(&p.counters[tile_lin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next launch
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+        const float *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
+        for (int sidx = 0; sidx < p.ksplit; ++sidx) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                float t[2][16];      // the 32 values of a row of blocks are requested together, then added: one round trip per batch
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        t[c][v] = __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * 2 + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[r][c][v] += t[c][v];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // ---- epilogue: bias, bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores --------
+    unsigned char *ob = lds + wave * (32 * kOutRowW4);
+    const float bias0 = p.bias[gn0 + wn0 + li], bias1 = p.bias[gn0 + wn0 + 32 + li];      // padded to Npad
+    const bool full = gm0 + T::kBM <= p.M && gn0 + T::kBN <= p.N && (p.N % 8) == 0;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const float b = c ? bias1 : bias0;
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const int row = 8 * (v >> 2) + 4 * lh + (v & 3);      // accumulator register v: row 8 (v / 4) + 4 (lane / 32) + v % 4
+                const uint32_t pr = bf16_pair_w4(acc[r][c][v] + b, acc[r][c][v + 1] + b);
+                *reinterpret_cast<uint16_t *>(ob + row * kOutRowW4 + (c * 32 + li) * 2) = (uint16_t)pr;
+                *reinterpret_cast<uint16_t *>(ob + (row + 1) * kOutRowW4 + (c * 32 + li) * 2) = (uint16_t)(pr >> 16);
+            }
+        }
+        // 32 rows x 128 bytes = 256 chunks of 16 bytes: four per lane, eight lanes per row
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int q = lane + 64 * i;
+            const int row = q >> 3, ch = q & 7;
+            const uint4 v = *reinterpret_cast<const uint4 *>(ob + row * kOutRowW4 + ch * 16);
+            const int grow = gm0 + r * 32 + row;
+            const int gcol = gn0 + wn0 + ch * 8;
+            uint16_t *dst = p.Y + (size_t)grow * p.N + gcol;
+            if (full) {
+                *reinterpret_cast<uint4 *>(dst) = v;
+            } else if (grow < p.M) {
+                const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
+                                       (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (gcol + k < p.N) dst[k] = e[k];
+            }
+        }
+    }
+}
+
+template <int RB>
+hipError_t launch_w4_tile(const GemmW4Params &p, hipStream_t stream) {
+    using T = W4Tile<RB>;
+    const int tiles_m = (p.M + T::kBM - 1) / T::kBM, tiles_n = (p.N + T::kBN - 1) / T::kBN;
+    // H, L2 and the bias are read with plain loads: every tile must lie inside the padded rows and columns
+    if (tiles_m * T::kBM > p.Mpad || tiles_n * T::kBN > p.Npad) return hipErrorInvalidValue;
+    const dim3 grid(tiles_m * tiles_n * p.ksplit), block(256);
+    if (p.dbg) {
+        auto k = gemm_w4a4_kernel<RB, 1>;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
+    } else {
+        auto k = gemm_w4a4_kernel<RB, 0>;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
+    }
+    return hipGetLastError();
+}
+
+// Separate up projection for the unfused baseline (Fig. 6a): Y += H L2 as its own pass that reads and rewrites
+// the 16-bit output.  Same arithmetic as the fused branch (bf16 MFMAs on the hi and lo parts of H); a wavefront
+// owns 32 rows x 64 columns, a workgroup four such blocks side by side.
+__global__ __launch_bounds__(256) void upproj_kernel(const uint8_t *hfrag, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int ksteps = rank / 16;
+    const int n0 = (blockIdx.x * 4 + wave) * 64;
+    const int m0 = blockIdx.y * 32;
+    floatx16 acc[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+    const uint8_t *hf = hfrag + (size_t)blockIdx.y * ksteps * 2048 + lane * 16;
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const bf16x8 hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(hf + (size_t)ks * 2048));
+        const bf16x8 lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(hf + (size_t)ks * 2048 + 1024));
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int col = n0 + c * 32 + li;       // < Npad: l2t is padded
+            const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(l2t + (size_t)col * rank + ks * 16 + 8 * lh));
+            acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, bl, acc[c], 0, 0, 0);
+            acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, bl, acc[c], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + 8 * (v >> 2) + 4 * lh + (v & 3);
+            const int col = n0 + c * 32 + li;
+            if (row < M && col < N) {
+                const size_t idx = (size_t)row * N + col;
+                Y[idx] = (uint16_t)bf16_bits_w4(__uint_as_float((uint32_t)Y[idx] << 16) + acc[c][v]);
+            }
+        }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_w4a4(const GemmW4Params &p, hipStream_t stream) {
+    if (p.M <= 0) return hipSuccess;
+    // what the kernel's addressing assumes
+    if (p.G <= 0 || p.K != p.G * kGroup || p.Mpad % kRowPad || p.Npad % kRowPad || p.Mpad < p.M || p.Npad < p.N || p.rank % 16 ||
+        w4_a_bytes(p.G, p.Mpad) >= (size_t)1 << 31 || w4_b_bytes(p.G, p.Npad) >= (size_t)1 << 31)
+        return hipErrorInvalidValue;
+    if (p.ksplit < 1 || p.ksplit > p.G || (p.ksplit > 1 && (p.dbg || !p.partial || !p.counters))) return hipErrorInvalidValue;
+    if (p.ksplit > 1 && (size_t)(p.ksplit - 1) * ((p.G + p.ksplit - 1) / p.ksplit) >= (size_t)p.G) return hipErrorInvalidValue;      // no empty split
+    return launch_w4_tile<4>(p, stream);
+}
+
+hipError_t launch_upproj(const uint8_t *hfrag, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank, hipStream_t stream) {
+    if (M <= 0 || rank <= 0) return hipSuccess;
+    const dim3 grid((N + 255) / 256, (M + 31) / 32), block(256);
+    hipLaunchKernelGGL(upproj_kernel, grid, block, 0, stream, hfrag, l2t, Y, M, N, rank);
+    return hipGetLastError();
+}
+
+}  // namespace svdq

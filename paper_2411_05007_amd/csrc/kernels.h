@@ -5,57 +5,47 @@
 
 namespace svdq {
 
-// Bit pattern of 1.5 * 2^23.  An int32 MFMA accumulator seeded with it holds, read back as fp32,
-// exactly 12582912 + (integer sum) as long as |sum| < 2^22, which turns the int->float conversion
-// of every per-group partial sum into part of the rescale FMA.
-constexpr int32_t kMagicBits = 0x4B400000;
-constexpr float kMagic = 12582912.0f;
-
 struct ActParams {
     const uint16_t *X;       // bf16 [M][K]
     const float *rinv;       // fp32 [K]
     const uint16_t *l1s;     // bf16, fragment order
-    uint8_t *codes;          // [G][Mpad][64], int8 = 16 * code
-    uint16_t *sx;            // fp16 [G][Mpad]
+    uint8_t *codes;          // INT4: activation blocks [G][Mpad / 32][1792] (6-bit codes + fp16 scales, layout.h)
+    uint16_t *sx;            // MXFP4 only: the scale bytes
     float *H;                // fp32 [Mpad][rank]
     uint8_t *hfrag;          // H as bf16 hi + lo parts in MFMA operand order (layout.h), Mpad * rank * 4 bytes
     int M, K, G, Mpad, rank;
     uint32_t *zero_words;    // cleared by the first workgroup: the arrival counters of the GEMM that follows
     int n_zero;
-    int fmt;                 // 0: INT4 as described above.  1: MXFP4 - codes = packed E2M1 in the GEMM's operand order,
+    int fmt;                 // 0: INT4.  1: MXFP4 - codes = packed E2M1 in the GEMM's operand order,
                              // sx = scale bytes (layout.h, fp4_code_offset / fp4_scale_offset)
 };
 
 // flags: bit 0 = quantize (codes + scales), bit 1 = down projection (H)
 hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream);
 
-struct GemmParams {
-    const uint8_t *xcodes;   // [G][Mpad][64], int8 = 16 * code
-    const uint16_t *sx;      // fp16 [G][Mpad]
+// W4A4 GEMM on the block-scaled matrix instruction: INT4 codes as 6-bit float operands, exact fp32 group sums,
+// scale tiles from an f16 MFMA, one FMA per partial sum (gemm_w4a4_kernel.hip; layouts in layout.h)
+struct GemmW4Params {
+    const uint8_t *xa;       // activation blocks [G][Mpad / 32][1600]: 6-bit codes + fp16 scales
+    const uint8_t *wb;       // weight blocks [G][Npad / 32][1088]: 4-bit codes + fp16 scales
     const uint8_t *hfrag;    // H as bf16 hi + lo parts in MFMA operand order (layout.h)
-    const uint8_t *wcodes;   // [G][Npad][32]
-    const uint16_t *sw;      // fp16 [G][Npad]
     const uint16_t *l2t;     // bf16 [Npad][rank]
     const float *bias;       // fp32 [Npad]
     uint16_t *Y;             // bf16 [M][N]
     int M, N, K, G, Mpad, Npad, rank;   // rank == 0: no low-rank branch
     int32_t *dbg;            // debug window of exact group sums, or null
     int m0, m1, n0, n1;
-    int magic;               // kMagicBits, passed at run time so it stays in registers
     int ksplit;              // workgroups per tile along K (1 = no split)
-    float *partial;          // ksplit > 1: fp32 [tile][split][BM * BN] partial tiles, register order
+    float *partial;          // ksplit > 1: fp32 [tile][split][BM * 256] partial tiles, register order
     uint32_t *counters;      // ksplit > 1: one arrival counter per tile, zero when the kernel starts
 };
-
-// tile: a tile-config id (see gemm_kernel.hip); p.ksplit > 1 needs p.partial and p.counters
-hipError_t launch_gemm(const GemmParams &p, int tile, hipStream_t stream);
+hipError_t launch_gemm_w4a4(const GemmW4Params &p, hipStream_t stream);
 
 // Y[m][n] += sum_j H[m][j] L2[j][n]  as a separate read-modify-write pass (unfused baseline only)
 hipError_t launch_upproj(const uint8_t *hfrag, const uint16_t *l2t, uint16_t *Y, int M, int N, int rank, hipStream_t stream);
 
 struct DebugActParams {
-    const uint8_t *codes;
-    const uint16_t *sx;
+    const uint8_t *codes;    // activation blocks (codes and scales)
     const float *H;
     int8_t *out_codes;       // [M][K] or null
     uint16_t *out_sx;        // [M][G] or null
@@ -97,7 +87,7 @@ hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream);
 struct W4A16Params {
     const uint16_t *X;       // bf16 [M][K]
     const float *rinv;       // fp32 [K]
-    const uint8_t *wcodes;   // [G][Npad][32]
+    const uint8_t *wcodes;   // weight blocks [G][Npad / 64][2304] (layout.h)
     const uint16_t *sw;      // fp16 [G][Npad]
     const float *H;          // fp32 [Mpad][rank], written by the projection launch before; unused when rank == 0
     const uint16_t *l2t;     // bf16 [Npad][rank]

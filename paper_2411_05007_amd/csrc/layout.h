@@ -1,22 +1,11 @@
 // Native buffer layouts shared by the host packer and the HIP kernels.
 //
-// Both 4-bit operands are stored "group-major": for every group g of 64 input channels, the
-// 64 codes of one row (a token of the activation, an output channel of the weight) are one
-// block, and the blocks of all rows of that group are contiguous, so the GEMM's K loop streams
-// one contiguous slab per operand per step:
-//
-//     weight codes  wcodes[g][n][32 bytes], byte j = code(k = 64 g + 2 j) & 15 | code(k = 64 g + 2 j + 1) << 4
-//     weight scales wscales[g][n]  (fp16)
-//     activation codes (workspace) xcodes[g][m / 32][j][h][m % 32][16 bytes], one int8 = 16 * code per
-//         channel: the 16-byte chunk (j, h) of a row holds its channels 32 h + 16 j .. + 15, i.e. what lane
-//         32 h + m % 32 feeds to the j-th of the two MFMAs of a group, so a wavefront's A operand is one
-//         contiguous kilobyte (act_chunk_offset).  Inside a chunk the channels sit in the order the GEMM's
-//         nibble widening gives the weight codes (even channels of each eight first, act_byte_pos), so
-//         both operands agree on k:
-//         the activation kernel emits its INT4 codes already in the int8 operand form of the
-//         matrix core (there is no 4-bit integer MFMA), which spares the GEMM the widening of
-//         this operand; the tensor lives only between the two kernels of one forward.
-//     activation scales (workspace) sx[g][m]  (fp16)
+// Both 4-bit operands are stored "group-major": for every group g of 64 input channels, the blocks of all rows (tokens
+// of the activation, output channels of the weight) of that group are contiguous, so the GEMM's K loop streams one
+// contiguous slab per operand per step.  The INT4 blocks (activation blocks of 32 rows, weight blocks of 64 columns,
+// each with its codes in the matrix instruction's operand order and its fp16 scales) are described further down,
+// next to the MXFP4 and 8-bit forms.
+//     weight scales wscales[g][n]  (fp16): a plain copy beside the blocks, read by the W4A16 kernels
 //     low-rank activations (workspace) H[m][rank] fp32, and the same values split into bf16 hi + lo parts
 //         (hi = bf16(h), lo = bf16(h - hi)) in the A-operand order of v_mfma_f32_32x32x16_bf16:
 //         hfrag[m / 32][rank step of 16][part][lane = 32 ((j % 16) / 8) + m % 32][8 bf16], so the GEMM loads
@@ -47,20 +36,7 @@ namespace svdq {
 
 constexpr int kGroup = 64;
 constexpr int kRowPad = 256;        // rows of every group-major tensor are padded to this
-constexpr int kCodeBytes = 32;      // packed bytes of one weight row of one group
-constexpr int kActBytes = 64;       // bytes of one activation row of one group (one int8 = 16 * code per channel)
 constexpr int kMaxRank = 256;
-
-// Position, inside its 16-byte chunk, of channel e (0..15) of an activation row: widening a packed dword of
-// eight weight nibbles yields the four even codes, then the four odd ones.
-inline __host__ __device__ int act_byte_pos(int e) { return (e & 8) + (e & 1) * 4 + ((e & 7) >> 1); }
-
-// Byte offset of the 16-byte chunk that holds channels 16 blk .. 16 blk + 15 of group g of activation row m
-// (blk = 2 h + j: lane half h, MFMA j).  Mpad is a multiple of 32.
-inline __host__ __device__ size_t act_chunk_offset(int g, int Mpad, int m, int blk) {
-    const int h = blk >> 1, j = blk & 1;
-    return ((((size_t)g * (Mpad / 32) + m / 32) * 2 + j) * 64 + (h * 32 + m % 32)) * 16;
-}
 
 // Byte offset of the 16-byte chunk of hfrag that holds columns 8 (j / 8) .. + 7 of row m; part 0 = hi, 1 = lo.
 inline __host__ __device__ size_t hfrag_offset(int rank, int m, int j, int part) {
@@ -78,6 +54,48 @@ inline __host__ __device__ size_t l1s_index(int K, int rank, int k, int j) {
     const int c = j / 16, lane = blk * 16 + (j % 16);
     return ((((size_t)g * 2 + s) * (rank / 16) + c) * 64 + lane) * 8 + e;
 }
+
+// ---- INT4 operands of the block-scaled matrix instruction (W4A4 GEMM) ------------------------------------------
+// v_mfma_scale_f32_32x32x64_f8f6f4 multiplies one group of 64 channels per instruction.  Its 6-bit float format
+// E2M3 (sign, two exponent bits, three mantissa bits) holds every INT4 code exactly: with the exponent bits zero
+// the element is sign * mantissa / 8, so code q becomes the six bits  s 0 0 m m m  with m = |q|; the instruction's
+// power-of-two block scales (2^3 for each operand) take the two factors 1/8 out again and the fp32 result is the
+// exact integer group sum.  Lane l of an operand feeds row (column) l % 32 with the 32 channels of half l / 32 of
+// the group, channel e of the half in bits 6 e .. 6 e + 5 of the lane's six registers.
+//
+//   activation blocks (workspace)  xa[g][m / 32][1792 bytes]: bytes 24 l .. 24 l + 23 = lane l's six registers,
+//       bytes 1536 + 4 (m % 32) = the row's fp16 group scale in the low half of a dword whose high half is zero;
+//       the last 128 bytes are padding that is never read (a block is seven times 256 bytes so that one LDS
+//       address register reaches the scales of every block).  The activation kernel writes this form directly.
+//   weight blocks (prepared layer) wb[g][n / 64][2176 bytes], one block per 64 columns (what one wavefront of the
+//       GEMM multiplies): bytes 1024 (n % 64 / 32) + 16 l .. + 15 = lane l's 32 codes at FOUR bits each, bytes
+//       2048 + 4 (n % 64) = the column's fp16 group scale, again as the low half of a dword.  A scale dword read into
+//       both registers of an f16 MFMA operand makes that operand without a vector instruction.
+//       The 4 stored bits of a code sit where
+//       three AND / AND-OR operations per register pair spread them into the 6-bit form (w4_b_bitpos): of every 16
+//       codes = 96 operand bits = registers T0 T1 T2, the stored pair S0 S1 holds T0's and T1's used bits in
+//       place, and T2's used bits in the positions that T0 and T1 leave zero (their exponent bits):
+//           T0 = S0 & ~Z0,  T1 = S1 & ~Z1,  T2 = (S0 & Z0) | (S1 & Z1).
+// A block carries its scales so that one contiguous copy brings everything a 32-row block needs for one group.
+constexpr int kW4ACodes = 1536, kW4AUsed = 1664, kW4ABlock = 1792;     // bytes of codes / of codes + scales / of the whole activation block
+constexpr int kW4BCodes = 2048, kW4BBlock = 2304;     // bytes of codes / of the whole weight block (64 columns)
+constexpr uint32_t kW4Z0 = 0x18618618u;               // exponent-bit positions inside T0 (bits 3, 4 of every 6)
+constexpr uint32_t kW4Z1 = 0x86186186u;               // the same inside T1 (T1 starts at bit 32 = bit 2 of element 5)
+inline __host__ __device__ size_t w4_a_block(int g, int Mpad, int m) { return ((size_t)g * (Mpad / 32) + m / 32) * kW4ABlock; }
+inline __host__ __device__ size_t w4_b_block(int g, int Npad, int n) { return ((size_t)g * (Npad / 64) + n / 64) * kW4BBlock; }
+inline __host__ __device__ size_t w4_a_bytes(int G, int Mpad) { return (size_t)G * (Mpad / 32) * kW4ABlock; }
+inline __host__ __device__ size_t w4_b_bytes(int G, int Npad) { return (size_t)G * (Npad / 64) * kW4BBlock; }
+// Bit position (0..127, inside lane l's 16 bytes of a weight block) of bit b of channel e (0..31) of the lane's half
+// group: b = 0..2 are the magnitude bits, b = 3 the sign.
+inline __host__ __device__ int w4_b_bitpos(int e, int b) {
+    const int pair = e / 16, p = 6 * (e % 16) + (b < 3 ? b : 5);      // position in the 96 operand bits T0 T1 T2
+    if (p < 32) return pair * 64 + p;
+    if (p < 64) return pair * 64 + p;                                  // S1 bit p - 32
+    const int q = p - 64;
+    return pair * 64 + (((kW4Z0 >> q) & 1u) ? q : 32 + q);
+}
+// The 6-bit operand form of code q in [-7, 7] (-8 is not a code of the symmetric quantizer).
+inline __host__ __device__ uint32_t w4_e2m3(int q) { return q < 0 ? (32u | (uint32_t)(-q)) : (uint32_t)q; }
 
 // ---- 8-bit setting (one int8 per code, one fp16 scale per token and per output channel) ---------------------
 // Both operands in the operand order of v_mfma_i32_32x32x32_i8, whose lane l feeds row (or column) l % 32 with
@@ -178,14 +196,11 @@ inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank, int kspl
     return w;
 }
 
-// How the GEMM of an M x N x (64 G) layer is launched when the caller does not force a tile shape.
-// Large launches use 128x128 tiles, two workgroups per CU.  A launch with fewer than two such workgroups
-// per CU uses 64x128 tiles, and if even those leave most SIMDs without a second wavefront, the K loop is
-// split over `ksplit` workgroups per tile: each writes its fp32 partial tile to the workspace, and the one
-// that finishes last adds them up (in split order, so the result does not depend on who is last) and stores Y.
+// How the W4A4 GEMM of an M x N x (64 G) layer is launched.  Tiles are 128 x 256, two workgroups per CU.  A launch
+// with at most one workgroup per CU splits a long K loop over up to four workgroups per tile (at least twelve groups
+// each): every workgroup writes its fp32 partial tile to the workspace, and the one that finishes last adds them up
+// (in split order, so the result does not depend on who is last) and stores Y.
 struct GemmPlan {
-    int tile;        // tile-config id of the GEMM kernel: 2 / 5 = 128x128, 4 / 6 = 64x128 (5 and 6: weight fragments fetched
-                     // by every wavefront itself instead of staged through LDS)
     int bm, bn;
     int tiles;       // workgroups per split
     int ksplit;      // >= 1
@@ -193,21 +208,12 @@ struct GemmPlan {
 constexpr int kMaxKSplit = 8;
 inline GemmPlan plan_gemm(int M, int N, int G, int ksplit_override = 0) {
     GemmPlan pl;
-    const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (tiles128 >= 512) {
-        // measured: the direct fetch is 2-11 % faster except on large launches with a long K (M = 4608, K = 12288:
-        // 3 % slower), where the staged path's requests four groups ahead hide more of the memory latency
-        pl.tile = G >= 128 ? 2 : 5; pl.bm = 128; pl.bn = 128; pl.tiles = (int)tiles128; pl.ksplit = 1;
-        return pl;
-    }
-    pl.tile = 6; pl.bm = 64; pl.bn = 128;
-    pl.tiles = ((M + 63) / 64) * ((N + 127) / 128);
-    const int waves = 2 * pl.tiles;                 // the chip has 1024 SIMDs and wants two wavefronts on each
+    pl.bm = 128; pl.bn = 256;
+    pl.tiles = ((M + 127) / 128) * ((N + 255) / 256);
     int s = 1;
-    // measured: parking and re-reading the partial tiles costs about as much as half of a 48-group K loop,
-    // so the split pays only when the launch is well below one wavefront per SIMD and K is long
-    if (waves <= 768) {
-        s = 4;
+    if (pl.tiles <= 256) {
+        s = 512 / pl.tiles;
+        if (s > 4) s = 4;
         while (s > 1 && G / s < 12) --s;            // at least twelve groups per split
     }
     if (ksplit_override > 0) s = ksplit_override < kMaxKSplit ? ksplit_override : kMaxKSplit;
@@ -230,7 +236,7 @@ inline int act_waves(int K, int rank) { return (K / kGroup >= 32 && act_lds_byte
 
 // Workspace carve-up for a forward of M tokens.
 struct Workspace {
-    size_t codes_off, sx_off, h_off, hfrag_off, counters_off, partial_off, total;
+    size_t codes_off, h_off, hfrag_off, counters_off, partial_off, total;
     int Mpad;
     int n_counters;      // one arrival counter per tile when the K loop is split, else 0
 };
@@ -238,9 +244,8 @@ inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_over
     Workspace w;
     w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
     const int G = K / kGroup;
-    w.codes_off = 0;
-    w.sx_off = align256((size_t)G * w.Mpad * kActBytes);
-    w.h_off = w.sx_off + align256((size_t)G * w.Mpad * 2);
+    w.codes_off = 0;                                                     // activation blocks: codes and scales
+    w.h_off = align256(w4_a_bytes(G, w.Mpad));
     w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
     w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
     const GemmPlan pl = plan_gemm(M > 0 ? M : 1, N, G, ksplit_override);

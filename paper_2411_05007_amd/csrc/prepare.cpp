@@ -27,7 +27,6 @@
 
 namespace {
 
-using svdq::kCodeBytes;
 using svdq::kGroup;
 using svdq::kRowPad;
 
@@ -371,17 +370,29 @@ void pack_native(const svdq_shape *sh, const float *rinv, const uint16_t *l1s, c
     std::memset(o_l2, 0, (size_t)Np * r * 2);
     for (int j = 0; j < r; ++j)
         for (int n = 0; n < N; ++n) o_l2[(size_t)n * r + j] = l2[(size_t)j * N + n];
-    std::memset(o_wcodes, 0, (size_t)G * Np * kCodeBytes);
+    // weight blocks of the GEMM (layout.h): per group and 64 columns, the 4-bit codes of each lane of the matrix
+    // instruction's operand (sign and magnitude, bit positions from w4_b_bitpos) followed by the columns' scales
+    std::memset(o_wcodes, 0, svdq::w4_b_bytes(G, Np));
     std::memset(o_wscales, 0, (size_t)G * Np * 2);
     parallel_for((size_t)G, [&](size_t g0, size_t g1, int) {
         for (size_t g = g0; g < g1; ++g)
             for (int n = 0; n < N; ++n) {
-                uint8_t *dst = o_wcodes + (g * Np + n) * kCodeBytes;
-                for (int j = 0; j < kCodeBytes; ++j) {
-                    const int8_t lo = qw[(g * kGroup + 2 * j) * (size_t)N + n];
-                    const int8_t hi = qw[(g * kGroup + 2 * j + 1) * (size_t)N + n];
-                    dst[j] = (uint8_t)((lo & 0xf) | ((hi & 0xf) << 4));
+                uint8_t *blk = o_wcodes + svdq::w4_b_block((int)g, Np, n);
+                uint8_t *half_block = blk + 1024 * ((n % 64) / 32);
+                for (int kk = 0; kk < kGroup; ++kk) {
+                    const int q = qw[(g * kGroup + kk) * (size_t)N + n];
+                    const int mag = q < 0 ? -q : q;
+                    uint8_t *lane = half_block + 16 * (32 * (kk / 32) + n % 32);
+                    for (int b = 0; b < 4; ++b) {
+                        const int bit = b < 3 ? (mag >> b) & 1 : (q < 0);
+                        if (bit) {
+                            const int pos = svdq::w4_b_bitpos(kk % 32, b);
+                            lane[pos / 8] |= (uint8_t)(1u << (pos % 8));
+                        }
+                    }
                 }
+                const uint32_t sc = sw[g * N + n];      // fp16 scale in the low half of a dword
+                std::memcpy(blk + svdq::kW4BCodes + 4 * (n % 64), &sc, 4);
                 o_wscales[g * Np + n] = sw[g * N + n];
             }
     });
@@ -742,7 +753,7 @@ int svdq_prepared_sizes(const svdq_shape *shape, svdq_sizes *out) {
     out->rinv = K * 4;
     out->l1s = std::max<size_t>(K * r * 2, 16);
     out->l2 = std::max<size_t>(Np * r * 2, 16);
-    out->wcodes = G * Np * kCodeBytes;
+    out->wcodes = svdq::w4_b_bytes((int)G, (int)Np);
     out->wscales = G * Np * 2;
     out->bias = Np * 4;
     return SVDQ_OK;
@@ -758,7 +769,7 @@ int svdq_pack(const svdq_shape *shape, const float *rinv, const uint16_t *l1s, c
     if (shape->rank > 0 && (!l1s || !l2)) return SVDQ_EINVAL;
     const size_t total = (size_t)shape->K * shape->N;
     for (size_t i = 0; i < total; ++i)
-        if (qw[i] < -8 || qw[i] > 7) return SVDQ_EINVAL;
+        if (qw[i] < -7 || qw[i] > 7) return SVDQ_EINVAL;      // the symmetric quantizer's range; -8 has no sign-magnitude form
     pack_native(shape, rinv, l1s, l2, qw, sw, bias, out_rinv, out_l1s, out_l2, out_wcodes, out_wscales, out_bias);
     return SVDQ_OK;
 }
@@ -1004,11 +1015,16 @@ int svdq_unpack_wcodes(const svdq_shape *shape, const uint8_t *wcodes, int8_t *o
     const int K = shape->K, N = shape->N, G = K / kGroup, Np = svdq::round_up(N, kRowPad);
     for (int g = 0; g < G; ++g)
         for (int n = 0; n < N; ++n) {
-            const uint8_t *src = wcodes + ((size_t)g * Np + n) * kCodeBytes;
-            for (int j = 0; j < kCodeBytes; ++j) {
-                const int lo = (int)((src[j] & 0xf) ^ 8) - 8, hi = (int)((src[j] >> 4) ^ 8) - 8;   // sign-extend 4 bits
-                out_qw[((size_t)g * kGroup + 2 * j) * N + n] = (int8_t)lo;
-                out_qw[((size_t)g * kGroup + 2 * j + 1) * N + n] = (int8_t)hi;
+            const uint8_t *half_block = wcodes + svdq::w4_b_block(g, Np, n) + 1024 * ((n % 64) / 32);
+            for (int kk = 0; kk < kGroup; ++kk) {
+                const uint8_t *lane = half_block + 16 * (32 * (kk / 32) + n % 32);
+                int v[4];
+                for (int b = 0; b < 4; ++b) {
+                    const int pos = svdq::w4_b_bitpos(kk % 32, b);
+                    v[b] = (lane[pos / 8] >> (pos % 8)) & 1;
+                }
+                const int mag = v[0] | (v[1] << 1) | (v[2] << 2);
+                out_qw[((size_t)g * kGroup + kk) * N + n] = (int8_t)(v[3] ? -mag : mag);
             }
         }
     return SVDQ_OK;

@@ -4,7 +4,9 @@
 //   Y = X^ Q(R) + H L2 + bias,   X^ = bf16(x) * (1 / lambda) in fp32,   Q(R) = s_w[g, n] * codes        (Eq. 5 without Q(X^))
 //
 // These layers see a handful of rows (one conditioning vector per image), so the kernels are weight-streaming ones:
-// every 4-bit code is read once and widened on the vector ALU; the matrix cores are not used.  Codes are summed
+// every 4-bit code is read once and turned into a float on the vector ALU (the 16 bytes of one operand lane of the
+// GEMM's weight blocks are spread to the 6-bit float form with four AND / AND-OR operations per 16 codes and
+// converted 32 at a time by v_cvt_scalef32_pk32_f32_fp6); the matrix cores are not used.  Codes are summed
 // against X^ in fp32 per group and scaled once per group; partial sums of wavefronts are added in wavefront order
 // (deterministic); then H L2 (H from w4a16_proj_kernel below, or from the activation kernel for many rows), bias, bf16.
 //   * one or two rows: w4a16_stream_kernel, one workgroup per compute unit, X^ in registers;
@@ -22,11 +24,34 @@ namespace {
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+typedef float floatx32 __attribute__((ext_vector_type(32)));
+
+// The 32 codes of one operand lane of a weight block (16 bytes: channels 32 h .. 32 h + 31 of a group for one
+// column, layout.h) as floats.  The stored bits are spread to the 6-bit form sign | 00 | magnitude, whose value as an
+// E2M3 float is code / 8; the conversion's scale of 8 returns the code itself.
+__device__ __forceinline__ floatx32 decode_lane(uint4 q) {
+    u32x6 t;
+    t[0] = q.x & ~kW4Z0;
+    t[1] = q.y & ~kW4Z1;
+    t[2] = (q.x & kW4Z0) | (q.y & kW4Z1);
+    t[3] = q.z & ~kW4Z0;
+    t[4] = q.w & ~kW4Z1;
+    t[5] = (q.z & kW4Z0) | (q.w & kW4Z1);
+    return __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(t, 8.0f);
+}
+// byte offset of operand lane (half h, column n) of group g's weight blocks
+__device__ __forceinline__ size_t lane_offset(int g, int Npad, int n, int h) {
+    return w4_b_block(g, Npad, n) + 1024 * ((n % 64) / 32) + 16 * (32 * h + n % 32);
+}
+
 // ROWS rows and CW columns per workgroup; a wavefront's lanes are (column, part): PARTS = 64 / CW lanes share one
-// column and split its 64 codes of a group into consecutive pieces.  UNROLL groups are loaded before the first is used.
+// column and split its 64 codes of a group into halves of 32 (CW = 32) or take them all (CW = 64).  UNROLL groups are
+// loaded before the first is used.
 template <int ROWS, int WAVES, int CW, int UNROLL>
 __global__ __launch_bounds__(WAVES * 64) void w4a16_kernel(W4A16Params p) {
-    constexpr int PARTS = 64 / CW, CODES = 64 / PARTS, DW = CODES / 8;
+    constexpr int PARTS = 64 / CW, HALVES = 2 / PARTS;      // operand lanes (halves of a group) per lane
+    static_assert(CW == 32 || CW == 64, "a lane takes one or both halves of its column's group");
     __shared__ __attribute__((aligned(16))) float xs[WAVES][ROWS][64];   // per wavefront: the group's slice of X^
     __shared__ float part[WAVES][PARTS][ROWS][CW];                       // partial sums of every (wavefront, part)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -64,24 +89,15 @@ __global__ __launch_bounds__(WAVES * 64) void w4a16_kernel(W4A16Params p) {
 #pragma unroll
     for (int m = 0; m < ROWS; ++m) acc[m] = 0.f;
     for (int g0 = wave; g0 < G; g0 += UNROLL * WAVES) {
-        uint32_t words[UNROLL][DW];
+        uint4 words[UNROLL][HALVES];
         uint16_t xr[UNROLL][ROWS];
         float rinv[UNROLL], s[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int g = g0 + u * WAVES < G ? g0 + u * WAVES : g0;      // past the end: a valid group, loaded and ignored
-            const uint32_t *wc = reinterpret_cast<const uint32_t *>(p.wcodes + ((size_t)g * p.Npad + n) * kCodeBytes) + pt * DW;
-            if constexpr (DW == 8) {
-                const uint4 c0 = reinterpret_cast<const uint4 *>(wc)[0], c1 = reinterpret_cast<const uint4 *>(wc)[1];
-                words[u][0] = c0.x; words[u][1] = c0.y; words[u][2] = c0.z; words[u][3] = c0.w;
-                words[u][4] = c1.x; words[u][5] = c1.y; words[u][6] = c1.z; words[u][7] = c1.w;
-            } else if constexpr (DW == 4) {
-                const uint4 c0 = reinterpret_cast<const uint4 *>(wc)[0];
-                words[u][0] = c0.x; words[u][1] = c0.y; words[u][2] = c0.z; words[u][3] = c0.w;
-            } else {
-                const uint2 c0 = reinterpret_cast<const uint2 *>(wc)[0];
-                words[u][0] = c0.x; words[u][1] = c0.y;
-            }
+#pragma unroll
+            for (int hh = 0; hh < HALVES; ++hh)
+                words[u][hh] = *reinterpret_cast<const uint4 *>(p.wcodes + lane_offset(g, p.Npad, n, PARTS == 2 ? pt : hh));
             s[u] = (float)__builtin_bit_cast(_Float16, p.sw[(size_t)g * p.Npad + n]);
             rinv[u] = p.rinv[g * 64 + lane];
 #pragma unroll
@@ -99,23 +115,20 @@ __global__ __launch_bounds__(WAVES * 64) void w4a16_kernel(W4A16Params p) {
 #pragma unroll
             for (int m = 0; m < ROWS; ++m) sum[m] = 0.f;
 #pragma unroll
-            for (int w8 = 0; w8 < DW; ++w8) {
-                float code[8];       // nibble t of the dword = channel 8 w8 + t of the piece (byte j: channels 2 j and 2 j + 1)
-#pragma unroll
-                for (int t = 0; t < 8; ++t) code[t] = (float)((int)(words[u][w8] << (28 - 4 * t)) >> 28);
+            for (int hh = 0; hh < HALVES; ++hh) {
+                const floatx32 code = decode_lane(words[u][hh]);      // element e = channel 32 h + e of the group
+                const int h = PARTS == 2 ? pt : hh;
 #pragma unroll
                 for (int m = 0; m < ROWS; ++m) {
-                    const float *xp = &xs[wave][m][pt * CODES + 8 * w8];
-                    const float4 xa = *reinterpret_cast<const float4 *>(xp);
-                    const float4 xb = *reinterpret_cast<const float4 *>(xp + 4);
-                    sum[m] = __builtin_fmaf(xa.x, code[0], sum[m]);
-                    sum[m] = __builtin_fmaf(xa.y, code[1], sum[m]);
-                    sum[m] = __builtin_fmaf(xa.z, code[2], sum[m]);
-                    sum[m] = __builtin_fmaf(xa.w, code[3], sum[m]);
-                    sum[m] = __builtin_fmaf(xb.x, code[4], sum[m]);
-                    sum[m] = __builtin_fmaf(xb.y, code[5], sum[m]);
-                    sum[m] = __builtin_fmaf(xb.z, code[6], sum[m]);
-                    sum[m] = __builtin_fmaf(xb.w, code[7], sum[m]);
+                    const float4 *xp = reinterpret_cast<const float4 *>(&xs[wave][m][32 * h]);
+#pragma unroll
+                    for (int e4 = 0; e4 < 8; ++e4) {
+                        const float4 xa = xp[e4];
+                        sum[m] = __builtin_fmaf(xa.x, code[4 * e4], sum[m]);
+                        sum[m] = __builtin_fmaf(xa.y, code[4 * e4 + 1], sum[m]);
+                        sum[m] = __builtin_fmaf(xa.z, code[4 * e4 + 2], sum[m]);
+                        sum[m] = __builtin_fmaf(xa.w, code[4 * e4 + 3], sum[m]);
+                    }
                 }
             }
 #pragma unroll
@@ -138,41 +151,32 @@ __global__ __launch_bounds__(WAVES * 64) void w4a16_kernel(W4A16Params p) {
     }
 }
 
-// sum over the 8 lanes l % 8 = 0..7 (the eight pieces of one column), same order in every lane
-__device__ __forceinline__ float sum_over_8_lanes(float a) {
-    a += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true));    // quad_perm [1,0,3,2]
-    a += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4E, 0xf, 0xf, true));    // quad_perm [2,3,0,1]
-    a += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x141, 0xf, 0xf, true));   // row_half_mirror
-    return a;
-}
-
-// One or two rows.  The layer's columns are dealt out in runs of 8 * CB, CB chosen on the host so that the workgroups
+// One or two rows.  The layer's columns are dealt out in runs of 32 * CB, CB chosen on the host so that the workgroups
 // fill the compute units evenly (one 16-wavefront workgroup per unit when the layer is wide enough).  A lane is
-// (column c8 of 8, piece p8 of 8): it reads ONE dword, eight codes, of its column per group, so a wavefront's load is
-// 256 consecutive bytes, and it keeps the matching eight channels of X^ of its wavefront's groups in registers for
-// all the columns of the run: no LDS in the loop.  Wavefront w of nw takes groups w, w + nw, w + 2 nw of every chunk
-// of 3 nw groups.  Pieces are summed across lanes (DPP), wavefronts through LDS in wavefront order.
-constexpr int kStreamCbMax = 12;     // 8-column blocks per workgroup, at most
-constexpr int kStreamBatch = 3;      // blocks loaded together
-constexpr int kStreamGpw = 3;        // groups per wavefront per chunk
+// (column c of 32, half h of the group): it reads the 16 bytes of ITS operand lane of the weight block, 32 codes, per
+// group and block of 32 columns - a wavefront's load is one contiguous kilobyte - and keeps the matching 32 channels
+// of X^ of its wavefront's current group in registers for all the columns of the run: no LDS in the loop.  Wavefront
+// w of nw takes groups w, w + nw, ...; the codes of the next group are requested while the current one is summed.
+// The two halves and the wavefronts are added in a fixed order through LDS.
+constexpr int kStreamCbMax = 3;      // 32-column blocks per workgroup, at most
 
 template <int ROWS>
 __global__ __launch_bounds__(1024) void w4a16_stream_kernel(W4A16Params p, int CB) {
-    constexpr int CBMAX = kStreamCbMax, CBB = kStreamBatch, GPW = kStreamGpw, NB = CBMAX / CBB;
-    __shared__ float part[16][ROWS][CBMAX * 8];
+    constexpr int CBMAX = kStreamCbMax;
+    __shared__ float part[16][2][ROWS][CBMAX * 32];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
-    const int c8 = lane >> 3, p8 = lane & 7;
-    const int n0 = blockIdx.x * CB * 8;
-    // byte offsets into the code and scale tensors stay below 2^32 (checked on the host): buffer loads, a per-lane
-    // offset that never changes plus a uniform one
-    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(p.wcodes, (size_t)(p.K / 64) * p.Npad * kCodeBytes);
-    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sw, (size_t)(p.K / 64) * p.Npad * 2);
-    const int w_voff = (n0 + c8) * kCodeBytes + p8 * 4, s_voff = (n0 + c8) * 2;
-    const int m0 = blockIdx.y * ROWS;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int n0 = blockIdx.x * CB * 32;
+    // byte offsets into the block and scale tensors stay below 2^31 (checked on the host): buffer loads, a per-lane
+    // offset that never changes plus a uniform one; reads past the end of a buffer return zero
     const int G = p.K / 64;
+    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(p.wcodes, w4_b_bytes(G, p.Npad));
+    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sw, (size_t)G * p.Npad * 2);
+    const int w_voff = 16 * lane, s_voff = c32 * 2;      // operand lane 32 h + c32 of a 32-column half block is its bytes 16 lane .. + 15
+    const int m0 = blockIdx.y * ROWS;
     // the thread that finishes output (row o_m, column n0 + o_c) forms its low-rank term and bias first
-    const int o_m = threadIdx.x / (CBMAX * 8), o_c = threadIdx.x % (CBMAX * 8), o_row = m0 + o_m, o_n = n0 + o_c;
-    const bool o_live = o_m < ROWS && o_c < CB * 8 && o_row < p.M && o_n < p.N;
+    const int o_m = threadIdx.x / (CBMAX * 32), o_c = threadIdx.x % (CBMAX * 32), o_row = m0 + o_m, o_n = n0 + o_c;
+    const bool o_live = o_m < ROWS && o_c < CB * 32 && o_row < p.M && o_n < p.N;
     float low = 0.f, bias = 0.f;
     if (o_live) {
         bias = p.bias[o_n];
@@ -196,86 +200,60 @@ __global__ __launch_bounds__(1024) void w4a16_stream_kernel(W4A16Params p, int C
     for (int cb = 0; cb < CBMAX; ++cb)
 #pragma unroll
         for (int m = 0; m < ROWS; ++m) acc[cb][m] = 0.f;
-    for (int gb = 0; gb < G; gb += nw * GPW) {
-        // X^ of this wavefront's groups: channels 64 g + 8 p8 .. + 7 of every row (rows past M repeat the last row; never stored)
-        float xh[GPW][ROWS][8];
-        int gi[GPW];
-        bool gv[GPW];
+    // codes and scales of one group for the run's blocks; a block past the run or past N repeats the run's first block (uniform)
+    struct Batch { uint4 codes[CBMAX]; uint16_t sc[CBMAX]; };
+    auto load_batch = [&](int g) {
+        Batch q;
 #pragma unroll
-        for (int u = 0; u < GPW; ++u) {
-            const int g = gb + wave + u * nw;
-            gv[u] = g < G;                                                // uniform over the wavefront
-            gi[u] = gv[u] ? g : G - 1;                                    // past the end: a valid group, loaded and ignored
-            const float4 ra = *reinterpret_cast<const float4 *>(p.rinv + gi[u] * 64 + p8 * 8);
-            const float4 rb = *reinterpret_cast<const float4 *>(p.rinv + gi[u] * 64 + p8 * 8 + 4);
+        for (int cb = 0; cb < CBMAX; ++cb) {
+            const bool live = cb < CB && n0 + cb * 32 < p.N;
+            const int first = n0 + (live ? cb * 32 : 0);                  // a multiple of 32, below Npad
+            q.codes[cb] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_voff, (int)(w4_b_block(g, p.Npad, first) + 1024 * ((first % 64) / 32)), 0));
+            q.sc[cb] = __builtin_amdgcn_raw_buffer_load_b16(rs_s, s_voff, (g * p.Npad + first) * 2, 0);
+        }
+        return q;
+    };
+    Batch cur = load_batch(wave < G ? wave : 0);
+    for (int g = wave; g < G; g += nw) {
+        // X^ of this group: channels 64 g + 32 h .. + 31 of every row (rows past M repeat the last row; never stored)
+        float xh[ROWS][32];
+#pragma unroll
+        for (int q4 = 0; q4 < 8; ++q4) {
+            const float4 r = *reinterpret_cast<const float4 *>(p.rinv + g * 64 + 32 * h + 4 * q4);
 #pragma unroll
             for (int m = 0; m < ROWS; ++m) {
                 const int row = m0 + m < p.M ? m0 + m : p.M - 1;
-                const uint4 xv = *reinterpret_cast<const uint4 *>(p.X + (size_t)row * p.K + gi[u] * 64 + p8 * 8);
-                xh[u][m][0] = __uint_as_float(xv.x << 16) * ra.x;
-                xh[u][m][1] = __uint_as_float(xv.x & 0xffff0000u) * ra.y;
-                xh[u][m][2] = __uint_as_float(xv.y << 16) * ra.z;
-                xh[u][m][3] = __uint_as_float(xv.y & 0xffff0000u) * ra.w;
-                xh[u][m][4] = __uint_as_float(xv.z << 16) * rb.x;
-                xh[u][m][5] = __uint_as_float(xv.z & 0xffff0000u) * rb.y;
-                xh[u][m][6] = __uint_as_float(xv.w << 16) * rb.z;
-                xh[u][m][7] = __uint_as_float(xv.w & 0xffff0000u) * rb.w;
+                const uint2 xv = *reinterpret_cast<const uint2 *>(p.X + (size_t)row * p.K + g * 64 + 32 * h + 4 * q4);
+                xh[m][4 * q4] = __uint_as_float(xv.x << 16) * r.x;
+                xh[m][4 * q4 + 1] = __uint_as_float(xv.x & 0xffff0000u) * r.y;
+                xh[m][4 * q4 + 2] = __uint_as_float(xv.y << 16) * r.z;
+                xh[m][4 * q4 + 3] = __uint_as_float(xv.y & 0xffff0000u) * r.w;
             }
         }
-        uint32_t codes[2][CBB][GPW];
-        uint16_t sc[2][CBB][GPW];
-        auto load_batch = [&](int b, int buf) {
+        const Batch nxt = load_batch(g + nw < G ? g + nw : g);          // past the end: this group again, loaded and ignored
 #pragma unroll
-            for (int i = 0; i < CBB; ++i) {
-                const int cb = b * CBB + i;
-                const bool live = cb < CB && n0 + cb * 8 < p.N;          // uniform; otherwise the run's first block again
-                const int first = live ? cb * 8 : 0;
+        for (int cb = 0; cb < CBMAX; ++cb) {
+            if (cb >= CB) break;                                          // uniform
+            const floatx32 code = decode_lane(cur.codes[cb]);
+            const float sc = (float)__builtin_bit_cast(_Float16, cur.sc[cb]);
 #pragma unroll
-                for (int u = 0; u < GPW; ++u) {
-                    const int at = gi[u] * p.Npad + first;
-                    codes[buf][i][u] = __builtin_amdgcn_raw_buffer_load_b32(rs_w, w_voff, at * kCodeBytes, 0);
-                    sc[buf][i][u] = __builtin_amdgcn_raw_buffer_load_b16(rs_s, s_voff, at * 2, 0);
-                }
-            }
-        };
-        load_batch(0, 0);
+            for (int m = 0; m < ROWS; ++m) {
+                float sum = 0.f;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            if (b * CBB >= CB) break;                                     // uniform
-            if (b + 1 < NB) load_batch(b + 1, (b + 1) & 1);
-#pragma unroll
-            for (int i = 0; i < CBB; ++i) {
-                const int cb = b * CBB + i;
-#pragma unroll
-                for (int u = 0; u < GPW; ++u) {
-                    if (!gv[u]) continue;                                 // uniform
-                    const uint32_t w = codes[b & 1][i][u];
-                    float code[8];   // nibble t = channel 8 p8 + t of the group
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) code[t] = (float)((int)(w << (28 - 4 * t)) >> 28);
-                    const float s = (float)__builtin_bit_cast(_Float16, sc[b & 1][i][u]);
-#pragma unroll
-                    for (int m = 0; m < ROWS; ++m) {
-                        float sum = 0.f;
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) sum = __builtin_fmaf(xh[u][m][t], code[t], sum);
-                        acc[cb][m] = __builtin_fmaf(s, sum, acc[cb][m]);
-                    }
-                }
+                for (int e = 0; e < 32; ++e) sum = __builtin_fmaf(xh[m][e], code[e], sum);
+                acc[cb][m] = __builtin_fmaf(sc, sum, acc[cb][m]);
             }
         }
+        cur = nxt;
     }
 #pragma unroll
     for (int cb = 0; cb < CBMAX; ++cb)
 #pragma unroll
-        for (int m = 0; m < ROWS; ++m) {
-            const float t = sum_over_8_lanes(acc[cb][m]);
-            if (p8 == 0) part[wave][m][cb * 8 + c8] = t;
-        }
+        for (int m = 0; m < ROWS; ++m) part[wave][h][m][cb * 32 + c32] = acc[cb][m];
     __syncthreads();
     if (o_live) {
         float y = 0.f;
-        for (int w = 0; w < nw; ++w) y += part[w][o_m][o_c];
+        for (int w = 0; w < nw; ++w) y += part[w][0][o_m][o_c] + part[w][1][o_m][o_c];
         y = (y + low) + bias;
         p.Y[(size_t)o_row * p.N + o_n] = __builtin_bit_cast(uint16_t, (__bf16)y);
     }
@@ -355,7 +333,7 @@ __global__ __launch_bounds__(1024) void w4a16_proj_kernel(const uint16_t *X, con
 struct StreamPlan { int cb, nw, wgs; };
 
 StreamPlan plan_stream(int N, int G, int passes) {
-    const int blocks = N / 8, kCUs = 256;
+    const int blocks = (N + 31) / 32, kCUs = 256;
     StreamPlan best{1, 16, blocks};
     long best_cost = -1;
     for (int cb = 1; cb <= kStreamCbMax; ++cb) {

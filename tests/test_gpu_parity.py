@@ -49,9 +49,9 @@ def _check_y(y_bits, ref_Y, what):
     return rel, mx
 
 
-def _run_and_compare(torch, xb, prep, rows=None, window=True, what="", tile=0, flags=0):
+def _run_and_compare(torch, xb, prep, rows=None, window=True, what="", ksplit=0, flags=0):
     """Forward on the GPU for all of xb; compare the given rows (default: all) with the oracle."""
-    S.svdq_forward_options(flags | (tile << S.OPT_TILE_SHIFT))
+    S.svdq_forward_options(flags | (ksplit << S.OPT_KSPLIT_SHIFT))
     layer = S.DeviceLayer(prep)
     x = S.bf16_tensor_from_bits(xb)
     M = xb.shape[0]
@@ -72,10 +72,11 @@ def _run_and_compare(torch, xb, prep, rows=None, window=True, what="", tile=0, f
     yb = S.bits_from_bf16_tensor(y)
     res = _check_y(yb[rows], ref["Y"], what)
     if window:
-        # exact int32 group sums on a window that straddles tile and wave-tile borders
+        # exact int32 group sums on a window that straddles a tile border (256 columns), else a wavefront border (64)
         r0 = int(rows[0])
         m0, m1 = r0, min(M, r0 + 3)
-        n0, n1 = max(0, min(layer.N - 1, 126)), min(layer.N, 131)
+        edge = 256 if layer.N > 258 else 64
+        n0, n1 = max(0, min(layer.N - 1, edge - 2)), min(layer.N, edge + 3)
         A = layer.debug_group_acc(m0, m1, n0, n1)
         sel = [int(np.where(rows == m)[0][0]) for m in range(m0, m1) if m in set(rows.tolist())]
         want = np.transpose(ref["A"][:, sel][:, :, n0:n1], (1, 2, 0))
@@ -277,14 +278,17 @@ def test_activation_scales_over_the_whole_fp16_range(torch):
     assert np.all(np.isfinite(O.bf16_to_f32(S.bits_from_bf16_tensor(y))))
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
-def test_every_gemm_tile_configuration(torch, tile):
+@pytest.mark.parametrize("ksplit", [1, 2, 3, 5, 8])
+def test_forced_k_splits(torch, ksplit):
+    """The K loop split over a forced number of workgroups per tile (option bits 8-11), including splits of unequal
+    length (18 groups over 5 and 8) on a launch that the library would not split by itself."""
     case = I.case_by_name("tiny")
     L = I.make_layer(case, M=300)
     w = np.ascontiguousarray(L["w"][:, :656])
     prep = S.svdq_prepare(w, L["x_absmax"], 32, bias=L["bias"][:656])
-    _say(f"tile {tile}")
-    _run_and_compare(torch, L["x_bf16"], prep, what=f"tile {tile}", tile=tile)
+    _say(f"forced K split {ksplit}")
+    _run_and_compare(torch, L["x_bf16"], prep, what=f"ksplit {ksplit}", ksplit=ksplit, window=False)
+    S.svdq_forward_options(0)
 
 
 def test_measurement_switches_match_the_oracle(torch):
@@ -383,6 +387,52 @@ def test_full_size_layers_on_sampled_rows(torch, name):
     rows = I.sample_rows(case.M, 40)
     _say(f"{name}: prepared; comparing {rows.size} rows")
     _run_and_compare(torch, L["x_bf16"], prep, rows=rows, what=name)
+
+
+def test_headline_layer_all_rows(torch):
+    """FLUX MLP up (M = 4608, K = 3072, N = 12288, r = 32) in the configuration bench.py times: EVERY row of Y, of the
+    activation codes and scales and of H against the oracle, and the exact group sums of one whole 128 x 256 tile plus
+    strips across the tile borders next to it."""
+    case = I.case_by_name("flux_mlp_up")
+    _say(f"headline, all rows: M={case.M} K={case.K} N={case.N} r={case.rank}: generating")
+    L = I.make_layer(case)
+    prep = S.svdq_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    S.svdq_forward_options(0)
+    layer = S.DeviceLayer(prep)
+    x = S.bf16_tensor_from_bits(L["x_bf16"])
+    y = torch.full((case.M, case.N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    ws = layer.workspace(case.M)
+    layer.forward(x, out=y, workspace=ws)
+    torch.cuda.synchronize()
+    U = S.svdq_unpack(prep)
+    codes, sx, H = layer.debug_act(workspace=ws, M=case.M)
+    yb = S.bits_from_bf16_tensor(y)
+    _say("headline, all rows: oracle in blocks of 512 rows")
+    worst = (0.0, 0.0)
+    num = den = 0.0
+    for r0 in range(0, case.M, 512):
+        rows = slice(r0, r0 + 512)
+        ref = O.forward(L["x_bf16"][rows], U)
+        assert np.array_equal(codes[rows], ref["qx"]), f"activation codes, rows {r0}.."
+        assert np.array_equal(sx[rows].view(np.uint16), ref["sx"].view(np.uint16)), f"activation scales, rows {r0}.."
+        assert np.max(np.abs(H[rows] - ref["H"])) <= 1e-5 * np.max(np.abs(ref["H"])), f"H, rows {r0}.."
+        yg = O.bf16_to_f32(yb[rows]).astype(np.float64)
+        yr = ref["Y"]
+        ymax = np.max(np.abs(yr))
+        assert np.all(np.isfinite(yg))
+        assert np.all(np.abs(yg - yr) <= 2.0 ** -7 * np.abs(yr) + 2e-5 * ymax), f"Y element-wise, rows {r0}.."
+        num += float(np.sum((yg - yr) ** 2))
+        den += float(np.sum(yr ** 2))
+        worst = max(worst, (float(np.max(np.abs(yg - yr)) / ymax), r0))
+    rel = (num / den) ** 0.5
+    _say(f"headline, all rows: rel-L2 {rel:.3e}, worst max-abs/max|Y| {worst[0]:.3e} (rows {worst[1]}..)")
+    assert rel <= REL_L2 and worst[0] <= MAX_ABS
+    # group sums: the whole tile (rows 128-255, columns 256-511), and strips across its four borders
+    ref = O.forward(L["x_bf16"][120:264], U, want_group_sums=True)          # rows 120..263
+    for (m0, m1, n0, n1) in ((128, 256, 256, 512), (124, 132, 250, 262), (252, 260, 506, 518), (124, 132, 506, 518)):
+        A = layer.debug_group_acc(m0, m1, n0, n1, workspace=ws, M=case.M)
+        want = np.transpose(ref["A"][:, m0 - 120:m1 - 120, n0:n1], (1, 2, 0))
+        assert np.array_equal(A, want), (m0, m1, n0, n1)
 
 
 SWEEP = [f"flux_block_{layer}_M{M}_r{r}" for M in (4608, 512) for r in (32, 128) for layer in ("qkv", "out", "mlp_up", "mlp_down")]

@@ -116,19 +116,36 @@ def test_pack_unpack_round_trip_and_byte_layout(lib):
     assert np.array_equal(U["qw"], qw) and np.array_equal(U["sw"], sw)
     assert np.array_equal(U["l1s"], l1s) and np.array_equal(U["l2"], l2)
     assert np.array_equal(U["rinv"], rinv) and np.array_equal(U["bias"], bias)
-    # documented layout: codes[g][row][32 bytes], byte j = code(2j) & 15 | code(2j+1) << 4, rows padded to 256
+    # documented layout: one block of 2304 bytes per group and 64 columns (columns padded to 256): the 16 bytes of
+    # operand lane 32 * (k % 64 // 32) + n % 32 of the half block (n % 64) // 32 hold 32 codes at 4 bits each,
+    # magnitude bits and sign at the positions that spread to the 6-bit float form with
+    #   T0 = S0 & ~Z0, T1 = S1 & ~Z1, T2 = (S0 & Z0) | (S1 & Z1)   per 16 codes,
+    # followed by the 64 columns' fp16 scales, each in the low half of a dword
     Np = 256
-    blk = P.wcodes.reshape(K // 64, Np, 32)
-    g, n, j = 2, 17, 5
-    want = (int(qw[64 * g + 2 * j, n]) & 15) | ((int(qw[64 * g + 2 * j + 1, n]) & 15) << 4)
-    assert blk[g, n, j] == want
-    assert np.all(blk[:, N:, :] == 0) and np.all(P.wscales.reshape(K // 64, Np)[:, N:] == 0)
+    blocks = P.wcodes.reshape(K // 64, Np // 64, 2304)
+    Z0, Z1 = 0x18618618, 0x86186186
+    for g, n in ((2, 17), (0, 79), (1, 40)):
+        blk = blocks[g, n // 64]
+        for h in (0, 1):
+            lane = blk[1024 * ((n % 64) // 32) + 16 * (32 * h + n % 32):][:16].view("<u4").astype(np.uint64)
+            ops = []
+            for pair in (0, 1):
+                s0, s1 = int(lane[2 * pair]), int(lane[2 * pair + 1])
+                ops += [s0 & ~Z0 & 0xffffffff, s1 & ~Z1 & 0xffffffff, (s0 & Z0) | (s1 & Z1)]
+            bits = sum(v << (32 * i) for i, v in enumerate(ops))          # the lane's 192 operand bits
+            for e in range(32):
+                c = (bits >> (6 * e)) & 63
+                assert (c >> 3) & 3 == 0                                  # exponent bits zero: the value is code / 8
+                assert (-(c & 7) if c & 32 else c & 7) == qw[64 * g + 32 * h + e, n], (g, n, h, e)
+        assert int(blk[2048 + 4 * (n % 64):][:4].view("<u4")[0]) == int(sw[g, n].view(np.uint16))
+    assert np.all(blocks[:, (N + 63) // 64:, :] == 0) and np.all(P.wscales.reshape(K // 64, Np)[:, N:] == 0)
     assert P.bias.shape == (Np,) and np.all(P.bias[N:] == 0)
-    # out-of-range code is rejected
-    bad = qw.copy()
-    bad[0, 0] = 9
-    with pytest.raises(S.SvdqError):
-        S.svdq_pack(rinv, l1s, l2, bad, sw, bias)
+    # out-of-range codes are rejected: the symmetric quantizer's range is [-7, 7]
+    for v in (9, -8):
+        bad = qw.copy()
+        bad[0, 0] = v
+        with pytest.raises(S.SvdqError):
+            S.svdq_pack(rinv, l1s, l2, bad, sw, bias)
 
 
 def test_shape_errors_and_workspace_size(lib):
@@ -141,15 +158,19 @@ def test_shape_errors_and_workspace_size(lib):
     assert lib.svdq_prepared_sizes(C.byref(S.make_shape(0, 64, 16)), C.byref(sz)) == -1
     assert lib.svdq_prepared_sizes(None, C.byref(sz)) == -1
     assert lib.svdq_prepared_sizes(C.byref(S.make_shape(128, 64, 16)), C.byref(sz)) == 0
-    assert (sz.rinv, sz.l1s, sz.l2, sz.wcodes, sz.wscales, sz.bias) == (512, 128 * 16 * 2, 256 * 16 * 2, 2 * 256 * 32, 2 * 256 * 2, 1024)
+    assert (sz.rinv, sz.l1s, sz.l2, sz.wcodes, sz.wscales, sz.bias) == (512, 128 * 16 * 2, 256 * 16 * 2, 2 * 4 * 2304, 2 * 256 * 2, 1024)
     sh = S.make_shape(3072, 12288, 32)
     ws = S.svdq_workspace_bytes(4608, sh)
-    # codes M*K (one int8 = 16 * code each) + scales 2*M*G + H 4*M*r as fp32 and again as bf16 hi/lo operand
-    # fragments, all with M padded to 256 (4608 is a multiple already)
-    assert ws == 4608 * 3072 + 2 * 4608 * 48 + 2 * 4 * 4608 * 32
-    # a one-token forward runs 64x128 tiles (96 of them) with the K loop split four ways: one arrival counter per
-    # tile (padded to 256 bytes) and four fp32 partial tiles per tile come on top
-    assert S.svdq_workspace_bytes(1, sh) == 256 * 3072 + 2 * 256 * 48 + 2 * 4 * 256 * 32 + 512 + 4 * 96 * 64 * 128 * 4
+    # activation blocks (1792 bytes per group and 32 tokens: 6-bit codes and fp16 scales) + H 4*M*r as fp32 and again
+    # as bf16 hi/lo operand fragments, all with M padded to 256 (4608 is a multiple already)
+    assert ws == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32
+    # a one-token forward runs one row of 48 tiles of 128 x 256 with the K loop split four ways: one arrival counter
+    # per tile (padded to 256 bytes) and four fp32 partial tiles per tile come on top
+    assert S.svdq_workspace_bytes(1, sh) == 48 * 8 * 1792 + 2 * 4 * 256 * 32 + 256 + 4 * 48 * 128 * 256 * 4
+    # the K split can be forced per thread through the option word (bits 8-11), which the size query follows
+    lib.svdq_forward_options(2 << 8)
+    assert S.svdq_workspace_bytes(1, sh) == 48 * 8 * 1792 + 2 * 4 * 256 * 32 + 256 + 2 * 48 * 128 * 256 * 4
+    lib.svdq_forward_options(0)
     assert S.svdq_workspace_bytes(16, S.make_shape(100, 64, 16)) == 0
     # forward argument checks happen before any GPU call
     bad = S.LayerDev()
