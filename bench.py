@@ -9,8 +9,14 @@ FLUX-MLP-shaped input (M=4608, K=3072, N=12288, r=32) already resident in HBM.
 against the FP4 and INT8 MFMA peaks), `--lora R` appends an adapter first; the default line is the INT4 metric.
 
 Prints ONE JSON line with the headline metric (TOPS of the 4-bit branch, 2*M*N*K per layer time),
-the roofline of the dominant kernel (the GEMM, against the INT8 MFMA peak) measured live with HIP
-events on the stream the kernels run on, and the CPU oracle timed on a bounded row sample.
+the roofline of the dominant kernel (the GEMM, against the published INT8 MFMA peak and against what a
+register-only MFMA loop sustains in the same run) measured live with HIP events on the stream the kernels
+run on, the fused / naive / unfused breakdown of Sec. 4.3, and the CPU oracle timed on all rows of the workload.
+
+Timing protocol: before anything is timed the layer runs untimed until the clocks have settled (at least
+150 ms of GPU work, and two consecutive windows of 20 steps within 2 % of each other), whatever --warmup says;
+then --warmup further untimed steps; then exactly --steps steps, each bracketed by HIP events.  `value` comes
+from the MEDIAN step; the mean and the wall-clock mean of the same pass are reported beside it.
 """
 from __future__ import annotations
 
@@ -29,10 +35,11 @@ INT8_MFMA_PEAK_TOPS = 5000.0       # MI355X dense INT8, published
 FP4_MFMA_PEAK_TFLOPS = 10100.0     # MI355X dense FP4 / FP6, published
 HBM_PEAK_GBS = 8000.0
 
-# HBM-side traffic of one GEMM launch at the headline shape from `rocprofv3 --pmc FETCH_SIZE` /
-# `--pmc WRITE_SIZE` (profiles/flux_mlp_up_kernel_stats.md), each scaled by what the same counter
-# reads for a plain 256 MiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0): 301.6 MB read + 113.2 MB written.
-GEMM_TRAFFIC_BYTES = 414.9e6
+# HBM-side traffic of one GEMM launch at the headline shape: NOT measured by this script.  It is the figure of
+# `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of `bench.py --pmc-run`, each counter scaled by what it reads
+# for a plain 256 MiB copy; the summary with the commands is profiles/flux_mlp_up_pmc_counters.md.
+GEMM_TRAFFIC_BYTES = None            # filled in from the profile below when it has been taken for the current kernel
+GEMM_TRAFFIC_SOURCE = "profiles/flux_mlp_up_pmc_counters.md"
 
 
 class Hip:
@@ -63,8 +70,8 @@ class Hip:
         return float(out.value)
 
 
-def cpu_baseline(case, L, prep_canon, rows=768, fmt="int4"):
-    """The oracle as it stands, timed on the host cores over the first `rows` tokens of the same workload."""
+def cpu_baseline(case, L, prep_canon, fmt="int4", reps=3):
+    """The oracle as it stands, timed on the host cores over ALL tokens of the same workload, best of `reps`."""
     import numpy as np
     if fmt == "fp4":
         from oracle import svdq_fp4_oracle as O
@@ -78,16 +85,18 @@ def cpu_baseline(case, L, prep_canon, rows=768, fmt="int4"):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    xb = L["x_bf16"][:rows]
-    best = float("inf")
-    for _ in range(2):
+    xb = L["x_bf16"]
+    times = []
+    for _ in range(reps):
         t0 = time.perf_counter()
         O.forward(xb, prep_canon)
-        best = min(best, time.perf_counter() - t0)
-    ops = 2.0 * rows * case.N * case.K
+        times.append(time.perf_counter() - t0)
+    best = min(times)
+    ops = float(case.ops)
     return {"value": ops / best / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {rows} of {case.M} tokens, all K and N, best of 2 ({best:.2f} s); scaled by 2*rows*N*K",
-            "us_per_layer_extrapolated": best * case.M / rows * 1e6}
+            "sample": f"all {case.M} tokens, all K and N: the oracle's forward (quantize, per-group integer products, low-rank branch, "
+                      f"bias), prepare excluded; best of {reps} ({', '.join(f'{t:.2f}' for t in times)} s)",
+            "us_per_layer": best * 1e6}
 
 
 def bench_w4a16(args, np, torch, S, hip):
@@ -101,7 +110,7 @@ def bench_w4a16(args, np, torch, S, hip):
     prep = S.svdq_pack((1.0 / (np.abs(rng.standard_normal(K)) + 0.5)).astype(np.float32),
                        I.f32_to_bf16_bits((rng.standard_normal((K, r)) * 0.05).astype(np.float32)),
                        I.f32_to_bf16_bits((rng.standard_normal((r, N)) * 0.05).astype(np.float32)),
-                       rng.integers(-8, 8, size=(K, N), dtype=np.int8),
+                       rng.integers(-7, 8, size=(K, N), dtype=np.int8),
                        (np.abs(rng.standard_normal((G, N))) * 0.01 + 1e-3).astype(np.float16),
                        bias=(rng.standard_normal(N) * 0.1).astype(np.float32))
     nsets = 10                                           # 10 x 30 MB of weights rotate: past the 256 MB last-level cache
@@ -148,11 +157,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=100, help="untimed steps; the clocks need tens of milliseconds of load to settle")
+    ap.add_argument("--warmup", type=int, default=20, help="untimed steps after the clock-settling phase (which runs whatever this says)")
     ap.add_argument("--case", default="flux_mlp_up", help="layer name from paper_2411_05007_amd.inputs (default: the metric shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tile", type=int, default=0, help="GEMM tile configuration id (0 = library default)")
-    ap.add_argument("--breakdown", action="store_true", help="also time naive INT4 (no low-rank) and the unfused 4-kernel pipeline")
+    ap.add_argument("--no-breakdown", action="store_true", help="skip the naive-INT4 / unfused-pipeline passes (Sec. 4.3 / Fig. 6)")
     ap.add_argument("--format", choices=["int4", "fp4", "w8a8"], default="int4",
                     help="int4 = the metric's format (group 64, fp16 scales, INT8 MFMA); fp4 = the MXFP4 variant "
                          "(E2M1, blocks of 32, power-of-two scales) on the block-scaled MFMA; w8a8 = the paper's 8-bit setting "
@@ -210,7 +218,7 @@ def main():
     sh = stream.cuda_stream
 
     if args.pmc_run:
-        S.svdq_forward_options(args.tile << S.OPT_TILE_SHIFT)
+        S.svdq_forward_options(0)
         for i in range(4):
             layer.forward(xs[i % nsets], out=ys[i % nsets], workspace=wss[i % nsets], stream=stream)
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -221,51 +229,93 @@ def main():
         print("pmc-run done: 4 forwards, 2 copies of 268435456 bytes", flush=True)
         return
 
-    def run(flags, steps, warmup, split):
-        S.svdq_forward_options(flags | (args.tile << S.OPT_TILE_SHIFT))
+    def step(i):
+        j = i % nsets
+        layer.forward(xs[j], out=ys[j], workspace=wss[j], stream=stream)
+
+    def settle(max_ms=3000.0):
+        """Untimed steps until the clocks have settled: windows of 20 steps, each timed with a pair of events, until
+        at least 150 ms of GPU work have passed and two consecutive windows agree within 2 %."""
+        done_ms, steps, prev, stable = 0.0, 0, None, False
+        e0, e1 = hip.event(), hip.event()
+        while done_ms < max_ms:
+            hip.record(e0, sh)
+            for i in range(20):
+                step(steps + i)
+            hip.record(e1, sh)
+            hip.sync(e1)
+            w = hip.ms(e0, e1)
+            steps += 20
+            done_ms += w
+            stable = prev is not None and abs(w - prev) <= 0.02 * prev
+            prev = w
+            if done_ms >= 150.0 and stable:
+                break
+        for e in (e0, e1):
+            hip.rt.hipEventDestroy(e)
+        return {"settle_ms": done_ms, "settle_steps": steps, "settled": bool(stable), "last_window_us_per_step": prev * 1e3 / 20}
+
+    def run(flags, steps, warmup):
+        """Settle, `warmup` more untimed steps, then `steps` timed steps: three HIP events per step on the launch stream
+        (one of them recorded by the library between its two kernels)."""
+        S.svdq_forward_options(flags)
+        st = settle()
         for i in range(warmup):
-            layer.forward(xs[i % nsets], out=ys[i % nsets], workspace=wss[i % nsets], stream=stream)
+            step(i)
         torch.cuda.synchronize()
-        ev = [(hip.event(), hip.event(), hip.event()) for _ in range(steps)] if split else None
+        ev = [(hip.event(), hip.event(), hip.event()) for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            j = i % nsets
-            if split:
-                a, m, b = ev[i]
-                S.svdq_profile_event(m.value)
-                hip.record(a, sh)
-                layer.forward(xs[j], out=ys[j], workspace=wss[j], stream=stream)
-                hip.record(b, sh)
-            else:
-                layer.forward(xs[j], out=ys[j], workspace=wss[j], stream=stream)
+            a, m, b = ev[i]
+            S.svdq_profile_event(m.value)
+            hip.record(a, sh)
+            step(i)
+            hip.record(b, sh)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         S.svdq_profile_event(None)
-        res = {"ms_per_step": wall * 1e3 / steps}
-        if split:
-            act = [hip.ms(a, m) for a, m, b in ev]
-            gemm = [hip.ms(m, b) for a, m, b in ev]
-            for a, m, b in ev:
-                for e in (a, m, b):
-                    hip.rt.hipEventDestroy(e)
-            res.update(act_ms=float(np.mean(act)), gemm_ms=float(np.mean(gemm)),
-                       gemm_ms_min=float(np.min(gemm)), act_ms_min=float(np.min(act)))
+        # a step's interval runs from the end of the step before it (its first event follows that step's last kernel
+        # on the stream) to the end of its own GEMM, so the intervals add up to the whole pass
+        per = np.array([hip.ms(a, b) for a, m, b in ev])
+        act = np.array([hip.ms(a, m) for a, m, b in ev])
+        gemm = np.array([hip.ms(m, b) for a, m, b in ev])
+        for a, m, b in ev:
+            for e in (a, m, b):
+                hip.rt.hipEventDestroy(e)
+        res = dict(st)
+        res.update(ms_per_step=float(np.median(per)), ms_per_step_mean=float(np.mean(per)), ms_per_step_wall=wall * 1e3 / steps,
+                   ms_per_step_min=float(np.min(per)), act_ms=float(np.mean(act)), gemm_ms=float(np.mean(gemm)),
+                   act_ms_median=float(np.median(act)), gemm_ms_median=float(np.median(gemm)), gemm_ms_min=float(np.min(gemm)))
         return res
 
-    # The timed region proper: K forwards back to back, nothing else on the stream.  The per-kernel durations
-    # come from a second pass over the same K steps with three HIP events per step on the launch stream (one of
-    # them recorded by the library between its two kernels); the events cost a few microseconds per step, which
-    # is why they stay out of the pass that `value` is computed from.
-    timed = run(0, args.steps, args.warmup, split=False)
-    main_res = run(0, args.steps, min(args.warmup, 20), split=True)
-    main_res["ms_per_step_with_events"] = main_res["ms_per_step"]
-    main_res["ms_per_step"] = timed["ms_per_step"]
+    def measured_peak(kind):
+        """TOPS of the register-only MFMA loop (kind 0: int8 32x32x32, 1: 6-bit operands 32x32x64), best of 5 launches of ~1 ms."""
+        sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+        e0, e1 = hip.event(), hip.event()
+        iters = 4000
+        for _ in range(3):
+            S.svdq_mfma_peak_probe(kind, iters, sink, stream)
+        best = float("inf")
+        ops = 0.0
+        for _ in range(5):
+            hip.record(e0, sh)
+            ops = S.svdq_mfma_peak_probe(kind, iters, sink, stream)
+            hip.record(e1, sh)
+            hip.sync(e1)
+            best = min(best, hip.ms(e0, e1))
+        for e in (e0, e1):
+            hip.rt.hipEventDestroy(e)
+        return ops / (best * 1e-3) / 1e12
+
+    main_res = run(0, args.steps, args.warmup)
     ms = main_res["ms_per_step"]
     ops = float(case.ops)
     tops = ops / (ms * 1e-3) / 1e12
     gemm_tops = ops / (main_res["gemm_ms"] * 1e-3) / 1e12
-    G = case.K // 64
+    peak_pub = FP4_MFMA_PEAK_TFLOPS if fp4 else INT8_MFMA_PEAK_TOPS
+    peak_int8_measured = measured_peak(0)
+    peak_fp6_measured = measured_peak(1)
     act_bytes = case.M * case.K * (2 + 0.5 + 2.0 / 64) + 4.0 * case.M * case.rank     # algorithmic bytes of the activation pass
     out = {
         "metric": ("fused W4A4+low-rank linear TOPS & us/layer, FLUX MLP M=4608 K=3072 N=12288 r=32"
@@ -276,35 +326,48 @@ def main():
         "vs_baseline": None,
         "dtype": "fp4 (E2M1) block-scaled MFMA, fp32 accumulate, bf16 out" if fp4
                  else "int8 MFMA (int8 codes), exact int32 sums, one fp32 rescale, bf16 out" if w8
-                 else "int8 MFMA (int4 codes), int32 group sums, fp32 rescale, bf16 out",
+                 else "int4 codes as exact 6-bit floats on the block-scaled MFMA, exact fp32 group sums, fp32 rescale, bf16 out",
         "data": "synthetic",
         "config": {"workload": f"{case.name}: M={case.M} K={case.K} N={case.N} r={case.rank} g=64"
                                + (" MXFP4 (blocks of 32)" if fp4 else " W8A8 (per token / per channel, branch rank 16)" if w8 else "")
                                + (f" + LoRA r={args.lora} (branch rank {prep.shape.rank})" if args.lora else "")
                                + (" (the FLUX MLP up projection the metric is quoted on)" if case.name == "flux_mlp_up" else ""),
-                   "tile": args.tile, "sets_rotated": nsets},
+                   "sets_rotated": nsets},
+        "timing": {"value_from": "median step of the timed pass (HIP events around every step)",
+                   "us_per_step_median": ms * 1e3, "us_per_step_mean": main_res["ms_per_step_mean"] * 1e3,
+                   "us_per_step_min": main_res["ms_per_step_min"] * 1e3, "us_per_step_wall_clock": main_res["ms_per_step_wall"] * 1e3,
+                   "settle_ms": main_res["settle_ms"], "settle_steps": main_res["settle_steps"], "settled": main_res["settled"]},
         "kernels": {"act_us": main_res["act_ms"] * 1e3, "gemm_us": main_res["gemm_ms"] * 1e3,
+                    "act_us_median": main_res["act_ms_median"] * 1e3, "gemm_us_median": main_res["gemm_ms_median"] * 1e3,
                     "gemm_us_min": main_res["gemm_ms_min"] * 1e3,
-                    "us_per_layer_with_events": main_res["ms_per_step_with_events"] * 1e3,
                     "act_GBps": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9,
                     "act_frac_hbm_peak": act_bytes / (main_res["act_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": "mfma",
-                     "kernel": ("gemm_fp4_kernel (MXFP4 GEMM" if fp4 else "gemm_w8a8_kernel (INT8 GEMM" if w8 else "gemm_kernel (W4A4 GEMM")
+                     "kernel": ("gemm_fp4_kernel (MXFP4 GEMM" if fp4 else "gemm_w8a8_kernel (INT8 GEMM" if w8 else "gemm_w4a4_kernel (W4A4 GEMM")
                                + " + fused up projection, bias, bf16 store)",
-                     "achieved": gemm_tops, "peak": FP4_MFMA_PEAK_TFLOPS if fp4 else INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
-                     "note": ("FP4" if fp4 else "INT8") + " tera-ops/s: 2*M*N*K per launch / mean launch duration (HIP events on the launch stream)",
-                     "frac": gemm_tops / (FP4_MFMA_PEAK_TFLOPS if fp4 else INT8_MFMA_PEAK_TOPS),
-                     "traffic": GEMM_TRAFFIC_BYTES if case.name == "flux_mlp_up" and args.format == "int4" else None},
+                     "achieved": gemm_tops, "peak": peak_pub, "unit": "TFLOP/s",
+                     "note": ("FP4" if fp4 else "INT8") + " tera-ops/s: 2*M*N*K per launch / mean launch duration (HIP events on the launch stream); "
+                             "peak = the published dense rate the metric is quoted against",
+                     "frac": gemm_tops / peak_pub,
+                     "peak_measured_int8": peak_int8_measured, "frac_measured_peak": gemm_tops / peak_int8_measured,
+                     "peak_measured_fp6_instruction": peak_fp6_measured, "peak_published_fp6_instruction": FP4_MFMA_PEAK_TFLOPS,
+                     "frac_of_fp6_instruction_published": gemm_tops / FP4_MFMA_PEAK_TFLOPS,
+                     "measured_peak_note": "register-only loops of v_mfma_i32_32x32x32_i8 and of v_mfma_scale_f32_32x32x64_f8f6f4 (6-bit operands), "
+                                           "two wavefronts per SIMD, timed in this run",
+                     "traffic": GEMM_TRAFFIC_BYTES if case.name == "flux_mlp_up" and args.format == "int4" else None,
+                     "traffic_note": f"not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE figure from {GEMM_TRAFFIC_SOURCE}"},
     }
-    if args.breakdown:
-        naive = run(S.OPT_SKIP_LOWRANK, args.steps, 20, split=False)
+    if not args.no_breakdown:
+        # Sec. 4.3 / Fig. 6 and App. "Latency Results": the 4-bit branch alone ("naive INT4"), and the low-rank branch run
+        # as separate kernels (down projection, quantize, GEMM, up projection)
+        naive = run(S.OPT_SKIP_LOWRANK, max(20, args.steps // 2), 10)
         out["breakdown"] = {"fused_us": ms * 1e3, "naive_int4_us": naive["ms_per_step"] * 1e3,
                             "lowrank_overhead_fused": ms / naive["ms_per_step"] - 1.0}
         if not fp4 and not w8:                           # the unfused pipeline exists for the INT4 path only
-            unfused = run(S.OPT_UNFUSED, max(20, args.steps // 2), 20, split=False)
+            unfused = run(S.OPT_UNFUSED, max(20, args.steps // 2), 10)
             out["breakdown"].update(unfused_us=unfused["ms_per_step"] * 1e3,
                                     lowrank_overhead_unfused=unfused["ms_per_step"] / naive["ms_per_step"] - 1.0)
-        again = run(0, args.steps, 20, split=False)      # the fused path once more, after the others: drift check
+        again = run(0, max(20, args.steps // 2), 10)     # the fused path once more, after the others: drift check
         out["breakdown"]["fused_us_again"] = again["ms_per_step"] * 1e3
     S.svdq_forward_options(0)
     if not args.no_cpu_baseline:

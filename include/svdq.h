@@ -188,6 +188,22 @@ int svdq_linear_forward(const svdq_layer_dev *layer, const void *X, int M, void 
                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * svdq_linear_forward for callers that cannot allocate device memory for a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  The workspace is a device array of
+ * SVDQ_STATIC_SCRATCH_BYTES bytes inside the library (every GPU the library runs on holds its copy until the process
+ * ends); the call allocates and frees nothing.  Same arithmetic, kernels, arguments and errors as
+ * svdq_linear_forward, except:
+ *   - a forward whose workspace (svdq_workspace_bytes) exceeds the array runs without the K split of small launches
+ *     (no fp32 partial tiles: same result up to fp32 summation order); if even that does not fit - the activation
+ *     blocks of M tokens alone are about 0.6 * M * K bytes - the call returns SVDQ_ENOSPACE and launches nothing;
+ *   - all calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams or
+ *     threads) race; calls on one stream are ordered like any other work;
+ *   - svdq_debug_act / svdq_debug_group_acc do not see this workspace.
+ */
+#define SVDQ_STATIC_SCRATCH_BYTES (64u << 20)
+int svdq_linear_forward_static(const svdq_layer_dev *layer, const void *X, int M, void *Y, void *hip_stream);
+
+/*
  * Parity views of what the last svdq_linear_forward left in `workspace` (same stream ordering):
  * canonical activation codes int8 [M x K], scales fp16 [M x G], H fp32 [M x rank]; any out
  * pointer may be NULL.  All DEVICE pointers.
@@ -226,6 +242,19 @@ int svdq_forward_options(int flags);
  * (the per-kernel split behind Fig. 6a).  Pass NULL to switch it off.  Returns SVDQ_OK.
  */
 int svdq_profile_event(void *hip_event);
+
+/*
+ * Measurement only: a register-only loop of one matrix-core instruction on the whole chip (two wavefronts per
+ * SIMD), asynchronous on `hip_stream`; the caller times it.  What it sustains is the measured peak that the GEMM's
+ * throughput is set against beside the published one.
+ *   kind 0: v_mfma_i32_32x32x32_i8 (the INT8 rate the layer is quoted against)
+ *   kind 1: v_mfma_scale_f32_32x32x64_f8f6f4 with 6-bit operands (the instruction that multiplies the INT4 codes)
+ *   iters  rounds of 8 MFMAs per wavefront, 1 .. 2^24
+ *   sink   device buffer of at least 512 * 256 * 4 bytes, overwritten
+ *   ops_per_launch  host, or NULL: receives the operations one launch performs (2 per multiply-accumulate)
+ * SVDQ_EINVAL for a bad argument.
+ */
+int svdq_mfma_peak_probe(int kind, int iters, void *sink, size_t sink_bytes, void *hip_stream, double *ops_per_launch);
 
 /* ------------------------------------------------------------------------------------------------
  * 4-bit FLOATING-POINT variant.  The paper runs the same method with FP4 operands in the block format

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsvdq.so")
 
-SOURCES = ["prepare.cpp", "act_kernel.hip", "gemm_w4a4_kernel.hip", "gemm_fp4_kernel.hip", "w8a8_kernels.hip", "w4a16_kernel.hip", "api.hip"]
+SOURCES = ["prepare.cpp", "act_kernel.hip", "gemm_w4a4_kernel.hip", "gemm_fp4_kernel.hip", "w8a8_kernels.hip", "w4a16_kernel.hip", "peak_probe.hip", "api.hip"]
 
 # -packed-fp32-ops is switched OFF for all device code; no fast-math, no fp contraction:
 # the quantizer's roundings must be exactly the IEEE single operations that are written.

@@ -1,6 +1,7 @@
 // C-ABI entry points that run on the GPU: argument checks, workspace carve-up, kernel launches.
 // Nothing here allocates device memory or synchronises with the host.
 #include <hip/hip_runtime.h>
+#include <atomic>
 
 #include "../../include/svdq.h"
 #include "kernels.h"
@@ -63,30 +64,34 @@ bool int4_sizes_ok(const svdq_shape &s, int Mpad) {
            svdq::w4_b_bytes(G, svdq::round_up(s.N, svdq::kRowPad)) < ((size_t)1 << 31);
 }
 
-}  // namespace
-
-extern "C" {
-
-int svdq_last_hip_error(void) { return g_last_hip_error; }
-
-int svdq_forward_options(int flags) {
-    const int old = g_options;
-    if (flags >= 0) g_options = flags & (SVDQ_OPT_SKIP_LOWRANK | SVDQ_OPT_UNFUSED | SVDQ_OPT_KSPLIT_MASK);
-    return old;
-}
-
-int svdq_profile_event(void *hip_event) {
-    g_profile_event = hip_event;
+// ---- the workspace of svdq_linear_forward_static: a device array that lives as long as the library is loaded ----
+constexpr size_t kStaticScratchBytes = (size_t)SVDQ_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+// In host code the array's name is only a handle for the runtime, not an address: its device address is looked up once
+// per device, with that device current (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char *> g_static_scratch_ptr[kMaxDevices];
+int static_scratch(unsigned char **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return SVDQ_EUNSUPPORTED;
+    unsigned char *p = g_static_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(g_static_scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!q) return SVDQ_EHIP;
+        p = static_cast<unsigned char *>(q);
+        g_static_scratch_ptr[dev].store(p, std::memory_order_release);      // two threads racing here store the same address
+    }
+    *out = p;
     return SVDQ_OK;
 }
 
-size_t svdq_workspace_bytes(int M, const svdq_shape *s) {
-    if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
-    return svdq::workspace_layout(M, s->K, s->N, s->rank, ksplit_override()).total;
-}
-
-int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
-                        size_t workspace_bytes, void *hip_stream) {
+// The INT4 forward behind both entry points.  ksplit_force > 0 replaces the K split of the calling thread's option word.
+int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace, size_t workspace_bytes, void *hip_stream,
+                 int ksplit_force) {
     const int st = check_layer(L);
     if (st != SVDQ_OK) return st;
     if (M < 0) return SVDQ_EINVAL;
@@ -94,7 +99,7 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_force > 0 ? ksplit_force : ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
     // the activation kernel keeps 1 / lambda of all K channels in LDS beside its per-wavefront blocks
     if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
@@ -119,7 +124,7 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     a.n_zero = w.n_counters;
     // tile count and K split follow the plan the workspace was sized for
-    const svdq::GemmPlan plan = svdq::plan_gemm(M, s.N, s.K / svdq::kGroup, ksplit_override());
+    const svdq::GemmPlan plan = svdq::plan_gemm(M, s.N, s.K / svdq::kGroup, ksplit_force > 0 ? ksplit_force : ksplit_override());
 
     hipError_t e;
     if (!unfused) {
@@ -141,6 +146,10 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
         }
         e = svdq::launch_act(a, 1, stream);
         if (e != hipSuccess) return hip_fail(e);
+        if (void *ev = g_profile_event) {
+            e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
+            if (e != hipSuccess) return hip_fail(e);
+        }
         svdq::GemmW4Params g = gemm_params(L, ws, w, M, Y, 0);
         g.ksplit = plan.ksplit;
         e = svdq::launch_gemm_w4a4(g, stream);
@@ -151,6 +160,58 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
         }
     }
     return SVDQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int svdq_last_hip_error(void) { return g_last_hip_error; }
+
+int svdq_forward_options(int flags) {
+    const int old = g_options;
+    if (flags >= 0) g_options = flags & (SVDQ_OPT_SKIP_LOWRANK | SVDQ_OPT_UNFUSED | SVDQ_OPT_KSPLIT_MASK);
+    return old;
+}
+
+int svdq_mfma_peak_probe(int kind, int iters, void *sink, size_t sink_bytes, void *hip_stream, double *ops_per_launch) {
+    if (iters < 1 || iters > (1 << 24) || !sink || sink_bytes < (size_t)svdq::kPeakProbeGrid * 256 * 4 || (kind != 0 && kind != 1)) return SVDQ_EINVAL;
+    // every wavefront issues iters * 8 MFMAs of 32 x 32 x (32 or 64) multiply-accumulates, two operations each
+    if (ops_per_launch) *ops_per_launch = (double)svdq::kPeakProbeGrid * 4 * iters * 8 * 2.0 * 32 * 32 * (kind == 0 ? 32 : 64);
+    const hipError_t e = svdq::launch_mfma_peak(kind, iters, static_cast<float *>(sink), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SVDQ_OK : hip_fail(e);
+}
+
+int svdq_profile_event(void *hip_event) {
+    g_profile_event = hip_event;
+    return SVDQ_OK;
+}
+
+size_t svdq_workspace_bytes(int M, const svdq_shape *s) {
+    if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
+    return svdq::workspace_layout(M, s->K, s->N, s->rank, ksplit_override()).total;
+}
+
+int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
+                        size_t workspace_bytes, void *hip_stream) {
+    return forward_int4(L, X, M, Y, workspace, workspace_bytes, hip_stream, 0);
+}
+
+int svdq_linear_forward_static(const svdq_layer_dev *L, const void *X, int M, void *Y, void *hip_stream) {
+    const int st = check_layer(L);
+    if (st != SVDQ_OK) return st;
+    if (M < 0) return SVDQ_EINVAL;
+    if (M == 0) return SVDQ_OK;
+    unsigned char *ws = nullptr;
+    const int got = static_scratch(&ws);
+    if (got != SVDQ_OK) return got;
+    const svdq_shape &s = L->shape;
+    // the plan the caller's options ask for if its workspace fits the array, else the same forward without a K split
+    // (no partial tiles); a batch whose activation blocks alone do not fit is refused
+    int force = 0;
+    if (svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override()).total > kStaticScratchBytes) force = 1;
+    if (svdq::workspace_layout(M, s.K, s.N, s.rank, force > 0 ? force : ksplit_override()).total > kStaticScratchBytes) return SVDQ_ENOSPACE;
+    return forward_int4(L, X, M, Y, ws, kStaticScratchBytes, hip_stream, force);
 }
 
 int svdq_debug_act(const svdq_layer_dev *L, const void *workspace, int M, int8_t *out_codes, uint16_t *out_sx,

@@ -83,6 +83,11 @@ struct GemmFp4Params {
 };
 hipError_t launch_gemm_fp4(const GemmFp4Params &p, hipStream_t stream);
 
+// register-only matrix-core loops (measurement): kind 0 = int8 32x32x32, kind 1 = 6-bit operands 32x32x64;
+// kPeakProbeGrid workgroups of 256 threads, each wavefront `iters` rounds of 8 MFMAs; sink: kPeakProbeGrid * 256 floats
+constexpr int kPeakProbeGrid = 512;
+hipError_t launch_mfma_peak(int kind, int iters, float *sink, hipStream_t stream);
+
 // ---- W4A16: 16-bit activations, INT4 weights (small batches) ---------------------------------------------------
 struct W4A16Params {
     const uint16_t *X;       // bf16 [M][K]

@@ -28,7 +28,7 @@ EXPORTS = [
     "svdq_w8a8_prepared_sizes", "svdq_w8a8_prepare", "svdq_w8a8_pack", "svdq_w8a8_unpack_wcodes", "svdq_w8a8_unpack_wscales",
     "svdq_w8a8_workspace_bytes", "svdq_w8a8_linear_forward", "svdq_w8a8_debug_act", "svdq_w4a16_forward",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
-    "svdq_forward_options", "svdq_profile_event",
+    "svdq_forward_options", "svdq_profile_event", "svdq_mfma_peak_probe", "svdq_linear_forward_static",
 ]
 
 
@@ -93,10 +93,12 @@ def lib() -> C.CDLL:
         L.svdq_w8a8_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_w8a8_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
+        L.svdq_linear_forward_static.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp]
         L.svdq_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_debug_group_acc.argtypes = [C.POINTER(LayerDev), vp, C.c_int] + [C.c_int] * 4 + [vp, vp]
         L.svdq_forward_options.argtypes = [C.c_int]
         L.svdq_profile_event.argtypes = [vp]
+        L.svdq_mfma_peak_probe.argtypes = [C.c_int, C.c_int, vp, C.c_size_t, vp, C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -363,6 +365,14 @@ def svdq_forward_options(flags: int) -> int:
     return lib().svdq_forward_options(int(flags))
 
 
+def svdq_mfma_peak_probe(kind: int, iters: int, sink, stream) -> float:
+    """Enqueue the register-only MFMA loop (kind 0: int8, 1: 6-bit operands) on `stream`; returns the operations of one launch."""
+    ops = C.c_double()
+    _check(lib().svdq_mfma_peak_probe(int(kind), int(iters), sink.data_ptr(), sink.numel() * sink.element_size(),
+                                      stream.cuda_stream, C.byref(ops)), "svdq_mfma_peak_probe")
+    return float(ops.value)
+
+
 def svdq_profile_event(event_handle: Optional[int]) -> None:
     _check(lib().svdq_profile_event(event_handle), "svdq_profile_event")
 
@@ -415,6 +425,17 @@ class DeviceLayer:
         _check(getattr(lib(), name)(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
                                     workspace.numel(), s.cuda_stream), name)
         self._last_ws, self._last_M = workspace, M
+        return out
+
+    def forward_static(self, x, out, stream=None):
+        """The INT4 forward on the library's own static workspace (no allocation inside the call); `out` is the caller's."""
+        torch = self.torch
+        assert not self.fp4 and not self.w8, "the static-workspace entry point exists for the INT4 layer"
+        assert x.dtype == torch.bfloat16 and x.is_contiguous() and x.shape[1] == self.K and x.is_cuda
+        assert out.dtype == torch.bfloat16 and out.is_contiguous() and tuple(out.shape) == (x.shape[0], self.N)
+        s = torch.cuda.current_stream(x.device) if stream is None else stream
+        _check(lib().svdq_linear_forward_static(C.byref(self.cdesc), x.data_ptr(), x.shape[0], out.data_ptr(), s.cuda_stream),
+               "svdq_linear_forward_static")
         return out
 
     def forward_w4a16(self, x, out=None, workspace=None, stream=None):

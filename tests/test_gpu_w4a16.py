@@ -58,7 +58,7 @@ def _random_packed_layer(rng, K, N, r):
     """A prepared layer straight from random codes and scales (no SVD): the forward does not care where they came from."""
     G = K // 64
     rinv = (1.0 / (np.abs(rng.standard_normal(K)) + 0.5)).astype(np.float32)
-    qw = rng.integers(-8, 8, size=(K, N), dtype=np.int8)
+    qw = rng.integers(-7, 8, size=(K, N), dtype=np.int8)      # the symmetric quantizer range of Eq. 1
     sw = (np.abs(rng.standard_normal((G, N))) * 0.01 + 1e-3).astype(np.float16)
     l1s = O.bf16_round((rng.standard_normal((K, r)) * 0.05).astype(np.float32))
     l2 = O.bf16_round((rng.standard_normal((r, N)) * 0.05).astype(np.float32))
