@@ -170,6 +170,9 @@ def main():
     ap.add_argument("--w4a16", type=int, default=0, metavar="ROWS",
                     help="time the 16-bit-activation forward (the adaptive-normalization linears) instead: ROWS conditioning "
                          "rows through a FLUX.1 modulation layer, 3072 -> 18432, rank 32; a memory-bound side path, not the metric")
+    ap.add_argument("--act-chunk", type=int, default=0, metavar="GROUPS",
+                    help="int4 only: groups of 64 channels per activation-kernel workgroup (255 = all of K), 0 = the library's choice")
+    ap.add_argument("--ksplit", type=int, default=0, metavar="S", help="int4 only: workgroups per output tile along K, 0 = the library's choice")
     ap.add_argument("--pmc-run", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a few forwards plus one plain copy of 256 MiB "
                          "(the known-size kernel the counters are scaled by), no timing, no JSON")
@@ -203,6 +206,8 @@ def main():
         up = (rng.standard_normal((args.lora, case.N)) * 0.02).astype(np.float32)
         prep = S.svdq_append_lora(prep, down, up, 1.0)
     layer = S.DeviceLayer(prep, dev)
+    base_opts = ((args.act_chunk & 0xff) << S.OPT_ACT_CHUNK_SHIFT) | ((args.ksplit & 0xf) << S.OPT_KSPLIT_SHIFT)
+    S.svdq_forward_options(base_opts)      # before the workspaces are sized
 
     # >= 3 independent (X, Y, workspace) sets so the footprint exceeds the 256 MB last-level cache
     nsets = 3
@@ -218,7 +223,7 @@ def main():
     sh = stream.cuda_stream
 
     if args.pmc_run:
-        S.svdq_forward_options(0)
+        S.svdq_forward_options(base_opts)
         for i in range(4):
             layer.forward(xs[i % nsets], out=ys[i % nsets], workspace=wss[i % nsets], stream=stream)
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -258,7 +263,7 @@ def main():
     def run(flags, steps, warmup):
         """Settle, `warmup` more untimed steps, then `steps` timed steps: three HIP events per step on the launch stream
         (one of them recorded by the library between its two kernels)."""
-        S.svdq_forward_options(flags)
+        S.svdq_forward_options(flags | base_opts)
         st = settle()
         for i in range(warmup):
             step(i)

@@ -231,7 +231,11 @@ enum {
                                   kernels; needs workspace of svdq_workspace_bytes()              */
     SVDQ_OPT_KSPLIT_SHIFT = 8, /* bits 8..11: workgroups per output tile along K (1..8), 0 = chosen by shape;
                                   set it before svdq_workspace_bytes(), which sizes the partial tiles  */
-    SVDQ_OPT_KSPLIT_MASK = 0xf00
+    SVDQ_OPT_KSPLIT_MASK = 0xf00,
+    SVDQ_OPT_ACT_CHUNK_SHIFT = 12, /* bits 12..19: groups of 64 input channels per activation-kernel workgroup
+                                  (1..254; 255 = all of K in one workgroup per 16 tokens), 0 = chosen by shape;
+                                  set it before svdq_workspace_bytes(), which sizes the parked partial H     */
+    SVDQ_OPT_ACT_CHUNK_MASK = 0xff000
 };
 int svdq_forward_options(int flags);
 

@@ -18,9 +18,6 @@ COMMON = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-ffp-contract=off", "-fno-fast-math",
-    # MFMA results go to ordinary VGPRs: the rescale consumes them on the vector ALU right away,
-    # and an AGPR destination would cost one v_accvgpr_read per partial sum
-    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]
 
@@ -32,6 +29,11 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+# GEMM kernels only: MFMA results go to ordinary VGPRs.  The rescale consumes them on the vector ALU right away, and an
+# AGPR destination would cost one v_accvgpr_read per partial sum.
+MFMA_VGPR = {"gemm_w4a4_kernel.hip", "gemm_fp4_kernel.hip", "w8a8_kernels.hip", "peak_probe.hip"}
+
+
 def build_library(verbose: bool = True, extra: list[str] | None = None) -> str:
     cc = hipcc()
     objs = []
@@ -39,7 +41,7 @@ def build_library(verbose: bool = True, extra: list[str] | None = None) -> str:
     os.makedirs(bdir, exist_ok=True)
     for src in SOURCES:
         obj = os.path.join(bdir, src.rsplit(".", 1)[0] + ".o")
-        cmd = [cc] + COMMON + (extra or [])
+        cmd = [cc] + COMMON + (["-mllvm", "-amdgpu-mfma-vgpr-form"] if src in MFMA_VGPR else []) + (extra or [])
         if src.endswith(".cpp"):
             cmd += ["-x", "hip"]
         cmd += ["-c", os.path.join(CSRC, src), "-o", obj]

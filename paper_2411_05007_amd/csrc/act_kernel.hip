@@ -3,11 +3,14 @@
 // and "Down Projection" share their input; quantizer = Eq. 1 per group of 64, App. "Implementation
 // Details").
 //
-// Work split: one workgroup (4 or 8 wavefronts) owns 16 tokens and all of K; wavefront w takes a contiguous
-// run of G / W groups.  A 16-token slice gives the chip barely more than one workgroup per CU, so the kernel is
-// written for latency: every wavefront keeps the loads of two groups in flight, registers stay under 128 so
-// two workgroups fit a CU (one round of workgroups, not two), and the final reduction is spread over all
-// threads.
+// Work split: one workgroup (4 or 8 wavefronts) owns 16 tokens and a run of groups of K (all of K, or one of
+// `chunks` runs); wavefront w takes a contiguous share of the run.  The kernel is written for latency: every
+// wavefront keeps the loads of two groups in flight, registers stay under 128 so that several workgroups fit a CU,
+// and the final reduction is spread over all threads.  A workgroup's life is a chain of round trips to memory, one
+// per two groups of a wavefront's share, so where a launch has few slices or K is long the runs are cut shorter and
+// more workgroups share the CUs; the partial H of a slice's runs then meet in the workspace, and the workgroup that
+// arrives last adds them in run order.  Parking is not free (device-scope accesses go past the L2), so the runs
+// are only cut as far as it pays (layout.h, plan_act).
 // Two lane maps are in play.  Memory is read with lane l -> token l/8 (and l/8 + 8 for the second load),
 // channels 8*(l%8) .. +7 of the group: every load instruction then covers whole 128-byte lines, which the
 // memory pipeline serves at twice the rate of the 16-lines-by-halves pattern that the matrix core's operand
@@ -20,6 +23,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "act_common.h"
 #include "buffer.h"
 #include "kernels.h"
 #include "layout.h"
@@ -31,17 +35,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-// round-to-nearest-even fp32 -> bf16 of two values (v_cvt_pk_bf16_f32), lo in the low half
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t bf16_rne_pair(float lo, float hi) {
-    bf16x2 v;
-    v[0] = (__bf16)lo;
-    v[1] = (__bf16)hi;
-    return __builtin_bit_cast(uint32_t, v);
-}
-
 // LDS of one workgroup: the smoothing factors of all its groups (fp32 [G][64], each wavefront stages and
 // reads only its own run of groups) followed by one private block per wavefront, used first to turn X from
 // the load map into the MFMA operand map and at the end for the wavefront's partial H.
@@ -50,24 +43,9 @@ struct ActLds {
     static constexpr int kRedRow = RBMAX * 16 + 1;
     static constexpr int kXRow = 144;      // 128 B of one token's group + 16: the 16 rows of an operand read fall on distinct banks
     static constexpr int kWaveBytes = (16 * kXRow > 16 * kRedRow * 4) ? 16 * kXRow : 16 * kRedRow * 4;
-    static __host__ __device__ size_t rinv_bytes(int G) { return (size_t)G * 64 * 4; }
+    static __host__ __device__ size_t rinv_bytes(int groups) { return (size_t)groups * 64 * 4; }
     static __host__ __device__ size_t wave_bytes() { return (size_t)WAVES * kWaveBytes; }
 };
-
-// maximum over the 4 lanes of a quad (one MXFP4 block of a token in the load map)
-__device__ __forceinline__ float max_over_4_lanes(float a) {
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true)));    // quad_perm [1,0,3,2]
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4E, 0xf, 0xf, true)));    // quad_perm [2,3,0,1]
-    return a;
-}
-
-// maximum over the 8 lanes l%8 = 0..7 that share a token in the load map
-__device__ __forceinline__ float max_over_8_lanes(float a) {
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true)));    // quad_perm [1,0,3,2]
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4E, 0xf, 0xf, true)));    // quad_perm [2,3,0,1]
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x141, 0xf, 0xf, true)));   // row_half_mirror
-    return a;
-}
 
 // Byte offsets inside one group's run of activation blocks (layout.h): the first dword a lane stores for token m
 // (dword 0 of its triple for an even c8, dword 2 for an odd one), and the token's scale dword.
@@ -76,16 +54,27 @@ __device__ __forceinline__ int w4_triple_offset(int m, int c8) {
 }
 __device__ __forceinline__ int w4_scale_offset(int m) { return (m / 32) * kW4ABlock + kW4ACodes + 4 * (m % 32); }
 
+// Workgroups that must fit a CU together (this caps the registers): four of four wavefronts up to rank 64, fewer
+// where the rank's accumulators and fragments need the room.
+constexpr int act_min_workgroups(int rbmax, int waves, bool stage) {
+    if (waves > 8 || (rbmax > 4 && stage)) return 1;
+    if (waves == 8) return 2;
+    return rbmax <= 4 ? 4 : rbmax <= 8 ? 3 : 2;
+}
+
 // FMT 0: INT4 codes with fp16 group scales; FMT 1: MXFP4 (E2M1 codes, one power-of-two scale byte per block of 32)
 template <int RBMAX, int WAVES, bool QUANT, bool PROJ, bool STAGE, int FMT>
-__global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) ? 2 : 1) void act_kernel(ActParams p) {
+__global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)) void act_kernel(ActParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char act_lds[];
     using L = ActLds<RBMAX, WAVES>;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = lane & 15, blk = lane >> 4;      // MFMA operand / accumulator map
     const int r8 = lane >> 3, c8 = lane & 7;         // load map: tokens r8 and r8 + 8, channels 8*c8 .. +7
-    const int m0 = blockIdx.x * 16;
+    // workgroups of one slice are neighbours in the launch order: they read neighbouring stretches of the same rows
+    const int nchunks = p.chunks > 1 ? p.chunks : 1;
+    const int slice = blockIdx.x / nchunks, chunk = blockIdx.x - slice * nchunks;
+    const int m0 = slice * 16;
     const int ma = m0 + r8, mb = ma + 8;
     const int rb = p.rank / 16;
 
@@ -97,8 +86,10 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     // last group once more (it recomputes and rewrites the same codes and is kept out of the projection), so
     // the loop body has no divergent or data-dependent control flow around its memory operations and the
     // load/store counters can be waited on precisely
-    const int per = (p.G + WAVES - 1) / WAVES;
-    const int g0 = wave * per, g1 = (g0 + per < p.G) ? g0 + per : p.G;
+    const int gbeg = nchunks > 1 ? chunk * p.gchunk : 0;                      // this workgroup's run of groups
+    const int gend = nchunks > 1 && gbeg + p.gchunk < p.G ? gbeg + p.gchunk : p.G;
+    const int per = (gend - gbeg + WAVES - 1) / WAVES;
+    const int g0 = gbeg + wave * per, g1 = (g0 + per < gend) ? g0 + per : gend;
     const int npairs = g0 < g1 ? (g1 - g0 + 1) / 2 : 0;
 
     // All global traffic of the loop goes through buffer descriptors: a per-lane byte offset fixed for the whole
@@ -132,8 +123,10 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     auto clampg = [&](int g) { return g < g1 ? g : g1 - 1; };
     auto fetch_x = [&](int g) {
         XStage s;
-        s.x0 = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, vxa, g * 128, 0));
-        s.x1 = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, vxb, g * 128, 0));
+        // X is read once: the loads carry the streaming hint, so that its lines do not push the L1 fragments, which every
+        // workgroup reads, out of the L2
+        s.x0 = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, vxa, g * 128, 2));
+        s.x1 = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, vxb, g * 128, 2));
         return s;
     };
     auto fetch_b = [&](int g) {
@@ -155,8 +148,9 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     // operands of its first two groups; the factors are the older loads, so dropping them into LDS (where
     // they cost no registers) waits for them alone.
     float *lrinv = reinterpret_cast<float *>(act_lds);
-    unsigned char *wlds = act_lds + L::rinv_bytes(QUANT ? p.G : 0) + (size_t)wave * L::kWaveBytes;
-    const int kr0 = 64 * g0 + 4 * lane, kr1 = kr0 + 256, kend = 64 * g1;
+    const int glds = nchunks > 1 ? p.gchunk : p.G;      // groups whose factors the LDS holds, from gbeg on
+    unsigned char *wlds = act_lds + L::rinv_bytes(QUANT ? glds : 0) + (size_t)wave * L::kWaveBytes;
+    const int kr0 = 64 * g0 + 4 * lane, kr1 = kr0 + 256, kend = 64 * g1, kbeg = 64 * gbeg;
     float4 rv0 = make_float4(0.f, 0.f, 0.f, 0.f), rv1 = rv0;
     if (QUANT && npairs > 0) {
         // out-of-run lanes read the run's first factors again (an address that is always valid) and drop them
@@ -178,10 +172,10 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     }
     if (QUANT && npairs > 0) {
         // only this wavefront reads what it writes here: no barrier, the LDS queue of a wavefront is in order
-        if (kr0 < kend) *reinterpret_cast<float4 *>(lrinv + kr0) = rv0;
-        if (kr1 < kend) *reinterpret_cast<float4 *>(lrinv + kr1) = rv1;
+        if (kr0 < kend) *reinterpret_cast<float4 *>(lrinv + (kr0 - kbeg)) = rv0;
+        if (kr1 < kend) *reinterpret_cast<float4 *>(lrinv + (kr1 - kbeg)) = rv1;
         for (int k = kr1 + 256; k < kend; k += 256)      // runs longer than eight groups: the rest, one load at a time
-            *reinterpret_cast<float4 *>(lrinv + k) = *reinterpret_cast<const float4 *>(p.rinv + k);
+            *reinterpret_cast<float4 *>(lrinv + (k - kbeg)) = *reinterpret_cast<const float4 *>(p.rinv + k);
     }
 
     // X of one group, load map -> LDS -> operand map: lane (row, blk) picks up channels 16*blk .. +15 of token row
@@ -228,7 +222,7 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
     auto smooth = [&](int g, const XStage &sx) {
         Smoothed o;
         if (QUANT) {
-            const float4 *rp = reinterpret_cast<const float4 *>(lrinv + 64 * g + 8 * c8);
+            const float4 *rp = reinterpret_cast<const float4 *>(lrinv + 64 * (g - gbeg) + 8 * c8);
             const float4 r0 = rp[0], r1 = rp[1];
             const float r[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
             const uint32_t wa[4] = {sx.x0.x, sx.x0.y, sx.x0.z, sx.x0.w};
@@ -243,49 +237,9 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
         }
         return o;
     };
-    // Eq. 1 for the 8 channels this lane holds of one token's group: s = max|x| / q_max over the whole group
-    // (8 lanes), stored as fp16; codes from x * (1/s).
-    // The codes leave in the operand form of the GEMM's matrix instruction (layout.h): 6 bits per code, sign, two
-    // zero bits, magnitude; the lane's 8 codes are 48 bits (lo: bits 0-31, hi: bits 32-47), channel e at bit 6 e.
-    // Magnitudes are integer-valued floats below 8, so four of them pack exactly into one float by Horner steps
-    // with 64 (< 2^21) and one conversion; the sign of a code is the sign of x^ (1 / lambda and 1 / s are
-    // positive; a zero code may carry a sign, which the format ignores).
+    // Eq. 1 for the 8 channels this lane holds of one token's group (act_common.h)
     auto encode = [&](const float (&xh)[QUANT ? 8 : 1], uint32_t &lo, uint32_t &hi, uint32_t &sbits) {
-        float amax = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xh[e]));
-        amax = max_over_8_lanes(amax);
-        // amax / 7.0f and 1.0f / s, both correctly rounded like the IEEE divisions they stand for, in three
-        // instructions each: a product with the rounded reciprocal (1/7 as a constant, v_rcp_f32 for s, good to
-        // one ulp), the exact remainder by FMA, one correction by FMA.  For the division by 7 this equals the
-        // IEEE quotient for every finite fp32 numerator, and for 1/s for every positive fp16 s even from a
-        // start two ulps off (both checked exhaustively on the host).
-        constexpr float kInv7 = 0x1.24924ap-3f;                  // 1.0f / 7.0f
-        const float q0 = amax * kInv7;
-        float s32 = __builtin_fmaf(__builtin_fmaf(-7.0f, q0, amax), kInv7, q0);
-        s32 = fminf(s32, 65504.0f);
-        const _Float16 sh = (_Float16)s32;
-        const float sc = (float)sh;
-        const float den = sc > 0.f ? sc : 1.0f;                  // branch-free: the reciprocal always runs
-        const float y0 = __builtin_amdgcn_rcpf(den);
-        const float rcp_any = __builtin_fmaf(__builtin_fmaf(-den, y0, 1.0f), y0, y0);
-        const float rcp = sc > 0.f ? rcp_any : 0.f;
-        float mag[8];
-        uint32_t sa = 0u, sb = 0u;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            mag[e] = fminf(fabsf(__builtin_rintf(xh[QUANT ? e : 0] * rcp)), 7.f);
-            const uint32_t bits = __float_as_uint(xh[QUANT ? e : 0]);
-            const int pos = 6 * (e & 3) + 5;                      // sign position inside the 24 bits of four codes
-            if (e < 4) sa |= (bits >> (31 - pos)) & (1u << pos);
-            else sb |= (bits >> (31 - pos)) & (1u << pos);
-        }
-        const float fa = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(mag[3], 64.f, mag[2]), 64.f, mag[1]), 64.f, mag[0]);
-        const float fb = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(mag[QUANT ? 7 : 0], 64.f, mag[QUANT ? 6 : 0]), 64.f, mag[QUANT ? 5 : 0]), 64.f, mag[QUANT ? 4 : 0]);
-        const uint32_t a24 = (uint32_t)fa | sa, b24 = (uint32_t)fb | sb;
-        lo = a24 | (b24 << 24);
-        hi = b24 >> 8;
-        sbits = __builtin_bit_cast(uint16_t, sh);
+        if constexpr (QUANT) w4_encode8(xh, lo, hi, sbits);
     };
     // Eq. 1 for one MXFP4 block (the 32 channels held by 4 neighbouring lanes): the scale is the smallest power
     // of two s = 2^e >= 2^-126 with max|x| <= 6 s, found from the exponent and mantissa bits of the maximum
@@ -381,18 +335,70 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
 #pragma unroll
                 for (int v = 0; v < 4; ++v) red[(4 * blk + v) * L::kRedRow + 16 * c + row] = acc[c][v];
         __syncthreads();
-        const unsigned char *all = act_lds + L::rinv_bytes(QUANT ? p.G : 0);
+        const unsigned char *all = act_lds + L::rinv_bytes(QUANT ? glds : 0);
         // a thread takes eight neighbouring columns of one token: two 16-byte stores of fp32 H, and one each
         // of the bf16 hi and lo parts that the GEMM feeds to its matrix core as they are
-        const int chunks = p.rank / 8;
-        for (int idx = threadIdx.x; idx < 16 * chunks; idx += WAVES * 64) {
-            const int r = idx / chunks, col = 8 * (idx - r * chunks);
+        const int octets = p.rank / 8;
+        float *sums = reinterpret_cast<float *>(act_lds + 16);      // [16][rank] sums over the runs, behind the verdict word
+        if (nchunks > 1) {
+            // This run's sum goes to the workspace with device-scope atomic stores (they go past the L2 caches of the
+            // chip's XCDs, which are not coherent with each other); consecutive threads take consecutive words of the
+            // 16 x rank block.  Once they are all acknowledged the workgroup marks its arrival word and then looks at
+            // the words of all runs of its slice: the workgroup whose mark comes last finds them all set, and only a
+            // workgroup that finds them all set goes on.  (Two that arrive together may both find that: both then
+            // compute the same sums from the same partials.)
+            float *mine = p.hpart + ((size_t)chunk * p.Mpad + m0) * p.rank;
+            for (int idx = threadIdx.x; idx < 16 * p.rank; idx += WAVES * 64) {
+                const int r = idx / p.rank, col = idx - r * p.rank;
+                float h = 0.f;
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) h += reinterpret_cast<const float *>(all + (size_t)w * L::kWaveBytes)[r * L::kRedRow + col];
+                __hip_atomic_store(mine + idx, h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();                                   // also: nobody reads the wavefronts' LDS blocks any more
+            uint32_t *verdict = reinterpret_cast<uint32_t *>(act_lds);
+            if (wave == 0) {
+                unsigned long long *words = p.arrived + (size_t)slice * nchunks;
+                if (lane == 0) (void)__hip_atomic_exchange(words + chunk, kActArrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the mark has been made before the first look
+                // lane c looks at run c (at most 64 runs), all lanes at once: one round trip
+                const unsigned long long seen = __hip_atomic_load(words + (lane < nchunks ? lane : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const bool every = __builtin_amdgcn_ballot_w64(seen != kActArrived) == 0ull;
+                if (lane == 0) *verdict = every ? 1u : 0u;
+            }
+            __syncthreads();
+            if (*verdict == 0u) return;
+            // the runs' partial sums, added in run order, consecutive threads consecutive words; all loads of a batch are
+            // requested before the first addition waits
+            for (int idx = threadIdx.x; idx < 16 * p.rank; idx += WAVES * 64) {
+                const float *src = p.hpart + (size_t)m0 * p.rank + idx;
+                float h = 0.f;
+                for (int c0 = 0; c0 < nchunks; c0 += 8) {
+                    float t[8];
+#pragma unroll
+                    for (int c = 0; c < 8; ++c)
+                        t[c] = c0 + c < nchunks ? __hip_atomic_load(src + (size_t)(c0 + c) * p.Mpad * p.rank, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) h += t[c];
+                }
+                sums[idx] = h;
+            }
+            __syncthreads();
+        }
+        for (int idx = threadIdx.x; idx < 16 * octets; idx += WAVES * 64) {
+            const int r = idx / octets, col = 8 * (idx - r * octets);
             float h[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (nchunks > 1) {
 #pragma unroll
-            for (int w = 0; w < WAVES; ++w) {
-                const float *pw = reinterpret_cast<const float *>(all + (size_t)w * L::kWaveBytes) + r * L::kRedRow + col;
+                for (int e = 0; e < 8; ++e) h[e] = sums[r * p.rank + col + e];
+            } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) h[e] += pw[e];
+                for (int w = 0; w < WAVES; ++w) {
+                    const float *pw = reinterpret_cast<const float *>(all + (size_t)w * L::kWaveBytes) + r * L::kRedRow + col;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) h[e] += pw[e];
+                }
             }
             const int m = m0 + r;       // < Mpad: rows past M land in padding
             float4 *hp = reinterpret_cast<float4 *>(p.H + (size_t)m * p.rank + col);
@@ -407,15 +413,23 @@ __global__ __launch_bounds__(WAVES * 64, ((RBMAX <= 4 || !STAGE) && WAVES <= 8) 
             *reinterpret_cast<uint4 *>(p.hfrag + hfrag_offset(p.rank, m, col, 0)) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
             *reinterpret_cast<uint4 *>(p.hfrag + hfrag_offset(p.rank, m, col, 1)) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
         }
+        // the arrival words go back to "not arrived" for the next launch (every workgroup of the slice has made its mark)
+        if (nchunks > 1 && (int)threadIdx.x < nchunks)
+            __hip_atomic_store(p.arrived + (size_t)slice * nchunks + threadIdx.x, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
 template <int RBMAX, int WAVES, bool STAGE, int FMT>
 hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     using L = ActLds<RBMAX, WAVES>;
-    const dim3 grid((p.M + 15) / 16), block(WAVES * 64);
+    const int nchunks = p.chunks > 1 ? p.chunks : 1;
+    // what the kernel's indexing assumes about a cut K: runs that cover it, no empty run, one arrival word per run and lane
+    if (nchunks > 1 && (p.gchunk < 1 || (size_t)p.gchunk * nchunks < (size_t)p.G || (nchunks - 1) * p.gchunk >= p.G || !p.hpart || !p.arrived || nchunks > 64))
+        return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((p.M + 15) / 16) * nchunks), block(WAVES * 64);
     const bool q = flags & 1, pr = (flags & 2) && p.rank > 0;
-    const size_t lds = (q ? L::rinv_bytes(p.G) : 0) + (pr ? L::wave_bytes() : 0);
+    size_t lds = (q ? L::rinv_bytes(nchunks > 1 ? p.gchunk : p.G) : 0) + (pr ? L::wave_bytes() : 0);
+    if (lds < 16) lds = 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
     if (q && pr) {
@@ -482,7 +496,7 @@ hipError_t launch_act_fmt(const ActParams &p, int flags, hipStream_t stream) {
     // wavefronts each, two workgroups load a CU like one of eight does, and everybody finishes together
     // (measured at M = 4608, K = 3072: 1.3 us of ~23 faster; with up to 256 workgroups eight wavefronts are faster).
     const int slabs = (p.M + 15) / 16;
-    const bool wide = act_waves(p.K, p.rank) == 8 && !(slabs > 256 && slabs <= 512 && p.G < 64);
+    const bool wide = p.chunks >= 1 ? p.waves == 8 : act_waves(p.K, p.rank) == 8 && !(slabs > 256 && slabs <= 512 && p.G < 64);
     if (p.rank <= 32) return wide ? launch_rb<2, 8, true, FMT>(p, flags, stream) : launch_rb<2, 4, true, FMT>(p, flags, stream);
     if (p.rank <= 64) return wide ? launch_rb<4, 8, false, FMT>(p, flags, stream) : launch_rb<4, 4, false, FMT>(p, flags, stream);
     if (p.rank <= 128) {

@@ -37,6 +37,8 @@ int check_layer(const svdq_layer_dev *L, int group = svdq::kGroup) {
 
 // forced K split of the calling thread's option word (0 = by shape)
 int ksplit_override() { return (g_options & SVDQ_OPT_KSPLIT_MASK) >> SVDQ_OPT_KSPLIT_SHIFT; }
+// forced number of groups per activation-kernel workgroup (0 = by shape)
+int act_override() { return (g_options & SVDQ_OPT_ACT_CHUNK_MASK) >> SVDQ_OPT_ACT_CHUNK_SHIFT; }
 
 svdq::GemmW4Params gemm_params(const svdq_layer_dev *L, unsigned char *ws, const svdq::Workspace &w, int M, void *Y, int rank) {
     const svdq_shape &s = L->shape;
@@ -89,9 +91,10 @@ int static_scratch(unsigned char **out) {
     return SVDQ_OK;
 }
 
-// The INT4 forward behind both entry points.  ksplit_force > 0 replaces the K split of the calling thread's option word.
+// The INT4 forward behind both entry points.  ksplit_force / act_force > 0 replace the K split of the GEMM / the groups
+// per activation-kernel workgroup of the calling thread's option word.
 int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace, size_t workspace_bytes, void *hip_stream,
-                 int ksplit_force) {
+                 int ksplit_force, int act_force) {
     const int st = check_layer(L);
     if (st != SVDQ_OK) return st;
     if (M < 0) return SVDQ_EINVAL;
@@ -99,11 +102,11 @@ int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *w
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_force > 0 ? ksplit_force : ksplit_override());
+    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_force > 0 ? ksplit_force : ksplit_override(),
+                                                     act_force > 0 ? act_force : act_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    // the activation kernel keeps 1 / lambda of all K channels in LDS beside its per-wavefront blocks
-    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
-        return SVDQ_EUNSUPPORTED;
+    // the activation kernel keeps 1 / lambda of its workgroups' channels in LDS beside its per-wavefront blocks
+    if (s.K > 32768 || svdq::act_lds_bytes(w.act.gchunk, s.rank, w.act.waves) > (size_t)svdq::kLdsBytesPerCU) return SVDQ_EUNSUPPORTED;
     // the kernels address X, the activation blocks and the weight blocks with 32-bit byte offsets
     if (!int4_sizes_ok(s, w.Mpad)) return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -123,6 +126,9 @@ int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *w
     a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
     a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     a.n_zero = w.n_counters;
+    a.chunks = w.act.chunks; a.gchunk = w.act.gchunk; a.waves = w.act.waves;
+    a.hpart = reinterpret_cast<float *>(ws + w.hpart_off);
+    a.arrived = reinterpret_cast<unsigned long long *>(ws + w.aflags_off);
     // tile count and K split follow the plan the workspace was sized for
     const svdq::GemmPlan plan = svdq::plan_gemm(M, s.N, s.K / svdq::kGroup, ksplit_force > 0 ? ksplit_force : ksplit_override());
 
@@ -170,7 +176,7 @@ int svdq_last_hip_error(void) { return g_last_hip_error; }
 
 int svdq_forward_options(int flags) {
     const int old = g_options;
-    if (flags >= 0) g_options = flags & (SVDQ_OPT_SKIP_LOWRANK | SVDQ_OPT_UNFUSED | SVDQ_OPT_KSPLIT_MASK);
+    if (flags >= 0) g_options = flags & (SVDQ_OPT_SKIP_LOWRANK | SVDQ_OPT_UNFUSED | SVDQ_OPT_KSPLIT_MASK | SVDQ_OPT_ACT_CHUNK_MASK);
     return old;
 }
 
@@ -189,12 +195,12 @@ int svdq_profile_event(void *hip_event) {
 
 size_t svdq_workspace_bytes(int M, const svdq_shape *s) {
     if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
-    return svdq::workspace_layout(M, s->K, s->N, s->rank, ksplit_override()).total;
+    return svdq::workspace_layout(M, s->K, s->N, s->rank, ksplit_override(), act_override()).total;
 }
 
 int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
                         size_t workspace_bytes, void *hip_stream) {
-    return forward_int4(L, X, M, Y, workspace, workspace_bytes, hip_stream, 0);
+    return forward_int4(L, X, M, Y, workspace, workspace_bytes, hip_stream, 0, 0);
 }
 
 int svdq_linear_forward_static(const svdq_layer_dev *L, const void *X, int M, void *Y, void *hip_stream) {
@@ -206,12 +212,18 @@ int svdq_linear_forward_static(const svdq_layer_dev *L, const void *X, int M, vo
     const int got = static_scratch(&ws);
     if (got != SVDQ_OK) return got;
     const svdq_shape &s = L->shape;
-    // the plan the caller's options ask for if its workspace fits the array, else the same forward without a K split
-    // (no partial tiles); a batch whose activation blocks alone do not fit is refused
-    int force = 0;
-    if (svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override()).total > kStaticScratchBytes) force = 1;
-    if (svdq::workspace_layout(M, s.K, s.N, s.rank, force > 0 ? force : ksplit_override()).total > kStaticScratchBytes) return SVDQ_ENOSPACE;
-    return forward_int4(L, X, M, Y, ws, kStaticScratchBytes, hip_stream, force);
+    // the plan the caller's options ask for if its workspace fits the array, else the same forward without parked partial
+    // results (no K split in the GEMM, one activation-kernel workgroup per 16 tokens); a batch whose activation blocks
+    // alone do not fit is refused
+    int kforce = 0, aforce = 0;
+    if (svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override(), act_override()).total > kStaticScratchBytes) {
+        kforce = 1;
+        aforce = svdq::kActChunkWhole;
+    }
+    if (svdq::workspace_layout(M, s.K, s.N, s.rank, kforce > 0 ? kforce : ksplit_override(), aforce > 0 ? aforce : act_override()).total >
+        kStaticScratchBytes)
+        return SVDQ_ENOSPACE;
+    return forward_int4(L, X, M, Y, ws, kStaticScratchBytes, hip_stream, kforce, aforce);
 }
 
 int svdq_debug_act(const svdq_layer_dev *L, const void *workspace, int M, int8_t *out_codes, uint16_t *out_sx,
@@ -265,7 +277,7 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     const svdq_shape &s = L->shape;
     const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank, ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+    if (s.K > 32768 || svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
     if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
         return SVDQ_EUNSUPPORTED;
@@ -344,7 +356,7 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
     const svdq_shape &s = L->shape;
     const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+    if (s.K > 32768 || svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
     if (!int4_sizes_ok(s, w.Mpad)) return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -404,7 +416,7 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     const svdq_shape &s = L->shape;
     const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.rank);
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    if (s.K > 32768 || svdq::act_lds_bytes(s.K, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+    if (s.K > 32768 || svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
     if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 31))
         return SVDQ_EUNSUPPORTED;

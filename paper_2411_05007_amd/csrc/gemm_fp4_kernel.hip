@@ -114,8 +114,6 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
-    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.xcodes, (size_t)p.G * p.Mpad * kFp4RowBytes);
-    const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(p.wcodes, (size_t)p.G * p.Npad * kFp4RowBytes);
     const __amdgpu_buffer_rsrc_t rs_sa = make_rsrc(p.bx, fp4_scale_bytes(p.G, p.Mpad));
     const __amdgpu_buffer_rsrc_t rs_sb = make_rsrc(p.bw, fp4_scale_bytes(p.G, p.Npad));
 

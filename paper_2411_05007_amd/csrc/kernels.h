@@ -18,6 +18,10 @@ struct ActParams {
     int n_zero;
     int fmt;                 // 0: INT4.  1: MXFP4 - codes = packed E2M1 in the GEMM's operand order,
                              // sx = scale bytes (layout.h, fp4_code_offset / fp4_scale_offset)
+    // K cut into runs (layout.h, ActPlan); chunks = 0: one workgroup per 16 tokens walks all of K, wavefronts chosen by the launcher
+    int chunks, gchunk, waves;
+    float *hpart;                    // fp32 [chunks][Mpad][rank]: partial H of every run (chunks > 1)
+    unsigned long long *arrived;     // [Mpad / 16][chunks]: arrival words (chunks > 1)
 };
 
 // flags: bit 0 = quantize (codes + scales), bit 1 = down projection (H)
@@ -26,8 +30,8 @@ hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream);
 // W4A4 GEMM on the block-scaled matrix instruction: INT4 codes as 6-bit float operands, exact fp32 group sums,
 // scale tiles from an f16 MFMA, one FMA per partial sum (gemm_w4a4_kernel.hip; layouts in layout.h)
 struct GemmW4Params {
-    const uint8_t *xa;       // activation blocks [G][Mpad / 32][1600]: 6-bit codes + fp16 scales
-    const uint8_t *wb;       // weight blocks [G][Npad / 32][1088]: 4-bit codes + fp16 scales
+    const uint8_t *xa;       // activation blocks [G][Mpad / 32][1792]: 6-bit codes + fp16 scales
+    const uint8_t *wb;       // weight blocks [G][Npad / 64][2304]: 4-bit codes + fp16 scales
     const uint8_t *hfrag;    // H as bf16 hi + lo parts in MFMA operand order (layout.h)
     const uint16_t *l2t;     // bf16 [Npad][rank]
     const float *bias;       // fp32 [Npad]

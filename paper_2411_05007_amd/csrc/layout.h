@@ -223,24 +223,66 @@ inline GemmPlan plan_gemm(int M, int N, int G, int ksplit_override = 0) {
     return pl;
 }
 
-// LDS bytes of one activation-kernel workgroup with `waves` wavefronts: 1 / lambda of all K channels (fp32), plus
-// one private block per wavefront (X turn-around during the loop, partial H at the end).
+// LDS bytes of one activation-kernel workgroup with `waves` wavefronts that covers `groups` groups of K: 1 / lambda of
+// those channels (fp32), plus one private block per wavefront (X turn-around during the loop, partial H at the end).
 constexpr int kLdsBytesPerCU = 160 * 1024;
-inline size_t act_lds_bytes(int K, int rank, int waves) {
+inline size_t act_lds_bytes(int groups, int rank, int waves) {
     const int rbmax = rank <= 32 ? 2 : rank <= 64 ? 4 : rank <= 128 ? 8 : 16;
     const size_t red = (size_t)16 * (rbmax * 16 + 1) * 4;
-    return (size_t)K * 4 + (size_t)waves * (red > 2304 ? red : 2304);
+    return (size_t)groups * kGroup * 4 + (size_t)waves * (red > 2304 ? red : 2304);
 }
-// Wavefronts per 16-token slice: eight when K gives each of them a few groups and their LDS fits, else four.
-inline int act_waves(int K, int rank) { return (K / kGroup >= 32 && act_lds_bytes(K, rank, 8) <= (size_t)kLdsBytesPerCU) ? 8 : 4; }
+// Wavefronts of a workgroup that walks all of K by itself: eight when K gives each of them a few groups and their LDS fits.
+inline int act_waves(int K, int rank) { return (K / kGroup >= 32 && act_lds_bytes(K / kGroup, rank, 8) <= (size_t)kLdsBytesPerCU) ? 8 : 4; }
+
+// How the INT4 forward's activation kernel is cut up.  A workgroup owns 16 tokens and a run of `gchunk` groups of K
+// (`chunks` runs cover K).  A workgroup's life is a chain of round trips to memory, one per two groups of a wavefront's
+// share, so a launch with few 16-token slices, or a long K, is cut into shorter runs that share the CUs; the workgroups
+// of a slice then park their partial H in the workspace and the last one to arrive adds them up in run order.  Parked
+// sums travel with device-scope accesses, past the L2, and cost more than they look: the runs are cut only as far as
+// the launch needs to reach two to three workgroups per CU.
+struct ActPlan {
+    int chunks;      // runs per 16-token slice, 1..64
+    int gchunk;      // groups per run (the last run may be shorter)
+    int waves;       // wavefronts per workgroup: 4 or 8
+};
+constexpr int kActChunkWhole = 255;      // override value: one run, all of K
+inline ActPlan plan_act(int M, int G, int rank, int gchunk_override = 0) {
+    ActPlan pl;
+    const int slices = (M + 15) / 16;
+    // Measured on the FLUX.1 / PixArt shapes: a launch that already has a workgroup for every other CU is best left
+    // alone up to K = 4608 and cut into runs of 48 groups beyond; a launch with fewer slices is cut into up to eight
+    // runs of at least eight groups, towards one workgroup per CU.
+    int runs = 1;
+    if (slices > 128) runs = G >= 128 ? (G + 47) / 48 : 1;
+    else runs = 256 / slices < 8 ? (256 + slices - 1) / slices : 8;
+    int gc = (G + runs - 1) / runs;
+    if (gc < 8) gc = 8;
+    gc = (gc + 3) / 4 * 4;                               // whole groups for each of four wavefronts
+    if (gchunk_override > 0) gc = gchunk_override;
+    if (gc >= kActChunkWhole || gc > G) gc = G > 0 ? G : 1;
+    if ((G + gc - 1) / gc > 64) gc = (G + 63) / 64;      // one arrival word per run and lane
+    pl.chunks = (G + gc - 1) / gc;
+    if (pl.chunks < 1) pl.chunks = 1;
+    pl.gchunk = gc;
+    // eight wavefronts when a run gives each of them a few groups and their LDS fits; a whole-K launch of 257-512 slices
+    // puts two workgroups on some CUs, which then set the kernel's time: with four wavefronts each, two workgroups
+    // load a CU like one of eight does, and everybody finishes together
+    pl.waves = (gc >= 32 && act_lds_bytes(gc, rank, 8) <= (size_t)kLdsBytesPerCU) ? 8 : 4;
+    if (pl.chunks == 1 && slices > 256 && slices <= 512 && G < 64) pl.waves = 4;
+    return pl;
+}
+// the value a workgroup leaves in its arrival word; the word is cleared again before the kernel ends, so whatever a
+// fresh workspace holds is taken for "not arrived" (anything but this one 64-bit value)
+constexpr unsigned long long kActArrived = 0x5356445141525256ull;
 
 // Workspace carve-up for a forward of M tokens.
 struct Workspace {
-    size_t codes_off, h_off, hfrag_off, counters_off, partial_off, total;
+    size_t codes_off, h_off, hfrag_off, counters_off, partial_off, hpart_off, aflags_off, total;
     int Mpad;
     int n_counters;      // one arrival counter per tile when the K loop is split, else 0
+    ActPlan act;
 };
-inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_override = 0) {
+inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_override = 0, int act_override = 0) {
     Workspace w;
     w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
     const int G = K / kGroup;
@@ -251,7 +293,12 @@ inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_over
     const GemmPlan pl = plan_gemm(M > 0 ? M : 1, N, G, ksplit_override);
     w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
     w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
-    w.total = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * pl.bm * pl.bn * 4) : 0);
+    w.hpart_off = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * pl.bm * pl.bn * 4) : 0);
+    // the activation kernel's partial H [chunks][Mpad][rank] fp32 and one arrival word per workgroup
+    w.act = plan_act(M > 0 ? M : 1, G, rank, act_override);
+    const bool parked = w.act.chunks > 1 && rank > 0;
+    w.aflags_off = w.hpart_off + (parked ? align256((size_t)w.act.chunks * w.Mpad * rank * 4) : 0);
+    w.total = w.aflags_off + (parked ? align256((size_t)(w.Mpad / 16) * w.act.chunks * 8) : 0);
     return w;
 }
 

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsvdq.so")
 OPT_SKIP_LOWRANK = 1
 OPT_UNFUSED = 2
 OPT_KSPLIT_SHIFT = 8
+OPT_ACT_CHUNK_SHIFT = 12
 
 EXPORTS = [
     "svdq_status_string", "svdq_last_hip_error", "svdq_prepared_sizes", "svdq_prepare", "svdq_pack",

@@ -291,6 +291,31 @@ def test_forced_k_splits(torch, ksplit):
     S.svdq_forward_options(0)
 
 
+@pytest.mark.parametrize("gchunk,rank,M", [(8, 32, 300), (12, 32, 77), (4, 16, 300), (8, 128, 130), (1, 32, 33), (255, 32, 300)])
+def test_forced_activation_runs(torch, gchunk, rank, M):
+    """K cut into runs of a forced length per activation-kernel workgroup (option bits 12-19): runs of unequal length
+    (18 groups in runs of 8, 12, 4), one group per run, all of K in one run; every rank's accumulator layout; and the
+    arrival words left ready for the next call (three forwards on one workspace, each checked bit for bit against the
+    first).  The partial H of the runs meet in the workspace and are added in run order by whoever arrives last."""
+    case = I.case_by_name("tiny")
+    L = I.make_layer(case, M=M)
+    w = np.ascontiguousarray(L["w"][:, :656])
+    prep = S.svdq_prepare(w, L["x_absmax"], rank, bias=L["bias"][:656])
+    _say(f"forced activation runs of {gchunk} groups, rank {rank}, M {M}")
+    _run_and_compare(torch, L["x_bf16"], prep, what=f"act runs {gchunk}", flags=gchunk << S.OPT_ACT_CHUNK_SHIFT, window=False)
+    layer = S.DeviceLayer(prep)
+    x = S.bf16_tensor_from_bits(L["x_bf16"])
+    ws = layer.workspace(M)
+    outs = []
+    for _ in range(3):
+        y = layer.forward(x, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append((S.bits_from_bf16_tensor(y).copy(), layer.debug_act(ws, M)[2].copy()))
+    for yb, H in outs[1:]:
+        assert np.array_equal(yb, outs[0][0]) and np.array_equal(H.view(np.uint32), outs[0][1].view(np.uint32))
+    S.svdq_forward_options(0)
+
+
 def test_measurement_switches_match_the_oracle(torch):
     case = I.case_by_name("tiny")
     L = I.make_layer(case, M=160)

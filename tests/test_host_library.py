@@ -148,6 +148,10 @@ def test_pack_unpack_round_trip_and_byte_layout(lib):
             S.svdq_pack(rinv, l1s, l2, bad, sw, bias)
 
 
+def align256(n):
+    return (n + 255) // 256 * 256
+
+
 def test_shape_errors_and_workspace_size(lib):
     sz = S.Sizes()
     assert lib.svdq_prepared_sizes(C.byref(S.make_shape(100, 64, 16)), C.byref(sz)) == -2     # K % 64
@@ -165,11 +169,18 @@ def test_shape_errors_and_workspace_size(lib):
     # as bf16 hi/lo operand fragments, all with M padded to 256 (4608 is a multiple already)
     assert ws == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32
     # a one-token forward runs one row of 48 tiles of 128 x 256 with the K loop split four ways: one arrival counter
-    # per tile (padded to 256 bytes) and four fp32 partial tiles per tile come on top
-    assert S.svdq_workspace_bytes(1, sh) == 48 * 8 * 1792 + 2 * 4 * 256 * 32 + 256 + 4 * 48 * 128 * 256 * 4
+    # per tile (padded to 256 bytes) and four fp32 partial tiles per tile come on top; and its activation kernel cuts K
+    # into six runs of eight groups, whose partial H (fp32, 256 padded rows) and 8-byte arrival words are parked too
+    act_parked = 6 * 256 * 32 * 4 + align256(16 * 6 * 8)
+    assert S.svdq_workspace_bytes(1, sh) == 48 * 8 * 1792 + 2 * 4 * 256 * 32 + 256 + 4 * 48 * 128 * 256 * 4 + act_parked
     # the K split can be forced per thread through the option word (bits 8-11), which the size query follows
     lib.svdq_forward_options(2 << 8)
-    assert S.svdq_workspace_bytes(1, sh) == 48 * 8 * 1792 + 2 * 4 * 256 * 32 + 256 + 2 * 48 * 128 * 256 * 4
+    assert S.svdq_workspace_bytes(1, sh) == 48 * 8 * 1792 + 2 * 4 * 256 * 32 + 256 + 2 * 48 * 128 * 256 * 4 + act_parked
+    # so can the activation kernel's share of K per workgroup (bits 12-19; 255 = all of K: nothing is parked)
+    lib.svdq_forward_options(255 << 12)
+    assert S.svdq_workspace_bytes(1, sh) == 48 * 8 * 1792 + 2 * 4 * 256 * 32 + 256 + 4 * 48 * 128 * 256 * 4
+    lib.svdq_forward_options(12 << 12)
+    assert S.svdq_workspace_bytes(4608, sh) == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32 + 4 * 4608 * 32 * 4 + align256((4608 // 16) * 4 * 8)
     lib.svdq_forward_options(0)
     assert S.svdq_workspace_bytes(16, S.make_shape(100, 64, 16)) == 0
     # forward argument checks happen before any GPU call
@@ -188,11 +199,14 @@ def test_shape_errors_and_workspace_size(lib):
                                    C.c_size_t(1 << 62), None) == -2
     assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), big, C.c_void_p(0x1000), C.c_void_p(0x1000),
                                    C.c_size_t(1 << 20), None) == -4
-    # more input channels than the activation kernel can keep smoothing factors for (the limit depends on the rank)
-    for K, r in ((32768 + 64, 32), (32768, 128), (24576, 256)):
+    # more input channels than the kernels take; and, with the activation kernel told to walk all of K in one workgroup,
+    # more than it can keep smoothing factors for in LDS (that limit depends on the rank)
+    for K, r, opt in ((32768 + 64, 32, 0), (32768, 128, 255 << 12), (24576, 256, 255 << 12)):
         fake.shape = S.make_shape(K, 3072, r)
+        lib.svdq_forward_options(opt)
         assert lib.svdq_linear_forward(C.byref(fake), C.c_void_p(0x1000), 16, C.c_void_p(0x1000), C.c_void_p(0x1000),
                                        C.c_size_t(1 << 62), None) == -2, (K, r)
+    lib.svdq_forward_options(0)
 
 
 def test_fp16_and_bf16_roundings_of_the_library_match_numpy(lib):
