@@ -54,6 +54,7 @@ svdq::GemmW4Params gemm_params(const svdq_layer_dev *L, unsigned char *ws, const
     g.rank = rank;
     g.dbg = nullptr;
     g.ksplit = 1;
+    g.tail = 0;
     g.partial = reinterpret_cast<float *>(ws + w.partial_off);
     g.counters = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     return g;
@@ -142,6 +143,7 @@ int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *w
         }
         svdq::GemmW4Params g = gemm_params(L, ws, w, M, Y, lowrank ? s.rank : 0);
         g.ksplit = plan.ksplit;
+        g.tail = plan.tail;
         e = svdq::launch_gemm_w4a4(g, stream);
         if (e != hipSuccess) return hip_fail(e);
     } else {
@@ -158,6 +160,7 @@ int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *w
         }
         svdq::GemmW4Params g = gemm_params(L, ws, w, M, Y, 0);
         g.ksplit = plan.ksplit;
+        g.tail = plan.tail;
         e = svdq::launch_gemm_w4a4(g, stream);
         if (e != hipSuccess) return hip_fail(e);
         if (lowrank) {

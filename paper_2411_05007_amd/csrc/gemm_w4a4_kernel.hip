@@ -95,9 +95,15 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     const int tiles_m = (p.M + T::kBM - 1) / T::kBM;
     const int tiles_n = (p.N + T::kBN - 1) / T::kBN;
     const int total = tiles_m * tiles_n;
-    const int split = (int)blockIdx.x / total;
-    const int bid = (int)blockIdx.x - split * total;
-    const int g_per = (p.G + p.ksplit - 1) / p.ksplit;
+    // the first total - tail workgroups own a whole tile each; then come the split tiles, the workgroups of one tile
+    // side by side in the launch order
+    const int nfull = total - p.tail;
+    const bool split_tile = (int)blockIdx.x >= nfull;
+    const int tpos = split_tile ? ((int)blockIdx.x - nfull) / p.ksplit : 0;      // index among the split tiles
+    const int split = split_tile ? ((int)blockIdx.x - nfull) - tpos * p.ksplit : 0;
+    const int bid = split_tile ? nfull + tpos : (int)blockIdx.x;                // position in the launch order of tiles
+    const int nsplit = split_tile ? p.ksplit : 1;
+    const int g_per = (p.G + nsplit - 1) / nsplit;
     const int g_begin = split * g_per;
     const int g_end = g_begin + g_per < p.G ? g_begin + g_per : p.G;
     int tile_m, tile_n;
@@ -419,22 +425,29 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     if (MODE == 1) return;   // the window export writes no Y
 
     // ---- split K loop: park the partial tile, the last workgroup to arrive adds them all up ------------------------
-    // Partial tiles are stored in register order (consecutive threads consecutive addresses) with device-scope atomic
-    // accesses: the L2 caches of the chip's eight XCDs are not coherent with each other, and these accesses go past
-    // them; no cache is flushed.  A workgroup takes its ticket once all its stores have been acknowledged; the holder
-    // of the last ticket reads all partials back, its own included, and adds them in split order, so the sum does not
-    // depend on who came last.  Nobody waits for anybody.
-    if (p.ksplit > 1) {
-        const int tile_lin = tile_m * tiles_n + tile_n;
-        constexpr int kTileWords = T::kBM * T::kBN;
-        float *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
+    // Partial tiles are stored in register order (16 bytes per thread and store, consecutive threads consecutive
+    // addresses) with device-scope accesses: the L2 caches of the chip's eight XCDs are not coherent with each other,
+    // and these accesses go past them; no cache is flushed.  A workgroup takes its ticket once all its stores have been
+    // acknowledged; the holder of the last ticket reads all partials back, its own included, and adds them in split
+    // order, so the sum does not depend on who came last.  Nobody waits for anybody.
+    if (nsplit > 1) {
+        const int tile_lin = tpos;
+        constexpr int kTileBytes = T::kBM * T::kBN * 4;
+        constexpr int kDevice = 16;      // cache policy bit "sc1": coherent at device scope
+        // (the launcher checks that the partial tiles stay below 2^31 bytes)
+        const __amdgpu_buffer_rsrc_t rs_p = make_rsrc(p.partial, (size_t)p.tail * p.ksplit * kTileBytes);
+        const int mine = (tile_lin * p.ksplit + split) * kTileBytes;
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    __hip_atomic_store(mine + ((r * 2 + c) * 16 + v) * 256, acc[r][c][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int q = 0; q < 4; ++q) {
+                    buffer_u32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(acc[r][c][4 * q + e]);
+                    buffer_store_b128<kDevice>(v, rs_p, 16 * tid, mine + ((r * 2 + c) * 4 + q) * 4096);
+                }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // every store of this thread has been acknowledged
         __syncthreads();
         uint32_t *ticket = reinterpret_cast<uint32_t *>(lds);      // the ring is no longer in use
@@ -450,21 +463,23 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
             for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
-        const float *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
         for (int sidx = 0; sidx < p.ksplit; ++sidx) {
+            const int theirs = (tile_lin * p.ksplit + sidx) * kTileBytes;
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
-                float t[2][16];      // the 32 values of a row of blocks are requested together, then added: one round trip per batch
+                buffer_u32x4 t[2][4];      // the 32 values of a row of blocks are requested together, then added: one round trip per batch
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        t[c][v] = __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * 2 + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int q = 0; q < 4; ++q)
+                        t[c][q] = __builtin_amdgcn_raw_buffer_load_b128(rs_p, 16 * tid, theirs + ((r * 2 + c) * 4 + q) * 4096, kDevice);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[r][c][v] += t[c][v];
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[r][c][4 * q + e] += __uint_as_float(t[c][q][e]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -515,7 +530,10 @@ hipError_t launch_w4_tile(const GemmW4Params &p, hipStream_t stream) {
     const int tiles_m = (p.M + T::kBM - 1) / T::kBM, tiles_n = (p.N + T::kBN - 1) / T::kBN;
     // H, L2 and the bias are read with plain loads: every tile must lie inside the padded rows and columns
     if (tiles_m * T::kBM > p.Mpad || tiles_n * T::kBN > p.Npad) return hipErrorInvalidValue;
-    const dim3 grid(tiles_m * tiles_n * p.ksplit), block(256);
+    // the parked partial tiles are addressed with 32-bit byte offsets
+    if (p.tail < 0 || p.tail > tiles_m * tiles_n || (p.ksplit > 1) != (p.tail > 0)) return hipErrorInvalidValue;
+    if (p.ksplit > 1 && (size_t)p.tail * p.ksplit * T::kBM * T::kBN * 4 >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    const dim3 grid(tiles_m * tiles_n - p.tail + p.tail * p.ksplit), block(256);
     if (p.dbg) {
         auto k = gemm_w4a4_kernel<RB, 1>;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);

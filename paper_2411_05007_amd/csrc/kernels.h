@@ -39,9 +39,10 @@ struct GemmW4Params {
     int M, N, K, G, Mpad, Npad, rank;   // rank == 0: no low-rank branch
     int32_t *dbg;            // debug window of exact group sums, or null
     int m0, m1, n0, n1;
-    int ksplit;              // workgroups per tile along K (1 = no split)
-    float *partial;          // ksplit > 1: fp32 [tile][split][BM * 256] partial tiles, register order
-    uint32_t *counters;      // ksplit > 1: one arrival counter per tile, zero when the kernel starts
+    int ksplit;              // workgroups per split tile along K (1 = no tile is split)
+    int tail;                // the last `tail` tiles of the launch order are split (layout.h, GemmPlan); 0 with ksplit == 1
+    float *partial;          // ksplit > 1: fp32 [split tile][split][BM * 256] partial tiles, register order
+    uint32_t *counters;      // ksplit > 1: one arrival counter per split tile, zero when the kernel starts
 };
 hipError_t launch_gemm_w4a4(const GemmW4Params &p, hipStream_t stream);
 

@@ -196,30 +196,45 @@ inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank, int kspl
     return w;
 }
 
-// How the W4A4 GEMM of an M x N x (64 G) layer is launched.  Tiles are 128 x 256, two workgroups per CU.  A launch
-// with at most one workgroup per CU splits a long K loop over up to four workgroups per tile (at least twelve groups
-// each): every workgroup writes its fp32 partial tile to the workspace, and the one that finishes last adds them up
-// (in split order, so the result does not depend on who is last) and stores Y.
+// How the W4A4 GEMM of an M x N x (64 G) layer is launched.  Tiles are 128 x 256, two workgroups per CU (512 places).
+// A launch with at most one workgroup per CU has the K loop of every tile split over up to four workgroups (at least
+// twelve groups each): every one of them writes its fp32 partial tile to the workspace, and the one that finishes last
+// adds them up (in split order, so the result does not depend on who is last) and stores Y.
+// The kernel can also split only the last `tail` tiles of the launch order (the partly filled last round of a large
+// launch); measured on the FLUX.1 shapes that gains nothing, because parked tiles travel with device-scope accesses,
+// past the L2, at a fraction of the ordinary bandwidth: 1728 tiles with the last 192 split two ways ran 192.9 us
+// against 192.2 us unsplit, and every forced split of a large launch was slower.  So large launches are not split.
 struct GemmPlan {
     int bm, bn;
-    int tiles;       // workgroups per split
-    int ksplit;      // >= 1
+    int tiles;       // output tiles
+    int tail;        // how many of them (the last in launch order) are split
+    int ksplit;      // workgroups per split tile, >= 1; workgroups in all = tiles - tail + tail * ksplit
 };
 constexpr int kMaxKSplit = 8;
+constexpr int kGemmPlaces = 512;
 inline GemmPlan plan_gemm(int M, int N, int G, int ksplit_override = 0) {
     GemmPlan pl;
     pl.bm = 128; pl.bn = 256;
     pl.tiles = ((M + 127) / 128) * ((N + 255) / 256);
     int s = 1;
-    if (pl.tiles <= 256) {
-        s = 512 / pl.tiles;
+    pl.tail = pl.tiles;
+    if (pl.tiles <= kGemmPlaces / 2) {
+        s = kGemmPlaces / pl.tiles;
         if (s > 4) s = 4;
-        while (s > 1 && G / s < 12) --s;            // at least twelve groups per split
     }
-    if (ksplit_override > 0) s = ksplit_override < kMaxKSplit ? ksplit_override : kMaxKSplit;
+    while (s > 1 && G / s < 12) --s;                // at least twelve groups per split
+    if (ksplit_override > 0) {
+        // forced: all tiles of a small launch, the tiles of the last round of a larger one
+        s = ksplit_override < kMaxKSplit ? ksplit_override : kMaxKSplit;
+        if (pl.tiles > kGemmPlaces / 2) pl.tail = pl.tiles % kGemmPlaces;
+    }
     if (s > G) s = G > 0 ? G : 1;
     const int per = (G + s - 1) / s;
     pl.ksplit = (G + per - 1) / per;                // no empty split
+    if (pl.ksplit <= 1 || pl.tail == 0) {
+        pl.ksplit = 1;
+        pl.tail = 0;
+    }
     return pl;
 }
 
@@ -279,7 +294,7 @@ constexpr unsigned long long kActArrived = 0x5356445141525256ull;
 struct Workspace {
     size_t codes_off, h_off, hfrag_off, counters_off, partial_off, hpart_off, aflags_off, total;
     int Mpad;
-    int n_counters;      // one arrival counter per tile when the K loop is split, else 0
+    int n_counters;      // one arrival counter per tile whose K loop is split
     ActPlan act;
 };
 inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_override = 0, int act_override = 0) {
@@ -291,9 +306,9 @@ inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_over
     w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
     w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
     const GemmPlan pl = plan_gemm(M > 0 ? M : 1, N, G, ksplit_override);
-    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
+    w.n_counters = pl.tail;                                               // one arrival counter per split tile
     w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
-    w.hpart_off = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * pl.bm * pl.bn * 4) : 0);
+    w.hpart_off = w.partial_off + align256((size_t)pl.ksplit * pl.tail * pl.bm * pl.bn * 4);
     // the activation kernel's partial H [chunks][Mpad][rank] fp32 and one arrival word per workgroup
     w.act = plan_act(M > 0 ? M : 1, G, rank, act_override);
     const bool parked = w.act.chunks > 1 && rank > 0;

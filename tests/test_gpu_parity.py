@@ -472,3 +472,18 @@ def test_block_sweep_cases_on_sampled_rows(torch, name):
     prep = S.svdq_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
     rows = I.sample_rows(case.M, 32)
     _run_and_compare(torch, L["x_bf16"], prep, rows=rows, what=name)
+
+
+def test_forced_split_of_the_last_round_of_a_large_launch(torch):
+    """A K split forced on a launch with more tiles than the chip has places applies to the tiles of its last, partly
+    filled round only (36 x 16 = 576 tiles on 512 places: the last 64 of the launch order), which sit scattered over the
+    output; all other tiles keep their single workgroup.  Sampled rows against the oracle, every column."""
+    case = I.case_by_name("flux_block_out_M4608_r32")
+    L = I.make_layer(case)
+    w = np.ascontiguousarray(np.concatenate([L["w"], L["w"][:, :1024]], axis=1))        # N = 4096: 16 tile columns
+    bias = np.concatenate([L["bias"], L["bias"][:1024]])
+    prep = S.svdq_prepare(w, L["x_absmax"], case.rank, bias=bias)
+    rows = I.sample_rows(case.M, 48)
+    _say("forced K split 3 on 576 tiles: the last 64 are split")
+    _run_and_compare(torch, L["x_bf16"], prep, rows=rows, what="tail split", ksplit=3)
+    S.svdq_forward_options(0)

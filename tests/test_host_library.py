@@ -168,6 +168,11 @@ def test_shape_errors_and_workspace_size(lib):
     # activation blocks (1792 bytes per group and 32 tokens: 6-bit codes and fp16 scales) + H 4*M*r as fp32 and again
     # as bf16 hi/lo operand fragments, all with M padded to 256 (4608 is a multiple already)
     assert ws == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32
+    # a forced K split of a large launch applies to the tiles of its last, partly filled round of workgroups (1728 tiles
+    # on 512 places: 192 tiles): an arrival counter and the fp32 partial tiles for each of those
+    lib.svdq_forward_options(2 << 8)
+    assert S.svdq_workspace_bytes(4608, sh) == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32 + 192 * 4 + 2 * 192 * 128 * 256 * 4
+    lib.svdq_forward_options(0)
     # a one-token forward runs one row of 48 tiles of 128 x 256 with the K loop split four ways: one arrival counter
     # per tile (padded to 256 bytes) and four fp32 partial tiles per tile come on top; and its activation kernel cuts K
     # into six runs of eight groups, whose partial H (fp32, 256 padded rows) and 8-byte arrival words are parked too
