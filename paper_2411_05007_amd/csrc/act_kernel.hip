@@ -431,21 +431,21 @@ hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     size_t lds = (q ? L::rinv_bytes(nchunks > 1 ? p.gchunk : p.G) : 0) + (pr ? L::wave_bytes() : 0);
     if (lds < 16) lds = 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    hipError_t e = hipSuccess;
+    // the limit on dynamic LDS is raised once per instantiation, to all a CU has (the size of a launch varies with K and the rank)
     if (q && pr) {
         auto k = act_kernel<RBMAX, WAVES, true, true, STAGE, FMT>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesPerCU);
+        if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
     } else if (q) {
         auto k = act_kernel<1, WAVES, true, false, false, FMT>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesPerCU);
+        if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
     } else if (pr) {
         auto k = act_kernel<RBMAX, WAVES, false, true, STAGE, 0>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesPerCU);
+        if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(k, grid, block, lds, stream, p);
     }
     return hipGetLastError();

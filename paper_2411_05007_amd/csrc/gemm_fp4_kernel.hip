@@ -359,8 +359,9 @@ hipError_t launch_fp4_tile(const GemmFp4Params &p, hipStream_t stream) {
     if (tiles_m * T::kBM > p.Mpad || tiles_n * T::kBN > p.Npad) return hipErrorInvalidValue;
     const dim3 grid(tiles_m * tiles_n * p.ksplit), block(256);
     auto k = gemm_fp4_kernel<RB, CB>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
-    if (e != hipSuccess) return e;
+    // the limit on dynamic LDS is raised once per instantiation, not per launch
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
     return hipGetLastError();
 }

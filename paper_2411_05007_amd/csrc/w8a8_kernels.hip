@@ -408,8 +408,9 @@ static hipError_t launch_w8_tile(const GemmW8Params &p, hipStream_t stream) {
     // H, L2, the scales and the bias are read with plain loads: every tile must lie inside the padded rows and columns
     if (tiles_m * T::kBM > p.Mpad || tiles_n * T::kBN > p.Npad) return hipErrorInvalidValue;
     auto k = gemm_w8a8_kernel<RB, CB>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
-    if (e != hipSuccess) return e;
+    // the limit on dynamic LDS is raised once per instantiation, not per launch
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(k, dim3(tiles_m * tiles_n), dim3(256), T::kLdsBytes, stream, p);
     return hipGetLastError();
 }
