@@ -62,7 +62,11 @@ constexpr int act_min_workgroups(int rbmax, int waves, bool stage) {
     return rbmax <= 4 ? 4 : rbmax <= 8 ? 3 : 2;
 }
 
-// FMT 0: INT4 codes with fp16 group scales; FMT 1: MXFP4 (E2M1 codes, one power-of-two scale byte per block of 32)
+// FMT 0: INT4 codes with fp16 group scales; FMT 1: MXFP4 (E2M1 codes, one power-of-two scale byte per block of 32);
+// FMT 2: INT8 codes with one fp16 scale per token (the 8-bit setting of App. "Implementation Details": per-token dynamic
+// activation quantization).  A token's scale needs its maximum over all of K before the first code can be written, so
+// that format walks its groups twice: once for the maxima (exchanged between the wavefronts through LDS), then the
+// ordinary loop, whose loads find the slice in the L2.  It does not take a cut K (chunks <= 1).
 template <int RBMAX, int WAVES, bool QUANT, bool PROJ, bool STAGE, int FMT>
 __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)) void act_kernel(ActParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char act_lds[];
@@ -97,8 +101,8 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     // rows past M read the last row; what they produce lands in padding rows and is never used
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.X, (size_t)p.M * p.K * 2);
     const __amdgpu_buffer_rsrc_t rs_l = make_rsrc(p.l1s, (size_t)p.K * p.rank * 2);
-    const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, FMT ? (size_t)p.G * p.Mpad * kFp4RowBytes : w4_a_bytes(p.G, p.Mpad));
-    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sx, FMT ? fp4_scale_bytes(p.G, p.Mpad) : (size_t)p.G * p.Mpad * 2);
+    const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(p.codes, FMT == 2 ? (size_t)p.K * p.Mpad : FMT == 1 ? (size_t)p.G * p.Mpad * kFp4RowBytes : w4_a_bytes(p.G, p.Mpad));
+    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(p.sx, FMT == 2 ? (size_t)p.Mpad * 2 : FMT == 1 ? fp4_scale_bytes(p.G, p.Mpad) : (size_t)p.G * p.Mpad * 2);
     // (byte offsets below 2^32: the entry point refuses batches of 2^31 elements or more; unsigned on purpose)
     const int vxa = (int)(((uint32_t)(ma < p.M ? ma : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
     const int vxb = (int)(((uint32_t)(mb < p.M ? mb : p.M - 1) * (uint32_t)p.K + 8u * (uint32_t)c8) * 2u);
@@ -106,9 +110,13 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     // INT4: the lane's 8 channels are half of one 16-channel triple (three registers of the GEMM's 6-bit operand form,
     // layout.h) of operand lane 32 (c8 / 4) + m % 32; the even lane of a pair stores the triple's first two dwords,
     // the odd lane the third, and lane c8 = 1 also the token's scale dword (w4_int4_offsets below)
-    const int vca = FMT ? (int)fp4_code_offset(0, p.Mpad, ma, c8 >> 2) + 4 * (c8 & 3) : w4_triple_offset(ma, c8);
-    const int vcb = FMT ? (int)fp4_code_offset(0, p.Mpad, mb, c8 >> 2) + 4 * (c8 & 3) : w4_triple_offset(mb, c8);
-    const int vsx = FMT ? (int)fp4_scale_offset(0, p.Mpad, (c8 & 1) ? mb : ma, c8 >> 2) : 0;
+    // INT8: the lane's 8 channels are half of a 16-byte operand chunk of v_mfma_i32_32x32x32_i8: 32-channel step c8 / 4 of
+    // the group, lane half (c8 % 4) / 2, bytes 8 (c8 % 2) .. + 7 (layout.h, i8_code_offset)
+    const int vca = FMT == 2 ? (int)i8_code_offset(8 * c8, p.Mpad, ma)
+                  : FMT == 1 ? (int)fp4_code_offset(0, p.Mpad, ma, c8 >> 2) + 4 * (c8 & 3) : w4_triple_offset(ma, c8);
+    const int vcb = FMT == 2 ? (int)i8_code_offset(8 * c8, p.Mpad, mb)
+                  : FMT == 1 ? (int)fp4_code_offset(0, p.Mpad, mb, c8 >> 2) + 4 * (c8 & 3) : w4_triple_offset(mb, c8);
+    const int vsx = FMT == 1 ? (int)fp4_scale_offset(0, p.Mpad, (c8 & 1) ? mb : ma, c8 >> 2) : 0;
     // second INT4 store of a lane: the triple's second dword (even lanes), the token's scale (lane c8 = 1), or the
     // third dword once more (the other odd lanes: same value to the same address)
     const int vca2 = (c8 & 1) ? (c8 == 1 ? w4_scale_offset(ma) : vca) : vca + 4;
@@ -176,6 +184,68 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
         if (kr1 < kend) *reinterpret_cast<float4 *>(lrinv + (kr1 - kbeg)) = rv1;
         for (int k = kr1 + 256; k < kend; k += 256)      // runs longer than eight groups: the rest, one load at a time
             *reinterpret_cast<float4 *>(lrinv + (k - kbeg)) = *reinterpret_cast<const float4 *>(p.rinv + k);
+    }
+
+    // INT8: the tokens' maxima over all of K first.  Every wavefront walks its run once with the loop's own load
+    // pattern (two groups in flight), the 8 lanes of a token combine by DPP, the wavefronts through their LDS blocks;
+    // Eq. 1 with q_max = 127: s = fp16(max / 127) (IEEE division, round to nearest even, saturating), codes from
+    // x * (1.0f / s).
+    float rcp8_a = 0.f, rcp8_b = 0.f;
+    if (QUANT && FMT == 2) {
+        float amax_a = 0.f, amax_b = 0.f;
+        auto fold = [&](int g, const XStage &sx) {
+            const float4 *rp = reinterpret_cast<const float4 *>(lrinv + 64 * (g - gbeg) + 8 * c8);
+            const float4 r0 = rp[0], r1 = rp[1];
+            const float r[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+            const uint32_t wa[4] = {sx.x0.x, sx.x0.y, sx.x0.z, sx.x0.w};
+            const uint32_t wb[4] = {sx.x1.x, sx.x1.y, sx.x1.z, sx.x1.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                amax_a = fmaxf(amax_a, fmaxf(fabsf(bf16lo(wa[i]) * r[2 * i]), fabsf(bf16hi(wa[i]) * r[2 * i + 1])));
+                amax_b = fmaxf(amax_b, fmaxf(fabsf(bf16lo(wb[i]) * r[2 * i]), fabsf(bf16hi(wb[i]) * r[2 * i + 1])));
+            }
+        };
+        if (npairs > 0) {
+            XStage p0 = fetch_x(g0), p1 = fetch_x(clampg(g0 + 1));
+            for (int ip = 0; ip < npairs; ++ip) {
+                const int g = g0 + 2 * ip;
+                fold(g, p0);
+                p0 = fetch_x(clampg(g + 2));
+                fold(clampg(g + 1), p1);      // a repeated last group changes no maximum
+                p1 = fetch_x(clampg(g + 3));
+            }
+        }
+        amax_a = max_over_8_lanes(amax_a);
+        amax_b = max_over_8_lanes(amax_b);
+        float *mx = reinterpret_cast<float *>(wlds);      // [16] maxima of this wavefront's run, at the head of its block
+        if (c8 == 0) {
+            mx[r8] = amax_a;
+            mx[r8 + 8] = amax_b;
+        }
+        __syncthreads();
+        const unsigned char *blocks = act_lds + L::rinv_bytes(glds);
+        amax_a = amax_b = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            const float *o = reinterpret_cast<const float *>(blocks + (size_t)w * L::kWaveBytes);
+            amax_a = fmaxf(amax_a, o[r8]);
+            amax_b = fmaxf(amax_b, o[r8 + 8]);
+        }
+        __syncthreads();      // the blocks go back to their owners
+        auto scale_of = [](float amax, _Float16 &sh) {
+            float s32 = amax / 127.0f;
+            s32 = fminf(s32, 65504.0f);
+            sh = (_Float16)s32;
+            const float sc = (float)sh;
+            return sc > 0.f ? 1.0f / sc : 0.f;
+        };
+        _Float16 sha, shb;
+        rcp8_a = scale_of(amax_a, sha);
+        rcp8_b = scale_of(amax_b, shb);
+        if (wave == 0 && c8 == 0) {      // rows past M: padding entries of the scale vector (it has Mpad of them)
+            p.sx[ma] = __builtin_bit_cast(uint16_t, sha);
+            p.sx[mb] = __builtin_bit_cast(uint16_t, shb);
+        }
     }
 
     // X of one group, load map -> LDS -> operand map: lane (row, blk) picks up channels 16*blk .. +15 of token row
@@ -275,6 +345,22 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             __builtin_amdgcn_raw_buffer_store_b32(wa, rs_c, vca, sc, 0);
             __builtin_amdgcn_raw_buffer_store_b32(wb, rs_c, vcb, sc, 0);
             __builtin_amdgcn_raw_buffer_store_b8((uint8_t)((c8 & 1) ? bb : ba), rs_s, vsx, (g >> 2) * p.Mpad * 8 + (g & 3), 0);
+        }
+        if (QUANT && FMT == 2) {
+            uint32_t wa[2] = {0u, 0u}, wb[2] = {0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float qa = fminf(127.f, fmaxf(-127.f, __builtin_rintf(sm.a[QUANT ? e : 0] * rcp8_a)));
+                const float qb = fminf(127.f, fmaxf(-127.f, __builtin_rintf(sm.b[QUANT ? e : 0] * rcp8_b)));
+                wa[e >> 2] |= ((uint32_t)(int)qa & 0xffu) << (8 * (e & 3));
+                wb[e >> 2] |= ((uint32_t)(int)qb & 0xffu) << (8 * (e & 3));
+            }
+            // a group is two 32-channel steps of operand blocks: Mpad * 64 bytes
+            const int sc = g * p.Mpad * 64;
+            __builtin_amdgcn_raw_buffer_store_b32(wa[0], rs_c, vca, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(wa[1], rs_c, vca + 4, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(wb[0], rs_c, vcb, sc, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(wb[1], rs_c, vcb + 4, sc, 0);
         }
         if (QUANT && FMT == 0) {
             uint32_t alo, ahi, blo, bhi, sa, sb;
@@ -428,7 +514,8 @@ hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
         return hipErrorInvalidValue;
     const dim3 grid((unsigned)((p.M + 15) / 16) * nchunks), block(WAVES * 64);
     const bool q = flags & 1, pr = (flags & 2) && p.rank > 0;
-    size_t lds = (q ? L::rinv_bytes(nchunks > 1 ? p.gchunk : p.G) : 0) + (pr ? L::wave_bytes() : 0);
+    // (the per-token format exchanges its maxima through the wavefronts' blocks even without a projection)
+    size_t lds = (q ? L::rinv_bytes(nchunks > 1 ? p.gchunk : p.G) : 0) + ((pr || FMT == 2) ? L::wave_bytes() : 0);
     if (lds < 16) lds = 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     // the limit on dynamic LDS is raised once per instantiation, to all a CU has (the size of a launch varies with K and the rank)
@@ -511,6 +598,11 @@ hipError_t launch_act_fmt(const ActParams &p, int flags, hipStream_t stream) {
 
 hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
+    if (p.fmt == 2) {
+        // per-token scales need all of K in one workgroup, and the offsets of the int8 codes fit 32 bits
+        if (p.chunks > 1 || (size_t)p.K * p.Mpad >= ((size_t)1 << 31) || ((flags & 1) && !p.sx)) return hipErrorInvalidValue;
+        return launch_act_fmt<2>(p, flags, stream);
+    }
     return p.fmt == 1 ? launch_act_fmt<1>(p, flags, stream) : launch_act_fmt<0>(p, flags, stream);
 }
 

@@ -427,26 +427,19 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     const bool lowrank = s.rank > 0 && !(g_options & SVDQ_OPT_SKIP_LOWRANK);
 
-    svdq::Quant8Params q{};
-    q.X = static_cast<const uint16_t *>(X);
-    q.rinv = static_cast<const float *>(L->rinv);
-    q.codes = ws + w.codes_off;
-    q.sx = reinterpret_cast<uint16_t *>(ws + w.sx_off);
-    q.M = M; q.K = s.K; q.Mpad = w.Mpad;
-    hipError_t e = svdq::launch_quant8(q, stream);
+    // one kernel: per-token maxima, then smoothing + INT8 codes + the down projection H = X L1s in one walk over X
+    svdq::ActParams a{};
+    a.X = static_cast<const uint16_t *>(X);
+    a.rinv = static_cast<const float *>(L->rinv);
+    a.l1s = static_cast<const uint16_t *>(L->l1s);
+    a.codes = ws + w.codes_off;
+    a.sx = reinterpret_cast<uint16_t *>(ws + w.sx_off);
+    a.H = reinterpret_cast<float *>(ws + w.h_off);
+    a.hfrag = ws + w.hfrag_off;
+    a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
+    a.fmt = 2;
+    hipError_t e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
     if (e != hipSuccess) return hip_fail(e);
-    if (lowrank) {
-        // the down projection H = X L1s: the 4-bit path's activation kernel in its projection-only mode
-        svdq::ActParams a{};
-        a.X = q.X;
-        a.rinv = q.rinv;
-        a.l1s = static_cast<const uint16_t *>(L->l1s);
-        a.H = reinterpret_cast<float *>(ws + w.h_off);
-        a.hfrag = ws + w.hfrag_off;
-        a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
-        e = svdq::launch_act(a, 2, stream);
-        if (e != hipSuccess) return hip_fail(e);
-    }
     if (void *ev = g_profile_event) {
         e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
         if (e != hipSuccess) return hip_fail(e);

@@ -10,14 +10,15 @@ struct ActParams {
     const float *rinv;       // fp32 [K]
     const uint16_t *l1s;     // bf16, fragment order
     uint8_t *codes;          // INT4: activation blocks [G][Mpad / 32][1792] (6-bit codes + fp16 scales, layout.h)
-    uint16_t *sx;            // MXFP4 only: the scale bytes
+    uint16_t *sx;            // MXFP4: the scale bytes; INT8: fp16 [Mpad], one scale per token
     float *H;                // fp32 [Mpad][rank]
     uint8_t *hfrag;          // H as bf16 hi + lo parts in MFMA operand order (layout.h), Mpad * rank * 4 bytes
     int M, K, G, Mpad, rank;
     uint32_t *zero_words;    // cleared by the first workgroup: the arrival counters of the GEMM that follows
     int n_zero;
     int fmt;                 // 0: INT4.  1: MXFP4 - codes = packed E2M1 in the GEMM's operand order,
-                             // sx = scale bytes (layout.h, fp4_code_offset / fp4_scale_offset)
+                             // sx = scale bytes (layout.h, fp4_code_offset / fp4_scale_offset).
+                             // 2: INT8 per token - codes in the int8 MFMA's operand order (layout.h, i8_code_offset)
     // K cut into runs (layout.h, ActPlan); chunks = 0: one workgroup per 16 tokens walks all of K, wavefronts chosen by the launcher
     int chunks, gchunk, waves;
     float *hpart;                    // fp32 [chunks][Mpad][rank]: partial H of every run (chunks > 1)
@@ -111,15 +112,6 @@ constexpr int kW4A16ProjRows = 16;     // up to this many rows the W4A16 forward
 hipError_t launch_w4a16_proj(const uint16_t *X, const uint16_t *l1s, float *H, int M, int K, int rank, hipStream_t stream);
 
 // ---- 8-bit setting -------------------------------------------------------------------------------------------
-struct Quant8Params {
-    const uint16_t *X;       // bf16 [M][K]
-    const float *rinv;       // fp32 [K]
-    uint8_t *codes;          // int8, operand order (layout.h, i8_code_offset), K * Mpad bytes
-    uint16_t *sx;            // fp16 [Mpad]
-    int M, K, Mpad;
-};
-hipError_t launch_quant8(const Quant8Params &p, hipStream_t stream);
-
 struct GemmW8Params {
     const uint8_t *xcodes;   // int8 [K / 32][Mpad / 32][64][16]
     const uint16_t *sx;      // fp16 [Mpad]

@@ -3,9 +3,8 @@
 //
 //   Y = s_x[m] s_w[n] (sum_k q_x[m,k] q_w[k,n])  +  H L2  +  bias                                   (Eq. 2, Eq. 5)
 //
-// quant8_kernel: smoothing and INT8 quantization with one fp16 scale per token (Eq. 1, q_max = 127), codes
-// written in the operand order of v_mfma_i32_32x32x32_i8.  The down projection H = X L1s is the 4-bit path's
-// activation kernel in its projection-only mode.
+// Smoothing, INT8 quantization with one fp16 scale per token (Eq. 1, q_max = 127; codes written in the operand order of
+// v_mfma_i32_32x32x32_i8) and the down projection H = X L1s are the activation kernel's third format (act_kernel.hip).
 // gemm_w8a8_kernel: the pipeline of the MXFP4 GEMM (128 x 256 workgroup tile, operands through a four-stage LDS ring
 // filled by direct-to-LDS loads, one barrier per step) with int8 MFMAs; a step is 32 channels, so the ring has the
 // same geometry (32 bytes per row and step).  The int32 sums are exact and are scaled once, after the K loop:
@@ -52,98 +51,6 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
     v[0] = (__bf16)lo;
     v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
-}
-__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// maximum over the 8 lanes l % 8 = 0..7 that share a token in the load map
-__device__ __forceinline__ float max_over_8_lanes(float a) {
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xB1, 0xf, 0xf, true)));    // quad_perm [1,0,3,2]
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4E, 0xf, 0xf, true)));    // quad_perm [2,3,0,1]
-    a = fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x141, 0xf, 0xf, true)));   // row_half_mirror
-    return a;
-}
-
-// Per-token INT8 quantization.  A workgroup of four wavefronts owns 16 tokens; wavefront w takes the 64-channel
-// groups w, w + 4, ...  Lane map of the 4-bit activation kernel: lane l -> tokens l / 8 and l / 8 + 8, channels
-// 8 (l % 8) .. + 7 of the group, so every load and store instruction covers whole lines.  Pass 1 finds the tokens'
-// maxima (8 lanes by DPP, 4 wavefronts through LDS); pass 2 reads X again (cache resident) and writes the codes.
-__global__ __launch_bounds__(256) void quant8_kernel(Quant8Params p) {
-    __shared__ float red[4][16];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r8 = lane >> 3, c8 = lane & 7;
-    const int m0 = blockIdx.x * 16;
-    const int ma = m0 + r8, mb = ma + 8;                               // < Mpad
-    const size_t xa = (size_t)(ma < p.M ? ma : p.M - 1) * p.K + 8 * c8;   // rows past M read the last row; their codes land in padding rows
-    const size_t xb = (size_t)(mb < p.M ? mb : p.M - 1) * p.K + 8 * c8;
-    const int G = p.K / 64;
-    auto smoothed = [&](int g, float (&a)[8], float (&b)[8]) {
-        const uint4 va = *reinterpret_cast<const uint4 *>(p.X + xa + (size_t)g * 64);
-        const uint4 vb = *reinterpret_cast<const uint4 *>(p.X + xb + (size_t)g * 64);
-        const float4 r0 = *reinterpret_cast<const float4 *>(p.rinv + g * 64 + 8 * c8);
-        const float4 r1 = *reinterpret_cast<const float4 *>(p.rinv + g * 64 + 8 * c8 + 4);
-        const float r[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
-        const uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a[2 * i] = bf16lo(wa[i]) * r[2 * i];
-            a[2 * i + 1] = bf16hi(wa[i]) * r[2 * i + 1];
-            b[2 * i] = bf16lo(wb[i]) * r[2 * i];
-            b[2 * i + 1] = bf16hi(wb[i]) * r[2 * i + 1];
-        }
-    };
-    float amax_a = 0.f, amax_b = 0.f;
-    for (int g = wave; g < G; g += 4) {
-        float a[8], b[8];
-        smoothed(g, a, b);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            amax_a = fmaxf(amax_a, fabsf(a[e]));
-            amax_b = fmaxf(amax_b, fabsf(b[e]));
-        }
-    }
-    amax_a = max_over_8_lanes(amax_a);
-    amax_b = max_over_8_lanes(amax_b);
-    if (c8 == 0) {
-        red[wave][r8] = amax_a;
-        red[wave][r8 + 8] = amax_b;
-    }
-    __syncthreads();
-    amax_a = fmaxf(fmaxf(red[0][r8], red[1][r8]), fmaxf(red[2][r8], red[3][r8]));
-    amax_b = fmaxf(fmaxf(red[0][r8 + 8], red[1][r8 + 8]), fmaxf(red[2][r8 + 8], red[3][r8 + 8]));
-    // Eq. 1: s = fp16(max / 127) (IEEE division, round to nearest even, saturating), codes from x * (1.0f / s)
-    auto scale_of = [](float amax, _Float16 &sh) {
-        float s32 = amax / 127.0f;
-        s32 = fminf(s32, 65504.0f);
-        sh = (_Float16)s32;
-        const float sc = (float)sh;
-        return sc > 0.f ? 1.0f / sc : 0.f;
-    };
-    _Float16 sha, shb;
-    const float rcp_a = scale_of(amax_a, sha), rcp_b = scale_of(amax_b, shb);
-    if (wave == 0 && c8 == 0) {
-        p.sx[ma] = __builtin_bit_cast(uint16_t, sha);
-        p.sx[mb] = __builtin_bit_cast(uint16_t, shb);
-    }
-    // the 8 channels of a lane are half of a 16-byte operand chunk: step 2 g + c8 / 4, lane half (c8 % 4) / 2, bytes 8 (c8 % 2) ..
-    const int step_in = c8 >> 2, half = (c8 & 3) >> 1, byte0 = 8 * (c8 & 1);
-    for (int g = wave; g < G; g += 4) {
-        float a[8], b[8];
-        smoothed(g, a, b);
-        uint32_t wa[2] = {0u, 0u}, wb[2] = {0u, 0u};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float qa = fminf(127.f, fmaxf(-127.f, __builtin_rintf(a[e] * rcp_a)));
-            const float qb = fminf(127.f, fmaxf(-127.f, __builtin_rintf(b[e] * rcp_b)));
-            wa[e >> 2] |= ((uint32_t)(int)qa & 0xffu) << (8 * (e & 3));
-            wb[e >> 2] |= ((uint32_t)(int)qb & 0xffu) << (8 * (e & 3));
-        }
-        const int gs = 2 * g + step_in;
-        const size_t oa = ((((size_t)gs * (p.Mpad / 32) + ma / 32) * 64 + half * 32 + ma % 32) * 16) + byte0;
-        const size_t ob = ((((size_t)gs * (p.Mpad / 32) + mb / 32) * 64 + half * 32 + mb % 32) * 16) + byte0;
-        *reinterpret_cast<uint2 *>(p.codes + oa) = make_uint2(wa[0], wa[1]);
-        *reinterpret_cast<uint2 *>(p.codes + ob) = make_uint2(wb[0], wb[1]);
-    }
 }
 
 // canonical views of the workspace for parity checks
@@ -386,13 +293,6 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
 }
 
 }  // namespace
-
-hipError_t launch_quant8(const Quant8Params &p, hipStream_t stream) {
-    if (p.M <= 0) return hipSuccess;
-    if (p.K % 64 || p.Mpad % kRowPad || p.Mpad < p.M) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(quant8_kernel, dim3((p.M + 15) / 16), dim3(256), 0, stream, p);
-    return hipGetLastError();
-}
 
 hipError_t launch_debug_act_w8(const DebugActW8Params &p, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
