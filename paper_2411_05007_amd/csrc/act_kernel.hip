@@ -42,7 +42,12 @@ template <int RBMAX, int WAVES>
 struct ActLds {
     static constexpr int kRedRow = RBMAX * 16 + 1;
     static constexpr int kXRow = 144;      // 128 B of one token's group + 16: the 16 rows of an operand read fall on distinct banks
-    static constexpr int kWaveBytes = (16 * kXRow > 16 * kRedRow * 4) ? 16 * kXRow : 16 * kRedRow * 4;
+    // behind that block: the INT4 codes and scales of the wavefront's 16 tokens of one group in the byte order of the
+    // activation block (two runs of 384 bytes, one per half of the group, and 64 bytes of scales), from where they leave
+    // with one 16-byte store per lane
+    static constexpr int kOutBytes = kActOutStage;
+    static constexpr int kMainBytes = (16 * kXRow > 16 * kRedRow * 4) ? 16 * kXRow : 16 * kRedRow * 4;
+    static constexpr int kWaveBytes = kMainBytes + kOutBytes;
     static __host__ __device__ size_t rinv_bytes(int groups) { return (size_t)groups * 64 * 4; }
     static __host__ __device__ size_t wave_bytes() { return (size_t)WAVES * kWaveBytes; }
 };
@@ -119,8 +124,15 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     const int vsx = FMT == 1 ? (int)fp4_scale_offset(0, p.Mpad, (c8 & 1) ? mb : ma, c8 >> 2) : 0;
     // second INT4 store of a lane: the triple's second dword (even lanes), the token's scale (lane c8 = 1), or the
     // third dword once more (the other odd lanes: same value to the same address)
-    const int vca2 = (c8 & 1) ? (c8 == 1 ? w4_scale_offset(ma) : vca) : vca + 4;
-    const int vcb2 = (c8 & 1) ? (c8 == 1 ? w4_scale_offset(mb) : vcb) : vcb + 4;
+    // (INT4: these are offsets into the wavefront's staging block, tokens r8 and r8 + 8 of its 16; the second word of
+    // a lane is the triple's second dword (even lanes), the token's scale (lane c8 = 1), or the third dword once more)
+    const int lca = 384 * (c8 >> 2) + 24 * r8 + 12 * ((c8 & 3) >> 1) + ((c8 & 1) ? 8 : 0), lcb = lca + 24 * 8;
+    const int lca2 = (c8 & 1) ? (c8 == 1 ? 768 + 4 * r8 : lca) : lca + 4;
+    const int lcb2 = (c8 & 1) ? (c8 == 1 ? 768 + 4 * (r8 + 8) : lcb) : lcb + 4;
+    // where lane l's 16 bytes of the staging block belong in the activation block of the slice's 32 tokens
+    const int half16 = (m0 >> 4) & 1;
+    const int vout = (m0 / 32) * kW4ABlock + (lane < 24 ? 384 * half16 + 16 * lane
+                                                : lane < 48 ? 768 + 384 * half16 + 16 * (lane - 24) : kW4ACodes + 64 * half16 + 16 * (lane - 48));
     struct XStage { uint4 x0, x1; };                   // 8 bf16 activations of token r8 and of token r8 + 8
     struct BStage { uint4 b[PROJ ? 2 * RBMAX : 1]; };  // L1s fragments: k steps 0 and 1 of every 16-column block
     // STAGE: the fragments of the next two groups wait in registers (at rank 128 this fills the register file
@@ -158,6 +170,7 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     float *lrinv = reinterpret_cast<float *>(act_lds);
     const int glds = nchunks > 1 ? p.gchunk : p.G;      // groups whose factors the LDS holds, from gbeg on
     unsigned char *wlds = act_lds + L::rinv_bytes(QUANT ? glds : 0) + (size_t)wave * L::kWaveBytes;
+    unsigned char *olds = wlds + L::kMainBytes;
     const int kr0 = 64 * g0 + 4 * lane, kr1 = kr0 + 256, kend = 64 * g1, kbeg = 64 * gbeg;
     float4 rv0 = make_float4(0.f, 0.f, 0.f, 0.f), rv1 = rv0;
     if (QUANT && npairs > 0) {
@@ -375,13 +388,18 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             const uint32_t b1 = odd ? ((blo >> 16) | (bhi << 16)) : blo;
             const uint32_t a2 = odd ? (c8 == 1 ? sa : a1) : (ahi | (na << 16));         // second: the scale, dword 2 again, or dword 1
             const uint32_t b2 = odd ? (c8 == 1 ? sb : b1) : (bhi | (nb << 16));
-            // Unconditional stores, the same four for every lane: rows past M land in the padding rows of the
-            // workspace (it is sized for Mpad rows).
+            // The words meet in the wavefront's staging block (only this wavefront touches it: the LDS queue of a
+            // wavefront is in order) and leave as 832 contiguous bytes in three runs; rows past M land in the padding
+            // rows of the workspace (it is sized for Mpad rows).
             const int sc = g * (p.Mpad / 32) * kW4ABlock;      // one group of blocks
-            __builtin_amdgcn_raw_buffer_store_b32(a1, rs_c, vca, sc, 0);
-            __builtin_amdgcn_raw_buffer_store_b32(b1, rs_c, vcb, sc, 0);
-            __builtin_amdgcn_raw_buffer_store_b32(a2, rs_c, vca2, sc, 0);
-            __builtin_amdgcn_raw_buffer_store_b32(b2, rs_c, vcb2, sc, 0);
+            *reinterpret_cast<uint32_t *>(olds + lca) = a1;
+            *reinterpret_cast<uint32_t *>(olds + lcb) = b1;
+            *reinterpret_cast<uint32_t *>(olds + lca2) = a2;
+            *reinterpret_cast<uint32_t *>(olds + lcb2) = b2;
+            if (lane < kActOutStage / 16) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(olds + 16 * lane);
+                buffer_store_b128<0>(__builtin_bit_cast(buffer_u32x4, v), rs_c, vout, sc);
+            }
         }
     };
 
@@ -514,8 +532,8 @@ hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
         return hipErrorInvalidValue;
     const dim3 grid((unsigned)((p.M + 15) / 16) * nchunks), block(WAVES * 64);
     const bool q = flags & 1, pr = (flags & 2) && p.rank > 0;
-    // (the per-token format exchanges its maxima through the wavefronts' blocks even without a projection)
-    size_t lds = (q ? L::rinv_bytes(nchunks > 1 ? p.gchunk : p.G) : 0) + ((pr || FMT == 2) ? L::wave_bytes() : 0);
+    // (the wavefronts' blocks also stage the INT4 codes on their way out and carry the per-token format's maxima)
+    size_t lds = (q ? L::rinv_bytes(nchunks > 1 ? p.gchunk : p.G) : 0) + L::wave_bytes();
     if (lds < 16) lds = 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     // the limit on dynamic LDS is raised once per instantiation, to all a CU has (the size of a launch varies with K and the rank)

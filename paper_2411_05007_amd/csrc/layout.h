@@ -241,10 +241,11 @@ inline GemmPlan plan_gemm(int M, int N, int G, int ksplit_override = 0) {
 // LDS bytes of one activation-kernel workgroup with `waves` wavefronts that covers `groups` groups of K: 1 / lambda of
 // those channels (fp32), plus one private block per wavefront (X turn-around during the loop, partial H at the end).
 constexpr int kLdsBytesPerCU = 160 * 1024;
+constexpr int kActOutStage = 2 * 384 + 64;      // a wavefront's 16 tokens of one group on their way out: codes of both halves, scales
 inline size_t act_lds_bytes(int groups, int rank, int waves) {
     const int rbmax = rank <= 32 ? 2 : rank <= 64 ? 4 : rank <= 128 ? 8 : 16;
     const size_t red = (size_t)16 * (rbmax * 16 + 1) * 4;
-    return (size_t)groups * kGroup * 4 + (size_t)waves * (red > 2304 ? red : 2304);
+    return (size_t)groups * kGroup * 4 + (size_t)waves * ((red > 2304 ? red : 2304) + kActOutStage);
 }
 // Wavefronts of a workgroup that walks all of K by itself: eight when K gives each of them a few groups and their LDS fits.
 inline int act_waves(int K, int rank) { return (K / kGroup >= 32 && act_lds_bytes(K / kGroup, rank, 8) <= (size_t)kLdsBytesPerCU) ? 8 : 4; }
