@@ -266,7 +266,7 @@ int svdq_debug_group_acc(const svdq_layer_dev *L, const void *workspace, int M, 
 
 size_t svdq_fp4_workspace_bytes(int M, const svdq_shape *s) {
     if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
-    return svdq::workspace_layout_fp4(M, s->K, s->N, s->rank, ksplit_override()).total;
+    return svdq::workspace_layout_fp4(M, s->K, s->N, s->rank, ksplit_override(), act_override()).total;
 }
 
 int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
@@ -278,10 +278,9 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank, ksplit_override());
+    const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank, ksplit_override(), act_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    if (s.K > 32768 || svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
-        return SVDQ_EUNSUPPORTED;
+    if (s.K > 32768 || svdq::act_lds_bytes(w.act_gchunk, s.rank, w.act_waves) > (size_t)svdq::kLdsBytesPerCU) return SVDQ_EUNSUPPORTED;
     if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
         return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -300,6 +299,9 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     a.fmt = 1;
     a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);      // arrival counters of a split K loop start at zero
     a.n_zero = w.n_counters;
+    a.chunks = w.act_chunks; a.gchunk = w.act_gchunk; a.waves = w.act_waves;
+    a.hpart = reinterpret_cast<float *>(ws + w.hpart_off);
+    a.arrived = reinterpret_cast<unsigned long long *>(ws + w.aflags_off);
     hipError_t e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
     if (e != hipSuccess) return hip_fail(e);
     if (void *ev = g_profile_event) {

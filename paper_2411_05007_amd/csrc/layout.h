@@ -176,25 +176,12 @@ inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0) {
 }
 
 struct WorkspaceFp4 {
-    size_t codes_off, bx_off, h_off, hfrag_off, counters_off, partial_off, total;
+    size_t codes_off, bx_off, h_off, hfrag_off, counters_off, partial_off, hpart_off, aflags_off, total;
     int Mpad;
     int n_counters;
+    int act_chunks, act_gchunk, act_waves;      // the activation kernel's cut of K (ActPlan below)
 };
-inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank, int ksplit_override = 0) {
-    WorkspaceFp4 w;
-    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
-    const int G = K / kGroup;
-    w.codes_off = 0;
-    w.bx_off = align256((size_t)G * w.Mpad * kFp4RowBytes);
-    w.h_off = w.bx_off + align256(fp4_scale_bytes(G, w.Mpad));
-    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, G, ksplit_override);
-    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
-    w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
-    w.total = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);
-    return w;
-}
+
 
 // How the W4A4 GEMM of an M x N x (64 G) layer is launched.  Tiles are 128 x 256, two workgroups per CU (512 places).
 // A launch with at most one workgroup per CU has the K loop of every tile split over up to four workgroups (at least
@@ -290,6 +277,29 @@ inline ActPlan plan_act(int M, int G, int rank, int gchunk_override = 0) {
 // the value a workgroup leaves in its arrival word; the word is cleared again before the kernel ends, so whatever a
 // fresh workspace holds is taken for "not arrived" (anything but this one 64-bit value)
 constexpr unsigned long long kActArrived = 0x5356445141525256ull;
+
+// Workspace of the MXFP4 forward (WorkspaceFp4 above).
+inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank, int ksplit_override = 0, int act_override = 0) {
+    WorkspaceFp4 w;
+    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
+    const int G = K / kGroup;
+    w.codes_off = 0;
+    w.bx_off = align256((size_t)G * w.Mpad * kFp4RowBytes);
+    w.h_off = w.bx_off + align256(fp4_scale_bytes(G, w.Mpad));
+    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, G, ksplit_override);
+    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
+    w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
+    w.hpart_off = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);
+    // the activation kernel's partial H [chunks][Mpad][rank] fp32 and one arrival word per workgroup, as in the INT4 workspace
+    const ActPlan ap = plan_act(M > 0 ? M : 1, G, rank, act_override);
+    w.act_chunks = ap.chunks; w.act_gchunk = ap.gchunk; w.act_waves = ap.waves;
+    const bool parked = ap.chunks > 1 && rank > 0;
+    w.aflags_off = w.hpart_off + (parked ? align256((size_t)ap.chunks * w.Mpad * rank * 4) : 0);
+    w.total = w.aflags_off + (parked ? align256((size_t)(w.Mpad / 16) * ap.chunks * 8) : 0);
+    return w;
+}
 
 // Workspace carve-up for a forward of M tokens.
 struct Workspace {

@@ -306,9 +306,12 @@ def test_fp4_prepare_matches_the_oracle_given_the_same_factors(lib):
         S.svdq_fp4_pack(U["rinv"], U["l1s"], U["l2"], U["qw"], bad, U["bias"])
     # workspace: codes G * Mpad * 32, scale dwords ceil(G/4) * Mpad * 8, H and its bf16 split (rank 0: one column each)
     assert S.svdq_workspace_bytes(300, prep.shape) == 4 * 512 * 32 + 1 * 512 * 8 + 2 * (512 * 1 * 4)
-    # a long K and few tiles: arrival counters (one per tile, padded to 256 bytes) and ksplit fp32 partial tiles of 128 x 256 per tile
+    # a long K and few tiles: arrival counters (one per tile, padded to 256 bytes) and ksplit fp32 partial tiles of 128 x 256 per
+    # tile; and the activation kernel's parked partial H (K cut into 8 runs of 24 groups for these 32 slices) with its
+    # 8-byte arrival words
     long_k = S.make_shape(12288, 3072, 32, group=32)
-    assert S.svdq_workspace_bytes(512, long_k) == 192 * 512 * 32 + 48 * 512 * 8 + 2 * (512 * 32 * 4) + 256 + 4 * 48 * 128 * 256 * 4
+    assert S.svdq_workspace_bytes(512, long_k) == (192 * 512 * 32 + 48 * 512 * 8 + 2 * (512 * 32 * 4) + 256 + 4 * 48 * 128 * 256 * 4
+                                                   + 8 * 512 * 32 * 4 + 32 * 8 * 8)
 
 
 def test_fp4_forward_argument_errors(lib):
@@ -324,9 +327,13 @@ def test_fp4_forward_argument_errors(lib):
     assert fwd(*args(16, 1 << 40)) == -2
     fake.shape = S.make_shape(3072, 3072, 32, group=32)
     assert lib.svdq_linear_forward(*args(16, 1 << 40)) == -2      # and the other way round
-    for K, r in ((32768 + 64, 32), (24576, 256)):          # the activation kernel's LDS limit applies to both formats
+    # too long a K; and the activation kernel's LDS limit (reached only with all of a long K forced into one run) applies
+    # to both formats
+    for K, r, opt in ((32768 + 64, 32, 0), (24576, 256, 255 << 12)):
         fake.shape = S.make_shape(K, 3072, r, group=32)
+        lib.svdq_forward_options(opt)
         assert fwd(*args(16, 1 << 62)) == -2, (K, r)
+    lib.svdq_forward_options(0)
     assert lib.svdq_fp4_workspace_bytes(-1, C.byref(fake.shape)) == 0
 
 
