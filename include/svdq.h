@@ -299,10 +299,13 @@ int svdq_fp4_debug_act(const svdq_layer_dev *layer, const void *workspace, int M
  * W4A16 (App. "Implementation Details": the inputs of the linear layers in adaptive normalization stay 16-bit):
  * the SAME prepared INT4 layer (shape.group = 64) applied to 16-bit activations,
  *   Y = bf16( (X * 1/lambda) Q(R) + (X l1s) l2 + bias ),   Q(R) = wscales * codes,
- * i.e. Eq. 5 without quantizing the activations.  Arguments, workspace (svdq_workspace_bytes), stream and errors as
- * for svdq_linear_forward.  A weight-streaming kernel meant for the handful of rows these layers see; any M is
- * accepted (eight rows per pass over the weights).  Enqueues two kernels (down projection, then the weight stream).
+ * i.e. Eq. 5 without quantizing the activations.  Arguments, stream and errors as for svdq_linear_forward; the
+ * workspace holds only H and its bf16 parts: svdq_w4a16_workspace_bytes(M, shape) bytes (a workspace sized for
+ * svdq_linear_forward is larger and does as well).  A weight-streaming kernel meant for the handful of rows these layers
+ * see; any M is accepted (eight rows per pass over the weights).  Enqueues two kernels (down projection, then the
+ * weight stream).
  */
+size_t svdq_w4a16_workspace_bytes(int M, const svdq_shape *shape);
 int svdq_w4a16_forward(const svdq_layer_dev *layer, const void *X, int M, void *Y,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
@@ -314,8 +317,8 @@ int svdq_w4a16_forward(const svdq_layer_dev *layer, const void *X, int M, void *
  *   Y = bf16( s_x[m] s_w[n] (exact int32 sum of code products) + (X l1s) l2 + bias ).
  * These entry points take a svdq_shape with group = 0.  Buffers, ownership, alignment, stream and error
  * behaviour are those of their INT4 namesakes; wcodes holds one int8 per weight (K * Npad bytes, operand order
- * of the int8 matrix-core instruction), wscales fp16 [Npad].  The forward enqueues three kernels (quantization,
- * down projection, GEMM).  The K / rank limits of svdq_linear_forward apply; K * Npad and K * Mpad below 2^31.
+ * of the int8 matrix-core instruction), wscales fp16 [Npad].  The forward enqueues two kernels (quantization with
+ * the down projection, GEMM).  The K / rank limits of svdq_linear_forward apply; K * Npad and K * Mpad below 2^31.
  * ------------------------------------------------------------------------------------------------ */
 int svdq_w8a8_prepared_sizes(const svdq_shape *shape, svdq_sizes *out);
 int svdq_w8a8_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,

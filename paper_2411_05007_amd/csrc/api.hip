@@ -350,6 +350,25 @@ int svdq_fp4_debug_act(const svdq_layer_dev *L, const void *workspace, int M, ui
 
 // ---- W4A16 -----------------------------------------------------------------------------------------------------
 
+// workspace of the 16-bit-activation forward: H fp32 [Mpad][rank] and its bf16 parts, nothing else
+struct W4A16Workspace {
+    size_t h_off, hfrag_off, total;
+    int Mpad;
+};
+static W4A16Workspace w4a16_workspace(int M, int rank) {
+    W4A16Workspace w;
+    w.Mpad = svdq::round_up(M > 0 ? M : 1, svdq::kRowPad);
+    w.h_off = 0;
+    w.hfrag_off = svdq::align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.total = 2 * w.hfrag_off;
+    return w;
+}
+
+size_t svdq_w4a16_workspace_bytes(int M, const svdq_shape *s) {
+    if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
+    return w4a16_workspace(M, s->rank).total;
+}
+
 int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
                        size_t workspace_bytes, void *hip_stream) {
     const int st = check_layer(L);
@@ -359,7 +378,7 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::Workspace w = svdq::workspace_layout(M, s.K, s.N, s.rank, ksplit_override());
+    const W4A16Workspace w = w4a16_workspace(M, s.rank);
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
     if (s.K > 32768 || svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;

@@ -27,7 +27,7 @@ EXPORTS = [
     "svdq_fp4_prepared_sizes", "svdq_fp4_prepare", "svdq_fp4_pack", "svdq_fp4_unpack_wcodes", "svdq_fp4_unpack_wscales",
     "svdq_fp4_workspace_bytes", "svdq_fp4_linear_forward", "svdq_fp4_debug_act",
     "svdq_w8a8_prepared_sizes", "svdq_w8a8_prepare", "svdq_w8a8_pack", "svdq_w8a8_unpack_wcodes", "svdq_w8a8_unpack_wscales",
-    "svdq_w8a8_workspace_bytes", "svdq_w8a8_linear_forward", "svdq_w8a8_debug_act", "svdq_w4a16_forward",
+    "svdq_w8a8_workspace_bytes", "svdq_w8a8_linear_forward", "svdq_w8a8_debug_act", "svdq_w4a16_forward", "svdq_w4a16_workspace_bytes",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
     "svdq_forward_options", "svdq_profile_event", "svdq_mfma_peak_probe", "svdq_linear_forward_static",
 ]
@@ -84,6 +84,8 @@ def lib() -> C.CDLL:
         L.svdq_fp4_linear_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
         L.svdq_fp4_debug_act.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, vp, vp]
         L.svdq_w4a16_forward.argtypes = [C.POINTER(LayerDev), vp, C.c_int, vp, vp, C.c_size_t, vp]
+        L.svdq_w4a16_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
+        L.svdq_w4a16_workspace_bytes.restype = C.c_size_t
         L.svdq_w8a8_workspace_bytes.restype = C.c_size_t
         L.svdq_w8a8_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
         L.svdq_w8a8_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
@@ -447,8 +449,8 @@ class DeviceLayer:
         M = x.shape[0]
         if out is None:
             out = torch.empty((M, self.N), dtype=torch.bfloat16, device=x.device)
-        if workspace is None:
-            workspace = self.workspace(M)
+        if workspace is None:      # H and its bf16 parts only
+            workspace = torch.empty(int(lib().svdq_w4a16_workspace_bytes(int(M), C.byref(self.shape))), dtype=torch.uint8, device=self.device)
         s = torch.cuda.current_stream(x.device) if stream is None else stream
         _check(lib().svdq_w4a16_forward(C.byref(self.cdesc), x.data_ptr(), M, out.data_ptr(), workspace.data_ptr(),
                                         workspace.numel(), s.cuda_stream), "svdq_w4a16_forward")

@@ -2,6 +2,8 @@
 workspace embedded in larger allocations whose surroundings hold a pattern, on ragged shapes (M, N off the tile
 sizes, split K loops and cut activation runs included), and the surroundings are compared afterwards.  The workspace
 is exactly as large as the size query says."""
+import ctypes as C
+
 import numpy as np
 import pytest
 
@@ -67,10 +69,15 @@ def test_int4_forward_stays_inside_its_buffers(torch, M, K, N, r, opts):
     # the parity views read the same workspace and write only their own outputs
     layer.debug_act(ws, M)
     _check(torch, big_ws, n, big_y, M, "int4 debug views")
-    # the 16-bit-activation forward of the same layer, on the same guarded buffers
+    # the 16-bit-activation forward of the same layer: on the same guarded buffers, and on a workspace of exactly its own size
     if M <= 64:
         layer.forward_w4a16(x, out=y, workspace=ws)
         _check(torch, big_ws, n, big_y, M, "w4a16")
+        n16 = int(S.lib().svdq_w4a16_workspace_bytes(M, C.byref(layer.shape)))
+        assert 0 < n16 < n
+        big16, ws16, big_y, y = _guarded(torch, layer, M, N, n16)
+        layer.forward_w4a16(x, out=y, workspace=ws16)
+        _check(torch, big16, n16, big_y, M, "w4a16, own workspace")
     S.svdq_forward_options(0)
 
 

@@ -188,6 +188,9 @@ def test_shape_errors_and_workspace_size(lib):
     assert S.svdq_workspace_bytes(4608, sh) == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32 + 4 * 4608 * 32 * 4 + align256((4608 // 16) * 4 * 8)
     lib.svdq_forward_options(0)
     assert S.svdq_workspace_bytes(16, S.make_shape(100, 64, 16)) == 0
+    # the 16-bit-activation forward needs H (fp32, 256 padded rows) and its bf16 parts only
+    assert lib.svdq_w4a16_workspace_bytes(3, C.byref(sh)) == 2 * 256 * 32 * 4
+    assert lib.svdq_w4a16_workspace_bytes(3, C.byref(S.make_shape(100, 64, 16))) == 0
     # forward argument checks happen before any GPU call
     bad = S.LayerDev()
     assert lib.svdq_linear_forward(C.byref(bad), None, 4, None, None, 0, None) == -1
