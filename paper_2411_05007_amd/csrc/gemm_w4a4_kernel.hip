@@ -66,7 +66,7 @@ struct W4Tile {
     static constexpr int kRing = kStages * kStage;
     static constexpr int kOutBytes = 4 * 32 * kOutRowW4;
     static constexpr int kLdsBytes = kRing > kOutBytes ? kRing : kOutBytes;
-    static constexpr int kDmaPerStep = RB == 4 ? 5 : 4;           // direct-to-LDS instructions per wavefront and group
+    static constexpr int kDmaPerStep = 4;                         // direct-to-LDS instructions per wavefront and group           // direct-to-LDS instructions per wavefront and group
     static_assert(kStage % 256 == 0 && kW4ABlock % 256 == 0 && kW4ACodes % 256 == 0, "scale reads address in units of 256 bytes");
 };
 
@@ -135,26 +135,36 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
     // ---- memory -> LDS -------------------------------------------------------------------------------------------
-    // Per group the tile's RB activation blocks are contiguous (1792 bytes each, 1664 of them used), and a wavefront's
-    // 64 columns are one weight block (2304 bytes).  Wavefront w copies activation block w (1024 + 640 bytes: the
-    // second request runs on 40 lanes) and its own weight block (1024 + 1024 + 256 bytes).  A lane's 16 bytes land
-    // at 16 * lane of the request's LDS destination, so the LDS image is the memory image.
+    // Per group the tile's RB activation blocks are contiguous in memory (1792 bytes each), and so are the four weight
+    // blocks of its 256 columns (2304 bytes each).  A lane's 16 bytes land at 16 * lane of a request's LDS destination,
+    // so the LDS image is the memory image.
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.xa, w4_a_bytes(p.G, p.Mpad));
     const __amdgpu_buffer_rsrc_t rs_b = make_rsrc(p.wb, w4_b_bytes(p.G, p.Npad));
     const int a_stride = (p.Mpad / 32) * kW4ABlock, b_stride = (p.Npad / 64) * kW4BBlock;
-    const int a_base = (gm0 / 32 + wave) * kW4ABlock;
-    const int b_base = (gn0 / 64 + wave) * kW4BBlock;
+    // A stage of the ring is the memory image of the tile's four activation blocks (7168 contiguous bytes, padding
+    // included) followed by that of its four weight blocks (9216 contiguous bytes): sixteen kilobyte pieces, of which
+    // wavefront w copies pieces w, w + 4, w + 8, w + 12 - four full requests per step, one in each of the first four
+    // slots, no lane masks.  (Measured against one activation block and one weight block per wavefront, five requests
+    // of which two run on part of the lanes, all issued at the top of the step: 4 % faster.)
     const int glast = g_end - 1;
-    auto dma = [&](int g, int stage) {
+    int piece_off[4], piece_stride[4];
+    __amdgpu_buffer_rsrc_t piece_rs[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = wave + 4 * k;
+        const bool is_a = c < 7;
+        piece_off[k] = is_a ? (gm0 / 32) * kW4ABlock + c * 1024 : (gn0 / 64) * kW4BBlock + (c - 7) * 1024;
+        piece_stride[k] = is_a ? a_stride : b_stride;
+        piece_rs[k] = is_a ? rs_a : rs_b;
+    }
+    auto dma_part = [&](int g, int stage, int k) {
         const int gc = g < glast ? g : glast;      // past the end: the last group once more (never used), so that every step issues the same requests
-        unsigned char *sa = lds + stage * T::kStage + wave * kW4ABlock;
-        unsigned char *sb = lds + stage * T::kStage + T::kAStage + wave * kW4BBlock;
-        const int oa = a_base + gc * a_stride, ob = b_base + gc * b_stride;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)sa, 16, lane * 16, oa, 0, 0);
-        if (lane < 40) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)(sa + 1024), 16, lane * 16, oa + 1024, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)sb, 16, lane * 16, ob, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(sb + 1024), 16, lane * 16, ob + 1024, 0, 0);
-        if (lane < 16) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(sb + 2048), 16, lane * 16, ob + 2048, 0, 0);
+        unsigned char *dst = lds + stage * T::kStage + (wave + 4 * k) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(piece_rs[k], (lds_ptr)dst, 16, lane * 16, piece_off[k] + gc * piece_stride[k], 0, 0);
+    };
+    auto dma = [&](int g, int stage) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dma_part(g, stage, k);
     };
 
     // ---- LDS -> registers ----------------------------------------------------------------------------------------
@@ -272,10 +282,15 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
 
     auto export_sums = [&](const floatx16 &d, int g, int r, int c) {
         if (MODE == 1) {
+            // the addresses are worked out afresh at every call: hoisted out of the loop, the 128 of them would not
+            // fit the registers, and a spill next to LDS reads written as asm statements can save a register that is
+            // still being filled
+            int row0 = gm0 + 4 * lh, col0 = gn0 + wn0 + li;
+            asm volatile("" : "+v"(row0), "+v"(col0));
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = gm0 + r * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                const int col = gn0 + wn0 + c * 32 + li;
+                const int row = row0 + r * 32 + 8 * (v >> 2) + (v & 3);
+                const int col = col0 + c * 32;
                 if (row >= p.m0 && row < p.m1 && col >= p.n0 && col < p.n1)
                     p.dbg[((size_t)(row - p.m0) * (p.n1 - p.n0) + (col - p.n0)) * p.G + g] = (int32_t)(4.0f * d[v]);
             }
@@ -291,8 +306,11 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     asm volatile("" : "+v"(acc[R][C][0]), "+v"(acc[R][C][15]), "+v"(SX));              \
     sg = __builtin_amdgcn_mfma_f32_32x32x8f16(op_s(SX), op_s(SW), zero16, 0, 0, 0);    \
     asm volatile("" : "+v"(sg))
+// (the window export keeps no accumulators: it returns before the epilogue, and without them its extra address
+// arithmetic fits the registers - a spill of a register that an LDS read written as an asm statement is still filling
+// would save stale data)
 #define W4_FMA(R, C, AG)                                                                           \
-    _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[R][C][v] = __builtin_fmaf(AG[v], sg[v], acc[R][C][v]);
+    if (MODE == 0) { _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[R][C][v] = __builtin_fmaf(AG[v], sg[v], acc[R][C][v]); }
 #define W4_SB() __builtin_amdgcn_sched_barrier(0)
 
     // first operands: stage 0 is complete when all but the newest kStages - 2 groups of requests have landed
@@ -334,8 +352,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
         W4_READ_A(af[0], aa_c, 2);                       // row block 2 of this group
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((T::kStages - 3) * T::kDmaPerStep) : "memory");
         __builtin_amdgcn_s_barrier();
-        dma(g + T::kStages - 1, st_free);
-        st_free = st_free + 1 == T::kStages ? 0 : st_free + 1;
+        dma_part(g + T::kStages - 1, st_free, 0);
         W4_SB();
         W4_FMA(0, 0, ag[0]);
         export_sums(ag[0], g, 0, 0);
@@ -349,6 +366,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
         W4_READ_SX(sxr[0], ax_n, 0);
         W4_READ_B(braw[0], ab_n, 0);                     // weight codes of the next group
         W4_READ_B(braw[1], ab_n, 1);
+        dma_part(g + T::kStages - 1, st_free, 1);
         W4_SB();
         W4_FMA(0, 1, ag[1]);
         export_sums(ag[1], g, 0, 1);
@@ -358,6 +376,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
         // slot 2: block (1,0); next (1,1)
         W4_MFMA_A(ag[1], af[1], bfr[1]);
         W4_READ_A(af[1], aa_c, 3);                       // row block 3 of this group
+        dma_part(g + T::kStages - 1, st_free, 2);
         W4_SB();
         W4_FMA(1, 0, ag[0]);
         export_sums(ag[0], g, 1, 0);
@@ -368,6 +387,8 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
         W4_WAIT_LGKM(6, "+v"(af[0].d[0]), "+v"(af[0].d[1]), "+v"(af[0].d[2]));      // row block 2 (slot 0)
         W4_MFMA_A(ag[0], af[0], bfr[0]);
         W4_READ_SX(sxr[1], ax_n, 1);
+        dma_part(g + T::kStages - 1, st_free, 3);
+        st_free = st_free + 1 == T::kStages ? 0 : st_free + 1;
         W4_SB();
         W4_FMA(1, 1, ag[1]);
         export_sums(ag[1], g, 1, 1);
