@@ -45,8 +45,9 @@ struct ActLds {
     // behind that block: the INT4 codes and scales of the wavefront's 16 tokens of one group in the byte order of the
     // activation block (two runs of 384 bytes, one per half of the group, and 64 bytes of scales), from where they leave
     // with one 16-byte store per lane
-    static constexpr int kOutBytes = kActOutStage;
-    static constexpr int kMainBytes = (16 * kXRow > 16 * kRedRow * 4) ? 16 * kXRow : 16 * kRedRow * 4;
+    // (two of each: a wavefront works on two groups at a time)
+    static constexpr int kOutBytes = 2 * kActOutStage;
+    static constexpr int kMainBytes = (2 * 16 * kXRow > 16 * kRedRow * 4) ? 2 * 16 * kXRow : 16 * kRedRow * 4;
     static constexpr int kWaveBytes = kMainBytes + kOutBytes;
     static __host__ __device__ size_t rinv_bytes(int groups) { return (size_t)groups * 64 * 4; }
     static __host__ __device__ size_t wave_bytes() { return (size_t)WAVES * kWaveBytes; }
@@ -262,15 +263,15 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     }
 
     // X of one group, load map -> LDS -> operand map: lane (row, blk) picks up channels 16*blk .. +15 of token row
-    auto to_lds = [&](const XStage &sx) {
+    auto to_lds = [&](const XStage &sx, int which) {
         if (PROJ) {
-            *reinterpret_cast<uint4 *>(wlds + r8 * L::kXRow + 16 * c8) = sx.x0;
-            *reinterpret_cast<uint4 *>(wlds + (r8 + 8) * L::kXRow + 16 * c8) = sx.x1;
+            *reinterpret_cast<uint4 *>(wlds + which * 16 * L::kXRow + r8 * L::kXRow + 16 * c8) = sx.x0;
+            *reinterpret_cast<uint4 *>(wlds + which * 16 * L::kXRow + (r8 + 8) * L::kXRow + 16 * c8) = sx.x1;
         }
     };
-    auto project = [&](int g, bool real, const BStage &sb) {
+    auto project = [&](int g, bool real, const BStage &sb, int which) {
         if (PROJ) {
-            const uint4 *ap = reinterpret_cast<const uint4 *>(wlds + row * L::kXRow + 32 * blk);
+            const uint4 *ap = reinterpret_cast<const uint4 *>(wlds + which * 16 * L::kXRow + row * L::kXRow + 32 * blk);
             uint4 x0 = ap[0], x1 = ap[1];
             if (!real) x0 = x1 = make_uint4(0u, 0u, 0u, 0u);     // the repeated group of an odd run adds nothing to H
             const int sg = g * 2 * rb * 1024;
@@ -375,6 +376,11 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             __builtin_amdgcn_raw_buffer_store_b32(wb[0], rs_c, vcb, sc, 0);
             __builtin_amdgcn_raw_buffer_store_b32(wb[1], rs_c, vcb + 4, sc, 0);
         }
+    };
+    // INT4: two groups at a time.  The four quantizer chains (two tokens of two groups) are independent, so their
+    // reductions, divisions and packing steps fill each other's latencies; the words of both groups then go through the
+    // wavefront's two staging blocks and leave with one 16-byte store per lane and group.
+    auto quantize_w4 = [&](const Smoothed &sm, unsigned char *stage) {
         if (QUANT && FMT == 0) {
             uint32_t alo, ahi, blo, bhi, sa, sb;
             encode(sm.a, alo, ahi, sa);
@@ -391,37 +397,82 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             // The words meet in the wavefront's staging block (only this wavefront touches it: the LDS queue of a
             // wavefront is in order) and leave as 832 contiguous bytes in three runs; rows past M land in the padding
             // rows of the workspace (it is sized for Mpad rows).
+            *reinterpret_cast<uint32_t *>(stage + lca) = a1;
+            *reinterpret_cast<uint32_t *>(stage + lcb) = b1;
+            *reinterpret_cast<uint32_t *>(stage + lca2) = a2;
+            *reinterpret_cast<uint32_t *>(stage + lcb2) = b2;
+        }
+    };
+    auto store_w4 = [&](int g, const unsigned char *stage) {
+        if (QUANT && FMT == 0) {
             const int sc = g * (p.Mpad / 32) * kW4ABlock;      // one group of blocks
-            *reinterpret_cast<uint32_t *>(olds + lca) = a1;
-            *reinterpret_cast<uint32_t *>(olds + lcb) = b1;
-            *reinterpret_cast<uint32_t *>(olds + lca2) = a2;
-            *reinterpret_cast<uint32_t *>(olds + lcb2) = b2;
             if (lane < kActOutStage / 16) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(olds + 16 * lane);
+                const uint4 v = *reinterpret_cast<const uint4 *>(stage + 16 * lane);
                 buffer_store_b128<0>(__builtin_bit_cast(buffer_u32x4, v), rs_c, vout, sc);
             }
         }
     };
 
-    // One step = one group.  Its operands were requested two steps ago; as soon as the raw X registers have
-    // been smoothed and dropped into LDS, and the MFMAs have consumed the L1s fragments, the same registers
-    // are refilled with the operands of the group two steps on, L1s fragments first: loads complete in order,
-    // so waiting for a step's fragments never waits for X requested after them.
-    auto step = [&](int g, bool real, XStage &xs, BStage &bs) {
-        to_lds(xs);
-        const Smoothed sm = smooth(g, xs);       // last use of the raw X registers: the refill below lands in them
-        project(g, real, bs);
+    // The operands of a step were requested one step ago; as soon as the raw X registers have been smoothed and dropped
+    // into LDS, and the MFMAs have consumed the L1s fragments, the same registers are refilled with the operands of the
+    // next step, L1s fragments first: loads complete in order, so waiting for a step's fragments never waits for X
+    // requested after them.
+    // Two groups per step, worked on together: their chains (LDS turn-around, reductions over lanes, the divisions)
+    // are independent of each other, and a workgroup is often alone on its CU, one wavefront per SIMD, with nobody
+    // else to fill the waits.
+    auto step2 = [&](int g, bool real1) {
+        const int g1c = clampg(g + 1);
+        to_lds(xs0, 0);
+        to_lds(xs1, 1);
+        const Smoothed sm0 = smooth(g, xs0);     // last use of the raw X registers: the refills below land in them
+        const Smoothed sm1 = smooth(g1c, xs1);
+        project(g, true, bs0, 0);
+        project(g1c, real1, bs1, 1);
         __builtin_amdgcn_sched_barrier(0);       // keep the refills here, in this order, in the instruction stream
+        bs0 = fetch_b(clampg(g + 2));
+        xs0 = fetch_x(clampg(g + 2));
+        bs1 = fetch_b(clampg(g + 3));
+        xs1 = fetch_x(clampg(g + 3));
+        __builtin_amdgcn_sched_barrier(0);
+        if (FMT == 0) {
+            quantize_w4(sm0, olds);
+            quantize_w4(sm1, olds + kActOutStage);
+            store_w4(g, olds);
+            store_w4(g1c, olds + kActOutStage);
+        } else {
+            quantize(g, sm0);
+            quantize(g1c, sm1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // One group per step, the two steps of a pair one after the other: faster by half a microsecond per launch where the
+    // projection is short (ranks up to 32: two column blocks), slower by 7 to 19 % from rank 64 on (measured on the
+    // FLUX.1 shapes at ranks 32 and 128).
+    auto step1 = [&](int g, bool real, XStage &xs, BStage &bs) {
+        to_lds(xs, 0);
+        const Smoothed sm = smooth(g, xs);
+        project(g, real, bs, 0);
+        __builtin_amdgcn_sched_barrier(0);
         bs = fetch_b(clampg(g + 2));
         xs = fetch_x(clampg(g + 2));
         __builtin_amdgcn_sched_barrier(0);
-        quantize(g, sm);
+        if (FMT == 0) {
+            quantize_w4(sm, olds);
+            store_w4(g, olds);
+        } else {
+            quantize(g, sm);
+        }
         __builtin_amdgcn_sched_barrier(0);
     };
+    constexpr bool kPairStep = RBMAX > 2;
     for (int ip = 0; ip < npairs; ++ip) {
         const int g = g0 + 2 * ip;
-        step(g, true, xs0, bs0);
-        step(clampg(g + 1), g + 1 < g1, xs1, bs1);
+        if (kPairStep) {
+            step2(g, g + 1 < g1);
+        } else {
+            step1(g, true, xs0, bs0);
+            step1(clampg(g + 1), g + 1 < g1, xs1, bs1);
+        }
     }
 
     // housekeeping for the kernel that follows on the stream: its tile arrival counters start at zero

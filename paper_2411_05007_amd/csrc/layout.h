@@ -232,7 +232,8 @@ constexpr int kActOutStage = 2 * 384 + 64;      // a wavefront's 16 tokens of on
 inline size_t act_lds_bytes(int groups, int rank, int waves) {
     const int rbmax = rank <= 32 ? 2 : rank <= 64 ? 4 : rank <= 128 ? 8 : 16;
     const size_t red = (size_t)16 * (rbmax * 16 + 1) * 4;
-    return (size_t)groups * kGroup * 4 + (size_t)waves * ((red > 2304 ? red : 2304) + kActOutStage);
+    // (a wavefront works on two groups at a time: two blocks of 16 x 144 bytes of X, two staging blocks)
+    return (size_t)groups * kGroup * 4 + (size_t)waves * ((red > 4608 ? red : 4608) + 2 * kActOutStage);
 }
 // Wavefronts of a workgroup that walks all of K by itself: eight when K gives each of them a few groups and their LDS fits.
 inline int act_waves(int K, int rank) { return (K / kGroup >= 32 && act_lds_bytes(K / kGroup, rank, 8) <= (size_t)kLdsBytesPerCU) ? 8 : 4; }
