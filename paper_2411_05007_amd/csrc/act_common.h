@@ -32,13 +32,9 @@ __device__ __forceinline__ float max_over_8_lanes(float a) {
 }
 
 // Eq. 1 for the 8 channels one lane holds of a token's group of 64 (the group's other 56 channels sit in the 7 lanes
-// beside it): s = max|x| / q_max over the whole group, stored as fp16; codes from x * (1 / s).
-// The codes leave in the operand form of the GEMM's matrix instruction (layout.h): 6 bits per code, sign, two zero
-// bits, magnitude; the lane's 8 codes are 48 bits (lo: bits 0-31, hi: bits 32-47), channel e at bit 6 e.
-// Magnitudes are integer-valued floats below 8, so four of them pack exactly into one float by Horner steps with 64
-// (< 2^21) and one conversion; the sign of a code is the sign of x^ (1 / lambda and 1 / s are positive; a zero code
-// may carry a sign, which the format ignores).
-__device__ __forceinline__ void w4_encode8(const float (&xh)[8], uint32_t &lo, uint32_t &hi, uint32_t &sbits) {
+// beside it): s = max|x| / q_max over the whole group, stored as fp16 (`sbits`); returns 1 / s, the factor that turns
+// x^ into its code (0 for a group of zeros).
+__device__ __forceinline__ float w4_group_rcp(const float (&xh)[8], uint32_t &sbits) {
     float amax = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xh[e]));
@@ -57,23 +53,45 @@ __device__ __forceinline__ void w4_encode8(const float (&xh)[8], uint32_t &lo, u
     const float den = sc > 0.f ? sc : 1.0f;                  // branch-free: the reciprocal always runs
     const float y0 = __builtin_amdgcn_rcpf(den);
     const float rcp_any = __builtin_fmaf(__builtin_fmaf(-den, y0, 1.0f), y0, y0);
-    const float rcp = sc > 0.f ? rcp_any : 0.f;
-    float mag[8];
-    uint32_t sa = 0u, sb = 0u;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        mag[e] = fminf(fabsf(__builtin_rintf(xh[e] * rcp)), 7.f);
-        const uint32_t bits = __float_as_uint(xh[e]);
-        const int pos = 6 * (e & 3) + 5;                      // sign position inside the 24 bits of four codes
-        if (e < 4) sa |= (bits >> (31 - pos)) & (1u << pos);
-        else sb |= (bits >> (31 - pos)) & (1u << pos);
-    }
-    const float fa = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(mag[3], 64.f, mag[2]), 64.f, mag[1]), 64.f, mag[0]);
-    const float fb = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(mag[7], 64.f, mag[6]), 64.f, mag[5]), 64.f, mag[4]);
-    const uint32_t a24 = (uint32_t)fa | sa, b24 = (uint32_t)fb | sb;
-    lo = a24 | (b24 << 24);
-    hi = b24 >> 8;
     sbits = __builtin_bit_cast(uint16_t, sh);
+    return sc > 0.f ? rcp_any : 0.f;
+}
+
+// The codes of up to four such 8-channel runs at once, in the operand form of the GEMM's matrix instruction
+// (layout.h): 6 bits per code - sign, two zero bits, magnitude - i.e. the 6-bit float (E2M3) of value q / 8, which is
+// what v_cvt_scalef32_2xpk16_fp6_f32 makes of x^ / s with the scale operand 8: it divides by 8 and rounds to the
+// nearest multiple of 1/8, ties to even, exactly the rounding of Eq. 1 for |x^ / s| < 7.5; the clamp to +-7 before it
+// stands for the clip of Eq. 1 (it acts only where s was rounded down hard, next to the bottom of the fp16 range, or
+// cut off at its top).  The instruction takes two vectors of 16 and interleaves them: element i of the first lands in
+// field 2 i, of the second in field 2 i + 1; so run j (j = 0..3) gives its even channels to elements 4 j .. 4 j + 3 of
+// the first vector and its odd channels to those of the second, and its 8 codes come out as bits 48 j .. 48 j + 47
+// of the 192, channel e at bit 6 e of the run.  A zero code keeps the sign of x^, which the format ignores.
+typedef float act_floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t act_u32x6 __attribute__((ext_vector_type(6)));
+template <int RUNS>
+__device__ __forceinline__ act_u32x6 w4_codes(const float (*const (&xh)[RUNS])[8], const float (&rcp)[RUNS]) {
+    act_floatx16 ev, od;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ev[i] = od[i] = 0.f;
+#pragma unroll
+    for (int j = 0; j < RUNS; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ev[4 * j + i] = __builtin_amdgcn_fmed3f((*xh[j])[2 * i] * rcp[j], -7.0f, 7.0f);
+            od[4 * j + i] = __builtin_amdgcn_fmed3f((*xh[j])[2 * i + 1] * rcp[j], -7.0f, 7.0f);
+        }
+    return __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(ev, od, 8.0f);
+}
+// run j of such a result as the 48 bits (lo: bits 0-31, hi: bits 32-47) that one lane stores
+__device__ __forceinline__ void w4_run48(const act_u32x6 &r, int j, uint32_t &lo, uint32_t &hi) {
+    const int w = (3 * j) >> 1;
+    if (j & 1) {
+        lo = (r[w] >> 16) | (r[w + 1] << 16);
+        hi = r[w + 1] >> 16;
+    } else {
+        lo = r[w];
+        hi = r[w + 1] & 0xffffu;
+    }
 }
 
 }  // namespace svdq

@@ -179,6 +179,9 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
         rv0 = *reinterpret_cast<const float4 *>(p.rinv + (kr0 < kend ? kr0 : 64 * g0));
         rv1 = *reinterpret_cast<const float4 *>(p.rinv + (kr1 < kend ? kr1 : 64 * g0));
     }
+    // Two groups in flight per wavefront.  (Measured at rank 32 with four and with six in flight, X and fragments alike:
+    // slower by 8 to 50 %, most on the longest K - more requests in flight slow the memory system down more than they
+    // hide of its latency.)
     XStage xs0, xs1;      // X of the next even / odd step
     BStage bs0, bs1;      // L1s fragments of the next even / odd step
     if (npairs > 0) {
@@ -321,10 +324,6 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
         }
         return o;
     };
-    // Eq. 1 for the 8 channels this lane holds of one token's group (act_common.h)
-    auto encode = [&](const float (&xh)[QUANT ? 8 : 1], uint32_t &lo, uint32_t &hi, uint32_t &sbits) {
-        if constexpr (QUANT) w4_encode8(xh, lo, hi, sbits);
-    };
     // Eq. 1 for one MXFP4 block (the 32 channels held by 4 neighbouring lanes): the scale is the smallest power
     // of two s = 2^e >= 2^-126 with max|x| <= 6 s, found from the exponent and mantissa bits of the maximum
     // (max|x| = 1.m * 2^(E - 127) <= 1.5 * 2^(e + 2)  <=>  e = E - 129, one more if 1.m > 1.5), stored as the
@@ -377,30 +376,50 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             __builtin_amdgcn_raw_buffer_store_b32(wb[1], rs_c, vcb + 4, sc, 0);
         }
     };
-    // INT4: two groups at a time.  The four quantizer chains (two tokens of two groups) are independent, so their
-    // reductions, divisions and packing steps fill each other's latencies; the words of both groups then go through the
-    // wavefront's two staging blocks and leave with one 16-byte store per lane and group.
+    // INT4: the codes of a lane's runs of 8 channels (two tokens of one group, or of two groups) come out of one pack
+    // conversion (act_common.h); the words of a group then go through one of the wavefront's staging blocks and leave
+    // with one 16-byte store per lane.
+    auto stage_w4 = [&](uint32_t alo, uint32_t ahi, uint32_t sa, uint32_t blo, uint32_t bhi, uint32_t sb, unsigned char *stage) {
+        // Two neighbouring lanes hold the 16 codes of one triple = 96 bits: dword 0 is the even lane's low word,
+        // dword 1 the even lane's high 16 bits and the odd lane's low 16, dword 2 the rest of the odd lane.
+        const uint32_t na = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)alo, 0xB1, 0xf, 0xf, true);      // the pair's other lane
+        const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)blo, 0xB1, 0xf, 0xf, true);
+        const bool odd = c8 & 1;
+        const uint32_t a1 = odd ? ((alo >> 16) | (ahi << 16)) : alo;                // first store: dword 2 (odd) or dword 0 (even)
+        const uint32_t b1 = odd ? ((blo >> 16) | (bhi << 16)) : blo;
+        const uint32_t a2 = odd ? (c8 == 1 ? sa : a1) : (ahi | (na << 16));         // second: the scale, dword 2 again, or dword 1
+        const uint32_t b2 = odd ? (c8 == 1 ? sb : b1) : (bhi | (nb << 16));
+        // The words meet in the wavefront's staging block (only this wavefront touches it: the LDS queue of a
+        // wavefront is in order) and leave as 832 contiguous bytes in three runs; rows past M land in the padding
+        // rows of the workspace (it is sized for Mpad rows).
+        *reinterpret_cast<uint32_t *>(stage + lca) = a1;
+        *reinterpret_cast<uint32_t *>(stage + lcb) = b1;
+        *reinterpret_cast<uint32_t *>(stage + lca2) = a2;
+        *reinterpret_cast<uint32_t *>(stage + lcb2) = b2;
+    };
+    // one group: tokens r8 and r8 + 8 are runs 0 and 1 of one conversion
     auto quantize_w4 = [&](const Smoothed &sm, unsigned char *stage) {
-        if (QUANT && FMT == 0) {
-            uint32_t alo, ahi, blo, bhi, sa, sb;
-            encode(sm.a, alo, ahi, sa);
-            encode(sm.b, blo, bhi, sb);
-            // Two neighbouring lanes hold the 16 codes of one triple = 96 bits: dword 0 is the even lane's low word,
-            // dword 1 the even lane's high 16 bits and the odd lane's low 16, dword 2 the rest of the odd lane.
-            const uint32_t na = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)alo, 0xB1, 0xf, 0xf, true);      // the pair's other lane
-            const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)blo, 0xB1, 0xf, 0xf, true);
-            const bool odd = c8 & 1;
-            const uint32_t a1 = odd ? ((alo >> 16) | (ahi << 16)) : alo;                // first store: dword 2 (odd) or dword 0 (even)
-            const uint32_t b1 = odd ? ((blo >> 16) | (bhi << 16)) : blo;
-            const uint32_t a2 = odd ? (c8 == 1 ? sa : a1) : (ahi | (na << 16));         // second: the scale, dword 2 again, or dword 1
-            const uint32_t b2 = odd ? (c8 == 1 ? sb : b1) : (bhi | (nb << 16));
-            // The words meet in the wavefront's staging block (only this wavefront touches it: the LDS queue of a
-            // wavefront is in order) and leave as 832 contiguous bytes in three runs; rows past M land in the padding
-            // rows of the workspace (it is sized for Mpad rows).
-            *reinterpret_cast<uint32_t *>(stage + lca) = a1;
-            *reinterpret_cast<uint32_t *>(stage + lcb) = b1;
-            *reinterpret_cast<uint32_t *>(stage + lca2) = a2;
-            *reinterpret_cast<uint32_t *>(stage + lcb2) = b2;
+        if constexpr (QUANT && FMT == 0) {
+            uint32_t sa, sb, alo, ahi, blo, bhi;
+            const float rcp[2] = {w4_group_rcp(sm.a, sa), w4_group_rcp(sm.b, sb)};
+            const float(*const runs[2])[8] = {&sm.a, &sm.b};
+            const act_u32x6 r = w4_codes<2>(runs, rcp);
+            w4_run48(r, 0, alo, ahi);
+            w4_run48(r, 1, blo, bhi);
+            stage_w4(alo, ahi, sa, blo, bhi, sb, stage);
+        }
+    };
+    // two groups: four runs, one conversion
+    auto quantize_w4_pair = [&](const Smoothed &s0, const Smoothed &s1, unsigned char *stage) {
+        if constexpr (QUANT && FMT == 0) {
+            uint32_t sc[4], lo[4], hi[4];
+            const float rcp[4] = {w4_group_rcp(s0.a, sc[0]), w4_group_rcp(s0.b, sc[1]), w4_group_rcp(s1.a, sc[2]), w4_group_rcp(s1.b, sc[3])};
+            const float(*const runs[4])[8] = {&s0.a, &s0.b, &s1.a, &s1.b};
+            const act_u32x6 r = w4_codes<4>(runs, rcp);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w4_run48(r, j, lo[j], hi[j]);
+            stage_w4(lo[0], hi[0], sc[0], lo[1], hi[1], sc[1], stage);
+            stage_w4(lo[2], hi[2], sc[2], lo[3], hi[3], sc[3], stage + kActOutStage);
         }
     };
     auto store_w4 = [&](int g, const unsigned char *stage) {
@@ -435,8 +454,7 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
         xs1 = fetch_x(clampg(g + 3));
         __builtin_amdgcn_sched_barrier(0);
         if (FMT == 0) {
-            quantize_w4(sm0, olds);
-            quantize_w4(sm1, olds + kActOutStage);
+            quantize_w4_pair(sm0, sm1, olds);
             store_w4(g, olds);
             store_w4(g1c, olds + kActOutStage);
         } else {
