@@ -285,3 +285,41 @@ def test_gptq_prepared_fp4_layer(torch):
         err.append(np.linalg.norm(y - ref) / np.linalg.norm(ref))
     _say(f"fp4 gptq: relative output error {err[1]:.4e} vs round-to-nearest {err[0]:.4e}")
     assert err[1] < err[0]
+
+
+def test_headline_layer_all_rows(torch):
+    """FLUX MLP up (M = 4608, K = 3072, N = 12288, r = 32) in the configuration bench.py times: EVERY row of Y, of the
+    activation codes and scale bytes and of H against the oracle, in blocks of 512 rows."""
+    case = I.case_by_name("flux_mlp_up")
+    _say(f"fp4 headline, all rows: M={case.M} K={case.K} N={case.N} r={case.rank}: generating")
+    L = I.make_layer(case)
+    prep = S.svdq_fp4_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    layer = S.DeviceLayer(prep)
+    x = S.bf16_tensor_from_bits(L["x_bf16"])
+    y = torch.full((case.M, case.N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    ws = layer.workspace(case.M)
+    layer.forward(x, out=y, workspace=ws)
+    torch.cuda.synchronize()
+    U = S.svdq_fp4_unpack(prep)
+    codes, bx, H = layer.debug_act(workspace=ws, M=case.M)
+    yb = S.bits_from_bf16_tensor(y)
+    num = den = 0.0
+    worst = 0.0
+    for r0 in range(0, case.M, 512):
+        rows = slice(r0, r0 + 512)
+        _say(f"fp4 headline, all rows: oracle rows {r0}..")
+        ref = F.forward(L["x_bf16"][rows], U)
+        assert np.array_equal(bx[rows], ref["bx"]), f"activation scale bytes, rows {r0}.."
+        assert np.array_equal(F.decode_e2m1(codes[rows]), F.decode_e2m1(ref["qx"])), f"activation codes, rows {r0}.."
+        assert np.max(np.abs(H[rows] - ref["H"])) <= 1e-5 * np.max(np.abs(ref["H"])), f"H, rows {r0}.."
+        yg = O.bf16_to_f32(yb[rows]).astype(np.float64)
+        r64 = ref["Y64"]
+        ymax = np.max(np.abs(r64))
+        assert np.all(np.isfinite(yg))
+        assert np.all(np.abs(yg - r64) <= 2.0 ** -7 * np.abs(r64) + 2e-5 * ymax), f"Y element-wise, rows {r0}.."
+        num += float(np.sum((yg - r64) ** 2))
+        den += float(np.sum(r64 ** 2))
+        worst = max(worst, float(np.max(np.abs(yg - r64)) / ymax))
+    rel = (num / den) ** 0.5
+    _say(f"fp4 headline, all rows: rel-L2 {rel:.3e}, worst max-abs/max|Y| {worst:.3e}")
+    assert rel <= REL_L2 and worst <= MAX_ABS

@@ -460,6 +460,53 @@ def test_headline_layer_all_rows(torch):
         assert np.array_equal(A, want), (m0, m1, n0, n1)
 
 
+def test_mlp_down_layer_all_rows(torch):
+    """FLUX MLP down (M = 4608, K = 12288, N = 3072, r = 32) in the configuration bench.py times - the activation
+    kernel's K cut into runs with parked partial H, a GEMM launch of 432 tiles that leaves places empty: EVERY row of
+    Y, of the activation codes and scales and of H against the oracle, and the exact group sums of windows across the
+    borders of the last tile row and tile column."""
+    case = I.case_by_name("flux_mlp_down")
+    _say(f"mlp down, all rows: M={case.M} K={case.K} N={case.N} r={case.rank}: generating")
+    L = I.make_layer(case)
+    prep = S.svdq_prepare(L["w"], L["x_absmax"], case.rank, bias=L["bias"])
+    S.svdq_forward_options(0)
+    layer = S.DeviceLayer(prep)
+    x = S.bf16_tensor_from_bits(L["x_bf16"])
+    y = torch.full((case.M, case.N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    ws = layer.workspace(case.M)
+    layer.forward(x, out=y, workspace=ws)
+    torch.cuda.synchronize()
+    U = S.svdq_unpack(prep)
+    codes, sx, H = layer.debug_act(workspace=ws, M=case.M)
+    yb = S.bits_from_bf16_tensor(y)
+    worst = 0.0
+    num = den = 0.0
+    for r0 in range(0, case.M, 512):
+        rows = slice(r0, r0 + 512)
+        _say(f"mlp down, all rows: oracle rows {r0}..")
+        ref = O.forward(L["x_bf16"][rows], U)
+        assert np.array_equal(codes[rows], ref["qx"]), f"activation codes, rows {r0}.."
+        assert np.array_equal(sx[rows].view(np.uint16), ref["sx"].view(np.uint16)), f"activation scales, rows {r0}.."
+        assert np.max(np.abs(H[rows] - ref["H"])) <= 1e-5 * np.max(np.abs(ref["H"])), f"H, rows {r0}.."
+        yg = O.bf16_to_f32(yb[rows]).astype(np.float64)
+        yr = ref["Y"]
+        ymax = np.max(np.abs(yr))
+        assert np.all(np.isfinite(yg))
+        assert np.all(np.abs(yg - yr) <= 2.0 ** -7 * np.abs(yr) + 2e-5 * ymax), f"Y element-wise, rows {r0}.."
+        num += float(np.sum((yg - yr) ** 2))
+        den += float(np.sum(yr ** 2))
+        worst = max(worst, float(np.max(np.abs(yg - yr)) / ymax))
+    rel = (num / den) ** 0.5
+    _say(f"mlp down, all rows: rel-L2 {rel:.3e}, worst max-abs/max|Y| {worst:.3e}")
+    assert rel <= REL_L2 and worst <= MAX_ABS
+    # group sums across the border between the last two tile rows (4480) and the last two tile columns (2816)
+    ref = O.forward(L["x_bf16"][4470:4490], U, want_group_sums=True)
+    for (m0, m1, n0, n1) in ((4476, 4484, 2810, 2822), (4472, 4488, 0, 8), (4478, 4482, 3064, 3072)):
+        A = layer.debug_group_acc(m0, m1, n0, n1, workspace=ws, M=case.M)
+        want = np.transpose(ref["A"][:, m0 - 4470:m1 - 4470, n0:n1], (1, 2, 0))
+        assert np.array_equal(A, want), (m0, m1, n0, n1)
+
+
 SWEEP = [f"flux_block_{layer}_M{M}_r{r}" for M in (4608, 512) for r in (32, 128) for layer in ("qkv", "out", "mlp_up", "mlp_down")]
 
 
