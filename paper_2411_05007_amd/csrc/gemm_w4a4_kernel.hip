@@ -21,8 +21,8 @@
 // Structure.  A workgroup of four wavefronts owns a (32 RB) x 256 tile; wavefront w owns all its rows and columns
 // 64 w .. 64 w + 63 (RB x 2 blocks of 32 x 32), two workgroups per CU.  Per group the workgroup needs RB activation
 // blocks (shared by the four wavefronts) and eight weight blocks (two per wavefront, private); each block carries
-// its codes and its fp16 scales (layout.h), and all of them go from memory straight into a four-stage LDS ring
-// with direct-to-LDS loads, three groups ahead, no stop in registers.  Weight codes stay at four bits until they
+// its codes and its fp16 scales (layout.h), and all of them go from memory straight into a three-stage LDS ring
+// with direct-to-LDS loads, two groups ahead, no stop in registers.  Weight codes stay at four bits until they
 // are in registers, where three AND / AND-OR operations per pair of registers spread them to the 6-bit form.
 // One barrier per group.  The instruction stream of a wavefront is a chain of slots, one per 32 x 32 block:
 //     MFMA A_g(next block) | 16 FMAs of this block | MFMA S_g(next block)
