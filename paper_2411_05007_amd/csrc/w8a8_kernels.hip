@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
         const int bid = (int)blockIdx.x;
         const int per = (total + 7) / 8;
         const int id = (total % 8 == 0) ? (bid % 8) * per + (bid / 8) : bid;      // a bijection only when 8 divides the count
-        constexpr int kBand = 4;
+        constexpr int kBand = 8;
         const int band = id / (kBand * tiles_n);
         const int band_rows = (tiles_m - band * kBand) < kBand ? (tiles_m - band * kBand) : kBand;
         const int in = id - band * kBand * tiles_n;
