@@ -33,6 +33,7 @@
 #include <stdint.h>
 
 #include "buffer.h"
+#include "gemm_common.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -71,12 +72,6 @@ struct W4Tile {
 };
 
 __device__ __forceinline__ uint32_t bf16_bits_w4(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
-__device__ __forceinline__ uint32_t bf16_pair_w4(float lo, float hi) {
-    bf16x2 v;
-    v[0] = (__bf16)lo;
-    v[1] = (__bf16)hi;
-    return __builtin_bit_cast(uint32_t, v);
-}
 
 // MODE 0: normal forward.  MODE 1: additionally export the exact group sums of a window (parity checks).
 template <int RB, int MODE>
@@ -108,19 +103,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     const int g_begin = split * g_per;
     const int g_end = g_begin + g_per < p.G ? g_begin + g_per : p.G;
     int tile_m, tile_n;
-    {
-        const int per = (total + 7) / 8;
-        const int id = (total % 8 == 0) ? (bid % 8) * per + (bid / 8) : bid;      // a bijection only when 8 divides the count
-        // The 64 tiles an XCD runs at a time (two per CU) are then 8 rows x 8 columns of tiles, the shape with the fewest
-        // distinct operand blocks.  Measured at 1728 tiles: bands of 4, 6, 8, 12 rows miss the L2 for 260, 224, 217,
-        // 239 MB per launch, all at the same speed (bands of 2 to 18 rows run within 1 % of each other).
-        constexpr int kBand = 8;
-        const int band = id / (kBand * tiles_n);
-        const int band_rows = (tiles_m - band * kBand) < kBand ? (tiles_m - band * kBand) : kBand;
-        const int in = id - band * kBand * tiles_n;
-        tile_m = band * kBand + in % band_rows;
-        tile_n = in / band_rows;
-    }
+    gemm_tile_of(bid, tiles_m, tiles_n, tile_m, tile_n);
     const int gm0 = tile_m * T::kBM, gn0 = tile_n * T::kBN;      // the launch checks that every tile lies inside the padded rows and columns
     if (MODE == 1) {   // window export: only tiles that touch the window do any work (uniform per workgroup)
         if (gm0 >= p.m1 || gm0 + T::kBM <= p.m0 || gn0 >= p.n1 || gn0 + T::kBN <= p.n0) return;
@@ -217,50 +200,12 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
 
     // ---- low-rank up projection: the accumulators START as H L2 (bf16 MFMAs, H as exact hi + lo parts) -----------
     if (MODE == 0 && p.rank > 0 && split == 0) {      // one split carries the low-rank product
-        const int ksteps = p.rank / 16;
-        const unsigned char *hf = p.hfrag + (size_t)(gm0 / 32) * ksteps * 2048 + lane * 16;
-        struct LowRank { uint4 hhi[RB], hlo[RB], braw[2]; };
         floatx16 lr[RB][2];
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
             for (int c = 0; c < 2; ++c) lr[r][c] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        auto load_step = [&](LowRank &o, int ks) {
-#pragma unroll
-            for (int r = 0; r < RB; ++r) {
-                const unsigned char *hp = hf + ((size_t)r * ksteps + ks) * 2048;
-                o.hhi[r] = *reinterpret_cast<const uint4 *>(hp);
-                o.hlo[r] = *reinterpret_cast<const uint4 *>(hp + 1024);
-            }
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int col = gn0 + wn0 + c * 32 + li;        // < Npad
-                o.braw[c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
-            }
-        };
-        auto multiply = [&](const LowRank &o) {
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const bf16x8 bl = __builtin_bit_cast(bf16x8, o.braw[c]);
-#pragma unroll
-                for (int r = 0; r < RB; ++r) {
-                    lr[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hhi[r]), bl, lr[r][c], 0, 0, 0);
-                    lr[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hlo[r]), bl, lr[r][c], 0, 0, 0);
-                }
-            }
-        };
-        LowRank e, o;
-        load_step(e, 0);
-        for (int ks = 0; ks < ksteps; ks += 2) {
-            if (ks + 1 < ksteps) load_step(o, ks + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(e);
-            if (ks + 1 < ksteps) {
-                if (ks + 2 < ksteps) load_step(e, ks + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply(o);
-            }
-        }
+        gemm_lowrank_product<RB, 2>(lr, p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane * 16, p.l2t, p.rank, gn0 + wn0, lane);
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
@@ -512,41 +457,9 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
 
     // ---- epilogue: bias, bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores --------
     unsigned char *ob = lds + wave * (32 * kOutRowW4);
-    const float bias0 = p.bias[gn0 + wn0 + li], bias1 = p.bias[gn0 + wn0 + 32 + li];      // padded to Npad
+    const float bias[2] = {p.bias[gn0 + wn0 + li], p.bias[gn0 + wn0 + 32 + li]};      // padded to Npad
     const bool full = gm0 + T::kBM <= p.M && gn0 + T::kBN <= p.N && (p.N % 8) == 0;
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const float b = c ? bias1 : bias0;
-#pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                const int row = 8 * (v >> 2) + 4 * lh + (v & 3);      // accumulator register v: row 8 (v / 4) + 4 (lane / 32) + v % 4
-                const uint32_t pr = bf16_pair_w4(acc[r][c][v] + b, acc[r][c][v + 1] + b);
-                *reinterpret_cast<uint16_t *>(ob + row * kOutRowW4 + (c * 32 + li) * 2) = (uint16_t)pr;
-                *reinterpret_cast<uint16_t *>(ob + (row + 1) * kOutRowW4 + (c * 32 + li) * 2) = (uint16_t)(pr >> 16);
-            }
-        }
-        // 32 rows x 128 bytes = 256 chunks of 16 bytes: four per lane, eight lanes per row
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int q = lane + 64 * i;
-            const int row = q >> 3, ch = q & 7;
-            const uint4 v = *reinterpret_cast<const uint4 *>(ob + row * kOutRowW4 + ch * 16);
-            const int grow = gm0 + r * 32 + row;
-            const int gcol = gn0 + wn0 + ch * 8;
-            uint16_t *dst = p.Y + (size_t)grow * p.N + gcol;
-            if (full) {
-                *reinterpret_cast<uint4 *>(dst) = v;
-            } else if (grow < p.M) {
-                const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
-                                       (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (gcol + k < p.N) dst[k] = e[k];
-            }
-        }
-    }
+    gemm_store_wave_tile<RB, 2>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm0, gn0 + wn0, full, lane);
 }
 
 template <int RB>

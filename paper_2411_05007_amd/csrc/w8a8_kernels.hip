@@ -14,6 +14,7 @@
 #include <stdint.h>
 
 #include "buffer.h"
+#include "gemm_common.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -46,13 +47,6 @@ struct W8Tile {
 };
 typedef __attribute__((address_space(3))) void *lds_ptr;
 constexpr int kI8RowBytes = 32;      // bytes of one row of one 32-channel step
-__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
-    bf16x2 v;
-    v[0] = (__bf16)lo;
-    v[1] = (__bf16)hi;
-    return __builtin_bit_cast(uint32_t, v);
-}
-
 // canonical views of the workspace for parity checks
 __global__ void debug_act_w8_kernel(DebugActW8Params p) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -84,17 +78,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
     const int total = tiles_m * tiles_n;
     const int g_begin = 0, g_end = p.K / 32;      // steps of 32 channels
     int tile_m, tile_n;
-    {
-        const int bid = (int)blockIdx.x;
-        const int per = (total + 7) / 8;
-        const int id = (total % 8 == 0) ? (bid % 8) * per + (bid / 8) : bid;      // a bijection only when 8 divides the count
-        constexpr int kBand = 8;
-        const int band = id / (kBand * tiles_n);
-        const int band_rows = (tiles_m - band * kBand) < kBand ? (tiles_m - band * kBand) : kBand;
-        const int in = id - band * kBand * tiles_n;
-        tile_m = band * kBand + in % band_rows;
-        tile_n = in / band_rows;
-    }
+    gemm_tile_of((int)blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
     const int gm0 = tile_m * kBM, gn0 = tile_n * kBN;      // the launch checks that every tile lies inside the padded rows and columns
 
     intx16 iacc[kRB][kCB];
@@ -211,45 +195,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
     // The operands of rank step ks + 1 are requested before step ks is multiplied, so the branch pays one memory
     // round trip (shared with the first operand blocks of the main loop), not one per 16 columns of H.
     if (p.rank > 0) {
-        const int ksteps = p.rank / 16;
-        const unsigned char *hf = p.hfrag + (size_t)((gm0 + wm0) / 32) * ksteps * 2048 + lane * 16;
-        struct LowRank { uint4 hhi[kRB], hlo[kRB], braw[kCB]; };
-        auto load_step = [&](LowRank &o, int ks) {
-#pragma unroll
-            for (int r = 0; r < kRB; ++r) {
-                const unsigned char *hp = hf + ((size_t)r * ksteps + ks) * 2048;
-                o.hhi[r] = *reinterpret_cast<const uint4 *>(hp);
-                o.hlo[r] = *reinterpret_cast<const uint4 *>(hp + 1024);
-            }
-#pragma unroll
-            for (int c = 0; c < kCB; ++c) {
-                const int col = gn0 + wn0 + c * 32 + li;        // < Npad
-                o.braw[c] = *reinterpret_cast<const uint4 *>(p.l2t + (size_t)col * p.rank + ks * 16 + 8 * lh);
-            }
-        };
-        auto multiply = [&](const LowRank &o) {
-#pragma unroll
-            for (int c = 0; c < kCB; ++c) {
-                const bf16x8 bl = __builtin_bit_cast(bf16x8, o.braw[c]);
-#pragma unroll
-                for (int r = 0; r < kRB; ++r) {
-                    acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hhi[r]), bl, acc[r][c], 0, 0, 0);
-                    acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.hlo[r]), bl, acc[r][c], 0, 0, 0);
-                }
-            }
-        };
-        LowRank e, o;
-        load_step(e, 0);
-        for (int ks = 0; ks < ksteps; ks += 2) {
-            if (ks + 1 < ksteps) load_step(o, ks + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(e);
-            if (ks + 1 < ksteps) {
-                if (ks + 2 < ksteps) load_step(e, ks + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply(o);
-            }
-        }
+        gemm_lowrank_product<kRB, kCB>(acc, p.hfrag + (size_t)((gm0 + wm0) / 32) * (p.rank / 16) * 2048 + lane * 16, p.l2t, p.rank, gn0 + wn0, lane);
     }
 
     // ---- epilogue: bias, bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores --------
@@ -258,38 +204,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
 #pragma unroll
     for (int c = 0; c < kCB; ++c) bias[c] = p.bias[gn0 + wn0 + c * 32 + li];      // padded to Npad
     const bool full = gm0 + kBM <= p.M && gn0 + kBN <= p.N && (p.N % 8) == 0;
-#pragma unroll
-    for (int r = 0; r < kRB; ++r) {
-#pragma unroll
-        for (int c = 0; c < kCB; ++c) {
-#pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                const int row = 8 * (v >> 2) + 4 * lh + (v & 3);      // accumulator register v: row 8 (v / 4) + 4 (lane / 32) + v % 4
-                const uint32_t pr = bf16_pair(acc[r][c][v] + bias[c], acc[r][c][v + 1] + bias[c]);
-                *reinterpret_cast<uint16_t *>(ob + row * kOutRowW8 + (c * 32 + li) * 2) = (uint16_t)pr;
-                *reinterpret_cast<uint16_t *>(ob + (row + 1) * kOutRowW8 + (c * 32 + li) * 2) = (uint16_t)(pr >> 16);
-            }
-        }
-        // 32 rows of kWN bf16 = 32 * kWN / 8 chunks of 16 bytes: kWN / 16 per lane, kWN / 8 lanes per row
-#pragma unroll
-        for (int i = 0; i < kWN / 16; ++i) {
-            const int q = lane + 64 * i;
-            const int row = q / (kWN / 8), ch = q % (kWN / 8);
-            const uint4 v = *reinterpret_cast<const uint4 *>(ob + row * kOutRowW8 + ch * 16);
-            const int grow = gm0 + wm0 + r * 32 + row;
-            const int gcol = gn0 + wn0 + ch * 8;
-            uint16_t *dst = p.Y + (size_t)grow * p.N + gcol;
-            if (full) {
-                *reinterpret_cast<uint4 *>(dst) = v;
-            } else if (grow < p.M) {
-                const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
-                                       (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (gcol + k < p.N) dst[k] = e[k];
-            }
-        }
-    }
+    gemm_store_wave_tile<kRB, kCB>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm0 + wm0, gn0 + wn0, full, lane);
 }
 
 }  // namespace
