@@ -82,8 +82,16 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     const int row = lane & 15, blk = lane >> 4;      // MFMA operand / accumulator map
     const int r8 = lane >> 3, c8 = lane & 7;         // load map: tokens r8 and r8 + 8, channels 8*c8 .. +7
     // workgroups of one slice are neighbours in the launch order: they read neighbouring stretches of the same rows
-    const int nchunks = p.chunks > 1 ? p.chunks : 1;
-    const int slice = blockIdx.x / nchunks, chunk = blockIdx.x - slice * nchunks;
+    // the first p.whole slices are cut into p.chunks0 runs of p.gchunk0 groups (or walked whole), all later slices into
+    // p.chunks runs of p.gchunk groups
+    const int cA = p.chunks0 > 1 ? p.chunks0 : 1, cB = p.chunks > 1 ? p.chunks : 1;
+    const int nA = p.whole * cA;
+    const bool later = (int)blockIdx.x >= nA;
+    const int nchunks = later ? cB : cA;
+    const int gchunk = later ? p.gchunk : p.gchunk0;
+    const int first = later ? p.whole : 0;                 // first slice of this part of the launch
+    const int rel = (int)blockIdx.x - (later ? nA : 0);
+    const int slice = first + rel / nchunks, chunk = rel % nchunks;
     const int m0 = slice * 16;
     const int ma = m0 + r8, mb = ma + 8;
     const int rb = p.rank / 16;
@@ -96,8 +104,8 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     // last group once more (it recomputes and rewrites the same codes and is kept out of the projection), so
     // the loop body has no divergent or data-dependent control flow around its memory operations and the
     // load/store counters can be waited on precisely
-    const int gbeg = nchunks > 1 ? chunk * p.gchunk : 0;                      // this workgroup's run of groups
-    const int gend = nchunks > 1 && gbeg + p.gchunk < p.G ? gbeg + p.gchunk : p.G;
+    const int gbeg = nchunks > 1 ? chunk * gchunk : 0;                      // this workgroup's run of groups
+    const int gend = nchunks > 1 && gbeg + gchunk < p.G ? gbeg + gchunk : p.G;
     const int per = (gend - gbeg + WAVES - 1) / WAVES;
     const int g0 = gbeg + wave * per, g1 = (g0 + per < gend) ? g0 + per : gend;
     const int npairs = g0 < g1 ? (g1 - g0 + 1) / 2 : 0;
@@ -169,7 +177,7 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
     // operands of its first two groups; the factors are the older loads, so dropping them into LDS (where
     // they cost no registers) waits for them alone.
     float *lrinv = reinterpret_cast<float *>(act_lds);
-    const int glds = nchunks > 1 ? p.gchunk : p.G;      // groups whose factors the LDS holds, from gbeg on
+    const int glds = nchunks > 1 ? gchunk : p.G;      // groups whose factors the LDS holds, from gbeg on
     unsigned char *wlds = act_lds + L::rinv_bytes(QUANT ? glds : 0) + (size_t)wave * L::kWaveBytes;
     unsigned char *olds = wlds + L::kMainBytes;
     const int kr0 = 64 * g0 + 4 * lane, kr1 = kr0 + 256, kend = 64 * g1, kbeg = 64 * gbeg;
@@ -520,7 +528,12 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             // the words of all runs of its slice: the workgroup whose mark comes last finds them all set, and only a
             // workgroup that finds them all set goes on.  (Two that arrive together may both find that: both then
             // compute the same sums from the same partials.)
-            float *mine = p.hpart + ((size_t)chunk * p.Mpad + m0) * p.rank;
+            // (parked sums [run][row][rank] and arrival words [slice][run], first those of the leading slices if they are
+            // cut, then those of the later slices)
+            const int mc = m0 - 16 * first, rows_cut = later ? p.Mpad - 16 * p.whole : 16 * p.whole;
+            float *hpart = p.hpart + (later && cA > 1 ? (size_t)cA * 16 * p.whole * p.rank : 0);
+            unsigned long long *words = p.arrived + (later && cA > 1 ? (size_t)nA : 0) + (size_t)(slice - first) * nchunks;
+            float *mine = hpart + ((size_t)chunk * rows_cut + mc) * p.rank;
             for (int idx = threadIdx.x; idx < 16 * p.rank; idx += WAVES * 64) {
                 const int r = idx / p.rank, col = idx - r * p.rank;
                 float h = 0.f;
@@ -532,7 +545,6 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             __syncthreads();                                   // also: nobody reads the wavefronts' LDS blocks any more
             uint32_t *verdict = reinterpret_cast<uint32_t *>(act_lds);
             if (wave == 0) {
-                unsigned long long *words = p.arrived + (size_t)slice * nchunks;
                 if (lane == 0) (void)__hip_atomic_exchange(words + chunk, kActArrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the mark has been made before the first look
                 // lane c looks at run c (at most 64 runs), all lanes at once: one round trip
@@ -545,13 +557,13 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             // the runs' partial sums, added in run order, consecutive threads consecutive words; all loads of a batch are
             // requested before the first addition waits
             for (int idx = threadIdx.x; idx < 16 * p.rank; idx += WAVES * 64) {
-                const float *src = p.hpart + (size_t)m0 * p.rank + idx;
+                const float *src = hpart + (size_t)mc * p.rank + idx;
                 float h = 0.f;
                 for (int c0 = 0; c0 < nchunks; c0 += 8) {
                     float t[8];
 #pragma unroll
                     for (int c = 0; c < 8; ++c)
-                        t[c] = c0 + c < nchunks ? __hip_atomic_load(src + (size_t)(c0 + c) * p.Mpad * p.rank, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+                        t[c] = c0 + c < nchunks ? __hip_atomic_load(src + (size_t)(c0 + c) * rows_cut * p.rank, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
 #pragma unroll
                     for (int c = 0; c < 8; ++c) h += t[c];
                 }
@@ -588,21 +600,25 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
         }
         // the arrival words go back to "not arrived" for the next launch (every workgroup of the slice has made its mark)
         if (nchunks > 1 && (int)threadIdx.x < nchunks)
-            __hip_atomic_store(p.arrived + (size_t)slice * nchunks + threadIdx.x, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.arrived + (later && cA > 1 ? (size_t)nA : 0) + (size_t)(slice - first) * nchunks + threadIdx.x, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
 template <int RBMAX, int WAVES, bool STAGE, int FMT>
 hipError_t launch_rb(const ActParams &p, int flags, hipStream_t stream) {
     using L = ActLds<RBMAX, WAVES>;
-    const int nchunks = p.chunks > 1 ? p.chunks : 1;
+    const int nchunks = p.chunks > 1 ? p.chunks : 1, cA = p.chunks0 > 1 ? p.chunks0 : 1;
+    const int slices = (p.M + 15) / 16;
     // what the kernel's indexing assumes about a cut K: runs that cover it, no empty run, one arrival word per run and lane
-    if (nchunks > 1 && (p.gchunk < 1 || (size_t)p.gchunk * nchunks < (size_t)p.G || (nchunks - 1) * p.gchunk >= p.G || !p.hpart || !p.arrived || nchunks > 64))
-        return hipErrorInvalidValue;
-    const dim3 grid((unsigned)((p.M + 15) / 16) * nchunks), block(WAVES * 64);
+    auto runs_ok = [&](int c, int g) { return g >= 1 && (size_t)g * c >= (size_t)p.G && (c - 1) * g < p.G && c <= 64 && p.hpart && p.arrived; };
+    if (nchunks > 1 && !runs_ok(nchunks, p.gchunk)) return hipErrorInvalidValue;
+    if (p.whole < 0 || p.whole > slices || (p.whole > 0 && cA > 1 && !runs_ok(cA, p.gchunk0))) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(p.whole * cA + (slices - p.whole) * nchunks)), block(WAVES * 64);
+    const int glds_a = cA > 1 ? p.gchunk0 : p.G, glds_b = nchunks > 1 ? p.gchunk : p.G;
+    const int glds = p.whole == 0 ? glds_b : p.whole == slices ? glds_a : glds_a > glds_b ? glds_a : glds_b;
     const bool q = flags & 1, pr = (flags & 2) && p.rank > 0;
     // (the wavefronts' blocks also stage the INT4 codes on their way out and carry the per-token format's maxima)
-    size_t lds = (q ? L::rinv_bytes(nchunks > 1 ? p.gchunk : p.G) : 0) + L::wave_bytes();
+    size_t lds = (q ? L::rinv_bytes(glds) : 0) + L::wave_bytes();
     if (lds < 16) lds = 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     // the limit on dynamic LDS is raised once per instantiation, to all a CU has (the size of a launch varies with K and the rank)

@@ -107,7 +107,7 @@ int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *w
                                                      act_force > 0 ? act_force : act_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
     // the activation kernel keeps 1 / lambda of its workgroups' channels in LDS beside its per-wavefront blocks
-    if (s.K > 32768 || svdq::act_lds_bytes(w.act.gchunk, s.rank, w.act.waves) > (size_t)svdq::kLdsBytesPerCU) return SVDQ_EUNSUPPORTED;
+    if (s.K > 32768 || svdq::act_lds_bytes(w.act.whole > 0 && w.act.gchunk0 > w.act.gchunk ? w.act.gchunk0 : w.act.gchunk, s.rank, w.act.waves) > (size_t)svdq::kLdsBytesPerCU) return SVDQ_EUNSUPPORTED;
     // the kernels address X, the activation blocks and the weight blocks with 32-bit byte offsets
     if (!int4_sizes_ok(s, w.Mpad)) return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -128,6 +128,7 @@ int forward_int4(const svdq_layer_dev *L, const void *X, int M, void *Y, void *w
     a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     a.n_zero = w.n_counters;
     a.chunks = w.act.chunks; a.gchunk = w.act.gchunk; a.waves = w.act.waves;
+    a.whole = w.act.whole; a.chunks0 = w.act.chunks0; a.gchunk0 = w.act.gchunk0;
     a.hpart = reinterpret_cast<float *>(ws + w.hpart_off);
     a.arrived = reinterpret_cast<unsigned long long *>(ws + w.aflags_off);
     // tile count and K split follow the plan the workspace was sized for
@@ -280,7 +281,7 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     const svdq_shape &s = L->shape;
     const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s.K, s.N, s.rank, ksplit_override(), act_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    if (s.K > 32768 || svdq::act_lds_bytes(w.act_gchunk, s.rank, w.act_waves) > (size_t)svdq::kLdsBytesPerCU) return SVDQ_EUNSUPPORTED;
+    if (s.K > 32768 || svdq::act_lds_bytes(w.act.whole > 0 && w.act.gchunk0 > w.act.gchunk ? w.act.gchunk0 : w.act.gchunk, s.rank, w.act.waves) > (size_t)svdq::kLdsBytesPerCU) return SVDQ_EUNSUPPORTED;
     if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 32))
         return SVDQ_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -299,7 +300,8 @@ int svdq_fp4_linear_forward(const svdq_layer_dev *L, const void *X, int M, void 
     a.fmt = 1;
     a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);      // arrival counters of a split K loop start at zero
     a.n_zero = w.n_counters;
-    a.chunks = w.act_chunks; a.gchunk = w.act_gchunk; a.waves = w.act_waves;
+    a.chunks = w.act.chunks; a.gchunk = w.act.gchunk; a.waves = w.act.waves;
+    a.whole = w.act.whole; a.chunks0 = w.act.chunks0; a.gchunk0 = w.act.gchunk0;
     a.hpart = reinterpret_cast<float *>(ws + w.hpart_off);
     a.arrived = reinterpret_cast<unsigned long long *>(ws + w.aflags_off);
     hipError_t e = svdq::launch_act(a, lowrank ? 3 : 1, stream);

@@ -21,8 +21,11 @@ struct ActParams {
                              // 2: INT8 per token - codes in the int8 MFMA's operand order (layout.h, i8_code_offset)
     // K cut into runs (layout.h, ActPlan); chunks = 0: one workgroup per 16 tokens walks all of K, wavefronts chosen by the launcher
     int chunks, gchunk, waves;
-    float *hpart;                    // fp32 [chunks][Mpad][rank]: partial H of every run (chunks > 1)
-    unsigned long long *arrived;     // [Mpad / 16][chunks]: arrival words (chunks > 1)
+    int whole, chunks0, gchunk0;     // the first `whole` 16-token slices are cut differently: chunks0 runs of gchunk0 groups (chunks0 <= 1: not cut)
+    // partial H of every run of the cut slices, fp32: [chunks0][16 whole][rank] (if chunks0 > 1), then [chunks][Mpad - 16 whole][rank] (if chunks > 1)
+    float *hpart;
+    // arrival words: [whole][chunks0] (if chunks0 > 1), then [Mpad / 16 - whole][chunks] (if chunks > 1)
+    unsigned long long *arrived;
 };
 
 // flags: bit 0 = quantize (codes + scales), bit 1 = down projection (H)

@@ -175,11 +175,19 @@ inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0) {
     return pl;
 }
 
+// how the activation kernel's launch is cut up (plan_act below)
+struct ActPlan {
+    int chunks;      // runs per 16-token slice, 1..64
+    int gchunk;      // groups per run (the last run may be shorter)
+    int waves;       // wavefronts per workgroup: 4 or 8
+    // the first `whole` slices of a launch can be cut differently from the rest (or not at all): chunks0 runs of gchunk0 groups
+    int whole, chunks0, gchunk0;
+};
 struct WorkspaceFp4 {
     size_t codes_off, bx_off, h_off, hfrag_off, counters_off, partial_off, hpart_off, aflags_off, total;
     int Mpad;
     int n_counters;
-    int act_chunks, act_gchunk, act_waves;      // the activation kernel's cut of K (ActPlan below)
+    ActPlan act;      // the activation kernel's cut of K
 };
 
 
@@ -244,20 +252,18 @@ inline int act_waves(int K, int rank) { return (K / kGroup >= 32 && act_lds_byte
 // of a slice then park their partial H in the workspace and the last one to arrive adds them up in run order.  Parked
 // sums travel with device-scope accesses, past the L2, and cost more than they look: the runs are cut only as far as
 // the launch needs to reach two to three workgroups per CU.
-struct ActPlan {
-    int chunks;      // runs per 16-token slice, 1..64
-    int gchunk;      // groups per run (the last run may be shorter)
-    int waves;       // wavefronts per workgroup: 4 or 8
-};
 constexpr int kActChunkWhole = 255;      // override value: one run, all of K
 inline ActPlan plan_act(int M, int G, int rank, int gchunk_override = 0) {
     ActPlan pl;
     const int slices = (M + 15) / 16;
-    // Measured on the FLUX.1 / PixArt shapes: a launch that already has a workgroup for every other CU is best left
-    // alone up to K = 4608 and cut into runs of 48 groups beyond; a launch with fewer slices is cut into up to eight
-    // runs of at least eight groups, towards one workgroup per CU.
+    // Measured on the FLUX.1 / PixArt shapes.  A launch with more slices than CUs walks K whole, up to 192 groups (48 KB
+    // of smoothing factors in LDS, two workgroups per CU): at M = 4608, K = 12288 whole slices take 45.9 us (rank 32) and
+    // 72.8 us (rank 128), runs of 96 groups 46.4 and 75.0, runs of 48 groups 52.0 and 83.3.  A launch with a
+    // workgroup for every other CU at least is left alone up to K = 4608 and cut into runs of 48 groups beyond; a
+    // launch with fewer slices is cut into up to eight runs of at least eight groups, towards one workgroup per CU.
     int runs = 1;
-    if (slices > 128) runs = G >= 128 ? (G + 47) / 48 : 1;
+    if (slices > 256) runs = (G + 191) / 192;
+    else if (slices > 128) runs = G >= 128 ? (G + 47) / 48 : 1;
     else runs = 256 / slices < 8 ? (256 + slices - 1) / slices : 8;
     int gc = (G + runs - 1) / runs;
     if (gc < 8) gc = 8;
@@ -268,16 +274,48 @@ inline ActPlan plan_act(int M, int G, int rank, int gchunk_override = 0) {
     pl.chunks = (G + gc - 1) / gc;
     if (pl.chunks < 1) pl.chunks = 1;
     pl.gchunk = gc;
-    // eight wavefronts when a run gives each of them a few groups and their LDS fits; a whole-K launch of 257-512 slices
-    // puts two workgroups on some CUs, which then set the kernel's time: with four wavefronts each, two workgroups
-    // load a CU like one of eight does, and everybody finishes together
+    // eight wavefronts when a run gives each of them a few groups and their LDS fits - but a launch with more slices
+    // than CUs puts several workgroups on a CU anyway, and those of four wavefronts then share it better
+    // (measured at K = 3072: M = 12288 32.6 us against 34.6, M = 16384 41.7 against 44.6; at M = 4608, K = 12288:
+    // 45.9 against 49.1, rank 128 72.8 against 78.6)
     pl.waves = (gc >= 32 && act_lds_bytes(gc, rank, 8) <= (size_t)kLdsBytesPerCU) ? 8 : 4;
-    if (pl.chunks == 1 && slices > 256 && slices <= 512 && G < 64) pl.waves = 4;
+    if (slices > 256) pl.waves = 4;
+    // A launch whose workgroups are 256 q + r leaves r CUs with one workgroup more than the rest, and they set the
+    // kernel's time.  Up to r = 128 the slices those r workgroups belong to (the last ones) are cut into shorter runs
+    // instead, about 256 workgroups of them, so that every CU gets the same extra share; the other slices stay as they
+    // are and pay nothing more for parked sums
+    // (measured at K = 3072, rank 32: M = 4608 20.2 -> 16.9 us, 5120 20.5 -> 18.1, 6144 21.4 -> 19.4, 8704 30.1 -> 26.4,
+    // 16896 47.2 -> 43.8; rank 128 at M = 4608: 30.1 -> 23.0; with r > 128 a finer cut does not pay).
+    pl.whole = 0; pl.chunks0 = 1; pl.gchunk0 = G > 0 ? G : 1;
+    int twos = 1;                                        // largest power of two that divides the runs per slice (up to 256)
+    while (twos < 256 && pl.chunks % (2 * twos) == 0) twos *= 2;
+    const int tail = slices % (256 / twos);              // the slices behind the last full round of 256 workgroups
+    const int rest = tail * pl.chunks;                   // their workgroups
+    if (gchunk_override == 0 && slices > 128 && slices > tail && rest > 0 && rest <= 128 && G >= 16) {
+        int c = 256 / rest;
+        if (c > 8) c = 8;
+        int g2 = (gc + c - 1) / c;
+        if (g2 < 4) g2 = 4;
+        g2 = (g2 + 3) / 4 * 4;                           // whole groups for each of four wavefronts
+        if (g2 < gc && (G + g2 - 1) / g2 <= 64) {
+            pl.whole = slices - tail;
+            pl.chunks0 = pl.chunks; pl.gchunk0 = gc;
+            pl.gchunk = g2;
+            pl.chunks = (G + g2 - 1) / g2;
+        }
+    }
     return pl;
 }
 // the value a workgroup leaves in its arrival word; the word is cleared again before the kernel ends, so whatever a
 // fresh workspace holds is taken for "not arrived" (anything but this one 64-bit value)
 constexpr unsigned long long kActArrived = 0x5356445141525256ull;
+// what the cut slices of a launch park in the workspace: fp32 partial H of every run, and one arrival word per run
+inline size_t act_parked_floats(const ActPlan &a, int Mpad, int rank) {
+    return (a.whole > 0 && a.chunks0 > 1 ? (size_t)a.chunks0 * 16 * a.whole * rank : 0) + (a.chunks > 1 ? (size_t)a.chunks * (Mpad - 16 * a.whole) * rank : 0);
+}
+inline size_t act_arrival_words(const ActPlan &a, int Mpad) {
+    return (a.whole > 0 && a.chunks0 > 1 ? (size_t)a.chunks0 * a.whole : 0) + (a.chunks > 1 ? (size_t)a.chunks * (Mpad / 16 - a.whole) : 0);
+}
 
 // Workspace of the MXFP4 forward (WorkspaceFp4 above).
 inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank, int ksplit_override = 0, int act_override = 0) {
@@ -293,12 +331,12 @@ inline WorkspaceFp4 workspace_layout_fp4(int M, int K, int N, int rank, int kspl
     w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
     w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
     w.hpart_off = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);
-    // the activation kernel's partial H [chunks][Mpad][rank] fp32 and one arrival word per workgroup, as in the INT4 workspace
+    // the activation kernel's partial H [chunks][rows of the cut slices][rank] fp32 and one arrival word per workgroup, as in the INT4 workspace
     const ActPlan ap = plan_act(M > 0 ? M : 1, G, rank, act_override);
-    w.act_chunks = ap.chunks; w.act_gchunk = ap.gchunk; w.act_waves = ap.waves;
+    w.act = ap;
     const bool parked = ap.chunks > 1 && rank > 0;
-    w.aflags_off = w.hpart_off + (parked ? align256((size_t)ap.chunks * w.Mpad * rank * 4) : 0);
-    w.total = w.aflags_off + (parked ? align256((size_t)(w.Mpad / 16) * ap.chunks * 8) : 0);
+    w.aflags_off = w.hpart_off + (parked ? align256(act_parked_floats(ap, w.Mpad, rank) * 4) : 0);
+    w.total = w.aflags_off + (parked ? align256(act_arrival_words(ap, w.Mpad) * 8) : 0);
     return w;
 }
 
@@ -321,11 +359,11 @@ inline Workspace workspace_layout(int M, int K, int N, int rank, int ksplit_over
     w.n_counters = pl.tail;                                               // one arrival counter per split tile
     w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
     w.hpart_off = w.partial_off + align256((size_t)pl.ksplit * pl.tail * pl.bm * pl.bn * 4);
-    // the activation kernel's partial H [chunks][Mpad][rank] fp32 and one arrival word per workgroup
+    // the activation kernel's partial H [chunks][rows of the cut slices][rank] fp32 and one arrival word per workgroup
     w.act = plan_act(M > 0 ? M : 1, G, rank, act_override);
     const bool parked = w.act.chunks > 1 && rank > 0;
-    w.aflags_off = w.hpart_off + (parked ? align256((size_t)w.act.chunks * w.Mpad * rank * 4) : 0);
-    w.total = w.aflags_off + (parked ? align256((size_t)(w.Mpad / 16) * w.act.chunks * 8) : 0);
+    w.aflags_off = w.hpart_off + (parked ? align256(act_parked_floats(w.act, w.Mpad, rank) * 4) : 0);
+    w.total = w.aflags_off + (parked ? align256(act_arrival_words(w.act, w.Mpad) * 8) : 0);
     return w;
 }
 

@@ -106,6 +106,17 @@ def test_ragged_shapes(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"fp4 ragged {M}x{K}x{N} r{r}")
 
 
+@pytest.mark.parametrize("M,K,N,r", [(4136, 1024, 80, 32), (4400, 1280, 64, 64)])
+def test_activation_launch_with_whole_and_cut_slices(torch, M, K, N, r):
+    """Launches of 256 q + r slices (r <= 128): the last r slices are cut into runs with parked partial H, the others
+    walked whole, in one launch; every row, the ragged last slice included."""
+    rng = np.random.default_rng(2900 + M + K)
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    prep = S.svdq_fp4_prepare(w, ax, r, bias=b)
+    _say(f"fp4 whole and cut slices: M={M} K={K} N={N} r={r}")
+    _run_and_compare(torch, xb, prep, what=f"fp4 whole+cut {M}x{K}x{N} r{r}")
+
+
 @pytest.mark.parametrize("M,K,N,r", [(100, 6144, 272, 32), (70, 6208, 144, 16), (200, 12288, 400, 48), (130, 4160, 528, 0)])
 def test_small_launches_with_split_k_loop(torch, M, K, N, r):
     """Few tiles and a long K: the K loop is split over several workgroups per tile (each a multiple of four steps),

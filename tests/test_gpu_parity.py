@@ -199,6 +199,25 @@ def test_lora_appended_without_requantization(torch, r, r_add):
     assert np.linalg.norm((y1 - y0) - delta) <= 2e-2 * np.linalg.norm(delta) + 2.0 ** -7 * np.linalg.norm(y1)
 
 
+@pytest.mark.parametrize("M,K,N,r", [(4136, 1024, 80, 32), (4230, 1152, 128, 128), (4500, 2048, 64, 16), (8300, 1024, 32, 32),
+                                     (4200, 8192, 32, 32), (2100, 12288, 64, 64)])
+def test_activation_launch_with_whole_and_cut_slices(torch, M, K, N, r):
+    """Launches of 256 q + r workgroups (r <= 128): the slices of the first 256 q are walked whole (K = 8192, 12288: in
+    runs of 48 groups), those of the last r are cut into shorter runs; the partial H of a slice's runs meet in the
+    workspace.  Every row of the codes, the scales, H and Y, the ragged last slice included."""
+    rng = np.random.default_rng(7000 + M + K + r)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, max(1, K // 100), replace=False)] *= 50
+    x[M - 2, 64:128] = 0.0
+    xb = O.bf16_round(x)
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    ax = np.abs(O.bf16_to_f32(xb)).max(axis=0)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    prep = S.svdq_prepare(w, ax, r, bias=b)
+    _say(f"whole and cut slices: M={M} K={K} N={N} r={r}")
+    _run_and_compare(torch, xb, prep, what=f"whole+cut {M}x{K}x{N} r{r}", window=False)
+
+
 @pytest.mark.parametrize("M,K,N,r", [(100, 3072, 272, 32), (70, 3136, 144, 16), (200, 6144, 400, 48)])
 def test_small_launches_with_split_k_loop(torch, M, K, N, r):
     """Few tiles and a long K: the library splits the K loop over several workgroups per tile, which park fp32

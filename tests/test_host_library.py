@@ -167,11 +167,14 @@ def test_shape_errors_and_workspace_size(lib):
     ws = S.svdq_workspace_bytes(4608, sh)
     # activation blocks (1792 bytes per group and 32 tokens: 6-bit codes and fp16 scales) + H 4*M*r as fp32 and again
     # as bf16 hi/lo operand fragments, all with M padded to 256 (4608 is a multiple already)
-    assert ws == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32
+    # and, for the activation kernel's cut slices (288 slices = 256 whole + 32 cut into 6 runs of 8 groups): their partial H
+    # per run as fp32 and one 8-byte arrival word per run
+    act_cut = 6 * (32 * 16) * 32 * 4 + 32 * 6 * 8
+    assert ws == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32 + act_cut
     # a forced K split of a large launch applies to the tiles of its last, partly filled round of workgroups (1728 tiles
     # on 512 places: 192 tiles): an arrival counter and the fp32 partial tiles for each of those
     lib.svdq_forward_options(2 << 8)
-    assert S.svdq_workspace_bytes(4608, sh) == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32 + 192 * 4 + 2 * 192 * 128 * 256 * 4
+    assert S.svdq_workspace_bytes(4608, sh) == 48 * (4608 // 32) * 1792 + 2 * 4 * 4608 * 32 + 192 * 4 + 2 * 192 * 128 * 256 * 4 + act_cut
     lib.svdq_forward_options(0)
     # a one-token forward runs one row of 48 tiles of 128 x 256 with the K loop split four ways: one arrival counter
     # per tile (padded to 256 bytes) and four fp32 partial tiles per tile come on top; and its activation kernel cuts K
