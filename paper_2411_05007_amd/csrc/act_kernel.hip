@@ -682,11 +682,11 @@ __global__ void debug_act_fp4_kernel(DebugActFp4Params p) {
 template <int FMT>
 hipError_t launch_act_fmt(const ActParams &p, int flags, hipStream_t stream) {
     // wavefronts per 16-token slice: more of them when K is long enough to give each a few groups.  Exception: a
-    // launch of 257-512 workgroups puts two of them on some CUs, which then set the kernel's time; with four
-    // wavefronts each, two workgroups load a CU like one of eight does, and everybody finishes together
-    // (measured at M = 4608, K = 3072: 1.3 us of ~23 faster; with up to 256 workgroups eight wavefronts are faster).
+    // launch with more slices than CUs puts several workgroups on a CU anyway, and those of four wavefronts share it
+    // better (measured for the per-token INT8 format at M = 4608: K = 3072 27.8 us against 29.8, K = 12288 91.9 against 99.2;
+    // with up to 256 workgroups eight wavefronts are faster).  A planned launch (chunks >= 1) brings its own choice.
     const int slabs = (p.M + 15) / 16;
-    const bool wide = p.chunks >= 1 ? p.waves == 8 : act_waves(p.K, p.rank) == 8 && !(slabs > 256 && slabs <= 512 && p.G < 64);
+    const bool wide = p.chunks >= 1 ? p.waves == 8 : act_waves(p.K, p.rank) == 8 && slabs <= 256;
     if (p.rank <= 32) return wide ? launch_rb<2, 8, true, FMT>(p, flags, stream) : launch_rb<2, 4, true, FMT>(p, flags, stream);
     if (p.rank <= 64) return wide ? launch_rb<4, 8, false, FMT>(p, flags, stream) : launch_rb<4, 4, false, FMT>(p, flags, stream);
     if (p.rank <= 128) {
