@@ -221,6 +221,21 @@ int svdq_debug_group_acc(const svdq_layer_dev *layer, const void *workspace, int
                          int m0, int m1, int n0, int n1, int32_t *out, void *hip_stream);
 
 /*
+ * Host only, touches no GPU: how a forward of M tokens through a layer of this shape (group 64: INT4, group 32: MXFP4)
+ * would be launched under the calling thread's options - the numbers the kernels' indexing relies on, for tests that
+ * check them over many shapes without a GPU.  out receives 16 values:
+ *   [0] runs per 16-token slice of the activation kernel, [1] groups of 64 channels per run, [2] wavefronts per
+ *   workgroup, [3] how many leading slices are cut differently, into [4] runs of [5] groups (runs <= 1: walked whole),
+ *   [6] workgroups of the activation kernel, [7] its LDS bytes per workgroup,
+ *   [8] output tiles of the GEMM, [9] how many of them have their K loop split, [10] into how many workgroups,
+ *   [11] workgroups of the GEMM,
+ *   [12] bytes / 256 of the workspace behind the GEMM's partial tiles (parked partial H and arrival words),
+ *   [13] bytes / 256 (rounded up) of the parked partial H, [14] arrival words, [15] bytes / 256 of the whole workspace.
+ * SVDQ_EINVAL for a null pointer or M <= 0, SVDQ_EUNSUPPORTED for a shape the forwards refuse outright.
+ */
+int svdq_debug_launch_plan(const svdq_shape *shape, int M, int32_t *out);
+
+/*
  * Measurement switches of the CALLING THREAD, read by the forwards and the workspace-size queries that this thread
  * makes (Sec. 4.3 / Fig. 6a, App. "Latency Results": naive INT4 and the unfused four-kernel pipeline).  Other
  * threads are not affected.  Returns the thread's previous flags; pass a negative value to query only.

@@ -207,6 +207,40 @@ int svdq_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, 
     return forward_int4(L, X, M, Y, workspace, workspace_bytes, hip_stream, 0, 0);
 }
 
+int svdq_debug_launch_plan(const svdq_shape *s, int M, int32_t *out) {
+    if (!s || !out || M <= 0) return SVDQ_EINVAL;
+    if (s->K <= 0 || s->N <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return SVDQ_EUNSUPPORTED;
+    const int G = s->K / svdq::kGroup;
+    svdq::ActPlan a;
+    size_t parked_bytes = 0, total = 0;
+    if (s->group == svdq::kFp4Block) {
+        const svdq::WorkspaceFp4 w = svdq::workspace_layout_fp4(M, s->K, s->N, s->rank, ksplit_override(), act_override());
+        const svdq::GemmPlanFp4 pl = svdq::plan_gemm_fp4(M, s->N, G, ksplit_override());
+        a = w.act;
+        out[8] = pl.tiles; out[9] = pl.ksplit > 1 ? pl.tiles : 0; out[10] = pl.ksplit; out[11] = pl.tiles * pl.ksplit;
+        parked_bytes = w.total - w.hpart_off; total = w.total;
+    } else if (s->group == svdq::kGroup) {
+        const svdq::Workspace w = svdq::workspace_layout(M, s->K, s->N, s->rank, ksplit_override(), act_override());
+        const svdq::GemmPlan pl = svdq::plan_gemm(M, s->N, G, ksplit_override());
+        a = w.act;
+        out[8] = pl.tiles; out[9] = pl.tail; out[10] = pl.ksplit; out[11] = pl.tiles - pl.tail + pl.tail * pl.ksplit;
+        parked_bytes = w.total - w.hpart_off; total = w.total;
+    } else {
+        return SVDQ_EUNSUPPORTED;
+    }
+    const int slices = (M + 15) / 16;
+    const int ca = a.chunks0 > 1 ? a.chunks0 : 1, cb = a.chunks > 1 ? a.chunks : 1;
+    const int glds = a.whole > 0 && a.gchunk0 > a.gchunk ? a.gchunk0 : a.gchunk;
+    out[0] = a.chunks; out[1] = a.gchunk; out[2] = a.waves; out[3] = a.whole; out[4] = a.chunks0; out[5] = a.gchunk0;
+    out[6] = a.whole * ca + (slices - a.whole) * cb;
+    out[7] = (int32_t)svdq::act_lds_bytes(glds, s->rank, a.waves);
+    out[12] = (int32_t)(parked_bytes >> 8);
+    out[13] = (int32_t)((svdq::act_parked_floats(a, svdq::round_up(M, svdq::kRowPad), s->rank) * 4 + 255) >> 8);
+    out[14] = (int32_t)svdq::act_arrival_words(a, svdq::round_up(M, svdq::kRowPad));
+    out[15] = (int32_t)(total >> 8);
+    return SVDQ_OK;
+}
+
 int svdq_linear_forward_static(const svdq_layer_dev *L, const void *X, int M, void *Y, void *hip_stream) {
     const int st = check_layer(L);
     if (st != SVDQ_OK) return st;

@@ -30,6 +30,7 @@ EXPORTS = [
     "svdq_w8a8_workspace_bytes", "svdq_w8a8_linear_forward", "svdq_w8a8_debug_act", "svdq_w4a16_forward", "svdq_w4a16_workspace_bytes",
     "svdq_workspace_bytes", "svdq_linear_forward", "svdq_debug_act", "svdq_debug_group_acc",
     "svdq_forward_options", "svdq_profile_event", "svdq_mfma_peak_probe", "svdq_linear_forward_static",
+    "svdq_debug_launch_plan",
 ]
 
 
@@ -65,6 +66,7 @@ def lib() -> C.CDLL:
         L.svdq_status_string.argtypes = [C.c_int]
         L.svdq_workspace_bytes.restype = C.c_size_t
         L.svdq_workspace_bytes.argtypes = [C.c_int, C.POINTER(Shape)]
+        L.svdq_debug_launch_plan.argtypes = [C.POINTER(Shape), C.c_int, C.POINTER(C.c_int32)]
         L.svdq_prepared_sizes.argtypes = [C.POINTER(Shape), C.POINTER(Sizes)]
         vp = C.c_void_p
         L.svdq_prepare.argtypes = [C.POINTER(Shape)] + [vp] * 9
@@ -378,6 +380,18 @@ def svdq_mfma_peak_probe(kind: int, iters: int, sink, stream) -> float:
 
 def svdq_profile_event(event_handle: Optional[int]) -> None:
     _check(lib().svdq_profile_event(event_handle), "svdq_profile_event")
+
+
+PLAN_FIELDS = ("act_runs", "act_groups_per_run", "act_waves", "act_leading_slices", "act_leading_runs", "act_leading_groups_per_run",
+               "act_workgroups", "act_lds_bytes", "gemm_tiles", "gemm_split_tiles", "gemm_ksplit", "gemm_workgroups",
+               "parked_bytes_256", "parked_h_bytes_256", "arrival_words", "workspace_bytes_256")
+
+
+def svdq_debug_launch_plan(M: int, shape: Shape) -> dict:
+    """The launch plan of a forward of M tokens (host only): see include/svdq.h."""
+    out = (C.c_int32 * 16)()
+    _check(lib().svdq_debug_launch_plan(C.byref(shape), int(M), out), "svdq_debug_launch_plan")
+    return dict(zip(PLAN_FIELDS, (int(v) for v in out)))
 
 
 def svdq_workspace_bytes(M: int, shape: Shape) -> int:

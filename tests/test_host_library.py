@@ -495,3 +495,60 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_launch_plans_keep_what_the_kernels_index_by(lib):
+    """The activation kernel and the GEMM take their slice, run, tile and split from the workgroup index alone; this
+    checks, without a GPU, what that arithmetic relies on - runs that cover K with none empty, a grid that matches,
+    LDS within a CU's, parked results inside the workspace - over the BASELINE shapes, their neighbours and a seeded
+    sweep, for the INT4 and the MXFP4 forward, and that the plan the metric shape runs with is the documented one."""
+    rng = np.random.default_rng(77)
+    Ms = [1, 15, 16, 17, 255, 256, 257, 512, 2047, 2048, 2049, 4095, 4096, 4097, 4111, 4112, 4608, 5000, 6144, 6145, 8191, 8192, 8200, 12288, 16384, 16896, 40000]
+    Ks = [64, 128, 1024, 1152, 3072, 4608, 8192, 9216, 12288, 16384, 32768]
+    cases = [(M, K, N, r, g) for M in Ms for K in Ks for (N, r) in ((3072, 32), (256, 128)) for g in (64, 32)]
+    for _ in range(1500):
+        cases.append((int(rng.integers(1, 20000)), 64 * int(rng.integers(1, 300)), 16 * int(rng.integers(1, 800)), 16 * int(rng.integers(0, 17)), int(rng.choice([64, 32]))))
+    seen_cut = seen_two = 0
+    for (M, K, N, r, g) in cases:
+        if r > min(K, N) or M * K >= 2 ** 31:
+            continue
+        p = S.svdq_debug_launch_plan(M, S.make_shape(K, N, r, group=g))
+        G, slices, what = K // 64, (M + 15) // 16, (M, K, N, r, g)
+        for runs, per in ((p["act_runs"], p["act_groups_per_run"]), (p["act_leading_runs"], p["act_leading_groups_per_run"])):
+            assert 1 <= runs <= 64, what
+            if runs > 1:
+                assert (runs - 1) * per < G <= runs * per and per >= 1, what
+        assert p["act_waves"] in (4, 8) and 0 <= p["act_leading_slices"] <= slices, what
+        ca, cb = max(p["act_leading_runs"], 1), max(p["act_runs"], 1)
+        assert p["act_workgroups"] == p["act_leading_slices"] * ca + (slices - p["act_leading_slices"]) * cb, what
+        if p["act_leading_slices"] > 0:
+            seen_cut += 1
+            seen_two += ca > 1
+            assert cb > 1 and (slices - p["act_leading_slices"]) * cb <= 256, what      # the cut tail fills one round at most
+        if K <= 24512:
+            assert p["act_lds_bytes"] <= 160 * 1024, what
+        # parked partial H and arrival words lie inside the workspace, behind everything else
+        Mpad = (M + 255) // 256 * 256
+        if r > 0 and (ca > 1 and p["act_leading_slices"] > 0 or cb > 1):
+            want = (ca * 16 * p["act_leading_slices"] * r if ca > 1 and p["act_leading_slices"] > 0 else 0) + (cb * (Mpad - 16 * p["act_leading_slices"]) * r if cb > 1 else 0)
+            assert p["parked_h_bytes_256"] == (want * 4 + 255) // 256, what
+            assert p["parked_bytes_256"] >= p["parked_h_bytes_256"] + (p["arrival_words"] * 8) // 256, what
+        assert p["workspace_bytes_256"] * 256 == S.svdq_workspace_bytes(M, S.make_shape(K, N, r, group=g)), what
+        # GEMM: no empty split, a workgroup per tile and split
+        assert p["gemm_ksplit"] >= 1 and 0 <= p["gemm_split_tiles"] <= p["gemm_tiles"], what
+        assert (p["gemm_ksplit"] > 1) == (p["gemm_split_tiles"] > 0), what
+        per = -(-G // p["gemm_ksplit"])
+        if g == 32 and p["gemm_ksplit"] > 1:
+            per = (per + 3) // 4 * 4
+        assert (p["gemm_ksplit"] - 1) * per < G, what
+        assert p["gemm_workgroups"] == p["gemm_tiles"] - p["gemm_split_tiles"] + p["gemm_split_tiles"] * p["gemm_ksplit"], what
+    assert seen_cut > 50 and seen_two > 5
+    # the metric shape: 256 slices whole, the last 32 in six runs of eight groups, four wavefronts; 1728 whole tiles
+    p = S.svdq_debug_launch_plan(4608, S.make_shape(3072, 12288, 32))
+    assert (p["act_leading_slices"], p["act_leading_runs"], p["act_runs"], p["act_groups_per_run"], p["act_waves"], p["act_workgroups"]) == (256, 1, 6, 8, 4, 448)
+    assert (p["gemm_tiles"], p["gemm_ksplit"], p["gemm_workgroups"]) == (1728, 1, 1728)
+    # the FLUX MLP down layer: K = 12288 walked whole, the last 32 slices in eight runs of 24 groups
+    p = S.svdq_debug_launch_plan(4608, S.make_shape(12288, 3072, 32))
+    assert (p["act_leading_slices"], p["act_leading_runs"], p["act_runs"], p["act_groups_per_run"], p["act_waves"]) == (256, 1, 8, 24, 4)
+    assert lib.svdq_debug_launch_plan(None, 1, None) == -1
+    assert lib.svdq_debug_launch_plan(C.byref(S.make_shape(100, 64, 16)), 5, (C.c_int32 * 16)()) == -2
