@@ -33,7 +33,7 @@ __device__ __forceinline__ void gemm_tile_of(int bid, int tiles_m, int tiles_n, 
 // 64 CB + 16 bytes) so that every store instruction writes whole 128-byte lines.
 //   acc_at(r, c, v): the accumulator;  bias[c]: the lane's bias of column block c;  (row0, col0): the wavefront's first
 //   output element;  full: the whole tile lies inside M x N and N % 8 == 0 (16-byte stores), else element-wise.
-template <int RB, int CB, typename AccAt>
+template <int RB, int CB, bool ADD_BIAS = true, typename AccAt>
 __device__ __forceinline__ void gemm_store_wave_tile(AccAt acc_at, const float (&bias)[CB], unsigned char *ob, uint16_t *Y, int M, int N,
                                                      int row0, int col0, bool full, int lane) {
     constexpr int kWN = 32 * CB, kOutRow = kWN * 2 + 16;
@@ -45,7 +45,8 @@ __device__ __forceinline__ void gemm_store_wave_tile(AccAt acc_at, const float (
 #pragma unroll
             for (int v = 0; v < 16; v += 2) {
                 const int row = 8 * (v >> 2) + 4 * lh + (v & 3);
-                const uint32_t pr = bf16_rne_pair(acc_at(r, c, v) + bias[c], acc_at(r, c, v + 1) + bias[c]);
+                const uint32_t pr = ADD_BIAS ? bf16_rne_pair(acc_at(r, c, v) + bias[c], acc_at(r, c, v + 1) + bias[c])
+                                             : bf16_rne_pair(acc_at(r, c, v), acc_at(r, c, v + 1));
                 *reinterpret_cast<uint16_t *>(ob + row * kOutRow + (c * 32 + li) * 2) = (uint16_t)pr;
                 *reinterpret_cast<uint16_t *>(ob + (row + 1) * kOutRow + (c * 32 + li) * 2) = (uint16_t)(pr >> 16);
             }

@@ -90,13 +90,17 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     gemm_tile_of((int)blockIdx.x - split * total, tiles_m, tiles_n, tile_m, tile_n);
     const int gm0 = tile_m * kBM, gn0 = tile_n * kBN;      // the launch checks that every tile lies inside the padded rows and columns
 
+    // the accumulators start as the bias (in the split that also carries the low-rank product): loaded here, it shares
+    // the round trip of the first operands; at the end of the tile its load would stand alone before the stores
     floatx16 acc[kRB][kCB];
 #pragma unroll
-    for (int r = 0; r < kRB; ++r)
+    for (int c = 0; c < kCB; ++c) {
+        const float b = split == 0 ? p.bias[gn0 + wn0 + c * 32 + li] : 0.f;      // padded to Npad
 #pragma unroll
-        for (int c = 0; c < kCB; ++c)
+        for (int r = 0; r < kRB; ++r)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[r][c][v] = b;
+    }
 
     const __amdgpu_buffer_rsrc_t rs_sa = make_rsrc(p.bx, fp4_scale_bytes(p.G, p.Mpad));
     const __amdgpu_buffer_rsrc_t rs_sb = make_rsrc(p.bw, fp4_scale_bytes(p.G, p.Npad));
@@ -257,13 +261,11 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
         }
     }
 
-    // ---- epilogue: bias, bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores --------
+    // ---- epilogue: bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores ----------------
     unsigned char *ob = lds + wave * (32 * kOutRowFp4);
-    float bias[kCB];
-#pragma unroll
-    for (int c = 0; c < kCB; ++c) bias[c] = p.bias[gn0 + wn0 + c * 32 + li];      // padded to Npad
+    const float bias[kCB] = {};      // already in the accumulators
     const bool full = gm0 + kBM <= p.M && gn0 + kBN <= p.N && (p.N % 8) == 0;
-    gemm_store_wave_tile<kRB, kCB>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm0 + wm0, gn0 + wn0, full, lane);
+    gemm_store_wave_tile<kRB, kCB, false>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm0 + wm0, gn0 + wn0, full, lane);
 }
 
 template <int RB, int CB>

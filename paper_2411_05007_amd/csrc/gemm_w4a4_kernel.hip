@@ -198,14 +198,21 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     for (int i = 0; i < T::kStages - 1; ++i) dma(g_begin + i, i);
     __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
 
-    // ---- low-rank up projection: the accumulators START as H L2 (bf16 MFMAs, H as exact hi + lo parts) -----------
-    if (MODE == 0 && p.rank > 0 && split == 0) {      // one split carries the low-rank product
+    // ---- bias and low-rank up projection: the accumulators START as bias + H L2 (the bias is the C operand of the
+    // first bf16 MFMAs; H as exact hi + lo parts).  Loaded here, the bias shares the round trip of the first operands; at
+    // the end of the tile its load would stand alone between the last group and the stores (1.4 % of the launch).
+    if (MODE == 0 && split == 0) {      // one split carries the bias and the low-rank product
+        const float b0 = p.bias[gn0 + wn0 + li], b1 = p.bias[gn0 + wn0 + 32 + li];      // padded to Npad
         floatx16 lr[RB][2];
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) lr[r][c] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        gemm_lowrank_product<RB, 2>(lr, p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane * 16, p.l2t, p.rank, gn0 + wn0, lane);
+            for (int c = 0; c < 2; ++c) {
+                const float b = c ? b1 : b0;
+                lr[r][c] = floatx16{b, b, b, b, b, b, b, b, b, b, b, b, b, b, b, b};
+            }
+        if (p.rank > 0)
+            gemm_lowrank_product<RB, 2>(lr, p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane * 16, p.l2t, p.rank, gn0 + wn0, lane);
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
@@ -455,11 +462,11 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
         }
     }
 
-    // ---- epilogue: bias, bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores --------
+    // ---- epilogue: bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores ----------------
     unsigned char *ob = lds + wave * (32 * kOutRowW4);
-    const float bias[2] = {p.bias[gn0 + wn0 + li], p.bias[gn0 + wn0 + 32 + li]};      // padded to Npad
     const bool full = gm0 + T::kBM <= p.M && gn0 + T::kBN <= p.N && (p.N % 8) == 0;
-    gemm_store_wave_tile<RB, 2>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm0, gn0 + wn0, full, lane);
+    const float bias[2] = {0.f, 0.f};
+    gemm_store_wave_tile<RB, 2, false>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm0, gn0 + wn0, full, lane);
 }
 
 template <int RB>
