@@ -67,6 +67,7 @@ struct W4Tile {
     static constexpr int kRing = kStages * kStage;
     static constexpr int kOutBytes = 4 * 32 * kOutRowW4;
     static constexpr int kLdsBytes = kRing > kOutBytes ? kRing : kOutBytes;
+    static constexpr int kLdsBytesPersistent = kRing + kOutBytes;      // the staging area beside the ring: the next tile's first groups arrive during the stores
     static constexpr int kDmaPerStep = 4;                         // direct-to-LDS instructions per wavefront and group           // direct-to-LDS instructions per wavefront and group
     static_assert(kStage % 256 == 0 && kW4ABlock % 256 == 0 && kW4ACodes % 256 == 0, "scale reads address in units of 256 bytes");
 };
@@ -74,7 +75,11 @@ struct W4Tile {
 __device__ __forceinline__ uint32_t bf16_bits_w4(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
 // MODE 0: normal forward.  MODE 1: additionally export the exact group sums of a window (parity checks).
-template <int RB, int MODE>
+// PERSIST: a launch of whole tiles with more tiles than the chip has places for workgroups runs as one workgroup per
+// place, which takes tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the order in which the hardware would have dealt
+// them out): a tile's first two groups are requested before the stores of the tile before it, so that from the second
+// tile on nothing waits for a kernel start, a tile decode or a first round trip to memory.
+template <int RB, int MODE, bool PERSIST>
 __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     using T = W4Tile<RB>;
     static_assert(RB == 4, "the slot schedule below is written for four row blocks");
@@ -102,9 +107,12 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     const int g_per = (p.G + nsplit - 1) / nsplit;
     const int g_begin = split * g_per;
     const int g_end = g_begin + g_per < p.G ? g_begin + g_per : p.G;
-    int tile_m, tile_n;
-    gemm_tile_of(bid, tiles_m, tiles_n, tile_m, tile_n);
-    const int gm0 = tile_m * T::kBM, gn0 = tile_n * T::kBN;      // the launch checks that every tile lies inside the padded rows and columns
+    int gm0, gn0;      // the launch checks that every tile lies inside the padded rows and columns
+    {
+        int tile_m, tile_n;
+        gemm_tile_of(bid, tiles_m, tiles_n, tile_m, tile_n);
+        gm0 = tile_m * T::kBM; gn0 = tile_n * T::kBN;
+    }
     if (MODE == 1) {   // window export: only tiles that touch the window do any work (uniform per workgroup)
         if (gm0 >= p.m1 || gm0 + T::kBM <= p.m0 || gn0 >= p.n1 || gn0 + T::kBN <= p.n0) return;
     }
@@ -113,12 +121,6 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     // wavefronts together issue 1.5 times as fast as the three-address v_fma_f32 that updating a vector element gets
     // (measured: 2.4 against 3.5 cycles per instruction and SIMD).
     float acc[RB][2][16];
-#pragma unroll
-    for (int r = 0; r < RB; ++r)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
     // ---- memory -> LDS -------------------------------------------------------------------------------------------
     // Per group the tile's RB activation blocks are contiguous in memory (1792 bytes each), and so are the four weight
@@ -135,11 +137,17 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     const int glast = g_end - 1;
     int piece_off[4], piece_stride[4];
     __amdgpu_buffer_rsrc_t piece_rs[4];
+    auto place_pieces = [&]() {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int c = wave + 4 * k;
+            piece_off[k] = c < 7 ? (gm0 / 32) * kW4ABlock + c * 1024 : (gn0 / 64) * kW4BBlock + (c - 7) * 1024;
+        }
+    };
+    place_pieces();
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const int c = wave + 4 * k;
-        const bool is_a = c < 7;
-        piece_off[k] = is_a ? (gm0 / 32) * kW4ABlock + c * 1024 : (gn0 / 64) * kW4BBlock + (c - 7) * 1024;
+        const bool is_a = wave + 4 * k < 7;
         piece_stride[k] = is_a ? a_stride : b_stride;
         piece_rs[k] = is_a ? rs_a : rs_b;
     }
@@ -158,10 +166,6 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     // LDS read wait for ALL outstanding memory-to-LDS requests, also those of later stages.  LDS operations of a
     // wavefront complete in order, so "all but the newest n" is an exact wait.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
-    const uint32_t la_a = lds_base + lane * 24;                                         // activation codes: 24 bytes per lane
-    const uint32_t la_sx = lds_base + li * 4;                                           // activation scales (+ 1536 + 1792 r through the offset field): both lane halves read the row's scale
-    const uint32_t la_b = lds_base + T::kAStage + wave * kW4BBlock + lane * 16;         // weight codes: 16 bytes per lane
-    const uint32_t la_sw = lds_base + T::kAStage + wave * kW4BBlock + kW4BCodes + li * 4;   // weight scales (+ 128 c through the offset field)
     struct AFrag { u32x2 d[3]; };
     struct BRaw { u32x4 d; };
     struct BFrag { uint32_t d[6]; };
@@ -198,11 +202,25 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     for (int i = 0; i < T::kStages - 1; ++i) dma(g_begin + i, i);
     __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
 
+    int wg = (int)blockIdx.x;      // PERSIST: the tile in hand
+    for (;;) {                     // one tile per trip; without PERSIST there is one trip
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+
     // ---- bias and low-rank up projection: the accumulators START as bias + H L2 (the bias is the C operand of the
     // first bf16 MFMAs; H as exact hi + lo parts).  Loaded here, the bias shares the round trip of the first operands; at
     // the end of the tile its load would stand alone between the last group and the stores (1.4 % of the launch).
     if (MODE == 0 && split == 0) {      // one split carries the bias and the low-rank product
-        const float b0 = p.bias[gn0 + wn0 + li], b1 = p.bias[gn0 + wn0 + 32 + li];      // padded to Npad
+        // (addresses from a lane number the compiler cannot trace back: worked out here, per tile, they live only as
+        // long as this phase; lifted out of the tile loop they would be kept, and spilled, across the main loop)
+        int lane_p = lane;
+        asm volatile("" : "+v"(lane_p));
+        const int li_p = lane_p & 31;
+        const float b0 = p.bias[gn0 + wn0 + li_p], b1 = p.bias[gn0 + wn0 + 32 + li_p];      // padded to Npad
         floatx16 lr[RB][2];
 #pragma unroll
         for (int r = 0; r < RB; ++r)
@@ -212,7 +230,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
                 lr[r][c] = floatx16{b, b, b, b, b, b, b, b, b, b, b, b, b, b, b, b};
             }
         if (p.rank > 0)
-            gemm_lowrank_product<RB, 2>(lr, p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane * 16, p.l2t, p.rank, gn0 + wn0, lane);
+            gemm_lowrank_product<RB, 2>(lr, p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane_p * 16, p.l2t, p.rank, gn0 + wn0, lane_p);
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
@@ -227,13 +245,21 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     // group g + 1).  Operand registers: two activation fragments (row blocks alternate between them), the two
     // expanded weight fragments (refreshed in place in slots 6 and 7), one scale operand per row block and per
     // column block.
+    // (the read addresses are worked out behind the low-rank product, from a lane number the compiler cannot trace back:
+    // kept in registers across that phase, which fills the register file, they would be spilled)
+    int lane_r = lane;
+    asm volatile("" : "+v"(lane_r));
+    const uint32_t la_a = lds_base + lane_r * 24;                                       // activation codes: 24 bytes per lane
+    const uint32_t la_sx = lds_base + (lane_r & 31) * 4;                                // activation scales (+ 1536 + 1792 r through the offset field): both lane halves read the row's scale
+    const uint32_t la_b = lds_base + T::kAStage + wave * kW4BBlock + lane_r * 16;       // weight codes: 16 bytes per lane
+    const uint32_t la_sw = lds_base + T::kAStage + wave * kW4BBlock + kW4BCodes + (lane_r & 31) * 4;   // weight scales (+ 128 c through the offset field)
     AFrag af[2];
     BRaw braw[2];
     BFrag bfr[2];
     u32x2 sxr[RB], swr[2];
     floatx16 ag[2], sg;
     uint32_t st_cur = 0, st_nxt = T::kStage;      // byte offsets of the stages of group g and g + 1
-    int st_free = T::kStages - 1;                 // index of the stage that the requests of the top of the step fill
+    int st_free = (T::kStages - 1) % T::kStages;  // index of the stage that the requests of the top of the step fill
 
     auto export_sums = [&](const floatx16 &d, int g, int r, int c) {
         if (MODE == 1) {
@@ -463,10 +489,31 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     }
 
     // ---- epilogue: bf16 (RNE), transposition through a wavefront-private LDS block, 16-byte stores ----------------
-    unsigned char *ob = lds + wave * (32 * kOutRowW4);
-    const bool full = gm0 + T::kBM <= p.M && gn0 + T::kBN <= p.N && (p.N % 8) == 0;
+    const int gm_out = gm0, gn_out = gn0;
+    bool more = false;
+    if (PERSIST) {
+        // the next tile's first groups are requested now: behind the barrier above nobody reads the ring any more,
+        // and the staging blocks of the stores lie beside it
+        wg += (int)gridDim.x;
+        more = wg < total;
+        if (more) {
+            int tile_m, tile_n;
+            gemm_tile_of(wg, tiles_m, tiles_n, tile_m, tile_n);
+            gm0 = tile_m * T::kBM; gn0 = tile_n * T::kBN;
+            place_pieces();
+#pragma unroll
+            for (int i = 0; i < T::kStages - 1; ++i) dma(g_begin + i, i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    unsigned char *ob = lds + (PERSIST ? T::kRing : 0) + wave * (32 * kOutRowW4);
+    const bool full = gm_out + T::kBM <= p.M && gn_out + T::kBN <= p.N && (p.N % 8) == 0;
     const float bias[2] = {0.f, 0.f};
-    gemm_store_wave_tile<RB, 2, false>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm0, gn0 + wn0, full, lane);
+    int lane_e = lane;      // (as above: the store addresses are worked out here, per tile)
+    asm volatile("" : "+v"(lane_e));
+    gemm_store_wave_tile<RB, 2, false>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm_out, gn_out + wn0, full, lane_e);
+    if (!PERSIST || !more) break;
+    }
 }
 
 template <int RB>
@@ -479,13 +526,20 @@ hipError_t launch_w4_tile(const GemmW4Params &p, hipStream_t stream) {
     if (p.tail < 0 || p.tail > tiles_m * tiles_n || (p.ksplit > 1) != (p.tail > 0)) return hipErrorInvalidValue;
     if (p.ksplit > 1 && (size_t)p.tail * p.ksplit * T::kBM * T::kBN * 4 >= ((size_t)1 << 31)) return hipErrorInvalidValue;
     const dim3 grid(tiles_m * tiles_n - p.tail + p.tail * p.ksplit), block(256);
+    if (!p.dbg && p.ksplit == 1 && tiles_m * tiles_n > kGemmPlaces) {
+        auto k = gemm_w4a4_kernel<RB, 0, true>;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytesPersistent);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(k, dim3(kGemmPlaces), block, T::kLdsBytesPersistent, stream, p);
+        return hipGetLastError();
+    }
     if (p.dbg) {
-        auto k = gemm_w4a4_kernel<RB, 1>;
+        auto k = gemm_w4a4_kernel<RB, 1, false>;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
         if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
     } else {
-        auto k = gemm_w4a4_kernel<RB, 0>;
+        auto k = gemm_w4a4_kernel<RB, 0, false>;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
         if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(k, grid, block, T::kLdsBytes, stream, p);
