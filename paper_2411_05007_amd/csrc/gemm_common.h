@@ -33,9 +33,11 @@ __device__ __forceinline__ void gemm_tile_of(int bid, int tiles_m, int tiles_n, 
 // 64 CB + 16 bytes) so that every store instruction writes whole 128-byte lines.
 //   acc_at(r, c, v): the accumulator;  bias[c]: the lane's bias of column block c;  (row0, col0): the wavefront's first
 //   output element;  full: the whole tile lies inside M x N and N % 8 == 0 (16-byte stores), else element-wise.
-template <int RB, int CB, bool ADD_BIAS = true, typename AccAt>
+//   between(r): called behind the stores of row block r (whose accumulators are dead from there on).
+struct GemmNothingBetween { __device__ __forceinline__ void operator()(int) const {} };
+template <int RB, int CB, bool ADD_BIAS = true, typename AccAt, typename Between = GemmNothingBetween>
 __device__ __forceinline__ void gemm_store_wave_tile(AccAt acc_at, const float (&bias)[CB], unsigned char *ob, uint16_t *Y, int M, int N,
-                                                     int row0, int col0, bool full, int lane) {
+                                                     int row0, int col0, bool full, int lane, Between between = Between()) {
     constexpr int kWN = 32 * CB, kOutRow = kWN * 2 + 16;
     const int li = lane & 31, lh = lane >> 5;
 #pragma unroll
@@ -70,6 +72,7 @@ __device__ __forceinline__ void gemm_store_wave_tile(AccAt acc_at, const float (
                     if (gcol + k < N) dst[k] = e[k];
             }
         }
+        between(r);
     }
 }
 
@@ -80,51 +83,66 @@ __device__ __forceinline__ void gemm_store_wave_tile(AccAt acc_at, const float (
 // The operands of rank step ks + 1 are requested before step ks is multiplied, so the branch pays one memory round
 // trip (shared with the first operand blocks of the caller's main loop), not one per 16 columns of H.
 typedef float gemm_floatx16 __attribute__((ext_vector_type(16)));
+// the operands of one rank step (16 columns of H) of a wavefront: its RB row blocks of H as hi and lo parts, its CB
+// column blocks of L2
+template <int RB, int CB>
+struct GemmLowRankStep { uint4 hhi[RB], hlo[RB], braw[CB]; };
+template <int RB, int CB>
+__device__ __forceinline__ void gemm_lowrank_load(GemmLowRankStep<RB, CB> &o, const unsigned char *hf, const uint16_t *l2t, int rank, int col0,
+                                                  int lane, int ks) {
+    const int li = lane & 31, lh = lane >> 5;
+    const int ksteps = rank / 16;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        const unsigned char *hp = hf + (r * ksteps + ks) * 2048;      // < 2^31: H fragments of one tile
+        o.hhi[r] = *reinterpret_cast<const uint4 *>(hp);
+        o.hlo[r] = *reinterpret_cast<const uint4 *>(hp + 1024);
+    }
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+        // element (col0 + 32 c + li) rank + ... of L2^T, as an unsigned 32-bit index: every launch checks that
+        // K Npad < 2^32, and rank <= K
+        const uint32_t col = (uint32_t)(col0 + c * 32 + li);        // < Npad
+        o.braw[c] = *reinterpret_cast<const uint4 *>(l2t + (col * (uint32_t)rank + (uint32_t)(ks * 16 + 8 * lh)));
+    }
+}
+template <int RB, int CB>
+__device__ __forceinline__ void gemm_lowrank_multiply(gemm_floatx16 (&acc)[RB][CB], const GemmLowRankStep<RB, CB> &o) {
+    typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+        const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, o.braw[c]);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, o.hhi[r]), bl, acc[r][c], 0, 0, 0);
+            acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, o.hlo[r]), bl, acc[r][c], 0, 0, 0);
+        }
+    }
+}
+// The product from rank step 0 on, with the operands of steps 0 (`e`) and 1 (`o`, if the rank has a second step) already
+// requested by the caller (gemm_lowrank_load).
+template <int RB, int CB>
+__device__ __forceinline__ void gemm_lowrank_product_from(gemm_floatx16 (&acc)[RB][CB], GemmLowRankStep<RB, CB> &e, GemmLowRankStep<RB, CB> &o,
+                                                          const unsigned char *hf, const uint16_t *l2t, int rank, int col0, int lane) {
+    const int ksteps = rank / 16;
+    for (int ks = 0; ks < ksteps; ks += 2) {
+        if (ks > 0 && ks + 1 < ksteps) gemm_lowrank_load<RB, CB>(o, hf, l2t, rank, col0, lane, ks + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        gemm_lowrank_multiply<RB, CB>(acc, e);
+        if (ks + 1 < ksteps) {
+            if (ks + 2 < ksteps) gemm_lowrank_load<RB, CB>(e, hf, l2t, rank, col0, lane, ks + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            gemm_lowrank_multiply<RB, CB>(acc, o);
+        }
+    }
+}
 template <int RB, int CB>
 __device__ __forceinline__ void gemm_lowrank_product(gemm_floatx16 (&acc)[RB][CB], const unsigned char *hf, const uint16_t *l2t, int rank,
                                                      int col0, int lane) {
-    typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-    const int li = lane & 31, lh = lane >> 5;
-    const int ksteps = rank / 16;
-    struct LowRank { uint4 hhi[RB], hlo[RB], braw[CB]; };
-    auto load_step = [&](LowRank &o, int ks) {
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-            const unsigned char *hp = hf + (r * ksteps + ks) * 2048;      // < 2^31: H fragments of one tile
-            o.hhi[r] = *reinterpret_cast<const uint4 *>(hp);
-            o.hlo[r] = *reinterpret_cast<const uint4 *>(hp + 1024);
-        }
-#pragma unroll
-        for (int c = 0; c < CB; ++c) {
-            // element (col0 + 32 c + li) rank + ... of L2^T, as an unsigned 32-bit index: every launch checks that
-            // K Npad < 2^32, and rank <= K
-            const uint32_t col = (uint32_t)(col0 + c * 32 + li);        // < Npad
-            o.braw[c] = *reinterpret_cast<const uint4 *>(l2t + (col * (uint32_t)rank + (uint32_t)(ks * 16 + 8 * lh)));
-        }
-    };
-    auto multiply = [&](const LowRank &o) {
-#pragma unroll
-        for (int c = 0; c < CB; ++c) {
-            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, o.braw[c]);
-#pragma unroll
-            for (int r = 0; r < RB; ++r) {
-                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, o.hhi[r]), bl, acc[r][c], 0, 0, 0);
-                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, o.hlo[r]), bl, acc[r][c], 0, 0, 0);
-            }
-        }
-    };
-    LowRank e, o;
-    load_step(e, 0);
-    for (int ks = 0; ks < ksteps; ks += 2) {
-        if (ks + 1 < ksteps) load_step(o, ks + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(e);
-        if (ks + 1 < ksteps) {
-            if (ks + 2 < ksteps) load_step(e, ks + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(o);
-        }
-    }
+    GemmLowRankStep<RB, CB> e, o;
+    gemm_lowrank_load<RB, CB>(e, hf, l2t, rank, col0, lane, 0);
+    if (rank > 16) gemm_lowrank_load<RB, CB>(o, hf, l2t, rank, col0, lane, 1);
+    gemm_lowrank_product_from<RB, CB>(acc, e, o, hf, l2t, rank, col0, lane);
 }
 
 }  // namespace svdq

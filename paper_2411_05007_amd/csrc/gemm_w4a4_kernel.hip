@@ -202,6 +202,35 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     for (int i = 0; i < T::kStages - 1; ++i) dma(g_begin + i, i);
     __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
 
+    // The bias and the operands of the first two rank steps of the low-rank product of the tile named by gm0 / gn0, into
+    // registers.  (Addresses from a lane number the compiler cannot trace back: worked out here, per tile, they live only
+    // as long as they are needed; lifted out of the tile loop they would be kept, and spilled, across the main loop.)
+    GemmLowRankStep<RB, 2> lr_e, lr_o;
+    float bias0 = 0.f, bias1 = 0.f;
+    // (part 0: the bias and rank step 0; part 1: rank step 1 - forty registers each, so between two tiles the second part
+    // waits until the stores have freed half of the accumulators)
+    auto fetch_lowrank = [&](int part) {
+        // (every path assigns: a value that could survive from the tile before would be kept alive across the main loop)
+        GemmLowRankStep<RB, 2> &dst = part ? lr_o : lr_e;
+        dst = GemmLowRankStep<RB, 2>{};
+        if (part == 0) bias0 = bias1 = 0.f;
+        if (MODE == 0 && split == 0) {      // one split carries the bias and the low-rank product
+            int lane_p = lane;
+            asm volatile("" : "+v"(lane_p));
+            const int li_p = lane_p & 31;
+            if (part == 0) {
+                bias0 = p.bias[gn0 + wn0 + li_p];      // padded to Npad
+                bias1 = p.bias[gn0 + wn0 + 32 + li_p];
+            }
+            if (p.rank > 16 * part) {
+                const unsigned char *hf = p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane_p * 16;
+                gemm_lowrank_load<RB, 2>(dst, hf, p.l2t, p.rank, gn0 + wn0, lane_p, part);
+            }
+        }
+    };
+    fetch_lowrank(0);
+    fetch_lowrank(1);
+
     int wg = (int)blockIdx.x;      // PERSIST: the tile in hand
     for (;;) {                     // one tile per trip; without PERSIST there is one trip
 #pragma unroll
@@ -212,25 +241,22 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
     // ---- bias and low-rank up projection: the accumulators START as bias + H L2 (the bias is the C operand of the
-    // first bf16 MFMAs; H as exact hi + lo parts).  Loaded here, the bias shares the round trip of the first operands; at
-    // the end of the tile its load would stand alone between the last group and the stores (1.4 % of the launch).
-    if (MODE == 0 && split == 0) {      // one split carries the bias and the low-rank product
-        // (addresses from a lane number the compiler cannot trace back: worked out here, per tile, they live only as
-        // long as this phase; lifted out of the tile loop they would be kept, and spilled, across the main loop)
-        int lane_p = lane;
-        asm volatile("" : "+v"(lane_p));
-        const int li_p = lane_p & 31;
-        const float b0 = p.bias[gn0 + wn0 + li_p], b1 = p.bias[gn0 + wn0 + 32 + li_p];      // padded to Npad
+    // first bf16 MFMAs; H as exact hi + lo parts).  Requested with the tile's first operands, the bias shares their round
+    // trip; at the end of the tile its load would stand alone between the last group and the stores (1.4 % of the launch).
+    if (MODE == 0 && split == 0) {
         floatx16 lr[RB][2];
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                const float b = c ? b1 : b0;
+                const float b = c ? bias1 : bias0;
                 lr[r][c] = floatx16{b, b, b, b, b, b, b, b, b, b, b, b, b, b, b, b};
             }
-        if (p.rank > 0)
-            gemm_lowrank_product<RB, 2>(lr, p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane_p * 16, p.l2t, p.rank, gn0 + wn0, lane_p);
+        if (p.rank > 0) {
+            int lane_p = lane;
+            asm volatile("" : "+v"(lane_p));
+            gemm_lowrank_product_from<RB, 2>(lr, lr_e, lr_o, p.hfrag + (size_t)(gm0 / 32) * (p.rank / 16) * 2048 + lane_p * 16, p.l2t, p.rank, gn0 + wn0, lane_p);
+        }
 #pragma unroll
         for (int r = 0; r < RB; ++r)
 #pragma unroll
@@ -504,6 +530,11 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
 #pragma unroll
             for (int i = 0; i < T::kStages - 1; ++i) dma(g_begin + i, i);
             __builtin_amdgcn_sched_barrier(0);
+            fetch_lowrank(0);      // and its bias and first low-rank operands: their round trip runs beside the stores
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            lr_e = GemmLowRankStep<RB, 2>{};      // (assigned on every path, see fetch_lowrank)
+            bias0 = bias1 = 0.f;
         }
     }
     unsigned char *ob = lds + (PERSIST ? T::kRing : 0) + wave * (32 * kOutRowW4);
@@ -511,7 +542,15 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     const float bias[2] = {0.f, 0.f};
     int lane_e = lane;      // (as above: the store addresses are worked out here, per tile)
     asm volatile("" : "+v"(lane_e));
-    gemm_store_wave_tile<RB, 2, false>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm_out, gn_out + wn0, full, lane_e);
+    gemm_store_wave_tile<RB, 2, false>([&](int r, int c, int v) { return acc[r][c][v]; }, bias, ob, p.Y, p.M, p.N, gm_out, gn_out + wn0, full, lane_e,
+                                       [&](int r) {
+                                           if (PERSIST && r == 1) {
+                                               __builtin_amdgcn_sched_barrier(0);
+                                               if (more) fetch_lowrank(1);
+                                               else lr_o = GemmLowRankStep<RB, 2>{};
+                                               __builtin_amdgcn_sched_barrier(0);
+                                           }
+                                       });
     if (!PERSIST || !more) break;
     }
 }
