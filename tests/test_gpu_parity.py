@@ -218,6 +218,31 @@ def test_activation_launch_with_whole_and_cut_slices(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"whole+cut {M}x{K}x{N} r{r}", window=False)
 
 
+@pytest.mark.parametrize("M,K,N,r", [(4500, 128, 4000, 32), (3200, 64, 11264, 16), (4400, 192, 4112, 0)])
+def test_large_launches_with_persistent_workgroups(torch, M, K, N, r):
+    """More tiles than workgroup places and a last round that is at most half full: 512 workgroups walk two or three
+    tiles each, the next tile's first groups, bias and low-rank operands requested before the stores of the tile in
+    hand.  Ragged last tile row and column (element-wise stores), a K of one group (shorter than the ring), rank 0;
+    576, 1100 and 595 tiles.  Every row against the oracle; twice on one workspace, bit for bit the same."""
+    rng = np.random.default_rng(9100 + M + N)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, 2, replace=False)] *= 30
+    xb = O.bf16_round(x)
+    w = (rng.standard_normal((K, N)) * 0.05).astype(np.float32)
+    ax = np.abs(O.bf16_to_f32(xb)).max(axis=0)
+    b = (rng.standard_normal(N) * 0.5).astype(np.float32)
+    prep = S.svdq_prepare(w, ax, r, bias=b)
+    plan = S.svdq_debug_launch_plan(M, prep.shape)
+    assert plan["gemm_tiles"] > 512 and 1 <= plan["gemm_tiles"] % 512 <= 256 and plan["gemm_ksplit"] == 1
+    _say(f"persistent workgroups: M={M} K={K} N={N} r={r}, {plan['gemm_tiles']} tiles")
+    _run_and_compare(torch, xb, prep, what=f"persistent {M}x{K}x{N} r{r}", window=True)
+    layer = S.DeviceLayer(prep)
+    xt = S.bf16_tensor_from_bits(xb)
+    ws = layer.workspace(M)
+    y0 = S.bits_from_bf16_tensor(layer.forward(xt, workspace=ws))
+    assert np.array_equal(S.bits_from_bf16_tensor(layer.forward(xt, workspace=ws)), y0)
+
+
 @pytest.mark.parametrize("M,K,N,r", [(100, 3072, 272, 32), (70, 3136, 144, 16), (200, 6144, 400, 48)])
 def test_small_launches_with_split_k_loop(torch, M, K, N, r):
     """Few tiles and a long K: the library splits the K loop over several workgroups per tile, which park fp32
