@@ -192,7 +192,7 @@ struct WorkspaceFp4 {
 
 
 // How the W4A4 GEMM of an M x N x (64 G) layer is launched.  Tiles are 128 x 256, two workgroups per CU (512 places).
-// A launch with at most one workgroup per CU has the K loop of every tile split over up to four workgroups (at least
+// A launch with at most one workgroup per CU has the K loop of every tile split over up to eight workgroups (at least
 // twelve groups each): every one of them writes its fp32 partial tile to the workspace, and the one that finishes last
 // adds them up (in split order, so the result does not depend on who is last) and stores Y.
 // The kernel can also split only the last `tail` tiles of the launch order (the partly filled last round of a large
@@ -215,7 +215,7 @@ inline GemmPlan plan_gemm(int M, int N, int G, int ksplit_override = 0) {
     pl.tail = pl.tiles;
     if (pl.tiles <= kGemmPlaces / 2) {
         s = kGemmPlaces / pl.tiles;
-        if (s > 4) s = 4;
+        if (s > kMaxKSplit) s = kMaxKSplit;      // (48 tiles, K = 12288: eight shares 47.6 us, four 50.0, six 52.8)
     }
     while (s > 1 && G / s < 12) --s;                // at least twelve groups per split
     if (ksplit_override > 0) {
