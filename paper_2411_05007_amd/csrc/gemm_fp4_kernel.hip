@@ -161,6 +161,7 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     dma(g_begin, 0);
     dma(g_begin + 1, 1);
     dma(g_begin + 2, 2);
+    dma(g_begin + 3, 3);
     __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
 
     // ---- low-rank up projection: the accumulators START as H L2 (bf16 MFMAs, H as exact hi + lo parts) ----
@@ -172,20 +173,27 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
 
     // ---- main loop -----------------------------------------------------------------------------------------------
     // Step g multiplies from registers that were read from LDS during step g - 1.  Per step and wavefront: wait until
-    // its own requests for step g + 1 have landed (all but the newest three, which are those for step g + 2), one
-    // barrier (now every wavefront's share of step g + 1 is in LDS, and everybody is done reading the stage that
-    // step g + 3 will overwrite), read step g + 1 into the other register set, request step g + 3, 8 MFMAs.
+    // its own requests for step g + 1 have landed, one barrier (now every wavefront's share of step g + 1 is in LDS, and
+    // everybody has read step g out of its stage, during step g - 1), read step g + 1 into the other register set,
+    // request step g + 4 into the stage that step g has just left, 8 or 9 MFMAs.  A step's operands are thus requested
+    // three steps before they are read (one step later, as the first version did, runs at the same speed on large
+    // launches and 3 % slower on small ones: the loop does not wait for memory).  Timing-only variants at the headline
+    // shape: the MFMAs alone 70 us, the data movement alone 60 us (LDS busy nine tenths of that: 36 KB per workgroup and
+    // step through a 128-byte port), both 99 us - the two overlap only in part.
+    // The wait names how many newer requests may still be in flight: the three each of steps g + 2 and g + 3, and in
+    // the two steps behind selector 0 the six scale loads of the next four steps, which were issued between them.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     SVDQ_READ_STAGE(f0, 0)
     SVDQ_READS_DONE(f0);
 #define SVDQ_FP4_STEP(SEL, cur, nxt)                                                                                  \
     if (g0 + SEL < g_end) {                                                                                           \
-        asm volatile("s_waitcnt vmcnt(3)" ::: "memory");                                                              \
+        if (SEL == 1 || SEL == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(6 + kRB + kCB) : "memory");                \
+        else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");                                                         \
         __builtin_amdgcn_s_barrier();                                                                                 \
         SVDQ_READ_STAGE(nxt, (SEL + 1) & 3)                                                                           \
         if (SEL == 0) load_scales(sn, q + 1 < q_end ? q + 1 : q);                                                     \
-        dma(g0 + SEL + 3, (SEL + 3) & 3);                                                                             \
+        dma(g0 + SEL + 4, SEL);                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                            \
         _Pragma("unroll") for (int r = 0; r < kRB; ++r)                                                               \
             _Pragma("unroll") for (int c = 0; c < kCB; ++c)                                                           \

@@ -133,23 +133,25 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
     dma(g_begin, 0);
     dma(g_begin + 1, 1);
     dma(g_begin + 2, 2);
+    dma(g_begin + 3, 3);
     __builtin_amdgcn_sched_barrier(0);      // the first operands are requested before H and L2
 
     // ---- main loop -----------------------------------------------------------------------------------------------
     // Step g multiplies from registers that were read from LDS during step g - 1.  Per step and wavefront: wait until
-    // its own requests for step g + 1 have landed (all but the newest three, which are those for step g + 2), one
-    // barrier (now every wavefront's share of step g + 1 is in LDS, and everybody is done reading the stage that
-    // step g + 3 will overwrite), read step g + 1 into the other register set, request step g + 3, 8 MFMAs.
+    // its own requests for step g + 1 have landed (all but the newest six, which are those for steps g + 2 and g + 3),
+    // one barrier (now every wavefront's share of step g + 1 is in LDS, and everybody has read step g out of its stage,
+    // during step g - 1), read step g + 1 into the other register set, request step g + 4 into the stage that step g
+    // has just left, 8 or 9 MFMAs.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     SVDQ_READ_STAGE(f0, 0)
     SVDQ_READS_DONE(f0);
 #define SVDQ_W8_STEP(SEL, cur, nxt)                                                                                  \
     if (g0 + SEL < g_end) {                                                                                           \
-        asm volatile("s_waitcnt vmcnt(3)" ::: "memory");                                                              \
+        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");                                                              \
         __builtin_amdgcn_s_barrier();                                                                                 \
         SVDQ_READ_STAGE(nxt, (SEL + 1) & 3)                                                                           \
-        dma(g0 + SEL + 3, (SEL + 3) & 3);                                                                             \
+        dma(g0 + SEL + 4, SEL);                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                            \
         _Pragma("unroll") for (int r = 0; r < kRB; ++r)                                                               \
             _Pragma("unroll") for (int c = 0; c < kCB; ++c)                                                           \
