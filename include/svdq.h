@@ -334,6 +334,9 @@ int svdq_w4a16_forward(const svdq_layer_dev *layer, const void *X, int M, void *
  * behaviour are those of their INT4 namesakes; wcodes holds one int8 per weight (K * Npad bytes, operand order
  * of the int8 matrix-core instruction), wscales fp16 [Npad].  The forward enqueues two kernels (quantization with
  * the down projection, GEMM).  The K / rank limits of svdq_linear_forward apply; K * Npad and K * Mpad below 2^31.
+ * The workspace also holds, for launches of few tiles with a long K, the int32 partial tiles and arrival counters of a
+ * split K loop (integer sums: the same bits as the unsplit loop); svdq_w8a8_workspace_bytes follows the calling
+ * thread's SVDQ_OPT_KSPLIT bits like its INT4 namesake.
  * ------------------------------------------------------------------------------------------------ */
 int svdq_w8a8_prepared_sizes(const svdq_shape *shape, svdq_sizes *out);
 int svdq_w8a8_prepare(const svdq_shape *shape, const float *W, const float *x_absmax, const float *bias,

@@ -462,7 +462,7 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
 
 size_t svdq_w8a8_workspace_bytes(int M, const svdq_shape *s) {
     if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
-    return svdq::workspace_layout_w8(M, s->K, s->rank).total;
+    return svdq::workspace_layout_w8(M, s->K, s->N, s->rank, ksplit_override()).total;
 }
 
 int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
@@ -474,7 +474,7 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.rank);
+    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.N, s.rank, ksplit_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
     if (s.K > 32768 || svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
@@ -495,6 +495,8 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     a.hfrag = ws + w.hfrag_off;
     a.M = M; a.K = s.K; a.G = s.K / svdq::kGroup; a.Mpad = w.Mpad; a.rank = s.rank;
     a.fmt = 2;
+    a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);      // the arrival counters of the GEMM's split K loop
+    a.n_zero = w.n_counters;
     hipError_t e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
     if (e != hipSuccess) return hip_fail(e);
     if (void *ev = g_profile_event) {
@@ -512,6 +514,9 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     g.Y = static_cast<uint16_t *>(Y);
     g.M = M; g.N = s.N; g.K = s.K; g.Mpad = w.Mpad; g.Npad = svdq::round_up(s.N, svdq::kRowPad);
     g.rank = lowrank ? s.rank : 0;
+    g.ksplit = w.ksplit;
+    g.partial = reinterpret_cast<int32_t *>(ws + w.partial_off);
+    g.counters = reinterpret_cast<uint32_t *>(ws + w.counters_off);
     e = svdq::launch_gemm_w8a8(g, stream);
     return e == hipSuccess ? SVDQ_OK : hip_fail(e);
 }
@@ -523,7 +528,7 @@ int svdq_w8a8_debug_act(const svdq_layer_dev *L, const void *workspace, int M, i
     if (M < 0 || !workspace) return SVDQ_EINVAL;
     if (M == 0) return SVDQ_OK;
     const svdq_shape &s = L->shape;
-    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.rank);
+    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.N, s.rank, ksplit_override());
     const unsigned char *ws = static_cast<const unsigned char *>(workspace);
     svdq::DebugActW8Params d{};
     d.codes = ws + w.codes_off;

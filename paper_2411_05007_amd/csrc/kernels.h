@@ -125,6 +125,9 @@ struct GemmW8Params {
     const float *bias;       // fp32 [Npad]
     uint16_t *Y;             // bf16 [M][N]
     int M, N, K, Mpad, Npad, rank;
+    int ksplit;              // workgroups per tile along K (1 = no split); splits are multiples of eight steps of 32 channels
+    int32_t *partial;        // ksplit > 1: int32 [tile][split][128 * 256] partial tiles, register order
+    uint32_t *counters;      // ksplit > 1: one arrival counter per tile, zero when the kernel starts
 };
 hipError_t launch_gemm_w8a8(const GemmW8Params &p, hipStream_t stream);
 

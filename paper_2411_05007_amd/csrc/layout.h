@@ -105,21 +105,6 @@ inline __host__ __device__ uint32_t w4_e2m3(int q) { return q < 0 ? (32u | (uint
 inline __host__ __device__ size_t i8_code_offset(int k, int rows_pad, int row) {
     return ((((size_t)(k / 32) * (rows_pad / 32) + row / 32) * 64 + ((k % 32) / 16) * 32 + row % 32) * 16) + k % 16;
 }
-struct WorkspaceW8 {
-    size_t codes_off, sx_off, h_off, hfrag_off, total;
-    int Mpad;
-};
-inline WorkspaceW8 workspace_layout_w8(int M, int K, int rank) {
-    WorkspaceW8 w;
-    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
-    w.codes_off = 0;
-    w.sx_off = align256((size_t)K * w.Mpad);
-    w.h_off = w.sx_off + align256((size_t)w.Mpad * 2);
-    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    w.total = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    return w;
-}
-
 // ---- MXFP4 variant (E2M1 elements, blocks of 32 along K, one power-of-two scale byte per block) ----------
 // Both operands use the A / B operand order of v_mfma_scale_f32_32x32x64_f8f6f4, whose lane l feeds row (or
 // column) l % 32 with the 32 elements of block l / 32 of a 64-channel step:
@@ -147,14 +132,14 @@ struct GemmPlanFp4 {
     int tile;        // 0: 128 x 256, 1: 192 x 192
     int tiles, ksplit;
 };
-inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0) {
+inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0, int min_steps = 32) {
     GemmPlanFp4 pl;
     pl.tiles = ((M + 127) / 128) * ((N + 255) / 256);
     int s = 1;
     if (pl.tiles <= 128) {                          // measured: with 160 tiles and 72 steps two splits are slower than none
         s = 512 / pl.tiles;
         if (s > 4) s = 4;
-        while (s > 1 && G / s < 32) --s;
+        while (s > 1 && G / s < min_steps) --s;
     }
     if (ksplit_override > 0) s = ksplit_override < kMaxKSplitFp4 ? ksplit_override : kMaxKSplitFp4;
     // normalise: splits are multiples of four steps, none empty
@@ -173,6 +158,34 @@ inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0) {
         }
     }
     return pl;
+}
+
+// The int8 MFMA takes twice the time of the 4-bit one per step of 64 channels, so a split of the 8-bit GEMM's K loop pays
+// from sixteen such steps per share on (measured at M = 512: K = 3072, 48 tiles: 28.0 -> 23.2 us with three shares;
+// K = 4608, 20 tiles: 39.8 -> 28.2 us with four; K = 12288, 48 tiles: 83.5 -> 39.5 us with four).
+constexpr int kW8MinSplitSteps = 16;
+// Workspace of the 8-bit forward: int8 codes in operand order, one fp16 scale per token, H twice (fp32 and bf16 parts),
+// and for small launches with a long K the arrival counters and int32 partial tiles of a split K loop (the MXFP4
+// GEMM's plan: same tiles, same rule).
+struct WorkspaceW8 {
+    size_t codes_off, sx_off, h_off, hfrag_off, counters_off, partial_off, total;
+    int Mpad;
+    int n_counters, ksplit;
+};
+inline WorkspaceW8 workspace_layout_w8(int M, int K, int N, int rank, int ksplit_override = 0) {
+    WorkspaceW8 w;
+    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
+    w.codes_off = 0;
+    w.sx_off = align256((size_t)K * w.Mpad);
+    w.h_off = w.sx_off + align256((size_t)w.Mpad * 2);
+    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, K / kGroup, ksplit_override, kW8MinSplitSteps);
+    w.ksplit = pl.ksplit;
+    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
+    w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
+    w.total = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);
+    return w;
 }
 
 // how the activation kernel's launch is cut up (plan_act below)

@@ -76,9 +76,14 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
     const int tiles_m = (p.M + kBM - 1) / kBM;
     const int tiles_n = (p.N + kBN - 1) / kBN;
     const int total = tiles_m * tiles_n;
-    const int g_begin = 0, g_end = p.K / 32;      // steps of 32 channels
+    // with a split K loop the grid holds ksplit copies of the tile set; copy `split` multiplies steps [g_begin, g_end)
+    // of 32 channels, a multiple of eight steps each (the MXFP4 GEMM's plan and rule, whose steps are 64 channels)
+    const int split = (int)blockIdx.x / total;
+    const int g_per = 2 * (((p.K / 64 + p.ksplit - 1) / p.ksplit + 3) / 4 * 4);
+    const int g_begin = split * g_per;
+    const int g_end = g_begin + g_per < p.K / 32 ? g_begin + g_per : p.K / 32;
     int tile_m, tile_n;
-    gemm_tile_of((int)blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    gemm_tile_of((int)blockIdx.x - split * total, tiles_m, tiles_n, tile_m, tile_n);
     const int gm0 = tile_m * kBM, gn0 = tile_n * kBN;      // the launch checks that every tile lies inside the padded rows and columns
 
     intx16 iacc[kRB][kCB];
@@ -171,6 +176,54 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
 
+    // ---- split K loop: park the partial tile, the last workgroup to arrive adds the others to its own --------------
+    // Partial tiles are int32, so the order of the additions does not matter: bit for bit the sum of the unsplit loop.
+    // They are stored in register order (consecutive threads consecutive addresses) with device-scope accesses - the
+    // L2 caches of the chip's eight XCDs are not coherent with each other, and these accesses go past them; no cache
+    // is flushed.  A workgroup takes its ticket once all its stores have been acknowledged; the holder of the last
+    // ticket reads the others' tiles back.  Nobody waits for anybody.
+    if (p.ksplit > 1) {
+        const int tile_lin = tile_m * tiles_n + tile_n;
+        constexpr int kTileWords = kBM * kBN;
+        int *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
+#pragma unroll
+        for (int r = 0; r < kRB; ++r)
+#pragma unroll
+            for (int c = 0; c < kCB; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    __hip_atomic_store(mine + ((r * kCB + c) * 16 + v) * 256, iacc[r][c][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // every store of this thread has been acknowledged
+        __syncthreads();
+        uint32_t *ticket = reinterpret_cast<uint32_t *>(lds);      // the ring is no longer in use
+        if (tid == 0) *ticket = __hip_atomic_fetch_add(&p.counters[tile_lin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const bool last = *ticket == (uint32_t)(p.ksplit - 1);
+        __syncthreads();                                          // the epilogue reuses this LDS word
+        if (!last) return;
+        if (tid == 0) __hip_atomic_store(&p.counters[tile_lin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next launch
+        const int *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
+        for (int sidx = 0; sidx < p.ksplit; ++sidx) {
+            if (sidx == split) continue;
+#pragma unroll
+            for (int r = 0; r < kRB; ++r) {
+                // the values of a row of blocks are requested together, then added: one round trip per batch
+                int t[kCB][16];
+#pragma unroll
+                for (int c = 0; c < kCB; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        t[c][v] = __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * kCB + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c = 0; c < kCB; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) iacc[r][c][v] += t[c][v];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
     // ---- Eq. 2, once per output: the exact int32 sums become fp32 and take both scales ---------------------------
     floatx16 acc[kRB][kCB];
     {
@@ -228,7 +281,7 @@ static hipError_t launch_w8_tile(const GemmW8Params &p, hipStream_t stream) {
     // the limit on dynamic LDS is raised once per instantiation, not per launch
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(k, dim3(tiles_m * tiles_n), dim3(256), T::kLdsBytes, stream, p);
+    hipLaunchKernelGGL(k, dim3(tiles_m * tiles_n * p.ksplit), dim3(256), T::kLdsBytes, stream, p);
     return hipGetLastError();
 }
 
@@ -238,8 +291,14 @@ hipError_t launch_gemm_w8a8(const GemmW8Params &p, hipStream_t stream) {
     if (p.K <= 0 || p.K % 64 || p.Mpad % kRowPad || p.Npad % kRowPad || p.Mpad < p.M || p.Npad < p.N || p.rank % 16 ||
         (size_t)p.K * p.Mpad >= (size_t)1 << 31 || (size_t)p.K * p.Npad >= (size_t)1 << 31)
         return hipErrorInvalidValue;
-    // the tile shape follows the MXFP4 GEMM's rule (192 x 192 where it saves a round of workgroup places); no split K loop here
-    const GemmPlanFp4 plan = plan_gemm_fp4(p.M, p.N, p.K / kGroup, 1);
+    // what a split K loop needs: its buffers, the 128 x 256 tile (whose partial tiles the workspace is sized for), and at
+    // least one step for every split (splits are multiples of four steps of 64 channels)
+    if (p.ksplit < 1 || (p.ksplit > 1 && (!p.partial || !p.counters))) return hipErrorInvalidValue;
+    const int G = p.K / kGroup;
+    if (p.ksplit > 1 && (size_t)(p.ksplit - 1) * (((G + p.ksplit - 1) / p.ksplit + 3) / 4 * 4) >= (size_t)G) return hipErrorInvalidValue;
+    if (p.ksplit > 1) return launch_w8_tile<2, 4>(p, stream);
+    // the tile shape follows the MXFP4 GEMM's rule (192 x 192 where it saves a round of workgroup places)
+    const GemmPlanFp4 plan = plan_gemm_fp4(p.M, p.N, G, 1);
     return plan.tile == 1 ? launch_w8_tile<3, 3>(p, stream) : launch_w8_tile<2, 4>(p, stream);
 }
 

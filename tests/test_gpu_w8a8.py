@@ -100,6 +100,33 @@ def test_ragged_shapes(torch, M, K, N, r):
     _run_and_compare(torch, xb, prep, what=f"w8a8 ragged {M}x{K}x{N} r{r}")
 
 
+@pytest.mark.parametrize("M,K,N,r", [(100, 6144, 272, 32), (70, 6208, 144, 16), (200, 12288, 400, 48), (130, 4160, 528, 0)])
+def test_small_launches_with_split_k_loop(torch, M, K, N, r):
+    """Few tiles and a long K: the K loop is split over several workgroups per tile (the MXFP4 GEMM's plan: multiples of
+    four steps of 64 channels; K = 6144: three splits, 6208: 36 + 36 + 25 steps, 12288: four, 4160: 36 + 29), which park
+    int32 partial tiles; the last to arrive adds the others' to its own.  Integer sums: the split result must equal the
+    unsplit one BIT FOR BIT; and twice on the same workspace (the arrival counters must be left ready)."""
+    rng = np.random.default_rng(3600 + M + K)
+    xb, w, ax, b = _random_layer(rng, M, K, N)
+    prep = S.svdq_w8a8_prepare(w, ax, r, bias=b)
+    _say(f"w8a8 split-K: M={M} K={K} N={N} r={r}")
+    S.svdq_forward_options(0)
+    _run_and_compare(torch, xb, prep, what=f"w8a8 split {M}x{K}x{N} r{r}")
+    layer = S.DeviceLayer(prep)
+    x = S.bf16_tensor_from_bits(xb)
+    ws = layer.workspace(M)
+    y0 = S.bits_from_bf16_tensor(layer.forward(x, workspace=ws))
+    for _ in range(3):
+        assert np.array_equal(S.bits_from_bf16_tensor(layer.forward(x, workspace=ws)), y0)
+    try:
+        for ks in (1, 2, 5):
+            S.svdq_forward_options(ks << S.OPT_KSPLIT_SHIFT)
+            ws_k = layer.workspace(M)      # sized under the same option word
+            assert np.array_equal(S.bits_from_bf16_tensor(layer.forward(x, workspace=ws_k)), y0), f"forced split {ks}"
+    finally:
+        S.svdq_forward_options(0)
+
+
 def test_extreme_codes_and_scales(torch):
     """All-(+127) tokens against all-(-127) channels (the largest integer sum), and scales across the fp16 range."""
     K, N, M = 1024, 64, 48
