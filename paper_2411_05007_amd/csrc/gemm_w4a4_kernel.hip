@@ -457,9 +457,9 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
     // Partial tiles are stored in register order (16 bytes per thread and store, consecutive threads consecutive
     // addresses) with device-scope accesses: the L2 caches of the chip's eight XCDs are not coherent with each other,
     // and these accesses go past them; no cache is flushed.  A workgroup takes its ticket once all its stores have been
-    // acknowledged; the holder of the last ticket reads all partials back, its own included, and adds them in split
+    // acknowledged; the holder of the last ticket reads the others' partials back and adds them all in split
     // order, so the sum does not depend on who came last.  Nobody waits for anybody.
-    if (nsplit > 1) {
+    if (!PERSIST && nsplit > 1) {      // (a persistent launch has no split tiles)
         const int tile_lin = tpos;
         constexpr int kTileBytes = T::kBM * T::kBN * 4;
         constexpr int kDevice = 16;      // cache policy bit "sc1": coherent at device scope
@@ -486,31 +486,45 @@ __global__ __launch_bounds__(256, 2) void gemm_w4a4_kernel(GemmW4Params p) {
         __syncthreads();                                          // the epilogue reuses this LDS word
         if (!last) return;
         if (tid == 0) __hip_atomic_store(&p.counters[tile_lin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next launch
+        // The shares are added in split order, one row of blocks at a time; this workgroup's own share takes its place
+        // in that order from the registers (it is parked as well - nobody knows beforehand who comes last - but not
+        // read back), so the sum is the same whoever finishes: ((P0 + P1) + P2) + ...
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
+        for (int r = 0; r < RB; ++r) {
+            float sum[2][16];
+            for (int sidx = 0; sidx < p.ksplit; ++sidx) {
+                float term[2][16];
+                if (sidx == split) {
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) term[c][v] = acc[r][c][v];
+                } else {
+                    const int theirs = (tile_lin * p.ksplit + sidx) * kTileBytes;
+                    buffer_u32x4 t[2][4];      // the 32 values of a row of blocks are requested together: one round trip per batch
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            t[c][q] = __builtin_amdgcn_raw_buffer_load_b128(rs_p, 16 * tid, theirs + ((r * 2 + c) * 4 + q) * 4096, kDevice);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) term[c][4 * q + e] = __uint_as_float(t[c][q][e]);
+                }
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sum[c][v] = sidx == 0 ? term[c][v] : sum[c][v] + term[c][v];
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
-        for (int sidx = 0; sidx < p.ksplit; ++sidx) {
-            const int theirs = (tile_lin * p.ksplit + sidx) * kTileBytes;
-#pragma unroll
-            for (int r = 0; r < RB; ++r) {
-                buffer_u32x4 t[2][4];      // the 32 values of a row of blocks are requested together, then added: one round trip per batch
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        t[c][q] = __builtin_amdgcn_raw_buffer_load_b128(rs_p, 16 * tid, theirs + ((r * 2 + c) * 4 + q) * 4096, kDevice);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[r][c][4 * q + e] += __uint_as_float(t[c][q][e]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+                for (int v = 0; v < 16; ++v) acc[r][c][v] = sum[c][v];
         }
     }
 
