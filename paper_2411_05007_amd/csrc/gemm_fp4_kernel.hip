@@ -217,22 +217,28 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
     __builtin_amdgcn_s_barrier();
 
     // ---- split K loop: park the partial tile, the last workgroup to arrive adds them all up -------------------------
-    // Partial tiles are stored in register order (128 floats per thread, consecutive threads consecutive addresses)
-    // with device-scope atomic accesses: the L2 caches of the chip's eight XCDs are not coherent with each other, and
+    // Partial tiles are stored in register order (16 bytes per thread and store, consecutive threads consecutive
+    // addresses) with device-scope accesses: the L2 caches of the chip's eight XCDs are not coherent with each other, and
     // these accesses go past them; no cache is flushed.  A workgroup takes its ticket once all its stores have been
     // acknowledged; the holder of the last ticket reads all partials back, its own included, and adds them in split
     // order, so the sum does not depend on who came last.  Nobody waits for anybody.
     if (p.ksplit > 1) {
         const int tile_lin = tile_m * tiles_n + tile_n;
         constexpr int kTileWords = T::kBM * T::kBN;
-        float *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
+        constexpr int kDevice = 16;      // cache policy bit "sc1": coherent at device scope
+        // (a descriptor over this tile's shares: 16-byte accesses, thread t's at 16 t of every 4 KB piece)
+        const __amdgpu_buffer_rsrc_t rs_p = make_rsrc(p.partial + (size_t)tile_lin * p.ksplit * kTileWords, (size_t)p.ksplit * kTileWords * 4);
 #pragma unroll
         for (int r = 0; r < kRB; ++r)
 #pragma unroll
             for (int c = 0; c < kCB; ++c)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    __hip_atomic_store(mine + ((r * kCB + c) * 16 + v) * 256, acc[r][c][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int q = 0; q < 4; ++q) {
+                    buffer_u32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(acc[r][c][4 * q + e]);
+                    buffer_store_b128<kDevice>(v, rs_p, 16 * tid, split * kTileWords * 4 + ((r * kCB + c) * 4 + q) * 4096);
+                }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // every store of this thread has been acknowledged
         __syncthreads();
         uint32_t *ticket = reinterpret_cast<uint32_t *>(lds);      // the ring is no longer in use
@@ -248,22 +254,23 @@ __global__ __launch_bounds__(256, 2) void gemm_fp4_kernel(GemmFp4Params p) {
             for (int c = 0; c < kCB; ++c)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
-        const float *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
         for (int sidx = 0; sidx < p.ksplit; ++sidx) {
 #pragma unroll
             for (int r = 0; r < kRB; ++r) {
-                // the 64 values of a row of blocks are requested together, then added: one round trip per batch
-                float t[kCB][16];
+                // the values of a row of blocks are requested together, then added: one round trip per batch
+                buffer_u32x4 t[kCB][4];
 #pragma unroll
                 for (int c = 0; c < kCB; ++c)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        t[c][v] = __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * kCB + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int q = 0; q < 4; ++q)
+                        t[c][q] = __builtin_amdgcn_raw_buffer_load_b128(rs_p, 16 * tid, sidx * kTileWords * 4 + ((r * kCB + c) * 4 + q) * 4096, kDevice);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int c = 0; c < kCB; ++c)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[r][c][v] += t[c][v];
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[r][c][4 * q + e] += __uint_as_float(t[c][q][e]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }

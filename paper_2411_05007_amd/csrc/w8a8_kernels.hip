@@ -178,21 +178,28 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
 
     // ---- split K loop: park the partial tile, the last workgroup to arrive adds the others to its own --------------
     // Partial tiles are int32, so the order of the additions does not matter: bit for bit the sum of the unsplit loop.
-    // They are stored in register order (consecutive threads consecutive addresses) with device-scope accesses - the
+    // They are stored in register order (16 bytes per thread and store, consecutive threads consecutive addresses)
+    // with device-scope accesses - the
     // L2 caches of the chip's eight XCDs are not coherent with each other, and these accesses go past them; no cache
     // is flushed.  A workgroup takes its ticket once all its stores have been acknowledged; the holder of the last
     // ticket reads the others' tiles back.  Nobody waits for anybody.
     if (p.ksplit > 1) {
         const int tile_lin = tile_m * tiles_n + tile_n;
         constexpr int kTileWords = kBM * kBN;
-        int *mine = p.partial + ((size_t)tile_lin * p.ksplit + split) * kTileWords + tid;
+        constexpr int kDevice = 16;      // cache policy bit "sc1": coherent at device scope
+        // (a descriptor over this tile's shares: 16-byte accesses, thread t's at 16 t of every 4 KB piece)
+        const __amdgpu_buffer_rsrc_t rs_p = make_rsrc(p.partial + (size_t)tile_lin * p.ksplit * kTileWords, (size_t)p.ksplit * kTileWords * 4);
 #pragma unroll
         for (int r = 0; r < kRB; ++r)
 #pragma unroll
             for (int c = 0; c < kCB; ++c)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    __hip_atomic_store(mine + ((r * kCB + c) * 16 + v) * 256, iacc[r][c][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int q = 0; q < 4; ++q) {
+                    buffer_u32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (uint32_t)iacc[r][c][4 * q + e];
+                    buffer_store_b128<kDevice>(v, rs_p, 16 * tid, split * kTileWords * 4 + ((r * kCB + c) * 4 + q) * 4096);
+                }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // every store of this thread has been acknowledged
         __syncthreads();
         uint32_t *ticket = reinterpret_cast<uint32_t *>(lds);      // the ring is no longer in use
@@ -202,23 +209,24 @@ __global__ __launch_bounds__(256, 2) void gemm_w8a8_kernel(GemmW8Params p) {
         __syncthreads();                                          // the epilogue reuses this LDS word
         if (!last) return;
         if (tid == 0) __hip_atomic_store(&p.counters[tile_lin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // ready for the next launch
-        const int *all = p.partial + (size_t)tile_lin * p.ksplit * kTileWords + tid;
         for (int sidx = 0; sidx < p.ksplit; ++sidx) {
             if (sidx == split) continue;
 #pragma unroll
             for (int r = 0; r < kRB; ++r) {
                 // the values of a row of blocks are requested together, then added: one round trip per batch
-                int t[kCB][16];
+                buffer_u32x4 t[kCB][4];
 #pragma unroll
                 for (int c = 0; c < kCB; ++c)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        t[c][v] = __hip_atomic_load(all + (size_t)sidx * kTileWords + ((r * kCB + c) * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int q = 0; q < 4; ++q)
+                        t[c][q] = __builtin_amdgcn_raw_buffer_load_b128(rs_p, 16 * tid, sidx * kTileWords * 4 + ((r * kCB + c) * 4 + q) * 4096, kDevice);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int c = 0; c < kCB; ++c)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) iacc[r][c][v] += t[c][v];
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) iacc[r][c][4 * q + e] += (int)t[c][q][e];
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
