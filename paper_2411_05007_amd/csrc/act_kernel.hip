@@ -234,7 +234,7 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
                 amax_b = fmaxf(amax_b, fmaxf(fabsf(bf16lo(wb[i]) * r[2 * i]), fabsf(bf16hi(wb[i]) * r[2 * i + 1])));
             }
         };
-        if (npairs > 0) {
+        if (npairs > 0 && p.maxmode != 2) {
             XStage p0 = fetch_x(g0), p1 = fetch_x(clampg(g0 + 1));
             for (int ip = 0; ip < npairs; ++ip) {
                 const int g = g0 + 2 * ip;
@@ -261,6 +261,23 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
             amax_b = fmaxf(amax_b, o[r8 + 8]);
         }
         __syncthreads();      // the blocks go back to their owners
+        // A launch that cuts K into runs cannot know a token's maximum from one run: it is made in two passes.  The
+        // first (maxmode 1) stops here and leaves the maxima of its runs, pmax[run][token]; the second (maxmode 2) skips
+        // the walk above and takes the maximum over the runs - the same value in every workgroup of a slice.
+        if (p.maxmode == 1) {
+            if (wave == 0 && c8 == 0) {
+                p.pmax[(size_t)chunk * p.Mpad + ma] = amax_a;      // rows past M: padding entries
+                p.pmax[(size_t)chunk * p.Mpad + mb] = amax_b;
+            }
+            return;
+        }
+        if (p.maxmode == 2) {
+            amax_a = amax_b = 0.f;
+            for (int c = 0; c < nchunks; ++c) {
+                amax_a = fmaxf(amax_a, p.pmax[(size_t)c * p.Mpad + ma]);
+                amax_b = fmaxf(amax_b, p.pmax[(size_t)c * p.Mpad + mb]);
+            }
+        }
         auto scale_of = [](float amax, _Float16 &sh) {
             float s32 = amax / 127.0f;
             s32 = fminf(s32, 65504.0f);
@@ -271,7 +288,7 @@ __global__ __launch_bounds__(WAVES * 64, act_min_workgroups(RBMAX, WAVES, STAGE)
         _Float16 sha, shb;
         rcp8_a = scale_of(amax_a, sha);
         rcp8_b = scale_of(amax_b, shb);
-        if (wave == 0 && c8 == 0) {      // rows past M: padding entries of the scale vector (it has Mpad of them)
+        if (wave == 0 && c8 == 0 && chunk == 0) {      // rows past M: padding entries of the scale vector (it has Mpad of them)
             p.sx[ma] = __builtin_bit_cast(uint16_t, sha);
             p.sx[mb] = __builtin_bit_cast(uint16_t, shb);
         }
@@ -707,7 +724,10 @@ hipError_t launch_act(const ActParams &p, int flags, hipStream_t stream) {
     if (p.M <= 0) return hipSuccess;
     if (p.fmt == 2) {
         // per-token scales need all of K in one workgroup, and the offsets of the int8 codes fit 32 bits
-        if (p.chunks > 1 || (size_t)p.K * p.Mpad >= ((size_t)1 << 31) || ((flags & 1) && !p.sx)) return hipErrorInvalidValue;
+        // (a cut K needs the two-pass form: maxima of the runs first, then the pass that is given them)
+        if ((p.chunks > 1 && p.maxmode == 0) || p.maxmode < 0 || p.maxmode > 2 || (p.maxmode != 0 && (!p.pmax || p.whole != 0)) ||
+            (size_t)p.K * p.Mpad >= ((size_t)1 << 31) || ((flags & 1) && !p.sx))
+            return hipErrorInvalidValue;
         return launch_act_fmt<2>(p, flags, stream);
     }
     return p.fmt == 1 ? launch_act_fmt<1>(p, flags, stream) : launch_act_fmt<0>(p, flags, stream);

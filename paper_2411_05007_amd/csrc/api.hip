@@ -462,7 +462,7 @@ int svdq_w4a16_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, v
 
 size_t svdq_w8a8_workspace_bytes(int M, const svdq_shape *s) {
     if (!s || M < 0 || s->K <= 0 || s->K % svdq::kGroup != 0 || s->rank < 0 || s->rank > svdq::kMaxRank) return 0;
-    return svdq::workspace_layout_w8(M, s->K, s->N, s->rank, ksplit_override()).total;
+    return svdq::workspace_layout_w8(M, s->K, s->N, s->rank, ksplit_override(), act_override()).total;
 }
 
 int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void *Y, void *workspace,
@@ -474,9 +474,10 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     if (!X || !Y || !workspace) return SVDQ_EINVAL;
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255)) return SVDQ_EINVAL;
     const svdq_shape &s = L->shape;
-    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.N, s.rank, ksplit_override());
+    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.N, s.rank, ksplit_override(), act_override());
     if (workspace_bytes < w.total) return SVDQ_ENOSPACE;
-    if (s.K > 32768 || svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank)) > (size_t)svdq::kLdsBytesPerCU)
+    if (s.K > 32768 || (w.act_cut ? svdq::act_lds_bytes(w.act.gchunk, s.rank, w.act.waves)
+                                  : svdq::act_lds_bytes(s.K / svdq::kGroup, s.rank, svdq::act_waves(s.K, s.rank))) > (size_t)svdq::kLdsBytesPerCU)
         return SVDQ_EUNSUPPORTED;
     if ((unsigned long long)w.Mpad * s.K >= (1ull << 31) || (unsigned long long)s.K * svdq::round_up(s.N, svdq::kRowPad) >= (1ull << 31))
         return SVDQ_EUNSUPPORTED;
@@ -484,7 +485,8 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     const bool lowrank = s.rank > 0 && !(g_options & SVDQ_OPT_SKIP_LOWRANK);
 
-    // one kernel: per-token maxima, then smoothing + INT8 codes + the down projection H = X L1s in one walk over X
+    // one kernel: per-token maxima, then smoothing + INT8 codes + the down projection H = X L1s in one walk over X;
+    // small launches: the same kernel twice over K cut into runs (the maxima of the runs, then everything else)
     svdq::ActParams a{};
     a.X = static_cast<const uint16_t *>(X);
     a.rinv = static_cast<const float *>(L->rinv);
@@ -497,7 +499,18 @@ int svdq_w8a8_linear_forward(const svdq_layer_dev *L, const void *X, int M, void
     a.fmt = 2;
     a.zero_words = reinterpret_cast<uint32_t *>(ws + w.counters_off);      // the arrival counters of the GEMM's split K loop
     a.n_zero = w.n_counters;
-    hipError_t e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
+    hipError_t e;
+    if (w.act_cut) {
+        a.chunks = w.act.chunks; a.gchunk = w.act.gchunk; a.waves = w.act.waves;
+        a.pmax = reinterpret_cast<float *>(ws + w.pmax_off);
+        a.hpart = reinterpret_cast<float *>(ws + w.hpart_off);
+        a.arrived = reinterpret_cast<unsigned long long *>(ws + w.aflags_off);
+        a.maxmode = 1;
+        e = svdq::launch_act(a, 1, stream);
+        if (e != hipSuccess) return hip_fail(e);
+        a.maxmode = 2;
+    }
+    e = svdq::launch_act(a, lowrank ? 3 : 1, stream);
     if (e != hipSuccess) return hip_fail(e);
     if (void *ev = g_profile_event) {
         e = hipEventRecord(static_cast<hipEvent_t>(ev), stream);
@@ -528,7 +541,7 @@ int svdq_w8a8_debug_act(const svdq_layer_dev *L, const void *workspace, int M, i
     if (M < 0 || !workspace) return SVDQ_EINVAL;
     if (M == 0) return SVDQ_OK;
     const svdq_shape &s = L->shape;
-    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.N, s.rank, ksplit_override());
+    const svdq::WorkspaceW8 w = svdq::workspace_layout_w8(M, s.K, s.N, s.rank, ksplit_override(), act_override());
     const unsigned char *ws = static_cast<const unsigned char *>(workspace);
     svdq::DebugActW8Params d{};
     d.codes = ws + w.codes_off;

@@ -26,6 +26,10 @@ struct ActParams {
     float *hpart;
     // arrival words: [whole][chunks0] (if chunks0 > 1), then [Mpad / 16 - whole][chunks] (if chunks > 1)
     unsigned long long *arrived;
+    // INT8 per token with K cut into runs: 1 = first pass, only the maxima of the runs, to pmax fp32 [chunks][Mpad];
+    // 2 = second pass, the maxima are taken from pmax.  0 = one pass (all of K in one workgroup).
+    int maxmode;
+    float *pmax;
 };
 
 // flags: bit 0 = quantize (codes + scales), bit 1 = down projection (H)

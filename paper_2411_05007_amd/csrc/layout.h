@@ -160,34 +160,6 @@ inline GemmPlanFp4 plan_gemm_fp4(int M, int N, int G, int ksplit_override = 0, i
     return pl;
 }
 
-// The int8 MFMA takes twice the time of the 4-bit one per step of 64 channels, so a split of the 8-bit GEMM's K loop pays
-// from sixteen such steps per share on (measured at M = 512: K = 3072, 48 tiles: 28.0 -> 23.2 us with three shares;
-// K = 4608, 20 tiles: 39.8 -> 28.2 us with four; K = 12288, 48 tiles: 83.5 -> 39.5 us with four).
-constexpr int kW8MinSplitSteps = 16;
-// Workspace of the 8-bit forward: int8 codes in operand order, one fp16 scale per token, H twice (fp32 and bf16 parts),
-// and for small launches with a long K the arrival counters and int32 partial tiles of a split K loop (the MXFP4
-// GEMM's plan: same tiles, same rule).
-struct WorkspaceW8 {
-    size_t codes_off, sx_off, h_off, hfrag_off, counters_off, partial_off, total;
-    int Mpad;
-    int n_counters, ksplit;
-};
-inline WorkspaceW8 workspace_layout_w8(int M, int K, int N, int rank, int ksplit_override = 0) {
-    WorkspaceW8 w;
-    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
-    w.codes_off = 0;
-    w.sx_off = align256((size_t)K * w.Mpad);
-    w.h_off = w.sx_off + align256((size_t)w.Mpad * 2);
-    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
-    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, K / kGroup, ksplit_override, kW8MinSplitSteps);
-    w.ksplit = pl.ksplit;
-    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
-    w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
-    w.total = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);
-    return w;
-}
-
 // how the activation kernel's launch is cut up (plan_act below)
 struct ActPlan {
     int chunks;      // runs per 16-token slice, 1..64
@@ -328,6 +300,45 @@ inline size_t act_parked_floats(const ActPlan &a, int Mpad, int rank) {
 }
 inline size_t act_arrival_words(const ActPlan &a, int Mpad) {
     return (a.whole > 0 && a.chunks0 > 1 ? (size_t)a.chunks0 * a.whole : 0) + (a.chunks > 1 ? (size_t)a.chunks * (Mpad / 16 - a.whole) : 0);
+}
+
+// The int8 MFMA takes twice the time of the 4-bit one per step of 64 channels, so a split of the 8-bit GEMM's K loop pays
+// from sixteen such steps per share on (measured at M = 512: K = 3072, 48 tiles: 28.0 -> 23.2 us with three shares;
+// K = 4608, 20 tiles: 39.8 -> 28.2 us with four; K = 12288, 48 tiles: 83.5 -> 39.5 us with four).
+constexpr int kW8MinSplitSteps = 16;
+// Workspace of the 8-bit forward: int8 codes in operand order, one fp16 scale per token, H twice (fp32 and bf16 parts),
+// and for small launches with a long K the arrival counters and int32 partial tiles of a split K loop (the MXFP4
+// GEMM's plan: same tiles, same rule).
+struct WorkspaceW8 {
+    size_t codes_off, sx_off, h_off, hfrag_off, counters_off, partial_off, pmax_off, hpart_off, aflags_off, total;
+    int Mpad;
+    int n_counters, ksplit;
+    bool act_cut;      // the activation kernel runs twice over K cut into runs (small launches): maxima of the runs, then the rest
+    ActPlan act;
+};
+inline WorkspaceW8 workspace_layout_w8(int M, int K, int N, int rank, int ksplit_override = 0, int act_override = 0) {
+    WorkspaceW8 w;
+    w.Mpad = round_up(M > 0 ? M : 1, kRowPad);
+    w.codes_off = 0;
+    w.sx_off = align256((size_t)K * w.Mpad);
+    w.h_off = w.sx_off + align256((size_t)w.Mpad * 2);
+    w.hfrag_off = w.h_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    w.counters_off = w.hfrag_off + align256((size_t)w.Mpad * (rank > 0 ? rank : 1) * 4);
+    const GemmPlanFp4 pl = plan_gemm_fp4(M > 0 ? M : 1, N, K / kGroup, ksplit_override, kW8MinSplitSteps);
+    w.ksplit = pl.ksplit;
+    w.n_counters = pl.ksplit > 1 ? pl.tiles : 0;
+    w.partial_off = w.counters_off + align256((size_t)w.n_counters * 4);
+    w.pmax_off = w.partial_off + (pl.ksplit > 1 ? align256((size_t)pl.ksplit * pl.tiles * 128 * 256 * 4) : 0);
+    // A token's scale needs its maximum over all of K, so the one-pass kernel gives a slice to one workgroup; a launch
+    // with few slices runs two passes over a cut K instead, like the INT4 forward's (measured at M = 512, K = 12288:
+    // 44 us in one pass)
+    w.act = plan_act(M > 0 ? M : 1, K / kGroup, rank, act_override);
+    w.act_cut = w.act.chunks > 1 && w.act.whole == 0 && (M + 15) / 16 <= 128;
+    w.hpart_off = w.pmax_off + (w.act_cut ? align256((size_t)w.act.chunks * w.Mpad * 4) : 0);
+    const bool parked = w.act_cut && rank > 0;
+    w.aflags_off = w.hpart_off + (parked ? align256(act_parked_floats(w.act, w.Mpad, rank) * 4) : 0);
+    w.total = w.aflags_off + (parked ? align256(act_arrival_words(w.act, w.Mpad) * 8) : 0);
+    return w;
 }
 
 // Workspace of the MXFP4 forward (WorkspaceFp4 above).
