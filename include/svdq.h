@@ -333,7 +333,8 @@ int svdq_w4a16_forward(const svdq_layer_dev *layer, const void *X, int M, void *
  * These entry points take a svdq_shape with group = 0.  Buffers, ownership, alignment, stream and error
  * behaviour are those of their INT4 namesakes; wcodes holds one int8 per weight (K * Npad bytes, operand order
  * of the int8 matrix-core instruction), wscales fp16 [Npad].  The forward enqueues two kernels (quantization with
- * the down projection, GEMM).  The K / rank limits of svdq_linear_forward apply; K * Npad and K * Mpad below 2^31.
+ * the down projection, GEMM); three for batches of at most 2048 tokens with a long K, where the first kernel runs
+ * twice over K cut into runs (the tokens' maxima, then everything else).  The K / rank limits of svdq_linear_forward apply; K * Npad and K * Mpad below 2^31.
  * The workspace also holds, for launches of few tiles with a long K, the int32 partial tiles and arrival counters of a
  * split K loop (integer sums: the same bits as the unsplit loop); svdq_w8a8_workspace_bytes follows the calling
  * thread's SVDQ_OPT_KSPLIT bits like its INT4 namesake.
