@@ -38,7 +38,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side traffic of one GEMM launch at the headline shape: NOT measured by this script.  It is the figure of
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of `bench.py --pmc-run`, each counter scaled by what it reads
 # for a plain 256 MiB copy; the summary with the commands is profiles/flux_mlp_up_pmc_counters.md.
-GEMM_TRAFFIC_BYTES = 347.3e6         # 234.1 MB read (FETCH_SIZE x 2.000) + 113.2 MB written (WRITE_SIZE x 1.000) per launch
+GEMM_TRAFFIC_BYTES = 347.9e6         # 234.7 MB read (FETCH_SIZE x 2.000) + 113.2 MB written (WRITE_SIZE x 1.000) per launch
 GEMM_TRAFFIC_SOURCE = "profiles/flux_mlp_up_pmc_counters.md"
 
 
